@@ -1,0 +1,47 @@
+"""CPU ORACLE (test infrastructure only) -- weighted log-prob loss in numpy fp64.
+
+Per-token objective of the paper's "Derivation" section: l_t = -log p(y_t | x_<=t); the tree loss
+is sum_t (g_t / K) l_t (Eq. 4), algebraically the same as the mean over the K branches of each
+branch's summed loss (Eq. 1).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _f64(x) -> np.ndarray:
+    if hasattr(x, "detach"):
+        x = x.detach().cpu().float().numpy()
+    return np.asarray(x, dtype=np.float64)
+
+
+def log_softmax_gather(logits, target):
+    """Per row: lse = log sum_v exp(z_v); logp = z[target] - lse (0 where target < 0)."""
+    z = _f64(logits)
+    target = np.asarray(target).astype(np.int64)
+    m = z.max(axis=1)
+    lse = m + np.log(np.exp(z - m[:, None]).sum(axis=1))
+    safe = np.where(target >= 0, target, 0)
+    logp = z[np.arange(z.shape[0]), safe] - lse
+    logp = np.where(target >= 0, logp, 0.0)
+    return logp, lse
+
+
+def loss_tree(logp, weight) -> float:
+    """Eq. 4: sum_t lambda_t * (-logp_t)."""
+    return float(np.sum(_f64(weight) * (-_f64(logp))))
+
+
+def loss_sep_avg(paths, logp, trained_tok, adv=None) -> float:
+    """Eq. 1: (1/K) sum over branches of the branch's summed per-token loss, every branch
+    evaluated on its own token list (shared tokens are counted once per branch)."""
+    logp = _f64(logp)
+    tr = _f64(trained_tok)
+    a = np.ones_like(logp) if adv is None else _f64(adv)
+    total = 0.0
+    for p in paths:
+        branch = 0.0
+        for t in p:
+            branch += tr[t] * a[t] * (-logp[t])
+        total += branch
+    return total / len(paths)

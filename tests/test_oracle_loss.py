@@ -1,0 +1,58 @@
+"""Pins for oracle/loss.py: closed forms, a library routine, and the Eq. 1 == Eq. 4 identity."""
+import numpy as np
+import torch
+
+import workloads as W
+from oracle import loss as L
+from oracle import meta as M
+
+
+def test_closed_forms():
+    V = 1024
+    z = np.full((3, V), 0.25)
+    logp, lse = L.log_softmax_gather(z, [0, 5, V - 1])
+    assert np.allclose(logp, -np.log(V), atol=1e-14) and np.allclose(lse, 0.25 + np.log(V), atol=1e-14)
+    z = np.zeros((2, V))
+    z[0, 7] = 80.0
+    z[1, 9] = 80.0
+    logp, _ = L.log_softmax_gather(z, [7, 3])
+    assert abs(logp[0]) < 1e-30 + V * np.exp(-80.0) * 1.01 and abs(logp[1] + 80.0) < 1e-12
+    logp, _ = L.log_softmax_gather(z, [-1, 9])
+    assert logp[0] == 0.0
+
+
+def test_against_library_log_softmax():
+    logits, target = W.loss_inputs(64, 777, 3, std=2.0)
+    logp, lse = L.log_softmax_gather(logits, target.numpy())
+    ref = torch.log_softmax(logits.double(), dim=-1)
+    want = ref[torch.arange(64), target.long()].numpy()
+    assert np.allclose(logp, want, atol=1e-13)
+    assert np.allclose(lse, torch.logsumexp(logits.double(), dim=-1).numpy(), atol=1e-13)
+
+
+def test_sep_avg_equals_tree_loss():
+    for seed in range(10):
+        t = W.random_tree(seed, n_nodes=2 + seed, lo=1, hi=6, n_roots=1 + seed % 2, p_zero=0.1)
+        m = M.dfs_meta(t.parent, t.seg_len, t.trained)
+        n = m["n_tokens"]
+        if n == 0:
+            continue
+        logits, target = W.loss_inputs(n, 50, seed)
+        logp, _ = L.log_softmax_gather(logits, target.numpy())
+        trained_tok = np.asarray(t.trained)[m["dfs_order"]][m["tok_node"]]
+        a = L.loss_sep_avg(M.paths(m), logp, trained_tok)
+        b = L.loss_tree(logp, m["tok_weight"])
+        assert abs(a - b) <= 1e-6 * max(1.0, abs(a))
+        # with exact (fp64) weights the two forms agree to rounding
+        w64 = trained_tok * (m["node_g"][m["tok_node"]] / m["K"])
+        assert abs(a - L.loss_tree(logp, w64)) <= 1e-13 * max(1.0, abs(a))
+
+
+def test_single_chain_is_plain_nll_sum():
+    c = W.chain_tree([4, 5])
+    m = M.dfs_meta(c.parent, c.seg_len, c.trained)
+    logits, target = W.loss_inputs(9, 31, 5)
+    logp, _ = L.log_softmax_gather(logits, target.numpy())
+    assert np.all(m["tok_weight"] == 1.0)
+    nll = torch.nn.functional.cross_entropy(logits.double(), target.long(), reduction="sum").item()
+    assert abs(L.loss_tree(logp, m["tok_weight"]) - nll) < 1e-12
