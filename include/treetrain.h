@@ -1,0 +1,218 @@
+/*
+ * treetrain.h -- C ABI of the MI355X (gfx950) tree-attention hot path of "Tree Training".
+ *
+ * The library processes one DFS-serialised trajectory tree: every token of the tree appears once,
+ * a node's tokens followed by its children's subtrees (paper Eq. 8).  In that order a node's
+ * subtree is one contiguous token range, so the tree attention mask (Section "Attention Mask":
+ * query i sees key j iff j <= i and both lie on a common root-to-leaf path) becomes a per-key
+ * upper bound:
+ *
+ *        visible(i, j)  <=>  j <= i + n_prefix < kend[j]
+ *
+ * on the unified key axis [prefix keys ; own keys].  For own keys kend[j] = n_prefix + end of the
+ * subtree of j's node; for cached prefix keys (partition boundaries, Section "Redundancy-Free Tree
+ * Partitioning" and Appendix "Ancestor-Aware Attention Bias") kend[j] = INT32_MAX for ancestors of
+ * the chunk and 0 for everything else in the cached slice.
+ *
+ * Conventions
+ *   - All functions return a tt_status (0 = ok, < 0 = error); none throws or aborts.  The message
+ *     for the last error on the calling thread is tt_last_error().
+ *   - Arguments are validated on the host before anything is launched; a failed call launches
+ *     nothing and writes nothing.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are GPU memory.  All buffers are
+ *     owned by the caller; the library allocates no device memory.  Scratch comes from a
+ *     caller-provided workspace (tt_tree_attn_workspace gives its size).
+ *   - Device calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream) and do not synchronise.
+ *   - Inputs are const and never modified.  Outputs are overwritten, except the documented
+ *     accumulators (dk_prefix_acc, dv_prefix_acc, loss_acc), which are added to.
+ *   - Tensor layout is token-major: [tokens][heads][d] with d contiguous.  Query head h reads
+ *     key/value head h / (hq / hkv).
+ *   - Results are deterministic: the same inputs give bit-identical outputs from run to run
+ *     (the paper reports exact run-to-run agreement, Appendix "Numerical Verification").
+ */
+#ifndef TREETRAIN_H
+#define TREETRAIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tt_status;
+#define TT_OK               0
+#define TT_ERR_NULL        -1   /* a required pointer is NULL                                   */
+#define TT_ERR_SHAPE       -2   /* a size is out of range or sizes are inconsistent             */
+#define TT_ERR_TREE        -3   /* parent array is not a forest (out of range, self loop, cycle) */
+#define TT_ERR_DTYPE       -4   /* unknown dtype code                                           */
+#define TT_ERR_ALIGN       -5   /* a device pointer or stride breaks the alignment rule         */
+#define TT_ERR_WORKSPACE   -6   /* workspace missing or too small                               */
+#define TT_ERR_HIP         -7   /* the HIP runtime reported an error at launch                  */
+#define TT_ERR_UNSUPPORTED -8   /* valid request that this build has no kernel for              */
+
+#define TT_DTYPE_BF16 0
+#define TT_DTYPE_FP32 1
+
+/* tt_attn_desc.flags: run bf16 tensors through the slow fp32-arithmetic kernels instead of the
+ * MFMA kernels (for cross-checks). */
+#define TT_FLAG_REFERENCE_KERNELS 1
+
+/* Keys per entry of the tile summaries (ktile_kend_min / ktile_kend_max). */
+#define TT_KTILE 64
+
+/* Message of the last failed call on this thread (library-owned, valid until the next call). */
+const char* tt_last_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t tt_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * tt_tree_build_meta  (host only; needs no GPU)
+ *
+ * Turns a trajectory tree -- nodes with token-segment lengths, "Derivation" section -- into
+ * everything the device calls need.
+ *   DFS order and ranges        Eq. 8; children are visited in ascending input id.
+ *   g_n, K                      number of root-to-leaf paths through node n / in total (one per
+ *                               leaf; a zero-length leaf still counts).
+ *   position ids                Eq. 9: total length of the strict ancestors + offset inside the
+ *                               node; a root starts at its root_pos_offset (Appendix "Depth-Based
+ *                               Position Offset": for a partition this is the ancestor-only depth
+ *                               of the cut node's end, not the length of the cached slice).
+ *   loss weights                Eq. 4: trained * g / K as one fp32 division.
+ *   kend, tile summaries        the visibility bound above and its min/max per TT_KTILE keys; the
+ *                               prefix region and the own region are tiled separately, each from
+ *                               its own first key: n_ktiles = ceil(n_prefix/TT_KTILE) +
+ *                               ceil(n_tokens/TT_KTILE).
+ *
+ * Inputs (host):
+ *   parent[n_nodes]        parent node id, -1 for a root.  Any numbering; several roots allowed.
+ *   seg_len[n_nodes]       tokens in the node, >= 0.
+ *   trained[n_nodes]       1 = model output (gets a loss weight), 0 = input; NULL = all trained.
+ *   root_pos_offset        NULL (= 0) or one value per root, in ascending root id.
+ *   g_override, K_override NULL / 0, or the whole tree's g per node (input numbering) and K when
+ *                          this forest is one partition of a larger tree.
+ *   n_prefix               cached prefix keys in front of the own keys (0 = none).
+ *   prefix_visible[n_prefix]  1 = ancestor of this chunk; NULL = all visible.
+ * Outputs (host, caller-allocated; any may be NULL to skip it).  Per-node arrays are indexed by
+ * DFS rank:
+ *   dfs_order[n_nodes]     input id of the node at each DFS rank.
+ *   node_start, node_end, subtree_end [n_nodes]   token ranges, own-sequence indices.
+ *   node_parent[n_nodes]   DFS rank of the parent, -1 for roots.
+ *   node_g[n_nodes]
+ *   tok_node, tok_pos [n_tokens]
+ *   tok_pred[n_tokens]     index of the token whose logits predict token t: t-1 inside a node,
+ *                          the last token of the nearest non-empty ancestor at a node's first
+ *                          token, -1 if there is none.
+ *   tok_weight[n_tokens]   fp32.
+ *   kend[n_prefix + n_tokens], ktile_kend_min, ktile_kend_max [n_ktiles].
+ * Errors: TT_ERR_NULL, TT_ERR_SHAPE (negative sizes, total tokens + prefix >= 2^31 - 1),
+ *   TT_ERR_TREE.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_nodes;
+  int32_t n_tokens;   /* DFS length N                                  */
+  int32_t n_leaves;   /* K                                             */
+  int32_t n_roots;
+  int32_t n_ktiles;   /* entries of the tile summaries                 */
+} tt_meta_sizes;
+
+tt_status tt_tree_meta_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                             int32_t n_prefix, tt_meta_sizes* out);
+
+tt_status tt_tree_build_meta(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                             const uint8_t* trained, const int32_t* root_pos_offset,
+                             const int32_t* g_override, int32_t K_override,
+                             int32_t n_prefix, const uint8_t* prefix_visible,
+                             int32_t* dfs_order, int32_t* node_start, int32_t* node_end,
+                             int32_t* subtree_end, int32_t* node_parent, int32_t* node_g,
+                             int32_t* tok_node, int32_t* tok_pos, int32_t* tok_pred,
+                             float* tok_weight,
+                             int32_t* kend, int32_t* ktile_kend_min, int32_t* ktile_kend_max);
+
+/* ------------------------------------------------------------------------------------------
+ * Tree attention (device).
+ *
+ * Forward, per query head:  S_ij = scale * <Q_i, K_j> on visible pairs, P = row softmax(S) in
+ * fp32, O = P V, LSE_i = ln sum_j exp(S_ij).  Every query sees at least itself, so no row is
+ * empty.  With this mask each token's output equals what plain causal attention over its own
+ * root-to-leaf sequence gives (forward equivalence, Eq. 6).
+ *
+ * Backward:  D_i = <dO_i, O_i>, dP = dO V^T, dS = P o (dP - D), dQ = scale dS K,
+ * dK = scale dS^T Q, dV = P^T dO; dK/dV are summed over the query heads of the group and over
+ * every visible query, i.e. over all branches that pass through the key (Eq. 5).  Gradients for
+ * cached prefix keys are ADDED in fp32 to dk_prefix_acc / dv_prefix_acc so that several child
+ * partitions can accumulate into one buffer without bf16 rounding between them (Appendix
+ * "Float32 Gradient Accumulation").
+ *
+ * dtype TT_DTYPE_BF16: bf16 tensors, bf16 MFMA with fp32 accumulation and fp32 softmax; d = 128.
+ * dtype TT_DTYPE_FP32: fp32 tensors and arithmetic, any d <= 256 (slow reference-grade path).
+ * Alignment: device pointers 16-byte aligned; token strides multiples of 8 elements.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_q;            /* own tokens N (queries; also the own keys)                     */
+  int32_t n_prefix;       /* cached prefix keys P (0 = none)                               */
+  int32_t hq, hkv, d;     /* query heads, key/value heads (hq % hkv == 0), head dim        */
+  int32_t dtype;          /* TT_DTYPE_*: type of q, k, v, o, d_o, dq, dk, dv               */
+  float   scale;          /* softmax scale, e.g. 1/sqrt(d)                                 */
+  int32_t flags;          /* 0 or TT_FLAG_*                                                */
+  int64_t q_stride_tok;   /* elements between consecutive tokens of q; 0 = hq*d            */
+  int64_t k_stride_tok;   /* same for k_own; 0 = hkv*d                                     */
+  int64_t v_stride_tok;   /* same for v_own; 0 = hkv*d                                     */
+} tt_attn_desc;
+
+/* Bytes of device workspace the forward (backward = 0) or backward (backward = 1) call needs;
+ * 0 if the descriptor is invalid. */
+size_t tt_tree_attn_workspace(const tt_attn_desc* desc, int32_t backward);
+
+/* q [n_q][hq][d] (token stride q_stride_tok); k_own, v_own [n_q][hkv][d]; k_prefix, v_prefix
+ * [n_prefix][hkv][d] contiguous, NULL iff n_prefix == 0; kend [n_prefix+n_q], kt_min, kt_max
+ * [n_ktiles] int32 as written by tt_tree_build_meta (device copies).
+ * Outputs: o [n_q][hq][d] contiguous, lse [hq][n_q] fp32 (natural log). */
+tt_status tt_tree_attn_fwd(const tt_attn_desc* desc,
+                           const void* q, const void* k_own, const void* v_own,
+                           const void* k_prefix, const void* v_prefix,
+                           const int32_t* kend, const int32_t* kt_min, const int32_t* kt_max,
+                           void* o, float* lse,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Inputs as for the forward plus o, d_o [n_q][hq][d] contiguous and lse from the forward.
+ * Outputs: dq [n_q][hq][d], dk_own, dv_own [n_q][hkv][d], contiguous, overwritten.
+ * dk_prefix_acc, dv_prefix_acc [n_prefix][hkv][d] fp32, accumulated (+=); NULL iff n_prefix == 0.
+ * Keys of the prefix with kend == 0 receive nothing. */
+tt_status tt_tree_attn_bwd(const tt_attn_desc* desc,
+                           const void* q, const void* k_own, const void* v_own,
+                           const void* k_prefix, const void* v_prefix,
+                           const int32_t* kend, const int32_t* kt_min, const int32_t* kt_max,
+                           const void* o, const void* d_o, const float* lse,
+                           void* dq, void* dk_own, void* dv_own,
+                           float* dk_prefix_acc, float* dv_prefix_acc,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * tt_tree_weighted_logprob (device)
+ *
+ * Per row r of the logits: lse_r = ln sum_v exp(z_rv), logp_r = z_r[target_r] - lse_r, and the
+ * tree loss of Eq. 4, loss += sum_r weight_r * (-logp_r), where weight_r = g/K of the target
+ * token (times an advantage for policy-gradient objectives, "Derivation" section).  The logits
+ * are read from memory once.
+ *   logits [n_rows][vocab], row stride `row_stride` elements (0 = vocab), dtype bf16 or fp32.
+ *   target [n_rows] int32; a negative target gives logp = 0 and adds nothing.
+ *   weight [n_rows] fp32 or NULL (= 1).
+ *   logp   [n_rows] fp32, required (also the staging for the deterministic reduction).
+ *   lse    [n_rows] fp32 or NULL.
+ *   loss_acc: one fp32, ADDED to (so that a long sequence can be processed in row chunks);
+ *     NULL skips the reduction.  The caller zeroes it before the first chunk.
+ * Alignment: logits aligned to its element size; rows that start on a 16-byte boundary (e.g. a
+ *   16-byte aligned base and row_stride * sizeof(element) a multiple of 16) take the all-vector
+ *   path, other rows peel a scalar head and tail.
+ * ------------------------------------------------------------------------------------------ */
+tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype,
+                                   const void* logits, int64_t row_stride,
+                                   const int32_t* target, const float* weight,
+                                   float* logp, float* lse, float* loss_acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TREETRAIN_H */

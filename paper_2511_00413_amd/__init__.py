@@ -1,0 +1,8 @@
+"""MI355X-native tree-attention hot path of Tree Training: thin Python binding over the C ABI in
+include/treetrain.h.  Every step runs in the HIP library; this package only marshals arguments
+(torch tensors supply device memory and the stream).  There is no CPU fallback: if the shared
+library is missing, importing the binding raises."""
+from .binding import (  # noqa: F401
+    TreeMeta, TreeTrainError, lib_path, tree_attn_bwd, tree_attn_fwd, tree_attn_workspace,
+    tree_build_meta, tree_meta_sizes, tree_weighted_logprob, last_error, version, KTILE,
+)

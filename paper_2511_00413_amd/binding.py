@@ -1,0 +1,274 @@
+"""ctypes binding of libtreetrain.so.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+KTILE = 64
+DTYPE_BF16, DTYPE_FP32 = 0, 1
+FLAG_REFERENCE_KERNELS = 1
+
+_c_i32p = ctypes.POINTER(ctypes.c_int32)
+_c_u8p = ctypes.POINTER(ctypes.c_uint8)
+_c_f32p = ctypes.POINTER(ctypes.c_float)
+_vp = ctypes.c_void_p
+
+
+class TreeTrainError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libtreetrain status {status}: {message}")
+        self.status = status
+
+
+class _MetaSizes(ctypes.Structure):
+    _fields_ = [("n_nodes", ctypes.c_int32), ("n_tokens", ctypes.c_int32), ("n_leaves", ctypes.c_int32),
+                ("n_roots", ctypes.c_int32), ("n_ktiles", ctypes.c_int32)]
+
+
+class _AttnDesc(ctypes.Structure):
+    _fields_ = [("n_q", ctypes.c_int32), ("n_prefix", ctypes.c_int32), ("hq", ctypes.c_int32),
+                ("hkv", ctypes.c_int32), ("d", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float), ("flags", ctypes.c_int32),
+                ("q_stride_tok", ctypes.c_int64), ("k_stride_tok", ctypes.c_int64),
+                ("v_stride_tok", ctypes.c_int64)]
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libtreetrain.so")
+
+
+_LIB = None
+
+
+def _lib() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(
+                f"{path} is missing: build it with `python -m paper_2511_00413_amd.build` "
+                "(there is no fallback implementation)")
+        lib = ctypes.CDLL(path)
+        lib.tt_last_error.restype = ctypes.c_char_p
+        lib.tt_version.restype = ctypes.c_int32
+        lib.tt_tree_attn_workspace.restype = ctypes.c_size_t
+        lib.tt_tree_attn_workspace.argtypes = [ctypes.POINTER(_AttnDesc), ctypes.c_int32]
+        lib.tt_tree_meta_sizes.restype = ctypes.c_int32
+        lib.tt_tree_meta_sizes.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.POINTER(_MetaSizes)]
+        lib.tt_tree_build_meta.restype = ctypes.c_int32
+        lib.tt_tree_build_meta.argtypes = [ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32,
+                                           ctypes.c_int32, _vp] + [_vp] * 13
+        lib.tt_tree_attn_fwd.restype = ctypes.c_int32
+        lib.tt_tree_attn_fwd.argtypes = [ctypes.POINTER(_AttnDesc)] + [_vp] * 10 + [_vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_attn_bwd.restype = ctypes.c_int32
+        lib.tt_tree_attn_bwd.argtypes = [ctypes.POINTER(_AttnDesc)] + [_vp] * 16 + [_vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_weighted_logprob.restype = ctypes.c_int32
+        lib.tt_tree_weighted_logprob.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp,
+                                                 ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+        _LIB = lib
+    return _LIB
+
+
+def last_error() -> str:
+    return _lib().tt_last_error().decode()
+
+
+def version() -> int:
+    return int(_lib().tt_version())
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise TreeTrainError(status, last_error())
+
+
+def _np(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_vp)
+
+
+@dataclass
+class TreeMeta:
+    n_nodes: int
+    n_tokens: int
+    n_leaves: int
+    n_roots: int
+    n_prefix: int
+    n_ktiles: int
+    dfs_order: np.ndarray
+    node_start: np.ndarray
+    node_end: np.ndarray
+    subtree_end: np.ndarray
+    node_parent: np.ndarray
+    node_g: np.ndarray
+    tok_node: np.ndarray
+    tok_pos: np.ndarray
+    tok_pred: np.ndarray
+    tok_weight: np.ndarray
+    kend: np.ndarray
+    ktile_kend_min: np.ndarray
+    ktile_kend_max: np.ndarray
+
+
+def tree_meta_sizes(parent, seg_len, n_prefix: int = 0) -> dict:
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    out = _MetaSizes()
+    _check(_lib().tt_tree_meta_sizes(len(parent), _hp(parent), _hp(seg_len), n_prefix, ctypes.byref(out)))
+    return {k: getattr(out, k) for k, _ in _MetaSizes._fields_}
+
+
+def tree_build_meta(parent, seg_len, trained=None, root_pos_offset=None, g_override=None,
+                    K_override: int = 0, n_prefix: int = 0, prefix_visible=None) -> TreeMeta:
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    if parent.shape != seg_len.shape or parent.ndim != 1:
+        raise ValueError("parent and seg_len must be 1-D arrays of equal length")
+    trained = _np(trained, np.uint8)
+    root_pos_offset = _np(root_pos_offset, np.int32)
+    g_override = _np(g_override, np.int32)
+    prefix_visible = _np(prefix_visible, np.uint8)
+    for name, arr, n in (("trained", trained, len(parent)), ("g_override", g_override, len(parent)),
+                         ("prefix_visible", prefix_visible, n_prefix)):
+        if arr is not None and arr.shape != (n,):
+            raise ValueError(f"{name} must have shape ({n},)")
+    sz = tree_meta_sizes(parent, seg_len, n_prefix)
+    if root_pos_offset is not None and root_pos_offset.shape != (sz["n_roots"],):
+        raise ValueError(f"root_pos_offset must have one entry per root ({sz['n_roots']})")
+    nn, nt, nk = sz["n_nodes"], sz["n_tokens"], sz["n_ktiles"]
+    i32 = lambda n: np.zeros(n, dtype=np.int32)
+    m = TreeMeta(nn, nt, sz["n_leaves"], sz["n_roots"], n_prefix, nk,
+                 i32(nn), i32(nn), i32(nn), i32(nn), i32(nn), i32(nn), i32(nt), i32(nt), i32(nt),
+                 np.zeros(nt, dtype=np.float32), i32(n_prefix + nt), i32(nk), i32(nk))
+    _check(_lib().tt_tree_build_meta(
+        nn, _hp(parent), _hp(seg_len), _hp(trained), _hp(root_pos_offset), _hp(g_override), K_override,
+        n_prefix, _hp(prefix_visible),
+        _hp(m.dfs_order), _hp(m.node_start), _hp(m.node_end), _hp(m.subtree_end), _hp(m.node_parent),
+        _hp(m.node_g), _hp(m.tok_node), _hp(m.tok_pos), _hp(m.tok_pred), _hp(m.tok_weight),
+        _hp(m.kend), _hp(m.ktile_kend_min), _hp(m.ktile_kend_max)))
+    return m
+
+
+# ---- device calls -----------------------------------------------------------------------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dp(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _desc(q, k, v, n_prefix: int, scale, reference_kernels: bool) -> _AttnDesc:
+    torch = _torch()
+    if q.dim() != 3 or k.dim() != 3 or v.dim() != 3:
+        raise ValueError("q, k, v must be [tokens, heads, d]")
+    if q.dtype not in (torch.bfloat16, torch.float32) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share dtype bf16 or fp32")
+    for t in (q, k, v):
+        if t.numel() > 0 and (t.stride(2) != 1 or t.stride(1) != t.shape[2]):
+            raise ValueError("heads and d must be contiguous (only the token stride is free)")
+    n_q, hq, d = q.shape
+    if k.shape[0] != n_q or v.shape != k.shape or k.shape[2] != d:
+        raise ValueError("k, v must be [n_q, hkv, d]")
+    return _AttnDesc(n_q, n_prefix, hq, k.shape[1], d,
+                     DTYPE_BF16 if q.dtype == torch.bfloat16 else DTYPE_FP32,
+                     float(d) ** -0.5 if scale is None else float(scale),
+                     FLAG_REFERENCE_KERNELS if reference_kernels else 0,
+                     *(t.stride(0) if t.shape[0] > 1 else t.shape[1] * t.shape[2] for t in (q, k, v)))
+
+
+def tree_attn_workspace(q, k, v, n_prefix: int = 0, backward: bool = False, scale=None,
+                        reference_kernels: bool = False) -> int:
+    d = _desc(q, k, v, n_prefix, scale, reference_kernels)
+    return int(_lib().tt_tree_attn_workspace(ctypes.byref(d), 1 if backward else 0))
+
+
+def _workspace(desc, backward, workspace, device):
+    torch = _torch()
+    need = int(_lib().tt_tree_attn_workspace(ctypes.byref(desc), 1 if backward else 0))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def tree_attn_fwd(q, k, v, kend, kt_min, kt_max, *, k_prefix=None, v_prefix=None, scale=None,
+                  o=None, lse=None, workspace=None, stream=None, reference_kernels: bool = False):
+    """q [N,hq,d]; k, v [N,hkv,d]; kend/kt_min/kt_max: int32 device tensors from tree_build_meta.
+    Returns (o [N,hq,d], lse [hq,N] fp32)."""
+    torch = _torch()
+    n_prefix = 0 if k_prefix is None else k_prefix.shape[0]
+    desc = _desc(q, k, v, n_prefix, scale, reference_kernels)
+    if k_prefix is not None:
+        k_prefix, v_prefix = k_prefix.contiguous(), v_prefix.contiguous()
+    if o is None:
+        o = torch.empty((desc.n_q, desc.hq, desc.d), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((desc.hq, desc.n_q), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _workspace(desc, False, workspace, q.device)
+    _check(_lib().tt_tree_attn_fwd(ctypes.byref(desc), _dp(q), _dp(k), _dp(v), _dp(k_prefix), _dp(v_prefix),
+                                   _dp(kend), _dp(kt_min), _dp(kt_max), _dp(o), _dp(lse),
+                                   _dp(workspace), ws_bytes, _stream_ptr(stream)))
+    return o, lse
+
+
+def tree_attn_bwd(q, k, v, kend, kt_min, kt_max, o, d_o, lse, *, k_prefix=None, v_prefix=None,
+                  dk_prefix_acc=None, dv_prefix_acc=None, scale=None, dq=None, dk=None, dv=None,
+                  workspace=None, stream=None, reference_kernels: bool = False):
+    """Returns (dq [N,hq,d], dk [N,hkv,d], dv [N,hkv,d]); prefix gradients are added into the fp32
+    accumulators dk_prefix_acc / dv_prefix_acc [P,hkv,d]."""
+    torch = _torch()
+    n_prefix = 0 if k_prefix is None else k_prefix.shape[0]
+    desc = _desc(q, k, v, n_prefix, scale, reference_kernels)
+    if k_prefix is not None:
+        k_prefix, v_prefix = k_prefix.contiguous(), v_prefix.contiguous()
+    if not (o.is_contiguous() and d_o.is_contiguous() and lse.is_contiguous()):
+        raise ValueError("o, d_o, lse must be contiguous")
+    if dq is None:
+        dq = torch.empty((desc.n_q, desc.hq, desc.d), dtype=q.dtype, device=q.device)
+    if dk is None:
+        dk = torch.empty((desc.n_q, desc.hkv, desc.d), dtype=q.dtype, device=q.device)
+    if dv is None:
+        dv = torch.empty((desc.n_q, desc.hkv, desc.d), dtype=q.dtype, device=q.device)
+    workspace, ws_bytes = _workspace(desc, True, workspace, q.device)
+    _check(_lib().tt_tree_attn_bwd(ctypes.byref(desc), _dp(q), _dp(k), _dp(v), _dp(k_prefix), _dp(v_prefix),
+                                   _dp(kend), _dp(kt_min), _dp(kt_max), _dp(o), _dp(d_o), _dp(lse),
+                                   _dp(dq), _dp(dk), _dp(dv), _dp(dk_prefix_acc), _dp(dv_prefix_acc),
+                                   _dp(workspace), ws_bytes, _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def tree_weighted_logprob(logits, target, weight=None, *, loss_acc=None, logp=None, lse=None,
+                          want_lse: bool = True, stream=None):
+    """logits [n, V] bf16/fp32 (row stride free), target [n] int32, weight [n] fp32 or None.
+    Returns (logp [n], lse [n] or None, loss_acc [1]); loss_acc is added to (zeroed if created here)."""
+    torch = _torch()
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [rows, vocab] with contiguous vocab")
+    if logits.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("logits must be bf16 or fp32")
+    n, vocab = logits.shape
+    if logp is None:
+        logp = torch.empty(n, dtype=torch.float32, device=logits.device)
+    if lse is None and want_lse:
+        lse = torch.empty(n, dtype=torch.float32, device=logits.device)
+    if loss_acc is None:
+        loss_acc = torch.zeros(1, dtype=torch.float32, device=logits.device)
+    _check(_lib().tt_tree_weighted_logprob(
+        n, vocab, DTYPE_BF16 if logits.dtype == torch.bfloat16 else DTYPE_FP32, _dp(logits),
+        logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(logp), _dp(lse), _dp(loss_acc),
+        _stream_ptr(stream)))
+    return logp, lse, loss_acc

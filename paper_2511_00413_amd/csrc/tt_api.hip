@@ -1,0 +1,150 @@
+// C ABI entry points of the device calls: argument validation on the host, then dispatch to the
+// kernels.  Nothing is launched unless every check passes.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include "tt_internal.h"
+#include "tt_kernels.h"
+
+namespace {
+
+using tt::fail;
+
+struct Checked {
+  tt::AttnArgs a;
+  bool bf16;
+  bool use_mfma;
+};
+
+size_t delta_bytes(const tt_attn_desc* d) {
+  return ((size_t)d->hq * (size_t)d->n_q * sizeof(float) + 255) & ~(size_t)255;
+}
+
+tt_status check_desc(const tt_attn_desc* d) {
+  if (!d) return fail(TT_ERR_NULL, "desc is NULL");
+  if (d->dtype != TT_DTYPE_BF16 && d->dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", d->dtype);
+  if (d->n_q < 0 || d->n_prefix < 0 || (int64_t)d->n_q + d->n_prefix >= INT32_MAX)
+    return fail(TT_ERR_SHAPE, "n_q=%d n_prefix=%d out of range", d->n_q, d->n_prefix);
+  if (d->hq <= 0 || d->hkv <= 0 || d->hq % d->hkv != 0 || d->hq > 65535)
+    return fail(TT_ERR_SHAPE, "hq=%d must be a positive multiple of hkv=%d (and <= 65535)", d->hq, d->hkv);
+  if (d->d <= 0 || d->d > 256 || d->d % 8 != 0) return fail(TT_ERR_SHAPE, "d=%d must be a multiple of 8 in [8, 256]", d->d);
+  if (!(d->scale > 0.f) || !std::isfinite(d->scale)) return fail(TT_ERR_SHAPE, "scale must be positive and finite");
+  if (d->flags & ~TT_FLAG_REFERENCE_KERNELS) return fail(TT_ERR_UNSUPPORTED, "unknown flags 0x%x", d->flags);
+  const int64_t qs = d->q_stride_tok ? d->q_stride_tok : (int64_t)d->hq * d->d;
+  const int64_t ks = d->k_stride_tok ? d->k_stride_tok : (int64_t)d->hkv * d->d;
+  const int64_t vs = d->v_stride_tok ? d->v_stride_tok : (int64_t)d->hkv * d->d;
+  if (qs < (int64_t)d->hq * d->d || ks < (int64_t)d->hkv * d->d || vs < (int64_t)d->hkv * d->d)
+    return fail(TT_ERR_SHAPE, "a token stride is smaller than heads*d");
+  if (qs % 8 || ks % 8 || vs % 8) return fail(TT_ERR_ALIGN, "token strides must be multiples of 8 elements");
+  return TT_OK;
+}
+
+bool mfma_supported(const tt_attn_desc* d) {
+  return d->dtype == TT_DTYPE_BF16 && d->d == 128 && !(d->flags & TT_FLAG_REFERENCE_KERNELS);
+}
+
+tt_status check_common(const tt_attn_desc* d, const void* q, const void* k_own, const void* v_own,
+                       const void* k_prefix, const void* v_prefix, const int32_t* kend,
+                       const int32_t* kt_min, const int32_t* kt_max, Checked& c) {
+  if (tt_status s = check_desc(d)) return s;
+  if (d->n_q > 0 && (!q || !k_own || !v_own)) return fail(TT_ERR_NULL, "q / k_own / v_own is NULL");
+  if ((int64_t)d->n_q + d->n_prefix > 0 && (!kend || !kt_min || !kt_max)) return fail(TT_ERR_NULL, "kend / kt_min / kt_max is NULL");
+  if ((d->n_prefix > 0) != (k_prefix != nullptr) || (d->n_prefix > 0) != (v_prefix != nullptr))
+    return fail(TT_ERR_NULL, "k_prefix / v_prefix must be given exactly when n_prefix > 0");
+  const void* ptrs[] = {q, k_own, v_own, k_prefix, v_prefix};
+  for (const void* p : ptrs)
+    if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
+  tt::AttnArgs& a = c.a;
+  a = tt::AttnArgs{};
+  a.n_q = d->n_q; a.n_prefix = d->n_prefix; a.hq = d->hq; a.hkv = d->hkv; a.d = d->d;
+  a.scale = d->scale;
+  a.q_stride = d->q_stride_tok ? d->q_stride_tok : (int64_t)d->hq * d->d;
+  a.k_stride = d->k_stride_tok ? d->k_stride_tok : (int64_t)d->hkv * d->d;
+  a.v_stride = d->v_stride_tok ? d->v_stride_tok : (int64_t)d->hkv * d->d;
+  a.q = q; a.k_own = k_own; a.v_own = v_own; a.k_prefix = k_prefix; a.v_prefix = v_prefix;
+  a.kend = kend; a.kt_min = kt_min; a.kt_max = kt_max;
+  c.bf16 = d->dtype == TT_DTYPE_BF16;
+  c.use_mfma = mfma_supported(d);
+  return TT_OK;
+}
+
+tt_status hip_result(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TT_OK;
+  return fail(TT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" size_t tt_tree_attn_workspace(const tt_attn_desc* desc, int32_t backward) {
+  tt::clear_error();
+  if (check_desc(desc) != TT_OK) return 0;
+  size_t bytes = 256;                         // never 0 for a valid descriptor
+  if (backward) bytes += delta_bytes(desc);
+  if (mfma_supported(desc)) bytes += tt::mfma_attn_workspace(desc->n_q, desc->n_prefix, desc->hq, desc->hkv, desc->d, backward != 0);
+  return bytes;
+}
+
+extern "C" tt_status tt_tree_attn_fwd(const tt_attn_desc* desc, const void* q, const void* k_own, const void* v_own,
+                                      const void* k_prefix, const void* v_prefix,
+                                      const int32_t* kend, const int32_t* kt_min, const int32_t* kt_max,
+                                      void* o, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  tt::clear_error();
+  Checked c;
+  if (tt_status s = check_common(desc, q, k_own, v_own, k_prefix, v_prefix, kend, kt_min, kt_max, c)) return s;
+  if (desc->n_q > 0 && (!o || !lse)) return fail(TT_ERR_NULL, "o / lse is NULL");
+  if (!tt::aligned16(o)) return fail(TT_ERR_ALIGN, "o is not 16-byte aligned");
+  const size_t need = tt_tree_attn_workspace(desc, 0);
+  if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
+    return fail(TT_ERR_WORKSPACE, "forward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+  c.a.o = o; c.a.lse = lse;
+  c.a.workspace = workspace; c.a.workspace_bytes = workspace_bytes;
+  hipStream_t st = (hipStream_t)stream;
+  if (c.use_mfma) return hip_result(tt::mfma_attn_fwd(c.a, st), "tree_attn_fwd");
+  return hip_result(tt::ref_attn_fwd(c.a, c.bf16, st), "tree_attn_fwd (reference kernels)");
+}
+
+extern "C" tt_status tt_tree_attn_bwd(const tt_attn_desc* desc, const void* q, const void* k_own, const void* v_own,
+                                      const void* k_prefix, const void* v_prefix,
+                                      const int32_t* kend, const int32_t* kt_min, const int32_t* kt_max,
+                                      const void* o, const void* d_o, const float* lse,
+                                      void* dq, void* dk_own, void* dv_own,
+                                      float* dk_prefix_acc, float* dv_prefix_acc,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  tt::clear_error();
+  Checked c;
+  if (tt_status s = check_common(desc, q, k_own, v_own, k_prefix, v_prefix, kend, kt_min, kt_max, c)) return s;
+  if (desc->n_q > 0 && (!o || !d_o || !lse || !dq || !dk_own || !dv_own)) return fail(TT_ERR_NULL, "o / d_o / lse / dq / dk_own / dv_own is NULL");
+  if ((desc->n_prefix > 0) != (dk_prefix_acc != nullptr) || (desc->n_prefix > 0) != (dv_prefix_acc != nullptr))
+    return fail(TT_ERR_NULL, "dk_prefix_acc / dv_prefix_acc must be given exactly when n_prefix > 0");
+  const void* ptrs[] = {o, d_o, dq, dk_own, dv_own, dk_prefix_acc, dv_prefix_acc};
+  for (const void* p : ptrs)
+    if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
+  const size_t need = tt_tree_attn_workspace(desc, 1);
+  if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
+    return fail(TT_ERR_WORKSPACE, "backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+  c.a.o = const_cast<void*>(o); c.a.lse = const_cast<float*>(lse); c.a.d_o = d_o;
+  c.a.dq = dq; c.a.dk_own = dk_own; c.a.dv_own = dv_own;
+  c.a.dk_prefix_acc = dk_prefix_acc; c.a.dv_prefix_acc = dv_prefix_acc;
+  c.a.delta = (float*)workspace;
+  c.a.workspace = (char*)workspace + delta_bytes(desc);
+  c.a.workspace_bytes = workspace_bytes - delta_bytes(desc);
+  hipStream_t st = (hipStream_t)stream;
+  if (c.use_mfma) return hip_result(tt::mfma_attn_bwd(c.a, st), "tree_attn_bwd");
+  return hip_result(tt::ref_attn_bwd(c.a, c.bf16, st), "tree_attn_bwd (reference kernels)");
+}
+
+extern "C" tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype, const void* logits,
+                                              int64_t row_stride, const int32_t* target, const float* weight,
+                                              float* logp, float* lse, float* loss_acc, void* stream) {
+  tt::clear_error();
+  if (dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (n_rows < 0 || n_rows > 0x7fffffffLL) return fail(TT_ERR_SHAPE, "n_rows=%lld out of range", (long long)n_rows);
+  if (vocab <= 0) return fail(TT_ERR_SHAPE, "vocab=%d must be positive", vocab);
+  if (row_stride == 0) row_stride = vocab;
+  if (row_stride < vocab) return fail(TT_ERR_SHAPE, "row_stride=%lld is smaller than vocab=%d", (long long)row_stride, vocab);
+  if (n_rows > 0 && (!logits || !target || !logp)) return fail(TT_ERR_NULL, "logits / target / logp is NULL");
+  const size_t es = dtype == TT_DTYPE_BF16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(logits) % es) return fail(TT_ERR_ALIGN, "logits is not aligned to its element size");
+  return hip_result(tt::weighted_logprob(n_rows, vocab, dtype == TT_DTYPE_BF16, logits, row_stride, target, weight,
+                                         logp, lse, loss_acc, (hipStream_t)stream),
+                    "tree_weighted_logprob");
+}

@@ -1,0 +1,41 @@
+// Kernel launch interfaces shared by the API layer and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace tt {
+
+// Arguments of one attention call, after validation; strides are in elements.
+struct RefArgs {
+  int n_q, n_prefix, hq, hkv, d;
+  float scale;
+  int64_t q_stride, k_stride, v_stride;
+  const void *q, *k_own, *v_own, *k_prefix, *v_prefix;
+  const int32_t *kend, *kt_min, *kt_max;
+  void* o;
+  float* lse;
+  // backward only
+  const void* d_o;
+  float* delta;                 // [hq][n_q] workspace: rowsum(dO o O)
+  void *dq, *dk_own, *dv_own;
+  float *dk_prefix_acc, *dv_prefix_acc;
+  void* workspace;              // remaining workspace after delta (MFMA path scratch)
+  size_t workspace_bytes;
+};
+typedef RefArgs AttnArgs;
+
+// fp32-arithmetic reference-grade kernels (tt_attn_ref.hip)
+hipError_t ref_attn_fwd(const RefArgs& a, bool bf16, hipStream_t st);
+hipError_t ref_attn_bwd(const RefArgs& a, bool bf16, hipStream_t st);
+
+// bf16 MFMA kernels, d = 128 (tt_attn_fwd.hip / tt_attn_bwd.hip)
+hipError_t mfma_attn_fwd(const AttnArgs& a, hipStream_t st);
+hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st);
+size_t mfma_attn_workspace(int n_q, int n_prefix, int hq, int hkv, int d, bool backward);
+
+// fused log-softmax / gather / weighting (tt_loss.hip)
+hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                            const int32_t* target, const float* weight, float* logp, float* lse,
+                            float* loss_acc, hipStream_t st);
+
+}  // namespace tt

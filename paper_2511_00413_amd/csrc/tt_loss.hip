@@ -1,0 +1,178 @@
+// Fused log-softmax / gather / loss weighting (paper Eq. 4: L_tree = sum_t (g_t/K) * l_t with
+// l_t = -log p(y_t | x_<=t); "Loss Weights" paragraph: one multiply per token).
+//
+// HBM-bound: each logits row is streamed from memory exactly once with 16-byte loads; every
+// thread keeps an online (max, sum-of-exp) pair in base 2, the pairs are merged across the
+// workgroup, and the target logit is fetched separately (one element).  The weighted sum over
+// rows is a second, single-workgroup kernel that adds the rows in a fixed order in fp64, so the
+// loss is bit-reproducible.
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include "tt_kernels.h"
+
+namespace tt {
+namespace {
+
+constexpr int LOSS_THREADS = 256;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct MS { float m, s; };   // running max (natural units) and sum of exp(z - m)
+
+__device__ __forceinline__ MS merge(MS a, MS b) {
+  const float m = fmaxf(a.m, b.m);
+  // exp2(-inf) = 0 handles empty partners; (-inf) - (-inf) is avoided by the select
+  const float sa = a.m == -INFINITY ? 0.f : a.s * exp2f((a.m - m) * LOG2E);
+  const float sb = b.m == -INFINITY ? 0.f : b.s * exp2f((b.m - m) * LOG2E);
+  return {m, sa + sb};
+}
+
+__device__ __forceinline__ void push8(MS& st, const float (&z)[8]) {  // z may hold -inf (masked vocabulary entries)
+  float vm = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+  const float m_new = fmaxf(st.m, vm);
+  const float mref = m_new == -INFINITY ? 0.f : m_new;      // all -inf so far: keep the sum at 0, no NaN
+  // the difference is taken before the scaling so that large |z| loses nothing
+  float acc = st.m == -INFINITY ? 0.f : st.s * exp2f((st.m - mref) * LOG2E);
+#pragma unroll
+  for (int e = 0; e < 8; e++) acc += exp2f((z[e] - mref) * LOG2E);
+  st.m = m_new;
+  st.s = acc;
+}
+
+__device__ __forceinline__ void push1(MS& st, float z) {
+  const float m_new = fmaxf(st.m, z);
+  const float old = st.m == -INFINITY ? 0.f : st.s * exp2f((st.m - m_new) * LOG2E);
+  st.s = old + exp2f((z - m_new) * LOG2E);
+  st.m = m_new;
+}
+
+__device__ __forceinline__ float elem(const float* p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float elem(const __hip_bfloat16* p, int64_t i) { return __bfloat162float(p[i]); }
+
+__device__ __forceinline__ void unpack8(const u32x4& v, float (&z)[8]) {
+  // bf16 -> fp32 is a 16-bit shift
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    z[2 * i] = __uint_as_float(w[i] << 16);
+    z[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
+// One workgroup per row.  T = float: a 16-byte load holds 4 elements (two loads per push8).
+template <typename T>
+__global__ void __launch_bounds__(LOSS_THREADS)
+row_logprob_kernel(int vocab, const T* __restrict__ logits, int64_t row_stride,
+                   const int32_t* __restrict__ target, float* __restrict__ logp, float* __restrict__ lse_out) {
+  constexpr int EPV = 16 / sizeof(T);               // elements per 16-byte vector
+  const int64_t r = blockIdx.x;
+  const T* row = logits + r * row_stride;
+  const int t = threadIdx.x;
+  // split the row into [0, head) scalar, [head, head + nvec*EPV) vector, rest scalar
+  const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
+  int head = (int)(((16 - (addr & 15)) & 15) / sizeof(T));
+  head = head < vocab ? head : vocab;
+  const int nvec = (vocab - head) / EPV;
+  const int tail0 = head + nvec * EPV;
+  MS st = {-INFINITY, 0.f};
+  const u32x4* vp = reinterpret_cast<const u32x4*>(row + head);
+  if constexpr (sizeof(T) == 2) {
+    int i = t;
+    // 4 loads in flight per thread
+    for (; i + 3 * LOSS_THREADS < nvec; i += 4 * LOSS_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      const u32x4 v1 = __builtin_nontemporal_load(vp + i + LOSS_THREADS);
+      const u32x4 v2 = __builtin_nontemporal_load(vp + i + 2 * LOSS_THREADS);
+      const u32x4 v3 = __builtin_nontemporal_load(vp + i + 3 * LOSS_THREADS);
+      float z[8];
+      unpack8(v0, z); push8(st, z);
+      unpack8(v1, z); push8(st, z);
+      unpack8(v2, z); push8(st, z);
+      unpack8(v3, z); push8(st, z);
+    }
+    for (; i < nvec; i += LOSS_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      float z[8];
+      unpack8(v0, z); push8(st, z);
+    }
+  } else {
+    int i = t;
+    for (; i + LOSS_THREADS < nvec; i += 2 * LOSS_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      const u32x4 v1 = __builtin_nontemporal_load(vp + i + LOSS_THREADS);
+      const float z[8] = {__uint_as_float(v0.x), __uint_as_float(v0.y), __uint_as_float(v0.z), __uint_as_float(v0.w),
+                          __uint_as_float(v1.x), __uint_as_float(v1.y), __uint_as_float(v1.z), __uint_as_float(v1.w)};
+      push8(st, z);
+    }
+    for (; i < nvec; i += LOSS_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      push1(st, __uint_as_float(v0.x)); push1(st, __uint_as_float(v0.y));
+      push1(st, __uint_as_float(v0.z)); push1(st, __uint_as_float(v0.w));
+    }
+  }
+  for (int e = t; e < head; e += LOSS_THREADS) push1(st, elem(row, e));
+  for (int e = tail0 + t; e < vocab; e += LOSS_THREADS) push1(st, elem(row, e));
+
+  // merge across the wavefront, then across the 4 wavefronts
+  for (int o = 32; o > 0; o >>= 1) {
+    MS other = {__shfl_xor(st.m, o), __shfl_xor(st.s, o)};
+    st = merge(st, other);
+  }
+  __shared__ MS part[LOSS_THREADS / 64];
+  if ((t & 63) == 0) part[t >> 6] = st;
+  __syncthreads();
+  if (t == 0) {
+    MS a = part[0];
+    for (int w = 1; w < LOSS_THREADS / 64; w++) a = merge(a, part[w]);
+    const float ln_s = LN2 * log2f(a.s);
+    const float lse = a.m + ln_s;
+    const int32_t y = target[r];
+    // (z_y - m) - ln(sum) keeps full precision when |m| is large
+    logp[r] = (y >= 0 && y < vocab) ? (elem(row, y) - a.m) - ln_s : 0.f;
+    if (lse_out) lse_out[r] = lse;
+  }
+}
+
+// loss_acc += sum_r weight_r * (-logp_r), rows added in a fixed order (fp64 partials).
+__global__ void __launch_bounds__(1024)
+weighted_sum_kernel(int64_t n_rows, const float* __restrict__ logp, const float* __restrict__ weight,
+                    const int32_t* __restrict__ target, float* __restrict__ loss_acc) {
+  __shared__ double part[1024];
+  double acc = 0.0;
+  for (int64_t r = threadIdx.x; r < n_rows; r += 1024) {
+    const float w = weight ? weight[r] : 1.f;
+    if (target[r] >= 0 && w != 0.f) acc += (double)w * (double)(-logp[r]);
+  }
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) part[threadIdx.x] += part[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss_acc = (float)((double)*loss_acc + part[0]);
+}
+
+}  // namespace
+
+hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                            const int32_t* target, const float* weight, float* logp, float* lse,
+                            float* loss_acc, hipStream_t st) {
+  if (n_rows == 0) return hipSuccess;
+  // grid.x is limited to 2^31-1 workgroups; rows beyond that are rejected by the API layer
+  if (bf16)
+    row_logprob_kernel<__hip_bfloat16><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
+        vocab, (const __hip_bfloat16*)logits, row_stride, target, logp, lse);
+  else
+    row_logprob_kernel<float><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
+        vocab, (const float*)logits, row_stride, target, logp, lse);
+  if (hipError_t e = hipGetLastError()) return e;
+  if (loss_acc) {
+    weighted_sum_kernel<<<1, 1024, 0, st>>>(n_rows, logp, weight, target, loss_acc);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
+
+}  // namespace tt

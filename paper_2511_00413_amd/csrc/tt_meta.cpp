@@ -1,0 +1,191 @@
+// Host-side tree metadata: DFS serialisation (paper Eq. 8), path counts g_n / K ("Derivation"),
+// tree position ids (Eq. 9, Appendix "Depth-Based Position Offset"), loss weights (Eq. 4) and the
+// per-key visibility bound with its tile summaries (Section "Attention Mask", Appendix
+// "Ancestor-Aware Attention Bias").  O(nodes + tokens), no recursion (trees can be deep chains).
+#include <climits>
+#include <vector>
+#include "tt_internal.h"
+
+namespace {
+
+struct Forest {
+  std::vector<int32_t> first_child, next_sibling, roots;   // input numbering
+  std::vector<int32_t> order;                              // order[rank] = input id
+  std::vector<int32_t> rank;                               // rank[input id]
+  int64_t n_tokens = 0;
+  int32_t n_leaves = 0;
+};
+
+// Validates the parent array and produces the pre-order.  Children keep ascending input id.
+tt_status build_forest(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t n_prefix,
+                       Forest& f) {
+  if (n_nodes < 0 || n_prefix < 0) return tt::fail(TT_ERR_SHAPE, "n_nodes=%d, n_prefix=%d must be >= 0", n_nodes, n_prefix);
+  if (n_nodes > 0 && (!parent || !seg_len)) return tt::fail(TT_ERR_NULL, "parent / seg_len is NULL");
+  f.first_child.assign(n_nodes, -1);
+  f.next_sibling.assign(n_nodes, -1);
+  std::vector<int32_t> last_child(n_nodes, -1);
+  int64_t total = 0;
+  for (int32_t i = 0; i < n_nodes; i++) {
+    const int32_t p = parent[i];
+    if (seg_len[i] < 0) return tt::fail(TT_ERR_SHAPE, "seg_len[%d]=%d is negative", i, seg_len[i]);
+    total += seg_len[i];
+    if (p < -1 || p >= n_nodes || p == i) return tt::fail(TT_ERR_TREE, "parent[%d]=%d is out of range", i, p);
+    if (p < 0) {
+      f.roots.push_back(i);
+    } else {
+      if (last_child[p] < 0) f.first_child[p] = i; else f.next_sibling[last_child[p]] = i;
+      last_child[p] = i;
+    }
+  }
+  if (total + n_prefix >= INT32_MAX) return tt::fail(TT_ERR_SHAPE, "tokens + prefix = %lld does not fit int32", (long long)(total + n_prefix));
+  f.n_tokens = total;
+  f.order.reserve(n_nodes);
+  std::vector<int32_t> stack;
+  for (int32_t r : f.roots) {
+    stack.push_back(r);
+    while (!stack.empty()) {
+      const int32_t i = stack.back();
+      stack.pop_back();
+      f.order.push_back(i);
+      if (f.next_sibling[i] >= 0) stack.push_back(f.next_sibling[i]);   // visited after i's subtree
+      if (f.first_child[i] >= 0) stack.push_back(f.first_child[i]);
+      else f.n_leaves++;
+    }
+  }
+  if ((int32_t)f.order.size() != n_nodes)
+    return tt::fail(TT_ERR_TREE, "parent array has a cycle: %d of %d nodes reachable from a root", (int)f.order.size(), n_nodes);
+  f.rank.assign(n_nodes, 0);
+  for (int32_t rk = 0; rk < n_nodes; rk++) f.rank[f.order[rk]] = rk;
+  return TT_OK;
+}
+
+int32_t n_ktiles_of(int64_t n_prefix, int64_t n_tokens) {
+  return (int32_t)(tt::ceil_div(n_prefix, TT_KTILE) + tt::ceil_div(n_tokens, TT_KTILE));
+}
+
+}  // namespace
+
+extern "C" tt_status tt_tree_meta_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                        int32_t n_prefix, tt_meta_sizes* out) {
+  tt::clear_error();
+  if (!out) return tt::fail(TT_ERR_NULL, "out is NULL");
+  Forest f;
+  if (tt_status s = build_forest(n_nodes, parent, seg_len, n_prefix, f)) return s;
+  out->n_nodes = n_nodes;
+  out->n_tokens = (int32_t)f.n_tokens;
+  out->n_leaves = f.n_leaves;
+  out->n_roots = (int32_t)f.roots.size();
+  out->n_ktiles = n_ktiles_of(n_prefix, f.n_tokens);
+  return TT_OK;
+}
+
+extern "C" tt_status tt_tree_build_meta(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                        const uint8_t* trained, const int32_t* root_pos_offset,
+                                        const int32_t* g_override, int32_t K_override,
+                                        int32_t n_prefix, const uint8_t* prefix_visible,
+                                        int32_t* dfs_order, int32_t* node_start, int32_t* node_end,
+                                        int32_t* subtree_end, int32_t* node_parent, int32_t* node_g,
+                                        int32_t* tok_node, int32_t* tok_pos, int32_t* tok_pred,
+                                        float* tok_weight,
+                                        int32_t* kend, int32_t* ktile_kend_min, int32_t* ktile_kend_max) {
+  tt::clear_error();
+  Forest f;
+  if (tt_status s = build_forest(n_nodes, parent, seg_len, n_prefix, f)) return s;
+  if ((g_override != nullptr) != (K_override > 0))
+    return tt::fail(TT_ERR_SHAPE, "g_override and K_override must be given together (K_override=%d)", K_override);
+  if (K_override < 0) return tt::fail(TT_ERR_SHAPE, "K_override=%d is negative", K_override);
+  const int32_t N = (int32_t)f.n_tokens;
+
+  // Per-node quantities in DFS rank.  Pre-order puts a parent before its children, so one
+  // forward sweep gives starts and positions and one backward sweep gives subtree ends and g.
+  std::vector<int32_t> start(n_nodes), end(n_nodes), sub_end(n_nodes), par(n_nodes), g(n_nodes), pos0(n_nodes), pred0(n_nodes);
+  int32_t tok = 0;
+  int32_t root_no = 0;
+  // roots in f.roots are ascending id and are visited in that order
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    start[rk] = tok;
+    tok += seg_len[i];
+    end[rk] = tok;
+    if (parent[i] < 0) {
+      par[rk] = -1;
+      pos0[rk] = root_pos_offset ? root_pos_offset[root_no] : 0;
+      pred0[rk] = -1;
+      root_no++;
+    } else {
+      const int32_t p = f.rank[parent[i]];
+      par[rk] = p;
+      const int64_t ps = (int64_t)pos0[p] + seg_len[parent[i]];
+      if (ps + seg_len[i] >= INT32_MAX) return tt::fail(TT_ERR_SHAPE, "position id overflows int32 at node %d", i);
+      pos0[rk] = (int32_t)ps;
+      // last token of the nearest ancestor that has any token
+      pred0[rk] = seg_len[parent[i]] > 0 ? end[p] - 1 : pred0[p];
+    }
+  }
+  for (int32_t rk = n_nodes - 1; rk >= 0; rk--) {
+    const int32_t i = f.order[rk];
+    if (f.first_child[i] < 0) { sub_end[rk] = end[rk]; g[rk] = 1; }
+  }
+  // children come after parents: accumulate leaves upwards, subtree end = max over descendants
+  {
+    std::vector<int32_t> acc_g(n_nodes, 0), acc_end(n_nodes, 0);
+    for (int32_t rk = n_nodes - 1; rk >= 0; rk--) {
+      const int32_t i = f.order[rk];
+      if (f.first_child[i] >= 0) { g[rk] = acc_g[rk]; sub_end[rk] = acc_end[rk] > end[rk] ? acc_end[rk] : end[rk]; }
+      if (par[rk] >= 0) {
+        acc_g[par[rk]] += g[rk];
+        if (sub_end[rk] > acc_end[par[rk]]) acc_end[par[rk]] = sub_end[rk];
+      }
+    }
+  }
+  const int32_t K = K_override > 0 ? K_override : f.n_leaves;
+
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    if (dfs_order) dfs_order[rk] = i;
+    if (node_start) node_start[rk] = start[rk];
+    if (node_end) node_end[rk] = end[rk];
+    if (subtree_end) subtree_end[rk] = sub_end[rk];
+    if (node_parent) node_parent[rk] = par[rk];
+    const int32_t gn = g_override ? g_override[i] : g[rk];
+    if (node_g) node_g[rk] = gn;
+    const float tr = (!trained || trained[i]) ? 1.0f : 0.0f;
+    const float w = K > 0 ? tr * ((float)gn / (float)K) : 0.0f;
+    for (int32_t t = start[rk]; t < end[rk]; t++) {
+      if (tok_node) tok_node[t] = rk;
+      if (tok_pos) tok_pos[t] = pos0[rk] + (t - start[rk]);
+      if (tok_pred) tok_pred[t] = t == start[rk] ? pred0[rk] : t - 1;
+      if (tok_weight) tok_weight[t] = w;
+      if (kend) kend[n_prefix + t] = n_prefix + sub_end[rk];
+    }
+  }
+  if (kend)
+    for (int32_t j = 0; j < n_prefix; j++) kend[j] = (!prefix_visible || prefix_visible[j]) ? INT32_MAX : 0;
+
+  if (ktile_kend_min || ktile_kend_max) {
+    // computed from the same rule as kend so that they can be requested without it
+    auto kend_at = [&](int32_t j, const std::vector<int32_t>& tok_sub_end) -> int32_t {
+      if (j < n_prefix) return (!prefix_visible || prefix_visible[j]) ? INT32_MAX : 0;
+      return n_prefix + tok_sub_end[j - n_prefix];
+    };
+    std::vector<int32_t> tok_sub_end(N);
+    for (int32_t rk = 0; rk < n_nodes; rk++)
+      for (int32_t t = start[rk]; t < end[rk]; t++) tok_sub_end[t] = sub_end[rk];
+    int32_t tile = 0;
+    const int32_t lo[2] = {0, n_prefix}, hi[2] = {n_prefix, n_prefix + N};
+    for (int region = 0; region < 2; region++) {
+      for (int32_t s = lo[region]; s < hi[region]; s += TT_KTILE, tile++) {
+        int32_t mn = INT32_MAX, mx = INT32_MIN;
+        const int32_t e = s + TT_KTILE < hi[region] ? s + TT_KTILE : hi[region];
+        for (int32_t j = s; j < e; j++) {
+          const int32_t v = kend_at(j, tok_sub_end);
+          mn = v < mn ? v : mn;
+          mx = v > mx ? v : mx;
+        }
+        if (ktile_kend_min) ktile_kend_min[tile] = mn;
+        if (ktile_kend_max) ktile_kend_max[tile] = mx;
+      }
+    }
+  }
+  return TT_OK;
+}

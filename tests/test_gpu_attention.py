@@ -1,0 +1,169 @@
+"""GPU parity: tree attention forward/backward through the C ABI against the per-branch CPU oracle.
+
+Tolerances (relative L2 over the whole tensor): fp32 path 1e-5; bf16 path 1e-2 for O and LSE,
+2e-2 for dQ/dK/dV.  The oracle consumes the same (bf16-rounded) inputs upcast to fp32."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_00413_amd as T
+import workloads as W
+from oracle import attention as A
+from oracle import meta as M
+from tt_testutil import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": dict(o=1e-5, lse=1e-5, dq=1e-5, dk=1e-5, dv=1e-5),
+       "bf16": dict(o=1e-2, lse=1e-2, dq=2e-2, dk=2e-2, dv=2e-2)}
+
+
+def _full_parity(tree, dims, seed, scale=None, reference_kernels=False, label=""):
+    from gpu_util import gpu_attention
+    meta = T.tree_build_meta(tree.parent, tree.seg_len, tree.trained)
+    om = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = meta.n_tokens
+    q, k, v, do = W.attn_inputs(n, n, dims, seed)
+    print(f"[case] {label} {tree.name} N={n} hq={dims.hq} hkv={dims.hkv} d={dims.d} {dims.dtype} ref={reference_kernels}", flush=True)
+    got = gpu_attention(meta, q, k, v, do, scale=scale, reference_kernels=reference_kernels)
+    want = A.branches(om, q.float(), k.float(), v.float(), do.float(), scale=scale)
+    errs = {key: rel_l2(got[key], want[key]) for key in ("o", "lse", "dq", "dk", "dv")}
+    print("   rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
+    for key, e in errs.items():
+        assert e <= TOL[dims.dtype][key], (key, e)
+    return errs
+
+
+def test_cfg1_fp32_worked_tree():
+    _full_parity(W.tree_cfg1(), W.DIMS[1], 1, label="cfg1")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_fp32_random_trees(seed):
+    t = W.random_tree(50 + seed, n_nodes=2 + 3 * seed, lo=1, hi=90, n_roots=1 + seed % 2, p_zero=0.15)
+    if t.n_tokens == 0:
+        pytest.skip("empty tree drawn")
+    hq, hkv, d = [(4, 4, 64), (8, 2, 128), (6, 3, 72), (2, 1, 256), (4, 2, 8), (8, 8, 32)][seed]
+    _full_parity(t, W.AttnDims(hq, hkv, d, "fp32", 1.0), seed, scale=0.2 if seed % 2 else None, label="fp32-random")
+
+
+@pytest.mark.parametrize("ref", [True, False], ids=["reference-kernels", "mfma"])
+@pytest.mark.parametrize("seed", range(4))
+def test_bf16_random_trees(seed, ref):
+    # several 64/128-token tiles per node, ragged tails, zero-length nodes, forests
+    t = W.random_tree(70 + seed, n_nodes=3 + 4 * seed, lo=1, hi=400, n_roots=1 + seed % 2, p_zero=0.1)
+    hq, hkv = [(4, 1), (8, 2), (4, 4), (16, 2)][seed]
+    _full_parity(t, W.AttnDims(hq, hkv, 128, "bf16", 0.5), seed, reference_kernels=ref, label="bf16-random")
+
+
+def test_bf16_chain_is_causal_attention():
+    _full_parity(W.chain_tree([300, 1, 211]), W.AttnDims(4, 2, 128, "bf16", 0.5), 3, label="chain")
+
+
+def test_bf16_forest_of_chains():
+    _full_parity(W.forest_of_chains([130, 64, 1, 257]), W.AttnDims(4, 2, 128, "bf16", 0.5), 4, label="forest")
+
+
+def test_bf16_single_token_and_tiny():
+    _full_parity(W.chain_tree([1]), W.AttnDims(2, 1, 128, "bf16", 0.5), 5, label="one-token")
+    _full_parity(W.tree_cfg1(), W.AttnDims(4, 4, 128, "bf16", 0.5), 6, label="cfg1-shape-bf16")
+
+
+def test_empty_tree_is_a_no_op():
+    from gpu_util import gpu_attention
+    meta = T.tree_build_meta([-1], [0])
+    dims = W.AttnDims(2, 1, 128, "bf16", 0.5)
+    q, k, v, do = W.attn_inputs(0, 0, dims, 1)
+    got = gpu_attention(meta, q, k, v, do)
+    assert got["o"].shape == (0, 2, 128) and got["dk"].shape == (0, 1, 128)
+
+
+def _prefix_case(dtype, seed, P, vis, chunk, hq, hkv, d, ref=False):
+    """Chunk behind a cached prefix vs the oracle on the equivalent whole tree: a root node made
+    of the visible prefix tokens with the chunk's roots hanging below it."""
+    from gpu_util import gpu_attention
+    dims = W.AttnDims(hq, hkv, d, dtype, 0.5 if dtype == "bf16" else 1.0)
+    nvis = int(vis.sum())
+    meta = T.tree_build_meta(chunk.parent, chunk.seg_len, chunk.trained, n_prefix=P, prefix_visible=vis,
+                             root_pos_offset=[nvis] * int((chunk.parent < 0).sum()))
+    n = meta.n_tokens
+    q, k, v, do = W.attn_inputs(n, n, dims, seed)
+    _, kp, vp, _ = W.attn_inputs(1, P, dims, seed + 100)
+    print(f"[case] prefix P={P} visible={nvis} N={n} {dtype} ref={ref}", flush=True)
+    got = gpu_attention(meta, q, k, v, do, k_prefix=kp, v_prefix=vp, reference_kernels=ref)
+    # whole tree: node 0 = visible prefix tokens, chunk nodes shifted by one
+    parent = np.concatenate([[-1], np.where(chunk.parent < 0, 0, chunk.parent + 1)]).astype(np.int32)
+    seg = np.concatenate([[nvis], chunk.seg_len]).astype(np.int32)
+    om = M.dfs_meta(parent, seg)
+    assert np.array_equal(om["tok_pos"][nvis:], meta.tok_pos)           # depth-based positions agree
+    sel = torch.from_numpy(np.nonzero(vis)[0])
+    # oracle order of the chunk tokens equals the library's DFS order (same child order)
+    qw = torch.cat([torch.zeros(nvis, hq, d), q.float()])
+    dow = torch.cat([torch.zeros(nvis, hq, d), do.float()])
+    kw = torch.cat([kp.float()[sel], k.float()])
+    vw = torch.cat([vp.float()[sel], v.float()])
+    want = A.branches(om, qw, kw, vw, dow)
+    tol = TOL[dtype]
+    errs = dict(o=rel_l2(got["o"], want["o"][nvis:]), lse=rel_l2(got["lse"], want["lse"][:, nvis:]),
+                dq=rel_l2(got["dq"], want["dq"][nvis:]), dk=rel_l2(got["dk"], want["dk"][nvis:]),
+                dv=rel_l2(got["dv"], want["dv"][nvis:]))
+    if nvis:
+        # fp32 accumulators: compare at fp32-level tolerance scaled by the bf16 product error
+        errs["dk_prefix"] = rel_l2(got["dk_prefix"][sel.numpy()], want["dk"][:nvis])
+        errs["dv_prefix"] = rel_l2(got["dv_prefix"][sel.numpy()], want["dv"][:nvis])
+    print("   rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
+    for key, e in errs.items():
+        assert e <= tol[key.split("_")[0]], (key, e)
+    hidden = np.nonzero(vis == 0)[0]
+    assert np.all(got["dk_prefix"][hidden] == 0) and np.all(got["dv_prefix"][hidden] == 0)
+    return meta, (q, k, v, do, kp, vp), got
+
+
+@pytest.mark.parametrize("dtype,ref", [("fp32", False), ("bf16", True), ("bf16", False)])
+def test_partition_prefix(dtype, ref):
+    s = W.step_cfg5(seed=3, n_chunk=700, n_prefix=900 + 37, lo=60, hi=300, root_visible=250)
+    _prefix_case(dtype, 11, s.n_prefix, s.prefix_visible, s.chunk, 4, 2, 128 if dtype == "bf16" else 64, ref)
+    allv = np.ones(200, dtype=np.uint8)
+    _prefix_case(dtype, 12, 200, allv, W.chain_tree([150]), 2, 1, 128 if dtype == "bf16" else 64, ref)
+
+
+def test_prefix_gradients_accumulate():
+    from gpu_util import gpu_attention
+    s = W.step_cfg5(seed=4, n_chunk=300, n_prefix=256, lo=50, hi=120, root_visible=100)
+    meta, (q, k, v, do, kp, vp), first = _prefix_case("bf16", 13, s.n_prefix, s.prefix_visible, s.chunk, 4, 2, 128)
+    acc = (torch.full(kp.shape, 1.5, dtype=torch.float32, device="cuda"),
+           torch.full(kp.shape, -2.0, dtype=torch.float32, device="cuda"))
+    again = gpu_attention(meta, q, k, v, do, k_prefix=kp, v_prefix=vp, prefix_acc=acc)
+    vis = s.prefix_visible.astype(bool)
+    assert np.allclose(again["dk_prefix"][vis], first["dk_prefix"][vis] + 1.5, rtol=0, atol=1e-5)
+    assert np.all(again["dv_prefix"][~vis] == -2.0)
+
+
+def test_deterministic_run_to_run():
+    from gpu_util import gpu_attention
+    t = W.random_tree(91, n_nodes=9, lo=30, hi=300)
+    meta = T.tree_build_meta(t.parent, t.seg_len)
+    dims = W.AttnDims(8, 2, 128, "bf16", 0.5)
+    q, k, v, do = W.attn_inputs(meta.n_tokens, meta.n_tokens, dims, 9)
+    a = gpu_attention(meta, q, k, v, do)
+    b = gpu_attention(meta, q, k, v, do)
+    for key in ("o", "lse", "dq", "dk", "dv"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_token_strides_of_a_fused_qkv_buffer():
+    from gpu_util import gpu_attention, dev, f64
+    t = W.random_tree(92, n_nodes=5, lo=20, hi=150)
+    meta = T.tree_build_meta(t.parent, t.seg_len)
+    n = meta.n_tokens
+    dims = W.AttnDims(4, 2, 128, "bf16", 0.5)
+    q, k, v, do = W.attn_inputs(n, n, dims, 10)
+    plain = gpu_attention(meta, q, k, v, do)
+    fused = torch.cat([q.reshape(n, -1), k.reshape(n, -1), v.reshape(n, -1)], dim=1).to("cuda")
+    qv = fused[:, :4 * 128].view(n, 4, 128)
+    kv = fused[:, 4 * 128:6 * 128].view(n, 2, 128)
+    vv = fused[:, 6 * 128:].view(n, 2, 128)
+    kend, kmin, kmax = dev(meta.kend), dev(meta.ktile_kend_min), dev(meta.ktile_kend_max)
+    o, lse = T.tree_attn_fwd(qv, kv, vv, kend, kmin, kmax)
+    dq, dk, dv = T.tree_attn_bwd(qv, kv, vv, kend, kmin, kmax, o, dev(do), lse)
+    assert np.array_equal(f64(o), plain["o"]) and np.array_equal(f64(dk), plain["dk"]) and np.array_equal(f64(dq), plain["dq"])

@@ -1,0 +1,90 @@
+"""The C-ABI library loads on a CPU-only box, exports every symbol the header declares, and
+reports invalid arguments by status code before launching anything (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_00413_amd as T
+from paper_2511_00413_amd import binding as B
+from tt_testutil import ROOT
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "treetrain.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol():
+    lib = ctypes.CDLL(T.lib_path())
+    names = _declared_symbols()
+    assert {"tt_tree_build_meta", "tt_tree_attn_fwd", "tt_tree_attn_bwd", "tt_tree_weighted_logprob",
+            "tt_tree_attn_workspace", "tt_tree_meta_sizes", "tt_last_error", "tt_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert T.version() >= 100
+
+
+def test_header_constants_match_binding():
+    text = open(os.path.join(ROOT, "include", "treetrain.h")).read()
+    assert int(re.search(r"#define TT_KTILE (\d+)", text).group(1)) == T.KTILE
+    assert int(re.search(r"#define TT_DTYPE_BF16 (\d+)", text).group(1)) == B.DTYPE_BF16
+    assert int(re.search(r"#define TT_DTYPE_FP32 (\d+)", text).group(1)) == B.DTYPE_FP32
+
+
+@pytest.mark.parametrize("parent,seg,code", [
+    ([1, 0], [1, 1], -3),          # cycle
+    ([0], [1], -3),                # self loop
+    ([-1, 5], [1, 1], -3),         # out of range
+    ([-1, -2], [1, 1], -3),
+    ([-1, 0], [1, -1], -2),        # negative length
+    ([-1, 0], [2**30, 2**30], -2), # token count overflows int32
+])
+def test_meta_rejects_bad_trees(parent, seg, code):
+    with pytest.raises(T.TreeTrainError) as e:
+        T.tree_build_meta(parent, seg)
+    assert e.value.status == code and T.last_error()
+
+
+def test_meta_empty_inputs():
+    m = T.tree_build_meta([], [])
+    assert m.n_tokens == 0 and m.n_leaves == 0 and m.n_ktiles == 0
+    m = T.tree_build_meta([-1, 0], [0, 0])
+    assert m.n_tokens == 0 and m.n_leaves == 1
+
+
+def test_device_calls_validate_before_launch():
+    lib = B._lib()
+    d = B._AttnDesc(16, 0, 4, 2, 128, 0, 0.1, 0, 0, 0, 0)
+    assert lib.tt_tree_attn_workspace(ctypes.byref(d), 0) > 0
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(4096)         # never dereferenced: the call must fail before any launch
+    rc = lib.tt_tree_attn_fwd(ctypes.byref(d), null, null, null, null, null, null, null, null, null, null, null, 0, null)
+    assert rc == -1
+    rc = lib.tt_tree_attn_fwd(ctypes.byref(d), fake, fake, fake, null, null, fake, fake, fake, fake, fake, null, 0, null)
+    assert rc == -6                      # workspace missing
+    rc = lib.tt_tree_attn_fwd(ctypes.byref(d), ctypes.c_void_p(4100), fake, fake, null, null, fake, fake, fake, fake, fake, fake, 1 << 20, null)
+    assert rc == -5                      # misaligned q
+    rc = lib.tt_tree_attn_fwd(ctypes.byref(d), fake, fake, fake, fake, null, fake, fake, fake, fake, fake, fake, 1 << 20, null)
+    assert rc == -1                      # prefix pointers without n_prefix
+    for bad in (dict(hq=3), dict(d=100), dict(dtype=7), dict(scale=0.0), dict(flags=64), dict(n_q=-1)):
+        vals = dict(n_q=16, n_prefix=0, hq=4, hkv=2, d=128, dtype=0, scale=0.1, flags=0)
+        vals.update(bad)
+        dd = B._AttnDesc(vals["n_q"], vals["n_prefix"], vals["hq"], vals["hkv"], vals["d"], vals["dtype"],
+                         vals["scale"], vals["flags"], 0, 0, 0)
+        assert lib.tt_tree_attn_workspace(ctypes.byref(dd), 0) == 0, bad
+        rc = lib.tt_tree_attn_fwd(ctypes.byref(dd), fake, fake, fake, null, null, fake, fake, fake, fake, fake, fake, 1 << 20, null)
+        assert rc < 0 and T.last_error(), bad
+    rc = lib.tt_tree_attn_bwd(ctypes.byref(d), *([fake] * 3), null, null, *([fake] * 3), *([fake] * 3), fake, fake, null, null, null, fake, 1 << 30, null)
+    assert rc == -1                      # dv_own NULL
+    rc = lib.tt_tree_weighted_logprob(4, 0, 0, fake, 0, fake, null, fake, null, null, null)
+    assert rc == -2
+    rc = lib.tt_tree_weighted_logprob(4, 128, 3, fake, 0, fake, null, fake, null, null, null)
+    assert rc == -4
+    rc = lib.tt_tree_weighted_logprob(4, 128, 0, fake, 64, fake, null, fake, null, null, null)
+    assert rc == -2                      # row stride smaller than vocab
+    rc = lib.tt_tree_weighted_logprob(4, 128, 0, null, 0, fake, null, fake, null, null, null)
+    assert rc == -1
