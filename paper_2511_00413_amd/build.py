@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtreetrain.so")
 
 SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_attn_ref.hip", "tt_loss.hip",
-           "tt_attn_mfma_stub.hip"]
+           "tt_attn_fwd.hip", "tt_attn_bwd.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

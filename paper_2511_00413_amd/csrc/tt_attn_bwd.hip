@@ -1,0 +1,514 @@
+// Tree attention backward on bf16 MFMA (gfx950), head dim 128.
+//
+//   D_i = <dO_i, O_i>;  P = exp(S - LSE);  dP = dO V^T;  dS = P o (dP - D);
+//   dQ = scale dS K;    dK = scale dS^T Q;  dV = P^T dO
+// dK/dV of a key sum over every visible query, i.e. over all branches through the key (paper
+// Eq. 5), and over the query heads of the kv group.  Gradients of cached prefix keys are added
+// in fp32 to caller-owned accumulators (Appendix "Float32 Gradient Accumulation").
+//
+// Three kernels, no atomics (results are bit-reproducible):
+//   delta     D_i                                                      (memory bound)
+//   dkdv      column-parallel: one workgroup = 128 keys x one kv head, 4 wavefronts x 32 keys;
+//             loops over the query heads of the group and over the query tiles that can see the
+//             keys -- a contiguous range [first key, max kend) because in DFS order a subtree is
+//             contiguous.  S[q,key] = Q K^T and dP[q,key] = dO V^T come out with one key per lane,
+//             already in B-operand layout for dV^T[d,key] += dO^T[d,q] P[q,key] and
+//             dK^T[d,key] += Q^T[d,q] dS[q,key]; Q^T / dO^T come from transposed LDS reads.
+//   dq        row-parallel, same structure as the forward: S^T = K Q^T, dP^T = V dO^T with one
+//             query per lane, dQ^T[d,q] += K^T[d,key] dS^T[key,q].
+#include <hip/hip_runtime.h>
+#include "tt_kernels.h"
+#include "tt_mfma.h"
+
+namespace tt {
+namespace {
+
+constexpr int D = 128;
+constexpr int NTHREADS = 256;
+constexpr int RP = D + 8;          // LDS row pitch (elements) of every staged tile: 272 B
+
+// ------------------------------------------------------------------------------------------------
+// delta[h][i] = sum_d dO[i][h][d] * O[i][h][d]; one wavefront per (token, head) row of 128
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NTHREADS)
+delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, float* __restrict__ delta,
+             int n_q, int hq) {
+  const int64_t row = (int64_t)blockIdx.x * (NTHREADS / 16) + (threadIdx.x >> 4);   // 16 lanes per row
+  const int sub = threadIdx.x & 15;
+  float acc = 0.f;
+  if (row < (int64_t)n_q * hq) {
+    const bf16x8 a = *(const bf16x8*)(o + row * D + sub * 8);
+    const bf16x8 b = *(const bf16x8*)(d_o + row * D + sub * 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc = fmaf((float)a[e], (float)b[e], acc);
+  }
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if (sub == 0 && row < (int64_t)n_q * hq) {
+    const int i = (int)(row / hq), h = (int)(row % hq);
+    delta[(int64_t)h * n_q + i] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dK / dV
+// ------------------------------------------------------------------------------------------------
+constexpr int KV_BN = 128;         // keys per workgroup (two TT_KTILE summaries)
+constexpr int KV_BM = 64;          // queries per staged tile
+
+struct KvSmem {
+  __bf16 q[2][KV_BM * RP];
+  __bf16 g[2][KV_BM * RP];         // dO
+  float lse2[2][KV_BM];            // LSE in base-2 units
+  float delta[2][KV_BM];
+};
+
+struct KvStaging {
+  i32x4 q[4], g[4];
+  float lse2, delta;
+};
+
+__device__ __forceinline__ void kv_load(const AttnArgs& a, int h, int q0, KvStaging& st) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int c = t + NTHREADS * u;
+    const int row = c >> 4, col = (c & 15) * 8;
+    const int i = q0 + row;
+    i32x4 zq = {0, 0, 0, 0}, zg = {0, 0, 0, 0};
+    if (i < a.n_q) {
+      zq = *(const i32x4*)((const __bf16*)a.q + (int64_t)i * a.q_stride + (int64_t)h * D + col);
+      zg = *(const i32x4*)((const __bf16*)a.d_o + ((int64_t)i * a.hq + h) * D + col);
+    }
+    st.q[u] = zq;
+    st.g[u] = zg;
+  }
+  st.lse2 = 0.f; st.delta = 0.f;
+  if (t < KV_BM && q0 + t < a.n_q) {
+    st.lse2 = a.lse[(int64_t)h * a.n_q + q0 + t] * LOG2E_F;
+    st.delta = a.delta[(int64_t)h * a.n_q + q0 + t];
+  }
+}
+
+__device__ __forceinline__ void kv_store(KvSmem& sm, int buf, const KvStaging& st) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int c = t + NTHREADS * u;
+    const int row = c >> 4, col = (c & 15) * 8;
+    *(i32x4*)(&sm.q[buf][row * RP + col]) = st.q[u];
+    *(i32x4*)(&sm.g[buf][row * RP + col]) = st.g[u];
+  }
+  if (t < KV_BM) { sm.lse2[buf][t] = st.lse2; sm.delta[buf][t] = st.delta; }
+}
+
+__global__ void __launch_bounds__(NTHREADS, 1)
+tree_attn_dkdv_kernel(AttnArgs a, int n_ptiles, int n_otiles) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  KvSmem& sm = *reinterpret_cast<KvSmem*>(smem_raw);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c32 = lane & 31, hf = lane >> 5;
+  const int G = a.hq / a.hkv;
+  const int P = a.n_prefix, N = a.n_q;
+  const int bid = blockIdx.x;
+  const int kvh = bid % a.hkv;
+  const int tile = bid / a.hkv;                    // prefix tiles first, then own tiles
+  const bool is_prefix = tile < n_ptiles;
+  const int k0 = is_prefix ? tile * KV_BN : (tile - n_ptiles) * KV_BN;   // region-local first key
+  const int region = is_prefix ? P : N;
+  const int j0 = is_prefix ? k0 : P + k0;          // unified index of the first key
+  // this lane's key
+  const int kl = k0 + 32 * w + c32;
+  const bool key_ok = kl < region;
+  const int j = j0 + 32 * w + c32;
+  const int my_kend = key_ok ? a.kend[j] : 0;
+  // wave-level and workgroup-level bounds of kend
+  int kmax_w = my_kend, kmin_w = key_ok ? my_kend : INT32_MAX;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    kmax_w = max(kmax_w, __shfl_xor(kmax_w, off));
+    kmin_w = min(kmin_w, __shfl_xor(kmin_w, off));
+  }
+  __shared__ int s_kmax[4];
+  if (lane == 0) s_kmax[w] = kmax_w;
+  __syncthreads();
+  const int kmax = max(max(s_kmax[0], s_kmax[1]), max(s_kmax[2], s_kmax[3]));
+  // queries that can see a key of this tile: own index in [i_lo, i_hi)
+  const int i_lo = is_prefix ? 0 : k0;
+  const int i_hi = (int)min((int64_t)N, (int64_t)kmax - P);
+  const int qt_lo = i_lo / KV_BM;
+  const int qt_hi = i_hi > i_lo ? (i_hi + KV_BM - 1) / KV_BM : qt_lo;
+  const int n_steps = (qt_hi - qt_lo) * G;         // (head, query tile) pairs, head-major
+
+  // ---- K / V fragments of this wave's 32 keys (B operands: column = key, k = d) ----
+  bf16x8 kf[8], vf[8];
+  {
+    const int krow = min(kl, region - 1);
+    const __bf16* kp = is_prefix ? (const __bf16*)a.k_prefix + ((int64_t)krow * a.hkv + kvh) * D
+                                 : (const __bf16*)a.k_own + (int64_t)krow * a.k_stride + (int64_t)kvh * D;
+    const __bf16* vp = is_prefix ? (const __bf16*)a.v_prefix + ((int64_t)krow * a.hkv + kvh) * D
+                                 : (const __bf16*)a.v_own + (int64_t)krow * a.v_stride + (int64_t)kvh * D;
+#pragma unroll
+    for (int s = 0; s < 8; s++) {
+      kf[s] = *(const bf16x8*)(kp + 16 * s + 8 * hf);
+      vf[s] = *(const bf16x8*)(vp + 16 * s + 8 * hf);
+    }
+  }
+  f32x16 dk_acc[4], dv_acc[4];
+#pragma unroll
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
+  const float c_scale = a.scale * LOG2E_F;
+
+  auto step_head = [&](int s) { return kvh * G + s / (qt_hi - qt_lo); };
+  auto step_q0 = [&](int s) { return (qt_lo + s % (qt_hi - qt_lo)) * KV_BM; };
+
+  KvStaging st;
+  if (n_steps > 0) {
+    kv_load(a, step_head(0), step_q0(0), st);
+    kv_store(sm, 0, st);
+  }
+  __syncthreads();
+
+  const int a_rd = c32 * RP + 8 * hf;                                   // row-major A operand reads
+  const int i16 = lane & 15, gidx = (lane >> 4) & 1;
+  const int t_rd = (4 * hf + (i16 >> 2)) * RP + 16 * gidx + 4 * (i16 & 3);  // transposed reads
+  // first / last key of this wave's block, unified
+  const int jw_first = j0 + 32 * w;
+  const int jw_last = jw_first + 31;
+
+  for (int s = 0; s < n_steps; s++) {
+    const int buf = s & 1;
+    if (s + 1 < n_steps) kv_load(a, step_head(s + 1), step_q0(s + 1), st);
+    const int q0 = step_q0(s);
+
+#pragma unroll
+    for (int qb = 0; qb < 2; qb++) {
+      const int gq_first = P + q0 + 32 * qb;                 // unified index of the block's first query
+      const int gq_last = min(gq_first + 31, P + N - 1);
+      // block-level skip: every key is after the last query, or no key's range reaches the block
+      if (jw_first > gq_last || kmax_w <= gq_first) continue;
+      const bool full = jw_last <= gq_first && kmin_w > gq_last && q0 + 32 * qb + 31 < N;
+
+      f32x16 s_acc, p_acc;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { s_acc[r] = 0.f; p_acc[r] = 0.f; }
+#pragma unroll
+      for (int ss = 0; ss < 8; ss++) {
+        const bf16x8 qa = *(const bf16x8*)(&sm.q[buf][a_rd + qb * 32 * RP + 16 * ss]);
+        s_acc = mfma32(qa, kf[ss], s_acc);
+      }
+#pragma unroll
+      for (int ss = 0; ss < 8; ss++) {
+        const bf16x8 ga = *(const bf16x8*)(&sm.g[buf][a_rd + qb * 32 * RP + 16 * ss]);
+        p_acc = mfma32(ga, vf[ss], p_acc);
+      }
+      // P and dS (rows = queries: (r/4)*8 + 4*hf + r%4 inside the block)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const int ql = qb * 32 + r4 * 8 + 4 * hf;
+        const f32x4 l2 = *(const f32x4*)(&sm.lse2[buf][ql]);
+        const f32x4 dl = *(const f32x4*)(&sm.delta[buf][ql]);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          float p = exp2f(fmaf(s_acc[r4 * 4 + e], c_scale, -l2[e]));
+          if (!full) {
+            const int gq = P + q0 + ql + e;
+            const bool vis = j <= gq && gq < my_kend && gq < P + N;
+            p = vis ? p : 0.f;
+          }
+          s_acc[r4 * 4 + e] = p;
+          p_acc[r4 * 4 + e] = p * (p_acc[r4 * 4 + e] - dl[e]);
+        }
+      }
+      // dV^T += dO^T P ; dK^T += Q^T dS
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        const bf16x8 pf = cvt8(s_acc[8 * t + 0], s_acc[8 * t + 1], s_acc[8 * t + 2], s_acc[8 * t + 3],
+                               s_acc[8 * t + 4], s_acc[8 * t + 5], s_acc[8 * t + 6], s_acc[8 * t + 7]);
+        const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
+                               p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
+#pragma unroll
+        for (int db = 0; db < 4; db++) {
+          const int off = t_rd + (qb * 32 + 16 * t) * RP + 32 * db;
+          const bf16x8 gt = cat4(lds_read_tr(&sm.g[buf][off]), lds_read_tr(&sm.g[buf][off + 8 * RP]));
+          dv_acc[db] = mfma32(gt, pf, dv_acc[db]);
+          const bf16x8 qtf = cat4(lds_read_tr(&sm.q[buf][off]), lds_read_tr(&sm.q[buf][off + 8 * RP]));
+          dk_acc[db] = mfma32(qtf, df, dk_acc[db]);
+        }
+      }
+    }
+
+    if (s + 1 < n_steps) kv_store(sm, buf ^ 1, st);
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulators hold dK^T / dV^T: column = key, rows d = db*32 + (r/4)*8 + 4*hf + r%4 ----
+  if (key_ok) {
+    if (is_prefix) {
+      if (my_kend > P) {       // a visible prefix key; others receive nothing
+        float* dkp = a.dk_prefix_acc + ((int64_t)kl * a.hkv + kvh) * D;
+        float* dvp = a.dv_prefix_acc + ((int64_t)kl * a.hkv + kvh) * D;
+#pragma unroll
+        for (int db = 0; db < 4; db++)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; r4++) {
+            const int d0 = db * 32 + r4 * 8 + 4 * hf;
+            f32x4 ck = *(f32x4*)(dkp + d0), cv = *(f32x4*)(dvp + d0);
+#pragma unroll
+            for (int e = 0; e < 4; e++) { ck[e] += a.scale * dk_acc[db][r4 * 4 + e]; cv[e] += dv_acc[db][r4 * 4 + e]; }
+            *(f32x4*)(dkp + d0) = ck;
+            *(f32x4*)(dvp + d0) = cv;
+          }
+      }
+    } else {
+      __bf16* dkp = (__bf16*)a.dk_own + ((int64_t)kl * a.hkv + kvh) * D;
+      __bf16* dvp = (__bf16*)a.dv_own + ((int64_t)kl * a.hkv + kvh) * D;
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++) {
+          const int d0 = db * 32 + r4 * 8 + 4 * hf;
+          *(bf16x4*)(dkp + d0) = cvt4(a.scale * dk_acc[db][r4 * 4 + 0], a.scale * dk_acc[db][r4 * 4 + 1],
+                                      a.scale * dk_acc[db][r4 * 4 + 2], a.scale * dk_acc[db][r4 * 4 + 3]);
+          *(bf16x4*)(dvp + d0) = cvt4(dv_acc[db][r4 * 4 + 0], dv_acc[db][r4 * 4 + 1],
+                                      dv_acc[db][r4 * 4 + 2], dv_acc[db][r4 * 4 + 3]);
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dQ
+// ------------------------------------------------------------------------------------------------
+constexpr int Q_BM = 128;          // queries per workgroup
+constexpr int Q_BN = 64;           // keys per tile (= TT_KTILE)
+
+struct QSmem {
+  __bf16 k[2][Q_BN * RP];
+  __bf16 v[2][Q_BN * RP];
+  int32_t kend[2][Q_BN];
+};
+
+struct QStaging {
+  i32x4 k[4], v[4];
+  int32_t kend;
+};
+
+struct QTileSrc {
+  const __bf16 *k, *v;
+  int64_t k_stride, v_stride;
+  int rows;
+  const int32_t* kend;
+};
+
+__device__ __forceinline__ void q_load(const QTileSrc& s, QStaging& st) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int c = t + NTHREADS * u;
+    const int row = c >> 4, col = (c & 15) * 8;
+    i32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
+    if (row < s.rows) {
+      zk = *(const i32x4*)(s.k + (int64_t)row * s.k_stride + col);
+      zv = *(const i32x4*)(s.v + (int64_t)row * s.v_stride + col);
+    }
+    st.k[u] = zk;
+    st.v[u] = zv;
+  }
+  st.kend = (t < Q_BN && t < s.rows) ? s.kend[t] : 0;
+}
+
+__device__ __forceinline__ void q_store(QSmem& sm, int buf, const QStaging& st) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int c = t + NTHREADS * u;
+    const int row = c >> 4, col = (c & 15) * 8;
+    *(i32x4*)(&sm.k[buf][row * RP + col]) = st.k[u];
+    *(i32x4*)(&sm.v[buf][row * RP + col]) = st.v[u];
+  }
+  if (t < Q_BN) sm.kend[buf][t] = st.kend;
+}
+
+__global__ void __launch_bounds__(NTHREADS, 1)
+tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  QSmem& sm = *reinterpret_cast<QSmem*>(smem_raw);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c32 = lane & 31, hf = lane >> 5;
+  const int G = a.hq / a.hkv;
+  const int bid = blockIdx.x;
+  const int kvh = bid % a.hkv;
+  const int rest = bid / a.hkv;
+  const int h = kvh * G + rest % G;
+  const int qt = n_qtiles - 1 - rest / G;
+  const int q0 = qt * Q_BM;
+  const int P = a.n_prefix, N = a.n_q;
+  const int q_hi = min(q0 + Q_BM, N);
+  const int gi_first = P + q0, gi_last = P + q_hi - 1;
+  const int npt = (P + Q_BN - 1) / Q_BN;
+  const int u_end = npt + (q_hi - 1) / Q_BN + 1;
+
+  const int q = q0 + 32 * w + c32;
+  const int my_q = min(q, N - 1);
+  const int gi = P + q;
+  bf16x8 qf[8], gf[8];
+  {
+    const __bf16* qp = (const __bf16*)a.q + (int64_t)my_q * a.q_stride + (int64_t)h * D + 8 * hf;
+    const __bf16* gp = (const __bf16*)a.d_o + ((int64_t)my_q * a.hq + h) * D + 8 * hf;
+#pragma unroll
+    for (int s = 0; s < 8; s++) { qf[s] = *(const bf16x8*)(qp + 16 * s); gf[s] = *(const bf16x8*)(gp + 16 * s); }
+  }
+  const float lse2 = a.lse[(int64_t)h * N + my_q] * LOG2E_F;
+  const float delta = a.delta[(int64_t)h * N + my_q];
+  const float c_scale = a.scale * LOG2E_F;
+
+  f32x16 dq_acc[4];
+#pragma unroll
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) dq_acc[db][r] = 0.f;
+
+  KTileIter it;
+  it.init(a.kt_max, u_end, gi_first);
+  auto tile_src = [&](int u) {
+    QTileSrc s;
+    if (u < npt) {
+      const int k0 = u * Q_BN;
+      s.k = (const __bf16*)a.k_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
+      s.v = (const __bf16*)a.v_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
+      s.k_stride = s.v_stride = (int64_t)a.hkv * D;
+      s.rows = min(Q_BN, P - k0);
+      s.kend = a.kend + k0;
+    } else {
+      const int k0 = (u - npt) * Q_BN;
+      s.k = (const __bf16*)a.k_own + (int64_t)k0 * a.k_stride + (int64_t)kvh * D;
+      s.v = (const __bf16*)a.v_own + (int64_t)k0 * a.v_stride + (int64_t)kvh * D;
+      s.k_stride = a.k_stride; s.v_stride = a.v_stride;
+      s.rows = min(Q_BN, N - k0);
+      s.kend = a.kend + P + k0;
+    }
+    return s;
+  };
+  auto tile_j0 = [&](int u) { return u < npt ? u * Q_BN : P + (u - npt) * Q_BN; };
+
+  QStaging st;
+  int u_cur = it.next();
+  if (u_cur >= 0) {
+    q_load(tile_src(u_cur), st);
+    q_store(sm, 0, st);
+  }
+  __syncthreads();
+  int buf = 0;
+
+  const int a_rd = c32 * RP + 8 * hf;
+  const int i16 = lane & 15, gidx = (lane >> 4) & 1;
+  const int t_rd = (4 * hf + (i16 >> 2)) * RP + 16 * gidx + 4 * (i16 & 3);
+
+  while (u_cur >= 0) {
+    const int u_next = it.next();
+    if (u_next >= 0) q_load(tile_src(u_next), st);
+    const int j0 = tile_j0(u_cur);
+    const int rows = u_cur < npt ? min(Q_BN, P - u_cur * Q_BN) : min(Q_BN, N - (u_cur - npt) * Q_BN);
+    const bool full = rows == Q_BN && j0 + Q_BN - 1 <= gi_first && a.kt_min[u_cur] > gi_last;
+
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      f32x16 s_acc, p_acc;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { s_acc[r] = 0.f; p_acc[r] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < 8; s++) {
+        const bf16x8 ka = *(const bf16x8*)(&sm.k[buf][a_rd + kb * 32 * RP + 16 * s]);
+        s_acc = mfma32(ka, qf[s], s_acc);
+      }
+#pragma unroll
+      for (int s = 0; s < 8; s++) {
+        const bf16x8 va = *(const bf16x8*)(&sm.v[buf][a_rd + kb * 32 * RP + 16 * s]);
+        p_acc = mfma32(va, gf[s], p_acc);
+      }
+      // dS^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const int jl = kb * 32 + r4 * 8 + 4 * hf;
+        i32x4 ke = {0, 0, 0, 0};
+        if (!full) ke = *(const i32x4*)(&sm.kend[buf][jl]);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          float p = exp2f(fmaf(s_acc[r4 * 4 + e], c_scale, -lse2));
+          if (!full) {
+            const int j = j0 + jl + e;
+            p = (j <= gi && gi < ke[e]) ? p : 0.f;
+          }
+          p_acc[r4 * 4 + e] = p * (p_acc[r4 * 4 + e] - delta);
+        }
+      }
+      // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
+                               p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
+#pragma unroll
+        for (int db = 0; db < 4; db++) {
+          const int off = t_rd + (kb * 32 + 16 * t) * RP + 32 * db;
+          const bf16x8 kt = cat4(lds_read_tr(&sm.k[buf][off]), lds_read_tr(&sm.k[buf][off + 8 * RP]));
+          dq_acc[db] = mfma32(kt, df, dq_acc[db]);
+        }
+      }
+    }
+
+    if (u_next >= 0) q_store(sm, buf ^ 1, st);
+    __syncthreads();
+    buf ^= 1;
+    u_cur = u_next;
+  }
+
+  if (q < N) {
+    __bf16* dqp = (__bf16*)a.dq + ((int64_t)q * a.hq + h) * D;
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const int d0 = db * 32 + r4 * 8 + 4 * hf;
+        *(bf16x4*)(dqp + d0) = cvt4(a.scale * dq_acc[db][r4 * 4 + 0], a.scale * dq_acc[db][r4 * 4 + 1],
+                                    a.scale * dq_acc[db][r4 * 4 + 2], a.scale * dq_acc[db][r4 * 4 + 3]);
+      }
+  }
+}
+
+}  // namespace
+
+size_t mfma_attn_workspace(int, int, int, int, int, bool) { return 0; }
+
+hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st) {
+  if (a.n_q == 0) return hipSuccess;
+  {
+    const int64_t rows = (int64_t)a.n_q * a.hq;
+    const int rows_per_block = NTHREADS / 16;
+    delta_kernel<<<(unsigned)((rows + rows_per_block - 1) / rows_per_block), NTHREADS, 0, st>>>(
+        (const __bf16*)a.o, (const __bf16*)a.d_o, a.delta, a.n_q, a.hq);
+    if (hipError_t e = hipGetLastError()) return e;
+  }
+  {
+    const int n_ptiles = (a.n_prefix + KV_BN - 1) / KV_BN, n_otiles = (a.n_q + KV_BN - 1) / KV_BN;
+    if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_dkdv_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KvSmem)))
+      return e;
+    const int64_t blocks = (int64_t)(n_ptiles + n_otiles) * a.hkv;
+    tree_attn_dkdv_kernel<<<(unsigned)blocks, NTHREADS, sizeof(KvSmem), st>>>(a, n_ptiles, n_otiles);
+    if (hipError_t e = hipGetLastError()) return e;
+  }
+  {
+    const int n_qtiles = (a.n_q + Q_BM - 1) / Q_BM;
+    if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_dq_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(QSmem)))
+      return e;
+    tree_attn_dq_kernel<<<(unsigned)((int64_t)n_qtiles * a.hq), NTHREADS, sizeof(QSmem), st>>>(a, n_qtiles);
+    if (hipError_t e = hipGetLastError()) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace tt
