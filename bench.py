@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-attention hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic tree: host metadata build
+(tree_build_meta) + upload of the mask bounds, tree attention forward, backward, and the weighted
+log-prob loss.  The headline value is the attention forward+backward rate in *useful* TFLOP/s:
+14 * Hq * D * visible_pairs flops (4 D per pair forward, 10 D backward) divided by the forward +
+backward time measured with events on the launch stream.  Inputs are resident in HBM before the
+timed region starts.
+
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="benchmark configuration (5 = one partition step: 32K chunk x 64K prefix)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-linearized", action="store_true")
+    ap.add_argument("--no-loss", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_00413_amd as T
+    from paper_2511_00413_amd import linearize
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = args.config
+    dims = W.DIMS[cfg]
+    tdt = torch.bfloat16 if dims.dtype == "bf16" else torch.float32
+
+    # ---------------- workload ----------------
+    if cfg == 5:
+        step_w = W.step_cfg5()
+        tree, n_prefix, prefix_visible = step_w.chunk, step_w.n_prefix, step_w.prefix_visible
+        root_off = [int(prefix_visible.sum())]
+        workload = "cfg5-step: 32768-token chunk (8 nodes) x 65536 cached prefix keys (variant b), GQA 64/8, d=128, bf16"
+    else:
+        tree, n_prefix, prefix_visible, root_off = W.tree_config(cfg), 0, None, None
+        workload = {
+            1: "cfg1: worked 3-leaf tree, N=240, MHA 4x64, fp32",
+            2: "cfg2: random depth-4 tree seed 117, N=16406, GQA 32/8, d=128, bf16, vocab 32768",
+            3: "cfg3: agentic fan-out 8K->16x(2K->2x1K), N=73728, GQA 64/8, d=128, bf16, vocab 151936 in 4K-row chunks",
+            4: "cfg4: deep chain seed 195, N=131091, GQA 32/8, d=128, bf16",
+        }[cfg]
+
+    def build_meta():
+        return T.tree_build_meta(tree.parent, tree.seg_len, tree.trained, root_pos_offset=root_off,
+                                 n_prefix=n_prefix, prefix_visible=prefix_visible)
+
+    meta = build_meta()
+    N = meta.n_tokens
+    pairs = linearize.visible_pairs(meta)
+    q, k, v, do = (x.to(dev) for x in W.attn_inputs(N, N, dims, cfg))
+    kp = vp = dkp = dvp = None
+    if n_prefix:
+        _, kp, vp, _ = (x.to(dev) for x in W.attn_inputs(1, n_prefix, dims, cfg + 100))
+        dkp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
+        dvp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
+    kend_d = torch.empty(n_prefix + N, dtype=torch.int32, device=dev)
+    kmin_d = torch.empty(meta.n_ktiles, dtype=torch.int32, device=dev)
+    kmax_d = torch.empty(meta.n_ktiles, dtype=torch.int32, device=dev)
+    kend_h = torch.empty(n_prefix + N, dtype=torch.int32).pin_memory()
+    kmin_h = torch.empty(meta.n_ktiles, dtype=torch.int32).pin_memory()
+    kmax_h = torch.empty(meta.n_ktiles, dtype=torch.int32).pin_memory()
+    w_h = torch.empty(N, dtype=torch.float32).pin_memory()
+    w_d = torch.empty(N, dtype=torch.float32, device=dev)
+
+    # loss inputs (value distribution of the config; drawn on the device to keep start-up short)
+    do_loss = dims.vocab > 0 and not args.no_loss
+    loss_rows = 0
+    if do_loss:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg * 1000 + 5)
+        chunk_rows = N if cfg != 3 else 4096
+        logits = (torch.randn((chunk_rows, dims.vocab), generator=gen, device=dev, dtype=torch.float32)
+                  * dims.logit_std).to(torch.bfloat16 if dims.logit_dtype == "bf16" else torch.float32)
+        target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
+        logp = torch.empty(N, dtype=torch.float32, device=dev)
+        lse_l = torch.empty(N, dtype=torch.float32, device=dev)
+        loss_acc = torch.zeros(1, dtype=torch.float32, device=dev)
+        loss_rows = N
+
+    ws_f = torch.empty(T.tree_attn_workspace(q, k, v, n_prefix, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(T.tree_attn_workspace(q, k, v, n_prefix, True), dtype=torch.uint8, device=dev)
+    o = torch.empty_like(q)
+    lse = torch.empty((dims.hq, N), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(q)
+    dk = torch.empty_like(k)
+    dv = torch.empty_like(v)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    host_ms = []
+
+    def step(events=None):
+        t0 = time.perf_counter()
+        m = build_meta()                                   # a1-a4 on the host
+        kend_h.numpy()[:] = m.kend
+        kmin_h.numpy()[:] = m.ktile_kend_min
+        kmax_h.numpy()[:] = m.ktile_kend_max
+        w_h.numpy()[:] = m.tok_weight
+        kend_d.copy_(kend_h, non_blocking=True)
+        kmin_d.copy_(kmin_h, non_blocking=True)
+        kmax_d.copy_(kmax_h, non_blocking=True)
+        w_d.copy_(w_h, non_blocking=True)
+        host_ms.append((time.perf_counter() - t0) * 1e3)
+        if events:
+            events[0].record()
+        T.tree_attn_fwd(q, k, v, kend_d, kmin_d, kmax_d, k_prefix=kp, v_prefix=vp, o=o, lse=lse, workspace=ws_f)
+        if events:
+            events[1].record()
+        T.tree_attn_bwd(q, k, v, kend_d, kmin_d, kmax_d, o, do, lse, k_prefix=kp, v_prefix=vp,
+                        dk_prefix_acc=dkp, dv_prefix_acc=dvp, dq=dq, dk=dk, dv=dv, workspace=ws_b)
+        if events:
+            events[2].record()
+        if do_loss:
+            loss_acc.zero_()
+            rows = logits.shape[0]
+            for lo in range(0, N, rows):
+                n = min(rows, N - lo)
+                T.tree_weighted_logprob(logits[:n], target[lo:lo + n], w_d[lo:lo + n], loss_acc=loss_acc,
+                                        logp=logp[lo:lo + n], lse=lse_l[lo:lo + n])
+        if events:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    host_ms.clear()
+    T.kernel_timing_enable(True)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ktimes = T.kernel_timing_read()
+    T.kernel_timing_enable(False)
+
+    ms_fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    ms_bwd = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    ms_loss = sum(e[2].elapsed_time(e[3]) for e in ev) / args.steps
+    useful_flop = 14.0 * dims.hq * dims.d * pairs
+    value = useful_flop / ((ms_fwd + ms_bwd) * 1e-3) / 1e12
+
+    # ---------------- roofline of the dominant kernel ----------------
+    alg_flop = {"attn_fwd": 4.0, "attn_dkdv": 8.0, "attn_dq": 2.0, "ref_fwd": 4.0, "ref_bwd": 10.0}
+    attn_k = {n: t for n, t in ktimes.items() if n in alg_flop and t[1] > 0}
+    roofline = None
+    kernel_ms = {n: (t[0] / t[1]) for n, t in ktimes.items() if t[1] > 0}
+    if attn_k:
+        dom = max(attn_k, key=lambda n: attn_k[n][0])
+        avg_ms = attn_k[dom][0] / attn_k[dom][1]
+        achieved = alg_flop[dom] * dims.hq * dims.d * pairs / (avg_ms * 1e-3) / 1e12
+        peak = PEAK_BF16_TFLOPS if dims.dtype == "bf16" else 157.3
+        roofline = {"kernel": dom, "bound": "mfma" if dims.dtype == "bf16" else "alu", "achieved": round(achieved, 2),
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                    "avg_ms": round(avg_ms, 4),
+                    "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
+    loss_gbps = None
+    if do_loss and "loss_rows" in kernel_ms:
+        esz = 2 if dims.logit_dtype == "bf16" else 4
+        bytes_total = loss_rows * (dims.vocab * esz + 12)
+        loss_ms_total = ktimes["loss_rows"][0] / args.steps
+        loss_gbps = bytes_total / (loss_ms_total * 1e-3) / 1e9
+
+    # ---------------- linearised per-branch baseline on the same GPU ----------------
+    lin = None
+    if not args.no_linearized and n_prefix == 0:
+        idx, lparent, lseg = linearize.linearized_forest(meta)
+        lmeta = T.tree_build_meta(lparent, lseg)
+        idx_d = torch.from_numpy(idx).to(dev)
+        ql, kl, vl, dol = (x.index_select(0, idx_d) for x in (q, k, v, do))
+        lk = [torch.from_numpy(x).to(dev) for x in (lmeta.kend, lmeta.ktile_kend_min, lmeta.ktile_kend_max)]
+        ol = torch.empty_like(ql); lsel = torch.empty((dims.hq, len(idx)), dtype=torch.float32, device=dev)
+        dql = torch.empty_like(ql); dkl = torch.empty_like(kl); dvl = torch.empty_like(vl)
+        wsl = torch.empty(T.tree_attn_workspace(ql, kl, vl, 0, True), dtype=torch.uint8, device=dev)
+        n_it = max(3, min(args.steps, 10))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for it in range(2 + n_it):
+            if it == 2:
+                e0.record()
+            T.tree_attn_fwd(ql, kl, vl, *lk, o=ol, lse=lsel, workspace=wsl)
+            T.tree_attn_bwd(ql, kl, vl, *lk, ol, dol, lsel, dq=dql, dk=dkl, dv=dvl, workspace=wsl)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_lin = e0.elapsed_time(e1) / n_it
+        pairs_lin = linearize.visible_pairs(lmeta)
+        lin = {"ms_fwd_bwd": round(ms_lin, 4), "n_lin": int(len(idx)), "pairs_lin": pairs_lin,
+               "speedup": round(ms_lin / (ms_fwd + ms_bwd), 3),
+               "r_tok": round(len(idx) / N, 3), "r_pair": round(pairs_lin / pairs, 3)}
+        lin["speedup_over_r_tok"] = round(lin["speedup"] / lin["r_tok"], 3)
+        lin["speedup_over_r_pair"] = round(lin["speedup"] / lin["r_pair"], 3)
+        del ql, kl, vl, dol, ol, dql, dkl, dvl
+
+    # ---------------- CPU oracle on a bounded sample (context only) ----------------
+    cpu = None
+    if not args.no_cpu_baseline and n_prefix == 0:
+        from oracle import attention as OA, meta as OM
+        om = OM.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+        G = dims.hq // dims.hkv
+        if cfg in (1, 2):
+            t0c = time.perf_counter()
+            OA.branches(om, q.float().cpu(), k.float().cpu(), v.float().cpu(), do.float().cpu(), kv_heads=[0])
+            dtc = time.perf_counter() - t0c
+            cpu_flop = 14.0 * G * dims.d * pairs
+            sample = "per-branch oracle, fwd+bwd, all branches, kv head group 0 of %d (%d query heads)" % (dims.hkv, G)
+        else:
+            # a slice of rows of the deepest leaf: same arithmetic, bounded time
+            rows = list(range(N - 96, N))
+            t0c = time.perf_counter()
+            OA.rows(om, q.float().cpu(), k.float().cpu(), v.float().cpu(), do.float().cpu(), 0, rows)
+            dtc = time.perf_counter() - t0c
+            depth = om["tok_pos"][rows].astype(np.int64) + 1
+            cpu_flop = 14.0 * G * dims.d * float(depth.sum())
+            sample = "per-row oracle, fwd+bwd, last 96 tokens, kv head group 0 (%d query heads)" % G
+        cpu = {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(),
+               "kind": "oracle", "sample": sample, "seconds": round(dtc, 2)}
+
+    out = {
+        "metric": "tree-attn fwd+bwd useful TFLOP/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dims.dtype, "data": "synthetic",
+        "config": {"workload": workload, "n_tokens": N, "n_prefix": n_prefix, "hq": dims.hq, "hkv": dims.hkv,
+                   "d": dims.d, "visible_pairs": pairs, "useful_tflop_per_step": round(useful_flop / 1e12, 4)},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "ms_attn_fwd": round(ms_fwd, 4), "ms_attn_bwd": round(ms_bwd, 4), "ms_loss": round(ms_loss, 4),
+        "ms_host_meta": round(float(np.mean(host_ms)), 4),
+        "kernel_avg_ms": {n: round(t, 4) for n, t in kernel_ms.items()},
+        "loss_hbm_gbps": None if loss_gbps is None else round(loss_gbps, 1),
+        "loss_frac_of_hbm_peak": None if loss_gbps is None else round(loss_gbps / PEAK_HBM_GBPS, 4),
+        "linearized": lin,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

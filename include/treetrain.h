@@ -212,6 +212,29 @@ tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype,
                                    const int32_t* target, const float* weight,
                                    float* logp, float* lse, float* loss_acc, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
+ * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
+ * the recorded events have completed and returns the totals since the last enable.
+ * ------------------------------------------------------------------------------------------ */
+#define TT_KERNEL_ATTN_FWD    0   /* bf16 MFMA forward                                   */
+#define TT_KERNEL_ATTN_DELTA  1   /* rowsum(dO o O)                                      */
+#define TT_KERNEL_ATTN_DKDV   2   /* bf16 MFMA dK/dV                                     */
+#define TT_KERNEL_ATTN_DQ     3   /* bf16 MFMA dQ                                        */
+#define TT_KERNEL_LOSS_ROWS   4   /* log-softmax + gather, one pass over the logits      */
+#define TT_KERNEL_LOSS_SUM    5   /* weighted sum over rows                              */
+#define TT_KERNEL_REF_FWD     6   /* fp32-arithmetic kernels                             */
+#define TT_KERNEL_REF_BWD     7
+#define TT_KERNEL_ATTN_PLAN   8   /* work decomposition of the dK/dV pass                */
+#define TT_KERNEL_ATTN_REDUCE 9   /* sum of dK/dV partials of key tiles that were cut    */
+#define TT_N_KERNELS          10
+typedef struct {
+  double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
+  int64_t launches[TT_N_KERNELS];
+} tt_kernel_times;
+tt_status tt_kernel_timing_enable(int32_t on);     /* also resets the totals */
+tt_status tt_kernel_timing_read(tt_kernel_times* out);
+
 #ifdef __cplusplus
 }
 #endif

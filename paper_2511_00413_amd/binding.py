@@ -70,8 +70,32 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_weighted_logprob.restype = ctypes.c_int32
         lib.tt_tree_weighted_logprob.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp,
                                                  ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+        lib.tt_kernel_timing_enable.restype = ctypes.c_int32
+        lib.tt_kernel_timing_enable.argtypes = [ctypes.c_int32]
+        lib.tt_kernel_timing_read.restype = ctypes.c_int32
+        lib.tt_kernel_timing_read.argtypes = [ctypes.POINTER(_KernelTimes)]
         _LIB = lib
     return _LIB
+
+
+KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
+                "attn_plan", "attn_reduce")
+
+
+class _KernelTimes(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * 10), ("launches", ctypes.c_int64 * 10)]
+
+
+def kernel_timing_enable(on: bool) -> None:
+    """Bracket every kernel launch with HIP events on its stream (resets the totals)."""
+    _check(_lib().tt_kernel_timing_enable(1 if on else 0))
+
+
+def kernel_timing_read() -> dict:
+    """Blocks until the recorded events completed; {kernel: (total_ms, launches)} since enable."""
+    out = _KernelTimes()
+    _check(_lib().tt_kernel_timing_read(ctypes.byref(out)))
+    return {n: (float(out.ms[i]), int(out.launches[i])) for i, n in enumerate(KERNEL_NAMES)}
 
 
 def last_error() -> str:

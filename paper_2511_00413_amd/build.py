@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtreetrain.so")
 
-SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_attn_ref.hip", "tt_loss.hip",
+SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_timing.hip", "tt_attn_ref.hip", "tt_loss.hip",
            "tt_attn_fwd.hip", "tt_attn_bwd.hip"]
 
 HIPCC_FLAGS = [
@@ -18,6 +18,8 @@ HIPCC_FLAGS = [
     "-Wno-unused-parameter",
     # packed-fp32 code generation is switched off for every HIP translation unit
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep MFMA results in architectural VGPRs: the softmax / dS arithmetic consumes them directly
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

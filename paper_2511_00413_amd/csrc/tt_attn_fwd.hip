@@ -117,7 +117,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   const float c_scale = a.scale * LOG2E_F;
 
   KTileIter it;
-  it.init(a.kt_max, u_end, gi_first);
+  it.init(a.kt_max, a.kt_min, u_end, gi_first);
 
   auto tile_src = [&](int u) {
     TileSrc s;
@@ -141,8 +141,12 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   // unified index of the first key of tile u
   auto tile_j0 = [&](int u) { return u < npt ? u * BN : P + (u - npt) * BN; };
 
+#pragma unroll
+  for (int s = 0; s < 8; s++) pin(qf[s]);
+
   Staging st;
   int u_cur = it.next();
+  int kmin_cur = it.kmin;
   if (u_cur >= 0) {
     load_tile(tile_src(u_cur), st);
     store_tile(sm, 0, st);
@@ -157,24 +161,23 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
 
   while (u_cur >= 0) {
     const int u_next = it.next();
+    const int kmin_next = it.kmin;
     if (u_next >= 0) load_tile(tile_src(u_next), st);
 
     const int j0 = tile_j0(u_cur);
     const int rows = u_cur < npt ? min(BN, P - u_cur * BN) : min(BN, N - (u_cur - npt) * BN);
     // everything visible: all keys exist, all are at or before the first query, and every bound
     // lies beyond the last query
-    const bool full = rows == BN && j0 + BN - 1 <= gi_first && a.kt_min[u_cur] > gi_last;
+    const bool full = rows == BN && j0 + BN - 1 <= gi_first && kmin_cur > gi_last;
 
     // ---- S^T = K Q^T ----
     f32x16 s_acc[2];
 #pragma unroll
     for (int kb = 0; kb < 2; kb++) {
 #pragma unroll
-      for (int r = 0; r < 16; r++) s_acc[kb][r] = 0.f;
-#pragma unroll
       for (int s = 0; s < 8; s++) {
         const bf16x8 kf = *(const bf16x8*)(&sm.k[buf][k_rd + kb * 32 * KP + 16 * s]);
-        s_acc[kb] = mfma32(kf, qf[s], s_acc[kb]);
+        s_acc[kb] = mfma32(kf, qf[s], s == 0 ? zero16() : s_acc[kb]);
       }
     }
 
@@ -205,22 +208,25 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     tmax = half_swap_max(tmax) * c_scale;               // c_scale > 0
     const float m_new = fmaxf(m_run, tmax);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: keep everything at 0
-    const float alpha = exp2f(m_run - m_use);
+    const float alpha = fast_exp2(m_run - m_use);
     m_run = m_new;
     float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int r = 0; r < 16; r++) {
-        const float p = exp2f(fmaf(s_acc[kb][r], c_scale, -m_use));
+        const float p = fast_exp2(fmaf(s_acc[kb][r], c_scale, -m_use));
         s_acc[kb][r] = p;
         psum += p;
       }
     l_run = l_run * alpha + psum;
+    // the running max rarely moves after the first tiles: rescale only when some lane needs it
+    if (__ballot(alpha != 1.f) != 0) {
 #pragma unroll
-    for (int db = 0; db < 4; db++)
+      for (int db = 0; db < 4; db++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+        for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+    }
 
     // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -240,6 +246,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     __syncthreads();
     buf ^= 1;
     u_cur = u_next;
+    kmin_cur = kmin_next;
   }
 
   // ---- epilogue ----
@@ -269,6 +276,7 @@ hipError_t mfma_attn_fwd(const AttnArgs& a, hipStream_t st) {
   if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_fwd_kernel,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem)))
     return e;
+  KernelTimer timer(TT_KERNEL_ATTN_FWD, st);
   tree_attn_fwd_kernel<<<(unsigned)blocks, NTHREADS, sizeof(Smem), st>>>(a, n_qtiles);
   return hipGetLastError();
 }

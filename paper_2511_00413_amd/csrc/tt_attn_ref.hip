@@ -242,6 +242,7 @@ template <typename T>
 hipError_t launch_fwd(const RefArgs& a, hipStream_t st) {
   if (a.n_q == 0) return hipSuccess;
   dim3 grid((a.n_q + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, a.hq);
+  KernelTimer timer(TT_KERNEL_REF_FWD, st);
   ref_fwd_kernel<T><<<grid, WAVE * ROWS_PER_BLOCK, sizeof(float) * a.d * ROWS_PER_BLOCK, st>>>(a);
   return hipGetLastError();
 }
@@ -250,6 +251,7 @@ template <typename T>
 hipError_t launch_bwd(const RefArgs& a, hipStream_t st) {
   if (a.n_q == 0) return hipSuccess;
   dim3 grid((a.n_q + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, a.hq);
+  KernelTimer timer(TT_KERNEL_REF_BWD, st);
   ref_delta_kernel<T><<<grid, WAVE * ROWS_PER_BLOCK, 0, st>>>(a);
   if (hipError_t e = hipGetLastError()) return e;
   ref_dq_kernel<T><<<grid, WAVE * ROWS_PER_BLOCK, sizeof(float) * a.d * ROWS_PER_BLOCK * 2, st>>>(a);

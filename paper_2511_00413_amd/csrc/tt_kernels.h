@@ -3,7 +3,24 @@
 #include <hip/hip_runtime.h>
 #include <cstdint>
 
+#include "treetrain.h"
+
 namespace tt {
+
+// Brackets one kernel launch with HIP events on its stream when kernel timing is enabled
+// (tt_kernel_timing_enable); does nothing otherwise.
+class KernelTimer {
+ public:
+  KernelTimer(int id, hipStream_t st);
+  ~KernelTimer();
+  KernelTimer(const KernelTimer&) = delete;
+  KernelTimer& operator=(const KernelTimer&) = delete;
+ private:
+  int id_;
+  hipStream_t st_;
+  bool active_;
+  hipEvent_t start_, stop_;
+};
 
 // Arguments of one attention call, after validation; strides are in elements.
 struct RefArgs {

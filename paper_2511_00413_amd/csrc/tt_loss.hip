@@ -161,14 +161,18 @@ hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* lo
                             float* loss_acc, hipStream_t st) {
   if (n_rows == 0) return hipSuccess;
   // grid.x is limited to 2^31-1 workgroups; rows beyond that are rejected by the API layer
+  {
+  KernelTimer timer(TT_KERNEL_LOSS_ROWS, st);
   if (bf16)
     row_logprob_kernel<__hip_bfloat16><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
         vocab, (const __hip_bfloat16*)logits, row_stride, target, logp, lse);
   else
     row_logprob_kernel<float><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
         vocab, (const float*)logits, row_stride, target, logp, lse);
+  }
   if (hipError_t e = hipGetLastError()) return e;
   if (loss_acc) {
+    KernelTimer timer(TT_KERNEL_LOSS_SUM, st);
     weighted_sum_kernel<<<1, 1024, 0, st>>>(n_rows, logp, weight, target, loss_acc);
     return hipGetLastError();
   }

@@ -28,6 +28,22 @@ constexpr float LN2_F = 0.6931471805599453f;
 
 #define TT_LDS(T) __attribute__((address_space(3))) T
 
+// 2^x as the bare hardware instruction (no denormal-range fix-up): the arguments here are <= 0 up to
+// rounding and results below 2^-126 may flush to zero, which is what a softmax weight wants.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Makes the compiler treat a register-resident fragment as consumed here, so that the wait for the
+// global load that produced it is placed at this point and not inside the main loop (where a
+// vmcnt wait would also stall on the prefetch of the next tile).
+__device__ __forceinline__ void pin(const bf16x8& f) { asm volatile("" ::"v"(f)); }
+
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int r = 0; r < 16; r++) z[r] = 0.f;
+  return z;
+}
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -70,24 +86,30 @@ __device__ __forceinline__ bf16x4 cvt4(float a0, float a1, float a2, float a3) {
 // diagonal whose largest visibility bound exceeds gi_first.  64 tiles are tested per step with one
 // wavefront-wide load + ballot; every wavefront of the workgroup walks the same sequence.
 struct KTileIter {
-  const int32_t* kt_max;
+  const int32_t *kt_max, *kt_min;
   int u_end;        // one past the last candidate tile
   int gi_first;
   int base;         // next window start
   uint64_t mask;    // unvisited candidates of the current window [base-64, base)
-  __device__ __forceinline__ void init(const int32_t* kt_max_, int u_end_, int gi_first_) {
-    kt_max = kt_max_; u_end = u_end_; gi_first = gi_first_; base = 0; mask = 0;
+  int kmin_lane;    // kt_min of tile base-64+lane (the window's values, one per lane)
+  int kmin;         // kt_min of the tile returned by the last next()
+  __device__ __forceinline__ void init(const int32_t* kt_max_, const int32_t* kt_min_, int u_end_, int gi_first_) {
+    kt_max = kt_max_; kt_min = kt_min_; u_end = u_end_; gi_first = gi_first_; base = 0; mask = 0;
+    kmin_lane = 0; kmin = 0;
   }
   __device__ __forceinline__ int next() {
     while (mask == 0) {
       if (base >= u_end) return -1;
       const int u = base + (int)(threadIdx.x & 63);
-      const bool cand = u < u_end && kt_max[u] > gi_first;
+      const bool in = u < u_end;
+      const bool cand = in && kt_max[u] > gi_first;
+      kmin_lane = in ? kt_min[u] : 0;
       mask = __ballot(cand);
       base += 64;
     }
     const int b = __builtin_ctzll(mask);
     mask &= mask - 1;
+    kmin = __builtin_amdgcn_readlane(kmin_lane, b);
     return base - 64 + b;
   }
 };
