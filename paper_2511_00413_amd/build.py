@@ -11,15 +11,19 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtreetrain.so")
 
 SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_timing.hip", "tt_attn_ref.hip", "tt_loss.hip",
-           "tt_attn_fwd.hip", "tt_attn_bwd.hip"]
+           "tt_attn_fwd.hip", "tt_attn_bwd.hip", "tt_attn_dkdv.hip"]
+
+# Kernels that run two waves per SIMD keep MFMA results in architectural VGPRs (the softmax / dS
+# arithmetic consumes them directly); the dK/dV kernel needs the accumulation VGPRs for its 128
+# accumulator registers per lane and is compiled with the default register form.
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+PER_FILE_FLAGS = {"tt_attn_fwd.hip": VGPR_FORM, "tt_attn_bwd.hip": VGPR_FORM}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
     "-Wno-unused-parameter",
     # packed-fp32 code generation is switched off for every HIP translation unit
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # keep MFMA results in architectural VGPRs: the softmax / dS arithmetic consumes them directly
-    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 
@@ -45,7 +49,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
         objs.append(obj)
         lang = ["-x", "hip"] if s.endswith(".hip") else []
-        cmd = [hipcc()] + HIPCC_FLAGS + list(extra_flags) + lang + ["-c", os.path.join(CSRC, s), "-o", obj]
+        cmd = [hipcc()] + HIPCC_FLAGS + PER_FILE_FLAGS.get(s, []) + list(extra_flags) + os.environ.get("TT_EXTRA_FLAGS", "").split() + lang + ["-c", os.path.join(CSRC, s), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -60,7 +64,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(f"--- {s}\n" + "\n".join(lines))
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", os.environ.get("TT_LIB_OUT", LIB)] + objs
     subprocess.run(cmd, check=True)
     return LIB
 

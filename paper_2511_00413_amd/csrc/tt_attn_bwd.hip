@@ -6,7 +6,7 @@
 // Eq. 5), and over the query heads of the kv group.  Gradients of cached prefix keys are added
 // in fp32 to caller-owned accumulators (Appendix "Float32 Gradient Accumulation").
 //
-// Three kernels, no atomics (results are bit-reproducible):
+// Kernels, no atomics (results are bit-reproducible); the dK/dV pass lives in tt_attn_dkdv.hip:
 //   delta     D_i                                                      (memory bound)
 //   dkdv      column-parallel: one workgroup = 128 keys x one kv head, 4 wavefronts x 32 keys;
 //             loops over the query heads of the group and over the query tiles that can see the
@@ -26,7 +26,6 @@ namespace {
 
 constexpr int D = 128;
 constexpr int NTHREADS = 256;
-constexpr int RP = D + 8;          // LDS row pitch (elements) of every staged tile: 272 B
 
 // ------------------------------------------------------------------------------------------------
 // delta[h][i] = sum_d dO[i][h][d] * O[i][h][d]; one wavefront per (token, head) row of 128
@@ -52,483 +51,98 @@ delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, float
 }
 
 // ------------------------------------------------------------------------------------------------
-// dK / dV
-// ------------------------------------------------------------------------------------------------
-constexpr int KV_BN = 128;         // keys per workgroup (two TT_KTILE summaries)
-constexpr int KV_BM = 64;          // queries per staged tile
-
-struct KvSmem {
-  __bf16 q[2][KV_BM * RP];
-  __bf16 g[2][KV_BM * RP];         // dO
-  float lse2[2][KV_BM];            // LSE in base-2 units
-  float delta[2][KV_BM];
-};
-
-struct KvStaging {
-  i32x4 q[4], g[4];
-  float lse2, delta;
-};
-
-__device__ __forceinline__ void kv_load(const AttnArgs& a, int h, int q0, KvStaging& st) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    const int i = q0 + row;
-    i32x4 zq = {0, 0, 0, 0}, zg = {0, 0, 0, 0};
-    if (i < a.n_q) {
-      zq = *(const i32x4*)((const __bf16*)a.q + (int64_t)i * a.q_stride + (int64_t)h * D + col);
-      zg = *(const i32x4*)((const __bf16*)a.d_o + ((int64_t)i * a.hq + h) * D + col);
-    }
-    st.q[u] = zq;
-    st.g[u] = zg;
-  }
-  st.lse2 = 0.f; st.delta = 0.f;
-  if (t < KV_BM && q0 + t < a.n_q) {
-    st.lse2 = a.lse[(int64_t)h * a.n_q + q0 + t] * LOG2E_F;
-    st.delta = a.delta[(int64_t)h * a.n_q + q0 + t];
-  }
-}
-
-__device__ __forceinline__ void kv_store(KvSmem& sm, int buf, const KvStaging& st) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    *(i32x4*)(&sm.q[buf][row * RP + col]) = st.q[u];
-    *(i32x4*)(&sm.g[buf][row * RP + col]) = st.g[u];
-  }
-  if (t < KV_BM) { sm.lse2[buf][t] = st.lse2; sm.delta[buf][t] = st.delta; }
-}
-
-// ---- work decomposition -------------------------------------------------------------------------
-// A key tile's work is its list of (query head, query tile) steps.  Tiles near the root of the tree
-// are seen by almost every query while leaf tiles are seen by few, so a tile's steps are cut into
-// chunks of at most `chunk` steps; a planner kernel sizes the chunks so that the launch has about
-// KV_TARGET_WORK work items, workgroups pull items from a counter, and tiles that were cut have
-// their fp32 partial results summed in chunk order by a reduce kernel (bit-reproducible).
-constexpr int KV_TARGET_WORK = 1024;     // work items (tile chunk x kv head) aimed for
-constexpr int KV_MIN_CHUNK = 32;         // steps
-constexpr int PLAN_THREADS = 1024;
-
-struct KvPlanHeader {
-  int n_work;        // work items = n_items * hkv
-  int counter;       // next work item to hand out
-  int chunk;         // steps per chunk
-  int n_split_items; // items [0, n_split_items) write partial slots (slot index = item index)
-};
-
-struct KvPlan {                // device pointers into the workspace
-  KvPlanHeader* hdr;
-  int *tile_nq, *tile_qtlo, *tile_nchunks, *tile_item0;   // [n_tiles]
-  int *item_tile, *item_chunk;                            // [max_items]
-  float* slots;                                           // [max_slots][hkv][2][KV_BN][D]
-  int n_tiles, n_ptiles, max_items, max_slots;
-};
-
-__host__ __device__ inline int kv_target_items(int hkv) { return (KV_TARGET_WORK + hkv - 1) / hkv; }
-
-__host__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-// Carves the plan out of `base`; with base == nullptr only the size is computed.
-__host__ inline size_t kv_plan_layout(void* base, int n_q, int n_prefix, int hkv, KvPlan* out) {
-  const int n_ptiles = (n_prefix + KV_BN - 1) / KV_BN, n_otiles = (n_q + KV_BN - 1) / KV_BN;
-  const int n_tiles = n_ptiles + n_otiles;
-  const int max_items = n_tiles + kv_target_items(hkv);
-  const int max_slots = 2 * kv_target_items(hkv);
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return base ? (char*)base + o : (char*)nullptr; };
-  char* hdr = take(sizeof(KvPlanHeader));
-  char* t0 = take(sizeof(int) * n_tiles);
-  char* t1 = take(sizeof(int) * n_tiles);
-  char* t2 = take(sizeof(int) * n_tiles);
-  char* t3 = take(sizeof(int) * n_tiles);
-  char* i0 = take(sizeof(int) * max_items);
-  char* i1 = take(sizeof(int) * max_items);
-  char* sl = take(sizeof(float) * (size_t)max_slots * hkv * 2 * KV_BN * D);
-  if (out) {
-    out->hdr = (KvPlanHeader*)hdr;
-    out->tile_nq = (int*)t0; out->tile_qtlo = (int*)t1; out->tile_nchunks = (int*)t2; out->tile_item0 = (int*)t3;
-    out->item_tile = (int*)i0; out->item_chunk = (int*)i1; out->slots = (float*)sl;
-    out->n_tiles = n_tiles; out->n_ptiles = n_ptiles; out->max_items = max_items; out->max_slots = max_slots;
-  }
-  return off;
-}
-
-// exclusive prefix sum of one int per thread over the workgroup; returns the total through *total
-__device__ inline int block_exclusive_scan(int v, int* scratch /*[PLAN_THREADS]*/, int* total) {
-  const int t = threadIdx.x;
-  scratch[t] = v;
-  __syncthreads();
-  for (int off = 1; off < PLAN_THREADS; off <<= 1) {
-    const int add = t >= off ? scratch[t - off] : 0;
-    __syncthreads();
-    scratch[t] += add;
-    __syncthreads();
-  }
-  const int incl = scratch[t];
-  *total = scratch[PLAN_THREADS - 1];
-  __syncthreads();
-  return incl - v;
-}
-
-__global__ void __launch_bounds__(PLAN_THREADS)
-kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_prefix, int G, int hkv) {
-  __shared__ int scratch[PLAN_THREADS];
-  const int t = threadIdx.x;
-  const int per = (pl.n_tiles + PLAN_THREADS - 1) / PLAN_THREADS;    // consecutive tiles per thread
-  const int lo = min(t * per, pl.n_tiles), hi = min(lo + per, pl.n_tiles);
-  const int np64 = (n_prefix + 63) / 64, no64 = (n_q + 63) / 64;
-  // pass 1: visible query tiles of every key tile
-  int my_steps = 0;
-  for (int tl = lo; tl < hi; tl++) {
-    int kmax, i_lo;
-    if (tl < pl.n_ptiles) {
-      const int e0 = 2 * tl, e1 = e0 + 1;
-      kmax = max(kt_max[e0], e1 < np64 ? kt_max[e1] : 0);
-      i_lo = 0;
-    } else {
-      const int to = tl - pl.n_ptiles;
-      const int e0 = np64 + 2 * to, e1 = e0 + 1;
-      kmax = max(kt_max[e0], e1 < np64 + no64 ? kt_max[e1] : 0);
-      i_lo = to * KV_BN;
-    }
-    const int i_hi = (int)min((int64_t)n_q, (int64_t)kmax - n_prefix);
-    const int qt_lo = i_lo / KV_BM;
-    const int nq = i_hi > i_lo ? (i_hi + KV_BM - 1) / KV_BM - qt_lo : 0;
-    pl.tile_nq[tl] = nq;
-    pl.tile_qtlo[tl] = qt_lo;
-    my_steps += nq * G;
-  }
-  int total_steps;
-  block_exclusive_scan(my_steps, scratch, &total_steps);
-  const int64_t all = (int64_t)total_steps * hkv;
-  const int chunk = (int)max((int64_t)KV_MIN_CHUNK, (all + KV_TARGET_WORK - 1) / KV_TARGET_WORK);
-  // pass 2: chunks per tile; cut tiles are numbered first (their item index is also their slot)
-  int my_split = 0, my_whole = 0;
-  for (int tl = lo; tl < hi; tl++) {
-    const int steps = pl.tile_nq[tl] * G;
-    const int nc = (steps + chunk - 1) / chunk;
-    pl.tile_nchunks[tl] = nc;
-    if (nc > 1) my_split += nc; else my_whole += nc;
-  }
-  int n_split, n_whole;
-  int split0 = block_exclusive_scan(my_split, scratch, &n_split);
-  int whole0 = block_exclusive_scan(my_whole, scratch, &n_whole) + n_split;
-  for (int tl = lo; tl < hi; tl++) {
-    const int nc = pl.tile_nchunks[tl];
-    int& cursor = nc > 1 ? split0 : whole0;
-    pl.tile_item0[tl] = cursor;
-    for (int c = 0; c < nc; c++) { pl.item_tile[cursor + c] = tl; pl.item_chunk[cursor + c] = c; }
-    cursor += nc;
-  }
-  if (t == 0) {
-    pl.hdr->n_work = (n_split + n_whole) * hkv;
-    pl.hdr->counter = 0;
-    pl.hdr->chunk = chunk;
-    pl.hdr->n_split_items = n_split;
-  }
-}
-
-__global__ void __launch_bounds__(NTHREADS, 1)
-tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  KvSmem& sm = *reinterpret_cast<KvSmem*>(smem_raw);
-  __shared__ int s_work;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c32 = lane & 31, hf = lane >> 5;
-  const int G = a.hq / a.hkv;
-  const int P = a.n_prefix, N = a.n_q;
-  const float c_scale = a.scale * LOG2E_F;
-  const int a_rd = c32 * RP + 8 * hf;                                   // row-major A operand reads
-  const int i16 = lane & 15, gidx = (lane >> 4) & 1;
-  const int t_rd = (4 * hf + (i16 >> 2)) * RP + 16 * gidx + 4 * (i16 & 3);  // transposed reads
-  const int n_work = pl.hdr->n_work;
-  const int chunk = pl.hdr->chunk;
-
-  for (;;) {
-    if (threadIdx.x == 0) s_work = atomicAdd(&pl.hdr->counter, 1);
-    __syncthreads();
-    const int work = s_work;
-    __syncthreads();                         // everyone has read s_work before it is rewritten
-    if (work >= n_work) break;               // the counter only grows: every wave gets here
-    const int kvh = work % a.hkv;            // neighbouring items differ in kv head (XCD locality)
-    const int item = work / a.hkv;
-    const int tile = pl.item_tile[item];
-    const int nq = pl.tile_nq[tile], qt_lo = pl.tile_qtlo[tile];
-    const int s_lo = pl.item_chunk[item] * chunk;
-    const int s_hi = min(s_lo + chunk, nq * G);
-    const bool partial = pl.tile_nchunks[tile] > 1;
-
-    const bool is_prefix = tile < pl.n_ptiles;
-    const int k0 = is_prefix ? tile * KV_BN : (tile - pl.n_ptiles) * KV_BN;   // region-local first key
-    const int region = is_prefix ? P : N;
-    const int j0 = is_prefix ? k0 : P + k0;          // unified index of the first key
-    // this lane's key
-    const int kl = k0 + 32 * w + c32;
-    const bool key_ok = kl < region;
-    const int j = j0 + 32 * w + c32;
-    const int my_kend = key_ok ? a.kend[j] : 0;
-    int kmax_w = my_kend, kmin_w = key_ok ? my_kend : INT32_MAX;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      kmax_w = max(kmax_w, __shfl_xor(kmax_w, off));
-      kmin_w = min(kmin_w, __shfl_xor(kmin_w, off));
-    }
-
-    // ---- K / V fragments of this wave's 32 keys (B operands: column = key, k = d) ----
-    bf16x8 kf[8], vf[8];
-    {
-      const int krow = min(kl, region - 1);
-      const __bf16* kp = is_prefix ? (const __bf16*)a.k_prefix + ((int64_t)krow * a.hkv + kvh) * D
-                                   : (const __bf16*)a.k_own + (int64_t)krow * a.k_stride + (int64_t)kvh * D;
-      const __bf16* vp = is_prefix ? (const __bf16*)a.v_prefix + ((int64_t)krow * a.hkv + kvh) * D
-                                   : (const __bf16*)a.v_own + (int64_t)krow * a.v_stride + (int64_t)kvh * D;
-#pragma unroll
-      for (int s = 0; s < 8; s++) {
-        kf[s] = *(const bf16x8*)(kp + 16 * s + 8 * hf);
-        vf[s] = *(const bf16x8*)(vp + 16 * s + 8 * hf);
-      }
-    }
-    f32x16 dk_acc[4], dv_acc[4];
-#pragma unroll
-    for (int db = 0; db < 4; db++) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
-
-    auto step_head = [&](int s) { return kvh * G + s / nq; };      // steps are head-major
-    auto step_q0 = [&](int s) { return (qt_lo + s % nq) * KV_BM; };
-
-#pragma unroll
-    for (int s = 0; s < 8; s++) { pin(kf[s]); pin(vf[s]); }
-
-    KvStaging st;
-    kv_load(a, step_head(s_lo), step_q0(s_lo), st);
-    kv_store(sm, 0, st);
-    __syncthreads();
-
-    // first / last key of this wave's block, unified
-    const int jw_first = j0 + 32 * w;
-    const int jw_last = jw_first + 31;
-
-    for (int s = s_lo; s < s_hi; s++) {
-      const int buf = (s - s_lo) & 1;
-      if (s + 1 < s_hi) kv_load(a, step_head(s + 1), step_q0(s + 1), st);
-      const int q0 = step_q0(s);
-
-#pragma unroll
-      for (int qb = 0; qb < 2; qb++) {
-        const int gq_first = P + q0 + 32 * qb;                 // unified index of the block's first query
-        const int gq_last = min(gq_first + 31, P + N - 1);
-        // block-level skip: every key is after the last query, or no key's range reaches the block
-        if (jw_first > gq_last || kmax_w <= gq_first) continue;
-        const bool full = jw_last <= gq_first && kmin_w > gq_last && q0 + 32 * qb + 31 < N;
-
-        f32x16 s_acc, p_acc;
-        bf16x8 qa[8], ga[8];
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) qa[ss] = *(const bf16x8*)(&sm.q[buf][a_rd + qb * 32 * RP + 16 * ss]);
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) ga[ss] = *(const bf16x8*)(&sm.g[buf][a_rd + qb * 32 * RP + 16 * ss]);
-        f32x4 l2[4], dl[4];
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-          l2[r4] = *(const f32x4*)(&sm.lse2[buf][qb * 32 + r4 * 8 + 4 * hf]);
-          dl[r4] = *(const f32x4*)(&sm.delta[buf][qb * 32 + r4 * 8 + 4 * hf]);
-        }
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) s_acc = mfma32(qa[ss], kf[ss], ss == 0 ? zero16() : s_acc);
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) p_acc = mfma32(ga[ss], vf[ss], ss == 0 ? zero16() : p_acc);
-        // P and dS (rows = queries: (r/4)*8 + 4*hf + r%4 inside the block)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            s_acc[r4 * 4 + e] = fast_exp2(fmaf(s_acc[r4 * 4 + e], c_scale, -l2[r4][e]));
-        if (!full) {
-          const int q_lim = min(my_kend, P + N);           // queries at or beyond this see nothing
-#pragma unroll
-          for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              const int gq = gq_first + r4 * 8 + 4 * hf + e;
-              s_acc[r4 * 4 + e] = (j <= gq && gq < q_lim) ? s_acc[r4 * 4 + e] : 0.f;
-            }
-        }
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            p_acc[r4 * 4 + e] = s_acc[r4 * 4 + e] * (p_acc[r4 * 4 + e] - dl[r4][e]);
-        // dV^T += dO^T P ; dK^T += Q^T dS
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          const bf16x8 pf = cvt8(s_acc[8 * t + 0], s_acc[8 * t + 1], s_acc[8 * t + 2], s_acc[8 * t + 3],
-                                 s_acc[8 * t + 4], s_acc[8 * t + 5], s_acc[8 * t + 6], s_acc[8 * t + 7]);
-          const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
-                                 p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
-#pragma unroll
-          for (int db = 0; db < 4; db++) {
-            const int off = t_rd + (qb * 32 + 16 * t) * RP + 32 * db;
-            const bf16x8 gt = cat4(lds_read_tr(&sm.g[buf][off]), lds_read_tr(&sm.g[buf][off + 8 * RP]));
-            dv_acc[db] = mfma32(gt, pf, dv_acc[db]);
-            const bf16x8 qtf = cat4(lds_read_tr(&sm.q[buf][off]), lds_read_tr(&sm.q[buf][off + 8 * RP]));
-            dk_acc[db] = mfma32(qtf, df, dk_acc[db]);
-          }
-        }
-      }
-
-      if (s + 1 < s_hi) kv_store(sm, buf ^ 1, st);
-      __syncthreads();
-    }
-
-    // ---- epilogue: accumulators hold dK^T / dV^T: column = key, rows d = db*32 + (r/4)*8 + 4*hf + r%4 ----
-    if (partial) {
-      // raw fp32 partial sums of this chunk; the reduce kernel adds the chunks in order
-      float* base = pl.slots + (((int64_t)item * a.hkv + kvh) * 2) * KV_BN * D + (int64_t)(32 * w + c32) * D;
-#pragma unroll
-      for (int db = 0; db < 4; db++)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-          const int d0 = db * 32 + r4 * 8 + 4 * hf;
-          f32x4 ck, cv;
-#pragma unroll
-          for (int e = 0; e < 4; e++) { ck[e] = dk_acc[db][r4 * 4 + e]; cv[e] = dv_acc[db][r4 * 4 + e]; }
-          *(f32x4*)(base + d0) = ck;
-          *(f32x4*)(base + KV_BN * D + d0) = cv;
-        }
-    } else if (key_ok) {
-      if (is_prefix) {
-        if (my_kend > P) {       // a visible prefix key; others receive nothing
-          float* dkp = a.dk_prefix_acc + ((int64_t)kl * a.hkv + kvh) * D;
-          float* dvp = a.dv_prefix_acc + ((int64_t)kl * a.hkv + kvh) * D;
-#pragma unroll
-          for (int db = 0; db < 4; db++)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; r4++) {
-              const int d0 = db * 32 + r4 * 8 + 4 * hf;
-              f32x4 ck = *(f32x4*)(dkp + d0), cv = *(f32x4*)(dvp + d0);
-#pragma unroll
-              for (int e = 0; e < 4; e++) { ck[e] += a.scale * dk_acc[db][r4 * 4 + e]; cv[e] += dv_acc[db][r4 * 4 + e]; }
-              *(f32x4*)(dkp + d0) = ck;
-              *(f32x4*)(dvp + d0) = cv;
-            }
-        }
-      } else {
-        __bf16* dkp = (__bf16*)a.dk_own + ((int64_t)kl * a.hkv + kvh) * D;
-        __bf16* dvp = (__bf16*)a.dv_own + ((int64_t)kl * a.hkv + kvh) * D;
-#pragma unroll
-        for (int db = 0; db < 4; db++)
-#pragma unroll
-          for (int r4 = 0; r4 < 4; r4++) {
-            const int d0 = db * 32 + r4 * 8 + 4 * hf;
-            *(bf16x4*)(dkp + d0) = cvt4(a.scale * dk_acc[db][r4 * 4 + 0], a.scale * dk_acc[db][r4 * 4 + 1],
-                                        a.scale * dk_acc[db][r4 * 4 + 2], a.scale * dk_acc[db][r4 * 4 + 3]);
-            *(bf16x4*)(dvp + d0) = cvt4(dv_acc[db][r4 * 4 + 0], dv_acc[db][r4 * 4 + 1],
-                                        dv_acc[db][r4 * 4 + 2], dv_acc[db][r4 * 4 + 3]);
-          }
-      }
-    }
-  }
-}
-
-// Sums the partial slots of every key tile that was cut into chunks, in chunk order, and writes the
-// final gradients (own keys: bf16; prefix keys: added to the fp32 accumulators).
-__global__ void __launch_bounds__(NTHREADS)
-kv_reduce_kernel(AttnArgs a, KvPlan pl) {
-  const int tile = blockIdx.x, kvh = blockIdx.y;
-  const int nc = pl.tile_nchunks[tile];
-  if (nc <= 1) return;
-  const int item0 = pl.tile_item0[tile];
-  const bool is_prefix = tile < pl.n_ptiles;
-  const int k0 = is_prefix ? tile * KV_BN : (tile - pl.n_ptiles) * KV_BN;
-  const int region = is_prefix ? a.n_prefix : a.n_q;
-  for (int u = 0; u < KV_BN * D / 4 / NTHREADS; u++) {
-    const int e = (threadIdx.x + NTHREADS * u) * 4;
-    const int key = e / D, d0 = e % D;
-    if (k0 + key >= region) continue;
-    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < nc; c++) {
-      const float* base = pl.slots + (((int64_t)(item0 + c) * a.hkv + kvh) * 2) * KV_BN * D + e;
-      sk += *(const f32x4*)base;
-      sv += *(const f32x4*)(base + KV_BN * D);
-    }
-    if (is_prefix) {
-      if (a.kend[k0 + key] > a.n_prefix) {
-        float* dkp = a.dk_prefix_acc + ((int64_t)(k0 + key) * a.hkv + kvh) * D + d0;
-        float* dvp = a.dv_prefix_acc + ((int64_t)(k0 + key) * a.hkv + kvh) * D + d0;
-        f32x4 ck = *(f32x4*)dkp, cv = *(f32x4*)dvp;
-        ck += a.scale * sk;
-        cv += sv;
-        *(f32x4*)dkp = ck;
-        *(f32x4*)dvp = cv;
-      }
-    } else {
-      __bf16* dkp = (__bf16*)a.dk_own + ((int64_t)(k0 + key) * a.hkv + kvh) * D + d0;
-      __bf16* dvp = (__bf16*)a.dv_own + ((int64_t)(k0 + key) * a.hkv + kvh) * D + d0;
-      *(bf16x4*)dkp = cvt4(a.scale * sk[0], a.scale * sk[1], a.scale * sk[2], a.scale * sk[3]);
-      *(bf16x4*)dvp = cvt4(sv[0], sv[1], sv[2], sv[3]);
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // dQ
 // ------------------------------------------------------------------------------------------------
 constexpr int Q_BM = 128;          // queries per workgroup
 constexpr int Q_BN = 64;           // keys per tile (= TT_KTILE)
+constexpr int Q_TILE_ELEMS = Q_BN * TILE_ROW;
 
 struct QSmem {
-  __bf16 k[2][Q_BN * RP];
-  __bf16 v[2][Q_BN * RP];
+  __bf16 k[2][Q_TILE_ELEMS];       // swizzled tiles, filled by asynchronous global -> LDS copies
+  __bf16 v[2][Q_TILE_ELEMS];
   int32_t kend[2][Q_BN];
 };
 
-struct QStaging {
-  i32x4 k[4], v[4];
-  int32_t kend;
+struct QCtx {
+  const AttnArgs& a;
+  int kvh, P, N, npt;
 };
 
-struct QTileSrc {
-  const __bf16 *k, *v;
-  int64_t k_stride, v_stride;
+// Starts the copy of key tile u (K, V rows) into stage `buf`; returns this lane's visibility bound
+// (wave 0 only) for the caller to store once the tile's math is done.
+__device__ __forceinline__ int q_issue_tile(const QCtx& c, QSmem& sm, int buf, int u, int w, int lane) {
+  const AttnArgs& a = c.a;
+  const __bf16 *kp, *vp;
+  const int32_t* ke;
+  uint32_t ks, vs;
   int rows;
-  const int32_t* kend;
-};
-
-__device__ __forceinline__ void q_load(const QTileSrc& s, QStaging& st) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    i32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-    if (row < s.rows) {
-      zk = *(const i32x4*)(s.k + (int64_t)row * s.k_stride + col);
-      zv = *(const i32x4*)(s.v + (int64_t)row * s.v_stride + col);
-    }
-    st.k[u] = zk;
-    st.v[u] = zv;
+  if (u < c.npt) {
+    const int k0 = u * Q_BN;
+    kp = (const __bf16*)a.k_prefix + ((int64_t)k0 * a.hkv + c.kvh) * D;
+    vp = (const __bf16*)a.v_prefix + ((int64_t)k0 * a.hkv + c.kvh) * D;
+    ks = vs = (uint32_t)a.hkv * D * 2;
+    rows = min(Q_BN, c.P - k0);
+    ke = a.kend + k0;
+  } else {
+    const int k0 = (u - c.npt) * Q_BN;
+    kp = (const __bf16*)a.k_own + (int64_t)k0 * a.k_stride + (int64_t)c.kvh * D;
+    vp = (const __bf16*)a.v_own + (int64_t)k0 * a.v_stride + (int64_t)c.kvh * D;
+    ks = (uint32_t)a.k_stride * 2;
+    vs = (uint32_t)a.v_stride * 2;
+    rows = min(Q_BN, c.N - k0);
+    ke = a.kend + c.P + k0;
   }
-  st.kend = (t < Q_BN && t < s.rows) ? s.kend[t] : 0;
+  dma_tile64(kp, ks, rows, sm.k[buf], w, lane);
+  dma_tile64(vp, vs, rows, sm.v[buf], w, lane);
+  int kv = 0;
+  if (w == 0) kv = lane < rows ? ke[lane] : 0;     // keys past the end of the region: visible to nobody
+  return kv;
 }
 
-__device__ __forceinline__ void q_store(QSmem& sm, int buf, const QStaging& st) {
-  const int t = threadIdx.x;
+// One key tile of the dQ pass.  FULL: no per-element visibility test, one branch-free block.
+template <bool FULL>
+__device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
+                                        f32x16 (&dq_acc)[4], float c_scale, float lse2, float delta,
+                                        int j0, int gi, int a_rd, TrBase t_rd, int hf) {
 #pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    *(i32x4*)(&sm.k[buf][row * RP + col]) = st.k[u];
-    *(i32x4*)(&sm.v[buf][row * RP + col]) = st.v[u];
+  for (int kb = 0; kb < 2; kb++) {
+    f32x16 s_acc, p_acc;
+#pragma unroll
+    for (int s = 0; s < 8; s++) s_acc = mfma32(lds_row_frag(sm.k[buf], a_rd, kb, s), qf[s], s == 0 ? zero16() : s_acc);
+#pragma unroll
+    for (int s = 0; s < 8; s++) p_acc = mfma32(lds_row_frag(sm.v[buf], a_rd, kb, s), gf[s], s == 0 ? zero16() : p_acc);
+    // dS^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block)
+#pragma unroll
+    for (int r = 0; r < 16; r++) s_acc[r] = fast_exp2(fmaf(s_acc[r], c_scale, -lse2));
+    if (!FULL) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const int jl = kb * 32 + r4 * 8 + 4 * hf;
+        const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const int j = j0 + jl + e;
+          s_acc[r4 * 4 + e] = (j <= gi && gi < ke[e]) ? s_acc[r4 * 4 + e] : 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; r++) p_acc[r] = s_acc[r] * (p_acc[r] - delta);
+    // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
+                             p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+        dq_acc[db] = mfma32(lds_tr_frag(sm.k[buf], t_rd, kb * 32 + 16 * t, db), df, dq_acc[db]);
+    }
   }
-  if (t < Q_BN) sm.kend[buf][t] = st.kend;
 }
 
 __global__ void __launch_bounds__(NTHREADS, 2)
 tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
   QSmem& sm = *reinterpret_cast<QSmem*>(smem_raw);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c32 = lane & 31, hf = lane >> 5;
@@ -544,6 +158,7 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   const int gi_first = P + q0, gi_last = P + q_hi - 1;
   const int npt = (P + Q_BN - 1) / Q_BN;
   const int u_end = npt + (q_hi - 1) / Q_BN + 1;
+  const QCtx ctx{a, kvh, P, N, npt};
 
   const int q = q0 + 32 * w + c32;
   const int my_q = min(q, N - 1);
@@ -561,107 +176,45 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 
   f32x16 dq_acc[4];
 #pragma unroll
-  for (int db = 0; db < 4; db++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) dq_acc[db][r] = 0.f;
+  for (int db = 0; db < 4; db++) dq_acc[db] = zero16();
 
   KTileIter it;
-  it.init(a.kt_max, a.kt_min, u_end, gi_first);
-  auto tile_src = [&](int u) {
-    QTileSrc s;
-    if (u < npt) {
-      const int k0 = u * Q_BN;
-      s.k = (const __bf16*)a.k_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
-      s.v = (const __bf16*)a.v_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
-      s.k_stride = s.v_stride = (int64_t)a.hkv * D;
-      s.rows = min(Q_BN, P - k0);
-      s.kend = a.kend + k0;
-    } else {
-      const int k0 = (u - npt) * Q_BN;
-      s.k = (const __bf16*)a.k_own + (int64_t)k0 * a.k_stride + (int64_t)kvh * D;
-      s.v = (const __bf16*)a.v_own + (int64_t)k0 * a.v_stride + (int64_t)kvh * D;
-      s.k_stride = a.k_stride; s.v_stride = a.v_stride;
-      s.rows = min(Q_BN, N - k0);
-      s.kend = a.kend + P + k0;
-    }
-    return s;
-  };
+  it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * Q_BN : P + (u - npt) * Q_BN; };
 
 #pragma unroll
   for (int s = 0; s < 8; s++) { pin(qf[s]); pin(gf[s]); }
 
-  QStaging st;
-  int u_cur = it.next();
-  int kmin_cur = it.kmin;
+  bool full_cur = false;
+  int u_cur = it.next(full_cur);
   if (u_cur >= 0) {
-    q_load(tile_src(u_cur), st);
-    q_store(sm, 0, st);
+    const int kv = q_issue_tile(ctx, sm, 0, u_cur, w, lane);
+    if (w == 0) sm.kend[0][lane] = kv;
   }
+  dma_wait_all();
   __syncthreads();
   int buf = 0;
 
-  const int a_rd = c32 * RP + 8 * hf;
-  const int i16 = lane & 15, gidx = (lane >> 4) & 1;
-  const int t_rd = (4 * hf + (i16 >> 2)) * RP + 16 * gidx + 4 * (i16 & 3);
+  const int a_rd = row_frag_base(lane);
+  const TrBase t_rd = tr_frag_base(lane);
 
-  while (u_cur >= 0) {
-    const int u_next = it.next();
-    const int kmin_next = it.kmin;
-    if (u_next >= 0) q_load(tile_src(u_next), st);
-    const int j0 = tile_j0(u_cur);
-    const int rows = u_cur < npt ? min(Q_BN, P - u_cur * Q_BN) : min(Q_BN, N - (u_cur - npt) * Q_BN);
-    const bool full = rows == Q_BN && j0 + Q_BN - 1 <= gi_first && kmin_cur > gi_last;
-
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      f32x16 s_acc, p_acc;
-      bf16x8 ka[8], va[8];
-#pragma unroll
-      for (int s = 0; s < 8; s++) ka[s] = *(const bf16x8*)(&sm.k[buf][a_rd + kb * 32 * RP + 16 * s]);
-#pragma unroll
-      for (int s = 0; s < 8; s++) va[s] = *(const bf16x8*)(&sm.v[buf][a_rd + kb * 32 * RP + 16 * s]);
-#pragma unroll
-      for (int s = 0; s < 8; s++) s_acc = mfma32(ka[s], qf[s], s == 0 ? zero16() : s_acc);
-#pragma unroll
-      for (int s = 0; s < 8; s++) p_acc = mfma32(va[s], gf[s], s == 0 ? zero16() : p_acc);
-      // dS^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block)
-#pragma unroll
-      for (int r = 0; r < 16; r++) s_acc[r] = fast_exp2(fmaf(s_acc[r], c_scale, -lse2));
-      if (!full) {
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-          const int jl = kb * 32 + r4 * 8 + 4 * hf;
-          const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int j = j0 + jl + e;
-            s_acc[r4 * 4 + e] = (j <= gi && gi < ke[e]) ? s_acc[r4 * 4 + e] : 0.f;
-          }
-        }
-      }
-#pragma unroll
-      for (int r = 0; r < 16; r++) p_acc[r] = s_acc[r] * (p_acc[r] - delta);
-      // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
-#pragma unroll
-      for (int t = 0; t < 2; t++) {
-        const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
-                               p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
-#pragma unroll
-        for (int db = 0; db < 4; db++) {
-          const int off = t_rd + (kb * 32 + 16 * t) * RP + 32 * db;
-          const bf16x8 kt = cat4(lds_read_tr(&sm.k[buf][off]), lds_read_tr(&sm.k[buf][off + 8 * RP]));
-          dq_acc[db] = mfma32(kt, df, dq_acc[db]);
-        }
-      }
-    }
-
-    if (u_next >= 0) q_store(sm, buf ^ 1, st);
-    __syncthreads();
-    buf ^= 1;
-    u_cur = u_next;
-    kmin_cur = kmin_next;
+#define TT_DQ_STEP(FULLFLAG)                                                                            \
+  {                                                                                                     \
+    bool full_next = false;                                                                             \
+    const int u_next = it.next(full_next);                                                              \
+    int kv_next = 0;                                                                                    \
+    if (u_next >= 0) kv_next = q_issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                         \
+    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, c_scale, lse2, delta, tile_j0(u_cur), gi, a_rd, t_rd, hf); \
+    if (u_next >= 0 && w == 0) sm.kend[buf ^ 1][lane] = kv_next;                                         \
+    dma_wait_all();                                                                                     \
+    __syncthreads();                                                                                    \
+    buf ^= 1;                                                                                           \
+    u_cur = u_next;                                                                                     \
+    full_cur = full_next;                                                                               \
   }
+  while (u_cur >= 0 && full_cur) TT_DQ_STEP(true)
+  while (u_cur >= 0) TT_DQ_STEP(false)
+#undef TT_DQ_STEP
 
   if (q < N) {
     __bf16* dqp = (__bf16*)a.dq + ((int64_t)q * a.hq + h) * D;
@@ -680,7 +233,7 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 
 size_t mfma_attn_workspace(int n_q, int n_prefix, int hq, int hkv, int d, bool backward) {
   if (!backward) return 0;
-  return kv_plan_layout(nullptr, n_q, n_prefix, hkv, nullptr);
+  return mfma_attn_dkdv_workspace(n_q, n_prefix, hkv);
 }
 
 hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st) {
@@ -693,34 +246,7 @@ hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st) {
         (const __bf16*)a.o, (const __bf16*)a.d_o, a.delta, a.n_q, a.hq);
     if (hipError_t e = hipGetLastError()) return e;
   }
-  {
-    KvPlan pl;
-    const size_t need = kv_plan_layout(a.workspace, a.n_q, a.n_prefix, a.hkv, &pl);
-    if (need > a.workspace_bytes) return hipErrorInvalidValue;
-    {
-      KernelTimer timer(TT_KERNEL_ATTN_PLAN, st);
-      kv_plan_kernel<<<1, PLAN_THREADS, 0, st>>>(pl, a.kt_max, a.n_q, a.n_prefix, a.hq / a.hkv, a.hkv);
-      if (hipError_t e = hipGetLastError()) return e;
-    }
-    if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_dkdv_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KvSmem)))
-      return e;
-    int dev = 0, n_cu = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-    // one resident workgroup per compute unit pulls work items until the counter runs out
-    const int64_t max_work = (int64_t)pl.max_items * a.hkv;
-    const unsigned grid = (unsigned)std::min<int64_t>(n_cu, max_work);
-    {
-      KernelTimer timer(TT_KERNEL_ATTN_DKDV, st);
-      tree_attn_dkdv_kernel<<<grid, NTHREADS, sizeof(KvSmem), st>>>(a, pl);
-      if (hipError_t e = hipGetLastError()) return e;
-    }
-    {
-      KernelTimer timer(TT_KERNEL_ATTN_REDUCE, st);
-      kv_reduce_kernel<<<dim3(pl.n_tiles, a.hkv), NTHREADS, 0, st>>>(a, pl);
-      if (hipError_t e = hipGetLastError()) return e;
-    }
-  }
+  if (hipError_t e = mfma_attn_dkdv(a, st)) return e;
   {
     const int n_qtiles = (a.n_q + Q_BM - 1) / Q_BM;
     if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_dq_kernel,

@@ -5,11 +5,12 @@
 // kend, which is all that is needed to skip a tile (nothing visible), run it unmasked (everything
 // visible) or apply the per-element test (boundary tile).
 //
-// One workgroup = 128 queries x one query head, 4 wavefronts x 32 queries.  Scores are produced
-// transposed, S^T[key, query] = K Q^T, so that a lane owns one query: the softmax statistics are
-// per-lane scalars (plus one exchange with the lane holding the other half of the column), and
-// P^T is already in B-operand layout for O^T[d, query] += V^T[d, key] P^T[key, query].  K and V
-// tiles are staged through LDS (double buffered); V^T fragments come from transposed LDS reads.
+// One workgroup = 128 queries x one query head, 4 wavefronts x 32 queries, two workgroups per
+// compute unit.  Scores are produced transposed, S^T[key, query] = K Q^T, so that a lane owns one
+// query: the softmax statistics are per-lane scalars (plus one exchange with the lane holding the
+// other half of the column), and P^T is already in B-operand layout for
+// O^T[d, query] += V^T[d, key] P^T[key, query].  K and V tiles go from global memory straight into
+// swizzled LDS tiles (asynchronous, double buffered); V^T fragments come from transposed LDS reads.
 #include <hip/hip_runtime.h>
 #include "tt_kernels.h"
 #include "tt_mfma.h"
@@ -21,64 +22,130 @@ constexpr int D = 128;
 constexpr int BM = 128;            // queries per workgroup
 constexpr int BN = 64;             // keys per tile (= TT_KTILE)
 constexpr int NTHREADS = 256;
-constexpr int KP = D + 8;          // K row pitch in LDS (elements): 272 B -> conflict-free b128 reads
-constexpr int VP = D + 32;         // V row pitch: 320 B -> conflict-free transposed b64 reads
-constexpr int K_TILE_ELEMS = BN * KP;
-constexpr int V_TILE_ELEMS = BN * VP;
+constexpr int TILE_ELEMS = BN * TILE_ROW;
 
 struct Smem {
-  __bf16 k[2][K_TILE_ELEMS];
-  __bf16 v[2][V_TILE_ELEMS];
+  __bf16 k[2][TILE_ELEMS];
+  __bf16 v[2][TILE_ELEMS];
   int32_t kend[2][BN];
 };
 
-// Registers holding one K/V tile in flight from global memory to LDS.
-struct Staging {
-  i32x4 k[4], v[4];
-  int32_t kend;
+struct Ctx {
+  const AttnArgs& a;
+  int kvh, P, N, npt;
 };
 
-struct TileSrc {
-  const __bf16* k;     // first row of the tile, already offset to the kv head
-  const __bf16* v;
-  int64_t k_stride, v_stride;
-  int rows;            // valid rows in the tile (1..64)
-  const int32_t* kend; // kend of the tile's first key
-};
-
-__device__ __forceinline__ void load_tile(const TileSrc& s, Staging& st) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    i32x4 zk = {0, 0, 0, 0}, zv = {0, 0, 0, 0};
-    if (row < s.rows) {
-      zk = *(const i32x4*)(s.k + (int64_t)row * s.k_stride + col);
-      zv = *(const i32x4*)(s.v + (int64_t)row * s.v_stride + col);
-    }
-    st.k[u] = zk;
-    st.v[u] = zv;
+// Starts the copy of key tile u (K, V rows and visibility bounds) into stage `buf`.
+__device__ __forceinline__ int issue_tile(const Ctx& c, Smem& sm, int buf, int u, int w, int lane) {
+  const AttnArgs& a = c.a;
+  const __bf16 *kp, *vp;
+  const int32_t* ke;
+  uint32_t ks, vs;
+  int rows;
+  if (u < c.npt) {
+    const int k0 = u * BN;
+    kp = (const __bf16*)a.k_prefix + ((int64_t)k0 * a.hkv + c.kvh) * D;
+    vp = (const __bf16*)a.v_prefix + ((int64_t)k0 * a.hkv + c.kvh) * D;
+    ks = vs = (uint32_t)a.hkv * D * 2;
+    rows = min(BN, c.P - k0);
+    ke = a.kend + k0;
+  } else {
+    const int k0 = (u - c.npt) * BN;
+    kp = (const __bf16*)a.k_own + (int64_t)k0 * a.k_stride + (int64_t)c.kvh * D;
+    vp = (const __bf16*)a.v_own + (int64_t)k0 * a.v_stride + (int64_t)c.kvh * D;
+    ks = (uint32_t)a.k_stride * 2;
+    vs = (uint32_t)a.v_stride * 2;
+    rows = min(BN, c.N - k0);
+    ke = a.kend + c.P + k0;
   }
+  dma_tile64(kp, ks, rows, sm.k[buf], w, lane);
+  dma_tile64(vp, vs, rows, sm.v[buf], w, lane);
   // keys past the end of the region get bound 0: visible to nobody
-  st.kend = (t < BN) ? (t < s.rows ? s.kend[t] : 0) : 0;
+  int kv = 0;
+  if (w == 0) kv = lane < rows ? ke[lane] : 0;
+  return kv;
 }
 
-__device__ __forceinline__ void store_tile(Smem& sm, int buf, const Staging& st) {
-  const int t = threadIdx.x;
+// One key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  FULL = every (query, key) pair of the
+// tile is visible: no per-element test, and the whole tile is one branch-free block so that the
+// compiler can overlap LDS reads, softmax arithmetic and MFMAs.
+template <bool FULL>
+__device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
+                                             float& m_run, float& l_run, float c_scale, int j0, int gi,
+                                             int k_rd, TrBase v_rd, int hf) {
+  f32x16 s_acc[2];
+  {
+    // all 16 K fragments are requested in program order first; the scheduling groups below keep 4
+    // reads in flight ahead of the MFMA that consumes them
+    bf16x8 kfr[16];
 #pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int c = t + NTHREADS * u;
-    const int row = c >> 4, col = (c & 15) * 8;
-    *(i32x4*)(&sm.k[buf][row * KP + col]) = st.k[u];
-    *(i32x4*)(&sm.v[buf][row * VP + col]) = st.v[u];
+    for (int i = 0; i < 16; i++) kfr[i] = lds_row_frag(sm.k[buf], k_rd, i >> 3, i & 7);
+#pragma unroll
+    for (int i = 0; i < 16; i++) s_acc[i >> 3] = mfma32(kfr[i], qf[i & 7], (i & 7) == 0 ? zero16() : s_acc[i >> 3]);
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // 4 LDS reads
+#pragma unroll
+    for (int i = 0; i < 12; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // 1 LDS read
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   }
-  if (t < BN) sm.kend[buf][t] = st.kend;
+  if (!FULL) {
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const int jl = kb * 32 + r4 * 8 + 4 * hf;
+        const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          const int j = j0 + jl + e;
+          const bool vis = j <= gi && gi < ke[e];
+          s_acc[kb][r4 * 4 + e] = vis ? s_acc[kb][r4 * 4 + e] : -INFINITY;
+        }
+      }
+  }
+
+  // ---- online softmax (base 2) ----
+  float tmax = s_acc[0][0];
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, s_acc[kb][r]);
+  tmax = half_swap_max(tmax) * c_scale;               // c_scale > 0
+  const float m_new = fmaxf(m_run, tmax);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: keep everything at 0
+  const float alpha = fast_exp2(m_run - m_use);
+  m_run = m_new;
+  float psum = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      const float p = fast_exp2(fmaf(s_acc[kb][r], c_scale, -m_use));
+      s_acc[kb][r] = p;
+      psum += p;
+    }
+  l_run = l_run * alpha + psum;
+#pragma unroll
+  for (int db = 0; db < 4; db++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+
+  // ---- O^T += V^T P^T ----
+#pragma unroll
+  for (int ks = 0; ks < 4; ks++) {
+    const int kb = ks >> 1, t8 = (ks & 1) * 8;
+    const bf16x8 pf = cvt8(s_acc[kb][t8 + 0], s_acc[kb][t8 + 1], s_acc[kb][t8 + 2], s_acc[kb][t8 + 3],
+                           s_acc[kb][t8 + 4], s_acc[kb][t8 + 5], s_acc[kb][t8 + 6], s_acc[kb][t8 + 7]);
+#pragma unroll
+    for (int db = 0; db < 4; db++) o_acc[db] = mfma32(lds_tr_frag(sm.v[buf], v_rd, 16 * ks, db), pf, o_acc[db]);
+  }
 }
 
 __global__ void __launch_bounds__(NTHREADS, 2)
 tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int c32 = lane & 31, hf = lane >> 5;
@@ -96,6 +163,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   const int gi_first = P + q0, gi_last = P + q_hi - 1;
   const int npt = (P + BN - 1) / BN;                 // prefix tiles
   const int u_end = npt + (q_hi - 1) / BN + 1;       // own tiles up to the diagonal
+  const Ctx ctx{a, kvh, P, N, npt};
 
   // ---- Q fragments (B operand: column = query, k = d) straight from global memory ----
   const int my_q = min(q0 + 32 * w + c32, N - 1);
@@ -109,145 +177,49 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
 
   f32x16 o_acc[4];
 #pragma unroll
-  for (int db = 0; db < 4; db++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) o_acc[db][r] = 0.f;
+  for (int db = 0; db < 4; db++) o_acc[db] = zero16();
   float m_run = -INFINITY;      // running max of scale*log2(e)*s  (shared by the two half-lanes)
   float l_run = 0.f;            // this lane's part of the running sum (own keys only)
   const float c_scale = a.scale * LOG2E_F;
 
   KTileIter it;
-  it.init(a.kt_max, a.kt_min, u_end, gi_first);
-
-  auto tile_src = [&](int u) {
-    TileSrc s;
-    if (u < npt) {
-      const int k0 = u * BN;
-      s.k = (const __bf16*)a.k_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
-      s.v = (const __bf16*)a.v_prefix + ((int64_t)k0 * a.hkv + kvh) * D;
-      s.k_stride = s.v_stride = (int64_t)a.hkv * D;
-      s.rows = min(BN, P - k0);
-      s.kend = a.kend + k0;
-    } else {
-      const int k0 = (u - npt) * BN;
-      s.k = (const __bf16*)a.k_own + (int64_t)k0 * a.k_stride + (int64_t)kvh * D;
-      s.v = (const __bf16*)a.v_own + (int64_t)k0 * a.v_stride + (int64_t)kvh * D;
-      s.k_stride = a.k_stride; s.v_stride = a.v_stride;
-      s.rows = min(BN, N - k0);
-      s.kend = a.kend + P + k0;
-    }
-    return s;
-  };
-  // unified index of the first key of tile u
+  it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * BN : P + (u - npt) * BN; };
 
 #pragma unroll
   for (int s = 0; s < 8; s++) pin(qf[s]);
 
-  Staging st;
-  int u_cur = it.next();
-  int kmin_cur = it.kmin;
+  bool full_cur = false;
+  int u_cur = it.next(full_cur);
   if (u_cur >= 0) {
-    load_tile(tile_src(u_cur), st);
-    store_tile(sm, 0, st);
+    const int kv = issue_tile(ctx, sm, 0, u_cur, w, lane);
+    if (w == 0) sm.kend[0][lane] = kv;
   }
+  dma_wait_all();
   __syncthreads();
   int buf = 0;
 
-  // per-lane LDS offsets
-  const int k_rd = c32 * KP + 8 * hf;                                   // + kb*32*KP + 16*s
-  const int i16 = lane & 15, gidx = (lane >> 4) & 1;
-  const int v_rd = (4 * hf + (i16 >> 2)) * VP + 16 * gidx + 4 * (i16 & 3);  // + (16*ks + 8*x)*VP + 32*db
+  const int k_rd = row_frag_base(lane);
+  const TrBase v_rd = tr_frag_base(lane);
 
-  while (u_cur >= 0) {
-    const int u_next = it.next();
-    const int kmin_next = it.kmin;
-    if (u_next >= 0) load_tile(tile_src(u_next), st);
-
-    const int j0 = tile_j0(u_cur);
-    const int rows = u_cur < npt ? min(BN, P - u_cur * BN) : min(BN, N - (u_cur - npt) * BN);
-    // everything visible: all keys exist, all are at or before the first query, and every bound
-    // lies beyond the last query
-    const bool full = rows == BN && j0 + BN - 1 <= gi_first && kmin_cur > gi_last;
-
-    // ---- S^T = K Q^T ----
-    f32x16 s_acc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-      for (int s = 0; s < 8; s++) {
-        const bf16x8 kf = *(const bf16x8*)(&sm.k[buf][k_rd + kb * 32 * KP + 16 * s]);
-        s_acc[kb] = mfma32(kf, qf[s], s == 0 ? zero16() : s_acc[kb]);
-      }
-    }
-
-    // ---- mask (boundary tiles only) ----
-    if (!full) {
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-          const int jl = kb * 32 + r4 * 8 + 4 * hf;
-          const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            const int j = j0 + jl + e;
-            const bool vis = j <= gi && gi < ke[e];
-            s_acc[kb][r4 * 4 + e] = vis ? s_acc[kb][r4 * 4 + e] : -INFINITY;
-          }
-        }
-      }
-    }
-
-    // ---- online softmax (base 2) ----
-    float tmax = s_acc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, s_acc[kb][r]);
-    tmax = half_swap_max(tmax) * c_scale;               // c_scale > 0
-    const float m_new = fmaxf(m_run, tmax);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: keep everything at 0
-    const float alpha = fast_exp2(m_run - m_use);
-    m_run = m_new;
-    float psum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const float p = fast_exp2(fmaf(s_acc[kb][r], c_scale, -m_use));
-        s_acc[kb][r] = p;
-        psum += p;
-      }
-    l_run = l_run * alpha + psum;
-    // the running max rarely moves after the first tiles: rescale only when some lane needs it
-    if (__ballot(alpha != 1.f) != 0) {
-#pragma unroll
-      for (int db = 0; db < 4; db++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
-    }
-
-    // ---- O^T += V^T P^T ----
-#pragma unroll
-    for (int ks = 0; ks < 4; ks++) {
-      const int kb = ks >> 1, t8 = (ks & 1) * 8;
-      const bf16x8 pf = cvt8(s_acc[kb][t8 + 0], s_acc[kb][t8 + 1], s_acc[kb][t8 + 2], s_acc[kb][t8 + 3],
-                             s_acc[kb][t8 + 4], s_acc[kb][t8 + 5], s_acc[kb][t8 + 6], s_acc[kb][t8 + 7]);
-#pragma unroll
-      for (int db = 0; db < 4; db++) {
-        const __bf16* vp = &sm.v[buf][v_rd + 16 * ks * VP + 32 * db];
-        const bf16x8 vf = cat4(lds_read_tr(vp), lds_read_tr(vp + 8 * VP));
-        o_acc[db] = mfma32(vf, pf, o_acc[db]);
-      }
-    }
-
-    if (u_next >= 0) store_tile(sm, buf ^ 1, st);
-    __syncthreads();
-    buf ^= 1;
-    u_cur = u_next;
-    kmin_cur = kmin_next;
+  // One pipeline step: start the copy of the next tile, do this tile's math, publish the next tile.
+#define TT_FWD_STEP(FULLFLAG)                                                                          \
+  {                                                                                                    \
+    bool full_next = false;                                                                            \
+    const int u_next = it.next(full_next);                                                             \
+    int kv_next = 0;                                                                                   \
+    if (u_next >= 0) kv_next = issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                          \
+    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, c_scale, tile_j0(u_cur), gi, k_rd, v_rd, hf); \
+    if (u_next >= 0 && w == 0) sm.kend[buf ^ 1][lane] = kv_next;                                        \
+    dma_wait_all();                                                                                    \
+    __syncthreads();                                                                                   \
+    buf ^= 1;                                                                                          \
+    u_cur = u_next;                                                                                    \
+    full_cur = full_next;                                                                              \
   }
+  while (u_cur >= 0 && full_cur) TT_FWD_STEP(true)
+  while (u_cur >= 0) TT_FWD_STEP(false)
+#undef TT_FWD_STEP
 
   // ---- epilogue ----
   const float l_tot = half_swap_sum(l_run);

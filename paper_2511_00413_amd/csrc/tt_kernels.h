@@ -49,6 +49,9 @@ hipError_t ref_attn_bwd(const RefArgs& a, bool bf16, hipStream_t st);
 hipError_t mfma_attn_fwd(const AttnArgs& a, hipStream_t st);
 hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st);
 size_t mfma_attn_workspace(int n_q, int n_prefix, int hq, int hkv, int d, bool backward);
+// dK/dV pass of the backward (tt_attn_dkdv.hip); a.workspace must hold mfma_attn_dkdv_workspace bytes
+hipError_t mfma_attn_dkdv(const AttnArgs& a, hipStream_t st);
+size_t mfma_attn_dkdv_workspace(int n_q, int n_prefix, int hkv);
 
 // fused log-softmax / gather / weighting (tt_loss.hip)
 hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,

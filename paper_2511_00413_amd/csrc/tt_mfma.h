@@ -81,35 +81,116 @@ __device__ __forceinline__ bf16x4 cvt4(float a0, float a1, float a2, float a3) {
   return __builtin_convertvector(v, bf16x4);
 }
 
+// ---- LDS tiles: rows of 128 bf16 = 16 chunks of 16 bytes, no padding ---------------------------------
+// Chunk c of row r is stored at chunk position c ^ swz(r).  With this permutation both access
+// patterns of the kernels are bank-conflict free: 16 lanes reading the same chunk of 16 consecutive
+// rows (A/B operand rows) and the 4-row x 64-byte blocks of a transposed read.
+constexpr int TILE_ROW = 128;                       // elements per row
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+// Per-lane base offset (elements) for operand-row reads: lane reads row (blk*32 + c32), d-step s,
+// at  row_frag_base(lane) ^ (s << 4)  + blk * 32 * TILE_ROW.
+__device__ __forceinline__ int row_frag_base(int lane) {
+  const int c32 = lane & 31, hf = lane >> 5;
+  return c32 * TILE_ROW + ((hf ^ swz(c32)) << 3);   // bit 0 of the chunk index carries hf
+}
+__device__ __forceinline__ bf16x8 lds_row_frag(const __bf16* tile, int base, int blk, int s) {
+  return *(const bf16x8*)(tile + blk * 32 * TILE_ROW + (base ^ (s << 4)));
+}
+
+// Per-lane base offsets (elements) for transposed reads.  The fragment for MFMA k-step with rows
+// R .. R+15 (R a multiple of 16) and column block db (32 columns) is
+//   cat4( tr(tile + R*TILE_ROW + (tr_base[0] ^ (db << 5))), tr(tile + R*TILE_ROW + (tr_base[1] ^ (db << 5))) )
+// and enumerates the rows in the accumulator-as-B-operand order (see the top of this file).
+struct TrBase { int x0, x1; };
+__device__ __forceinline__ TrBase tr_frag_base(int lane) {
+  const int hf = lane >> 5, i16 = lane & 15, gidx = (lane >> 4) & 1;
+  const int q2 = i16 >> 2, cc = (i16 & 3) >> 1, half = (i16 & 1) * 4;
+  TrBase b;
+  // row = R + 8x + 4hf + q2; chunk = 4db + 2gidx + cc; swz(row) = (q2 << 2) | (hf + 2x)
+  b.x0 = ((4 * hf + q2) << 7) | (q2 << 5) | ((((2 * gidx + cc) ^ hf) & 3) << 3) | half;
+  b.x1 = ((8 + 4 * hf + q2) << 7) | (q2 << 5) | ((((2 * gidx + cc) ^ (hf + 2)) & 3) << 3) | half;
+  return b;
+}
+__device__ __forceinline__ bf16x8 lds_tr_frag(const __bf16* tile, TrBase b, int R, int db) {
+  const __bf16* p = tile + R * TILE_ROW;
+  return cat4(lds_read_tr(p + (b.x0 ^ (db << 5))), lds_read_tr(p + (b.x1 ^ (db << 5))));
+}
+
+// Asynchronous 16-byte-per-lane copy global -> LDS that bypasses the registers: lane l's 16 bytes
+// land at lds_dst + 16*l (lds_dst is wave-uniform), read from gbase + voff (gbase wave-uniform).
+// Completion is tracked by vmcnt; the data is visible to other waves after a wait + barrier.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t voff, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+// 4-byte-per-lane variant: lane l's dword lands at lds_dst + 4*l
+__device__ __forceinline__ void dma4(const void* gbase, uint32_t voff, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_dst), "v"(voff), "s"(gbase) : "memory", "m0");
+}
+__device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ uint32_t lds_addr_uniform(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)p);
+}
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const void*)(((uint64_t)hi << 32) | lo);
+}
+
+// Loads 64 rows x 128 bf16 (row stride `stride_b` bytes, rows >= `rows` clamped to the last valid
+// row) into a swizzled LDS tile; each of the 4 waves moves 16 rows with 4 dma16 instructions.
+__device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b, int rows, __bf16* tile, int w, int lane) {
+  const int lr = lane >> 4, pc = lane & 15;
+  const void* gb = uniform_ptr(gbase);
+#pragma unroll
+  for (int u = 0; u < 4; u++) {
+    const int row = 16 * w + 4 * u + lr;
+    const int rc = min(row, rows - 1);
+    const int c = pc ^ ((lr << 2) | u);               // = pc ^ swz(row)
+    dma16(gb, (uint32_t)rc * stride_b + (uint32_t)c * 16u, lds_addr_uniform(tile + (16 * w + 4 * u) * TILE_ROW));
+  }
+}
+
 // Iterates over the key tiles (TT_KTILE keys each, prefix tiles first, then own tiles) that can hold
 // a key visible to some query of the range [gi_first, gi_last] (unified indices): tiles up to the
-// diagonal whose largest visibility bound exceeds gi_first.  64 tiles are tested per step with one
-// wavefront-wide load + ballot; every wavefront of the workgroup walks the same sequence.
+// diagonal whose largest visibility bound exceeds gi_first.  Tiles in which every (query, key) pair
+// is visible ("full": all 64 keys exist, all lie at or before the first query, and the smallest
+// bound lies beyond the last query) are delivered first, then the tiles that need the per-element
+// test -- softmax accumulation does not care about the order, and the two kinds run in separate
+// branch-free loops.  64 tiles are classified per step with one wavefront-wide load + ballot;
+// every wavefront of the workgroup walks the same sequence.
 struct KTileIter {
   const int32_t *kt_max, *kt_min;
   int u_end;        // one past the last candidate tile
-  int gi_first;
+  int gi_first, gi_last;
+  int npt, P, N;    // prefix tiles, prefix keys, own keys
   int base;         // next window start
-  uint64_t mask;    // unvisited candidates of the current window [base-64, base)
-  int kmin_lane;    // kt_min of tile base-64+lane (the window's values, one per lane)
-  int kmin;         // kt_min of the tile returned by the last next()
-  __device__ __forceinline__ void init(const int32_t* kt_max_, const int32_t* kt_min_, int u_end_, int gi_first_) {
-    kt_max = kt_max_; kt_min = kt_min_; u_end = u_end_; gi_first = gi_first_; base = 0; mask = 0;
-    kmin_lane = 0; kmin = 0;
+  int phase;        // 0: full tiles, 1: boundary tiles
+  uint64_t mask;    // undelivered tiles of the current window [base-64, base)
+  __device__ __forceinline__ void init(const int32_t* kt_max_, const int32_t* kt_min_, int u_end_, int gi_first_,
+                                       int gi_last_, int npt_, int P_, int N_) {
+    kt_max = kt_max_; kt_min = kt_min_; u_end = u_end_; gi_first = gi_first_; gi_last = gi_last_;
+    npt = npt_; P = P_; N = N_; base = 0; phase = 0; mask = 0;
   }
-  __device__ __forceinline__ int next() {
+  // returns the next tile or -1; is_full tells which kind it is
+  __device__ __forceinline__ int next(bool& is_full) {
     while (mask == 0) {
-      if (base >= u_end) return -1;
+      if (base >= u_end) {
+        if (phase == 1) return -1;
+        phase = 1; base = 0;
+      }
       const int u = base + (int)(threadIdx.x & 63);
       const bool in = u < u_end;
-      const bool cand = in && kt_max[u] > gi_first;
-      kmin_lane = in ? kt_min[u] : 0;
-      mask = __ballot(cand);
+      const int j0 = u < npt ? u * 64 : P + (u - npt) * 64;
+      const int rows = u < npt ? P - u * 64 : N - (u - npt) * 64;
+      const bool cand = in && kt_max[in ? u : 0] > gi_first;
+      const bool full = cand && rows >= 64 && j0 + 63 <= gi_first && kt_min[in ? u : 0] > gi_last;
+      mask = __ballot(phase == 0 ? full : (cand && !full));
       base += 64;
     }
     const int b = __builtin_ctzll(mask);
     mask &= mask - 1;
-    kmin = __builtin_amdgcn_readlane(kmin_lane, b);
+    is_full = phase == 0;
     return base - 64 + b;
   }
 };
