@@ -39,7 +39,7 @@ class _AttnDesc(ctypes.Structure):
 
 
 def lib_path() -> str:
-    return os.environ.get("TT_LIB", os.path.join(HERE, "libtreetrain.so"))
+    return os.path.join(HERE, "libtreetrain.so")
 
 
 _LIB = None

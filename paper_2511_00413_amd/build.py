@@ -49,7 +49,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
         objs.append(obj)
         lang = ["-x", "hip"] if s.endswith(".hip") else []
-        cmd = [hipcc()] + HIPCC_FLAGS + PER_FILE_FLAGS.get(s, []) + list(extra_flags) + os.environ.get("TT_EXTRA_FLAGS", "").split() + lang + ["-c", os.path.join(CSRC, s), "-o", obj]
+        cmd = [hipcc()] + HIPCC_FLAGS + PER_FILE_FLAGS.get(s, []) + list(extra_flags) + lang + ["-c", os.path.join(CSRC, s), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -64,7 +64,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(f"--- {s}\n" + "\n".join(lines))
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", os.environ.get("TT_LIB_OUT", LIB)] + objs
+    cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -1,0 +1,130 @@
+"""Redundancy-free tree partitioning, end to end through the C ABI: a tree is cut into connected
+subtrees at node boundaries; every partition attends to the cached K/V of its ancestors' partition
+(with the non-ancestor part of the cached slice masked), gradients for the cached keys come back
+through the fp32 accumulators, and the stitched result must equal the oracle run on the whole tree
+(which knows nothing about partitions).  The greedy packer below is test harness only."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_00413_amd as T
+import workloads as W
+from oracle import attention as A
+from oracle import meta as M
+from tt_testutil import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def greedy_partitions(parent, seg_len, cap):
+    n = len(parent)
+    kids = [[] for _ in range(n)]
+    roots = []
+    for i, p in enumerate(parent):
+        (roots if p < 0 else kids[p]).append(i)
+    parts = []          # each: list of node ids in DFS order, first is the partition root
+
+    def grow(part, size, node):
+        part.append(node)
+        size += int(seg_len[node])
+        for c in kids[node]:
+            if size + int(seg_len[c]) <= cap:
+                size = grow(part, size, c)
+            else:
+                pending.append(c)
+        return size
+
+    pending = list(roots)
+    while pending:
+        r = pending.pop(0)
+        part = []
+        grow(part, 0, r)
+        parts.append(part)
+    return parts
+
+
+@pytest.mark.parametrize("seed,cap,dtype", [(3, 700, "bf16"), (5, 300, "bf16"), (7, 500, "fp32")])
+def test_stitched_partitions_equal_whole_tree(seed, cap, dtype):
+    tree = W.random_tree(200 + seed, n_nodes=14, lo=20, hi=260, shuffle=False)
+    d = 128 if dtype == "bf16" else 64
+    dims = W.AttnDims(4, 2, d, dtype, 0.5 if dtype == "bf16" else 1.0)
+    whole = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = whole["n_tokens"]
+    q, k, v, do = W.attn_inputs(n, n, dims, seed)           # whole-tree DFS order
+    want = A.branches(whole, q.float(), k.float(), v.float(), do.float())
+
+    rank = {int(nid): rk for rk, nid in enumerate(whole["dfs_order"])}
+    node_tokens = lambda nid: np.arange(whole["node_start"][rank[nid]], whole["node_end"][rank[nid]])
+    parts = greedy_partitions(list(tree.parent), list(tree.seg_len), cap)
+    assert len(parts) >= 3
+    print(f"[case] partitions seed={seed} cap={cap} {dtype}: {len(parts)} partitions, N={n}", flush=True)
+
+    got = dict(o=np.zeros((n, dims.hq, d)), lse=np.zeros((dims.hq, n)), dq=np.zeros((n, dims.hq, d)),
+               dk=np.zeros((n, dims.hkv, d)), dv=np.zeros((n, dims.hkv, d)))
+    ctx = {}            # partition root node -> (cached token ids, visible flags) it sees as prefix
+    part_of = {}
+    for pi, part in enumerate(parts):
+        for nid in part:
+            part_of[nid] = pi
+    for part in parts:
+        root = part[0]
+        ctx_tok, ctx_vis = ctx.get(root, (np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.uint8)))
+        # partition-local tree
+        local = {nid: i for i, nid in enumerate(part)}
+        lparent = [-1 if nid == root else local[int(tree.parent[nid])] for nid in part]
+        lseg = [int(tree.seg_len[nid]) for nid in part]
+        pos_off = int(whole["node_pos0"][rank[root]])
+        g_glob = [int(whole["node_g"][rank[nid]]) for nid in part]
+        ltrained = [int(tree.trained[nid]) for nid in part]
+        meta = T.tree_build_meta(lparent, lseg, ltrained, root_pos_offset=[pos_off], g_override=g_glob,
+                                 K_override=int(whole["K"]), n_prefix=len(ctx_tok), prefix_visible=ctx_vis)
+        own = np.concatenate([node_tokens(part[i]) for i in meta.dfs_order])   # global ids, local DFS order
+        assert bool(np.array_equal(meta.tok_pos, whole["tok_pos"][own])), "depth-based positions"
+        assert bool(np.array_equal(meta.tok_weight, whole["tok_weight"][own])), "global g / K weights"
+        sel = torch.from_numpy(own)
+        dev = lambda x: x.cuda()
+        kend, kmin, kmax = (torch.from_numpy(x).cuda() for x in (meta.kend, meta.ktile_kend_min, meta.ktile_kend_max))
+        kp = vp = dkp = dvp = None
+        if len(ctx_tok):
+            csel = torch.from_numpy(ctx_tok)
+            kp, vp = dev(k[csel].contiguous()), dev(v[csel].contiguous())
+            dkp = torch.zeros(kp.shape, dtype=torch.float32, device="cuda")
+            dvp = torch.zeros(kp.shape, dtype=torch.float32, device="cuda")
+        qd, kd, vd, dod = dev(q[sel].contiguous()), dev(k[sel].contiguous()), dev(v[sel].contiguous()), dev(do[sel].contiguous())
+        o, lse = T.tree_attn_fwd(qd, kd, vd, kend, kmin, kmax, k_prefix=kp, v_prefix=vp)
+        dq, dk, dv = T.tree_attn_bwd(qd, kd, vd, kend, kmin, kmax, o, dod, lse, k_prefix=kp, v_prefix=vp,
+                                     dk_prefix_acc=dkp, dv_prefix_acc=dvp)
+        torch.cuda.synchronize()
+        got["o"][own] = o.float().cpu().numpy()
+        got["lse"][:, own] = lse.cpu().numpy()
+        got["dq"][own] = dq.float().cpu().numpy()
+        got["dk"][own] += dk.float().cpu().numpy()
+        got["dv"][own] += dv.float().cpu().numpy()
+        if len(ctx_tok):
+            vis = ctx_vis.astype(bool)
+            dkc, dvc = dkp.cpu().numpy(), dvp.cpu().numpy()
+            assert np.all(dkc[~vis] == 0) and np.all(dvc[~vis] == 0)
+            np.add.at(got["dk"], ctx_tok[vis], dkc[vis])
+            np.add.at(got["dv"], ctx_tok[vis], dvc[vis])
+        # gateways for the child partitions cut below this one: cached slice = this partition's own
+        # cache + its own tokens up to the end of the cut node; visible = ancestors of the child
+        for nid in part:
+            for c in [x for x in range(len(tree.parent)) if int(tree.parent[x]) == nid and part_of[x] != part_of[nid]]:
+                anc = set()
+                a = nid
+                while a in local:
+                    anc.add(a)
+                    a = int(tree.parent[a]) if a != root else -2
+                upto = int(np.nonzero(meta.dfs_order == local[nid])[0][0])       # local DFS rank of the cut node
+                toks, flags = [ctx_tok], [ctx_vis]
+                for rk in range(upto + 1):
+                    lid = part[int(meta.dfs_order[rk])]
+                    t = node_tokens(lid)
+                    toks.append(t)
+                    flags.append(np.full(len(t), 1 if lid in anc else 0, dtype=np.uint8))
+                ctx[c] = (np.concatenate(toks).astype(np.int64), np.concatenate(flags))
+    tol = dict(o=1e-2, lse=1e-2, dq=2e-2, dk=2e-2, dv=2e-2) if dtype == "bf16" else dict.fromkeys(("o", "lse", "dq", "dk", "dv"), 1e-5)
+    errs = {key: rel_l2(got[key], want[key]) for key in tol}
+    print("   rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
+    for key, e in errs.items():
+        assert e <= tol[key], (key, e)
