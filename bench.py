@@ -22,6 +22,15 @@ import numpy as np
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0
 
+# HBM bytes per launch (read + write) of the attention kernels, from the rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs summarised under profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the plain
+# 1 GiB copy of the same run).  Offline measurements: reported only for the workload they cover.
+MEASURED_TRAFFIC_BYTES = {
+    (2, "attn_fwd"): 217.1e6 + 136.6e6,
+    (2, "attn_dkdv"): 4268.9e6 + 174.4e6,
+    (2, "attn_dq"): 371.3e6 + 134.4e6,
+}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -33,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-linearized", action="store_true")
     ap.add_argument("--no-loss", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region, run one plain 1 GiB device copy (a known-size kernel "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -181,7 +193,7 @@ def main():
         achieved = alg_flop[dom] * dims.hq * dims.d * pairs / (avg_ms * 1e-3) / 1e12
         peak = PEAK_BF16_TFLOPS if dims.dtype == "bf16" else 157.3
         roofline = {"kernel": dom, "bound": "mfma" if dims.dtype == "bf16" else "alu", "achieved": round(achieved, 2),
-                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, dom)),
                     "avg_ms": round(avg_ms, 4),
                     "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
     loss_gbps = None
@@ -243,6 +255,13 @@ def main():
             sample = "per-row oracle, fwd+bwd, last 96 tokens, kv head group 0 (%d query heads)" % G
         cpu = {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(),
                "kind": "oracle", "sample": sample, "seconds": round(dtc, 2)}
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "tree-attn fwd+bwd useful TFLOP/s",
