@@ -24,7 +24,8 @@ constexpr int NTHREADS = 256;
 // dK / dV
 // ------------------------------------------------------------------------------------------------
 constexpr int KV_BN = 128;         // keys per workgroup (two TT_KTILE summaries)
-constexpr int KV_BM = 64;          // queries per staged tile
+constexpr int KV_BM = 64;          // queries per staged tile (one pipeline step)
+constexpr int KV_NQB = KV_BM / 32;  // 32-query blocks per step
 
 struct KvSmem {
   __bf16 q[2][KV_BM * TILE_ROW];   // swizzled tiles, filled by asynchronous global -> LDS copies
@@ -36,14 +37,23 @@ struct KvSmem {
 // Starts the copy of one (head, query tile) step into stage `buf`.
 __device__ __forceinline__ void kv_issue(const AttnArgs& a, KvSmem& sm, int buf, int h, int q0, int w, int lane) {
   const int rows = min(KV_BM, a.n_q - q0);
-  dma_tile64((const __bf16*)a.q + (int64_t)q0 * a.q_stride + (int64_t)h * D, (uint32_t)a.q_stride * 2, rows, sm.q[buf], w, lane);
-  dma_tile64((const __bf16*)a.d_o + ((int64_t)q0 * a.hq + h) * D, (uint32_t)a.hq * D * 2, rows, sm.g[buf], w, lane);
-  // per-query scalars: wave 0 copies LSE, wave 1 copies delta (rows past the end repeat the last one;
-  // such rows are masked by the boundary test)
-  if (w < 2) {
-    const float* src = (w == 0 ? a.lse : a.delta) + (int64_t)h * a.n_q + q0;
-    float* dst = w == 0 ? sm.lse[buf] : sm.delta[buf];
-    dma4(uniform_ptr(src), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(dst));
+  const __bf16* qsrc = (const __bf16*)a.q + (int64_t)q0 * a.q_stride + (int64_t)h * D;
+  const __bf16* gsrc = (const __bf16*)a.d_o + ((int64_t)q0 * a.hq + h) * D;
+#pragma unroll
+  for (int c = 0; c < KV_BM / 64; c++) {
+    dma_tile64(qsrc, (uint32_t)a.q_stride * 2, rows, sm.q[buf] + c * 64 * TILE_ROW, w, lane, 64 * c);
+    dma_tile64(gsrc, (uint32_t)a.hq * D * 2, rows, sm.g[buf] + c * 64 * TILE_ROW, w, lane, 64 * c);
+  }
+  // per-query scalars, 64 per wave: LSE then delta, spread over the waves (rows past the end repeat
+  // the last one; such rows are masked by the boundary test)
+  constexpr int PARTS = KV_BM / 64;                 // 64-float pieces per array
+  static_assert(2 * PARTS <= 4, "at most one scalar piece per wave");
+  if (w < 2 * PARTS) {
+    const bool is_lse = w < PARTS;
+    const int part = is_lse ? w : w - PARTS;
+    const float* src = (is_lse ? a.lse : a.delta) + (int64_t)h * a.n_q + q0;
+    float* dst = (is_lse ? sm.lse[buf] : sm.delta[buf]) + 64 * part;
+    dma4(uniform_ptr(src), (uint32_t)min(64 * part + lane, rows - 1) * 4u, lds_addr_uniform(dst));
   }
 }
 
@@ -176,6 +186,58 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   }
 }
 
+// One (head, 64-query tile) step for a wavefront whose 32 keys are visible to all 64 queries: no
+// visibility test and no branch, so the compiler can run the score MFMAs of both 32-query blocks
+// back to back and overlap the exp / dS arithmetic of one block with the MFMAs of the other.
+__device__ __forceinline__ void kv_step_full(const KvSmem& sm, int buf, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
+                                             f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], float c_scale,
+                                             int a_rd, TrBase t_rd, int hf, int qb0) {
+  f32x16 s_acc[2], p_acc[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+#pragma unroll
+    for (int ss = 0; ss < 8; ss++)
+      s_acc[qb] = mfma32(lds_row_frag(sm.q[buf], a_rd, qb0 + qb, ss), kf[ss], ss == 0 ? zero16() : s_acc[qb]);
+#pragma unroll
+    for (int ss = 0; ss < 8; ss++)
+      p_acc[qb] = mfma32(lds_row_frag(sm.g[buf], a_rd, qb0 + qb, ss), vf[ss], ss == 0 ? zero16() : p_acc[qb]);
+  }
+  // keep 6 operand reads in flight ahead of the MFMA that consumes them
+  __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+  for (int i = 0; i < 26; i++) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+#pragma unroll
+  for (int qb = 0; qb < 2; qb++) {
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++) {
+      const f32x4 l2 = *(const f32x4*)(&sm.lse[buf][(qb0 + qb) * 32 + r4 * 8 + 4 * hf]) * LOG2E_F;
+      const f32x4 dl = *(const f32x4*)(&sm.delta[buf][(qb0 + qb) * 32 + r4 * 8 + 4 * hf]);
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        const float p = fast_exp2(fmaf(s_acc[qb][r4 * 4 + e], c_scale, -l2[e]));
+        s_acc[qb][r4 * 4 + e] = p;
+        p_acc[qb][r4 * 4 + e] = p * (p_acc[qb][r4 * 4 + e] - dl[e]);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const bf16x8 pf = cvt8(s_acc[qb][8 * t + 0], s_acc[qb][8 * t + 1], s_acc[qb][8 * t + 2], s_acc[qb][8 * t + 3],
+                             s_acc[qb][8 * t + 4], s_acc[qb][8 * t + 5], s_acc[qb][8 * t + 6], s_acc[qb][8 * t + 7]);
+      const bf16x8 df = cvt8(p_acc[qb][8 * t + 0], p_acc[qb][8 * t + 1], p_acc[qb][8 * t + 2], p_acc[qb][8 * t + 3],
+                             p_acc[qb][8 * t + 4], p_acc[qb][8 * t + 5], p_acc[qb][8 * t + 6], p_acc[qb][8 * t + 7]);
+#pragma unroll
+      for (int db = 0; db < 4; db++) {
+        dv_acc[db] = mfma32(lds_tr_frag(sm.g[buf], t_rd, (qb0 + qb) * 32 + 16 * t, db), pf, dv_acc[db]);
+        dk_acc[db] = mfma32(lds_tr_frag(sm.q[buf], t_rd, (qb0 + qb) * 32 + 16 * t, db), df, dk_acc[db]);
+      }
+    }
+  }
+}
+
 __global__ void __launch_bounds__(NTHREADS, 1)
 tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -258,8 +320,14 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
       if (s + 1 < s_hi) kv_issue(a, sm, buf ^ 1, step_head(s + 1), step_q0(s + 1), w, lane);   // lands during this step
       const int q0 = step_q0(s);
 
+      // all 32 keys of this wave visible to all queries of the tile?
+      if (jw_last <= P + q0 && kmin_w > P + q0 + KV_BM - 1 && q0 + KV_BM <= N) {
 #pragma unroll
-      for (int qb = 0; qb < 2; qb++) {
+        for (int half = 0; half < KV_NQB / 2; half++)
+          kv_step_full(sm, buf, kf, vf, dk_acc, dv_acc, c_scale, a_rd, t_rd, hf, 2 * half);
+      } else
+#pragma unroll
+      for (int qb = 0; qb < KV_NQB; qb++) {
         const int gq_first = P + q0 + 32 * qb;                 // unified index of the block's first query
         const int gq_last = min(gq_first + 31, P + N - 1);
         // block-level skip: every key is after the last query, or no key's range reaches the block

@@ -137,15 +137,17 @@ __device__ __forceinline__ const void* uniform_ptr(const void* p) {
   return (const void*)(((uint64_t)hi << 32) | lo);
 }
 
-// Loads 64 rows x 128 bf16 (row stride `stride_b` bytes, rows >= `rows` clamped to the last valid
-// row) into a swizzled LDS tile; each of the 4 waves moves 16 rows with 4 dma16 instructions.
-__device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b, int rows, __bf16* tile, int w, int lane) {
+// Loads 64 rows x 128 bf16 into a swizzled LDS tile: tile row r comes from source row
+// min(row0 + r, rows - 1) of a matrix with row stride `stride_b` bytes (so rows past the end repeat the
+// last valid row); each of the 4 waves moves 16 rows with 4 dma16 instructions.
+__device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b, int rows, __bf16* tile, int w, int lane,
+                                           int row0 = 0) {
   const int lr = lane >> 4, pc = lane & 15;
   const void* gb = uniform_ptr(gbase);
 #pragma unroll
   for (int u = 0; u < 4; u++) {
     const int row = 16 * w + 4 * u + lr;
-    const int rc = min(row, rows - 1);
+    const int rc = min(row0 + row, rows - 1);
     const int c = pc ^ ((lr << 2) | u);               // = pc ^ swz(row)
     dma16(gb, (uint32_t)rc * stride_b + (uint32_t)c * 16u, lds_addr_uniform(tile + (16 * w + 4 * u) * TILE_ROW));
   }
