@@ -23,6 +23,7 @@ constexpr int BM = 128;            // queries per workgroup
 constexpr int BN = 64;             // keys per tile (= TT_KTILE)
 constexpr int NTHREADS = 256;
 constexpr int TILE_ELEMS = BN * TILE_ROW;
+constexpr float RESCALE_SLACK = 8.f;   // log2 units
 
 struct Smem {
   __bf16 k[2][TILE_ELEMS];
@@ -113,10 +114,21 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
 #pragma unroll
     for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, s_acc[kb][r]);
   tmax = half_swap_max(tmax) * c_scale;               // c_scale > 0
-  const float m_new = fmaxf(m_run, tmax);
-  const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing visible yet: keep everything at 0
-  const float alpha = fast_exp2(m_run - m_use);
-  m_run = m_new;
+  // m_run is the reference the exponentials are taken against.  It follows the running maximum
+  // lazily: probabilities may exceed 1 by up to 2^RESCALE_SLACK (harmless in bf16 / fp32), and only
+  // when some lane's maximum has grown past that slack are the output accumulators rescaled --
+  // after the first few tiles that almost never happens.
+  if (__ballot(tmax > m_run + RESCALE_SLACK) != 0) {
+    const float m_new = fmaxf(m_run, tmax);
+    const float alpha = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);   // m_run = -inf: alpha = 0
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+  }
+  const float m_use = m_run == -INFINITY ? 0.f : m_run;   // nothing visible yet: keep everything at 0
   float psum = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
@@ -126,11 +138,7 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
       s_acc[kb][r] = p;
       psum += p;
     }
-  l_run = l_run * alpha + psum;
-#pragma unroll
-  for (int db = 0; db < 4; db++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+  l_run += psum;
 
   // ---- O^T += V^T P^T ----
 #pragma unroll
