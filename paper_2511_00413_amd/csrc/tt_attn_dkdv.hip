@@ -187,54 +187,83 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
 }
 
 // One (head, 64-query tile) step for a wavefront whose 32 keys are visible to all 64 queries: no
-// visibility test and no branch, so the compiler can run the score MFMAs of both 32-query blocks
-// back to back and overlap the exp / dS arithmetic of one block with the MFMAs of the other.
+// visibility test and no branch.  The step is written as 64 "slots" of one MFMA each; every slot
+// also issues the LDS reads for an MFMA a few slots ahead and a slice of the exp / dS arithmetic of
+// the other 32-query block, and ends with a scheduling fence so that the emitted order is the
+// written order:
+//   slots  0..15  S, dP of query block 0
+//   slots 16..31  S, dP of block 1      + P, dS arithmetic of block 0 (one element per slot)
+//   slots 32..47  dV, dK from block 0   + P, dS arithmetic of block 1
+//   slots 48..63  dV, dK from block 1
 __device__ __forceinline__ void kv_step_full(const KvSmem& sm, int buf, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
                                              f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], float c_scale,
                                              int a_rd, TrBase t_rd, int hf, int qb0) {
+  constexpr int AHEAD_A = 6;      // operand-row reads in flight (one b128 read per MFMA)
+  constexpr int AHEAD_C = 3;      // transposed fragments in flight (two b64 reads per MFMA)
   f32x16 s_acc[2], p_acc[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
-#pragma unroll
-    for (int ss = 0; ss < 8; ss++)
-      s_acc[qb] = mfma32(lds_row_frag(sm.q[buf], a_rd, qb0 + qb, ss), kf[ss], ss == 0 ? zero16() : s_acc[qb]);
-#pragma unroll
-    for (int ss = 0; ss < 8; ss++)
-      p_acc[qb] = mfma32(lds_row_frag(sm.g[buf], a_rd, qb0 + qb, ss), vf[ss], ss == 0 ? zero16() : p_acc[qb]);
-  }
-  // keep 6 operand reads in flight ahead of the MFMA that consumes them
-  __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
-#pragma unroll
-  for (int i = 0; i < 26; i++) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
-#pragma unroll
-  for (int qb = 0; qb < 2; qb++) {
+  f32x4 l2[2][4], dl[2][4];
+  bf16x8 fa[AHEAD_A], fc[AHEAD_C];
+  bf16x8 pf[2], df[2];            // P / dS of the block being consumed, per 16-query k-step
+
+  // operand of score slot i: i>>4 = query block, (i>>3)&1 = 0: Q rows (S), 1: dO rows (dP), i&7 = d-step
+  auto read_a = [&](int i) {
+    return lds_row_frag(((i >> 3) & 1) ? sm.g[buf] : sm.q[buf], a_rd, qb0 + (i >> 4), i & 7);
+  };
+  // operand of gradient slot j: j>>4 = query block, (j>>3)&1 = k-step t, (j>>1)&3 = d block,
+  // j&1 = 0: dO^T (feeds dV with P), 1: Q^T (feeds dK with dS)
+  auto read_c = [&](int j) {
+    return lds_tr_frag((j & 1) ? sm.q[buf] : sm.g[buf], t_rd, (qb0 + (j >> 4)) * 32 + 16 * ((j >> 3) & 1), (j >> 1) & 3);
+  };
+  auto scalars = [&](int b) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
-      const f32x4 l2 = *(const f32x4*)(&sm.lse[buf][(qb0 + qb) * 32 + r4 * 8 + 4 * hf]) * LOG2E_F;
-      const f32x4 dl = *(const f32x4*)(&sm.delta[buf][(qb0 + qb) * 32 + r4 * 8 + 4 * hf]);
-#pragma unroll
-      for (int e = 0; e < 4; e++) {
-        const float p = fast_exp2(fmaf(s_acc[qb][r4 * 4 + e], c_scale, -l2[e]));
-        s_acc[qb][r4 * 4 + e] = p;
-        p_acc[qb][r4 * 4 + e] = p * (p_acc[qb][r4 * 4 + e] - dl[e]);
-      }
+      l2[b][r4] = *(const f32x4*)(&sm.lse[buf][(qb0 + b) * 32 + r4 * 8 + 4 * hf]) * LOG2E_F;
+      dl[b][r4] = *(const f32x4*)(&sm.delta[buf][(qb0 + b) * 32 + r4 * 8 + 4 * hf]);
     }
+  };
+  auto element = [&](int b, int e) {       // P and dS of accumulator register e of block b
+    const float p = fast_exp2(fmaf(s_acc[b][e], c_scale, -l2[b][e >> 2][e & 3]));
+    s_acc[b][e] = p;
+    p_acc[b][e] = p * (p_acc[b][e] - dl[b][e >> 2][e & 3]);
+  };
+  auto convert = [&](int b, int t) {
+    pf[t] = cvt8(s_acc[b][8 * t + 0], s_acc[b][8 * t + 1], s_acc[b][8 * t + 2], s_acc[b][8 * t + 3],
+                 s_acc[b][8 * t + 4], s_acc[b][8 * t + 5], s_acc[b][8 * t + 6], s_acc[b][8 * t + 7]);
+    df[t] = cvt8(p_acc[b][8 * t + 0], p_acc[b][8 * t + 1], p_acc[b][8 * t + 2], p_acc[b][8 * t + 3],
+                 p_acc[b][8 * t + 4], p_acc[b][8 * t + 5], p_acc[b][8 * t + 6], p_acc[b][8 * t + 7]);
+  };
+
 #pragma unroll
-    for (int t = 0; t < 2; t++) {
-      const bf16x8 pf = cvt8(s_acc[qb][8 * t + 0], s_acc[qb][8 * t + 1], s_acc[qb][8 * t + 2], s_acc[qb][8 * t + 3],
-                             s_acc[qb][8 * t + 4], s_acc[qb][8 * t + 5], s_acc[qb][8 * t + 6], s_acc[qb][8 * t + 7]);
-      const bf16x8 df = cvt8(p_acc[qb][8 * t + 0], p_acc[qb][8 * t + 1], p_acc[qb][8 * t + 2], p_acc[qb][8 * t + 3],
-                             p_acc[qb][8 * t + 4], p_acc[qb][8 * t + 5], p_acc[qb][8 * t + 6], p_acc[qb][8 * t + 7]);
+  for (int i = 0; i < AHEAD_A; i++) fa[i] = read_a(i);
+  scalars(0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- score slots ----
 #pragma unroll
-      for (int db = 0; db < 4; db++) {
-        dv_acc[db] = mfma32(lds_tr_frag(sm.g[buf], t_rd, (qb0 + qb) * 32 + 16 * t, db), pf, dv_acc[db]);
-        dk_acc[db] = mfma32(lds_tr_frag(sm.q[buf], t_rd, (qb0 + qb) * 32 + 16 * t, db), df, dk_acc[db]);
-      }
-    }
+  for (int i = 0; i < 32; i++) {
+    const int b = i >> 4, ss = i & 7;
+    if ((i >> 3) & 1) p_acc[b] = mfma32(fa[i % AHEAD_A], vf[ss], ss == 0 ? zero16() : p_acc[b]);
+    else s_acc[b] = mfma32(fa[i % AHEAD_A], kf[ss], ss == 0 ? zero16() : s_acc[b]);
+    if (i + AHEAD_A < 32) fa[i % AHEAD_A] = read_a(i + AHEAD_A);
+    if (i == 8) scalars(1);
+    if (i >= 32 - AHEAD_C) fc[i - (32 - AHEAD_C)] = read_c(i - (32 - AHEAD_C));   // first gradient fragments
+    if (i >= 16) element(0, i - 16);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  convert(0, 0);
+  convert(0, 1);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- gradient slots ----
+#pragma unroll
+  for (int j = 0; j < 32; j++) {
+    const int t = (j >> 3) & 1, db = (j >> 1) & 3;
+    if (j == 16) { convert(1, 0); convert(1, 1); }
+    if (j & 1) dk_acc[db] = mfma32(fc[j % AHEAD_C], df[t], dk_acc[db]);
+    else dv_acc[db] = mfma32(fc[j % AHEAD_C], pf[t], dv_acc[db]);
+    if (j + AHEAD_C < 32) fc[j % AHEAD_C] = read_c(j + AHEAD_C);
+    if (j < 16) element(1, j);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
