@@ -68,9 +68,11 @@ struct QCtx {
   int kvh, P, N, npt;
 };
 
-// Starts the copy of key tile u (K, V rows) into stage `buf`; returns this lane's visibility bound
-// (wave 0 only) for the caller to store once the tile's math is done.
-__device__ __forceinline__ int q_issue_tile(const QCtx& c, QSmem& sm, int buf, int u, int w, int lane) {
+// Starts the copy of key tile u (K, V rows and visibility bounds) into stage `buf`, all through the
+// asynchronous global -> LDS path (a load into a register would make the compiler wait for every
+// outstanding memory operation, the tile copies included, at its first use).  Rows past the end of
+// the region repeat the last valid row; dq_tile keeps them invisible.
+__device__ __forceinline__ void q_issue_tile(const QCtx& c, QSmem& sm, int buf, int u, int w, int lane) {
   const AttnArgs& a = c.a;
   const __bf16 *kp, *vp;
   const int32_t* ke;
@@ -94,16 +96,15 @@ __device__ __forceinline__ int q_issue_tile(const QCtx& c, QSmem& sm, int buf, i
   }
   dma_tile64(kp, ks, rows, sm.k[buf], w, lane);
   dma_tile64(vp, vs, rows, sm.v[buf], w, lane);
-  int kv = 0;
-  if (w == 0) kv = lane < rows ? ke[lane] : 0;     // keys past the end of the region: visible to nobody
-  return kv;
+  if (w == 0) dma4(uniform_ptr(ke), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(sm.kend[buf]));
 }
 
 // One key tile of the dQ pass.  FULL: no per-element visibility test, one branch-free block.
 template <bool FULL>
 __device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
                                         f32x16 (&dq_acc)[4], float c_scale, float lse2, float delta,
-                                        int j0, int gi, int a_rd, TrBase t_rd, int hf) {
+                                        int j0, int j_last, int gi, int a_rd, TrBase t_rd, int hf) {
+  const int gi_c = min(gi, j_last);       // causal bound that also hides the rows past the last key
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
     f32x16 s_acc, p_acc;
@@ -122,7 +123,7 @@ __device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const int j = j0 + jl + e;
-          s_acc[r4 * 4 + e] = (j <= gi && gi < ke[e]) ? s_acc[r4 * 4 + e] : 0.f;
+          s_acc[r4 * 4 + e] = (j <= gi_c && gi < ke[e]) ? s_acc[r4 * 4 + e] : 0.f;
         }
       }
     }
@@ -181,16 +182,18 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   KTileIter it;
   it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * Q_BN : P + (u - npt) * Q_BN; };
+  auto tile_j_last = [&](int u) {
+    return u < npt ? min(u * Q_BN + Q_BN, P) - 1 : P + min((u - npt) * Q_BN + Q_BN, N) - 1;
+  };
 
 #pragma unroll
   for (int s = 0; s < 8; s++) { pin(qf[s]); pin(gf[s]); }
+  pin(lse2);
+  pin(delta);
 
   bool full_cur = false;
   int u_cur = it.next(full_cur);
-  if (u_cur >= 0) {
-    const int kv = q_issue_tile(ctx, sm, 0, u_cur, w, lane);
-    if (w == 0) sm.kend[0][lane] = kv;
-  }
+  if (u_cur >= 0) q_issue_tile(ctx, sm, 0, u_cur, w, lane);
   dma_wait_all();
   __syncthreads();
   int buf = 0;
@@ -202,10 +205,9 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   {                                                                                                     \
     bool full_next = false;                                                                             \
     const int u_next = it.next(full_next);                                                              \
-    int kv_next = 0;                                                                                    \
-    if (u_next >= 0) kv_next = q_issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                         \
-    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, c_scale, lse2, delta, tile_j0(u_cur), gi, a_rd, t_rd, hf); \
-    if (u_next >= 0 && w == 0) sm.kend[buf ^ 1][lane] = kv_next;                                         \
+    if (u_next >= 0) q_issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                   \
+    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, c_scale, lse2, delta, tile_j0(u_cur), tile_j_last(u_cur), gi, \
+                      a_rd, t_rd, hf);                                                                  \
     dma_wait_all();                                                                                     \
     __syncthreads();                                                                                    \
     buf ^= 1;                                                                                           \

@@ -1,6 +1,6 @@
 // Tree attention backward, dK/dV pass, on bf16 MFMA (gfx950), head dim 128.
 //
-// Column-parallel: one work item = 128 keys x one kv head (4 wavefronts x 32 keys) x a chunk of the
+// Column-parallel: one work item = 256 keys x one kv head (8 wavefronts x 32 keys, two per SIMD) x a chunk of the
 // (query head, query tile) steps that can see those keys.  In DFS order a subtree is contiguous, so
 // the queries that see a key tile form the contiguous range [first key, max kend).
 // S[q,key] = Q K^T and dP[q,key] = dO V^T come out with one key per lane, already in B-operand
@@ -18,42 +18,58 @@ namespace tt {
 namespace {
 
 constexpr int D = 128;
-constexpr int NTHREADS = 256;
+constexpr int KV_NW = 8;                 // wavefronts per workgroup, 32 keys each
+constexpr int NTHREADS = 64 * KV_NW;
 
 // ------------------------------------------------------------------------------------------------
 // dK / dV
 // ------------------------------------------------------------------------------------------------
-constexpr int KV_BN = 128;         // keys per workgroup (two TT_KTILE summaries)
+constexpr int KV_BN = 32 * KV_NW;  // keys per workgroup
 constexpr int KV_BM = 64;          // queries per staged tile (one pipeline step)
 constexpr int KV_NQB = KV_BM / 32;  // 32-query blocks per step
 
+constexpr int KV_KREG = 6;                 // K fragments (k-steps) held in registers; the rest sit in LDS
+constexpr int KV_NFRAG = 8 + (8 - KV_KREG);
 struct KvSmem {
   __bf16 q[2][KV_BM * TILE_ROW];   // swizzled tiles, filled by asynchronous global -> LDS copies
   __bf16 g[2][KV_BM * TILE_ROW];   // dO
   float lse[2][KV_BM];             // natural-log LSE of the tile's queries
   float delta[2][KV_BM];
+  // B-operand fragments of this wave's keys that do not fit in registers, private to each lane
+  // (lane l of wave w keeps fragment f at [w][f][8 l]): the 8 k-steps of V (dP = dO V^T), then
+  // k-steps KV_KREG .. 7 of K
+  __bf16 frag[KV_NW][KV_NFRAG][64 * 8];
+  int work;
 };
+// byte offsets between the LDS arrays, used as immediate offsets of the LDS reads
+constexpr int KV_STAGE_B = KV_BM * TILE_ROW * 2;        // one staged tile
+constexpr int KV_G_OFF = 2 * KV_STAGE_B;                // q[b] -> g[b]
+constexpr int KV_SCALAR_STAGE_B = KV_BM * 4;            // lse[b] -> lse[b ^ 1]
+constexpr int KV_DELTA_OFF = 2 * KV_SCALAR_STAGE_B;     // lse[b] -> delta[b]
+constexpr int KV_RING = 2;                              // operand fragments requested ahead of their MFMA
 
-// Starts the copy of one (head, query tile) step into stage `buf`.
+__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int off) { return *(TT_LDS(const bf16x8)*)(addr + off); }
+__device__ __forceinline__ bf16x8 lds_tr2(uint32_t a0, uint32_t a1, int off) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a0 + off));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a1 + off));
+  return cat4(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi));
+}
+
+// Starts the copy of one (head, query tile) step into stage `buf`.  `lane` should be a value the
+// compiler cannot trace back to the thread index, so that the per-lane source offsets are
+// recomputed here instead of being kept in registers across the whole item.
 __device__ __forceinline__ void kv_issue(const AttnArgs& a, KvSmem& sm, int buf, int h, int q0, int w, int lane) {
   const int rows = min(KV_BM, a.n_q - q0);
   const __bf16* qsrc = (const __bf16*)a.q + (int64_t)q0 * a.q_stride + (int64_t)h * D;
   const __bf16* gsrc = (const __bf16*)a.d_o + ((int64_t)q0 * a.hq + h) * D;
-#pragma unroll
-  for (int c = 0; c < KV_BM / 64; c++) {
-    dma_tile64(qsrc, (uint32_t)a.q_stride * 2, rows, sm.q[buf] + c * 64 * TILE_ROW, w, lane, 64 * c);
-    dma_tile64(gsrc, (uint32_t)a.hq * D * 2, rows, sm.g[buf] + c * 64 * TILE_ROW, w, lane, 64 * c);
-  }
-  // per-query scalars, 64 per wave: LSE then delta, spread over the waves (rows past the end repeat
-  // the last one; such rows are masked by the boundary test)
-  constexpr int PARTS = KV_BM / 64;                 // 64-float pieces per array
-  static_assert(2 * PARTS <= 4, "at most one scalar piece per wave");
-  if (w < 2 * PARTS) {
-    const bool is_lse = w < PARTS;
-    const int part = is_lse ? w : w - PARTS;
-    const float* src = (is_lse ? a.lse : a.delta) + (int64_t)h * a.n_q + q0;
-    float* dst = (is_lse ? sm.lse[buf] : sm.delta[buf]) + 64 * part;
-    dma4(uniform_ptr(src), (uint32_t)min(64 * part + lane, rows - 1) * 4u, lds_addr_uniform(dst));
+  dma_tile64<KV_NW>(qsrc, (uint32_t)a.q_stride * 2, rows, sm.q[buf], w, lane);
+  dma_tile64<KV_NW>(gsrc, (uint32_t)a.hq * D * 2, rows, sm.g[buf], w, lane);
+  // per-query scalars: LSE by wave 0, delta by wave 1 (rows past the end repeat the last one; such
+  // rows are masked by the boundary test)
+  if (w < 2) {
+    const float* src = (w == 0 ? a.lse : a.delta) + (int64_t)h * a.n_q + q0;
+    float* dst = w == 0 ? sm.lse[buf] : sm.delta[buf];
+    dma4(uniform_ptr(src), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(dst));
   }
 }
 
@@ -138,15 +154,14 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   // pass 1: visible query tiles of every key tile
   int my_steps = 0;
   for (int tl = lo; tl < hi; tl++) {
-    int kmax, i_lo;
+    int kmax = 0, i_lo;
+    constexpr int EPT = KV_BN / 64;          // summary entries per key tile
     if (tl < pl.n_ptiles) {
-      const int e0 = 2 * tl, e1 = e0 + 1;
-      kmax = max(kt_max[e0], e1 < np64 ? kt_max[e1] : 0);
+      for (int e = EPT * tl; e < EPT * tl + EPT && e < np64; e++) kmax = max(kmax, kt_max[e]);
       i_lo = 0;
     } else {
       const int to = tl - pl.n_ptiles;
-      const int e0 = np64 + 2 * to, e1 = e0 + 1;
-      kmax = max(kt_max[e0], e1 < np64 + no64 ? kt_max[e1] : 0);
+      for (int e = EPT * to; e < EPT * to + EPT && e < no64; e++) kmax = max(kmax, kt_max[np64 + e]);
       i_lo = to * KV_BN;
     }
     const int i_hi = (int)min((int64_t)n_q, (int64_t)kmax - n_prefix);
@@ -186,107 +201,46 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   }
 }
 
-// One (head, 64-query tile) step for a wavefront whose 32 keys are visible to all 64 queries: no
-// visibility test and no branch.  The step is written as 64 "slots" of one MFMA each; every slot
-// also issues the LDS reads for an MFMA a few slots ahead and a slice of the exp / dS arithmetic of
-// the other 32-query block, and ends with a scheduling fence so that the emitted order is the
-// written order:
-//   slots  0..15  S, dP of query block 0
-//   slots 16..31  S, dP of block 1      + P, dS arithmetic of block 0 (one element per slot)
-//   slots 32..47  dV, dK from block 0   + P, dS arithmetic of block 1
-//   slots 48..63  dV, dK from block 1
-__device__ __forceinline__ void kv_step_full(const KvSmem& sm, int buf, const bf16x8 (&kf)[8], const bf16x8 (&vf)[8],
-                                             f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], float c_scale,
-                                             int a_rd, TrBase t_rd, int hf, int qb0) {
-  constexpr int AHEAD_A = 6;      // operand-row reads in flight (one b128 read per MFMA)
-  constexpr int AHEAD_C = 3;      // transposed fragments in flight (two b64 reads per MFMA)
-  f32x16 s_acc[2], p_acc[2];
-  f32x4 l2[2][4], dl[2][4];
-  bf16x8 fa[AHEAD_A], fc[AHEAD_C];
-  bf16x8 pf[2], df[2];            // P / dS of the block being consumed, per 16-query k-step
-
-  // operand of score slot i: i>>4 = query block, (i>>3)&1 = 0: Q rows (S), 1: dO rows (dP), i&7 = d-step
-  auto read_a = [&](int i) {
-    return lds_row_frag(((i >> 3) & 1) ? sm.g[buf] : sm.q[buf], a_rd, qb0 + (i >> 4), i & 7);
-  };
-  // operand of gradient slot j: j>>4 = query block, (j>>3)&1 = k-step t, (j>>1)&3 = d block,
-  // j&1 = 0: dO^T (feeds dV with P), 1: Q^T (feeds dK with dS)
-  auto read_c = [&](int j) {
-    return lds_tr_frag((j & 1) ? sm.q[buf] : sm.g[buf], t_rd, (qb0 + (j >> 4)) * 32 + 16 * ((j >> 3) & 1), (j >> 1) & 3);
-  };
-  auto scalars = [&](int b) {
-#pragma unroll
-    for (int r4 = 0; r4 < 4; r4++) {
-      l2[b][r4] = *(const f32x4*)(&sm.lse[buf][(qb0 + b) * 32 + r4 * 8 + 4 * hf]) * LOG2E_F;
-      dl[b][r4] = *(const f32x4*)(&sm.delta[buf][(qb0 + b) * 32 + r4 * 8 + 4 * hf]);
-    }
-  };
-  auto element = [&](int b, int e) {       // P and dS of accumulator register e of block b
-    const float p = fast_exp2(fmaf(s_acc[b][e], c_scale, -l2[b][e >> 2][e & 3]));
-    s_acc[b][e] = p;
-    p_acc[b][e] = p * (p_acc[b][e] - dl[b][e >> 2][e & 3]);
-  };
-  auto convert = [&](int b, int t) {
-    pf[t] = cvt8(s_acc[b][8 * t + 0], s_acc[b][8 * t + 1], s_acc[b][8 * t + 2], s_acc[b][8 * t + 3],
-                 s_acc[b][8 * t + 4], s_acc[b][8 * t + 5], s_acc[b][8 * t + 6], s_acc[b][8 * t + 7]);
-    df[t] = cvt8(p_acc[b][8 * t + 0], p_acc[b][8 * t + 1], p_acc[b][8 * t + 2], p_acc[b][8 * t + 3],
-                 p_acc[b][8 * t + 4], p_acc[b][8 * t + 5], p_acc[b][8 * t + 6], p_acc[b][8 * t + 7]);
-  };
-
-#pragma unroll
-  for (int i = 0; i < AHEAD_A; i++) fa[i] = read_a(i);
-  scalars(0);
-  __builtin_amdgcn_sched_barrier(0);
-
-  // ---- score slots ----
-#pragma unroll
-  for (int i = 0; i < 32; i++) {
-    const int b = i >> 4, ss = i & 7;
-    if ((i >> 3) & 1) p_acc[b] = mfma32(fa[i % AHEAD_A], vf[ss], ss == 0 ? zero16() : p_acc[b]);
-    else s_acc[b] = mfma32(fa[i % AHEAD_A], kf[ss], ss == 0 ? zero16() : s_acc[b]);
-    if (i + AHEAD_A < 32) fa[i % AHEAD_A] = read_a(i + AHEAD_A);
-    if (i == 8) scalars(1);
-    if (i >= 32 - AHEAD_C) fc[i - (32 - AHEAD_C)] = read_c(i - (32 - AHEAD_C));   // first gradient fragments
-    if (i >= 16) element(0, i - 16);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  convert(0, 0);
-  convert(0, 1);
-  __builtin_amdgcn_sched_barrier(0);
-
-  // ---- gradient slots ----
-#pragma unroll
-  for (int j = 0; j < 32; j++) {
-    const int t = (j >> 3) & 1, db = (j >> 1) & 3;
-    if (j == 16) { convert(1, 0); convert(1, 1); }
-    if (j & 1) dk_acc[db] = mfma32(fc[j % AHEAD_C], df[t], dk_acc[db]);
-    else dv_acc[db] = mfma32(fc[j % AHEAD_C], pf[t], dv_acc[db]);
-    if (j + AHEAD_C < 32) fc[j % AHEAD_C] = read_c(j + AHEAD_C);
-    if (j < 16) element(1, j);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-__global__ void __launch_bounds__(NTHREADS, 1)
+__global__ void __launch_bounds__(NTHREADS, 2)
 tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
   KvSmem& sm = *reinterpret_cast<KvSmem*>(smem_raw);
-  __shared__ int s_work;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // wave-uniform: lives in a scalar register
   const int c32 = lane & 31, hf = lane >> 5;
   const int G = a.hq / a.hkv;
   const int P = a.n_prefix, N = a.n_q;
   const float c_scale = a.scale * LOG2E_F;
-  const int a_rd = row_frag_base(lane);        // operand-row reads
-  const TrBase t_rd = tr_frag_base(lane);      // transposed reads
   const int n_work = pl.hdr->n_work;
   const int chunk = pl.hdr->chunk;
 
+  // LDS byte addresses of this lane's operand fragments in stage `buf` of the Q tile.  The dO tile,
+  // the 32-query block, the k-step rows and the per-query scalars are reached through immediate
+  // offsets; when the stage flips the addresses move by +-one stage.  (A swizzled tile needs one
+  // address per k-step / column block: the permutation is an exclusive-or, not an offset.)
+  const uint32_t sm_base = (uint32_t)(uintptr_t)&sm;
+  uint32_t ra[8], ta[8];
+  {
+    const int a_rd = row_frag_base(lane);
+    const TrBase t_rd = tr_frag_base(lane);
+#pragma unroll
+    for (int ss = 0; ss < 8; ss++) ra[ss] = sm_base + 2u * (uint32_t)(a_rd ^ (ss << 4));
+#pragma unroll
+    for (int db = 0; db < 4; db++) {
+      ta[2 * db] = sm_base + 2u * (uint32_t)(t_rd.x0 ^ (db << 5));
+      ta[2 * db + 1] = sm_base + 2u * (uint32_t)(t_rd.x1 ^ (db << 5));
+    }
+  }
+  uint32_t la = sm_base + (uint32_t)offsetof(KvSmem, lse) + 16u * hf;      // lse[buf][4 hf]
+  const uint32_t va = sm_base + (uint32_t)offsetof(KvSmem, frag) + (uint32_t)(KV_NFRAG * 1024) * w + 16u * lane;
+  int buf = 0;                                  // stage of the next step; carried across work items
+  int stage_step = KV_STAGE_B, scalar_step = KV_SCALAR_STAGE_B;   // signed distance to the other stage
+
   for (;;) {
-    if (threadIdx.x == 0) s_work = atomicAdd(&pl.hdr->counter, 1);
+    if (threadIdx.x == 0) sm.work = atomicAdd(&pl.hdr->counter, 1);
     __syncthreads();
-    const int work = s_work;
-    __syncthreads();                         // everyone has read s_work before it is rewritten
+    const int work = sm.work;
+    __syncthreads();                         // everyone has read the slot before it is rewritten
     if (work >= n_work) break;               // the counter only grows: every wave gets here
     const int kvh = work % a.hkv;            // neighbouring items differ in kv head (XCD locality)
     const int item = work / a.hkv;
@@ -311,9 +265,13 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
       kmax_w = max(kmax_w, __shfl_xor(kmax_w, off));
       kmin_w = min(kmin_w, __shfl_xor(kmin_w, off));
     }
+    kmax_w = __builtin_amdgcn_readfirstlane(kmax_w);
+    kmin_w = __builtin_amdgcn_readfirstlane(kmin_w);
+    const int q_lim = min(my_kend, P + N);           // queries at or beyond this do not see the key
 
-    // ---- K / V fragments of this wave's 32 keys (B operands: column = key, k = d) ----
-    bf16x8 kf[8], vf[8];
+    // ---- K fragments of this wave's 32 keys stay in registers (B operands: column = key, k = d);
+    //      the V fragments go to this lane's private LDS slots ----
+    bf16x8 kf[KV_KREG];
     {
       const int krow = min(kl, region - 1);
       const __bf16* kp = is_prefix ? (const __bf16*)a.k_prefix + ((int64_t)krow * a.hkv + kvh) * D
@@ -321,22 +279,37 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
       const __bf16* vp = is_prefix ? (const __bf16*)a.v_prefix + ((int64_t)krow * a.hkv + kvh) * D
                                    : (const __bf16*)a.v_own + (int64_t)krow * a.v_stride + (int64_t)kvh * D;
 #pragma unroll
+      for (int s = 0; s < KV_KREG; s++) kf[s] = *(const bf16x8*)(kp + 16 * s + 8 * hf);
+#pragma unroll
       for (int s = 0; s < 8; s++) {
-        kf[s] = *(const bf16x8*)(kp + 16 * s + 8 * hf);
-        vf[s] = *(const bf16x8*)(vp + 16 * s + 8 * hf);
+        const bf16x8 vf = *(const bf16x8*)(vp + 16 * s + 8 * hf);
+        *(TT_LDS(bf16x8)*)(va + 1024 * s) = vf;
+      }
+#pragma unroll
+      for (int s = KV_KREG; s < 8; s++) {
+        const bf16x8 kx = *(const bf16x8*)(kp + 16 * s + 8 * hf);
+        *(TT_LDS(bf16x8)*)(va + 1024 * (8 + s - KV_KREG)) = kx;
       }
     }
     f32x16 dk_acc[4], dv_acc[4];
 #pragma unroll
     for (int db = 0; db < 4; db++) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
 
-    auto step_head = [&](int s) { return kvh * G + s / nq; };      // steps are head-major
-    auto step_q0 = [&](int s) { return (qt_lo + s % nq) * KV_BM; };
+    // steps are head-major: step s = (head kvh*G + s / nq, query tile qt_lo + s % nq)
+    int head = kvh * G + s_lo / nq;
+    int qi = s_lo % nq;
 
+    // every register loaded from global memory is consumed here, so that no wait for it (which would
+    // also wait for the tile copies in flight) lands inside the step loop
 #pragma unroll
-    for (int s = 0; s < 8; s++) { pin(kf[s]); pin(vf[s]); }
+    for (int s = 0; s < KV_KREG; s++) pin(kf[s]);
+    pin(q_lim);
 
-    kv_issue(a, sm, 0, step_head(s_lo), step_q0(s_lo), w, lane);
+    {
+      int lane_o = lane;
+      asm volatile("" : "+v"(lane_o));
+      kv_issue(a, sm, buf, head, (qt_lo + qi) * KV_BM, w, lane_o);
+    }
     dma_wait_all();
     __syncthreads();
 
@@ -345,16 +318,14 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
     const int jw_last = jw_first + 31;
 
     for (int s = s_lo; s < s_hi; s++) {
-      const int buf = (s - s_lo) & 1;
-      if (s + 1 < s_hi) kv_issue(a, sm, buf ^ 1, step_head(s + 1), step_q0(s + 1), w, lane);   // lands during this step
-      const int q0 = step_q0(s);
+      const int q0 = (qt_lo + qi) * KV_BM;
+      if (++qi == nq) { qi = 0; head++; }
+      if (s + 1 < s_hi) {                      // the next step's tiles land during this step
+        int lane_o = lane;
+        asm volatile("" : "+v"(lane_o));
+        kv_issue(a, sm, buf ^ 1, head, (qt_lo + qi) * KV_BM, w, lane_o);
+      }
 
-      // all 32 keys of this wave visible to all queries of the tile?
-      if (jw_last <= P + q0 && kmin_w > P + q0 + KV_BM - 1 && q0 + KV_BM <= N) {
-#pragma unroll
-        for (int half = 0; half < KV_NQB / 2; half++)
-          kv_step_full(sm, buf, kf, vf, dk_acc, dv_acc, c_scale, a_rd, t_rd, hf, 2 * half);
-      } else
 #pragma unroll
       for (int qb = 0; qb < KV_NQB; qb++) {
         const int gq_first = P + q0 + 32 * qb;                 // unified index of the block's first query
@@ -362,56 +333,104 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
         // block-level skip: every key is after the last query, or no key's range reaches the block
         if (jw_first > gq_last || kmax_w <= gq_first) continue;
         const bool full = jw_last <= gq_first && kmin_w > gq_last && q0 + 32 * qb + 31 < N;
+        const int qo = qb * 32 * TILE_ROW * 2;                 // byte offset of the block's rows
 
+        // The block is written as a sequence of slots -- one MFMA, the LDS reads for the MFMA
+        // KV_RING slots ahead, a share of the softmax arithmetic -- each closed by a scheduling
+        // fence, so that operand fragments live only briefly (the accumulators and K fragments
+        // already take 160 of the 256 registers per lane).
         f32x16 s_acc, p_acc;
-        f32x4 l2[4], dl[4];
+        bf16x8 fc[KV_RING];
+        // transposed fragments of the output phase: slot n < 8: dO^T for dV, k-step t = n / 4, column
+        // block db = n % 4; n >= 8: Q^T for dK
+        auto read_c = [&](int n) {
+          const int db = n & 3, t = (n >> 2) & 1;
+          const int off = (n < 8 ? KV_G_OFF : 0) + qo + 16 * t * TILE_ROW * 2;
+          return lds_tr2(ta[2 * db], ta[2 * db + 1], off);
+        };
+        {
+          bf16x8 fq[KV_RING], fg[KV_RING], fv[KV_RING];   // fv doubles as the ring of LDS-resident K fragments
 #pragma unroll
-        for (int r4 = 0; r4 < 4; r4++) {
-          l2[r4] = *(const f32x4*)(&sm.lse[buf][qb * 32 + r4 * 8 + 4 * hf]) * LOG2E_F;
-          dl[r4] = *(const f32x4*)(&sm.delta[buf][qb * 32 + r4 * 8 + 4 * hf]);
+          for (int i = 0; i < KV_RING; i++) fq[i] = lds_b128(ra[i], qo);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ss = 0; ss < 8; ss++) {
+            s_acc = mfma32(fq[ss % KV_RING], ss < KV_KREG ? kf[ss < KV_KREG ? ss : 0] : fv[ss % KV_RING], ss == 0 ? zero16() : s_acc);
+            if (ss + KV_RING < 8) {
+              fq[ss % KV_RING] = lds_b128(ra[ss + KV_RING], qo);
+              if (ss + KV_RING >= KV_KREG) fv[(ss + KV_RING) % KV_RING] = lds_b128(va, 1024 * (8 + ss + KV_RING - KV_KREG));
+            } else {
+              const int i = ss + KV_RING - 8;
+              fg[i] = lds_b128(ra[i], KV_G_OFF + qo);
+              fv[i] = lds_b128(va, 1024 * i);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+          for (int ss = 0; ss < 8; ss++) {
+            p_acc = mfma32(fg[ss % KV_RING], fv[ss % KV_RING], ss == 0 ? zero16() : p_acc);
+            if (ss + KV_RING < 8) {
+              fg[ss % KV_RING] = lds_b128(ra[ss + KV_RING], KV_G_OFF + qo);
+              fv[ss % KV_RING] = lds_b128(va, 1024 * (ss + KV_RING));
+            } else {
+              fc[ss + KV_RING - 8] = read_c(ss + KV_RING - 8);
+            }
+            // P = exp2(S c - LSE2) for two accumulator registers per slot, in the MFMA's shadow
+            {
+              const int e0 = 2 * ss;
+              const f32x2 l2 = *(TT_LDS(const f32x2)*)(la + qb * 128 + (e0 >> 2) * 32 + (e0 & 3) * 4) * LOG2E_F;
+              s_acc[e0] = fast_exp2(fmaf(s_acc[e0], c_scale, -l2[0]));
+              s_acc[e0 + 1] = fast_exp2(fmaf(s_acc[e0 + 1], c_scale, -l2[1]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) s_acc = mfma32(lds_row_frag(sm.q[buf], a_rd, qb, ss), kf[ss], ss == 0 ? zero16() : s_acc);
-#pragma unroll
-        for (int ss = 0; ss < 8; ss++) p_acc = mfma32(lds_row_frag(sm.g[buf], a_rd, qb, ss), vf[ss], ss == 0 ? zero16() : p_acc);
-        // P and dS (rows = queries: (r/4)*8 + 4*hf + r%4 inside the block)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            s_acc[r4 * 4 + e] = fast_exp2(fmaf(s_acc[r4 * 4 + e], c_scale, -l2[r4][e]));
         if (!full) {
-          const int q_lim = min(my_kend, P + N);           // queries at or beyond this see nothing
+          asm volatile("" ::: "memory");                   // keep this a real branch (no if-conversion)
+          const int jm = jw_first + (lane & 31);           // this lane's key, unified
 #pragma unroll
           for (int r4 = 0; r4 < 4; r4++)
 #pragma unroll
             for (int e = 0; e < 4; e++) {
               const int gq = gq_first + r4 * 8 + 4 * hf + e;
-              s_acc[r4 * 4 + e] = (j <= gq && gq < q_lim) ? s_acc[r4 * 4 + e] : 0.f;
+              s_acc[r4 * 4 + e] = (jm <= gq && gq < q_lim) ? s_acc[r4 * 4 + e] : 0.f;
             }
         }
+        // dV^T += dO^T P  (8 slots, with dS = P (dP - delta) computed in their shadow), then
+        // dK^T += Q^T dS  (8 slots); rows = queries (r/4)*8 + 4*hf + r%4 inside the block
+        {
+          bf16x8 pf[2], df[2];
+          pf[0] = cvt8(s_acc[0], s_acc[1], s_acc[2], s_acc[3], s_acc[4], s_acc[5], s_acc[6], s_acc[7]);
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            p_acc[r4 * 4 + e] = s_acc[r4 * 4 + e] * (p_acc[r4 * 4 + e] - dl[r4][e]);
-        // dV^T += dO^T P ; dK^T += Q^T dS
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          const bf16x8 pf = cvt8(s_acc[8 * t + 0], s_acc[8 * t + 1], s_acc[8 * t + 2], s_acc[8 * t + 3],
-                                 s_acc[8 * t + 4], s_acc[8 * t + 5], s_acc[8 * t + 6], s_acc[8 * t + 7]);
-          const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
-                                 p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
-#pragma unroll
-          for (int db = 0; db < 4; db++) {
-            dv_acc[db] = mfma32(lds_tr_frag(sm.g[buf], t_rd, qb * 32 + 16 * t, db), pf, dv_acc[db]);
-            dk_acc[db] = mfma32(lds_tr_frag(sm.q[buf], t_rd, qb * 32 + 16 * t, db), df, dk_acc[db]);
+          for (int n = 0; n < 16; n++) {
+            const int t = (n >> 2) & 1, db = n & 3;
+            if (n < 8) dv_acc[db] = mfma32(fc[n % KV_RING], pf[t], dv_acc[db]);
+            else dk_acc[db] = mfma32(fc[n % KV_RING], df[t], dk_acc[db]);
+            if (n + KV_RING < 16) fc[n % KV_RING] = read_c(n + KV_RING);
+            if (n < 8) {
+              const int e0 = 2 * n;
+              const f32x2 dl = *(TT_LDS(const f32x2)*)(la + KV_DELTA_OFF + qb * 128 + (e0 >> 2) * 32 + (e0 & 3) * 4);
+              p_acc[e0] = s_acc[e0] * (p_acc[e0] - dl[0]);
+              p_acc[e0 + 1] = s_acc[e0 + 1] * (p_acc[e0 + 1] - dl[1]);
+              if (n == 2) pf[1] = cvt8(s_acc[8], s_acc[9], s_acc[10], s_acc[11], s_acc[12], s_acc[13], s_acc[14], s_acc[15]);
+              if (n == 4) df[0] = cvt8(p_acc[0], p_acc[1], p_acc[2], p_acc[3], p_acc[4], p_acc[5], p_acc[6], p_acc[7]);
+            }
+            if (n == 8) df[1] = cvt8(p_acc[8], p_acc[9], p_acc[10], p_acc[11], p_acc[12], p_acc[13], p_acc[14], p_acc[15]);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
 
       dma_wait_all();
       __syncthreads();
+      // the next step reads the other stage
+#pragma unroll
+      for (int i = 0; i < 8; i++) { ra[i] += stage_step; ta[i] += stage_step; }
+      la += scalar_step;
+      stage_step = -stage_step;
+      scalar_step = -scalar_step;
+      buf ^= 1;
     }
 
     // ---- epilogue: accumulators hold dK^T / dV^T: column = key, rows d = db*32 + (r/4)*8 + 4*hf + r%4 ----

@@ -36,8 +36,11 @@ struct Ctx {
   int kvh, P, N, npt;
 };
 
-// Starts the copy of key tile u (K, V rows and visibility bounds) into stage `buf`.
-__device__ __forceinline__ int issue_tile(const Ctx& c, Smem& sm, int buf, int u, int w, int lane) {
+// Starts the copy of key tile u (K, V rows and visibility bounds) into stage `buf`.  Everything goes
+// through the asynchronous global -> LDS path: an ordinary load into a register would make the
+// compiler wait for all outstanding memory operations -- the tile copies included -- at its first use.
+// Rows past the end of the region repeat the last valid row; process_tile keeps them invisible.
+__device__ __forceinline__ void issue_tile(const Ctx& c, Smem& sm, int buf, int u, int w, int lane) {
   const AttnArgs& a = c.a;
   const __bf16 *kp, *vp;
   const int32_t* ke;
@@ -61,10 +64,7 @@ __device__ __forceinline__ int issue_tile(const Ctx& c, Smem& sm, int buf, int u
   }
   dma_tile64(kp, ks, rows, sm.k[buf], w, lane);
   dma_tile64(vp, vs, rows, sm.v[buf], w, lane);
-  // keys past the end of the region get bound 0: visible to nobody
-  int kv = 0;
-  if (w == 0) kv = lane < rows ? ke[lane] : 0;
-  return kv;
+  if (w == 0) dma4(uniform_ptr(ke), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(sm.kend[buf]));
 }
 
 // One key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  FULL = every (query, key) pair of the
@@ -72,7 +72,7 @@ __device__ __forceinline__ int issue_tile(const Ctx& c, Smem& sm, int buf, int u
 // compiler can overlap LDS reads, softmax arithmetic and MFMAs.
 template <bool FULL>
 __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
-                                             float& m_run, float& l_run, float c_scale, int j0, int gi,
+                                             float& m_run, float& l_run, float c_scale, int j0, int j_last, int gi,
                                              int k_rd, TrBase v_rd, int hf) {
   f32x16 s_acc[2];
   {
@@ -92,6 +92,7 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   }
   if (!FULL) {
+    const int gi_c = min(gi, j_last);     // causal bound that also hides the rows past the last key
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
@@ -101,7 +102,7 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const int j = j0 + jl + e;
-          const bool vis = j <= gi && gi < ke[e];
+          const bool vis = j <= gi_c && gi < ke[e];
           s_acc[kb][r4 * 4 + e] = vis ? s_acc[kb][r4 * 4 + e] : -INFINITY;
         }
       }
@@ -193,16 +194,14 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   KTileIter it;
   it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * BN : P + (u - npt) * BN; };
+  auto tile_j_last = [&](int u) { return u < npt ? min(u * BN + BN, P) - 1 : P + min((u - npt) * BN + BN, N) - 1; };
 
 #pragma unroll
   for (int s = 0; s < 8; s++) pin(qf[s]);
 
   bool full_cur = false;
   int u_cur = it.next(full_cur);
-  if (u_cur >= 0) {
-    const int kv = issue_tile(ctx, sm, 0, u_cur, w, lane);
-    if (w == 0) sm.kend[0][lane] = kv;
-  }
+  if (u_cur >= 0) issue_tile(ctx, sm, 0, u_cur, w, lane);
   dma_wait_all();
   __syncthreads();
   int buf = 0;
@@ -215,10 +214,9 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   {                                                                                                    \
     bool full_next = false;                                                                            \
     const int u_next = it.next(full_next);                                                             \
-    int kv_next = 0;                                                                                   \
-    if (u_next >= 0) kv_next = issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                          \
-    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, c_scale, tile_j0(u_cur), gi, k_rd, v_rd, hf); \
-    if (u_next >= 0 && w == 0) sm.kend[buf ^ 1][lane] = kv_next;                                        \
+    if (u_next >= 0) issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                    \
+    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, c_scale, tile_j0(u_cur), tile_j_last(u_cur), gi, \
+                           k_rd, v_rd, hf);                                                            \
     dma_wait_all();                                                                                    \
     __syncthreads();                                                                                   \
     buf ^= 1;                                                                                          \

@@ -36,6 +36,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // global load that produced it is placed at this point and not inside the main loop (where a
 // vmcnt wait would also stall on the prefetch of the next tile).
 __device__ __forceinline__ void pin(const bf16x8& f) { asm volatile("" ::"v"(f)); }
+__device__ __forceinline__ void pin(float f) { asm volatile("" ::"v"(f)); }
+__device__ __forceinline__ void pin(int f) { asm volatile("" ::"v"(f)); }
 
 __device__ __forceinline__ f32x16 zero16() {
   f32x16 z;
@@ -139,17 +141,20 @@ __device__ __forceinline__ const void* uniform_ptr(const void* p) {
 
 // Loads 64 rows x 128 bf16 into a swizzled LDS tile: tile row r comes from source row
 // min(row0 + r, rows - 1) of a matrix with row stride `stride_b` bytes (so rows past the end repeat the
-// last valid row); each of the 4 waves moves 16 rows with 4 dma16 instructions.
+// last valid row); each of the NW waves moves 64/NW rows with 16/NW dma16 instructions.
+template <int NW = 4>
 __device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b, int rows, __bf16* tile, int w, int lane,
                                            int row0 = 0) {
+  constexpr int PER = 16 / NW;                       // instructions per wave (4 rows each)
   const int lr = lane >> 4, pc = lane & 15;
   const void* gb = uniform_ptr(gbase);
 #pragma unroll
-  for (int u = 0; u < 4; u++) {
-    const int row = 16 * w + 4 * u + lr;
+  for (int u = 0; u < PER; u++) {
+    const int r4 = PER * w + u;                      // group of 4 rows
+    const int row = 4 * r4 + lr;
     const int rc = min(row0 + row, rows - 1);
-    const int c = pc ^ ((lr << 2) | u);               // = pc ^ swz(row)
-    dma16(gb, (uint32_t)rc * stride_b + (uint32_t)c * 16u, lds_addr_uniform(tile + (16 * w + 4 * u) * TILE_ROW));
+    const int c = pc ^ ((lr << 2) | (r4 & 3));        // = pc ^ swz(row)
+    dma16(gb, (uint32_t)rc * stride_b + (uint32_t)c * 16u, lds_addr_uniform(tile + 4 * r4 * TILE_ROW));
   }
 }
 
