@@ -125,6 +125,7 @@ extern "C" tt_status tt_tree_attn_bwd(const tt_attn_desc* desc, const void* q, c
   c.a.dq = dq; c.a.dk_own = dk_own; c.a.dv_own = dv_own;
   c.a.dk_prefix_acc = dk_prefix_acc; c.a.dv_prefix_acc = dv_prefix_acc;
   c.a.delta = (float*)workspace;
+  c.a.neg_lse2 = nullptr;                      // carved out of the remaining workspace by the MFMA path
   c.a.workspace = (char*)workspace + delta_bytes(desc);
   c.a.workspace_bytes = workspace_bytes - delta_bytes(desc);
   hipStream_t st = (hipStream_t)stream;

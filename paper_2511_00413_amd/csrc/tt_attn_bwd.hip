@@ -28,11 +28,13 @@ constexpr int D = 128;
 constexpr int NTHREADS = 256;
 
 // ------------------------------------------------------------------------------------------------
-// delta[h][i] = sum_d dO[i][h][d] * O[i][h][d]; one wavefront per (token, head) row of 128
+// Per-row terms of the backward pass, stored negated so that the MFMA accumulators can start from them:
+//   neg_delta[h][i] = -sum_d dO[i][h][d] * O[i][h][d]      neg_lse2[h][i] = -lse[h][i] * log2(e)
+// 16 lanes per (token, head) row of 128.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NTHREADS)
-delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, float* __restrict__ delta,
-             int n_q, int hq) {
+delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, const float* __restrict__ lse,
+             float* __restrict__ neg_delta, float* __restrict__ neg_lse2, int n_q, int hq) {
   const int64_t row = (int64_t)blockIdx.x * (NTHREADS / 16) + (threadIdx.x >> 4);   // 16 lanes per row
   const int sub = threadIdx.x & 15;
   float acc = 0.f;
@@ -46,7 +48,8 @@ delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, float
   for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
   if (sub == 0 && row < (int64_t)n_q * hq) {
     const int i = (int)(row / hq), h = (int)(row % hq);
-    delta[(int64_t)h * n_q + i] = acc;
+    neg_delta[(int64_t)h * n_q + i] = -acc;
+    neg_lse2[(int64_t)h * n_q + i] = -lse[(int64_t)h * n_q + i] * LOG2E_F;
   }
 }
 
@@ -102,19 +105,21 @@ __device__ __forceinline__ void q_issue_tile(const QCtx& c, QSmem& sm, int buf, 
 // One key tile of the dQ pass.  FULL: no per-element visibility test, one branch-free block.
 template <bool FULL>
 __device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
-                                        f32x16 (&dq_acc)[4], float c_scale, float lse2, float delta,
+                                        f32x16 (&dq_acc)[4], const f32x16& neg_lse2, const f32x16& neg_delta,
                                         int j0, int j_last, int gi, int a_rd, TrBase t_rd, int hf) {
   const int gi_c = min(gi, j_last);       // causal bound that also hides the rows past the last key
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
     f32x16 s_acc, p_acc;
+    // The accumulators start from -LSE and -delta of the lane's query (and Q carries the softmax
+    // scale), so the MFMA chains deliver the exponent and dP - delta directly.
 #pragma unroll
-    for (int s = 0; s < 8; s++) s_acc = mfma32(lds_row_frag(sm.k[buf], a_rd, kb, s), qf[s], s == 0 ? zero16() : s_acc);
+    for (int s = 0; s < 8; s++) s_acc = mfma32(lds_row_frag(sm.k[buf], a_rd, kb, s), qf[s], s == 0 ? neg_lse2 : s_acc);
 #pragma unroll
-    for (int s = 0; s < 8; s++) p_acc = mfma32(lds_row_frag(sm.v[buf], a_rd, kb, s), gf[s], s == 0 ? zero16() : p_acc);
+    for (int s = 0; s < 8; s++) p_acc = mfma32(lds_row_frag(sm.v[buf], a_rd, kb, s), gf[s], s == 0 ? neg_delta : p_acc);
     // dS^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block)
 #pragma unroll
-    for (int r = 0; r < 16; r++) s_acc[r] = fast_exp2(fmaf(s_acc[r], c_scale, -lse2));
+    for (int r = 0; r < 16; r++) s_acc[r] = fast_exp2(s_acc[r]);
     if (!FULL) {
 #pragma unroll
       for (int r4 = 0; r4 < 4; r4++) {
@@ -128,7 +133,7 @@ __device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (
       }
     }
 #pragma unroll
-    for (int r = 0; r < 16; r++) p_acc[r] = s_acc[r] * (p_acc[r] - delta);
+    for (int r = 0; r < 16; r++) p_acc[r] = s_acc[r] * p_acc[r];
     // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
 #pragma unroll
     for (int t = 0; t < 2; t++) {
@@ -171,9 +176,18 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 #pragma unroll
     for (int s = 0; s < 8; s++) { qf[s] = *(const bf16x8*)(qp + 16 * s); gf[s] = *(const bf16x8*)(gp + 16 * s); }
   }
-  const float lse2 = a.lse[(int64_t)h * N + my_q] * LOG2E_F;
-  const float delta = a.delta[(int64_t)h * N + my_q];
-  const float c_scale = a.scale * LOG2E_F;
+  const float nlse2 = a.neg_lse2[(int64_t)h * N + my_q];
+  const float ndelta = a.delta[(int64_t)h * N + my_q];
+  // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
+  // as the base-2 exponent
+  {
+    const float c_scale = a.scale * LOG2E_F;
+#pragma unroll
+    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
+  }
+  f32x16 neg_lse2, neg_delta;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { neg_lse2[r] = nlse2; neg_delta[r] = ndelta; }
 
   f32x16 dq_acc[4];
 #pragma unroll
@@ -188,8 +202,8 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 
 #pragma unroll
   for (int s = 0; s < 8; s++) { pin(qf[s]); pin(gf[s]); }
-  pin(lse2);
-  pin(delta);
+  pin(neg_lse2);
+  pin(neg_delta);
 
   bool full_cur = false;
   int u_cur = it.next(full_cur);
@@ -206,7 +220,7 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
     bool full_next = false;                                                                             \
     const int u_next = it.next(full_next);                                                              \
     if (u_next >= 0) q_issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                   \
-    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, c_scale, lse2, delta, tile_j0(u_cur), tile_j_last(u_cur), gi, \
+    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, neg_lse2, neg_delta, tile_j0(u_cur), tile_j_last(u_cur), gi, \
                       a_rd, t_rd, hf);                                                                  \
     dma_wait_all();                                                                                     \
     __syncthreads();                                                                                    \
@@ -233,19 +247,28 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 
 }  // namespace
 
+static size_t row_stat_bytes(int n_q, int hq) { return ((size_t)hq * (size_t)n_q * sizeof(float) + 255) & ~(size_t)255; }
+
 size_t mfma_attn_workspace(int n_q, int n_prefix, int hq, int hkv, int d, bool backward) {
   if (!backward) return 0;
-  return mfma_attn_dkdv_workspace(n_q, n_prefix, hkv);
+  return row_stat_bytes(n_q, hq) + mfma_attn_dkdv_workspace(n_q, n_prefix, hkv);
 }
 
-hipError_t mfma_attn_bwd(const AttnArgs& a, hipStream_t st) {
-  if (a.n_q == 0) return hipSuccess;
+hipError_t mfma_attn_bwd(const AttnArgs& args, hipStream_t st) {
+  if (args.n_q == 0) return hipSuccess;
+  // the front of the workspace holds -lse * log2(e); the rest goes to the dK/dV pass
+  AttnArgs a = args;
+  const size_t stat = row_stat_bytes(a.n_q, a.hq);
+  if (a.workspace_bytes < stat) return hipErrorInvalidValue;
+  a.neg_lse2 = (float*)a.workspace;
+  a.workspace = (char*)a.workspace + stat;
+  a.workspace_bytes -= stat;
   {
     const int64_t rows = (int64_t)a.n_q * a.hq;
     const int rows_per_block = NTHREADS / 16;
     KernelTimer timer(TT_KERNEL_ATTN_DELTA, st);
     delta_kernel<<<(unsigned)((rows + rows_per_block - 1) / rows_per_block), NTHREADS, 0, st>>>(
-        (const __bf16*)a.o, (const __bf16*)a.d_o, a.delta, a.n_q, a.hq);
+        (const __bf16*)a.o, (const __bf16*)a.d_o, a.lse, a.delta, a.neg_lse2, a.n_q, a.hq);
     if (hipError_t e = hipGetLastError()) return e;
   }
   if (hipError_t e = mfma_attn_dkdv(a, st)) return e;

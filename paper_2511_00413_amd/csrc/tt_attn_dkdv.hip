@@ -33,8 +33,8 @@ constexpr int KV_NFRAG = 8 + (8 - KV_KREG);
 struct KvSmem {
   __bf16 q[2][KV_BM * TILE_ROW];   // swizzled tiles, filled by asynchronous global -> LDS copies
   __bf16 g[2][KV_BM * TILE_ROW];   // dO
-  float lse[2][KV_BM];             // natural-log LSE of the tile's queries
-  float delta[2][KV_BM];
+  float lse[2][KV_BM];             // -LSE * log2(e) of the tile's queries
+  float delta[2][KV_BM];           // -delta
   // B-operand fragments of this wave's keys that do not fit in registers, private to each lane
   // (lane l of wave w keeps fragment f at [w][f][8 l]): the 8 k-steps of V (dP = dO V^T), then
   // k-steps KV_KREG .. 7 of K
@@ -64,10 +64,10 @@ __device__ __forceinline__ void kv_issue(const AttnArgs& a, KvSmem& sm, int buf,
   const __bf16* gsrc = (const __bf16*)a.d_o + ((int64_t)q0 * a.hq + h) * D;
   dma_tile64<KV_NW>(qsrc, (uint32_t)a.q_stride * 2, rows, sm.q[buf], w, lane);
   dma_tile64<KV_NW>(gsrc, (uint32_t)a.hq * D * 2, rows, sm.g[buf], w, lane);
-  // per-query scalars: LSE by wave 0, delta by wave 1 (rows past the end repeat the last one; such
-  // rows are masked by the boundary test)
+  // per-query terms (-LSE log2 e by wave 0, -delta by wave 1; rows past the end repeat the last one,
+  // such rows are masked by the boundary test)
   if (w < 2) {
-    const float* src = (w == 0 ? a.lse : a.delta) + (int64_t)h * a.n_q + q0;
+    const float* src = (w == 0 ? a.neg_lse2 : a.delta) + (int64_t)h * a.n_q + q0;
     float* dst = w == 0 ? sm.lse[buf] : sm.delta[buf];
     dma4(uniform_ptr(src), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(dst));
   }
@@ -210,7 +210,7 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
   const int c32 = lane & 31, hf = lane >> 5;
   const int G = a.hq / a.hkv;
   const int P = a.n_prefix, N = a.n_q;
-  const float c_scale = a.scale * LOG2E_F;
+  const float c_scale = a.scale * LOG2E_F;     // folded into K: S comes out of the MFMAs as a base-2 exponent
   const int n_work = pl.hdr->n_work;
   const int chunk = pl.hdr->chunk;
 
@@ -279,7 +279,7 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
       const __bf16* vp = is_prefix ? (const __bf16*)a.v_prefix + ((int64_t)krow * a.hkv + kvh) * D
                                    : (const __bf16*)a.v_own + (int64_t)krow * a.v_stride + (int64_t)kvh * D;
 #pragma unroll
-      for (int s = 0; s < KV_KREG; s++) kf[s] = *(const bf16x8*)(kp + 16 * s + 8 * hf);
+      for (int s = 0; s < KV_KREG; s++) kf[s] = scale_frag(*(const bf16x8*)(kp + 16 * s + 8 * hf), c_scale);
 #pragma unroll
       for (int s = 0; s < 8; s++) {
         const bf16x8 vf = *(const bf16x8*)(vp + 16 * s + 8 * hf);
@@ -287,7 +287,7 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
       }
 #pragma unroll
       for (int s = KV_KREG; s < 8; s++) {
-        const bf16x8 kx = *(const bf16x8*)(kp + 16 * s + 8 * hf);
+        const bf16x8 kx = scale_frag(*(const bf16x8*)(kp + 16 * s + 8 * hf), c_scale);
         *(TT_LDS(bf16x8)*)(va + 1024 * (8 + s - KV_KREG)) = kx;
       }
     }
@@ -350,12 +350,26 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
         };
         {
           bf16x8 fq[KV_RING], fg[KV_RING], fv[KV_RING];   // fv doubles as the ring of LDS-resident K fragments
+          // the accumulators start from -LSE log2 e and -delta of their rows' queries, so the MFMA
+          // chains deliver the exponent of P and dP - delta
+#pragma unroll
+          for (int r4 = 0; r4 < 4; r4++) {
+            const f32x4 t = *(TT_LDS(const f32x4)*)(la + qb * 128 + r4 * 32);
+#pragma unroll
+            for (int e = 0; e < 4; e++) s_acc[r4 * 4 + e] = t[e];
+          }
 #pragma unroll
           for (int i = 0; i < KV_RING; i++) fq[i] = lds_b128(ra[i], qo);
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int ss = 0; ss < 8; ss++) {
-            s_acc = mfma32(fq[ss % KV_RING], ss < KV_KREG ? kf[ss < KV_KREG ? ss : 0] : fv[ss % KV_RING], ss == 0 ? zero16() : s_acc);
+            s_acc = mfma32(fq[ss % KV_RING], ss < KV_KREG ? kf[ss < KV_KREG ? ss : 0] : fv[ss % KV_RING], s_acc);
+            if (ss >= 4) {
+              const int r4 = ss - 4;
+              const f32x4 t = *(TT_LDS(const f32x4)*)(la + KV_DELTA_OFF + qb * 128 + r4 * 32);
+#pragma unroll
+              for (int e = 0; e < 4; e++) p_acc[r4 * 4 + e] = t[e];
+            }
             if (ss + KV_RING < 8) {
               fq[ss % KV_RING] = lds_b128(ra[ss + KV_RING], qo);
               if (ss + KV_RING >= KV_KREG) fv[(ss + KV_RING) % KV_RING] = lds_b128(va, 1024 * (8 + ss + KV_RING - KV_KREG));
@@ -368,20 +382,16 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
           }
 #pragma unroll
           for (int ss = 0; ss < 8; ss++) {
-            p_acc = mfma32(fg[ss % KV_RING], fv[ss % KV_RING], ss == 0 ? zero16() : p_acc);
+            p_acc = mfma32(fg[ss % KV_RING], fv[ss % KV_RING], p_acc);
             if (ss + KV_RING < 8) {
               fg[ss % KV_RING] = lds_b128(ra[ss + KV_RING], KV_G_OFF + qo);
               fv[ss % KV_RING] = lds_b128(va, 1024 * (ss + KV_RING));
             } else {
               fc[ss + KV_RING - 8] = read_c(ss + KV_RING - 8);
             }
-            // P = exp2(S c - LSE2) for two accumulator registers per slot, in the MFMA's shadow
-            {
-              const int e0 = 2 * ss;
-              const f32x2 l2 = *(TT_LDS(const f32x2)*)(la + qb * 128 + (e0 >> 2) * 32 + (e0 & 3) * 4) * LOG2E_F;
-              s_acc[e0] = fast_exp2(fmaf(s_acc[e0], c_scale, -l2[0]));
-              s_acc[e0 + 1] = fast_exp2(fmaf(s_acc[e0 + 1], c_scale, -l2[1]));
-            }
+            // P = exp2(exponent) for two accumulator registers per slot, in the MFMA's shadow
+            s_acc[2 * ss] = fast_exp2(s_acc[2 * ss]);
+            s_acc[2 * ss + 1] = fast_exp2(s_acc[2 * ss + 1]);
             __builtin_amdgcn_sched_barrier(0);
           }
         }
@@ -396,7 +406,7 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
               s_acc[r4 * 4 + e] = (jm <= gq && gq < q_lim) ? s_acc[r4 * 4 + e] : 0.f;
             }
         }
-        // dV^T += dO^T P  (8 slots, with dS = P (dP - delta) computed in their shadow), then
+        // dV^T += dO^T P  (8 slots, with dS = P (dP - delta) = P * p_acc computed in their shadow), then
         // dK^T += Q^T dS  (8 slots); rows = queries (r/4)*8 + 4*hf + r%4 inside the block
         {
           bf16x8 pf[2], df[2];
@@ -410,9 +420,8 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
             if (n + KV_RING < 16) fc[n % KV_RING] = read_c(n + KV_RING);
             if (n < 8) {
               const int e0 = 2 * n;
-              const f32x2 dl = *(TT_LDS(const f32x2)*)(la + KV_DELTA_OFF + qb * 128 + (e0 >> 2) * 32 + (e0 & 3) * 4);
-              p_acc[e0] = s_acc[e0] * (p_acc[e0] - dl[0]);
-              p_acc[e0 + 1] = s_acc[e0 + 1] * (p_acc[e0 + 1] - dl[1]);
+              p_acc[e0] = s_acc[e0] * p_acc[e0];
+              p_acc[e0 + 1] = s_acc[e0 + 1] * p_acc[e0 + 1];
               if (n == 2) pf[1] = cvt8(s_acc[8], s_acc[9], s_acc[10], s_acc[11], s_acc[12], s_acc[13], s_acc[14], s_acc[15]);
               if (n == 4) df[0] = cvt8(p_acc[0], p_acc[1], p_acc[2], p_acc[3], p_acc[4], p_acc[5], p_acc[6], p_acc[7]);
             }

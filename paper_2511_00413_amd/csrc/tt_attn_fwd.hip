@@ -72,7 +72,7 @@ __device__ __forceinline__ void issue_tile(const Ctx& c, Smem& sm, int buf, int 
 // compiler can overlap LDS reads, softmax arithmetic and MFMAs.
 template <bool FULL>
 __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
-                                             float& m_run, float& l_run, float c_scale, int j0, int j_last, int gi,
+                                             float& m_run, float& l_run, f32x16& neg_m, int j0, int j_last, int gi,
                                              int k_rd, TrBase v_rd, int hf) {
   f32x16 s_acc[2];
   {
@@ -82,7 +82,7 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
 #pragma unroll
     for (int i = 0; i < 16; i++) kfr[i] = lds_row_frag(sm.k[buf], k_rd, i >> 3, i & 7);
 #pragma unroll
-    for (int i = 0; i < 16; i++) s_acc[i >> 3] = mfma32(kfr[i], qf[i & 7], (i & 7) == 0 ? zero16() : s_acc[i >> 3]);
+    for (int i = 0; i < 16; i++) s_acc[i >> 3] = mfma32(kfr[i], qf[i & 7], (i & 7) == 0 ? neg_m : s_acc[i >> 3]);
     __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // 4 LDS reads
 #pragma unroll
     for (int i = 0; i < 12; i++) {
@@ -109,33 +109,41 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
   }
 
   // ---- online softmax (base 2) ----
+  // Q carries scale * log2(e) and the accumulators started from -m_ref (neg_m), so s_acc already is
+  // the exponent relative to the reference m_ref = m_run (0 while nothing has been seen).  The
+  // reference follows the running maximum lazily: probabilities may exceed 1 by up to
+  // 2^RESCALE_SLACK (harmless in bf16 / fp32), and only when some lane's maximum has grown past that
+  // slack -- or the lane sees its first key -- are reference, scores and output accumulators moved;
+  // after the first few tiles that almost never happens.
   float tmax = s_acc[0][0];
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) tmax = fmaxf(tmax, s_acc[kb][r]);
-  tmax = half_swap_max(tmax) * c_scale;               // c_scale > 0
-  // m_run is the reference the exponentials are taken against.  It follows the running maximum
-  // lazily: probabilities may exceed 1 by up to 2^RESCALE_SLACK (harmless in bf16 / fp32), and only
-  // when some lane's maximum has grown past that slack are the output accumulators rescaled --
-  // after the first few tiles that almost never happens.
-  if (__ballot(tmax > m_run + RESCALE_SLACK) != 0) {
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = m_new == -INFINITY ? 1.f : fast_exp2(m_run - m_new);   // m_run = -inf: alpha = 0
-    m_run = m_new;
-    l_run *= alpha;
+  tmax = half_swap_max(tmax);
+  {
+    const bool unset = m_run == -INFINITY;
+    const bool move = tmax > (unset ? -INFINITY : RESCALE_SLACK);
+    if (__ballot(move) != 0) {
+      const float shift = move ? tmax : 0.f;
+      const float alpha = unset ? 1.f : fast_exp2(-shift);      // nothing accumulated yet: nothing to scale
+      if (move) m_run = (unset ? 0.f : m_run) + shift;
+      l_run *= alpha;
 #pragma unroll
-    for (int db = 0; db < 4; db++)
+      for (int db = 0; db < 4; db++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+        for (int r = 0; r < 16; r++) o_acc[db][r] *= alpha;
+      const float nm = m_run == -INFINITY ? 0.f : -m_run;
+#pragma unroll
+      for (int r = 0; r < 16; r++) { s_acc[0][r] -= shift; s_acc[1][r] -= shift; neg_m[r] = nm; }
+    }
   }
-  const float m_use = m_run == -INFINITY ? 0.f : m_run;   // nothing visible yet: keep everything at 0
   float psum = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      const float p = fast_exp2(fmaf(s_acc[kb][r], c_scale, -m_use));
+      const float p = fast_exp2(s_acc[kb][r]);
       s_acc[kb][r] = p;
       psum += p;
     }
@@ -187,9 +195,16 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   f32x16 o_acc[4];
 #pragma unroll
   for (int db = 0; db < 4; db++) o_acc[db] = zero16();
-  float m_run = -INFINITY;      // running max of scale*log2(e)*s  (shared by the two half-lanes)
+  float m_run = -INFINITY;      // softmax reference in log2 units (shared by the two half-lanes); -inf: no key seen yet
   float l_run = 0.f;            // this lane's part of the running sum (own keys only)
-  const float c_scale = a.scale * LOG2E_F;
+  f32x16 neg_m = zero16();      // -(reference), the value every score accumulator starts from
+  // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
+  // as a base-2 exponent
+  {
+    const float c_scale = a.scale * LOG2E_F;
+#pragma unroll
+    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
+  }
 
   KTileIter it;
   it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
@@ -215,7 +230,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     bool full_next = false;                                                                            \
     const int u_next = it.next(full_next);                                                             \
     if (u_next >= 0) issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                    \
-    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, c_scale, tile_j0(u_cur), tile_j_last(u_cur), gi, \
+    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, neg_m, tile_j0(u_cur), tile_j_last(u_cur), gi,   \
                            k_rd, v_rd, hf);                                                            \
     dma_wait_all();                                                                                    \
     __syncthreads();                                                                                   \

@@ -33,7 +33,8 @@ struct RefArgs {
   float* lse;
   // backward only
   const void* d_o;
-  float* delta;                 // [hq][n_q] workspace: rowsum(dO o O)
+  float* delta;                 // [hq][n_q] workspace: rowsum(dO o O); the MFMA path stores its negation here
+  float* neg_lse2;              // [hq][n_q] MFMA path only: -lse * log2(e)
   void *dq, *dk_own, *dv_own;
   float *dk_prefix_acc, *dv_prefix_acc;
   void* workspace;              // remaining workspace after delta (MFMA path scratch)

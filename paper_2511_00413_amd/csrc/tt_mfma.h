@@ -37,6 +37,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // vmcnt wait would also stall on the prefetch of the next tile).
 __device__ __forceinline__ void pin(const bf16x8& f) { asm volatile("" ::"v"(f)); }
 __device__ __forceinline__ void pin(float f) { asm volatile("" ::"v"(f)); }
+__device__ __forceinline__ void pin(const float __attribute__((ext_vector_type(16)))& f) { asm volatile("" ::"v"(f)); }
 __device__ __forceinline__ void pin(int f) { asm volatile("" ::"v"(f)); }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -77,6 +78,11 @@ __device__ __forceinline__ bf16x8 cvt8(float a0, float a1, float a2, float a3, f
   typedef float f32x8 __attribute__((ext_vector_type(8)));
   f32x8 v = {a0, a1, a2, a3, a4, a5, a6, a7};
   return __builtin_convertvector(v, bf16x8);
+}
+// fragment * c, rounded to bf16 (nearest even)
+__device__ __forceinline__ bf16x8 scale_frag(bf16x8 f, float c) {
+  typedef float f32x8 __attribute__((ext_vector_type(8)));
+  return __builtin_convertvector(__builtin_convertvector(f, f32x8) * c, bf16x8);
 }
 __device__ __forceinline__ bf16x4 cvt4(float a0, float a1, float a2, float a3) {
   f32x4 v = {a0, a1, a2, a3};
