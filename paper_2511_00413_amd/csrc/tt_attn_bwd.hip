@@ -102,29 +102,60 @@ __device__ __forceinline__ void q_issue_tile(const QCtx& c, QSmem& sm, int buf, 
   if (w == 0) dma4(uniform_ptr(ke), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(sm.kend[buf]));
 }
 
-// One key tile of the dQ pass.  FULL: no per-element visibility test, one branch-free block.
+constexpr int Q_STAGE_B = Q_TILE_ELEMS * 2;     // bytes of one staged tile
+constexpr int Q_V_OFF = 2 * Q_STAGE_B;          // k[b] -> v[b]
+constexpr int Q_RING = 3;                       // operand fragments requested ahead of their MFMA
+
+// One key tile of the dQ pass.  FULL: no per-element visibility test.  ra / ta are this lane's
+// fragment addresses in the K tile of the current stage, ka the address of kend[stage][4 hf].
+// Each 32-key block is a sequence of slots -- one MFMA, the LDS read for the MFMA Q_RING slots
+// ahead, a share of the arithmetic -- closed by scheduling fences.
 template <bool FULL>
-__device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
+__device__ __forceinline__ void dq_tile(const uint32_t (&ra)[8], const uint32_t (&ta)[8], uint32_t ka,
+                                        const bf16x8 (&qf)[8], const bf16x8 (&gf)[8],
                                         f32x16 (&dq_acc)[4], const f32x16& neg_lse2, const f32x16& neg_delta,
-                                        int j0, int j_last, int gi, int a_rd, TrBase t_rd, int hf) {
+                                        int j0, int j_last, int gi, int hf) {
   const int gi_c = min(gi, j_last);       // causal bound that also hides the rows past the last key
+  bf16x8 fk[Q_RING], fv[Q_RING], fc[Q_RING];
+  // transposed K fragments of the dQ phase: slot n: k-step t = n / 4 (16 keys), column block db = n % 4
+  auto read_c = [&](int kb, int n) {
+    const int db = n & 3, t = n >> 2;
+    return lds_tr2(ta[2 * db], ta[2 * db + 1], (kb * 32 + 16 * t) * TILE_ROW * 2);
+  };
+#pragma unroll
+  for (int i = 0; i < Q_RING; i++) fk[i] = lds_b128(ra[i], 0);
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
+    const int ko = kb * 32 * TILE_ROW * 2;
     f32x16 s_acc, p_acc;
     // The accumulators start from -LSE and -delta of the lane's query (and Q carries the softmax
     // scale), so the MFMA chains deliver the exponent and dP - delta directly.
 #pragma unroll
-    for (int s = 0; s < 8; s++) s_acc = mfma32(lds_row_frag(sm.k[buf], a_rd, kb, s), qf[s], s == 0 ? neg_lse2 : s_acc);
+    for (int ss = 0; ss < 8; ss++) {
+      s_acc = mfma32(fk[ss % Q_RING], qf[ss], ss == 0 ? neg_lse2 : s_acc);
+      const int nx = ss + Q_RING;
+      if (nx < 8) fk[nx % Q_RING] = lds_b128(ra[nx], ko);
+      else fv[nx - 8] = lds_b128(ra[nx - 8], Q_V_OFF + ko);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
-    for (int s = 0; s < 8; s++) p_acc = mfma32(lds_row_frag(sm.v[buf], a_rd, kb, s), gf[s], s == 0 ? neg_delta : p_acc);
-    // dS^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block)
-#pragma unroll
-    for (int r = 0; r < 16; r++) s_acc[r] = fast_exp2(s_acc[r]);
+    for (int ss = 0; ss < 8; ss++) {
+      p_acc = mfma32(fv[ss % Q_RING], gf[ss], ss == 0 ? neg_delta : p_acc);
+      const int nx = ss + Q_RING;
+      if (nx < 8) fv[nx % Q_RING] = lds_b128(ra[nx], Q_V_OFF + ko);
+      else fc[nx - 8] = read_c(kb, nx - 8);
+      // P^T (rows = keys: (r/4)*8 + 4*hf + r%4 inside the 32-key block), two registers per slot
+      s_acc[2 * ss] = fast_exp2(s_acc[2 * ss]);
+      s_acc[2 * ss + 1] = fast_exp2(s_acc[2 * ss + 1]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (!FULL) {
+      asm volatile("" ::: "memory");
 #pragma unroll
       for (int r4 = 0; r4 < 4; r4++) {
         const int jl = kb * 32 + r4 * 8 + 4 * hf;
-        const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
+        const i32x4 ke = *(TT_LDS(const i32x4)*)(ka + kb * 128 + r4 * 32);
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const int j = j0 + jl + e;
@@ -132,16 +163,24 @@ __device__ __forceinline__ void dq_tile(const QSmem& sm, int buf, const bf16x8 (
         }
       }
     }
+    // dS^T = P^T (dP^T - delta), then dQ^T[d, q] += K^T[d, key] dS^T[key, q]
+    bf16x8 df[2];
 #pragma unroll
-    for (int r = 0; r < 16; r++) p_acc[r] = s_acc[r] * p_acc[r];
-    // dQ^T[d, q] += K^T[d, key] dS^T[key, q]
+    for (int r = 0; r < 8; r++) p_acc[r] = s_acc[r] * p_acc[r];
+    df[0] = cvt8(p_acc[0], p_acc[1], p_acc[2], p_acc[3], p_acc[4], p_acc[5], p_acc[6], p_acc[7]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 2; t++) {
-      const bf16x8 df = cvt8(p_acc[8 * t + 0], p_acc[8 * t + 1], p_acc[8 * t + 2], p_acc[8 * t + 3],
-                             p_acc[8 * t + 4], p_acc[8 * t + 5], p_acc[8 * t + 6], p_acc[8 * t + 7]);
+    for (int n = 0; n < 8; n++) {
+      dq_acc[n & 3] = mfma32(fc[n % Q_RING], df[n >> 2], dq_acc[n & 3]);
+      const int nx = n + Q_RING;
+      if (nx < 8) fc[nx % Q_RING] = read_c(kb, nx);
+      else if (kb == 0) fk[nx - 8] = lds_b128(ra[nx - 8], 32 * TILE_ROW * 2);     // first K fragments of block 1
+      if (n < 2) {
 #pragma unroll
-      for (int db = 0; db < 4; db++)
-        dq_acc[db] = mfma32(lds_tr_frag(sm.k[buf], t_rd, kb * 32 + 16 * t, db), df, dq_acc[db]);
+        for (int r = 8 + 4 * n; r < 12 + 4 * n; r++) p_acc[r] = s_acc[r] * p_acc[r];
+      }
+      if (n == 2) df[1] = cvt8(p_acc[8], p_acc[9], p_acc[10], p_acc[11], p_acc[12], p_acc[13], p_acc[14], p_acc[15]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
@@ -150,7 +189,8 @@ __global__ void __launch_bounds__(NTHREADS, 2)
 tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   QSmem& sm = *reinterpret_cast<QSmem*>(smem_raw);
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c32 = lane & 31, hf = lane >> 5;
   const int G = a.hq / a.hkv;
   const int bid = blockIdx.x;
@@ -212,18 +252,26 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   __syncthreads();
   int buf = 0;
 
-  const int a_rd = row_frag_base(lane);
-  const TrBase t_rd = tr_frag_base(lane);
+  // LDS byte addresses of this lane's fragments in stage `buf` of the K tile; V, the 32-key block and
+  // the k-step rows are immediate offsets, and the addresses move by +-one stage when the stage flips
+  uint32_t ra[8], ta[8];
+  const uint32_t sm_base = (uint32_t)(uintptr_t)&sm;
+  frag_addresses(sm_base, lane, ra, ta);
+  uint32_t ka = sm_base + (uint32_t)offsetof(QSmem, kend) + 16u * hf;
+  int stage_step = Q_STAGE_B, kend_step = Q_BN * 4;
 
 #define TT_DQ_STEP(FULLFLAG)                                                                            \
   {                                                                                                     \
     bool full_next = false;                                                                             \
     const int u_next = it.next(full_next);                                                              \
     if (u_next >= 0) q_issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                   \
-    dq_tile<FULLFLAG>(sm, buf, qf, gf, dq_acc, neg_lse2, neg_delta, tile_j0(u_cur), tile_j_last(u_cur), gi, \
-                      a_rd, t_rd, hf);                                                                  \
+    dq_tile<FULLFLAG>(ra, ta, ka, qf, gf, dq_acc, neg_lse2, neg_delta, tile_j0(u_cur), tile_j_last(u_cur), gi, hf); \
     dma_wait_all();                                                                                     \
     __syncthreads();                                                                                    \
+    _Pragma("unroll") for (int i = 0; i < 8; i++) { ra[i] += stage_step; ta[i] += stage_step; }          \
+    ka += kend_step;                                                                                    \
+    stage_step = -stage_step;                                                                           \
+    kend_step = -kend_step;                                                                             \
     buf ^= 1;                                                                                           \
     u_cur = u_next;                                                                                     \
     full_cur = full_next;                                                                               \

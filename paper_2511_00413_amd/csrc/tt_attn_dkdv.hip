@@ -48,12 +48,6 @@ constexpr int KV_SCALAR_STAGE_B = KV_BM * 4;            // lse[b] -> lse[b ^ 1]
 constexpr int KV_DELTA_OFF = 2 * KV_SCALAR_STAGE_B;     // lse[b] -> delta[b]
 constexpr int KV_RING = 2;                              // operand fragments requested ahead of their MFMA
 
-__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int off) { return *(TT_LDS(const bf16x8)*)(addr + off); }
-__device__ __forceinline__ bf16x8 lds_tr2(uint32_t a0, uint32_t a1, int off) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a0 + off));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a1 + off));
-  return cat4(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi));
-}
 
 // Starts the copy of one (head, query tile) step into stage `buf`.  `lane` should be a value the
 // compiler cannot trace back to the thread index, so that the per-lane source offsets are
@@ -220,17 +214,7 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
   // address per k-step / column block: the permutation is an exclusive-or, not an offset.)
   const uint32_t sm_base = (uint32_t)(uintptr_t)&sm;
   uint32_t ra[8], ta[8];
-  {
-    const int a_rd = row_frag_base(lane);
-    const TrBase t_rd = tr_frag_base(lane);
-#pragma unroll
-    for (int ss = 0; ss < 8; ss++) ra[ss] = sm_base + 2u * (uint32_t)(a_rd ^ (ss << 4));
-#pragma unroll
-    for (int db = 0; db < 4; db++) {
-      ta[2 * db] = sm_base + 2u * (uint32_t)(t_rd.x0 ^ (db << 5));
-      ta[2 * db + 1] = sm_base + 2u * (uint32_t)(t_rd.x1 ^ (db << 5));
-    }
-  }
+  frag_addresses(sm_base, lane, ra, ta);
   uint32_t la = sm_base + (uint32_t)offsetof(KvSmem, lse) + 16u * hf;      // lse[buf][4 hf]
   const uint32_t va = sm_base + (uint32_t)offsetof(KvSmem, frag) + (uint32_t)(KV_NFRAG * 1024) * w + 16u * lane;
   int buf = 0;                                  // stage of the next step; carried across work items
@@ -493,25 +477,44 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
 }
 
 // Sums the partial slots of every key tile that was cut into chunks, in chunk order, and writes the
-// final gradients (own keys: bf16; prefix keys: added to the fp32 accumulators).
-__global__ void __launch_bounds__(NTHREADS)
+// final gradients (own keys: bf16; prefix keys: added to the fp32 accumulators).  One workgroup
+// handles RED_KEYS keys of one (tile, kv head); a thread owns 4 consecutive d of one key.
+constexpr int RED_THREADS = 256;
+constexpr int RED_KEYS = RED_THREADS * 4 / D;        // 8 keys per pass
+constexpr int RED_PASSES = 4;                        // passes per workgroup
+__global__ void __launch_bounds__(RED_THREADS)
 kv_reduce_kernel(AttnArgs a, KvPlan pl) {
-  const int tile = blockIdx.x, kvh = blockIdx.y;
+  constexpr int PARTS = KV_BN / (RED_KEYS * RED_PASSES);
+  const int tile = blockIdx.x / PARTS, part = blockIdx.x % PARTS, kvh = blockIdx.y;
   const int nc = pl.tile_nchunks[tile];
   if (nc <= 1) return;
   const int item0 = pl.tile_item0[tile];
   const bool is_prefix = tile < pl.n_ptiles;
   const int k0 = is_prefix ? tile * KV_BN : (tile - pl.n_ptiles) * KV_BN;
   const int region = is_prefix ? a.n_prefix : a.n_q;
-  for (int u = 0; u < KV_BN * D / 4 / NTHREADS; u++) {
-    const int e = (threadIdx.x + NTHREADS * u) * 4;
+  const int64_t slot_stride = (int64_t)a.hkv * 2 * KV_BN * D;             // floats between consecutive chunks
+  const float* slot0 = pl.slots + ((int64_t)item0 * a.hkv + kvh) * 2 * KV_BN * D;
+#pragma unroll
+  for (int u = 0; u < RED_PASSES; u++) {
+    const int e = ((part * RED_PASSES + u) * RED_THREADS + threadIdx.x) * 4;
     const int key = e / D, d0 = e % D;
     if (k0 + key >= region) continue;
     f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < nc; c++) {
-      const float* base = pl.slots + (((int64_t)(item0 + c) * a.hkv + kvh) * 2) * KV_BN * D + e;
-      sk += *(const f32x4*)base;
-      sv += *(const f32x4*)(base + KV_BN * D);
+    const float* base = slot0 + e;
+    int c = 0;
+    for (; c + 4 <= nc; c += 4) {                      // four chunks in flight; summed in chunk order
+      f32x4 tk[4], tv[4];
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        tk[i] = __builtin_nontemporal_load((const f32x4*)(base + (c + i) * slot_stride));
+        tv[i] = __builtin_nontemporal_load((const f32x4*)(base + (c + i) * slot_stride + KV_BN * D));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; i++) { sk += tk[i]; sv += tv[i]; }
+    }
+    for (; c < nc; c++) {
+      sk += __builtin_nontemporal_load((const f32x4*)(base + c * slot_stride));
+      sv += __builtin_nontemporal_load((const f32x4*)(base + c * slot_stride + KV_BN * D));
     }
     if (is_prefix) {
       if (a.kend[k0 + key] > a.n_prefix) {
@@ -560,7 +563,7 @@ hipError_t mfma_attn_dkdv(const AttnArgs& a, hipStream_t st) {
   }
   {
     KernelTimer timer(TT_KERNEL_ATTN_REDUCE, st);
-    kv_reduce_kernel<<<dim3(pl.n_tiles, a.hkv), NTHREADS, 0, st>>>(a, pl);
+    kv_reduce_kernel<<<dim3(pl.n_tiles * (KV_BN / (RED_KEYS * RED_PASSES)), a.hkv), RED_THREADS, 0, st>>>(a, pl);
     if (hipError_t e = hipGetLastError()) return e;
   }
   return hipSuccess;

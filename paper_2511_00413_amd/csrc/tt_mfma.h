@@ -125,6 +125,29 @@ __device__ __forceinline__ bf16x8 lds_tr_frag(const __bf16* tile, TrBase b, int 
   return cat4(lds_read_tr(p + (b.x0 ^ (db << 5))), lds_read_tr(p + (b.x1 ^ (db << 5))));
 }
 
+// Reads through explicit LDS byte addresses.  A kernel keeps one address per swizzle variant in a
+// register (the swizzle is an exclusive-or, so it cannot be expressed as an offset) and reaches the
+// tile, the row block and the pipeline stage through the immediate offset of the instruction.
+__device__ __forceinline__ bf16x8 lds_b128(uint32_t addr, int off) { return *(TT_LDS(const bf16x8)*)(addr + off); }
+__device__ __forceinline__ bf16x8 lds_tr2(uint32_t a0, uint32_t a1, int off) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a0 + off));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((TT_LDS(s16x4)*)(a1 + off));
+  return cat4(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi));
+}
+// Byte addresses of a lane's operand-row fragments (k-step ss) and transposed fragments (column block
+// db, halves x = 0, 1) inside a swizzled tile that starts at LDS byte address `tile`.
+__device__ __forceinline__ void frag_addresses(uint32_t tile, int lane, uint32_t (&ra)[8], uint32_t (&ta)[8]) {
+  const int a_rd = row_frag_base(lane);
+  const TrBase t_rd = tr_frag_base(lane);
+#pragma unroll
+  for (int ss = 0; ss < 8; ss++) ra[ss] = tile + 2u * (uint32_t)(a_rd ^ (ss << 4));
+#pragma unroll
+  for (int db = 0; db < 4; db++) {
+    ta[2 * db] = tile + 2u * (uint32_t)(t_rd.x0 ^ (db << 5));
+    ta[2 * db + 1] = tile + 2u * (uint32_t)(t_rd.x1 ^ (db << 5));
+  }
+}
+
 // Asynchronous 16-byte-per-lane copy global -> LDS that bypasses the registers: lane l's 16 bytes
 // land at lds_dst + 16*l (lds_dst is wave-uniform), read from gbase + voff (gbase wave-uniform).
 // Completion is tracked by vmcnt; the data is visible to other waves after a wait + barrier.
