@@ -67,38 +67,50 @@ __device__ __forceinline__ void issue_tile(const Ctx& c, Smem& sm, int buf, int 
   if (w == 0) dma4(uniform_ptr(ke), (uint32_t)min(lane, rows - 1) * 4u, lds_addr_uniform(sm.kend[buf]));
 }
 
+constexpr int STAGE_B = TILE_ELEMS * 2;       // bytes of one staged tile
+constexpr int V_OFF = 2 * STAGE_B;            // k[b] -> v[b]
+constexpr int RING = 3;                       // operand fragments requested ahead of their MFMA
+
 // One key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  FULL = every (query, key) pair of the
-// tile is visible: no per-element test, and the whole tile is one branch-free block so that the
-// compiler can overlap LDS reads, softmax arithmetic and MFMAs.
+// tile is visible: no per-element test.  ra / ta are this lane's fragment addresses in the K tile of
+// the current stage, ka the address of kend[stage][4 hf].  The tile is a sequence of slots -- one
+// MFMA, the LDS read for the MFMA RING slots ahead, a share of the softmax arithmetic -- closed by
+// scheduling fences; the exponentials of key step ks + 1 are computed under the MFMAs of step ks.
 template <bool FULL>
-__device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
+__device__ __forceinline__ void process_tile(const uint32_t (&ra)[8], const uint32_t (&ta)[8], uint32_t ka,
+                                             const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
                                              float& m_run, float& l_run, f32x16& neg_m, int j0, int j_last, int gi,
-                                             int k_rd, TrBase v_rd, int hf) {
+                                             int hf) {
   f32x16 s_acc[2];
-  {
-    // all 16 K fragments are requested in program order first; the scheduling groups below keep 4
-    // reads in flight ahead of the MFMA that consumes them
-    bf16x8 kfr[16];
+  bf16x8 fk[RING], fvt[RING];
+  // K fragment of slot i: key block i % 2, k-step i / 2; V^T fragment of slot n: key step n / 4
+  // (16 keys), column block n % 4
+  auto read_k = [&](int i) { return lds_b128(ra[i >> 1], (i & 1) * 32 * TILE_ROW * 2); };
+  auto read_vt = [&](int n) {
+    const int db = n & 3, ks = n >> 2;
+    return lds_tr2(ta[2 * db], ta[2 * db + 1], V_OFF + 16 * ks * TILE_ROW * 2);
+  };
 #pragma unroll
-    for (int i = 0; i < 16; i++) kfr[i] = lds_row_frag(sm.k[buf], k_rd, i >> 3, i & 7);
+  for (int i = 0; i < RING; i++) fk[i] = read_k(i);
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 16; i++) s_acc[i >> 3] = mfma32(kfr[i], qf[i & 7], (i & 7) == 0 ? neg_m : s_acc[i >> 3]);
-    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);          // 4 LDS reads
-#pragma unroll
-    for (int i = 0; i < 12; i++) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // 1 LDS read
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  for (int i = 0; i < 16; i++) {
+    const int kb = i & 1, ss = i >> 1;
+    s_acc[kb] = mfma32(fk[i % RING], qf[ss], ss == 0 ? neg_m : s_acc[kb]);
+    const int nx = i + RING;
+    if (nx < 16) fk[nx % RING] = read_k(nx);
+    else fvt[nx - 16] = read_vt(nx - 16);
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (!FULL) {
+    asm volatile("" ::: "memory");
     const int gi_c = min(gi, j_last);     // causal bound that also hides the rows past the last key
 #pragma unroll
     for (int kb = 0; kb < 2; kb++)
 #pragma unroll
       for (int r4 = 0; r4 < 4; r4++) {
         const int jl = kb * 32 + r4 * 8 + 4 * hf;
-        const i32x4 ke = *(const i32x4*)(&sm.kend[buf][jl]);
+        const i32x4 ke = *(TT_LDS(const i32x4)*)(ka + kb * 128 + r4 * 32);
 #pragma unroll
         for (int e = 0; e < 4; e++) {
           const int j = j0 + jl + e;
@@ -138,33 +150,47 @@ __device__ __forceinline__ void process_tile(const Smem& sm, int buf, const bf16
       for (int r = 0; r < 16; r++) { s_acc[0][r] -= shift; s_acc[1][r] -= shift; neg_m[r] = nm; }
     }
   }
-  float psum = 0.f;
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) {
-      const float p = fast_exp2(s_acc[kb][r]);
-      s_acc[kb][r] = p;
-      psum += p;
-    }
-  l_run += psum;
 
-  // ---- O^T += V^T P^T ----
+  // ---- P = exp2(s), O^T += V^T P^T ----
+  // key step ks covers accumulator registers 8 (ks % 2) .. + 7 of key block ks / 2
+  float psum = 0.f;
+  bf16x8 pf[2];
+  auto exps = [&](int ks, int r0, int cnt) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ks++) {
+    for (int r = 8 * (ks & 1) + r0; r < 8 * (ks & 1) + r0 + cnt; r++) {
+      const float pv = fast_exp2(s_acc[ks >> 1][r]);
+      s_acc[ks >> 1][r] = pv;
+      psum += pv;
+    }
+  };
+  auto pack = [&](int ks) {
     const int kb = ks >> 1, t8 = (ks & 1) * 8;
-    const bf16x8 pf = cvt8(s_acc[kb][t8 + 0], s_acc[kb][t8 + 1], s_acc[kb][t8 + 2], s_acc[kb][t8 + 3],
-                           s_acc[kb][t8 + 4], s_acc[kb][t8 + 5], s_acc[kb][t8 + 6], s_acc[kb][t8 + 7]);
+    return cvt8(s_acc[kb][t8 + 0], s_acc[kb][t8 + 1], s_acc[kb][t8 + 2], s_acc[kb][t8 + 3],
+                s_acc[kb][t8 + 4], s_acc[kb][t8 + 5], s_acc[kb][t8 + 6], s_acc[kb][t8 + 7]);
+  };
+  exps(0, 0, 8);
+  pf[0] = pack(0);
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int db = 0; db < 4; db++) o_acc[db] = mfma32(lds_tr_frag(sm.v[buf], v_rd, 16 * ks, db), pf, o_acc[db]);
+  for (int n = 0; n < 16; n++) {
+    const int ks = n >> 2, db = n & 3;
+    o_acc[db] = mfma32(fvt[n % RING], pf[ks & 1], o_acc[db]);
+    if (n + RING < 16) fvt[(n + RING) % RING] = read_vt(n + RING);
+    if (ks < 3) {
+      exps(ks + 1, 2 * db, 2);
+      if (db == 3) pf[(ks + 1) & 1] = pack(ks + 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+  l_run += psum;
 }
 
 __global__ void __launch_bounds__(NTHREADS, 2)
 tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c32 = lane & 31, hf = lane >> 5;
   const int G = a.hq / a.hkv;
   // consecutive workgroups take different kv heads (they land on different XCDs, so each XCD's L2
@@ -221,8 +247,13 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   __syncthreads();
   int buf = 0;
 
-  const int k_rd = row_frag_base(lane);
-  const TrBase v_rd = tr_frag_base(lane);
+  // LDS byte addresses of this lane's fragments in stage `buf` of the K tile; V, the 32-key block and
+  // the k-step rows are immediate offsets, and the addresses move by +-one stage when the stage flips
+  uint32_t ra[8], ta[8];
+  const uint32_t sm_base = (uint32_t)(uintptr_t)&sm;
+  frag_addresses(sm_base, lane, ra, ta);
+  uint32_t ka = sm_base + (uint32_t)offsetof(Smem, kend) + 16u * hf;
+  int stage_step = STAGE_B, kend_step = BN * 4;
 
   // One pipeline step: start the copy of the next tile, do this tile's math, publish the next tile.
 #define TT_FWD_STEP(FULLFLAG)                                                                          \
@@ -230,10 +261,13 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     bool full_next = false;                                                                            \
     const int u_next = it.next(full_next);                                                             \
     if (u_next >= 0) issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                    \
-    process_tile<FULLFLAG>(sm, buf, qf, o_acc, m_run, l_run, neg_m, tile_j0(u_cur), tile_j_last(u_cur), gi,   \
-                           k_rd, v_rd, hf);                                                            \
+    process_tile<FULLFLAG>(ra, ta, ka, qf, o_acc, m_run, l_run, neg_m, tile_j0(u_cur), tile_j_last(u_cur), gi, hf); \
     dma_wait_all();                                                                                    \
     __syncthreads();                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < 8; i++) { ra[i] += stage_step; ta[i] += stage_step; }         \
+    ka += kend_step;                                                                                   \
+    stage_step = -stage_step;                                                                          \
+    kend_step = -kend_step;                                                                            \
     buf ^= 1;                                                                                          \
     u_cur = u_next;                                                                                    \
     full_cur = full_next;                                                                              \
