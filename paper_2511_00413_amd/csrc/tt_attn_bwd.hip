@@ -64,6 +64,7 @@ struct QSmem {
   __bf16 k[2][Q_TILE_ELEMS];       // swizzled tiles, filled by asynchronous global -> LDS copies
   __bf16 v[2][Q_TILE_ELEMS];
   int32_t kend[2][Q_BN];
+  KTileMasks masks;
 };
 
 struct QCtx {
@@ -218,39 +219,15 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   }
   const float nlse2 = a.neg_lse2[(int64_t)h * N + my_q];
   const float ndelta = a.delta[(int64_t)h * N + my_q];
-  // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
-  // as the base-2 exponent
-  {
-    const float c_scale = a.scale * LOG2E_F;
-#pragma unroll
-    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
-  }
-  f32x16 neg_lse2, neg_delta;
-#pragma unroll
-  for (int r = 0; r < 16; r++) { neg_lse2[r] = nlse2; neg_delta[r] = ndelta; }
 
   f32x16 dq_acc[4];
 #pragma unroll
   for (int db = 0; db < 4; db++) dq_acc[db] = zero16();
 
-  KTileIter it;
-  it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * Q_BN : P + (u - npt) * Q_BN; };
   auto tile_j_last = [&](int u) {
     return u < npt ? min(u * Q_BN + Q_BN, P) - 1 : P + min((u - npt) * Q_BN + Q_BN, N) - 1;
   };
-
-#pragma unroll
-  for (int s = 0; s < 8; s++) { pin(qf[s]); pin(gf[s]); }
-  pin(neg_lse2);
-  pin(neg_delta);
-
-  bool full_cur = false;
-  int u_cur = it.next(full_cur);
-  if (u_cur >= 0) q_issue_tile(ctx, sm, 0, u_cur, w, lane);
-  dma_wait_all();
-  __syncthreads();
-  int buf = 0;
 
   // LDS byte addresses of this lane's fragments in stage `buf` of the K tile; V, the 32-key block and
   // the k-step rows are immediate offsets, and the addresses move by +-one stage when the stage flips
@@ -259,6 +236,7 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   frag_addresses(sm_base, lane, ra, ta);
   uint32_t ka = sm_base + (uint32_t)offsetof(QSmem, kend) + 16u * hf;
   int stage_step = Q_STAGE_B, kend_step = Q_BN * 4;
+  int buf = 0;
 
 #define TT_DQ_STEP(FULLFLAG)                                                                            \
   {                                                                                                     \
@@ -276,8 +254,40 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
     u_cur = u_next;                                                                                     \
     full_cur = full_next;                                                                               \
   }
-  while (u_cur >= 0 && full_cur) TT_DQ_STEP(true)
-  while (u_cur >= 0) TT_DQ_STEP(false)
+  // candidate tiles are classified in chunks of 64 *   // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
+  // longer than 262144 keys)
+  KTileIter it;
+  it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
+  // the first tile's copy is started before anything waits for the per-query operands, so that the
+  // memory round trips of the prologue (Q / dO / row terms, tile summaries, first tile) overlap
+  bool full_cur = false;
+  int u_cur = it.next(full_cur);
+  if (u_cur >= 0) q_issue_tile(ctx, sm, buf, u_cur, w, lane);
+  // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
+  // as the base-2 exponent
+  {
+    const float c_scale = a.scale * LOG2E_F;
+#pragma unroll
+    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
+  }
+  f32x16 neg_lse2, neg_delta;
+#pragma unroll
+  for (int r = 0; r < 16; r++) { neg_lse2[r] = nlse2; neg_delta[r] = ndelta; }
+#pragma unroll
+  for (int s = 0; s < 8; s++) { pin(qf[s]); pin(gf[s]); }
+  pin(neg_lse2);
+  pin(neg_delta);
+  for (int tile0 = 0;;) {
+    dma_wait_all();
+    __syncthreads();
+    while (u_cur >= 0 && full_cur) TT_DQ_STEP(true)
+    while (u_cur >= 0) TT_DQ_STEP(false)
+    tile0 += 64 * KT_MAX_WIN;
+    if (tile0 >= u_end) break;
+    it.fill(&sm.masks, a.kt_max, a.kt_min, tile0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
+    u_cur = it.next(full_cur);
+    if (u_cur >= 0) q_issue_tile(ctx, sm, buf, u_cur, w, lane);
+  }
 #undef TT_DQ_STEP
 
   if (q < N) {

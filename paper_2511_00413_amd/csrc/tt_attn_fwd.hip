@@ -29,6 +29,7 @@ struct Smem {
   __bf16 k[2][TILE_ELEMS];
   __bf16 v[2][TILE_ELEMS];
   int32_t kend[2][BN];
+  KTileMasks masks;
 };
 
 struct Ctx {
@@ -224,28 +225,9 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   float m_run = -INFINITY;      // softmax reference in log2 units (shared by the two half-lanes); -inf: no key seen yet
   float l_run = 0.f;            // this lane's part of the running sum (own keys only)
   f32x16 neg_m = zero16();      // -(reference), the value every score accumulator starts from
-  // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
-  // as a base-2 exponent
-  {
-    const float c_scale = a.scale * LOG2E_F;
-#pragma unroll
-    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
-  }
 
-  KTileIter it;
-  it.init(a.kt_max, a.kt_min, u_end, gi_first, gi_last, npt, P, N);
   auto tile_j0 = [&](int u) { return u < npt ? u * BN : P + (u - npt) * BN; };
   auto tile_j_last = [&](int u) { return u < npt ? min(u * BN + BN, P) - 1 : P + min((u - npt) * BN + BN, N) - 1; };
-
-#pragma unroll
-  for (int s = 0; s < 8; s++) pin(qf[s]);
-
-  bool full_cur = false;
-  int u_cur = it.next(full_cur);
-  if (u_cur >= 0) issue_tile(ctx, sm, 0, u_cur, w, lane);
-  dma_wait_all();
-  __syncthreads();
-  int buf = 0;
 
   // LDS byte addresses of this lane's fragments in stage `buf` of the K tile; V, the 32-key block and
   // the k-step rows are immediate offsets, and the addresses move by +-one stage when the stage flips
@@ -254,6 +236,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   frag_addresses(sm_base, lane, ra, ta);
   uint32_t ka = sm_base + (uint32_t)offsetof(Smem, kend) + 16u * hf;
   int stage_step = STAGE_B, kend_step = BN * 4;
+  int buf = 0;
 
   // One pipeline step: start the copy of the next tile, do this tile's math, publish the next tile.
 #define TT_FWD_STEP(FULLFLAG)                                                                          \
@@ -272,8 +255,35 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     u_cur = u_next;                                                                                    \
     full_cur = full_next;                                                                              \
   }
-  while (u_cur >= 0 && full_cur) TT_FWD_STEP(true)
-  while (u_cur >= 0) TT_FWD_STEP(false)
+  // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
+  // longer than 262144 keys)
+  KTileIter it;
+  it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
+  // the first tile's copy is started before anything waits for the Q fragments, so that the memory
+  // round trips of the prologue (Q, tile summaries, first tile) overlap
+  bool full_cur = false;
+  int u_cur = it.next(full_cur);
+  if (u_cur >= 0) issue_tile(ctx, sm, buf, u_cur, w, lane);
+  {
+    // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the
+    // MFMAs as a base-2 exponent
+    const float c_scale = a.scale * LOG2E_F;
+#pragma unroll
+    for (int s = 0; s < 8; s++) qf[s] = scale_frag(qf[s], c_scale);
+#pragma unroll
+    for (int s = 0; s < 8; s++) pin(qf[s]);
+  }
+  for (int tile0 = 0;;) {
+    dma_wait_all();
+    __syncthreads();
+    while (u_cur >= 0 && full_cur) TT_FWD_STEP(true)
+    while (u_cur >= 0) TT_FWD_STEP(false)
+    tile0 += 64 * KT_MAX_WIN;
+    if (tile0 >= u_end) break;
+    it.fill(&sm.masks, a.kt_max, a.kt_min, tile0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
+    u_cur = it.next(full_cur);
+    if (u_cur >= 0) issue_tile(ctx, sm, buf, u_cur, w, lane);
+  }
 #undef TT_FWD_STEP
 
   // ---- epilogue ----

@@ -193,41 +193,59 @@ __device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b,
 // is visible ("full": all 64 keys exist, all lie at or before the first query, and the smallest
 // bound lies beyond the last query) are delivered first, then the tiles that need the per-element
 // test -- softmax accumulation does not care about the order, and the two kinds run in separate
-// branch-free loops.  64 tiles are classified per step with one wavefront-wide load + ballot;
-// every wavefront of the workgroup walks the same sequence.
+// branch-free loops.
+//
+// The classification is done up front, once per chunk of KT_MAX_WIN * 64 tiles: the waves of the
+// workgroup share the windows of 64 tiles, classify each with one wavefront-wide pair of loads + two
+// ballots, and leave the two bit masks in LDS; next() only reads those masks, so the tile loops hold
+// no global load.  Every wavefront walks the same sequence.
+constexpr int KT_MAX_WIN = 64;
+struct KTileMasks { uint64_t m[2][KT_MAX_WIN]; };       // [0]: full tiles, [1]: boundary tiles
 struct KTileIter {
-  const int32_t *kt_max, *kt_min;
-  int u_end;        // one past the last candidate tile
-  int gi_first, gi_last;
-  int npt, P, N;    // prefix tiles, prefix keys, own keys
-  int base;         // next window start
+  const KTileMasks* masks;
+  int tile0;        // first tile of the chunk
+  int n_win;        // windows in the chunk
+  int win;          // next window
   int phase;        // 0: full tiles, 1: boundary tiles
-  uint64_t mask;    // undelivered tiles of the current window [base-64, base)
-  __device__ __forceinline__ void init(const int32_t* kt_max_, const int32_t* kt_min_, int u_end_, int gi_first_,
-                                       int gi_last_, int npt_, int P_, int N_) {
-    kt_max = kt_max_; kt_min = kt_min_; u_end = u_end_; gi_first = gi_first_; gi_last = gi_last_;
-    npt = npt_; P = P_; N = N_; base = 0; phase = 0; mask = 0;
+  uint64_t mask;    // undelivered tiles of the current window
+  // Classifies tiles [tile0, min(u_end, tile0 + 64 KT_MAX_WIN)); all waves of the workgroup call it
+  // (it contains a barrier); nw = waves per workgroup, w = this wave.
+  __device__ __forceinline__ void fill(KTileMasks* lds, const int32_t* kt_max, const int32_t* kt_min, int tile0_,
+                                       int u_end, int gi_first, int gi_last, int npt, int P, int N, int w, int nw) {
+    masks = lds; tile0 = tile0_; win = 0; phase = 0; mask = 0;
+    n_win = min(KT_MAX_WIN, (u_end - tile0 + 63) >> 6);
+    const int lane = (int)(threadIdx.x & 63);
+    for (int wi = w; wi < n_win; wi += nw) {
+      const int u = tile0 + wi * 64 + lane;
+      const bool in = u < u_end;
+      const int kmx = kt_max[in ? u : 0], kmn = kt_min[in ? u : 0];     // both loads in flight together
+      const int j0 = u < npt ? u * 64 : P + (u - npt) * 64;
+      const int rows = u < npt ? P - u * 64 : N - (u - npt) * 64;
+      const bool cand = in && kmx > gi_first;
+      const bool full = cand && rows >= 64 && j0 + 63 <= gi_first && kmn > gi_last;
+      const uint64_t mf = __ballot(full), mb = __ballot(cand && !full);
+      if (lane == 0) { lds->m[0][wi] = mf; lds->m[1][wi] = mb; }
+    }
+    __syncthreads();
   }
   // returns the next tile or -1; is_full tells which kind it is
   __device__ __forceinline__ int next(bool& is_full) {
     while (mask == 0) {
-      if (base >= u_end) {
+      if (win >= n_win) {
         if (phase == 1) return -1;
-        phase = 1; base = 0;
+        phase = 1; win = 0;
       }
-      const int u = base + (int)(threadIdx.x & 63);
-      const bool in = u < u_end;
-      const int j0 = u < npt ? u * 64 : P + (u - npt) * 64;
-      const int rows = u < npt ? P - u * 64 : N - (u - npt) * 64;
-      const bool cand = in && kt_max[in ? u : 0] > gi_first;
-      const bool full = cand && rows >= 64 && j0 + 63 <= gi_first && kt_min[in ? u : 0] > gi_last;
-      mask = __ballot(phase == 0 ? full : (cand && !full));
-      base += 64;
+      const uint64_t m = masks->m[phase][win];
+      // (the builtin returns a signed int: without the casts the low half would be sign-extended)
+      const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)m);
+      const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(m >> 32));
+      mask = ((uint64_t)hi << 32) | lo;
+      win++;
     }
     const int b = __builtin_ctzll(mask);
     mask &= mask - 1;
     is_full = phase == 0;
-    return base - 64 + b;
+    return tile0 + (win - 1) * 64 + b;
   }
 };
 
