@@ -73,7 +73,7 @@ __device__ __forceinline__ void kv_issue(const AttnArgs& a, KvSmem& sm, int buf,
 // chunks of at most `chunk` steps; a planner kernel sizes the chunks so that the launch has about
 // KV_TARGET_WORK work items, workgroups pull items from a counter, and tiles that were cut have
 // their fp32 partial results summed in chunk order by a reduce kernel (bit-reproducible).
-constexpr int KV_TARGET_WORK = 1024;     // work items (tile chunk x kv head) aimed for
+constexpr int KV_TARGET_WORK = 768;      // work items (tile chunk x kv head) aimed for
 constexpr int KV_MIN_CHUNK = 32;         // steps
 constexpr int PLAN_THREADS = 1024;
 
