@@ -240,10 +240,11 @@ def main():
         G = dims.hq // dims.hkv
         if cfg in (1, 2):
             t0c = time.perf_counter()
-            OA.branches(om, q.float().cpu(), k.float().cpu(), v.float().cpu(), do.float().cpu(), kv_heads=[0])
+            n_groups = min(dims.hkv, 4)          # about 10 s of host time at config 2
+            OA.branches(om, q.float().cpu(), k.float().cpu(), v.float().cpu(), do.float().cpu(), kv_heads=list(range(n_groups)))
             dtc = time.perf_counter() - t0c
-            cpu_flop = 14.0 * G * dims.d * pairs
-            sample = "per-branch oracle, fwd+bwd, all branches, kv head group 0 of %d (%d query heads)" % (dims.hkv, G)
+            cpu_flop = 14.0 * G * n_groups * dims.d * pairs
+            sample = "per-branch oracle, fwd+bwd, all branches, kv head groups 0..%d of %d (%d query heads)" % (n_groups - 1, dims.hkv, G * n_groups)
         else:
             # a slice of rows of the deepest leaf: same arithmetic, bounded time
             rows = list(range(N - 96, N))
