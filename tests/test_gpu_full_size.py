@@ -136,3 +136,29 @@ def test_cfg5_partition_step_sampled():
     dv_sum = (got["dv"].float().sum(dim=0) + got["dvp"].sum(dim=0)).cpu().numpy()
     do_sum = do.float().view(n, dims.hkv, G, dims.d).sum(dim=(0, 2)).numpy()
     assert rel_l2(dv_sum, do_sum) <= 2e-2
+
+
+def test_more_than_4096_key_tiles():
+    """A sequence longer than 4096 key tiles (262144 keys): the forward / dQ kernels classify their
+    candidate tiles in several chunks, and the dK/dV planner cuts the long visible ranges."""
+    # trunk, two leaves below it, then a second root whose queries skip every earlier tile
+    parent = np.array([-1, 0, 0, -1], dtype=np.int32)
+    seg = np.array([255000, 6100, 4037, 1500], dtype=np.int32)
+    tree = W.Tree(parent=parent, seg_len=seg, trained=np.ones(4, dtype=np.uint8), name="long-trunk")
+    dims = W.AttnDims(2, 1, 128, "bf16", 0.5)
+    meta = T.tree_build_meta(tree.parent, tree.seg_len, tree.trained)
+    om = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = meta.n_tokens
+    assert n > 4096 * 64
+    print(f"[case] long trunk N={n}", flush=True)
+    q, k, v, do = W.attn_inputs(n, n, dims, 77)
+    got = _run_gpu(meta, q, k, v, do)
+    qf, kf, vf, dof = q.float(), k.float(), v.float(), do.float()
+    ns, ne = om["node_start"], om["node_end"]
+    rows = sorted({0, 4096 * 64 - 1, 4096 * 64, int(ne[0]) - 1, int(ns[1]) + 7, int(ne[1]) - 1, int(ns[2]), int(ne[2]) - 1,
+                   int(ns[3]), n - 1})
+    keys = [int(ne[1]) - 1, int(ne[2]) - 3, int(ns[3]), n - 1]        # few queries see these
+    _sample_check(om, got, qf, kf, vf, dof, 0, rows, keys, 2)
+    dv_sum = got["dv"].float().sum(dim=0).cpu().numpy()
+    do_sum = do.float().view(n, 1, 2, dims.d).sum(dim=(0, 2)).numpy()
+    assert rel_l2(dv_sum, do_sum) <= 2e-2
