@@ -81,7 +81,7 @@ template <bool FULL>
 __device__ __forceinline__ void process_tile(const uint32_t (&ra)[8], const uint32_t (&ta)[8], uint32_t ka,
                                              const bf16x8 (&qf)[8], f32x16 (&o_acc)[4],
                                              float& m_run, float& l_run, f32x16& neg_m, int j0, int j_last, int gi,
-                                             int hf) {
+                                             int hf, int cls) {
   f32x16 s_acc[2];
   bf16x8 fk[RING], fvt[RING];
   // K fragment of slot i: key block i % 2, k-step i / 2; V^T fragment of slot n: key step n / 4
@@ -104,21 +104,42 @@ __device__ __forceinline__ void process_tile(const uint32_t (&ra)[8], const uint
     __builtin_amdgcn_sched_barrier(0);
   }
   if (!FULL) {
+    // cls (wave-uniform) says which of the two tests the tile needs; most boundary tiles need one
     asm volatile("" ::: "memory");
     const int gi_c = min(gi, j_last);     // causal bound that also hides the rows past the last key
+    if (cls == KT_NEED_KEND) {
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++)
+      for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; r4++) {
-        const int jl = kb * 32 + r4 * 8 + 4 * hf;
-        const i32x4 ke = *(TT_LDS(const i32x4)*)(ka + kb * 128 + r4 * 32);
+        for (int r4 = 0; r4 < 4; r4++) {
+          const i32x4 ke = *(TT_LDS(const i32x4)*)(ka + kb * 128 + r4 * 32);
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
-          const int j = j0 + jl + e;
-          const bool vis = j <= gi_c && gi < ke[e];
-          s_acc[kb][r4 * 4 + e] = vis ? s_acc[kb][r4 * 4 + e] : -INFINITY;
+          for (int e = 0; e < 4; e++) s_acc[kb][r4 * 4 + e] = gi < ke[e] ? s_acc[kb][r4 * 4 + e] : -INFINITY;
         }
-      }
+    } else if (cls == KT_NEED_CAUSAL) {
+      const int rel = gi_c - j0;          // keys 0 .. rel of the tile are visible
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++)
+#pragma unroll
+          for (int e = 0; e < 4; e++)
+            s_acc[kb][r4 * 4 + e] = kb * 32 + r4 * 8 + 4 * hf + e <= rel ? s_acc[kb][r4 * 4 + e] : -INFINITY;
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++) {
+          const int jl = kb * 32 + r4 * 8 + 4 * hf;
+          const i32x4 ke = *(TT_LDS(const i32x4)*)(ka + kb * 128 + r4 * 32);
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const int j = j0 + jl + e;
+            const bool vis = j <= gi_c && gi < ke[e];
+            s_acc[kb][r4 * 4 + e] = vis ? s_acc[kb][r4 * 4 + e] : -INFINITY;
+          }
+        }
+    }
   }
 
   // ---- online softmax (base 2) ----
@@ -241,10 +262,10 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   // One pipeline step: start the copy of the next tile, do this tile's math, publish the next tile.
 #define TT_FWD_STEP(FULLFLAG)                                                                          \
   {                                                                                                    \
-    bool full_next = false;                                                                            \
-    const int u_next = it.next(full_next);                                                             \
+    int cls_next = KT_FULL;                                                                            \
+    const int u_next = it.next(cls_next);                                                              \
     if (u_next >= 0) issue_tile(ctx, sm, buf ^ 1, u_next, w, lane);                                    \
-    process_tile<FULLFLAG>(ra, ta, ka, qf, o_acc, m_run, l_run, neg_m, tile_j0(u_cur), tile_j_last(u_cur), gi, hf); \
+    process_tile<FULLFLAG>(ra, ta, ka, qf, o_acc, m_run, l_run, neg_m, tile_j0(u_cur), tile_j_last(u_cur), gi, hf, cls_cur); \
     dma_wait_all();                                                                                    \
     __syncthreads();                                                                                   \
     _Pragma("unroll") for (int i = 0; i < 8; i++) { ra[i] += stage_step; ta[i] += stage_step; }         \
@@ -253,7 +274,7 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
     kend_step = -kend_step;                                                                            \
     buf ^= 1;                                                                                          \
     u_cur = u_next;                                                                                    \
-    full_cur = full_next;                                                                              \
+    cls_cur = cls_next;                                                                                \
   }
   // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
   // longer than 262144 keys)
@@ -261,8 +282,8 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
   // the first tile's copy is started before anything waits for the Q fragments, so that the memory
   // round trips of the prologue (Q, tile summaries, first tile) overlap
-  bool full_cur = false;
-  int u_cur = it.next(full_cur);
+  int cls_cur = KT_FULL;
+  int u_cur = it.next(cls_cur);
   if (u_cur >= 0) issue_tile(ctx, sm, buf, u_cur, w, lane);
   {
     // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the
@@ -276,12 +297,12 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   for (int tile0 = 0;;) {
     dma_wait_all();
     __syncthreads();
-    while (u_cur >= 0 && full_cur) TT_FWD_STEP(true)
+    while (u_cur >= 0 && cls_cur == KT_FULL) TT_FWD_STEP(true)
     while (u_cur >= 0) TT_FWD_STEP(false)
     tile0 += 64 * KT_MAX_WIN;
     if (tile0 >= u_end) break;
     it.fill(&sm.masks, a.kt_max, a.kt_min, tile0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
-    u_cur = it.next(full_cur);
+    u_cur = it.next(cls_cur);
     if (u_cur >= 0) issue_tile(ctx, sm, buf, u_cur, w, lane);
   }
 #undef TT_FWD_STEP

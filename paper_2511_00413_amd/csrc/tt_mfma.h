@@ -200,7 +200,9 @@ __device__ __forceinline__ void dma_tile64(const void* gbase, uint32_t stride_b,
 // ballots, and leave the two bit masks in LDS; next() only reads those masks, so the tile loops hold
 // no global load.  Every wavefront walks the same sequence.
 constexpr int KT_MAX_WIN = 64;
-struct KTileMasks { uint64_t m[2][KT_MAX_WIN]; };       // [0]: full tiles, [1]: boundary tiles
+// Class of a candidate tile: which per-element tests it needs (0 = none: a full tile).
+enum : int { KT_FULL = 0, KT_NEED_KEND = 1, KT_NEED_CAUSAL = 2 };
+struct KTileMasks { uint64_t m[4][KT_MAX_WIN]; };       // [0] full, [1] boundary, [2] boundary needing the kend test, [3] ... the causal test
 struct KTileIter {
   const KTileMasks* masks;
   int tile0;        // first tile of the chunk
@@ -208,11 +210,12 @@ struct KTileIter {
   int win;          // next window
   int phase;        // 0: full tiles, 1: boundary tiles
   uint64_t mask;    // undelivered tiles of the current window
+  uint64_t m_kend, m_causal;   // test bits of the current window (boundary phase)
   // Classifies tiles [tile0, min(u_end, tile0 + 64 KT_MAX_WIN)); all waves of the workgroup call it
   // (it contains a barrier); nw = waves per workgroup, w = this wave.
   __device__ __forceinline__ void fill(KTileMasks* lds, const int32_t* kt_max, const int32_t* kt_min, int tile0_,
                                        int u_end, int gi_first, int gi_last, int npt, int P, int N, int w, int nw) {
-    masks = lds; tile0 = tile0_; win = 0; phase = 0; mask = 0;
+    masks = lds; tile0 = tile0_; win = 0; phase = 0; mask = 0; m_kend = 0; m_causal = 0;
     n_win = min(KT_MAX_WIN, (u_end - tile0 + 63) >> 6);
     const int lane = (int)(threadIdx.x & 63);
     for (int wi = w; wi < n_win; wi += nw) {
@@ -222,29 +225,38 @@ struct KTileIter {
       const int j0 = u < npt ? u * 64 : P + (u - npt) * 64;
       const int rows = u < npt ? P - u * 64 : N - (u - npt) * 64;
       const bool cand = in && kmx > gi_first;
-      const bool full = cand && rows >= 64 && j0 + 63 <= gi_first && kmn > gi_last;
-      const uint64_t mf = __ballot(full), mb = __ballot(cand && !full);
-      if (lane == 0) { lds->m[0][wi] = mf; lds->m[1][wi] = mb; }
+      // the causal test also hides the rows past the last key of a ragged tile
+      const bool need_causal = cand && !(rows >= 64 && j0 + 63 <= gi_first);
+      const bool need_kend = cand && !(kmn > gi_last);
+      const bool full = cand && !need_causal && !need_kend;
+      const uint64_t mf = __ballot(full), mb = __ballot(cand && !full), mk = __ballot(need_kend), mc = __ballot(need_causal);
+      if (lane == 0) { lds->m[0][wi] = mf; lds->m[1][wi] = mb; lds->m[2][wi] = mk; lds->m[3][wi] = mc; }
     }
     __syncthreads();
   }
-  // returns the next tile or -1; is_full tells which kind it is
-  __device__ __forceinline__ int next(bool& is_full) {
+  __device__ static __forceinline__ uint64_t uniform64(uint64_t m) {
+    // (the builtin returns a signed int: without the casts the low half would be sign-extended)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)m);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(m >> 32));
+    return ((uint64_t)hi << 32) | lo;
+  }
+  // returns the next tile or -1; cls tells which tests it needs (KT_FULL: none)
+  __device__ __forceinline__ int next(int& cls) {
     while (mask == 0) {
       if (win >= n_win) {
         if (phase == 1) return -1;
         phase = 1; win = 0;
       }
-      const uint64_t m = masks->m[phase][win];
-      // (the builtin returns a signed int: without the casts the low half would be sign-extended)
-      const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)m);
-      const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(m >> 32));
-      mask = ((uint64_t)hi << 32) | lo;
+      mask = uniform64(masks->m[phase][win]);
+      if (phase == 1) {
+        m_kend = uniform64(masks->m[2][win]);
+        m_causal = uniform64(masks->m[3][win]);
+      }
       win++;
     }
     const int b = __builtin_ctzll(mask);
     mask &= mask - 1;
-    is_full = phase == 0;
+    cls = phase == 0 ? KT_FULL : (int)((m_kend >> b) & 1) * KT_NEED_KEND + (int)((m_causal >> b) & 1) * KT_NEED_CAUSAL;
     return tile0 + (win - 1) * 64 + b;
   }
 };
