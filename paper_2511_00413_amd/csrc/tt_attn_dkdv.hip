@@ -68,28 +68,41 @@ __device__ __forceinline__ void kv_issue(const AttnArgs& a, KvSmem& sm, int buf,
 }
 
 // ---- work decomposition -------------------------------------------------------------------------
-// A key tile's work is its list of (query head, query tile) steps.  Tiles near the root of the tree
-// are seen by almost every query while leaf tiles are seen by few, so a tile's steps are cut into
-// chunks of at most `chunk` steps; a planner kernel sizes the chunks so that the launch has about
-// KV_TARGET_WORK work items, workgroups pull items from a counter, and tiles that were cut have
-// their fp32 partial results summed in chunk order by a reduce kernel (bit-reproducible).
+// Key tiles.  A workgroup works on up to KV_BN consecutive keys and walks the (query head, query
+// tile) steps of every query tile that can see one of them, so keys with different visibility ranges
+// in one tile leave wavefronts idle.  In DFS order the keys of a tree node are consecutive and share
+// their range; the planner therefore forms tiles from runs of consecutive 64-key summary entries with
+// the same largest bound (kt_max), at most KV_BN / 64 entries per tile, instead of cutting the key
+// axis at fixed multiples of KV_BN.
+//
+// Work items.  A tile's work is its list of steps.  Tiles near the root of the tree are seen by
+// almost every query while leaf tiles are seen by few, so a tile's steps are cut into chunks of at
+// most `chunk` steps; the planner sizes the chunks so that the launch has about KV_TARGET_WORK work
+// items, workgroups pull items from a counter, and tiles that were cut have their fp32 partial
+// results summed in chunk order by a reduce kernel (bit-reproducible).
 constexpr int KV_TARGET_WORK = 768;      // work items (tile chunk x kv head) aimed for
 constexpr int KV_MIN_CHUNK = 32;         // steps
 constexpr int PLAN_THREADS = 1024;
+constexpr int KV_EPT = KV_BN / 64;       // summary entries per key tile, at most
 
 struct KvPlanHeader {
   int n_work;        // work items = n_items * hkv
   int counter;       // next work item to hand out
   int chunk;         // steps per chunk
   int n_split_items; // items [0, n_split_items) write partial slots (slot index = item index)
+  int n_tiles;       // key tiles formed
+  int n_split_tiles; // tiles cut into more than one chunk (listed in split_tile)
 };
 
 struct KvPlan {                // device pointers into the workspace
   KvPlanHeader* hdr;
-  int *tile_nq, *tile_qtlo, *tile_nchunks, *tile_item0;   // [n_tiles]
+  int *tile_e0, *tile_ne;                                 // [max_tiles] first summary entry, entries (64 keys each)
+  int *tile_nq, *tile_qtlo, *tile_nchunks, *tile_item0;   // [max_tiles]
   int *item_tile, *item_chunk;                            // [max_items]
+  int* split_tile;                                        // [max_split_tiles]
   float* slots;                                           // [max_slots][hkv][2][KV_BN][D]
-  int n_tiles, n_ptiles, max_items, max_slots;
+  int np64, no64;                                         // summary entries of the prefix / own region
+  int max_tiles, max_items, max_slots, max_split_tiles;
 };
 
 __host__ __device__ inline int kv_target_items(int hkv) { return (KV_TARGET_WORK + hkv - 1) / hkv; }
@@ -97,101 +110,139 @@ __host__ __device__ inline int kv_target_items(int hkv) { return (KV_TARGET_WORK
 __host__ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Carves the plan out of `base`; with base == nullptr only the size is computed.
+// Bounds: every tile holds at least one summary entry, so there are at most np64 + no64 tiles; a
+// tile that is cut has more than `chunk` steps and the steps of one kv head sum to at most
+// chunk * kv_target_items, so at most kv_target_items tiles are cut, into at most
+// 2 * kv_target_items chunks.
 __host__ inline size_t kv_plan_layout(void* base, int n_q, int n_prefix, int hkv, KvPlan* out) {
-  const int n_ptiles = (n_prefix + KV_BN - 1) / KV_BN, n_otiles = (n_q + KV_BN - 1) / KV_BN;
-  const int n_tiles = n_ptiles + n_otiles;
-  const int max_items = n_tiles + kv_target_items(hkv);
+  const int np64 = (n_prefix + 63) / 64, no64 = (n_q + 63) / 64;
+  const int max_tiles = np64 + no64;
+  const int max_items = max_tiles + kv_target_items(hkv);
   const int max_slots = 2 * kv_target_items(hkv);
+  const int max_split_tiles = kv_target_items(hkv);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes); return base ? (char*)base + o : (char*)nullptr; };
   char* hdr = take(sizeof(KvPlanHeader));
-  char* t0 = take(sizeof(int) * n_tiles);
-  char* t1 = take(sizeof(int) * n_tiles);
-  char* t2 = take(sizeof(int) * n_tiles);
-  char* t3 = take(sizeof(int) * n_tiles);
+  char* t[6];
+  for (int i = 0; i < 6; i++) t[i] = take(sizeof(int) * max_tiles);
   char* i0 = take(sizeof(int) * max_items);
   char* i1 = take(sizeof(int) * max_items);
+  char* st = take(sizeof(int) * max_split_tiles);
   char* sl = take(sizeof(float) * (size_t)max_slots * hkv * 2 * KV_BN * D);
   if (out) {
     out->hdr = (KvPlanHeader*)hdr;
-    out->tile_nq = (int*)t0; out->tile_qtlo = (int*)t1; out->tile_nchunks = (int*)t2; out->tile_item0 = (int*)t3;
-    out->item_tile = (int*)i0; out->item_chunk = (int*)i1; out->slots = (float*)sl;
-    out->n_tiles = n_tiles; out->n_ptiles = n_ptiles; out->max_items = max_items; out->max_slots = max_slots;
+    out->tile_e0 = (int*)t[0]; out->tile_ne = (int*)t[1];
+    out->tile_nq = (int*)t[2]; out->tile_qtlo = (int*)t[3]; out->tile_nchunks = (int*)t[4]; out->tile_item0 = (int*)t[5];
+    out->item_tile = (int*)i0; out->item_chunk = (int*)i1; out->split_tile = (int*)st; out->slots = (float*)sl;
+    out->np64 = np64; out->no64 = no64;
+    out->max_tiles = max_tiles; out->max_items = max_items; out->max_slots = max_slots; out->max_split_tiles = max_split_tiles;
   }
   return off;
 }
 
-// exclusive prefix sum of one int per thread over the workgroup; returns the total through *total
-__device__ inline int block_exclusive_scan(int v, int* scratch /*[PLAN_THREADS]*/, int* total) {
+// exclusive prefix sum / prefix maximum of one int per thread over the workgroup; the reduction over
+// all threads is returned through *total
+template <bool MAX>
+__device__ inline int block_exclusive_scan(int v, int* scratch /*[PLAN_THREADS]*/, int* total, int identity = 0) {
   const int t = threadIdx.x;
   scratch[t] = v;
   __syncthreads();
   for (int off = 1; off < PLAN_THREADS; off <<= 1) {
-    const int add = t >= off ? scratch[t - off] : 0;
+    const int other = t >= off ? scratch[t - off] : identity;
     __syncthreads();
-    scratch[t] += add;
+    scratch[t] = MAX ? max(scratch[t], other) : scratch[t] + other;
     __syncthreads();
   }
-  const int incl = scratch[t];
+  const int excl = t > 0 ? scratch[t - 1] : identity;
   *total = scratch[PLAN_THREADS - 1];
   __syncthreads();
-  return incl - v;
+  return excl;
 }
 
 __global__ void __launch_bounds__(PLAN_THREADS)
 kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_prefix, int G, int hkv) {
   __shared__ int scratch[PLAN_THREADS];
   const int t = threadIdx.x;
-  const int per = (pl.n_tiles + PLAN_THREADS - 1) / PLAN_THREADS;    // consecutive tiles per thread
-  const int lo = min(t * per, pl.n_tiles), hi = min(lo + per, pl.n_tiles);
-  const int np64 = (n_prefix + 63) / 64, no64 = (n_q + 63) / 64;
-  // pass 1: visible query tiles of every key tile
-  int my_steps = 0;
-  for (int tl = lo; tl < hi; tl++) {
-    int kmax = 0, i_lo;
-    constexpr int EPT = KV_BN / 64;          // summary entries per key tile
-    if (tl < pl.n_ptiles) {
-      for (int e = EPT * tl; e < EPT * tl + EPT && e < np64; e++) kmax = max(kmax, kt_max[e]);
-      i_lo = 0;
-    } else {
-      const int to = tl - pl.n_ptiles;
-      for (int e = EPT * to; e < EPT * to + EPT && e < no64; e++) kmax = max(kmax, kt_max[np64 + e]);
-      i_lo = to * KV_BN;
+  const int np64 = pl.np64, n_ent = pl.np64 + pl.no64;
+  // a run starts at the first entry of a region and wherever the largest bound changes
+  auto run_break = [&](int e) { return e == 0 || e == np64 || kt_max[e] != kt_max[e - 1]; };
+
+  // ---- pass 1: tiles = runs cut every KV_EPT entries; each thread owns consecutive entries ----
+  const int per = (n_ent + PLAN_THREADS - 1) / PLAN_THREADS;
+  const int lo = min(t * per, n_ent), hi = min(lo + per, n_ent);
+  int last_break = -1;
+  for (int e = lo; e < hi; e++)
+    if (run_break(e)) last_break = e;
+  int unused;
+  const int carry = block_exclusive_scan<true>(last_break, scratch, &unused, -1);    // start of the run my first entry is in
+  int my_tiles = 0;
+  {
+    int run_start = carry;
+    for (int e = lo; e < hi; e++) {
+      if (run_break(e)) run_start = e;
+      if (((e - run_start) % KV_EPT) == 0) my_tiles++;
     }
-    const int i_hi = (int)min((int64_t)n_q, (int64_t)kmax - n_prefix);
-    const int qt_lo = i_lo / KV_BM;
-    const int nq = i_hi > i_lo ? (i_hi + KV_BM - 1) / KV_BM - qt_lo : 0;
-    pl.tile_nq[tl] = nq;
-    pl.tile_qtlo[tl] = qt_lo;
-    my_steps += nq * G;
+  }
+  int n_tiles;
+  int tl = block_exclusive_scan<false>(my_tiles, scratch, &n_tiles);
+  int my_steps = 0;
+  {
+    int run_start = carry;
+    for (int e = lo; e < hi; e++) {
+      if (run_break(e)) run_start = e;
+      if (((e - run_start) % KV_EPT) != 0) continue;
+      // the tile runs to the next break, region end or KV_EPT entries
+      const int e_end = e < np64 ? np64 : n_ent;
+      int ne = 1;
+      while (ne < KV_EPT && e + ne < e_end && kt_max[e + ne] == kt_max[e]) ne++;
+      const int kmax = kt_max[e];
+      const int i_lo = e < np64 ? 0 : (e - np64) * 64;                 // first query that can see a key of the tile
+      const int i_hi = (int)min((int64_t)n_q, (int64_t)kmax - n_prefix);
+      const int qt_lo = i_lo / KV_BM;
+      const int nq = i_hi > i_lo ? (i_hi + KV_BM - 1) / KV_BM - qt_lo : 0;
+      pl.tile_e0[tl] = e;
+      pl.tile_ne[tl] = ne;
+      pl.tile_nq[tl] = nq;
+      pl.tile_qtlo[tl] = qt_lo;
+      my_steps += nq * G;
+      tl++;
+    }
   }
   int total_steps;
-  block_exclusive_scan(my_steps, scratch, &total_steps);
+  block_exclusive_scan<false>(my_steps, scratch, &total_steps);       // (its barriers also publish the tile tables)
   const int64_t all = (int64_t)total_steps * hkv;
   const int chunk = (int)max((int64_t)KV_MIN_CHUNK, (all + KV_TARGET_WORK - 1) / KV_TARGET_WORK);
-  // pass 2: chunks per tile; cut tiles are numbered first (their item index is also their slot)
-  int my_split = 0, my_whole = 0;
-  for (int tl = lo; tl < hi; tl++) {
-    const int steps = pl.tile_nq[tl] * G;
+
+  // ---- pass 2: chunks per tile; cut tiles are numbered first (their item index is also their slot);
+  //      each thread owns consecutive tiles ----
+  const int per_t = (n_tiles + PLAN_THREADS - 1) / PLAN_THREADS;
+  const int tlo = min(t * per_t, n_tiles), thi = min(tlo + per_t, n_tiles);
+  int my_split = 0, my_whole = 0, my_split_tiles = 0;
+  for (int i = tlo; i < thi; i++) {
+    const int steps = pl.tile_nq[i] * G;
     const int nc = (steps + chunk - 1) / chunk;
-    pl.tile_nchunks[tl] = nc;
-    if (nc > 1) my_split += nc; else my_whole += nc;
+    pl.tile_nchunks[i] = nc;
+    if (nc > 1) { my_split += nc; my_split_tiles++; } else my_whole += nc;
   }
-  int n_split, n_whole;
-  int split0 = block_exclusive_scan(my_split, scratch, &n_split);
-  int whole0 = block_exclusive_scan(my_whole, scratch, &n_whole) + n_split;
-  for (int tl = lo; tl < hi; tl++) {
-    const int nc = pl.tile_nchunks[tl];
+  int n_split, n_whole, n_split_tiles;
+  int split0 = block_exclusive_scan<false>(my_split, scratch, &n_split);
+  int whole0 = block_exclusive_scan<false>(my_whole, scratch, &n_whole) + n_split;
+  int st0 = block_exclusive_scan<false>(my_split_tiles, scratch, &n_split_tiles);
+  for (int i = tlo; i < thi; i++) {
+    const int nc = pl.tile_nchunks[i];
     int& cursor = nc > 1 ? split0 : whole0;
-    pl.tile_item0[tl] = cursor;
-    for (int c = 0; c < nc; c++) { pl.item_tile[cursor + c] = tl; pl.item_chunk[cursor + c] = c; }
+    pl.tile_item0[i] = cursor;
+    for (int c = 0; c < nc; c++) { pl.item_tile[cursor + c] = i; pl.item_chunk[cursor + c] = c; }
     cursor += nc;
+    if (nc > 1) pl.split_tile[st0++] = i;
   }
   if (t == 0) {
     pl.hdr->n_work = (n_split + n_whole) * hkv;
     pl.hdr->counter = 0;
     pl.hdr->chunk = chunk;
     pl.hdr->n_split_items = n_split;
+    pl.hdr->n_tiles = n_tiles;
+    pl.hdr->n_split_tiles = n_split_tiles;
   }
 }
 
@@ -234,13 +285,15 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
     const int s_hi = min(s_lo + chunk, nq * G);
     const bool partial = pl.tile_nchunks[tile] > 1;
 
-    const bool is_prefix = tile < pl.n_ptiles;
-    const int k0 = is_prefix ? tile * KV_BN : (tile - pl.n_ptiles) * KV_BN;   // region-local first key
+    const int e0 = pl.tile_e0[tile];
+    const int n_keys = pl.tile_ne[tile] * 64;        // keys of the tile (the last entry of a region may be ragged)
+    const bool is_prefix = e0 < pl.np64;
+    const int k0 = (is_prefix ? e0 : e0 - pl.np64) * 64;                      // region-local first key
     const int region = is_prefix ? P : N;
     const int j0 = is_prefix ? k0 : P + k0;          // unified index of the first key
-    // this lane's key
+    // this lane's key; wavefronts beyond the tile's keys have nothing to do
     const int kl = k0 + 32 * w + c32;
-    const bool key_ok = kl < region;
+    const bool key_ok = 32 * w + c32 < n_keys && kl < region;
     const int j = j0 + 32 * w + c32;
     const int my_kend = key_ok ? a.kend[j] : 0;
     int kmax_w = my_kend, kmin_w = key_ok ? my_kend : INT32_MAX;
@@ -482,15 +535,18 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
 constexpr int RED_THREADS = 256;
 constexpr int RED_KEYS = RED_THREADS * 4 / D;        // 8 keys per pass
 constexpr int RED_PASSES = 4;                        // passes per workgroup
+constexpr int RED_PARTS = KV_BN / (RED_KEYS * RED_PASSES);
 __global__ void __launch_bounds__(RED_THREADS)
 kv_reduce_kernel(AttnArgs a, KvPlan pl) {
-  constexpr int PARTS = KV_BN / (RED_KEYS * RED_PASSES);
-  const int tile = blockIdx.x / PARTS, part = blockIdx.x % PARTS, kvh = blockIdx.y;
+  const int si = blockIdx.x / RED_PARTS, part = blockIdx.x % RED_PARTS, kvh = blockIdx.y;
+  if (si >= pl.hdr->n_split_tiles) return;
+  const int tile = pl.split_tile[si];
   const int nc = pl.tile_nchunks[tile];
-  if (nc <= 1) return;
   const int item0 = pl.tile_item0[tile];
-  const bool is_prefix = tile < pl.n_ptiles;
-  const int k0 = is_prefix ? tile * KV_BN : (tile - pl.n_ptiles) * KV_BN;
+  const int e0 = pl.tile_e0[tile];
+  const int n_keys = pl.tile_ne[tile] * 64;
+  const bool is_prefix = e0 < pl.np64;
+  const int k0 = (is_prefix ? e0 : e0 - pl.np64) * 64;
   const int region = is_prefix ? a.n_prefix : a.n_q;
   const int64_t slot_stride = (int64_t)a.hkv * 2 * KV_BN * D;             // floats between consecutive chunks
   const float* slot0 = pl.slots + ((int64_t)item0 * a.hkv + kvh) * 2 * KV_BN * D;
@@ -498,7 +554,7 @@ kv_reduce_kernel(AttnArgs a, KvPlan pl) {
   for (int u = 0; u < RED_PASSES; u++) {
     const int e = ((part * RED_PASSES + u) * RED_THREADS + threadIdx.x) * 4;
     const int key = e / D, d0 = e % D;
-    if (k0 + key >= region) continue;
+    if (key >= n_keys || k0 + key >= region) continue;
     f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
     const float* base = slot0 + e;
     int c = 0;
@@ -563,7 +619,7 @@ hipError_t mfma_attn_dkdv(const AttnArgs& a, hipStream_t st) {
   }
   {
     KernelTimer timer(TT_KERNEL_ATTN_REDUCE, st);
-    kv_reduce_kernel<<<dim3(pl.n_tiles * (KV_BN / (RED_KEYS * RED_PASSES)), a.hkv), RED_THREADS, 0, st>>>(a, pl);
+    kv_reduce_kernel<<<dim3(pl.max_split_tiles * RED_PARTS, a.hkv), RED_THREADS, 0, st>>>(a, pl);
     if (hipError_t e = hipGetLastError()) return e;
   }
   return hipSuccess;
