@@ -21,11 +21,16 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 struct MS { float m, s; };   // running max (natural units) and sum of exp(z - m)
 
+// 2^x as the bare hardware instruction: every argument here is <= 0, and a term below 2^-126 may
+// flush to zero (it could not change a sum whose largest term is 1).  The library exp2f spends
+// several more instructions per element on that range, which made the kernel ALU-bound.
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ MS merge(MS a, MS b) {
   const float m = fmaxf(a.m, b.m);
   // exp2(-inf) = 0 handles empty partners; (-inf) - (-inf) is avoided by the select
-  const float sa = a.m == -INFINITY ? 0.f : a.s * exp2f((a.m - m) * LOG2E);
-  const float sb = b.m == -INFINITY ? 0.f : b.s * exp2f((b.m - m) * LOG2E);
+  const float sa = a.m == -INFINITY ? 0.f : a.s * ex2((a.m - m) * LOG2E);
+  const float sb = b.m == -INFINITY ? 0.f : b.s * ex2((b.m - m) * LOG2E);
   return {m, sa + sb};
 }
 
@@ -34,17 +39,17 @@ __device__ __forceinline__ void push8(MS& st, const float (&z)[8]) {  // z may h
   const float m_new = fmaxf(st.m, vm);
   const float mref = m_new == -INFINITY ? 0.f : m_new;      // all -inf so far: keep the sum at 0, no NaN
   // the difference is taken before the scaling so that large |z| loses nothing
-  float acc = st.m == -INFINITY ? 0.f : st.s * exp2f((st.m - mref) * LOG2E);
+  float acc = st.m == -INFINITY ? 0.f : st.s * ex2((st.m - mref) * LOG2E);
 #pragma unroll
-  for (int e = 0; e < 8; e++) acc += exp2f((z[e] - mref) * LOG2E);
+  for (int e = 0; e < 8; e++) acc += ex2((z[e] - mref) * LOG2E);
   st.m = m_new;
   st.s = acc;
 }
 
 __device__ __forceinline__ void push1(MS& st, float z) {
   const float m_new = fmaxf(st.m, z);
-  const float old = st.m == -INFINITY ? 0.f : st.s * exp2f((st.m - m_new) * LOG2E);
-  st.s = old + exp2f((z - m_new) * LOG2E);
+  const float old = st.m == -INFINITY ? 0.f : st.s * ex2((st.m - m_new) * LOG2E);
+  st.s = old + ex2((z - m_new) * LOG2E);
   st.m = m_new;
 }
 
