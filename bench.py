@@ -26,9 +26,9 @@ PEAK_HBM_GBPS = 8000.0
 # WRITE_SIZE runs summarised under profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the plain
 # 1 GiB copy of the same run).  Offline measurements: reported only for the workload they cover.
 MEASURED_TRAFFIC_BYTES = {
-    (2, "attn_fwd"): 214.8e6 + 136.6e6,
-    (2, "attn_dkdv"): 2524.3e6 + 262.8e6,
-    (2, "attn_dq"): 363.9e6 + 134.4e6,
+    (2, "attn_fwd"): 230.3e6 + 149.2e6,
+    (2, "attn_dkdv"): 2394.4e6 + 271.8e6,
+    (2, "attn_dq"): 372.4e6 + 142.8e6,
 }
 
 
