@@ -45,3 +45,22 @@ def loss_sep_avg(paths, logp, trained_tok, adv=None) -> float:
             branch += tr[t] * a[t] * (-logp[t])
         total += branch
     return total / len(paths)
+
+
+def dlogits(logits, target, weight, lse=None, grad_scale: float = 1.0) -> np.ndarray:
+    """Gradient of grad_scale * sum_r weight_r * (-logp_r) with respect to the logits:
+    d/dz_rv = grad_scale * weight_r * (softmax(z_r)_v - [v == target_r]); rows with a negative
+    target contribute nothing to the loss and get a zero gradient.  (Derivative of Eq. 4 through
+    l_t = -log softmax; `lse` may be passed in, it is what the forward pass saved.)"""
+    z = _f64(logits)
+    target = np.asarray(target).astype(np.int64)
+    w = np.ones(z.shape[0]) if weight is None else _f64(weight)
+    if lse is None:
+        _, lse = log_softmax_gather(z, target)
+    p = np.exp(z - _f64(lse)[:, None])
+    g = p.copy()
+    rows = np.nonzero(target >= 0)[0]
+    g[rows, target[rows]] -= 1.0
+    g *= (grad_scale * w)[:, None]
+    g[target < 0] = 0.0
+    return g

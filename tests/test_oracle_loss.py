@@ -56,3 +56,53 @@ def test_single_chain_is_plain_nll_sum():
     assert np.all(m["tok_weight"] == 1.0)
     nll = torch.nn.functional.cross_entropy(logits.double(), target.long(), reduction="sum").item()
     assert abs(L.loss_tree(logp, m["tok_weight"]) - nll) < 1e-12
+
+
+def _rand_case(seed, rows=7, vocab=23):
+    rng = np.random.default_rng(seed)
+    z = rng.normal(size=(rows, vocab)) * 3.0
+    y = rng.integers(0, vocab, size=rows)
+    y[1] = -1                                   # an ignored row
+    w = rng.uniform(0.1, 2.0, size=rows)
+    return z, y, w
+
+
+def test_dlogits_matches_finite_differences():
+    z, y, w = _rand_case(3)
+    g = L.dlogits(z, y, w, grad_scale=0.7)
+    f = lambda zz: 0.7 * L.loss_tree(L.log_softmax_gather(zz, y)[0], w)
+    h = 1e-6
+    for (r, v) in [(0, 0), (0, int(y[0])), (2, 5), (3, int(y[3])), (6, 22), (1, 4)]:
+        zp, zm = z.copy(), z.copy()
+        zp[r, v] += h
+        zm[r, v] -= h
+        fd = (f(zp) - f(zm)) / (2 * h)
+        assert abs(fd - g[r, v]) <= 1e-7 * max(1.0, abs(fd)), (r, v, fd, g[r, v])
+
+
+def test_dlogits_closed_forms():
+    # uniform logits: softmax = 1/V everywhere
+    V = 16
+    z = np.full((2, V), 1.25)
+    g = L.dlogits(z, [3, -1], [2.0, 5.0])
+    want = np.full(V, 2.0 / V)
+    want[3] -= 2.0
+    assert np.allclose(g[0], want, rtol=0, atol=1e-15)
+    assert np.all(g[1] == 0.0)                    # ignored row
+    # every row with a valid target sums to zero (softmax sums to one)
+    z, y, w = _rand_case(5, rows=9, vocab=31)
+    g = L.dlogits(z, y, w)
+    assert np.abs(g[y >= 0].sum(axis=1)).max() <= 1e-14
+    # a saved lse gives the same result as recomputing it
+    _, lse = L.log_softmax_gather(z, y)
+    assert np.array_equal(L.dlogits(z, y, w, lse=lse), g)
+
+
+def test_dlogits_against_library_autograd():
+    z, y, w = _rand_case(11, rows=12, vocab=40)
+    zt = torch.tensor(z, dtype=torch.float64, requires_grad=True)
+    yt = torch.tensor(np.where(y >= 0, y, 0))
+    nll = torch.nn.functional.cross_entropy(zt, yt, reduction="none")
+    loss = (torch.tensor(w * (y >= 0)) * nll).sum()
+    loss.backward()
+    assert np.allclose(zt.grad.numpy(), L.dlogits(z, y, w), rtol=1e-12, atol=1e-14)
