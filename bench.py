@@ -119,6 +119,7 @@ def main():
         logp = torch.empty(N, dtype=torch.float32, device=dev)
         lse_l = torch.empty(N, dtype=torch.float32, device=dev)
         loss_acc = torch.zeros(1, dtype=torch.float32, device=dev)
+        dlogits = torch.empty_like(logits)          # gradient of the loss w.r.t. the logits (same chunking)
         loss_rows = N
 
     ws_f = torch.empty(T.tree_attn_workspace(q, k, v, n_prefix, False), dtype=torch.uint8, device=dev)
@@ -160,6 +161,8 @@ def main():
                 n = min(rows, N - lo)
                 T.tree_weighted_logprob(logits[:n], target[lo:lo + n], w_d[lo:lo + n], loss_acc=loss_acc,
                                         logp=logp[lo:lo + n], lse=lse_l[lo:lo + n])
+                T.tree_weighted_logprob_bwd(logits[:n], target[lo:lo + n], w_d[lo:lo + n], lse_l[lo:lo + n],
+                                            out=dlogits[:n])
         if events:
             events[3].record()
 
@@ -196,12 +199,14 @@ def main():
                     "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, dom)),
                     "avg_ms": round(avg_ms, 4),
                     "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
-    loss_gbps = None
+    loss_gbps = loss_bwd_gbps = None
     if do_loss and "loss_rows" in kernel_ms:
         esz = 2 if dims.logit_dtype == "bf16" else 4
         bytes_total = loss_rows * (dims.vocab * esz + 12)
         loss_ms_total = ktimes["loss_rows"][0] / args.steps
         loss_gbps = bytes_total / (loss_ms_total * 1e-3) / 1e9
+        # backward: one read of the logits + one write of the gradient + target, weight, lse per row
+        loss_bwd_gbps = loss_rows * (2 * dims.vocab * esz + 12) / (ktimes["loss_bwd"][0] / args.steps * 1e-3) / 1e9
 
     # ---------------- linearised per-branch baseline on the same GPU ----------------
     lin = None
@@ -277,6 +282,8 @@ def main():
         "kernel_avg_ms": {n: round(t, 4) for n, t in kernel_ms.items()},
         "loss_hbm_gbps": None if loss_gbps is None else round(loss_gbps, 1),
         "loss_frac_of_hbm_peak": None if loss_gbps is None else round(loss_gbps / PEAK_HBM_GBPS, 4),
+        "loss_bwd_hbm_gbps": None if loss_bwd_gbps is None else round(loss_bwd_gbps, 1),
+        "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -213,6 +213,26 @@ tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype,
                                    float* logp, float* lse, float* loss_acc, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * tt_tree_weighted_logprob_bwd (device)
+ *
+ * Gradient of grad_scale * sum_r weight_r * (-logp_r) (Eq. 4 through l_t = -log softmax) with
+ * respect to the logits:
+ *   dlogits[r][v] = grad_scale * weight_r * (exp(z_rv - lse_r) - [v == target_r]),
+ * zero for rows with a negative target.  One read of the logits, one write of the gradient.
+ *   logits, target, weight as for tt_tree_weighted_logprob; lse [n_rows] fp32 from that call
+ *   (required).  dlogits [n_rows][vocab], row stride `dlogits_row_stride` elements (0 = vocab),
+ *   same dtype as the logits (bf16: round to nearest even); it may alias logits when the two
+ *   strides are equal (every element is read before it is written, by the same thread).
+ * Alignment: both arrays aligned to the element size; rows of which both the logits and the
+ *   gradient start on a 16-byte boundary take the vector path, other rows a scalar path.
+ * ------------------------------------------------------------------------------------------ */
+tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab, int32_t dtype,
+                                       const void* logits, int64_t row_stride,
+                                       const int32_t* target, const float* weight, const float* lse,
+                                       float grad_scale, void* dlogits, int64_t dlogits_row_stride,
+                                       void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
  * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
  * the recorded events have completed and returns the totals since the last enable.
@@ -227,7 +247,8 @@ tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype,
 #define TT_KERNEL_REF_BWD     7
 #define TT_KERNEL_ATTN_PLAN   8   /* work decomposition of the dK/dV pass                */
 #define TT_KERNEL_ATTN_REDUCE 9   /* sum of dK/dV partials of key tiles that were cut    */
-#define TT_N_KERNELS          10
+#define TT_KERNEL_LOSS_BWD    10  /* gradient of the loss with respect to the logits     */
+#define TT_N_KERNELS          11
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

@@ -70,6 +70,9 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_weighted_logprob.restype = ctypes.c_int32
         lib.tt_tree_weighted_logprob.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp,
                                                  ctypes.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+        lib.tt_tree_weighted_logprob_bwd.restype = ctypes.c_int32
+        lib.tt_tree_weighted_logprob_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
+                                                     _vp, _vp, _vp, ctypes.c_float, _vp, ctypes.c_int64, _vp]
         lib.tt_kernel_timing_enable.restype = ctypes.c_int32
         lib.tt_kernel_timing_enable.argtypes = [ctypes.c_int32]
         lib.tt_kernel_timing_read.restype = ctypes.c_int32
@@ -79,11 +82,11 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce")
+                "attn_plan", "attn_reduce", "loss_bwd")
 
 
 class _KernelTimes(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 10), ("launches", ctypes.c_int64 * 10)]
+    _fields_ = [("ms", ctypes.c_double * len(KERNEL_NAMES)), ("launches", ctypes.c_int64 * len(KERNEL_NAMES))]
 
 
 def kernel_timing_enable(on: bool) -> None:
@@ -296,3 +299,24 @@ def tree_weighted_logprob(logits, target, weight=None, *, loss_acc=None, logp=No
         logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(logp), _dp(lse), _dp(loss_acc),
         _stream_ptr(stream)))
     return logp, lse, loss_acc
+
+
+def tree_weighted_logprob_bwd(logits, target, weight, lse, *, grad_scale: float = 1.0, out=None, stream=None):
+    """dlogits = grad_scale * weight * (softmax(logits) - onehot(target)), same dtype and shape as logits
+    (zero rows where target < 0); lse [n] fp32 is the one tree_weighted_logprob returned.  `out` may be
+    the logits tensor itself (in place)."""
+    torch = _torch()
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [rows, vocab] with contiguous vocab")
+    if logits.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("logits must be bf16 or fp32")
+    n, vocab = logits.shape
+    if out is None:
+        out = torch.empty((n, vocab), dtype=logits.dtype, device=logits.device)
+    if out.shape != logits.shape or out.dtype != logits.dtype or out.stride(1) != 1:
+        raise ValueError("out must match logits in shape and dtype, with contiguous vocab")
+    _check(_lib().tt_tree_weighted_logprob_bwd(
+        n, vocab, DTYPE_BF16 if logits.dtype == torch.bfloat16 else DTYPE_FP32, _dp(logits),
+        logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(lse), float(grad_scale), _dp(out),
+        out.stride(0) if n > 1 else vocab, _stream_ptr(stream)))
+    return out

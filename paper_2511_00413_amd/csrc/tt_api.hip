@@ -149,3 +149,28 @@ extern "C" tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int
                                          logp, lse, loss_acc, (hipStream_t)stream),
                     "tree_weighted_logprob");
 }
+
+extern "C" tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab, int32_t dtype, const void* logits,
+                                                  int64_t row_stride, const int32_t* target, const float* weight,
+                                                  const float* lse, float grad_scale, void* dlogits,
+                                                  int64_t dlogits_row_stride, void* stream) {
+  tt::clear_error();
+  if (dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (n_rows < 0 || n_rows > 0x7fffffffLL) return fail(TT_ERR_SHAPE, "n_rows=%lld out of range", (long long)n_rows);
+  if (vocab <= 0) return fail(TT_ERR_SHAPE, "vocab=%d must be positive", vocab);
+  if (row_stride == 0) row_stride = vocab;
+  if (dlogits_row_stride == 0) dlogits_row_stride = vocab;
+  if (row_stride < vocab || dlogits_row_stride < vocab)
+    return fail(TT_ERR_SHAPE, "row strides %lld / %lld are smaller than vocab=%d", (long long)row_stride,
+                (long long)dlogits_row_stride, vocab);
+  if (!std::isfinite(grad_scale)) return fail(TT_ERR_SHAPE, "grad_scale must be finite");
+  if (n_rows > 0 && (!logits || !target || !lse || !dlogits)) return fail(TT_ERR_NULL, "logits / target / lse / dlogits is NULL");
+  if (dlogits == logits && dlogits_row_stride != row_stride)
+    return fail(TT_ERR_SHAPE, "dlogits may alias logits only with equal row strides");
+  const size_t es = dtype == TT_DTYPE_BF16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(logits) % es || reinterpret_cast<uintptr_t>(dlogits) % es)
+    return fail(TT_ERR_ALIGN, "logits / dlogits is not aligned to its element size");
+  return hip_result(tt::weighted_logprob_bwd(n_rows, vocab, dtype == TT_DTYPE_BF16, logits, row_stride, target, weight,
+                                             lse, grad_scale, dlogits, dlogits_row_stride, (hipStream_t)stream),
+                    "tree_weighted_logprob_bwd");
+}

@@ -58,5 +58,8 @@ size_t mfma_attn_dkdv_workspace(int n_q, int n_prefix, int hkv);
 hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
                             const int32_t* target, const float* weight, float* logp, float* lse,
                             float* loss_acc, hipStream_t st);
+hipError_t weighted_logprob_bwd(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                                const int32_t* target, const float* weight, const float* lse, float grad_scale,
+                                void* dlogits, int64_t out_stride, hipStream_t st);
 
 }  // namespace tt

@@ -159,6 +159,81 @@ weighted_sum_kernel(int64_t n_rows, const float* __restrict__ logp, const float*
   if (threadIdx.x == 0) *loss_acc = (float)((double)*loss_acc + part[0]);
 }
 
+// ---- backward: dlogits = grad_scale * weight * (softmax - onehot) --------------------------------
+typedef float f32x8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+
+// w_r (exp(z - lse) - [v == y]) for the 8 (bf16) or 4 (fp32) elements of one 16-byte vector whose
+// first element has index `base` in the row
+__device__ __forceinline__ u32x4 grad_vec_bf16(const u32x4& v, float lse, float w, int base, int y) {
+  float z[8];
+  unpack8(v, z);
+  f32x8v g;
+#pragma unroll
+  for (int e = 0; e < 8; e++) g[e] = w * ex2((z[e] - lse) * LOG2E);
+  if ((unsigned)(y - base) < 8u) {              // the target element lives in this vector (at most once per row)
+#pragma unroll
+    for (int e = 0; e < 8; e++) g[e] -= (base + e == y) ? w : 0.f;
+  }
+  const bf16x8v b = __builtin_convertvector(g, bf16x8v);     // round to nearest even
+  return __builtin_bit_cast(u32x4, b);
+}
+__device__ __forceinline__ u32x4 grad_vec_f32(const u32x4& v, float lse, float w, int base, int y) {
+  const float z[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+  float g[4];
+#pragma unroll
+  for (int e = 0; e < 4; e++) g[e] = w * ex2((z[e] - lse) * LOG2E) - ((base + e == y) ? w : 0.f);
+  u32x4 o;
+  o.x = __float_as_uint(g[0]); o.y = __float_as_uint(g[1]); o.z = __float_as_uint(g[2]); o.w = __float_as_uint(g[3]);
+  return o;
+}
+__device__ __forceinline__ void store_elem(float* p, int64_t i, float g) { p[i] = g; }
+__device__ __forceinline__ void store_elem(__hip_bfloat16* p, int64_t i, float g) { p[i] = __float2bfloat16(g); }
+
+// One workgroup per row: one 16-byte load and one 16-byte store per vector, four vectors in flight.
+template <typename T>
+__global__ void __launch_bounds__(LOSS_THREADS)
+row_dlogits_kernel(int vocab, const T* logits, int64_t row_stride, const int32_t* __restrict__ target,
+                   const float* __restrict__ weight, const float* __restrict__ lse_in, float grad_scale,
+                   T* dlogits, int64_t out_stride) {
+  constexpr int EPV = 16 / sizeof(T);
+  const int64_t r = blockIdx.x;
+  const T* row = logits + r * row_stride;
+  T* out = dlogits + r * out_stride;
+  const int t = threadIdx.x;
+  const int y = target[r];
+  const float w = y >= 0 ? grad_scale * (weight ? weight[r] : 1.f) : 0.f;     // ignored row: zeros
+  const float lse = y >= 0 ? lse_in[r] : 0.f;
+  const bool vec_ok = ((reinterpret_cast<uintptr_t>(row) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  const int nvec = vec_ok ? vocab / EPV : 0;
+  const u32x4* vp = reinterpret_cast<const u32x4*>(row);
+  u32x4* op = reinterpret_cast<u32x4*>(out);
+  auto grad = [&](const u32x4& v, int i) {
+    if constexpr (sizeof(T) == 2) return grad_vec_bf16(v, lse, w, i * EPV, y);
+    else return grad_vec_f32(v, lse, w, i * EPV, y);
+  };
+  int i = t;
+  for (; i + 3 * LOSS_THREADS < nvec; i += 4 * LOSS_THREADS) {
+    const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+    const u32x4 v1 = __builtin_nontemporal_load(vp + i + LOSS_THREADS);
+    const u32x4 v2 = __builtin_nontemporal_load(vp + i + 2 * LOSS_THREADS);
+    const u32x4 v3 = __builtin_nontemporal_load(vp + i + 3 * LOSS_THREADS);
+    __builtin_nontemporal_store(grad(v0, i), op + i);
+    __builtin_nontemporal_store(grad(v1, i + LOSS_THREADS), op + i + LOSS_THREADS);
+    __builtin_nontemporal_store(grad(v2, i + 2 * LOSS_THREADS), op + i + 2 * LOSS_THREADS);
+    __builtin_nontemporal_store(grad(v3, i + 3 * LOSS_THREADS), op + i + 3 * LOSS_THREADS);
+  }
+  for (; i < nvec; i += LOSS_THREADS) {
+    const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+    __builtin_nontemporal_store(grad(v0, i), op + i);
+  }
+  // the rest of the row (everything, for a row that is not 16-byte aligned), element by element
+  for (int e = nvec * EPV + t; e < vocab; e += LOSS_THREADS) {
+    const float g = w * ex2((elem(row, e) - lse) * LOG2E) - (e == y ? w : 0.f);
+    store_elem(out, e, g);
+  }
+}
+
 }  // namespace
 
 hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
@@ -182,6 +257,20 @@ hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* lo
     return hipGetLastError();
   }
   return hipSuccess;
+}
+
+hipError_t weighted_logprob_bwd(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                                const int32_t* target, const float* weight, const float* lse, float grad_scale,
+                                void* dlogits, int64_t out_stride, hipStream_t st) {
+  if (n_rows == 0) return hipSuccess;
+  KernelTimer timer(TT_KERNEL_LOSS_BWD, st);
+  if (bf16)
+    row_dlogits_kernel<__hip_bfloat16><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
+        vocab, (const __hip_bfloat16*)logits, row_stride, target, weight, lse, grad_scale, (__hip_bfloat16*)dlogits, out_stride);
+  else
+    row_dlogits_kernel<float><<<(unsigned)n_rows, LOSS_THREADS, 0, st>>>(
+        vocab, (const float*)logits, row_stride, target, weight, lse, grad_scale, (float*)dlogits, out_stride);
+  return hipGetLastError();
 }
 
 }  // namespace tt

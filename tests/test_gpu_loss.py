@@ -87,3 +87,65 @@ def test_special_rows():
     # deterministic
     logp2, _, loss2 = _run(z, tgt, None)
     assert np.array_equal(logp, logp2) and loss == loss2
+
+
+# ---- backward: gradient with respect to the logits ------------------------------------------------
+# bf16 output: one round-to-nearest-even of each element (relative 2^-9) on top of fp32 arithmetic ->
+# rel-L2 <= 4e-3 and every element within 2^-8 relative + a small absolute floor; fp32 output: 1e-5.
+
+def _check_bwd(logits, target, weight, grad_scale=1.0, inplace=False):
+    print(f"[case] loss bwd rows={logits.shape[0]} vocab={logits.shape[1]} {logits.dtype} inplace={inplace}", flush=True)
+    lg = logits.cuda()
+    tg = target.cuda()
+    wt = None if weight is None else torch.from_numpy(weight).cuda()
+    _, lse, _ = T.tree_weighted_logprob(lg, tg, wt)
+    src = lg.clone() if inplace else lg
+    got = T.tree_weighted_logprob_bwd(src, tg, wt, lse, grad_scale=grad_scale, out=src if inplace else None)
+    torch.cuda.synchronize()
+    got = got.float().cpu().numpy().astype(np.float64)
+    want = L.dlogits(logits, target.numpy(), weight, grad_scale=grad_scale)
+    num = np.sqrt(((got - want) ** 2).sum())
+    den = max(np.sqrt((want ** 2).sum()), 1e-30)
+    if logits.dtype == torch.bfloat16:
+        assert num / den <= 4e-3, num / den
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-7 * np.abs(want).max())
+    else:
+        assert num / den <= 1e-5, num / den
+    # ignored rows are exactly zero
+    ign = target.numpy() < 0
+    assert np.all(got[ign] == 0.0)
+    return got
+
+
+@pytest.mark.parametrize("rows,vocab,dtype", [(37, 32768, "bf16"), (5, 151936, "bf16"), (64, 777, "bf16"),
+                                              (33, 1001, "fp32"), (3, 8, "fp32"), (9, 1, "bf16"), (300, 5000, "bf16"),
+                                              (16, 4096, "fp32")])
+def test_bwd_shapes_and_misaligned_rows(rows, vocab, dtype):
+    logits, target = W.loss_inputs(rows, vocab, rows + 3 * vocab, 2.0, dtype)
+    target = target.clone()
+    if rows > 2:
+        target[1] = -1
+    w = (np.random.default_rng(rows).random(rows) + 0.25).astype(np.float32)
+    _check_bwd(logits, target, w, grad_scale=0.5)
+
+
+def test_bwd_in_place_and_no_weight():
+    logits, target = W.loss_inputs(24, 2048, 19, 2.0, "bf16")
+    a = _check_bwd(logits, target, None)
+    b = _check_bwd(logits, target, None, inplace=True)
+    assert np.array_equal(a, b)
+
+
+def test_bwd_strided_rows():
+    logits, target = W.loss_inputs(20, 1024, 23, 2.0, "bf16")
+    wide = torch.zeros(20, 1536, dtype=torch.bfloat16)
+    wide[:, :1024] = logits
+    lg = wide.cuda()[:, :1024]
+    _, lse, _ = T.tree_weighted_logprob(lg, target.cuda(), None)
+    out_wide = torch.full((20, 1280), 7.0, dtype=torch.bfloat16, device="cuda")
+    T.tree_weighted_logprob_bwd(lg, target.cuda(), None, lse, out=out_wide[:, :1024])
+    torch.cuda.synchronize()
+    want = L.dlogits(logits, target.numpy(), None)
+    got = out_wide[:, :1024].float().cpu().numpy()
+    assert np.sqrt(((got - want) ** 2).sum()) / np.sqrt((want ** 2).sum()) <= 4e-3
+    assert float((out_wide[:, 1024:] - 7.0).abs().max()) == 0.0       # nothing written past the row
