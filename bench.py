@@ -42,6 +42,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-linearized", action="store_true")
     ap.add_argument("--no-loss", action="store_true")
+    ap.add_argument("--no-rope", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size kernel "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -130,6 +131,13 @@ def main():
     dk = torch.empty_like(k)
     dv = torch.empty_like(v)
 
+    # rotary embedding with the tree position ids: q_raw / k_raw -> q / k before the attention, and the
+    # inverse rotation of dq / dk after it (the steps either side of the attention path)
+    q_raw, k_raw = q.clone(), k.clone()
+    pos_h = torch.empty(N, dtype=torch.int32).pin_memory()
+    pos_d = torch.empty(N, dtype=torch.int32, device=dev)
+    do_rope = dims.dtype == "bf16" and not args.no_rope
+
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     host_ms = []
 
@@ -144,7 +152,13 @@ def main():
         kmin_d.copy_(kmin_h, non_blocking=True)
         kmax_d.copy_(kmax_h, non_blocking=True)
         w_d.copy_(w_h, non_blocking=True)
+        if do_rope:
+            pos_h.numpy()[:] = m.tok_pos
+            pos_d.copy_(pos_h, non_blocking=True)
         host_ms.append((time.perf_counter() - t0) * 1e3)
+        if do_rope:
+            T.tree_rope(q_raw, pos_d, out=q)
+            T.tree_rope(k_raw, pos_d, out=k)
         if events:
             events[0].record()
         T.tree_attn_fwd(q, k, v, kend_d, kmin_d, kmax_d, k_prefix=kp, v_prefix=vp, o=o, lse=lse, workspace=ws_f)
@@ -154,6 +168,9 @@ def main():
                         dk_prefix_acc=dkp, dv_prefix_acc=dvp, dq=dq, dk=dk, dv=dv, workspace=ws_b)
         if events:
             events[2].record()
+        if do_rope:
+            T.tree_rope(dq, pos_d, inverse=True, out=dq)
+            T.tree_rope(dk, pos_d, inverse=True, out=dk)
         if do_loss:
             loss_acc.zero_()
             rows = logits.shape[0]
@@ -207,6 +224,12 @@ def main():
         loss_gbps = bytes_total / (loss_ms_total * 1e-3) / 1e9
         # backward: one read of the logits + one write of the gradient + target, weight, lse per row
         loss_bwd_gbps = loss_rows * (2 * dims.vocab * esz + 12) / (ktimes["loss_bwd"][0] / args.steps * 1e-3) / 1e9
+
+    rope_gbps = None
+    if do_rope and "rope" in kernel_ms:
+        esz_a = 2
+        rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * esz_a * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
+        rope_gbps = rope_bytes / (ktimes["rope"][0] / args.steps * 1e-3) / 1e9
 
     # ---------------- linearised per-branch baseline on the same GPU ----------------
     lin = None
@@ -282,6 +305,7 @@ def main():
         "kernel_avg_ms": {n: round(t, 4) for n, t in kernel_ms.items()},
         "loss_hbm_gbps": None if loss_gbps is None else round(loss_gbps, 1),
         "loss_frac_of_hbm_peak": None if loss_gbps is None else round(loss_gbps / PEAK_HBM_GBPS, 4),
+        "rope_hbm_gbps": None if rope_gbps is None else round(rope_gbps, 1),
         "loss_bwd_hbm_gbps": None if loss_bwd_gbps is None else round(loss_bwd_gbps, 1),
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,

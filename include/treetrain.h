@@ -233,6 +233,24 @@ tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab, int32_t dt
                                        void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * tt_tree_rope (device)
+ *
+ * Rotary position embedding of a [n_tokens][n_heads][d] tensor (Q or K) with the tree position ids
+ * tok_pos of tt_tree_build_meta (Eq. 9).  Rotate-half convention: for i in [0, d/2)
+ *   angle = tok_pos[t] * theta_base^(-2i/d)
+ *   y[i]       = x[i] cos(angle) - x[i + d/2] sin(angle)
+ *   y[i + d/2] = x[i + d/2] cos(angle) + x[i] sin(angle)
+ * inverse != 0 rotates by -angle (undoes the rotation; also the backward pass: feed dY, get dX).
+ *   x, y: dtype bf16 or fp32, token strides in elements (0 = n_heads * d), heads and d contiguous;
+ *   y may be x (in place) when the strides are equal.  tok_pos [n_tokens] int32, non-negative.
+ *   d must be a multiple of 16 (bf16) / 8 (fp32), at most 1024; x, y 16-byte aligned, token strides a multiple of
+ *   8 (bf16) / 4 (fp32) elements; n_heads * d <= 65536.
+ * ------------------------------------------------------------------------------------------ */
+tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dtype,
+                       const void* x, int64_t x_stride_tok, const int32_t* tok_pos,
+                       float theta_base, int32_t inverse, void* y, int64_t y_stride_tok, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
  * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
  * the recorded events have completed and returns the totals since the last enable.
@@ -248,7 +266,8 @@ tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab, int32_t dt
 #define TT_KERNEL_ATTN_PLAN   8   /* work decomposition of the dK/dV pass                */
 #define TT_KERNEL_ATTN_REDUCE 9   /* sum of dK/dV partials of key tiles that were cut    */
 #define TT_KERNEL_LOSS_BWD    10  /* gradient of the loss with respect to the logits     */
-#define TT_N_KERNELS          11
+#define TT_KERNEL_ROPE        11  /* rotary position embedding                           */
+#define TT_N_KERNELS          12
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

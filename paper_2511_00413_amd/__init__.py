@@ -4,6 +4,6 @@ include/treetrain.h.  Every step runs in the HIP library; this package only mars
 library is missing, importing the binding raises."""
 from .binding import (  # noqa: F401
     TreeMeta, TreeTrainError, lib_path, tree_attn_bwd, tree_attn_fwd, tree_attn_workspace,
-    tree_build_meta, tree_meta_sizes, tree_weighted_logprob, tree_weighted_logprob_bwd, last_error, version, KTILE,
+    tree_build_meta, tree_meta_sizes, tree_weighted_logprob, tree_weighted_logprob_bwd, tree_rope, last_error, version, KTILE,
     kernel_timing_enable, kernel_timing_read,
 )

@@ -73,6 +73,9 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_weighted_logprob_bwd.restype = ctypes.c_int32
         lib.tt_tree_weighted_logprob_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                                      _vp, _vp, _vp, ctypes.c_float, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_rope.restype = ctypes.c_int32
+        lib.tt_tree_rope.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
+                                     _vp, ctypes.c_float, ctypes.c_int32, _vp, ctypes.c_int64, _vp]
         lib.tt_kernel_timing_enable.restype = ctypes.c_int32
         lib.tt_kernel_timing_enable.argtypes = [ctypes.c_int32]
         lib.tt_kernel_timing_read.restype = ctypes.c_int32
@@ -82,7 +85,7 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce", "loss_bwd")
+                "attn_plan", "attn_reduce", "loss_bwd", "rope")
 
 
 class _KernelTimes(ctypes.Structure):
@@ -299,6 +302,25 @@ def tree_weighted_logprob(logits, target, weight=None, *, loss_acc=None, logp=No
         logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(logp), _dp(lse), _dp(loss_acc),
         _stream_ptr(stream)))
     return logp, lse, loss_acc
+
+
+def tree_rope(x, tok_pos, *, theta_base: float = 1.0e6, inverse: bool = False, out=None, stream=None):
+    """Rotary embedding of x [n, heads, d] (bf16/fp32, heads and d contiguous, free token stride) with the
+    tree position ids tok_pos [n] int32; `inverse` undoes it / is its backward.  `out` may be x (in place)."""
+    torch = _torch()
+    if x.dim() != 3 or x.stride(2) != 1 or (x.shape[1] > 1 and x.stride(1) != x.shape[2]):
+        raise ValueError("x must be [tokens, heads, d] with heads and d contiguous")
+    if x.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("x must be bf16 or fp32")
+    n, h, d = x.shape
+    if out is None:
+        out = torch.empty((n, h, d), dtype=x.dtype, device=x.device)
+    if out.shape != x.shape or out.dtype != x.dtype or out.stride(2) != 1 or (h > 1 and out.stride(1) != d):
+        raise ValueError("out must match x in shape and dtype, heads and d contiguous")
+    _check(_lib().tt_tree_rope(n, h, d, DTYPE_BF16 if x.dtype == torch.bfloat16 else DTYPE_FP32, _dp(x),
+                               x.stride(0) if n > 1 else h * d, _dp(tok_pos), float(theta_base), 1 if inverse else 0,
+                               _dp(out), out.stride(0) if n > 1 else h * d, _stream_ptr(stream)))
+    return out
 
 
 def tree_weighted_logprob_bwd(logits, target, weight, lse, *, grad_scale: float = 1.0, out=None, stream=None):

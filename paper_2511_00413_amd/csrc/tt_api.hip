@@ -174,3 +174,27 @@ extern "C" tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab,
                                              lse, grad_scale, dlogits, dlogits_row_stride, (hipStream_t)stream),
                     "tree_weighted_logprob_bwd");
 }
+
+extern "C" tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dtype, const void* x,
+                                  int64_t x_stride_tok, const int32_t* tok_pos, float theta_base, int32_t inverse,
+                                  void* y, int64_t y_stride_tok, void* stream) {
+  tt::clear_error();
+  if (dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (n_tokens < 0 || n_tokens > 0x7fffffffLL) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
+  const int epv = dtype == TT_DTYPE_BF16 ? 8 : 4;
+  if (n_heads <= 0 || d <= 0 || d > 1024 || d % (2 * epv) != 0 || (int64_t)n_heads * d > 65536)
+    return fail(TT_ERR_SHAPE, "n_heads=%d, d=%d: d must be a multiple of %d in [%d, 1024] and n_heads * d <= 65536", n_heads, d,
+                2 * epv, 2 * epv);
+  if (!(theta_base > 1.f) || !std::isfinite(theta_base)) return fail(TT_ERR_SHAPE, "theta_base must be finite and > 1");
+  if (x_stride_tok == 0) x_stride_tok = (int64_t)n_heads * d;
+  if (y_stride_tok == 0) y_stride_tok = (int64_t)n_heads * d;
+  if (x_stride_tok < (int64_t)n_heads * d || y_stride_tok < (int64_t)n_heads * d || x_stride_tok % epv || y_stride_tok % epv)
+    return fail(TT_ERR_SHAPE, "token strides %lld / %lld must be >= n_heads * d and a multiple of %d elements",
+                (long long)x_stride_tok, (long long)y_stride_tok, epv);
+  if (n_tokens > 0 && (!x || !y || !tok_pos)) return fail(TT_ERR_NULL, "x / y / tok_pos is NULL");
+  if (!tt::aligned16(x) || !tt::aligned16(y)) return fail(TT_ERR_ALIGN, "x / y is not 16-byte aligned");
+  if (x == y && x_stride_tok != y_stride_tok) return fail(TT_ERR_SHAPE, "y may alias x only with equal token strides");
+  return hip_result(tt::rope(n_tokens, n_heads, d, dtype == TT_DTYPE_BF16, x, x_stride_tok, tok_pos, theta_base, inverse != 0,
+                             y, y_stride_tok, (hipStream_t)stream),
+                    "tree_rope");
+}
