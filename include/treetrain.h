@@ -190,6 +190,105 @@ tt_status tt_tree_attn_bwd(const tt_attn_desc* desc,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Tree partitioning (host planner + device driver)
+ *
+ * A tree that does not fit in one pass is cut into partitions (Section "Redundancy-Free Tree
+ * Partitioning"): each a connected subtree, cut at node boundaries, at most `capacity` tokens,
+ * every partition with one parent partition.  Each token is still computed once: a partition
+ * attends to a cached slice of its parent partition's keys/values (Appendix "Zero-Overhead
+ * Partition Boundaries"), gradients for those cached keys flow back in fp32.
+ *
+ * tt_tree_partition_plan (host only; needs no GPU)
+ *   Packing rule (a deterministic greedy stand-in for the paper's bin-packing solver, which this
+ *   library does not contain): partitions are opened in first-in-first-out order of their root
+ *   nodes, the tree's roots first in ascending id.  A partition takes its root, then walks
+ *   depth-first with children in ascending id; a child joins if the partition's running token
+ *   count plus the child's own length is <= capacity, otherwise the edge is cut and the child is
+ *   queued as a later partition's root.  A node longer than `capacity` forms a partition alone.
+ *   Boundary bookkeeping for partition p whose root's parent node n_c lies in partition P:
+ *     cached slice  = P's cached slice, then P's own tokens (P's DFS order) up to the end of n_c;
+ *     visible flags = P's flags carried over, then 1 on the nodes of the path P.root .. n_c and
+ *                     0 on everything else (Appendix "Ancestor-Aware Attention Bias");
+ *     pos_offset    = pos_offset(P) + depth-based position of n_c's first token in P + |n_c|
+ *                     (Appendix "Depth-Based Position Offset").
+ *   Token indices are positions in the WHOLE tree's DFS serialisation (the order
+ *   tt_tree_build_meta gives for the same parent / seg_len).
+ * Outputs (host, caller-allocated, sizes from tt_tree_partition_sizes; any may be NULL):
+ *   part_of_node[n_nodes]       partition of each node (input numbering)
+ *   part_node_off[n_parts+1], part_nodes[n_nodes]   node ids per partition, in its DFS order
+ *   part_parent[n_parts]        parent partition, -1 for a partition rooted at a tree root
+ *   part_cut_node[n_parts]      n_c (input id), -1
+ *   part_pos_offset[n_parts]
+ *   part_tok_off[n_parts+1], own_tok[n_tokens]      own tokens per partition, its DFS order
+ *   part_prefix_off[n_parts+1], prefix_tok[sum_prefix], prefix_visible[sum_prefix]
+ *   kend[sum_prefix + n_tokens] partition p's bounds on its [slice ; own] key axis start at
+ *                               part_prefix_off[p] + part_tok_off[p]; same meaning as the kend of
+ *                               tt_tree_build_meta called on the partition
+ *   part_ktile_off[n_parts+1], kt_min, kt_max [sum_ktiles]   tile summaries per partition
+ * Partitions are numbered parents first.
+ * Errors: TT_ERR_NULL, TT_ERR_SHAPE (capacity < 1, negative sizes, overflow), TT_ERR_TREE.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_parts;
+  int32_t n_tokens;         /* whole tree                                         */
+  int32_t max_part_tokens;  /* most own tokens in one partition                   */
+  int32_t max_prefix;       /* longest cached slice                               */
+  int64_t sum_prefix;       /* entries of prefix_tok / prefix_visible             */
+  int64_t sum_ktiles;       /* entries of kt_min / kt_max                         */
+} tt_partition_sizes;
+
+tt_status tt_tree_partition_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                  int32_t capacity, tt_partition_sizes* out);
+
+tt_status tt_tree_partition_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                 int32_t capacity,
+                                 int32_t* part_of_node, int32_t* part_node_off, int32_t* part_nodes,
+                                 int32_t* part_parent, int32_t* part_cut_node, int32_t* part_pos_offset,
+                                 int32_t* part_tok_off, int32_t* own_tok,
+                                 int64_t* part_prefix_off, int32_t* prefix_tok, uint8_t* prefix_visible,
+                                 int32_t* kend, int64_t* part_ktile_off, int32_t* kt_min, int32_t* kt_max);
+
+/* Partitioned tree attention (device): the whole tree in one call, one attention pass per
+ * partition.  Tensors are whole-tree tensors in whole-tree DFS order, exactly as for
+ * tt_tree_attn_fwd / tt_tree_attn_bwd with n_prefix = 0 (desc->n_q = plan->n_tokens,
+ * desc->n_prefix = 0), and the results equal those calls' results up to floating-point summation
+ * order.  Per partition the driver gathers the partition's rows and its cached slice, runs the
+ * attention kernels with the plan's bounds, and scatters the results back.  The backward visits
+ * partitions children first (Appendix "Backward Pass"), adds every partition's cached-key
+ * gradients into whole-tree fp32 accumulators (Appendix "Float32 Gradient Accumulation") and
+ * rounds dk / dv once at the end: dk = own-partition dk + accumulated cached-key gradients.
+ *   plan: the three offset tables are HOST arrays, the five index / bound arrays are DEVICE
+ *   copies of the planner's outputs of the same names.
+ * Errors: as the attention calls; TT_ERR_SHAPE if the plan's sizes disagree with desc. */
+typedef struct {
+  int32_t n_parts;
+  int32_t n_tokens;
+  const int32_t* part_tok_off;      /* host   [n_parts+1] */
+  const int64_t* part_prefix_off;   /* host   [n_parts+1] */
+  const int64_t* part_ktile_off;    /* host   [n_parts+1] */
+  const int32_t* own_tok;           /* device [n_tokens]  */
+  const int32_t* prefix_tok;        /* device [sum_prefix] */
+  const int32_t* kend;              /* device [sum_prefix + n_tokens] */
+  const int32_t* kt_min;            /* device [sum_ktiles] */
+  const int32_t* kt_max;            /* device [sum_ktiles] */
+} tt_partition_plan;
+
+/* Bytes of device workspace; 0 if desc or plan is invalid. */
+size_t tt_tree_attn_partitioned_workspace(const tt_attn_desc* desc, const tt_partition_plan* plan,
+                                          int32_t backward);
+
+tt_status tt_tree_attn_partitioned_fwd(const tt_attn_desc* desc, const tt_partition_plan* plan,
+                                       const void* q, const void* k, const void* v,
+                                       void* o, float* lse,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+tt_status tt_tree_attn_partitioned_bwd(const tt_attn_desc* desc, const tt_partition_plan* plan,
+                                       const void* q, const void* k, const void* v,
+                                       const void* o, const void* d_o, const float* lse,
+                                       void* dq, void* dk, void* dv,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * tt_tree_weighted_logprob (device)
  *
  * Per row r of the logits: lse_r = ln sum_v exp(z_rv), logp_r = z_r[target_r] - lse_r, and the
@@ -267,7 +366,9 @@ tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dty
 #define TT_KERNEL_ATTN_REDUCE 9   /* sum of dK/dV partials of key tiles that were cut    */
 #define TT_KERNEL_LOSS_BWD    10  /* gradient of the loss with respect to the logits     */
 #define TT_KERNEL_ROPE        11  /* rotary position embedding                           */
-#define TT_N_KERNELS          12
+#define TT_KERNEL_PART_GATHER  12  /* partition driver: row gathers                      */
+#define TT_KERNEL_PART_SCATTER 13  /* partition driver: row scatters, accumulate, finalise */
+#define TT_N_KERNELS          14
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

@@ -30,6 +30,17 @@ class _MetaSizes(ctypes.Structure):
                 ("n_roots", ctypes.c_int32), ("n_ktiles", ctypes.c_int32)]
 
 
+class _PartitionSizes(ctypes.Structure):
+    _fields_ = [("n_parts", ctypes.c_int32), ("n_tokens", ctypes.c_int32), ("max_part_tokens", ctypes.c_int32),
+                ("max_prefix", ctypes.c_int32), ("sum_prefix", ctypes.c_int64), ("sum_ktiles", ctypes.c_int64)]
+
+
+class _PartitionPlan(ctypes.Structure):
+    _fields_ = [("n_parts", ctypes.c_int32), ("n_tokens", ctypes.c_int32),
+                ("part_tok_off", _vp), ("part_prefix_off", _vp), ("part_ktile_off", _vp),
+                ("own_tok", _vp), ("prefix_tok", _vp), ("kend", _vp), ("kt_min", _vp), ("kt_max", _vp)]
+
+
 class _AttnDesc(ctypes.Structure):
     _fields_ = [("n_q", ctypes.c_int32), ("n_prefix", ctypes.c_int32), ("hq", ctypes.c_int32),
                 ("hkv", ctypes.c_int32), ("d", ctypes.c_int32), ("dtype", ctypes.c_int32),
@@ -76,6 +87,16 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_rope.restype = ctypes.c_int32
         lib.tt_tree_rope.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                      _vp, ctypes.c_float, ctypes.c_int32, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_partition_sizes.restype = ctypes.c_int32
+        lib.tt_tree_partition_sizes.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.POINTER(_PartitionSizes)]
+        lib.tt_tree_partition_plan.restype = ctypes.c_int32
+        lib.tt_tree_partition_plan.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32] + [_vp] * 15
+        lib.tt_tree_attn_partitioned_workspace.restype = ctypes.c_size_t
+        lib.tt_tree_attn_partitioned_workspace.argtypes = [ctypes.POINTER(_AttnDesc), ctypes.POINTER(_PartitionPlan), ctypes.c_int32]
+        lib.tt_tree_attn_partitioned_fwd.restype = ctypes.c_int32
+        lib.tt_tree_attn_partitioned_fwd.argtypes = [ctypes.POINTER(_AttnDesc), ctypes.POINTER(_PartitionPlan)] + [_vp] * 5 + [_vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_attn_partitioned_bwd.restype = ctypes.c_int32
+        lib.tt_tree_attn_partitioned_bwd.argtypes = [ctypes.POINTER(_AttnDesc), ctypes.POINTER(_PartitionPlan)] + [_vp] * 9 + [_vp, ctypes.c_size_t, _vp]
         lib.tt_kernel_timing_enable.restype = ctypes.c_int32
         lib.tt_kernel_timing_enable.argtypes = [ctypes.c_int32]
         lib.tt_kernel_timing_read.restype = ctypes.c_int32
@@ -85,7 +106,7 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce", "loss_bwd", "rope")
+                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter")
 
 
 class _KernelTimes(ctypes.Structure):
@@ -183,6 +204,75 @@ def tree_build_meta(parent, seg_len, trained=None, root_pos_offset=None, g_overr
         _hp(m.node_g), _hp(m.tok_node), _hp(m.tok_pos), _hp(m.tok_pred), _hp(m.tok_weight),
         _hp(m.kend), _hp(m.ktile_kend_min), _hp(m.ktile_kend_max)))
     return m
+
+
+@dataclass
+class PartitionPlan:
+    """Outputs of tt_tree_partition_plan (numpy, host).  `device` holds torch copies of the five arrays the
+    device driver reads, once to_device() was called."""
+    n_parts: int
+    n_tokens: int
+    capacity: int
+    max_part_tokens: int
+    max_prefix: int
+    part_of_node: np.ndarray
+    part_node_off: np.ndarray
+    part_nodes: np.ndarray
+    part_parent: np.ndarray
+    part_cut_node: np.ndarray
+    part_pos_offset: np.ndarray
+    part_tok_off: np.ndarray
+    own_tok: np.ndarray
+    part_prefix_off: np.ndarray
+    prefix_tok: np.ndarray
+    prefix_visible: np.ndarray
+    kend: np.ndarray
+    part_ktile_off: np.ndarray
+    kt_min: np.ndarray
+    kt_max: np.ndarray
+    device: Optional[dict] = None
+
+    def to_device(self, device="cuda"):
+        torch = _torch()
+        self.device = {name: torch.from_numpy(getattr(self, name)).to(device)
+                       for name in ("own_tok", "prefix_tok", "kend", "kt_min", "kt_max")}
+        return self
+
+    def _c(self) -> _PartitionPlan:
+        if self.device is None:
+            raise ValueError("call to_device() on the plan first")
+        d = self.device
+        return _PartitionPlan(self.n_parts, self.n_tokens, _hp(self.part_tok_off), _hp(self.part_prefix_off),
+                              _hp(self.part_ktile_off), *(ctypes.c_void_p(d[n].data_ptr()) for n in
+                                                         ("own_tok", "prefix_tok", "kend", "kt_min", "kt_max")))
+
+
+def tree_partition_sizes(parent, seg_len, capacity: int) -> dict:
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    out = _PartitionSizes()
+    _check(_lib().tt_tree_partition_sizes(len(parent), _hp(parent), _hp(seg_len), int(capacity), ctypes.byref(out)))
+    return {f: int(getattr(out, f)) for f, _ in _PartitionSizes._fields_}
+
+
+def tree_partition_plan(parent, seg_len, capacity: int) -> PartitionPlan:
+    """Cuts the tree into partitions of at most `capacity` tokens and lays out everything the partitioned
+    attention calls need (host only)."""
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    if len(parent) != len(seg_len):
+        raise ValueError("parent and seg_len differ in length")
+    sz = tree_partition_sizes(parent, seg_len, capacity)
+    n, npart, ntok = len(parent), sz["n_parts"], sz["n_tokens"]
+    arr = dict(
+        part_of_node=np.zeros(n, np.int32), part_node_off=np.zeros(npart + 1, np.int32), part_nodes=np.zeros(n, np.int32),
+        part_parent=np.zeros(npart, np.int32), part_cut_node=np.zeros(npart, np.int32),
+        part_pos_offset=np.zeros(npart, np.int32), part_tok_off=np.zeros(npart + 1, np.int32),
+        own_tok=np.zeros(ntok, np.int32), part_prefix_off=np.zeros(npart + 1, np.int64),
+        prefix_tok=np.zeros(sz["sum_prefix"], np.int32), prefix_visible=np.zeros(sz["sum_prefix"], np.uint8),
+        kend=np.zeros(sz["sum_prefix"] + ntok, np.int32), part_ktile_off=np.zeros(npart + 1, np.int64),
+        kt_min=np.zeros(sz["sum_ktiles"], np.int32), kt_max=np.zeros(sz["sum_ktiles"], np.int32))
+    _check(_lib().tt_tree_partition_plan(n, _hp(parent), _hp(seg_len), int(capacity), *(_hp(a) for a in arr.values())))
+    return PartitionPlan(n_parts=npart, n_tokens=ntok, capacity=int(capacity), max_part_tokens=sz["max_part_tokens"],
+                         max_prefix=sz["max_prefix"], **arr)
 
 
 # ---- device calls -----------------------------------------------------------------------------
@@ -342,3 +432,58 @@ def tree_weighted_logprob_bwd(logits, target, weight, lse, *, grad_scale: float 
         logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(lse), float(grad_scale), _dp(out),
         out.stride(0) if n > 1 else vocab, _stream_ptr(stream)))
     return out
+
+
+def tree_attn_partitioned_workspace(q, k, v, plan: PartitionPlan, backward: bool = False, scale=None,
+                                    reference_kernels: bool = False) -> int:
+    d = _desc(q, k, v, 0, scale, reference_kernels)
+    c = plan._c()
+    return int(_lib().tt_tree_attn_partitioned_workspace(ctypes.byref(d), ctypes.byref(c), 1 if backward else 0))
+
+
+def _part_workspace(desc, cplan, backward, workspace, device):
+    torch = _torch()
+    need = int(_lib().tt_tree_attn_partitioned_workspace(ctypes.byref(desc), ctypes.byref(cplan), 1 if backward else 0))
+    if need == 0:
+        raise TreeTrainError(-2, last_error())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
+def tree_attn_partitioned_fwd(q, k, v, plan: PartitionPlan, *, scale=None, o=None, lse=None, workspace=None,
+                              stream=None, reference_kernels: bool = False):
+    """Whole-tree q [N,hq,d], k, v [N,hkv,d] in whole-tree DFS order; one attention pass per partition of
+    `plan`.  Returns (o [N,hq,d], lse [hq,N])."""
+    torch = _torch()
+    desc = _desc(q, k, v, 0, scale, reference_kernels)
+    cplan = plan._c()
+    if o is None:
+        o = torch.empty((desc.n_q, desc.hq, desc.d), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((desc.hq, desc.n_q), dtype=torch.float32, device=q.device)
+    workspace, ws_bytes = _part_workspace(desc, cplan, False, workspace, q.device)
+    _check(_lib().tt_tree_attn_partitioned_fwd(ctypes.byref(desc), ctypes.byref(cplan), _dp(q), _dp(k), _dp(v),
+                                               _dp(o), _dp(lse), _dp(workspace), ws_bytes, _stream_ptr(stream)))
+    return o, lse
+
+
+def tree_attn_partitioned_bwd(q, k, v, plan: PartitionPlan, o, d_o, lse, *, scale=None, dq=None, dk=None, dv=None,
+                              workspace=None, stream=None, reference_kernels: bool = False):
+    """Returns whole-tree (dq, dk, dv); cached-key gradients of all partitions are summed in fp32 inside."""
+    torch = _torch()
+    desc = _desc(q, k, v, 0, scale, reference_kernels)
+    cplan = plan._c()
+    if not (o.is_contiguous() and d_o.is_contiguous() and lse.is_contiguous()):
+        raise ValueError("o, d_o, lse must be contiguous")
+    if dq is None:
+        dq = torch.empty((desc.n_q, desc.hq, desc.d), dtype=q.dtype, device=q.device)
+    if dk is None:
+        dk = torch.empty((desc.n_q, desc.hkv, desc.d), dtype=q.dtype, device=q.device)
+    if dv is None:
+        dv = torch.empty((desc.n_q, desc.hkv, desc.d), dtype=q.dtype, device=q.device)
+    workspace, ws_bytes = _part_workspace(desc, cplan, True, workspace, q.device)
+    _check(_lib().tt_tree_attn_partitioned_bwd(ctypes.byref(desc), ctypes.byref(cplan), _dp(q), _dp(k), _dp(v),
+                                               _dp(o), _dp(d_o), _dp(lse), _dp(dq), _dp(dk), _dp(dv),
+                                               _dp(workspace), ws_bytes, _stream_ptr(stream)))
+    return dq, dk, dv

@@ -19,7 +19,11 @@ size_t delta_bytes(const tt_attn_desc* d) {
   return ((size_t)d->hq * (size_t)d->n_q * sizeof(float) + 255) & ~(size_t)255;
 }
 
-tt_status check_desc(const tt_attn_desc* d) {
+tt_status check_desc(const tt_attn_desc* d) { return tt::check_attn_desc(d); }
+
+}  // namespace
+
+tt_status tt::check_attn_desc(const tt_attn_desc* d) {
   if (!d) return fail(TT_ERR_NULL, "desc is NULL");
   if (d->dtype != TT_DTYPE_BF16 && d->dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", d->dtype);
   if (d->n_q < 0 || d->n_prefix < 0 || (int64_t)d->n_q + d->n_prefix >= INT32_MAX)
@@ -37,6 +41,8 @@ tt_status check_desc(const tt_attn_desc* d) {
   if (qs % 8 || ks % 8 || vs % 8) return fail(TT_ERR_ALIGN, "token strides must be multiples of 8 elements");
   return TT_OK;
 }
+
+namespace {
 
 bool mfma_supported(const tt_attn_desc* d) {
   return d->dtype == TT_DTYPE_BF16 && d->d == 128 && !(d->flags & TT_FLAG_REFERENCE_KERNELS);

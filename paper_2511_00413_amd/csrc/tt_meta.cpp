@@ -6,17 +6,8 @@
 #include <vector>
 #include "tt_internal.h"
 
-namespace {
+namespace tt {
 
-struct Forest {
-  std::vector<int32_t> first_child, next_sibling, roots;   // input numbering
-  std::vector<int32_t> order;                              // order[rank] = input id
-  std::vector<int32_t> rank;                               // rank[input id]
-  int64_t n_tokens = 0;
-  int32_t n_leaves = 0;
-};
-
-// Validates the parent array and produces the pre-order.  Children keep ascending input id.
 tt_status build_forest(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t n_prefix,
                        Forest& f) {
   if (n_nodes < 0 || n_prefix < 0) return tt::fail(TT_ERR_SHAPE, "n_nodes=%d, n_prefix=%d must be >= 0", n_nodes, n_prefix);
@@ -58,6 +49,13 @@ tt_status build_forest(int32_t n_nodes, const int32_t* parent, const int32_t* se
   for (int32_t rk = 0; rk < n_nodes; rk++) f.rank[f.order[rk]] = rk;
   return TT_OK;
 }
+
+}  // namespace tt
+
+namespace {
+
+using tt::Forest;
+using tt::build_forest;
 
 int32_t n_ktiles_of(int64_t n_prefix, int64_t n_tokens) {
   return (int32_t)(tt::ceil_div(n_prefix, TT_KTILE) + tt::ceil_div(n_tokens, TT_KTILE));

@@ -128,3 +128,126 @@ def test_stitched_partitions_equal_whole_tree(seed, cap, dtype):
     print("   rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
     for key, e in errs.items():
         assert e <= tol[key], (key, e)
+
+
+# ---- the partition driver inside the library: planner + one call for the whole tree ----
+
+def _whole_tree_case(seed, n_nodes, lo, hi, dtype, p_zero=0.0, n_roots=1, shuffle=False):
+    tree = W.random_tree(seed, n_nodes=n_nodes, lo=lo, hi=hi, shuffle=shuffle, p_zero=p_zero, n_roots=n_roots)
+    d = 128 if dtype == "bf16" else 64
+    dims = W.AttnDims(4, 2, d, dtype, 0.5 if dtype == "bf16" else 1.0)
+    whole = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = whole["n_tokens"]
+    q, k, v, do = W.attn_inputs(n, n, dims, seed)
+    return tree, dims, whole, n, q, k, v, do
+
+
+def _tol(dtype):
+    if dtype == "bf16":
+        return dict(o=1e-2, lse=1e-2, dq=2e-2, dk=2e-2, dv=2e-2)
+    return dict.fromkeys(("o", "lse", "dq", "dk", "dv"), 1e-5)
+
+
+@pytest.mark.parametrize("seed,cap,dtype,kw", [
+    (11, 700, "bf16", {}),
+    (12, 300, "bf16", dict(shuffle=True)),
+    (13, 450, "bf16", dict(p_zero=0.2, n_roots=2)),
+    (14, 500, "fp32", {}),
+])
+def test_library_driver_equals_whole_tree_oracle(seed, cap, dtype, kw):
+    tree, dims, whole, n, q, k, v, do = _whole_tree_case(400 + seed, 16, 20, 260, dtype, **kw)
+    want = A.branches(whole, q.float(), k.float(), v.float(), do.float())
+    plan = T.tree_partition_plan(tree.parent, tree.seg_len, cap).to_device()
+    assert plan.n_parts >= 3 and plan.max_prefix > 0
+    print(f"[case] library driver seed={seed} cap={cap} {dtype}: {plan.n_parts} partitions, N={n}, "
+          f"longest slice {plan.max_prefix}", flush=True)
+    qd, kd, vd, dod = (x.cuda() for x in (q, k, v, do))
+    o, lse = T.tree_attn_partitioned_fwd(qd, kd, vd, plan)
+    dq, dk, dv = T.tree_attn_partitioned_bwd(qd, kd, vd, plan, o, dod, lse)
+    torch.cuda.synchronize()
+    got = dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+    errs = {key: rel_l2(got[key].float().cpu().numpy(), want[key]) for key in got}
+    print("   rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
+    for key, e in errs.items():
+        assert e <= _tol(dtype)[key], (key, e)
+    # a second call with the same workspace contents left behind gives the same bits
+    o2, lse2 = T.tree_attn_partitioned_fwd(qd, kd, vd, plan)
+    dq2, dk2, dv2 = T.tree_attn_partitioned_bwd(qd, kd, vd, plan, o2, dod, lse2)
+    torch.cuda.synchronize()
+    for a, b in ((o, o2), (lse, lse2), (dq, dq2), (dk, dk2), (dv, dv2)):
+        assert torch.equal(a, b)
+
+
+def test_library_driver_single_partition_is_the_plain_call():
+    """Capacity >= N: one partition, identity gather; bit-identical to tt_tree_attn_fwd / bwd."""
+    tree, dims, whole, n, q, k, v, do = _whole_tree_case(431, 12, 30, 200, "bf16")
+    plan = T.tree_partition_plan(tree.parent, tree.seg_len, n).to_device()
+    assert plan.n_parts == 1 and plan.max_prefix == 0
+    meta = T.tree_build_meta(tree.parent, tree.seg_len, tree.trained)
+    kend, kmin, kmax = (torch.from_numpy(x).cuda() for x in (meta.kend, meta.ktile_kend_min, meta.ktile_kend_max))
+    qd, kd, vd, dod = (x.cuda() for x in (q, k, v, do))
+    print(f"[case] library driver single partition N={n}", flush=True)
+    o, lse = T.tree_attn_partitioned_fwd(qd, kd, vd, plan)
+    dq, dk, dv = T.tree_attn_partitioned_bwd(qd, kd, vd, plan, o, dod, lse)
+    o1, lse1 = T.tree_attn_fwd(qd, kd, vd, kend, kmin, kmax)
+    dq1, dk1, dv1 = T.tree_attn_bwd(qd, kd, vd, kend, kmin, kmax, o1, dod, lse1)
+    torch.cuda.synchronize()
+    for a, b in ((o, o1), (lse, lse1), (dq, dq1), (dk, dk1), (dv, dv1)):
+        assert torch.equal(a, b)
+
+
+def test_library_driver_strided_qkv_and_sampled_rows():
+    """q, k, v as slices of one fused [N, (hq+2hkv)*d] buffer; a mid-size tree (several key tiles per
+    partition), checked on sampled query rows / key rows against the oracle's row-wise functions."""
+    tree = W.random_tree(777, n_nodes=40, lo=100, hi=900, shuffle=False)
+    dims = W.AttnDims(8, 2, 128, "bf16", 0.5)
+    whole = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = whole["n_tokens"]
+    q, k, v, do = W.attn_inputs(n, n, dims, 777)
+    fused = torch.cat([q.reshape(n, -1), k.reshape(n, -1), v.reshape(n, -1)], dim=1).cuda()
+    hq, hkv, d = dims.hq, dims.hkv, dims.d
+    qd = fused[:, :hq * d].view(n, hq, d)
+    kd = fused[:, hq * d:(hq + hkv) * d].view(n, hkv, d)
+    vd = fused[:, (hq + hkv) * d:].view(n, hkv, d)
+    assert not qd.is_contiguous()
+    plan = T.tree_partition_plan(tree.parent, tree.seg_len, 4096).to_device()
+    print(f"[case] library driver fused qkv N={n}: {plan.n_parts} partitions, longest slice {plan.max_prefix}", flush=True)
+    assert plan.n_parts >= 4
+    dod = do.cuda()
+    o, lse = T.tree_attn_partitioned_fwd(qd, kd, vd, plan)
+    dq, dk, dv = T.tree_attn_partitioned_bwd(qd, kd, vd, plan, o, dod, lse)
+    # the plain whole-tree call on the same tensors: same kernels, other tiling / summation order
+    meta = T.tree_build_meta(tree.parent, tree.seg_len, tree.trained)
+    kend, kmin, kmax = (torch.from_numpy(x).cuda() for x in (meta.kend, meta.ktile_kend_min, meta.ktile_kend_max))
+    o1, lse1 = T.tree_attn_fwd(qd, kd, vd, kend, kmin, kmax)
+    dq1, dk1, dv1 = T.tree_attn_bwd(qd, kd, vd, kend, kmin, kmax, o1, dod, lse1)
+    torch.cuda.synchronize()
+    for name, a, b in (("o", o, o1), ("lse", lse, lse1), ("dq", dq, dq1), ("dk", dk, dk1), ("dv", dv, dv1)):
+        e = rel_l2(a.float().cpu().numpy(), b.float().cpu().numpy())
+        print(f"   partitioned vs whole-tree call {name}: {e:.2e}", flush=True)
+        assert e <= 1e-2, (name, e)
+    rng = np.random.default_rng(5)
+    rows = np.sort(rng.choice(n, 48, replace=False))
+    keys = np.sort(rng.choice(n, 48, replace=False))
+    for kvh in range(hkv):
+        r = A.rows(whole, q.float(), k.float(), v.float(), do.float(), kvh, rows, keys)
+        G = hq // hkv
+        hs = slice(kvh * G, (kvh + 1) * G)
+        assert rel_l2(o[rows][:, hs].float().cpu().numpy(), r["o"]) <= 1e-2
+        assert rel_l2(lse[hs][:, rows].T.cpu().numpy(), r["lse"]) <= 1e-2
+        assert rel_l2(dq[rows][:, hs].float().cpu().numpy(), r["dq"]) <= 2e-2
+        assert rel_l2(dk[keys][:, kvh].float().cpu().numpy(), r["dk"]) <= 2e-2
+        assert rel_l2(dv[keys][:, kvh].float().cpu().numpy(), r["dv"]) <= 2e-2
+
+
+def test_library_driver_errors():
+    tree, dims, whole, n, q, k, v, do = _whole_tree_case(440, 8, 20, 100, "bf16")
+    plan = T.tree_partition_plan(tree.parent, tree.seg_len, 150).to_device()
+    qd, kd, vd = (x.cuda() for x in (q, k, v))
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(T.TreeTrainError) as e:
+        T.tree_attn_partitioned_fwd(qd, kd, vd, plan, workspace=small)
+    assert e.value.status == -6
+    with pytest.raises(T.TreeTrainError) as e:                  # plan of another tree size
+        T.tree_attn_partitioned_fwd(qd[:-1], kd[:-1], vd[:-1], plan)
+    assert e.value.status == -2
