@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--no-linearized", action="store_true")
     ap.add_argument("--no-loss", action="store_true")
     ap.add_argument("--no-rope", action="store_true")
+    ap.add_argument("--no-partitioned", action="store_true")
+    ap.add_argument("--partition-capacity", type=int, default=0,
+                    help="token capacity for the partitioned leg (0 = about a quarter of the tree)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (a known-size kernel "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -260,6 +263,60 @@ def main():
         lin["speedup_over_r_pair"] = round(lin["speedup"] / lin["r_pair"], 3)
         del ql, kl, vl, dol, ol, dql, dkl, dvl
 
+    # ---------------- the same tree cut into partitions (boundary overhead) ----------------
+    part = None
+    if not args.no_partitioned and n_prefix == 0 and dims.dtype == "bf16":
+        cap = args.partition_capacity or max(1024, (N // 4 + 1023) // 1024 * 1024)
+        t0p = time.perf_counter()
+        plan = T.tree_partition_plan(tree.parent, tree.seg_len, cap)
+        plan_ms = (time.perf_counter() - t0p) * 1e3
+        plan.to_device(dev)
+        wsp = torch.empty(T.tree_attn_partitioned_workspace(q, k, v, plan, True), dtype=torch.uint8, device=dev)
+        op = torch.empty_like(q); lsep = torch.empty_like(lse)
+        dqp = torch.empty_like(q); dkp_ = torch.empty_like(k); dvp_ = torch.empty_like(v)
+        n_it = max(3, min(args.steps, 10))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        def part_step():
+            T.tree_attn_partitioned_fwd(q, k, v, plan, o=op, lse=lsep, workspace=wsp)
+            T.tree_attn_partitioned_bwd(q, k, v, plan, op, do, lsep, dq=dqp, dk=dkp_, dv=dvp_, workspace=wsp)
+        for it in range(2 + n_it):
+            if it == 2:
+                e0.record()
+            part_step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_part = e0.elapsed_time(e1) / n_it
+        T.kernel_timing_enable(True)               # a second pass for the per-kernel split
+        for it in range(n_it):
+            part_step()
+        pt = T.kernel_timing_read()
+        T.kernel_timing_enable(False)
+        # bytes the copy kernels move per fwd+bwd (each row read once and written once)
+        esz_a = 2
+        q_row, kv_row, kvf = dims.hq * dims.d * esz_a, dims.hkv * dims.d * esz_a, dims.hkv * dims.d * 4
+        own = np.diff(plan.part_tok_off).astype(np.int64)
+        pre = np.diff(plan.part_prefix_off).astype(np.int64)
+        own_g = own * (plan.part_own_start < 0)          # rows that are gathered / scattered (not used in place)
+        pre_g = pre * (plan.part_prefix_start < 0)
+        gather_b = int((2 * (own_g * (q_row + 2 * kv_row) + pre_g * 2 * kv_row)).sum()                # forward
+                       + (2 * (own_g * (3 * q_row + 2 * kv_row) + pre_g * 2 * kv_row)).sum() + 2 * dims.hq * N * 4)
+        scatter_b = int((2 * own_g * q_row).sum() + 2 * dims.hq * N * 4                                  # forward
+                        + (2 * own_g * (q_row + 2 * kv_row)).sum() + (pre_g * 2 * kvf).sum()             # results, zeroing
+                        + (pre_g * 2 * 3 * kvf).sum()                                                    # accumulate
+                        + 2 * N * kvf + 2 * N * (kvf + 2 * kv_row))                                      # clear, finalise
+        move_ms = (pt["part_gather"][0] + pt["part_scatter"][0]) / n_it
+        part = {"capacity": cap, "n_parts": plan.n_parts, "max_prefix": plan.max_prefix,
+                "in_place_own": int((plan.part_own_start >= 0).sum()), "in_place_prefix": int((plan.part_prefix_start >= 0).sum()),
+                "sum_prefix": int(plan.part_prefix_off[-1]), "ms_fwd_bwd": round(ms_part, 4),
+                "ms_whole_fwd_bwd": round(ms_fwd + ms_bwd, 4),
+                "ratio_to_whole": round(ms_part / (ms_fwd + ms_bwd), 3),
+                "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
+                "ms_gather": round(pt["part_gather"][0] / n_it, 4), "ms_scatter": round(pt["part_scatter"][0] / n_it, 4),
+                "movement_gb": round((gather_b + scatter_b) / 1e9, 4),
+                "movement_hbm_gbps": round((gather_b + scatter_b) / (move_ms * 1e-3) / 1e9, 1) if move_ms > 0 else None,
+                "ms_host_plan": round(plan_ms, 3)}
+        del op, lsep, dqp, dkp_, dvp_, wsp
+
     # ---------------- CPU oracle on a bounded sample (context only) ----------------
     cpu = None
     if not args.no_cpu_baseline and n_prefix == 0:
@@ -309,6 +366,7 @@ def main():
         "loss_bwd_hbm_gbps": None if loss_bwd_gbps is None else round(loss_bwd_gbps, 1),
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,
+        "partitioned": part,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -220,6 +220,9 @@ tt_status tt_tree_attn_bwd(const tt_attn_desc* desc,
  *   part_cut_node[n_parts]      n_c (input id), -1
  *   part_pos_offset[n_parts]
  *   part_tok_off[n_parts+1], own_tok[n_tokens]      own tokens per partition, its DFS order
+ *   part_own_start[n_parts]     first own token if the partition's own tokens are one ascending run
+ *                               of whole-tree indices (then no gather is needed), else -1
+ *   part_prefix_start[n_parts]  the same for the cached slice (-1 also for an empty slice)
  *   part_prefix_off[n_parts+1], prefix_tok[sum_prefix], prefix_visible[sum_prefix]
  *   kend[sum_prefix + n_tokens] partition p's bounds on its [slice ; own] key axis start at
  *                               part_prefix_off[p] + part_tok_off[p]; same meaning as the kend of
@@ -246,18 +249,21 @@ tt_status tt_tree_partition_plan(int32_t n_nodes, const int32_t* parent, const i
                                  int32_t* part_parent, int32_t* part_cut_node, int32_t* part_pos_offset,
                                  int32_t* part_tok_off, int32_t* own_tok,
                                  int64_t* part_prefix_off, int32_t* prefix_tok, uint8_t* prefix_visible,
-                                 int32_t* kend, int64_t* part_ktile_off, int32_t* kt_min, int32_t* kt_max);
+                                 int32_t* kend, int64_t* part_ktile_off, int32_t* kt_min, int32_t* kt_max,
+                                 int32_t* part_own_start, int32_t* part_prefix_start);
 
 /* Partitioned tree attention (device): the whole tree in one call, one attention pass per
  * partition.  Tensors are whole-tree tensors in whole-tree DFS order, exactly as for
  * tt_tree_attn_fwd / tt_tree_attn_bwd with n_prefix = 0 (desc->n_q = plan->n_tokens,
  * desc->n_prefix = 0), and the results equal those calls' results up to floating-point summation
  * order.  Per partition the driver gathers the partition's rows and its cached slice, runs the
- * attention kernels with the plan's bounds, and scatters the results back.  The backward visits
+ * attention kernels with the plan's bounds, and scatters the results back; where the plan marks
+ * the rows as one contiguous run (part_own_start / part_prefix_start) the kernels read and write
+ * the whole-tree tensors in place instead.  The backward visits
  * partitions children first (Appendix "Backward Pass"), adds every partition's cached-key
  * gradients into whole-tree fp32 accumulators (Appendix "Float32 Gradient Accumulation") and
  * rounds dk / dv once at the end: dk = own-partition dk + accumulated cached-key gradients.
- *   plan: the three offset tables are HOST arrays, the five index / bound arrays are DEVICE
+ *   plan: the offset tables and run starts are HOST arrays, the five index / bound arrays are DEVICE
  *   copies of the planner's outputs of the same names.
  * Errors: as the attention calls; TT_ERR_SHAPE if the plan's sizes disagree with desc. */
 typedef struct {
@@ -266,6 +272,8 @@ typedef struct {
   const int32_t* part_tok_off;      /* host   [n_parts+1] */
   const int64_t* part_prefix_off;   /* host   [n_parts+1] */
   const int64_t* part_ktile_off;    /* host   [n_parts+1] */
+  const int32_t* part_own_start;    /* host   [n_parts], or NULL = always gather */
+  const int32_t* part_prefix_start; /* host   [n_parts], or NULL = always gather */
   const int32_t* own_tok;           /* device [n_tokens]  */
   const int32_t* prefix_tok;        /* device [sum_prefix] */
   const int32_t* kend;              /* device [sum_prefix + n_tokens] */

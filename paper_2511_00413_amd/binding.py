@@ -38,6 +38,7 @@ class _PartitionSizes(ctypes.Structure):
 class _PartitionPlan(ctypes.Structure):
     _fields_ = [("n_parts", ctypes.c_int32), ("n_tokens", ctypes.c_int32),
                 ("part_tok_off", _vp), ("part_prefix_off", _vp), ("part_ktile_off", _vp),
+                ("part_own_start", _vp), ("part_prefix_start", _vp),
                 ("own_tok", _vp), ("prefix_tok", _vp), ("kend", _vp), ("kt_min", _vp), ("kt_max", _vp)]
 
 
@@ -90,7 +91,7 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
         lib.tt_tree_partition_sizes.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.POINTER(_PartitionSizes)]
         lib.tt_tree_partition_plan.restype = ctypes.c_int32
-        lib.tt_tree_partition_plan.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32] + [_vp] * 15
+        lib.tt_tree_partition_plan.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32] + [_vp] * 17
         lib.tt_tree_attn_partitioned_workspace.restype = ctypes.c_size_t
         lib.tt_tree_attn_partitioned_workspace.argtypes = [ctypes.POINTER(_AttnDesc), ctypes.POINTER(_PartitionPlan), ctypes.c_int32]
         lib.tt_tree_attn_partitioned_fwd.restype = ctypes.c_int32
@@ -230,7 +231,10 @@ class PartitionPlan:
     part_ktile_off: np.ndarray
     kt_min: np.ndarray
     kt_max: np.ndarray
+    part_own_start: np.ndarray
+    part_prefix_start: np.ndarray
     device: Optional[dict] = None
+    in_place: bool = True          # False: the driver gathers every partition (for cross-checks)
 
     def to_device(self, device="cuda"):
         torch = _torch()
@@ -243,7 +247,8 @@ class PartitionPlan:
             raise ValueError("call to_device() on the plan first")
         d = self.device
         return _PartitionPlan(self.n_parts, self.n_tokens, _hp(self.part_tok_off), _hp(self.part_prefix_off),
-                              _hp(self.part_ktile_off), *(ctypes.c_void_p(d[n].data_ptr()) for n in
+                              _hp(self.part_ktile_off), _hp(self.part_own_start) if self.in_place else None,
+                              _hp(self.part_prefix_start) if self.in_place else None, *(ctypes.c_void_p(d[n].data_ptr()) for n in
                                                          ("own_tok", "prefix_tok", "kend", "kt_min", "kt_max")))
 
 
@@ -269,7 +274,8 @@ def tree_partition_plan(parent, seg_len, capacity: int) -> PartitionPlan:
         own_tok=np.zeros(ntok, np.int32), part_prefix_off=np.zeros(npart + 1, np.int64),
         prefix_tok=np.zeros(sz["sum_prefix"], np.int32), prefix_visible=np.zeros(sz["sum_prefix"], np.uint8),
         kend=np.zeros(sz["sum_prefix"] + ntok, np.int32), part_ktile_off=np.zeros(npart + 1, np.int64),
-        kt_min=np.zeros(sz["sum_ktiles"], np.int32), kt_max=np.zeros(sz["sum_ktiles"], np.int32))
+        kt_min=np.zeros(sz["sum_ktiles"], np.int32), kt_max=np.zeros(sz["sum_ktiles"], np.int32),
+        part_own_start=np.zeros(npart, np.int32), part_prefix_start=np.zeros(npart, np.int32))
     _check(_lib().tt_tree_partition_plan(n, _hp(parent), _hp(seg_len), int(capacity), *(_hp(a) for a in arr.values())))
     return PartitionPlan(n_parts=npart, n_tokens=ntok, capacity=int(capacity), max_part_tokens=sz["max_part_tokens"],
                          max_prefix=sz["max_prefix"], **arr)

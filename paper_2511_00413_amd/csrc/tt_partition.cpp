@@ -189,7 +189,8 @@ extern "C" tt_status tt_tree_partition_plan(int32_t n_nodes, const int32_t* pare
                                             int32_t* part_parent, int32_t* part_cut_node, int32_t* part_pos_offset,
                                             int32_t* part_tok_off, int32_t* own_tok,
                                             int64_t* part_prefix_off, int32_t* prefix_tok, uint8_t* prefix_visible,
-                                            int32_t* kend, int64_t* part_ktile_off, int32_t* kt_min, int32_t* kt_max) {
+                                            int32_t* kend, int64_t* part_ktile_off, int32_t* kt_min, int32_t* kt_max,
+                                            int32_t* part_own_start, int32_t* part_prefix_start) {
   tt::clear_error();
   if ((kt_min || kt_max) && !(kt_min && kt_max))
     return tt::fail(TT_ERR_NULL, "kt_min and kt_max are written together; one of them is NULL");
@@ -207,6 +208,19 @@ extern "C" tt_status tt_tree_partition_plan(int32_t n_nodes, const int32_t* pare
   copy_out(part_prefix_off, pl.part_prefix_off);
   copy_out(prefix_tok, pl.prefix_tok);
   copy_out(prefix_visible, pl.prefix_visible);
+
+  // partitions whose rows are one ascending run of whole-tree indices need no gather
+  auto run_start = [](const int32_t* tok, int64_t n) -> int32_t {
+    if (n == 0) return -1;
+    for (int64_t j = 1; j < n; j++) if (tok[j] != tok[0] + j) return -1;
+    return tok[0];
+  };
+  for (int32_t p = 0; p < pl.n_parts; p++) {
+    if (part_own_start)
+      part_own_start[p] = run_start(pl.own_tok.data() + pl.part_tok_off[p], pl.part_tok_off[p + 1] - pl.part_tok_off[p]);
+    if (part_prefix_start)
+      part_prefix_start[p] = run_start(pl.prefix_tok.data() + pl.part_prefix_off[p], prefix_len[p]);
+  }
 
   // visibility bounds and their tile summaries, partition by partition
   std::vector<int32_t> ke;

@@ -152,13 +152,38 @@ Buffers carve(void* ws, const Dims& d, bool backward) {
   return b;
 }
 
-tt_attn_desc part_desc(const tt_attn_desc* whole, int32_t n_own, int32_t n_prefix) {
+// Descriptor of one partition's pass.  `in_place`: q, k, v are read from the whole-tree tensors
+// (their token strides apply); otherwise from gathered, contiguous rows.
+tt_attn_desc part_desc(const tt_attn_desc* whole, int32_t n_own, int32_t n_prefix, bool in_place = false) {
   tt_attn_desc d = *whole;
   d.n_q = n_own;
   d.n_prefix = n_prefix;
-  d.q_stride_tok = d.k_stride_tok = d.v_stride_tok = 0;      // gathered rows are contiguous
+  if (!in_place) d.q_stride_tok = d.k_stride_tok = d.v_stride_tok = 0;
   return d;
 }
+
+// One partition's view of the plan.
+struct Part {
+  int32_t t0, n_own, n_pre;
+  int64_t p0;
+  int32_t own_start;      // >= 0: own rows are whole-tree rows [own_start, own_start + n_own)
+  int32_t pre_start;      // >= 0: the cached slice is whole-tree rows [pre_start, pre_start + n_pre)
+};
+
+Part part_of(const tt_partition_plan* plan, int32_t p, bool kv_contiguous) {
+  Part x;
+  x.t0 = plan->part_tok_off[p];
+  x.n_own = plan->part_tok_off[p + 1] - x.t0;
+  x.p0 = plan->part_prefix_off[p];
+  x.n_pre = (int32_t)(plan->part_prefix_off[p + 1] - x.p0);
+  x.own_start = plan->part_own_start && x.n_own > 0 ? plan->part_own_start[p] : -1;
+  // the attention calls take the cached slice as contiguous rows, so in-place use needs unpadded k, v
+  x.pre_start = plan->part_prefix_start && kv_contiguous && x.n_pre > 0 ? plan->part_prefix_start[p] : -1;
+  return x;
+}
+
+inline const void* row_ptr(const void* base, int64_t row, int64_t stride_bytes) { return (const char*)base + row * stride_bytes; }
+inline void* row_ptr(void* base, int64_t row, int64_t stride_bytes) { return (char*)base + row * stride_bytes; }
 
 tt_status check_plan(const tt_attn_desc* desc, const tt_partition_plan* plan, bool backward, Dims& dm) {
   if (!desc || !plan) return fail(TT_ERR_NULL, "desc / plan is NULL");
@@ -181,6 +206,10 @@ tt_status check_plan(const tt_attn_desc* desc, const tt_partition_plan* plan, bo
     if (n_own < 0 || n_pre < 0 || n_own + n_pre >= INT32_MAX || plan->part_tok_off[p] < 0 || plan->part_tok_off[p + 1] > dm.n ||
         n_kt != tt::ceil_div(n_pre, TT_KTILE) + tt::ceil_div(n_own, TT_KTILE))
       return fail(TT_ERR_SHAPE, "plan offsets of partition %d are inconsistent", p);
+    if (plan->part_own_start && plan->part_own_start[p] >= 0 && (int64_t)plan->part_own_start[p] + n_own > dm.n)
+      return fail(TT_ERR_SHAPE, "part_own_start[%d]=%d runs past the last token", p, plan->part_own_start[p]);
+    if (plan->part_prefix_start && plan->part_prefix_start[p] >= 0 && (int64_t)plan->part_prefix_start[p] + n_pre > dm.n)
+      return fail(TT_ERR_SHAPE, "part_prefix_start[%d]=%d runs past the last token", p, plan->part_prefix_start[p]);
     dm.max_own = std::max<int32_t>(dm.max_own, (int32_t)n_own);
     dm.max_prefix = std::max<int32_t>(dm.max_prefix, (int32_t)n_pre);
     if (n_own > 0) {
@@ -277,26 +306,38 @@ extern "C" tt_status tt_tree_attn_partitioned_fwd(const tt_attn_desc* desc, cons
   const int64_t qs = stride_bytes(desc->q_stride_tok, desc->hq, desc->d, dm.esz);
   const int64_t ks = stride_bytes(desc->k_stride_tok, desc->hkv, desc->d, dm.esz);
   const int64_t vs = stride_bytes(desc->v_stride_tok, desc->hkv, desc->d, dm.esz);
+  const bool kv_contig = ks == (int64_t)dm.kv_row && vs == (int64_t)dm.kv_row;
   for (int32_t p = 0; p < dm.np; p++) {
-    const int32_t t0 = plan->part_tok_off[p], n_own = plan->part_tok_off[p + 1] - t0;
-    const int64_t p0 = plan->part_prefix_off[p];
-    const int32_t n_pre = (int32_t)(plan->part_prefix_off[p + 1] - p0);
-    if (n_own == 0) continue;
-    const int32_t* own = plan->own_tok + t0;
-    const int32_t* pre = n_pre ? plan->prefix_tok + p0 : nullptr;
-    mv.gather(q, qs, own, n_own, dm.q_row, b.q);
-    mv.gather(k, ks, own, n_own, dm.kv_row, b.k);
-    mv.gather(v, vs, own, n_own, dm.kv_row, b.v);
-    mv.gather(k, ks, pre, n_pre, dm.kv_row, b.kp);
-    mv.gather(v, vs, pre, n_pre, dm.kv_row, b.vp);
+    const Part x = part_of(plan, p, kv_contig);
+    if (x.n_own == 0) continue;
+    const int32_t* own = plan->own_tok + x.t0;
+    const int32_t* pre = x.n_pre ? plan->prefix_tok + x.p0 : nullptr;
+    const bool own_ip = x.own_start >= 0, pre_ip = x.pre_start >= 0;
+    const void *qp = b.q, *kp = b.k, *vp = b.v, *kpre = nullptr, *vpre = nullptr;
+    void* op = b.o;
+    if (own_ip) {
+      qp = row_ptr(q, x.own_start, qs); kp = row_ptr(k, x.own_start, ks); vp = row_ptr(v, x.own_start, vs);
+      op = row_ptr(o, x.own_start, (int64_t)dm.q_row);
+    } else {
+      mv.gather(q, qs, own, x.n_own, dm.q_row, b.q);
+      mv.gather(k, ks, own, x.n_own, dm.kv_row, b.k);
+      mv.gather(v, vs, own, x.n_own, dm.kv_row, b.v);
+    }
+    if (pre_ip) {
+      kpre = row_ptr(k, x.pre_start, ks); vpre = row_ptr(v, x.pre_start, vs);
+    } else if (x.n_pre) {
+      mv.gather(k, ks, pre, x.n_pre, dm.kv_row, b.kp);
+      mv.gather(v, vs, pre, x.n_pre, dm.kv_row, b.vp);
+      kpre = b.kp; vpre = b.vp;
+    }
     if (tt_status s = hip_ok("partition gather")) return s;
-    const tt_attn_desc d = part_desc(desc, n_own, n_pre);
-    if (tt_status s = tt_tree_attn_fwd(&d, b.q, b.k, b.v, n_pre ? b.kp : nullptr, n_pre ? b.vp : nullptr,
-                                       plan->kend + p0 + t0, plan->kt_min + plan->part_ktile_off[p],
-                                       plan->kt_max + plan->part_ktile_off[p], b.o, b.lse, b.attn_ws, dm.attn_ws, stream))
+    const tt_attn_desc d = part_desc(desc, x.n_own, x.n_pre, own_ip);
+    if (tt_status s = tt_tree_attn_fwd(&d, qp, kp, vp, kpre, vpre,
+                                       plan->kend + x.p0 + x.t0, plan->kt_min + plan->part_ktile_off[p],
+                                       plan->kt_max + plan->part_ktile_off[p], op, b.lse, b.attn_ws, dm.attn_ws, stream))
       return s;
-    mv.scatter(b.o, own, n_own, dm.q_row, o);
-    mv.lse_scatter(b.lse, n_own, own, dm.n, desc->hq, lse);
+    if (!own_ip) mv.scatter(b.o, own, x.n_own, dm.q_row, o);
+    mv.lse_scatter(b.lse, x.n_own, own, dm.n, desc->hq, lse);
     if (tt_status s = hip_ok("partition scatter")) return s;
   }
   return TT_OK;
@@ -324,35 +365,56 @@ extern "C" tt_status tt_tree_attn_partitioned_bwd(const tt_attn_desc* desc, cons
     mv.zero(b.acc_dk, (size_t)dm.n * kv_floats * sizeof(float));
     mv.zero(b.acc_dv, (size_t)dm.n * kv_floats * sizeof(float));
   }
+  const bool kv_contig = ks == (int64_t)dm.kv_row && vs == (int64_t)dm.kv_row;
   for (int32_t p = dm.np - 1; p >= 0; p--) {          // children before parents
-    const int32_t t0 = plan->part_tok_off[p], n_own = plan->part_tok_off[p + 1] - t0;
-    const int64_t p0 = plan->part_prefix_off[p];
-    const int32_t n_pre = (int32_t)(plan->part_prefix_off[p + 1] - p0);
-    if (n_own == 0) continue;
-    const int32_t* own = plan->own_tok + t0;
-    const int32_t* pre = n_pre ? plan->prefix_tok + p0 : nullptr;
-    mv.gather(q, qs, own, n_own, dm.q_row, b.q);
-    mv.gather(k, ks, own, n_own, dm.kv_row, b.k);
-    mv.gather(v, vs, own, n_own, dm.kv_row, b.v);
-    mv.gather(o, (int64_t)dm.q_row, own, n_own, dm.q_row, b.o);
-    mv.gather(d_o, (int64_t)dm.q_row, own, n_own, dm.q_row, b.d_o);
-    mv.lse_gather(lse, dm.n, own, n_own, desc->hq, b.lse);
-    mv.gather(k, ks, pre, n_pre, dm.kv_row, b.kp);
-    mv.gather(v, vs, pre, n_pre, dm.kv_row, b.vp);
-    mv.zero(b.dkp, (size_t)n_pre * kv_floats * sizeof(float));
-    mv.zero(b.dvp, (size_t)n_pre * kv_floats * sizeof(float));
+    const Part x = part_of(plan, p, kv_contig);
+    if (x.n_own == 0) continue;
+    const int32_t* own = plan->own_tok + x.t0;
+    const int32_t* pre = x.n_pre ? plan->prefix_tok + x.p0 : nullptr;
+    const bool own_ip = x.own_start >= 0, pre_ip = x.pre_start >= 0;
+    const void *qp = b.q, *kp = b.k, *vp = b.v, *op = b.o, *dop = b.d_o, *kpre = nullptr, *vpre = nullptr;
+    void *dqp = b.dq, *dkp = b.dk, *dvp = b.dv;
+    float *dk_acc = nullptr, *dv_acc = nullptr;
+    if (own_ip) {
+      qp = row_ptr(q, x.own_start, qs); kp = row_ptr(k, x.own_start, ks); vp = row_ptr(v, x.own_start, vs);
+      op = row_ptr(o, x.own_start, (int64_t)dm.q_row); dop = row_ptr(d_o, x.own_start, (int64_t)dm.q_row);
+      dqp = row_ptr(dq, x.own_start, (int64_t)dm.q_row);
+      dkp = row_ptr(dk, x.own_start, (int64_t)dm.kv_row); dvp = row_ptr(dv, x.own_start, (int64_t)dm.kv_row);
+    } else {
+      mv.gather(q, qs, own, x.n_own, dm.q_row, b.q);
+      mv.gather(k, ks, own, x.n_own, dm.kv_row, b.k);
+      mv.gather(v, vs, own, x.n_own, dm.kv_row, b.v);
+      mv.gather(o, (int64_t)dm.q_row, own, x.n_own, dm.q_row, b.o);
+      mv.gather(d_o, (int64_t)dm.q_row, own, x.n_own, dm.q_row, b.d_o);
+    }
+    mv.lse_gather(lse, dm.n, own, x.n_own, desc->hq, b.lse);
+    if (pre_ip) {
+      // the kernels add straight into the whole-tree fp32 accumulators
+      kpre = row_ptr(k, x.pre_start, ks); vpre = row_ptr(v, x.pre_start, vs);
+      dk_acc = b.acc_dk + (size_t)x.pre_start * kv_floats; dv_acc = b.acc_dv + (size_t)x.pre_start * kv_floats;
+    } else if (x.n_pre) {
+      mv.gather(k, ks, pre, x.n_pre, dm.kv_row, b.kp);
+      mv.gather(v, vs, pre, x.n_pre, dm.kv_row, b.vp);
+      mv.zero(b.dkp, (size_t)x.n_pre * kv_floats * sizeof(float));
+      mv.zero(b.dvp, (size_t)x.n_pre * kv_floats * sizeof(float));
+      kpre = b.kp; vpre = b.vp; dk_acc = b.dkp; dv_acc = b.dvp;
+    }
     if (tt_status s = hip_ok("partition gather")) return s;
-    const tt_attn_desc d = part_desc(desc, n_own, n_pre);
-    if (tt_status s = tt_tree_attn_bwd(&d, b.q, b.k, b.v, n_pre ? b.kp : nullptr, n_pre ? b.vp : nullptr,
-                                       plan->kend + p0 + t0, plan->kt_min + plan->part_ktile_off[p],
-                                       plan->kt_max + plan->part_ktile_off[p], b.o, b.d_o, b.lse, b.dq, b.dk, b.dv,
-                                       n_pre ? b.dkp : nullptr, n_pre ? b.dvp : nullptr, b.attn_ws, dm.attn_ws, stream))
+    const tt_attn_desc d = part_desc(desc, x.n_own, x.n_pre, own_ip);
+    if (tt_status s = tt_tree_attn_bwd(&d, qp, kp, vp, kpre, vpre,
+                                       plan->kend + x.p0 + x.t0, plan->kt_min + plan->part_ktile_off[p],
+                                       plan->kt_max + plan->part_ktile_off[p], op, dop, b.lse, dqp, dkp, dvp,
+                                       dk_acc, dv_acc, b.attn_ws, dm.attn_ws, stream))
       return s;
-    mv.scatter(b.dq, own, n_own, dm.q_row, dq);
-    mv.scatter(b.dk, own, n_own, dm.kv_row, dk);
-    mv.scatter(b.dv, own, n_own, dm.kv_row, dv);
-    mv.scatter_add(b.dkp, pre, n_pre, kv_floats, b.acc_dk);
-    mv.scatter_add(b.dvp, pre, n_pre, kv_floats, b.acc_dv);
+    if (!own_ip) {
+      mv.scatter(b.dq, own, x.n_own, dm.q_row, dq);
+      mv.scatter(b.dk, own, x.n_own, dm.kv_row, dk);
+      mv.scatter(b.dv, own, x.n_own, dm.kv_row, dv);
+    }
+    if (!pre_ip && x.n_pre) {
+      mv.scatter_add(b.dkp, pre, x.n_pre, kv_floats, b.acc_dk);
+      mv.scatter_add(b.dvp, pre, x.n_pre, kv_floats, b.acc_dv);
+    }
     if (tt_status s = hip_ok("partition scatter")) return s;
   }
   if (any_prefix && dm.n > 0) {

@@ -29,6 +29,8 @@ def _compare(parent, seg, cap):
         assert np.array_equal(own, g["own_tok"])
         assert np.array_equal(got.prefix_tok[pre], g["prefix_tok"])
         assert np.array_equal(got.prefix_visible[pre], g["prefix_visible"])
+        run = lambda t: int(t[0]) if len(t) and np.array_equal(t, t[0] + np.arange(len(t))) else -1
+        assert got.part_own_start[p] == run(g["own_tok"]) and got.part_prefix_start[p] == run(g["prefix_tok"])
         # bounds and tile summaries = the oracle's metadata of the partition taken as a local tree
         local = {nid: i for i, nid in enumerate(parts[p])}
         lparent = [-1 if nid == parts[p][0] else local[parent[nid]] for nid in parts[p]]
