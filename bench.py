@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--no-loss", action="store_true")
     ap.add_argument("--no-rope", action="store_true")
     ap.add_argument("--no-partitioned", action="store_true")
+    ap.add_argument("--partition-gather-all", action="store_true",
+                    help="partitioned leg: gather / scatter every partition, also those that could be used in place")
     ap.add_argument("--partition-capacity", type=int, default=0,
                     help="token capacity for the partitioned leg (0 = about a quarter of the tree)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -271,6 +273,10 @@ def main():
         plan = T.tree_partition_plan(tree.parent, tree.seg_len, cap)
         plan_ms = (time.perf_counter() - t0p) * 1e3
         plan.to_device(dev)
+        if args.partition_gather_all:
+            plan.in_place = False
+            plan.part_own_start[:] = -1
+            plan.part_prefix_start[:] = -1
         wsp = torch.empty(T.tree_attn_partitioned_workspace(q, k, v, plan, True), dtype=torch.uint8, device=dev)
         op = torch.empty_like(q); lsep = torch.empty_like(lse)
         dqp = torch.empty_like(q); dkp_ = torch.empty_like(k); dvp_ = torch.empty_like(v)

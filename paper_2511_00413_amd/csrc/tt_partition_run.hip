@@ -8,9 +8,8 @@
 #include "tt_internal.h"
 #include "tt_kernels.h"
 
+namespace tt {
 namespace {
-
-using tt::fail;
 
 constexpr int COPY_THREADS = 256;
 
@@ -284,6 +283,9 @@ tt_status check_tensors(const tt_attn_desc* desc, const tt_partition_plan* plan,
 }
 
 }  // namespace
+}  // namespace tt
+
+using namespace tt;
 
 extern "C" size_t tt_tree_attn_partitioned_workspace(const tt_attn_desc* desc, const tt_partition_plan* plan, int32_t backward) {
   tt::clear_error();
