@@ -125,6 +125,7 @@ def dfs_meta(parent, seg_len, trained=None, root_pos_offset=None) -> Dict[str, o
         node_parent=np.asarray(node_parent, dtype=np.int32),
         node_pos0=np.asarray(node_pos0, dtype=np.int32),
         tok_node=tok_node, tok_pos=tok_pos, tok_pred=tok_pred, tok_weight=tok_weight,
+        tok_trained=np.asarray([trained[order[rk]] for rk in tok_node], dtype=np.uint8),
     )
 
 
@@ -254,3 +255,44 @@ def mask_chunks(meta) -> np.ndarray:
 def por(n_tree: int, n_base: int) -> float:
     """Potential Overlap Ratio, Eq. 12."""
     return 1.0 - n_tree / n_base
+
+
+WEIGHT_PATH_SUM, WEIGHT_UNIFORM, WEIGHT_PATH_TOKEN_MEAN = 0, 1, 2
+
+
+def path_weights(meta, scheme: int = WEIGHT_PATH_SUM, path_weight=None, advantage=None) -> np.ndarray:
+    """General per-token loss weights ("Derivation", last paragraph): with path weights w_k a token's
+    weight is the sum of w_k over the root-to-leaf paths that contain it, lambda_t = sum_{k: t in p_k} w_k;
+    untrained tokens get 0 (only model output is trained, Fig. 1); a per-token advantage (policy-gradient
+    objective, l_t = -A_t log p) multiplies in.  Written as the definition: one pass over every path.
+
+    scheme WEIGHT_PATH_SUM         w_k = path_weight[k], paths in DFS order of their leaves
+           WEIGHT_UNIFORM          lambda_t = 1 for every unique token (the paper's example of another objective)
+           WEIGHT_PATH_TOKEN_MEAN  w_k = 1 / (K * number of trained tokens on path k): every branch's loss is
+                                   its token mean, branches averaged (w_k = 0 for a branch without trained tokens)
+    Arithmetic: sums in fp64, one rounding to fp32, then the fp32 product with the advantage."""
+    n = meta["n_tokens"]
+    trained = np.asarray(meta["tok_trained"]) != 0
+    pl = paths(meta)
+    K = len(pl)
+    if scheme == WEIGHT_UNIFORM:
+        lam = np.ones(n, dtype=np.float64)
+    else:
+        if scheme == WEIGHT_PATH_SUM:
+            w = np.asarray(path_weight, dtype=np.float32).astype(np.float64)
+            assert len(w) == K
+        elif scheme == WEIGHT_PATH_TOKEN_MEAN:
+            w = np.zeros(K)
+            for k, p in enumerate(pl):
+                cnt = int(trained[p].sum())
+                w[k] = 1.0 / (float(K) * cnt) if cnt else 0.0
+        else:
+            raise ValueError("unknown scheme")
+        lam = np.zeros(n, dtype=np.float64)
+        for k, p in enumerate(pl):
+            for t in p:
+                lam[t] += w[k]
+    lam = np.where(trained, lam, 0.0).astype(np.float32)
+    if advantage is not None:
+        lam = lam * np.asarray(advantage, dtype=np.float32)
+    return lam.astype(np.float32)
