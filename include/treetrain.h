@@ -131,6 +131,33 @@ tt_status tt_tree_build_meta(int32_t n_nodes, const int32_t* parent, const int32
                              int32_t* kend, int32_t* ktile_kend_min, int32_t* ktile_kend_max);
 
 /* ------------------------------------------------------------------------------------------
+ * tt_tree_path_weights  (host only; needs no GPU)
+ *
+ * General per-token loss weights ("Derivation", last paragraph): with a weight w_k per
+ * root-to-leaf path, lambda_t = sum of w_k over the paths through t; the loss is then the single
+ * weighted sum over unique tokens that tt_tree_weighted_logprob computes.  tt_tree_build_meta's
+ * tok_weight is the special case w_k = 1/K.
+ *   scheme TT_WEIGHT_PATH_SUM         w_k = path_weight[k]; paths are numbered by the DFS order of
+ *                                     their leaves (leaf_node[k] gives the leaf's input id)
+ *          TT_WEIGHT_UNIFORM          lambda_t = 1 for every unique token
+ *          TT_WEIGHT_PATH_TOKEN_MEAN  w_k = 1 / (K * trained tokens on path k): each branch's loss
+ *                                     is its token mean, branches averaged; a branch without
+ *                                     trained tokens has w_k = 0
+ *   trained[n_nodes] or NULL (all trained): tokens of untrained nodes get weight 0.
+ *   advantage[n_tokens] or NULL: per-token advantage in DFS order (policy-gradient objective,
+ *                                l_t = -A_t log p), multiplied in as an fp32 product.
+ * Outputs (host): tok_weight[n_tokens] fp32 in DFS order; leaf_node[n_leaves] or NULL.
+ * Arithmetic: path sums in fp64, one rounding to fp32.
+ * Errors: TT_ERR_NULL, TT_ERR_SHAPE, TT_ERR_TREE, TT_ERR_UNSUPPORTED (unknown scheme).
+ * ------------------------------------------------------------------------------------------ */
+#define TT_WEIGHT_PATH_SUM        0
+#define TT_WEIGHT_UNIFORM         1
+#define TT_WEIGHT_PATH_TOKEN_MEAN 2
+tt_status tt_tree_path_weights(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                               const uint8_t* trained, int32_t scheme, const float* path_weight,
+                               const float* advantage, float* tok_weight, int32_t* leaf_node);
+
+/* ------------------------------------------------------------------------------------------
  * Tree attention (device).
  *
  * Forward, per query head:  S_ij = scale * <Q_i, K_j> on visible pairs, P = row softmax(S) in

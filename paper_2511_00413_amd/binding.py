@@ -88,6 +88,8 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_rope.restype = ctypes.c_int32
         lib.tt_tree_rope.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                      _vp, ctypes.c_float, ctypes.c_int32, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_path_weights.restype = ctypes.c_int32
+        lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
         lib.tt_tree_partition_sizes.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, ctypes.POINTER(_PartitionSizes)]
         lib.tt_tree_partition_plan.restype = ctypes.c_int32
@@ -205,6 +207,29 @@ def tree_build_meta(parent, seg_len, trained=None, root_pos_offset=None, g_overr
         _hp(m.node_g), _hp(m.tok_node), _hp(m.tok_pos), _hp(m.tok_pred), _hp(m.tok_weight),
         _hp(m.kend), _hp(m.ktile_kend_min), _hp(m.ktile_kend_max)))
     return m
+
+
+WEIGHT_PATH_SUM, WEIGHT_UNIFORM, WEIGHT_PATH_TOKEN_MEAN = 0, 1, 2
+
+
+def tree_path_weights(parent, seg_len, trained=None, *, scheme: int = WEIGHT_PATH_SUM, path_weight=None, advantage=None):
+    """General loss weights lambda_t = sum of path weights over the paths through t (host).
+    Returns (tok_weight [n_tokens] fp32, leaf_node [n_leaves] int32: the leaf of path k)."""
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    if len(parent) != len(seg_len):
+        raise ValueError("parent and seg_len differ in length")
+    trained = _np(trained, np.uint8)
+    sz = tree_meta_sizes(parent, seg_len)
+    path_weight, advantage = _np(path_weight, np.float32), _np(advantage, np.float32)
+    if path_weight is not None and len(path_weight) != sz["n_leaves"]:
+        raise ValueError(f"path_weight has {len(path_weight)} entries for {sz['n_leaves']} paths")
+    if advantage is not None and len(advantage) != sz["n_tokens"]:
+        raise ValueError("advantage must have one entry per token")
+    w = np.zeros(sz["n_tokens"], np.float32)
+    leaf = np.zeros(sz["n_leaves"], np.int32)
+    _check(_lib().tt_tree_path_weights(len(parent), _hp(parent), _hp(seg_len), _hp(trained), int(scheme), _hp(path_weight),
+                                       _hp(advantage), _hp(w), _hp(leaf)))
+    return w, leaf
 
 
 @dataclass

@@ -187,3 +187,46 @@ extern "C" tt_status tt_tree_build_meta(int32_t n_nodes, const int32_t* parent, 
   }
   return TT_OK;
 }
+
+extern "C" tt_status tt_tree_path_weights(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                          const uint8_t* trained, int32_t scheme, const float* path_weight,
+                                          const float* advantage, float* tok_weight, int32_t* leaf_node) {
+  tt::clear_error();
+  Forest f;
+  if (tt_status s = build_forest(n_nodes, parent, seg_len, 0, f)) return s;
+  if (scheme != TT_WEIGHT_PATH_SUM && scheme != TT_WEIGHT_UNIFORM && scheme != TT_WEIGHT_PATH_TOKEN_MEAN)
+    return tt::fail(TT_ERR_UNSUPPORTED, "unknown weight scheme %d", scheme);
+  if (scheme == TT_WEIGHT_PATH_SUM && f.n_leaves > 0 && !path_weight)
+    return tt::fail(TT_ERR_NULL, "path_weight is NULL for TT_WEIGHT_PATH_SUM");
+  if (f.n_tokens > 0 && !tok_weight) return tt::fail(TT_ERR_NULL, "tok_weight is NULL");
+  auto is_trained = [&](int32_t i) { return !trained || trained[i]; };
+
+  // w_k per leaf (fp64), leaves numbered in DFS order; then lambda of a node = sum over the leaves of
+  // its subtree, accumulated children-to-parent in reverse pre-order.
+  std::vector<double> lam(n_nodes, 0.0);
+  std::vector<int64_t> trained_above(n_nodes, 0);      // trained tokens on the path root .. node (pre-order rank)
+  const int32_t K = f.n_leaves;
+  int32_t leaf = 0;
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    const int64_t up = parent[i] < 0 ? 0 : trained_above[f.rank[parent[i]]];
+    trained_above[rk] = up + (is_trained(i) ? seg_len[i] : 0);
+    if (f.first_child[i] >= 0) continue;
+    if (leaf_node) leaf_node[leaf] = i;
+    if (scheme == TT_WEIGHT_PATH_SUM) lam[rk] = (double)path_weight[leaf];
+    else if (scheme == TT_WEIGHT_PATH_TOKEN_MEAN) lam[rk] = trained_above[rk] > 0 ? 1.0 / ((double)K * (double)trained_above[rk]) : 0.0;
+    leaf++;
+  }
+  for (int32_t rk = n_nodes - 1; rk >= 0; rk--) {
+    const int32_t i = f.order[rk];
+    if (parent[i] >= 0) lam[f.rank[parent[i]]] += lam[rk];
+  }
+  int64_t t = 0;
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    float w = scheme == TT_WEIGHT_UNIFORM ? 1.0f : (float)lam[rk];
+    if (!is_trained(i)) w = 0.0f;
+    for (int32_t j = 0; j < seg_len[i]; j++, t++) tok_weight[t] = advantage ? w * advantage[t] : w;
+  }
+  return TT_OK;
+}

@@ -149,3 +149,32 @@ def test_bwd_strided_rows():
     got = out_wide[:, :1024].float().cpu().numpy()
     assert np.sqrt(((got - want) ** 2).sum()) / np.sqrt((want ** 2).sum()) <= 4e-3
     assert float((out_wide[:, 1024:] - 7.0).abs().max()) == 0.0       # nothing written past the row
+
+
+@pytest.mark.parametrize("scheme", ["path_sum", "token_mean", "uniform"])
+def test_general_path_weights_against_branch_by_branch_loss(scheme):
+    """"Derivation", general path weights: the GPU's single weighted sum over unique tokens with
+    lambda from tt_tree_path_weights equals the loss evaluated branch by branch, each branch on its
+    own token list with its own weight (and advantages for the policy-gradient form)."""
+    t = W.random_tree(91, n_nodes=14, lo=3, hi=40, shuffle=True)
+    m = M.dfs_meta(t.parent, t.seg_len, t.trained)
+    n, K = m["n_tokens"], m["K"]
+    rng = np.random.default_rng(3)
+    adv = rng.normal(size=n).astype(np.float32)
+    logits, target = W.loss_inputs(n, 4096, 17, 2.0, "bf16")
+    wl, _ = L.log_softmax_gather(logits, target.numpy())
+    tr = m["tok_trained"].astype(np.float64)
+    paths = M.paths(m)
+    if scheme == "path_sum":
+        w = rng.uniform(0.1, 2.0, K).astype(np.float32)
+        lam, _ = T.tree_path_weights(t.parent, t.seg_len, t.trained, path_weight=w, advantage=adv)
+        want = sum(float(w[k]) * sum(tr[i] * adv[i] * -wl[i] for i in p) for k, p in enumerate(paths))
+    elif scheme == "token_mean":
+        lam, _ = T.tree_path_weights(t.parent, t.seg_len, t.trained, scheme=T.WEIGHT_PATH_TOKEN_MEAN)
+        want = sum(sum(tr[i] * -wl[i] for i in p) / tr[p].sum() for p in paths if tr[p].sum()) / K
+    else:
+        lam, _ = T.tree_path_weights(t.parent, t.seg_len, t.trained, scheme=T.WEIGHT_UNIFORM)
+        want = float((tr * -wl).sum())
+    print(f"[case] loss with general path weights, scheme {scheme}, N={n}, K={K}", flush=True)
+    _, _, loss = _run(logits, target, lam)
+    assert abs(loss - want) <= 1e-3 * max(abs(want), 1e-6), (loss, want)
