@@ -1,0 +1,80 @@
+"""Oracle for the SSM-layer adaptations (Section "Implementation", paragraph "SSM Layers (GDN)";
+Appendix "Tree-Correct Causal Convolution", "Tree-Aware SSM State Routing").
+
+TEST INFRASTRUCTURE ONLY: plain numpy in fp64, no relation to the HIP library's code.
+
+Both adaptations have a plain definition, which is what is written here: every token sees, as its
+left context / incoming recurrent state, exactly what it would see in a standalone forward over its
+own root-to-token sequence.  With `tok_pred[t]` = the token that precedes t on that sequence
+(t-1 inside a node, the last token of the nearest non-empty ancestor at a node's first token, -1 at
+the start of a branch) the causal convolution and the recurrence simply follow `tok_pred` instead
+of t-1.  The paper's chunk-per-node procedures (parent's saved conv context, parent's end state)
+compute the same thing node by node.
+"""
+from typing import Optional
+
+import numpy as np
+
+
+def _f64(x) -> np.ndarray:
+    if hasattr(x, "detach"):
+        x = x.detach().cpu().float().numpy()
+    return np.asarray(x, dtype=np.float64)
+
+
+def pred_chain(tok_pred, depth: int) -> np.ndarray:
+    """P[m][t] = the m-th predecessor of t along its own sequence (P[0][t] = t), -1 if there is none."""
+    tok_pred = np.asarray(tok_pred, dtype=np.int64)
+    n = len(tok_pred)
+    P = np.full((depth, n), -1, dtype=np.int64)
+    if depth:
+        P[0] = np.arange(n)
+    for m in range(1, depth):
+        prev = P[m - 1]
+        P[m] = np.where(prev >= 0, tok_pred[np.maximum(prev, 0)], -1)
+    return P
+
+
+def _silu(z):
+    return z / (1.0 + np.exp(-z))
+
+
+def _dsilu(z):
+    s = 1.0 / (1.0 + np.exp(-z))
+    return s * (1.0 + z * (1.0 - s))
+
+
+def tree_conv(x, weight, bias, tok_pred, activation: Optional[str] = "silu"):
+    """Depthwise causal convolution along every token's own sequence.
+    x [N, C]; weight [C, K] (weight[c, K-1] multiplies the token itself, weight[c, 0] the token K-1
+    steps back -- the layout of a depthwise conv1d with left padding K-1); bias [C] or None;
+    positions before the start of a branch contribute zero.  Returns (y [N, C], pre-activation)."""
+    x, w = _f64(x), _f64(weight)
+    n, c = x.shape
+    K = w.shape[1]
+    P = pred_chain(tok_pred, K)
+    pre = np.zeros((n, c)) if bias is None else np.tile(_f64(bias), (n, 1))
+    for m in range(K):
+        ok = P[m] >= 0
+        pre[ok] += w[:, K - 1 - m][None, :] * x[P[m][ok]]
+    if activation == "silu":
+        return _silu(pre), pre
+    assert activation is None
+    return pre, pre
+
+
+def tree_conv_bwd(x, weight, bias, tok_pred, dy, activation: Optional[str] = "silu"):
+    """Vector-Jacobian product of tree_conv: (dx [N, C], dweight [C, K], dbias [C]) for upstream dy."""
+    x, w, dy = _f64(x), _f64(weight), _f64(dy)
+    n, c = x.shape
+    K = w.shape[1]
+    P = pred_chain(tok_pred, K)
+    _, pre = tree_conv(x, w, bias, tok_pred, activation)
+    g = dy * _dsilu(pre) if activation == "silu" else dy
+    dx = np.zeros((n, c))
+    dw = np.zeros((c, K))
+    for m in range(K):
+        ok = P[m] >= 0
+        np.add.at(dx, P[m][ok], w[:, K - 1 - m][None, :] * g[ok])
+        dw[:, K - 1 - m] = (g[ok] * x[P[m][ok]]).sum(axis=0)
+    return dx, dw, g.sum(axis=0)

@@ -1,0 +1,109 @@
+"""Pins for oracle/ssm.py.  The tree convolution against a library conv1d run on every branch's own
+sequence (forward and, through autograd, backward), finite differences, and the cases the paper
+describes: sibling tokens never leak into a child's window, a short parent passes its own parent's
+tail on to the grandchildren."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import meta as M
+from oracle import ssm as S
+
+
+def _branch_conv(xb, w, b, act):
+    """Library causal depthwise conv1d on one branch sequence xb [L, C] (torch, fp64)."""
+    K = w.shape[1]
+    z = torch.nn.functional.conv1d(torch.nn.functional.pad(xb.T[None], (K - 1, 0)), w[:, None, :], b, groups=w.shape[0])[0].T
+    return torch.nn.functional.silu(z) if act == "silu" else z
+
+
+@pytest.mark.parametrize("seed,K,act", [(0, 4, "silu"), (1, 3, "silu"), (2, 4, None), (3, 2, "silu"), (4, 5, "silu"), (5, 4, "silu")])
+def test_equals_library_conv_on_every_branch(seed, K, act):
+    t = W.random_tree(60 + seed, n_nodes=4 + 2 * seed, lo=1, hi=5, n_roots=1 + seed % 2, p_zero=0.2)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n, C = m["n_tokens"], 6
+    rng = np.random.default_rng(seed)
+    x, w, b, dy = rng.normal(size=(n, C)), rng.normal(size=(C, K)), rng.normal(size=C), rng.normal(size=(n, C))
+    y, _ = S.tree_conv(x, w, b, m["tok_pred"], act)
+    dx, dw, db = S.tree_conv_bwd(x, w, b, m["tok_pred"], dy, act)
+    # every branch on its own; a token shared by g branches gets 1/g of its upstream gradient in each
+    share = np.zeros(n)
+    paths = [p for p in M.paths(m) if len(p)]
+    for p in paths:
+        share[p] += 1
+    xt = torch.tensor(x, requires_grad=True)
+    wt = torch.tensor(w, requires_grad=True)
+    bt = torch.tensor(b, requires_grad=True)
+    total = 0.0
+    for p in paths:
+        idx = torch.tensor(p, dtype=torch.long)
+        yb = _branch_conv(xt[idx], wt, bt, act)
+        assert np.allclose(yb.detach().numpy(), y[p], rtol=1e-12, atol=1e-12)
+        total = total + (yb * torch.tensor(dy[p] / share[p][:, None])).sum()
+    total.backward()
+    assert np.allclose(xt.grad.numpy(), dx, rtol=1e-10, atol=1e-12)
+    assert np.allclose(wt.grad.numpy(), dw, rtol=1e-10, atol=1e-12)
+    assert np.allclose(bt.grad.numpy(), db, rtol=1e-10, atol=1e-12)
+
+
+def test_finite_differences():
+    m = M.dfs_meta([-1, 0, 0, 1], [2, 1, 3, 2])
+    rng = np.random.default_rng(1)
+    n, C, K = m["n_tokens"], 3, 4
+    x, w, b, dy = rng.normal(size=(n, C)), rng.normal(size=(C, K)), rng.normal(size=C), rng.normal(size=(n, C))
+    dx, dw, db = S.tree_conv_bwd(x, w, b, m["tok_pred"], dy)
+    f = lambda x_, w_, b_: float((S.tree_conv(x_, w_, b_, m["tok_pred"])[0] * dy).sum())
+    eps = 1e-6
+    for arr, grad, which in ((x, dx, 0), (w, dw, 1), (b, db, 2)):
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args_hi = [x, w, b]; args_lo = [x, w, b]
+            args_hi[which], args_lo[which] = hi, lo
+            assert abs((f(*args_hi) - f(*args_lo)) / (2 * eps) - grad[idx]) < 1e-6
+
+
+def test_sibling_tokens_do_not_leak_and_parent_tail_does():
+    """Figure "SSM causal convolution" (K = 3): n0 -> {n1 -> {n3, n4}, n2}.  In DFS order n2 follows
+    n4; its window must hold n0's last two tokens, not n4's."""
+    parent = [-1, 0, 0, 1, 1]
+    seg = [3, 2, 2, 2, 2]
+    m = M.dfs_meta(parent, seg)
+    assert list(m["dfs_order"]) == [0, 1, 3, 4, 2]
+    rng = np.random.default_rng(2)
+    n, C, K = m["n_tokens"], 2, 3
+    x, w = rng.normal(size=(n, C)), rng.normal(size=(C, K))
+    rank = {int(i): rk for rk, i in enumerate(m["dfs_order"])}
+    tok = lambda nid: np.arange(m["node_start"][rank[nid]], m["node_end"][rank[nid]])
+    y, _ = S.tree_conv(x, w, None, m["tok_pred"], None)
+    x2 = x.copy()
+    x2[tok(4)] += 1.0                                           # the DFS-adjacent sibling branch
+    x2[tok(3)] -= 1.0
+    x2[tok(1)] *= 2.0
+    y2, _ = S.tree_conv(x2, w, None, m["tok_pred"], None)
+    assert np.array_equal(y2[tok(2)], y[tok(2)])
+    # first token of n2 by hand: w[:,2]*x[n2[0]] + w[:,1]*x[n0[-1]] + w[:,0]*x[n0[-2]]
+    t0, p = tok(2)[0], tok(0)
+    assert np.allclose(y[t0], w[:, 2] * x[t0] + w[:, 1] * x[p[-1]] + w[:, 0] * x[p[-2]])
+    x3 = x.copy()
+    x3[p[-1]] += 1.0
+    assert not np.allclose(S.tree_conv(x3, w, None, m["tok_pred"], None)[0][t0], y[t0])
+
+
+def test_short_parent_passes_grandparent_tail_on():
+    """Appendix "Tree-Correct Causal Convolution": the saved context is the tail of [parent context ;
+    chunk], so a one-token parent hands its own parent's tokens on; a zero-length node hands
+    everything on; the start of a branch is zero-padded."""
+    m = M.dfs_meta([-1, 0, 1, 2], [3, 1, 0, 2])
+    K, C = 4, 1
+    x = np.arange(1, 7, dtype=np.float64)[:, None]              # tokens 1..6
+    w = np.asarray([[1000.0, 100.0, 10.0, 1.0]])
+    y, _ = S.tree_conv(x, w, None, m["tok_pred"], None)
+    # sequence is 1 2 3 | 4 | (empty) | 5 6
+    assert y[:, 0].tolist() == [1.0, 12.0, 123.0, 1234.0, 2345.0, 3456.0]
+    # a second root starts from zero context
+    m = M.dfs_meta([-1, -1], [2, 2])
+    y, _ = S.tree_conv(np.asarray([[1.0], [2.0], [3.0], [4.0]]), w, None, m["tok_pred"], None)
+    assert y[:, 0].tolist() == [1.0, 12.0, 3.0, 34.0]
