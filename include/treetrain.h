@@ -385,6 +385,53 @@ tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dty
                        float theta_base, int32_t inverse, void* y, int64_t y_stride_tok, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Tree-correct causal convolution (device; host helper for the backward)
+ *
+ * The depthwise causal conv1d in front of an SSM (GDN) layer, Section "Implementation", paragraph
+ * "SSM Layers (GDN)" (ii) and Appendix "Tree-Correct Causal Convolution": every token's window
+ * holds the K-1 tokens that precede it on its own root-to-token sequence (not the K-1 tokens
+ * before it in DFS order), zero before the start of a branch:
+ *     y[t][c] = act( bias[c] + sum_{m=0..K-1} weight[c][K-1-m] * x[pred^m(t)][c] )
+ * with pred = tok_pred of tt_tree_build_meta (pred^0(t) = t).  This equals the paper's
+ * node-by-node procedure (parent's saved context prepended to each chunk) and a plain causal
+ * conv1d run on every branch separately.
+ *   x, y, dy, dx [n_tokens][channels], dtype bf16 or fp32, token strides in elements (0 = channels);
+ *   weight [channels][K] fp32 (weight[c][K-1] multiplies the token itself), bias [channels] fp32
+ *   or NULL; K in {2, 3, 4}; activation 0 = none, 1 = SiLU; channels a multiple of 8 (bf16) / 4.
+ * Backward: dx (same dtype as x), dweight [channels][K] and dbias [channels] (fp32, overwritten;
+ *   dbias may be NULL).  Successors of a token that do not directly follow it in DFS order (the
+ *   second and later children of a branch point) are found through a small host-built list:
+ *   tt_tree_conv_plan lists every token that has such successors (fix_tok, ascending), and for
+ *   each, in CSR form (fix_off), the first token of every such run (fix_t) with its distance
+ *   (fix_r, 1..K-1).  The device call takes device copies of the four arrays.
+ *   Sums over tokens are taken in a fixed order: results are bit-reproducible.
+ * Errors: TT_ERR_NULL, TT_ERR_SHAPE, TT_ERR_DTYPE, TT_ERR_ALIGN (16-byte pointers, strides a
+ *   multiple of 8 / 4 elements), TT_ERR_UNSUPPORTED (K outside 2..4), TT_ERR_WORKSPACE.
+ * ------------------------------------------------------------------------------------------ */
+tt_status tt_tree_conv_fwd(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype,
+                           int32_t activation, const void* x, int64_t x_stride_tok,
+                           const float* weight, const float* bias, const int32_t* tok_pred,
+                           void* y, int64_t y_stride_tok, void* stream);
+
+/* Host: sizes, then contents, of the backward's successor list for kernel size K. */
+tt_status tt_tree_conv_plan_sizes(int64_t n_tokens, const int32_t* tok_pred, int32_t kernel_size,
+                                  int32_t* n_fix, int32_t* n_pairs);
+tt_status tt_tree_conv_plan(int64_t n_tokens, const int32_t* tok_pred, int32_t kernel_size,
+                            int32_t* fix_tok /* [n_fix] */, int32_t* fix_off /* [n_fix+1] */,
+                            int32_t* fix_t /* [n_pairs] */, int32_t* fix_r /* [n_pairs] */);
+
+size_t tt_tree_conv_bwd_workspace(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype);
+
+tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype,
+                           int32_t activation, const void* x, int64_t x_stride_tok,
+                           const float* weight, const float* bias, const int32_t* tok_pred,
+                           const void* dy, int64_t dy_stride_tok,
+                           int32_t n_fix, const int32_t* fix_tok, const int32_t* fix_off,
+                           const int32_t* fix_t, const int32_t* fix_r,
+                           void* dx, int64_t dx_stride_tok, float* dweight, float* dbias,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
  * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
  * the recorded events have completed and returns the totals since the last enable.
@@ -403,7 +450,10 @@ tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dty
 #define TT_KERNEL_ROPE        11  /* rotary position embedding                           */
 #define TT_KERNEL_PART_GATHER  12  /* partition driver: row gathers                      */
 #define TT_KERNEL_PART_SCATTER 13  /* partition driver: row scatters, accumulate, finalise */
-#define TT_N_KERNELS          14
+#define TT_KERNEL_CONV_FWD     14  /* tree-correct causal convolution                    */
+#define TT_KERNEL_CONV_BWD     15
+#define TT_KERNEL_CONV_FIX     16  /* its branch-point fix-up and weight-gradient reduce */
+#define TT_N_KERNELS          17
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

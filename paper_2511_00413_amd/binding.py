@@ -88,6 +88,19 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_rope.restype = ctypes.c_int32
         lib.tt_tree_rope.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                      _vp, ctypes.c_float, ctypes.c_int32, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_conv_fwd.restype = ctypes.c_int32
+        lib.tt_tree_conv_fwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp,
+                                         ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_conv_plan_sizes.restype = ctypes.c_int32
+        lib.tt_tree_conv_plan_sizes.argtypes = [ctypes.c_int64, _vp, ctypes.c_int32, _c_i32p, _c_i32p]
+        lib.tt_tree_conv_plan.restype = ctypes.c_int32
+        lib.tt_tree_conv_plan.argtypes = [ctypes.c_int64, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
+        lib.tt_tree_conv_bwd_workspace.restype = ctypes.c_size_t
+        lib.tt_tree_conv_bwd_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.tt_tree_conv_bwd.restype = ctypes.c_int32
+        lib.tt_tree_conv_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp,
+                                         ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_int32, _vp, _vp, _vp, _vp,
+                                         _vp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         lib.tt_tree_path_weights.restype = ctypes.c_int32
         lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
@@ -109,7 +122,7 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter")
+                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix")
 
 
 class _KernelTimes(ctypes.Structure):
@@ -210,6 +223,32 @@ def tree_build_meta(parent, seg_len, trained=None, root_pos_offset=None, g_overr
 
 
 WEIGHT_PATH_SUM, WEIGHT_UNIFORM, WEIGHT_PATH_TOKEN_MEAN = 0, 1, 2
+
+
+@dataclass
+class ConvPlan:
+    """Host output of tt_tree_conv_plan: tokens with successors that do not directly follow them."""
+    kernel_size: int
+    fix_tok: np.ndarray
+    fix_off: np.ndarray
+    fix_t: np.ndarray
+    fix_r: np.ndarray
+    device: Optional[dict] = None
+
+    def to_device(self, device="cuda"):
+        torch = _torch()
+        self.device = {n: torch.from_numpy(getattr(self, n)).to(device) for n in ("fix_tok", "fix_off", "fix_t", "fix_r")}
+        return self
+
+
+def tree_conv_plan(tok_pred, kernel_size: int) -> ConvPlan:
+    tok_pred = _np(tok_pred, np.int32)
+    nf, npairs = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(_lib().tt_tree_conv_plan_sizes(len(tok_pred), _hp(tok_pred), int(kernel_size), ctypes.byref(nf), ctypes.byref(npairs)))
+    fix_tok, fix_off = np.zeros(nf.value, np.int32), np.zeros(nf.value + 1, np.int32)
+    fix_t, fix_r = np.zeros(npairs.value, np.int32), np.zeros(npairs.value, np.int32)
+    _check(_lib().tt_tree_conv_plan(len(tok_pred), _hp(tok_pred), int(kernel_size), _hp(fix_tok), _hp(fix_off), _hp(fix_t), _hp(fix_r)))
+    return ConvPlan(int(kernel_size), fix_tok, fix_off, fix_t, fix_r)
 
 
 def tree_path_weights(parent, seg_len, trained=None, *, scheme: int = WEIGHT_PATH_SUM, path_weight=None, advantage=None):
@@ -518,3 +557,54 @@ def tree_attn_partitioned_bwd(q, k, v, plan: PartitionPlan, o, d_o, lse, *, scal
                                                _dp(o), _dp(d_o), _dp(lse), _dp(dq), _dp(dk), _dp(dv),
                                                _dp(workspace), ws_bytes, _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def _conv_check(x, weight, what="x"):
+    torch = _torch()
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError(f"{what} must be [tokens, channels] with contiguous channels")
+    if x.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError(f"{what} must be bf16 or fp32")
+    if weight.dim() != 2 or weight.shape[0] != x.shape[1] or weight.dtype != torch.float32 or not weight.is_contiguous():
+        raise ValueError("weight must be a contiguous fp32 [channels, K] tensor")
+    return x.shape[0], x.shape[1], weight.shape[1], DTYPE_BF16 if x.dtype == torch.bfloat16 else DTYPE_FP32
+
+
+def _row_stride(t):
+    return t.stride(0) if t.shape[0] > 1 else t.shape[1]
+
+
+def tree_conv_fwd(x, weight, bias, tok_pred, *, silu: bool = True, out=None, stream=None):
+    """Tree-correct depthwise causal conv: x [n, C] bf16/fp32, weight [C, K] fp32, bias [C] fp32 or None,
+    tok_pred [n] int32 (from tree_build_meta).  Returns y [n, C]."""
+    torch = _torch()
+    n, c, k, dt = _conv_check(x, weight)
+    if out is None:
+        out = torch.empty((n, c), dtype=x.dtype, device=x.device)
+    _check(_lib().tt_tree_conv_fwd(n, c, k, dt, 1 if silu else 0, _dp(x), _row_stride(x), _dp(weight), _dp(bias), _dp(tok_pred),
+                                   _dp(out), _row_stride(out), _stream_ptr(stream)))
+    return out
+
+
+def tree_conv_bwd(x, weight, bias, tok_pred, dy, plan: ConvPlan, *, silu: bool = True, want_dbias: bool = True,
+                  workspace=None, stream=None):
+    """Returns (dx [n, C] in x's dtype, dweight [C, K] fp32, dbias [C] fp32 or None)."""
+    torch = _torch()
+    n, c, k, dt = _conv_check(x, weight)
+    _conv_check(dy, weight, "dy")
+    if plan.kernel_size != k:
+        raise ValueError(f"the plan was made for kernel size {plan.kernel_size}, weight has {k}")
+    if plan.device is None:
+        plan.to_device(x.device)
+    dx = torch.empty((n, c), dtype=x.dtype, device=x.device)
+    dw = torch.empty((c, k), dtype=torch.float32, device=x.device)
+    db = torch.empty(c, dtype=torch.float32, device=x.device) if want_dbias else None
+    need = int(_lib().tt_tree_conv_bwd_workspace(n, c, k, dt))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    d = plan.device
+    _check(_lib().tt_tree_conv_bwd(n, c, k, dt, 1 if silu else 0, _dp(x), _row_stride(x), _dp(weight), _dp(bias), _dp(tok_pred),
+                                   _dp(dy), _row_stride(dy), len(plan.fix_tok), _dp(d["fix_tok"]), _dp(d["fix_off"]),
+                                   _dp(d["fix_t"]), _dp(d["fix_r"]), _dp(dx), _row_stride(dx), _dp(dw), _dp(db),
+                                   _dp(workspace), workspace.numel(), _stream_ptr(stream)))
+    return dx, dw, db

@@ -1,6 +1,7 @@
 // C ABI entry points of the device calls: argument validation on the host, then dispatch to the
 // kernels.  Nothing is launched unless every check passes.
 #include <hip/hip_runtime.h>
+#include <climits>
 #include <cmath>
 #include "tt_internal.h"
 #include "tt_kernels.h"
@@ -203,4 +204,78 @@ extern "C" tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, 
   return hip_result(tt::rope(n_tokens, n_heads, d, dtype == TT_DTYPE_BF16, x, x_stride_tok, tok_pos, theta_base, inverse != 0,
                              y, y_stride_tok, (hipStream_t)stream),
                     "tree_rope");
+}
+
+namespace {
+
+struct ConvChecked { bool bf16; int64_t xs, ys; };
+
+// Common validation of the convolution calls; strides come back in bytes.
+tt_status check_conv(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype, int32_t activation,
+                     const void* x, int64_t x_stride, const float* weight, const int32_t* tok_pred, const void* y,
+                     int64_t y_stride, ConvChecked& c) {
+  if (dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
+  if (kernel_size < 2 || kernel_size > 4) return fail(TT_ERR_UNSUPPORTED, "kernel_size=%d: only 2, 3, 4 are built", kernel_size);
+  if (activation != 0 && activation != 1) return fail(TT_ERR_UNSUPPORTED, "activation=%d: 0 (none) or 1 (SiLU)", activation);
+  const int epv = dtype == TT_DTYPE_BF16 ? 8 : 4;
+  if (channels <= 0 || channels % epv) return fail(TT_ERR_SHAPE, "channels=%d must be a positive multiple of %d", channels, epv);
+  if (x_stride == 0) x_stride = channels;
+  if (y_stride == 0) y_stride = channels;
+  if (x_stride < channels || y_stride < channels || x_stride % epv || y_stride % epv)
+    return fail(TT_ERR_ALIGN, "token strides %lld / %lld must be >= channels and a multiple of %d elements", (long long)x_stride,
+                (long long)y_stride, epv);
+  if (!weight) return fail(TT_ERR_NULL, "weight is NULL");
+  if (n_tokens > 0 && (!x || !y || !tok_pred)) return fail(TT_ERR_NULL, "x / output / tok_pred is NULL");
+  if (!tt::aligned16(x) || !tt::aligned16(y)) return fail(TT_ERR_ALIGN, "a tensor pointer is not 16-byte aligned");
+  c.bf16 = dtype == TT_DTYPE_BF16;
+  const int64_t esz = c.bf16 ? 2 : 4;
+  c.xs = x_stride * esz; c.ys = y_stride * esz;
+  return TT_OK;
+}
+
+}  // namespace
+
+extern "C" tt_status tt_tree_conv_fwd(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype, int32_t activation,
+                                      const void* x, int64_t x_stride_tok, const float* weight, const float* bias,
+                                      const int32_t* tok_pred, void* y, int64_t y_stride_tok, void* stream) {
+  tt::clear_error();
+  ConvChecked c;
+  if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, tok_pred, y, y_stride_tok, c))
+    return s;
+  if (x == y) return fail(TT_ERR_SHAPE, "y may not alias x (later tokens read earlier rows of x)");
+  return hip_result(tt::conv_fwd(n_tokens, channels, kernel_size, c.bf16, activation == 1, x, c.xs, weight, bias, tok_pred, y, c.ys,
+                                 (hipStream_t)stream),
+                    "tree_conv_fwd");
+}
+
+extern "C" size_t tt_tree_conv_bwd_workspace(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype) {
+  tt::clear_error();
+  if ((dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) || n_tokens < 0 || n_tokens >= INT32_MAX || channels <= 0 ||
+      kernel_size < 2 || kernel_size > 4)
+    return 0;
+  return tt::conv_bwd_workspace(n_tokens, channels, kernel_size, dtype == TT_DTYPE_BF16);
+}
+
+extern "C" tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype, int32_t activation,
+                                      const void* x, int64_t x_stride_tok, const float* weight, const float* bias,
+                                      const int32_t* tok_pred, const void* dy, int64_t dy_stride_tok, int32_t n_fix,
+                                      const int32_t* fix_tok, const int32_t* fix_off, const int32_t* fix_t, const int32_t* fix_r,
+                                      void* dx, int64_t dx_stride_tok, float* dweight, float* dbias, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  tt::clear_error();
+  ConvChecked c, cd;
+  if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, tok_pred, dx, dx_stride_tok, c))
+    return s;
+  if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, dy, dy_stride_tok, weight, tok_pred, dx, dx_stride_tok, cd))
+    return s;
+  if (!dweight) return fail(TT_ERR_NULL, "dweight is NULL");
+  if (n_fix < 0 || (n_fix > 0 && (!fix_tok || !fix_off || !fix_t || !fix_r))) return fail(TT_ERR_NULL, "n_fix=%d with a NULL list", n_fix);
+  if (dx == x || dx == dy) return fail(TT_ERR_SHAPE, "dx may not alias x or dy");
+  const size_t need = tt::conv_bwd_workspace(n_tokens, channels, kernel_size, c.bf16);
+  if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
+    return fail(TT_ERR_WORKSPACE, "conv backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+  return hip_result(tt::conv_bwd(n_tokens, channels, kernel_size, c.bf16, activation == 1, x, c.xs, weight, bias, tok_pred, dy, cd.xs,
+                                 n_fix, fix_tok, fix_off, fix_t, fix_r, dx, c.ys, dweight, dbias, workspace, (hipStream_t)stream),
+                    "tree_conv_bwd");
 }

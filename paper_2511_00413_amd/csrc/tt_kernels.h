@@ -66,4 +66,14 @@ hipError_t weighted_logprob_bwd(int64_t n_rows, int vocab, bool bf16, const void
 hipError_t rope(int64_t n_tokens, int n_heads, int d, bool bf16, const void* x, int64_t x_stride, const int32_t* pos,
                 float theta_base, bool inverse, void* y, int64_t y_stride, hipStream_t st);
 
+// tree-correct causal convolution (tt_conv.hip); strides in bytes
+hipError_t conv_fwd(int64_t n_tokens, int channels, int kernel_size, bool bf16, bool silu, const void* x, int64_t x_stride_bytes,
+                    const float* weight, const float* bias, const int32_t* tok_pred, void* y, int64_t y_stride_bytes,
+                    hipStream_t st);
+hipError_t conv_bwd(int64_t n_tokens, int channels, int kernel_size, bool bf16, bool silu, const void* x, int64_t x_stride_bytes,
+                    const float* weight, const float* bias, const int32_t* tok_pred, const void* dy, int64_t dy_stride_bytes,
+                    int n_fix, const int32_t* fix_tok, const int32_t* fix_off, const int32_t* fix_t, const int32_t* fix_r,
+                    void* dx, int64_t dx_stride_bytes, float* dweight, float* dbias, void* workspace, hipStream_t st);
+size_t conv_bwd_workspace(int64_t n_tokens, int channels, int kernel_size, bool bf16);
+
 }  // namespace tt

@@ -230,3 +230,68 @@ extern "C" tt_status tt_tree_path_weights(int32_t n_nodes, const int32_t* parent
   }
   return TT_OK;
 }
+
+namespace {
+
+// Tokens whose successors on some branch do not directly follow them in DFS order, for the backward of
+// the tree convolution.  A "jump" token t (tok_pred[t] >= 0 and != t-1) is such a successor of each
+// of its first K-1 predecessors; pairs come out grouped by predecessor, ascending.
+tt_status conv_pairs(int64_t n_tokens, const int32_t* tok_pred, int32_t K, std::vector<int32_t>& s_of, std::vector<int32_t>& t_of,
+                     std::vector<int32_t>& r_of) {
+  if (n_tokens < 0 || n_tokens >= INT32_MAX) return tt::fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
+  if (K < 2 || K > 4) return tt::fail(TT_ERR_UNSUPPORTED, "kernel_size=%d: only 2, 3, 4 are built", K);
+  if (n_tokens > 0 && !tok_pred) return tt::fail(TT_ERR_NULL, "tok_pred is NULL");
+  for (int64_t t = 0; t < n_tokens; t++)
+    if (tok_pred[t] < -1 || tok_pred[t] >= t) return tt::fail(TT_ERR_TREE, "tok_pred[%lld]=%d is not an earlier token", (long long)t, tok_pred[t]);
+  // count per predecessor, then fill (stable: pairs of one predecessor stay in ascending t)
+  std::vector<int32_t> cnt(n_tokens + 1, 0);
+  auto for_each_pair = [&](auto&& fn) {
+    for (int64_t t = 0; t < n_tokens; t++) {
+      if (tok_pred[t] < 0 || tok_pred[t] == t - 1) continue;
+      int32_t a = tok_pred[t];
+      for (int32_t r = 1; r < K && a >= 0; r++, a = tok_pred[a]) fn(a, (int32_t)t, r);
+    }
+  };
+  for_each_pair([&](int32_t a, int32_t, int32_t) { cnt[a + 1]++; });
+  for (int64_t i = 0; i < n_tokens; i++) cnt[i + 1] += cnt[i];
+  const int32_t total = n_tokens ? cnt[n_tokens] : 0;
+  s_of.assign(total, 0); t_of.assign(total, 0); r_of.assign(total, 0);
+  std::vector<int32_t> cur(cnt.begin(), cnt.end() - 1);
+  for_each_pair([&](int32_t a, int32_t t, int32_t r) {
+    const int32_t k = cur[a]++;
+    s_of[k] = a; t_of[k] = t; r_of[k] = r;
+  });
+  return TT_OK;
+}
+
+}  // namespace
+
+extern "C" tt_status tt_tree_conv_plan_sizes(int64_t n_tokens, const int32_t* tok_pred, int32_t kernel_size, int32_t* n_fix,
+                                             int32_t* n_pairs) {
+  tt::clear_error();
+  if (!n_fix || !n_pairs) return tt::fail(TT_ERR_NULL, "n_fix / n_pairs is NULL");
+  std::vector<int32_t> s_of, t_of, r_of;
+  if (tt_status s = conv_pairs(n_tokens, tok_pred, kernel_size, s_of, t_of, r_of)) return s;
+  int32_t nf = 0;
+  for (size_t k = 0; k < s_of.size(); k++) nf += k == 0 || s_of[k] != s_of[k - 1];
+  *n_fix = nf;
+  *n_pairs = (int32_t)s_of.size();
+  return TT_OK;
+}
+
+extern "C" tt_status tt_tree_conv_plan(int64_t n_tokens, const int32_t* tok_pred, int32_t kernel_size, int32_t* fix_tok,
+                                       int32_t* fix_off, int32_t* fix_t, int32_t* fix_r) {
+  tt::clear_error();
+  if (!fix_off) return tt::fail(TT_ERR_NULL, "fix_off is NULL");
+  std::vector<int32_t> s_of, t_of, r_of;
+  if (tt_status s = conv_pairs(n_tokens, tok_pred, kernel_size, s_of, t_of, r_of)) return s;
+  if (!s_of.empty() && (!fix_tok || !fix_t || !fix_r)) return tt::fail(TT_ERR_NULL, "fix_tok / fix_t / fix_r is NULL");
+  int32_t nf = 0;
+  for (size_t k = 0; k < s_of.size(); k++) {
+    if (k == 0 || s_of[k] != s_of[k - 1]) { fix_tok[nf] = s_of[k]; fix_off[nf] = (int32_t)k; nf++; }
+    fix_t[k] = t_of[k];
+    fix_r[k] = r_of[k];
+  }
+  fix_off[nf] = (int32_t)s_of.size();
+  return TT_OK;
+}
