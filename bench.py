@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-loss", action="store_true")
     ap.add_argument("--no-rope", action="store_true")
     ap.add_argument("--no-partitioned", action="store_true")
+    ap.add_argument("--no-conv", action="store_true")
+    ap.add_argument("--conv-channels", type=int, default=8192,
+                    help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
     ap.add_argument("--partition-gather-all", action="store_true",
                     help="partitioned leg: gather / scatter every partition, also those that could be used in place")
     ap.add_argument("--partition-capacity", type=int, default=0,
@@ -323,6 +326,38 @@ def main():
                 "ms_host_plan": round(plan_ms, 3)}
         del op, lsep, dqp, dkp_, dvp_, wsp
 
+    # ---------------- tree-correct causal convolution on the same tree (SSM-layer adaptation) ----------------
+    conv = None
+    if not args.no_conv and n_prefix == 0 and dims.dtype == "bf16":
+        C, Kc = args.conv_channels, 4
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg * 1000 + 9)
+        xc = torch.randn((N, C), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        dyc = torch.randn((N, C), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        wc = torch.randn((C, Kc), generator=gen, device=dev, dtype=torch.float32) * 0.5
+        bc = torch.randn(C, generator=gen, device=dev, dtype=torch.float32) * 0.1
+        pred_d = torch.from_numpy(meta.tok_pred).to(dev)
+        cplan = T.tree_conv_plan(meta.tok_pred, Kc).to_device(dev)
+        yc = torch.empty_like(xc)
+        n_it = max(3, min(args.steps, 10))
+        for it in range(2 + n_it):
+            if it == 2:
+                torch.cuda.synchronize()
+                T.kernel_timing_enable(True)
+            T.tree_conv_fwd(xc, wc, bc, pred_d, out=yc)
+            T.tree_conv_bwd(xc, wc, bc, pred_d, dyc, cplan)
+        ct = T.kernel_timing_read()
+        T.kernel_timing_enable(False)
+        f_ms, b_ms, x_ms = (ct[n][0] / n_it for n in ("conv_fwd", "conv_bwd", "conv_fix"))
+        f_bytes = 2 * N * C * 2 + 4 * N                      # read x, write y, tok_pred
+        b_bytes = 3 * N * C * 2 + 4 * N                      # read x and dy, write dx
+        conv = {"channels": C, "kernel_size": Kc, "fix_tokens": int(len(cplan.fix_tok)),
+                "ms_fwd": round(f_ms, 4), "ms_bwd": round(b_ms, 4), "ms_bwd_fix_and_reduce": round(x_ms, 4),
+                "fwd_hbm_gbps": round(f_bytes / (f_ms * 1e-3) / 1e9, 1), "bwd_hbm_gbps": round(b_bytes / (b_ms * 1e-3) / 1e9, 1),
+                "fwd_frac_of_hbm_peak": round(f_bytes / (f_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                "bwd_frac_of_hbm_peak": round(b_bytes / (b_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}
+        del xc, dyc, yc
+
     # ---------------- CPU oracle on a bounded sample (context only) ----------------
     cpu = None
     if not args.no_cpu_baseline and n_prefix == 0:
@@ -373,6 +408,7 @@ def main():
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,
         "partitioned": part,
+        "tree_conv": conv,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

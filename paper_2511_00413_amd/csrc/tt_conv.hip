@@ -33,23 +33,18 @@ __device__ __forceinline__ void load_row(const void* base, int64_t row, int64_t 
   }
 }
 
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
+typedef float f32x8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
 
 template <bool BF16>
 __device__ __forceinline__ void store_row(void* base, int64_t row, int64_t stride_bytes, int cv, const float (&v)[Chan<BF16>::NV]) {
   char* p = (char*)base + row * stride_bytes + (int64_t)cv * 16;
   if (BF16) {
-    uint4 u;
-    u.x = bf16_rne(v[0]) | (bf16_rne(v[1]) << 16);
-    u.y = bf16_rne(v[2]) | (bf16_rne(v[3]) << 16);
-    u.z = bf16_rne(v[4]) | (bf16_rne(v[5]) << 16);
-    u.w = bf16_rne(v[6]) | (bf16_rne(v[7]) << 16);
-    *reinterpret_cast<uint4*>(p) = u;
+    f32x8v f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) f[i] = v[i];
+    const bf16x8v b = __builtin_convertvector(f, bf16x8v);       // round to nearest even
+    *reinterpret_cast<uint4*>(p) = __builtin_bit_cast(uint4, b);
   } else {
     *reinterpret_cast<float4*>(p) = float4{v[0], v[1], v[2], v[3]};
   }
@@ -69,9 +64,14 @@ struct ConvArgs {
   const int32_t *fix_tok, *fix_off, *fix_t, *fix_r;
 };
 
-__device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
+// sigmoid through the bare exp2 / reciprocal instructions (1 ulp each; the results are rounded to
+// bf16 or meet fp32 sums of comparable error)
+__device__ __forceinline__ float sigmoid_f(float z) {
+  return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * z));
+}
+__device__ __forceinline__ float silu_f(float z) { return z * sigmoid_f(z); }
 __device__ __forceinline__ float dsilu_f(float z) {
-  const float s = 1.f / (1.f + __expf(-z));
+  const float s = sigmoid_f(z);
   return s * (1.f + z * (1.f - s));
 }
 
@@ -131,6 +131,8 @@ __device__ __forceinline__ void shift_window(float (&win)[K > 1 ? K - 1 : 1][Cha
     for (int i = 0; i < NV; i++) win[0][i] = xt[i];
 }
 
+constexpr int CONV_U = 4;      // tokens whose loads are issued together
+
 template <bool BF16, int K>
 __global__ __launch_bounds__(CONV_THREADS) void tree_conv_fwd_kernel(ConvArgs a) {
   constexpr int NV = Chan<BF16>::NV;
@@ -144,18 +146,30 @@ __global__ __launch_bounds__(CONV_THREADS) void tree_conv_fwd_kernel(ConvArgs a)
   float win[K > 1 ? K - 1 : 1][NV];
   const int t0 = (int)tile * a.tok_tile;
   const int t1 = min(t0 + a.tok_tile, a.n_tokens);
-  for (int t = t0; t < t1; t++) {
-    const int p = a.tok_pred[t];
-    float xt[NV], pre[NV];
-    load_row<BF16>(a.x, t, a.x_stride, cv, xt);
-    if (t == t0 || p != t - 1) rebuild_window<BF16, K>(a, p, cv, win);
-    pre_activation<BF16, K>(wt, xt, win, pre);
-    if (a.silu) {
+  for (int tb = t0; tb < t1; tb += CONV_U) {
+    int p[CONV_U];
+    float xt[CONV_U][NV];
 #pragma unroll
-      for (int i = 0; i < NV; i++) pre[i] = silu_f(pre[i]);
+    for (int u = 0; u < CONV_U; u++) {
+      const int t = min(tb + u, t1 - 1);
+      p[u] = a.tok_pred[t];
+      load_row<BF16>(a.x, t, a.x_stride, cv, xt[u]);
     }
-    store_row<BF16>(a.y, t, a.y_stride, cv, pre);
-    shift_window<BF16, K>(win, xt);
+#pragma unroll
+    for (int u = 0; u < CONV_U; u++) {
+      const int t = tb + u;
+      if (t < t1) {
+        float pre[NV];
+        if (t == t0 || p[u] != t - 1) rebuild_window<BF16, K>(a, p[u], cv, win);
+        pre_activation<BF16, K>(wt, xt[u], win, pre);
+        if (a.silu) {
+#pragma unroll
+          for (int i = 0; i < NV; i++) pre[i] = silu_f(pre[i]);
+        }
+        store_row<BF16>(a.y, t, a.y_stride, cv, pre);
+        shift_window<BF16, K>(win, xt[u]);
+      }
+    }
   }
 }
 
@@ -203,56 +217,66 @@ __global__ __launch_bounds__(CONV_THREADS) void tree_conv_bwd_kernel(ConvArgs a)
   for (int j = 0; j < K; j++) lk[j] = false;
   const int t0 = (int)tile * a.tok_tile;
   const int t1 = min(t0 + a.tok_tile, a.n_tokens);
-  for (int t = t0; t < t1 + K - 1; t++) {
-    // shift the ring
+  const int t_end = t1 + K - 1;                     // look-ahead: g of the K-1 tokens after the tile
+  for (int tb = t0; tb < t_end; tb += CONV_U) {
+    int p[CONV_U];
+    float xt[CONV_U][NV], dyt[CONV_U][NV];
 #pragma unroll
-    for (int j = K - 1; j >= 1; j--) {
-      lk[j] = lk[j - 1];
-#pragma unroll
-      for (int i = 0; i < NV; i++) gq[j][i] = gq[j - 1][i];
+    for (int u = 0; u < CONV_U; u++) {
+      const int t = min(tb + u, a.n_tokens - 1);
+      p[u] = a.tok_pred[t];
+      load_row<BF16>(a.x, t, a.x_stride, cv, xt[u]);
+      load_row<BF16>(a.dy, t, a.dy_stride, cv, dyt[u]);
     }
-    if (t < a.n_tokens) {
-      const int p = a.tok_pred[t];
-      float xt[NV], pre[NV];
-      load_row<BF16>(a.x, t, a.x_stride, cv, xt);
-      if (t == t0 || p != t - 1) rebuild_window<BF16, K>(a, p, cv, win);
-      pre_activation<BF16, K>(wt, xt, win, pre);
-      load_row<BF16>(a.dy, t, a.dy_stride, cv, gq[0]);
-      if (a.silu) {
 #pragma unroll
-        for (int i = 0; i < NV; i++) gq[0][i] *= dsilu_f(pre[i]);
+    for (int u = 0; u < CONV_U; u++) {
+      const int t = tb + u;
+      if (t >= t_end) break;
+      // shift the ring
+#pragma unroll
+      for (int j = K - 1; j >= 1; j--) {
+        lk[j] = lk[j - 1];
+#pragma unroll
+        for (int i = 0; i < NV; i++) gq[j][i] = gq[j - 1][i];
       }
-      lk[0] = p == t - 1;
-      if (t < t1) {
+      if (t < a.n_tokens) {
+        float pre[NV];
+        if (t == t0 || p[u] != t - 1) rebuild_window<BF16, K>(a, p[u], cv, win);
+        pre_activation<BF16, K>(wt, xt[u], win, pre);
 #pragma unroll
-        for (int i = 0; i < NV; i++) {
-          db[i] += gq[0][i];
-          dw[K - 1][i] += gq[0][i] * xt[i];
+        for (int i = 0; i < NV; i++) gq[0][i] = a.silu ? dyt[u][i] * dsilu_f(pre[i]) : dyt[u][i];
+        lk[0] = p[u] == t - 1;
+        if (t < t1) {
 #pragma unroll
-          for (int m = 1; m < K; m++) dw[K - 1 - m][i] += gq[0][i] * win[m - 1][i];
+          for (int i = 0; i < NV; i++) {
+            db[i] += gq[0][i];
+            dw[K - 1][i] += gq[0][i] * xt[u][i];
+#pragma unroll
+            for (int m = 1; m < K; m++) dw[K - 1 - m][i] += gq[0][i] * win[m - 1][i];
+          }
         }
+        shift_window<BF16, K>(win, xt[u]);
+      } else {
+        lk[0] = false;
+#pragma unroll
+        for (int i = 0; i < NV; i++) gq[0][i] = 0.f;
       }
-      shift_window<BF16, K>(win, xt);
-    } else {
-      lk[0] = false;
+      const int s = t - (K - 1);
+      if (s >= t0) {          // s < t1 by the loop bound
+        float dx[NV];
 #pragma unroll
-      for (int i = 0; i < NV; i++) gq[0][i] = 0.f;
-    }
-    const int s = t - (K - 1);
-    if (s >= t0) {          // s < t1 by the loop bound
-      float dx[NV];
+        for (int i = 0; i < NV; i++) dx[i] = wt.w[K - 1][i] * gq[K - 1][i];
+        bool valid = true;
 #pragma unroll
-      for (int i = 0; i < NV; i++) dx[i] = wt.w[K - 1][i] * gq[K - 1][i];
-      bool valid = true;
+        for (int m = 1; m < K; m++) {
+          valid = valid && lk[K - 1 - m];
+          if (valid) {
 #pragma unroll
-      for (int m = 1; m < K; m++) {
-        valid = valid && lk[K - 1 - m];
-        if (valid) {
-#pragma unroll
-          for (int i = 0; i < NV; i++) dx[i] += wt.w[K - 1 - m][i] * gq[K - 1 - m][i];
+            for (int i = 0; i < NV; i++) dx[i] += wt.w[K - 1 - m][i] * gq[K - 1 - m][i];
+          }
         }
+        store_row<BF16>(a.y, s, a.y_stride, cv, dx);
       }
-      store_row<BF16>(a.y, s, a.y_stride, cv, dx);
     }
   }
   float* part = a.partial + (int64_t)tile * (K + 1) * a.channels + cv * NV;
@@ -310,8 +334,18 @@ __global__ __launch_bounds__(CONV_THREADS) void tree_conv_reduce_kernel(const fl
   const int64_t gid = (int64_t)blockIdx.x * CONV_THREADS + threadIdx.x;
   if (gid >= (int64_t)(K + 1) * channels) return;
   const int j = (int)(gid / channels), c = (int)(gid - (int64_t)j * channels);
+  const float* src = partial + (int64_t)j * channels + c;
+  const int64_t step = (int64_t)(K + 1) * channels;
   float acc = 0.f;
-  for (int t = 0; t < n_tiles; t++) acc += partial[((int64_t)t * (K + 1) + j) * channels + c];
+  int t = 0;
+  for (; t + 8 <= n_tiles; t += 8) {               // eight loads in flight, added in tile order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) v[u] = src[(t + u) * step];
+#pragma unroll
+    for (int u = 0; u < 8; u++) acc += v[u];
+  }
+  for (; t < n_tiles; t++) acc += src[t * step];
   if (j < K) dweight[(int64_t)c * K + j] = acc;
   else if (dbias) dbias[c] = acc;
 }
