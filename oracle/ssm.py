@@ -78,3 +78,38 @@ def tree_conv_bwd(x, weight, bias, tok_pred, dy, activation: Optional[str] = "si
         np.add.at(dx, P[m][ok], w[:, K - 1 - m][None, :] * g[ok])
         dw[:, K - 1 - m] = (g[ok] * x[P[m][ok]]).sum(axis=0)
     return dx, dw, g.sum(axis=0)
+
+
+def gdn_tree(q, k, v, g, beta, tok_pred, scale: Optional[float] = None, return_states: bool = False):
+    """Gated delta rule with tree state routing (Section "Implementation", "SSM Layers (GDN)" (i);
+    Appendix "Tree-Aware SSM State Routing"), as the token-by-token recurrence it is defined by.
+
+    Per value head h (key head h // (Hv // Hk)), state S in R^{Dk x Dv}, token t with predecessor
+    p = tok_pred[t] on its own sequence (S_p = 0 where p = -1: the start of a branch):
+        S~  = exp(g_t) * S_p                         decay
+        d   = beta_t * (v_t - S~^T k_t)              delta-rule correction of the value
+        S_t = S~ + k_t d^T
+        o_t = scale * S_t^T q_t
+    Reading the state of the PREDECESSOR ON THE TOKEN'S OWN SEQUENCE -- the end state of the parent
+    node at a node's first token -- instead of the previous token in DFS order is the whole
+    adaptation; the paper's node-per-chunk procedure computes exactly this.
+    q, k [N, Hk, Dk]; v [N, Hv, Dv]; g, beta [N, Hv] (g <= 0 is the log of the decay).
+    Returns o [N, Hv, Dv] (and the state after every token if asked; small inputs only)."""
+    q, k, v, g, beta = _f64(q), _f64(k), _f64(v), _f64(g), _f64(beta)
+    n, hk, dk = q.shape
+    hv, dv = v.shape[1], v.shape[2]
+    rep = hv // hk
+    scale = float(dk) ** -0.5 if scale is None else float(scale)
+    tok_pred = np.asarray(tok_pred, dtype=np.int64)
+    states = np.zeros((n, hv, dk, dv))
+    o = np.zeros((n, hv, dv))
+    for t in range(n):
+        p = tok_pred[t]
+        for h in range(hv):
+            kt, qt = k[t, h // rep], q[t, h // rep]
+            s = np.exp(g[t, h]) * (states[p, h] if p >= 0 else np.zeros((dk, dv)))
+            d = beta[t, h] * (v[t, h] - s.T @ kt)
+            s = s + np.outer(kt, d)
+            states[t, h] = s
+            o[t, h] = scale * (s.T @ qt)
+    return (o, states) if return_states else o

@@ -107,3 +107,101 @@ def test_short_parent_passes_grandparent_tail_on():
     m = M.dfs_meta([-1, -1], [2, 2])
     y, _ = S.tree_conv(np.asarray([[1.0], [2.0], [3.0], [4.0]]), w, None, m["tok_pred"], None)
     assert y[:, 0].tolist() == [1.0, 12.0, 3.0, 34.0]
+
+
+# ---- gated delta rule with tree state routing ----
+
+def _gdn_inputs(n, hk, hv, dk, dv, seed):
+    rng = np.random.default_rng(seed)
+    q = rng.normal(size=(n, hk, dk)); k = rng.normal(size=(n, hk, dk))
+    q /= np.linalg.norm(q, axis=-1, keepdims=True); k /= np.linalg.norm(k, axis=-1, keepdims=True)
+    v = rng.normal(size=(n, hv, dv))
+    g = -rng.uniform(0.01, 0.5, size=(n, hv))
+    beta = rng.uniform(0.1, 0.9, size=(n, hv))
+    return q, k, v, g, beta
+
+
+def _gdn_chain_library(q, k, v, g, beta, scale):
+    """One sequence, written with library matrix routines in the chunk-free 'delta rule as a linear
+    attention with a triangular solve' form: with decay products D_ij = exp(sum_{j<l<=i} g_l),
+    u = (I + tril(diag(beta) (K K^T) * D, -1))^{-1} diag(beta) V  and  o = scale * tril((Q K^T) * D) u.
+    A different route to the same numbers than the recurrence (whole sequence as one chunk, zero
+    initial state)."""
+    import scipy.linalg
+    n = len(q)
+    gc = np.cumsum(g)
+    D = np.exp(gc[:, None] - gc[None, :])
+    A = np.tril(beta[:, None] * (k @ k.T) * D, -1)
+    u = scipy.linalg.solve_triangular(np.eye(n) + A, beta[:, None] * v, lower=True, unit_diagonal=True)
+    return scale * (np.tril((q @ k.T) * D) @ u)
+
+
+def test_gdn_chain_equals_triangular_solve_form():
+    n, dk, dv = 37, 8, 5
+    q, k, v, g, beta = _gdn_inputs(n, 1, 1, dk, dv, 0)
+    tok_pred = np.arange(-1, n - 1)
+    o = S.gdn_tree(q, k, v, g, beta, tok_pred, scale=0.7)
+    want = _gdn_chain_library(q[:, 0], k[:, 0], v[:, 0], g[:, 0], beta[:, 0], 0.7)
+    assert np.allclose(o[:, 0], want, rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_gdn_tree_equals_every_branch_run_alone(seed):
+    """Forward equivalence (Eq. 6) for the SSM layer: a token's output in the tree equals its output
+    when its branch is run as a standalone sequence."""
+    t = W.random_tree(70 + seed, n_nodes=5 + 2 * seed, lo=1, hi=6, n_roots=1 + seed % 2, p_zero=0.15)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n = m["n_tokens"]
+    q, k, v, g, beta = _gdn_inputs(n, 2, 4, 6, 5, seed)
+    o = S.gdn_tree(q, k, v, g, beta, m["tok_pred"])
+    for p in M.paths(m):
+        if not len(p):
+            continue
+        chain = np.arange(-1, len(p) - 1)
+        ob = S.gdn_tree(q[p], k[p], v[p], g[p], beta[p], chain)
+        assert np.allclose(ob, o[p], rtol=1e-11, atol=1e-13)
+        for h in range(4):                      # and the library route on the same branch
+            want = _gdn_chain_library(q[p, h // 2], k[p, h // 2], v[p, h], g[p, h], beta[p, h], 6 ** -0.5)
+            assert np.allclose(o[p, h], want, rtol=1e-9, atol=1e-11)
+
+
+def test_gdn_sibling_state_does_not_leak():
+    """Figure "SSM state routing": n0 -> {n1 -> {n3, n4}, n2}; n2 must start from n0's state, so
+    nothing in n1's subtree may influence it, while n0's tokens must."""
+    m = M.dfs_meta([-1, 0, 0, 1, 1], [3, 2, 2, 2, 2])
+    n = m["n_tokens"]
+    q, k, v, g, beta = _gdn_inputs(n, 1, 1, 4, 3, 5)
+    rank = {int(i): rk for rk, i in enumerate(m["dfs_order"])}
+    tok = lambda nid: np.arange(m["node_start"][rank[nid]], m["node_end"][rank[nid]])
+    o = S.gdn_tree(q, k, v, g, beta, m["tok_pred"])
+    v2 = v.copy()
+    for nid in (1, 3, 4):
+        v2[tok(nid)] += 1.0
+    o2 = S.gdn_tree(q, k, v2, g, beta, m["tok_pred"])
+    assert np.array_equal(o2[tok(2)], o[tok(2)])
+    v3 = v.copy()
+    v3[tok(0)[-1]] += 1.0
+    assert not np.allclose(S.gdn_tree(q, k, v3, g, beta, m["tok_pred"])[tok(2)], o[tok(2)])
+
+
+def test_gdn_closed_forms():
+    # beta = 0: nothing is ever written, outputs are zero
+    q, k, v, g, beta = _gdn_inputs(9, 1, 2, 4, 3, 1)
+    assert np.all(S.gdn_tree(q, k, v, g, 0 * beta, np.arange(-1, 8)) == 0)
+    # one token, beta = 1: S = k v^T, o = scale (q.k) v
+    o = S.gdn_tree(q[:1], k[:1], v[:1], g[:1], np.ones((1, 2)), [-1], scale=1.0)
+    assert np.allclose(o[0], (q[0, 0] @ k[0, 0]) * v[0])
+    # beta = 1, no decay, the same unit key twice: the second write replaces the first value
+    kk = np.zeros((2, 1, 4)); kk[:, 0, 1] = 1.0
+    o = S.gdn_tree(kk, kk, v[:2, :1], np.zeros((2, 1)), np.ones((2, 1)), [-1, 0], scale=1.0)
+    assert np.allclose(o[1, 0], v[1, 0]) and np.allclose(o[0, 0], v[0, 0])
+    # orthogonal keys, beta = 1: plain decayed linear attention  o_t = sum_j exp(sum_{j<l<=t} g_l) (q_t.k_j) v_j
+    n = 4
+    ko = np.eye(4)[:n][:, None, :]
+    qq = np.random.default_rng(2).normal(size=(n, 1, 4))
+    gg = -np.random.default_rng(3).uniform(0.1, 0.4, size=(n, 1))
+    vv = v[:n, :1]
+    o = S.gdn_tree(qq, ko, vv, gg, np.ones((n, 1)), np.arange(-1, n - 1), scale=1.0)
+    for t_ in range(n):
+        want = sum(np.exp(gg[j + 1:t_ + 1, 0].sum()) * (qq[t_, 0] @ ko[j, 0]) * vv[j, 0] for j in range(t_ + 1))
+        assert np.allclose(o[t_, 0], want)
