@@ -432,6 +432,45 @@ tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_si
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Gated delta rule with tree state routing, forward (device; host plan)
+ *
+ * The recurrent core of a GDN layer, Section "Implementation", paragraph "SSM Layers (GDN)" (i)
+ * and Appendix "Tree-Aware SSM State Routing".  Per value head (key head = value head /
+ * (hv / hk)), state S in R^{dk x dv}; token t with predecessor p = tok_pred[t] on its own
+ * root-to-token sequence (S_p = 0 at the start of a branch):
+ *     S~ = exp(g_t) S_p;   S_t = S~ + beta_t k_t (v_t - S~^T k_t)^T;   o_t = scale S_t^T q_t
+ * i.e. a node's first token continues from the end state of its PARENT node, not from the
+ * previous node in DFS order.  Computed in chunks of TT_GDN_CHUNK tokens that never cross a node
+ * boundary (bf16 MFMA, fp32 accumulation, fp32 state).
+ * tt_tree_gdn_plan (host): the chunk list in DFS order and, per chunk, where its entering state
+ *   comes from and whether its leaving state must be kept:
+ *     chunk_tok0, chunk_len [n_chunks]   first token (DFS index) and length (1..TT_GDN_CHUNK)
+ *     chunk_src [n_chunks]   -2 = continues the previous chunk's sequence (state stays on chip),
+ *                            -1 = zero state, >= 0 = saved state slot
+ *     chunk_dst [n_chunks]   -1, or the slot the chunk's leaving state is saved to (nodes that
+ *                            have two or more token-bearing child branches)
+ *   Zero-length nodes have no chunk; their children continue from the nearest token-bearing
+ *   ancestor.
+ * tt_tree_gdn_fwd (device): q, k [n_tokens][hk][128], v, o [n_tokens][hv][128] bf16 contiguous;
+ *   g, beta [n_tokens][hv] fp32 (g <= 0: log of the decay); the four chunk arrays are device
+ *   copies of the plan.  dk = dv = 128, hv a multiple of hk.  q and k are used as given
+ *   (normalise them beforehand if the layer does).
+ * Errors: TT_ERR_NULL, TT_ERR_SHAPE, TT_ERR_TREE, TT_ERR_ALIGN, TT_ERR_UNSUPPORTED (dims other
+ *   than 128), TT_ERR_WORKSPACE.
+ * ------------------------------------------------------------------------------------------ */
+#define TT_GDN_CHUNK 64
+tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                                 int32_t* n_chunks, int32_t* n_slots);
+tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
+                           int32_t* chunk_tok0, int32_t* chunk_len, int32_t* chunk_src, int32_t* chunk_dst);
+size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32_t hv);
+tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
+                          const void* q, const void* k, const void* v, const float* g, const float* beta,
+                          int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                          const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                          void* o, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
  * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
  * the recorded events have completed and returns the totals since the last enable.
@@ -453,7 +492,9 @@ tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_si
 #define TT_KERNEL_CONV_FWD     14  /* tree-correct causal convolution                    */
 #define TT_KERNEL_CONV_BWD     15
 #define TT_KERNEL_CONV_FIX     16  /* its branch-point fix-up and weight-gradient reduce */
-#define TT_N_KERNELS          17
+#define TT_KERNEL_GDN_PREPARE  17  /* gated delta rule: per-chunk operands (parallel)     */
+#define TT_KERNEL_GDN_SCAN     18  /* gated delta rule: state scan over the tree          */
+#define TT_N_KERNELS          19
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

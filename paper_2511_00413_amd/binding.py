@@ -101,6 +101,16 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_conv_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp,
                                          ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_int32, _vp, _vp, _vp, _vp,
                                          _vp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_gdn_plan_sizes.restype = ctypes.c_int32
+        lib.tt_tree_gdn_plan_sizes.argtypes = [ctypes.c_int32, _vp, _vp, _c_i32p, _c_i32p]
+        lib.tt_tree_gdn_plan.restype = ctypes.c_int32
+        lib.tt_tree_gdn_plan.argtypes = [ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _vp]
+        lib.tt_tree_gdn_workspace.restype = ctypes.c_size_t
+        lib.tt_tree_gdn_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.tt_tree_gdn_fwd.restype = ctypes.c_int32
+        lib.tt_tree_gdn_fwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                        _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp,
+                                        ctypes.c_size_t, _vp]
         lib.tt_tree_path_weights.restype = ctypes.c_int32
         lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
@@ -122,7 +132,7 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix")
+                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix", "gdn_prepare", "gdn_scan")
 
 
 class _KernelTimes(ctypes.Structure):
@@ -239,6 +249,37 @@ class ConvPlan:
         torch = _torch()
         self.device = {n: torch.from_numpy(getattr(self, n)).to(device) for n in ("fix_tok", "fix_off", "fix_t", "fix_r")}
         return self
+
+
+GDN_CHUNK = 64
+
+
+@dataclass
+class GdnPlan:
+    """Host output of tt_tree_gdn_plan: the chunk program of the gated-delta-rule scan."""
+    n_chunks: int
+    n_slots: int
+    chunk_tok0: np.ndarray
+    chunk_len: np.ndarray
+    chunk_src: np.ndarray
+    chunk_dst: np.ndarray
+    device: Optional[dict] = None
+
+    def to_device(self, device="cuda"):
+        torch = _torch()
+        self.device = {n: torch.from_numpy(getattr(self, n)).to(device) for n in ("chunk_tok0", "chunk_len", "chunk_src", "chunk_dst")}
+        return self
+
+
+def tree_gdn_plan(parent, seg_len) -> GdnPlan:
+    parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
+    if len(parent) != len(seg_len):
+        raise ValueError("parent and seg_len differ in length")
+    nc, ns = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(_lib().tt_tree_gdn_plan_sizes(len(parent), _hp(parent), _hp(seg_len), ctypes.byref(nc), ctypes.byref(ns)))
+    arrs = [np.zeros(nc.value, np.int32) for _ in range(4)]
+    _check(_lib().tt_tree_gdn_plan(len(parent), _hp(parent), _hp(seg_len), *(_hp(a) for a in arrs)))
+    return GdnPlan(nc.value, ns.value, *arrs)
 
 
 def tree_conv_plan(tok_pred, kernel_size: int) -> ConvPlan:
@@ -608,3 +649,31 @@ def tree_conv_bwd(x, weight, bias, tok_pred, dy, plan: ConvPlan, *, silu: bool =
                                    _dp(d["fix_t"]), _dp(d["fix_r"]), _dp(dx), _row_stride(dx), _dp(dw), _dp(db),
                                    _dp(workspace), workspace.numel(), _stream_ptr(stream)))
     return dx, dw, db
+
+
+def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, workspace=None, stream=None):
+    """Gated delta rule with tree state routing: q, k [n, hk, 128], v [n, hv, 128] bf16 contiguous; g, beta
+    [n, hv] fp32 (g = log decay <= 0).  Returns o [n, hv, 128] bf16."""
+    torch = _torch()
+    for t in (q, k, v):
+        if t.dim() != 3 or t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError("q, k, v must be contiguous bf16 [tokens, heads, dim]")
+    n, hk, dk = q.shape
+    hv, dv = v.shape[1], v.shape[2]
+    if k.shape != q.shape or v.shape[0] != n:
+        raise ValueError("k must match q, v must have the same token count")
+    for t in (g, beta):
+        if t.shape != (n, hv) or t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("g, beta must be contiguous fp32 [tokens, hv]")
+    if plan.device is None:
+        plan.to_device(q.device)
+    if out is None:
+        out = torch.empty((n, hv, dv), dtype=torch.bfloat16, device=q.device)
+    need = int(_lib().tt_tree_gdn_workspace(plan.n_chunks, plan.n_slots, hv))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    d = plan.device
+    _check(_lib().tt_tree_gdn_fwd(n, hk, hv, dk, dv, float(dk) ** -0.5 if scale is None else float(scale), _dp(q), _dp(k), _dp(v),
+                                  _dp(g), _dp(beta), plan.n_chunks, _dp(d["chunk_tok0"]), _dp(d["chunk_len"]), _dp(d["chunk_src"]),
+                                  _dp(d["chunk_dst"]), plan.n_slots, _dp(out), _dp(workspace), workspace.numel(), _stream_ptr(stream)))
+    return out

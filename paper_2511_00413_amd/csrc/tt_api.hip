@@ -279,3 +279,34 @@ extern "C" tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_
                                  n_fix, fix_tok, fix_off, fix_t, fix_r, dx, c.ys, dweight, dbias, workspace, (hipStream_t)stream),
                     "tree_conv_bwd");
 }
+
+extern "C" size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32_t hv) {
+  tt::clear_error();
+  if (n_chunks < 0 || n_slots < 0 || hv <= 0) return 0;
+  return tt::gdn_workspace(n_chunks, n_slots, hv);
+}
+
+extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
+                                     const void* q, const void* k, const void* v, const float* g, const float* beta,
+                                     int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                                     const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots, void* o,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  tt::clear_error();
+  if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
+  if (dk != 128 || dv != 128) return fail(TT_ERR_UNSUPPORTED, "dk=%d, dv=%d: only 128 x 128 states are built", dk, dv);
+  if (hk <= 0 || hv <= 0 || hv % hk != 0 || hv > 65535) return fail(TT_ERR_SHAPE, "hv=%d must be a positive multiple of hk=%d", hv, hk);
+  if (!(scale > 0.f) || !std::isfinite(scale)) return fail(TT_ERR_SHAPE, "scale must be positive and finite");
+  if (n_chunks < 0 || n_slots < 0 || n_chunks > 65535 * 16) return fail(TT_ERR_SHAPE, "n_chunks=%d, n_slots=%d out of range", n_chunks, n_slots);
+  if ((n_tokens > 0) != (n_chunks > 0)) return fail(TT_ERR_SHAPE, "n_tokens=%lld with %d chunks", (long long)n_tokens, n_chunks);
+  if (n_chunks > 0 && (!q || !k || !v || !g || !beta || !o || !chunk_tok0 || !chunk_len || !chunk_src || !chunk_dst))
+    return fail(TT_ERR_NULL, "a tensor or plan pointer is NULL");
+  const void* ptrs[] = {q, k, v, o};
+  for (const void* p : ptrs)
+    if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
+  const size_t need = tt::gdn_workspace(n_chunks, n_slots, hv);
+  if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
+    return fail(TT_ERR_WORKSPACE, "gdn forward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+  return hip_result(tt::gdn_fwd(n_tokens, hk, hv, scale, q, k, v, g, beta, n_chunks, chunk_tok0, chunk_len, chunk_src, chunk_dst,
+                                n_slots, o, workspace, (hipStream_t)stream),
+                    "tree_gdn_fwd");
+}

@@ -1,0 +1,316 @@
+// Gated delta rule with tree state routing, forward (Section "Implementation", paragraph "SSM Layers
+// (GDN)" (i); Appendix "Tree-Aware SSM State Routing"): the recurrent state at a node's first token
+// is the end state of its parent node, not of the previous node in DFS order.
+//
+// Chunked form, 64 tokens per chunk, chunks never cross a node boundary.  With gamma_i the running
+// sum of the log-decays inside a chunk, beta the write strengths and S0 the state entering the chunk:
+//     A  = strictly-lower( beta_i (k_i . k_j) exp(gamma_i - gamma_j) )
+//     U  = (I + A)^-1 (beta * V)                 W = (I + A)^-1 (beta * exp(gamma) * K)
+//     Vn = U - W S0
+//     O  = scale (Q * exp(gamma)) S0 + scale tril( (Q K^T) * exp(gamma_i - gamma_j) ) Vn
+//     S1 = exp(gamma_last) S0 + (K * exp(gamma_last - gamma))^T Vn
+// which is the token recurrence  S <- e^g S + beta k (v - (e^g S)^T k)^T,  o = scale S^T q  written
+// per chunk.  Two kernels:
+//   gdn_prepare_kernel  (chunk, value head): everything that does not depend on S0 -- K K^T and
+//       Q K^T on MFMA, the unit-lower-triangular solve by forward substitution with one lane per
+//       column of [V | K] (no synchronisation inside the solve), operands written in the layouts
+//       the second kernel's MFMA fragments want;
+//   gdn_scan_kernel  (32 value columns, value head): walks the chunks in DFS order with the state
+//       in MFMA accumulators (the columns of S evolve independently, so a head is cut into four
+//       independent workgroups); state routing = where a chunk takes S0 from (registers when it
+//       continues the previous chunk's sequence, a saved node-end state, or zero).
+#include <hip/hip_runtime.h>
+#include "tt_internal.h"
+#include "tt_kernels.h"
+#include "tt_mfma.h"
+
+namespace tt {
+namespace {
+
+constexpr int GC = TT_GDN_CHUNK;     // tokens per chunk (64)
+constexpr int GD = 128;              // head dim of keys and values
+constexpr int GROW = GD + 8;         // padded LDS row (elements) for [*][128] bf16 tiles
+constexpr int G_THREADS = 256;
+constexpr int G_DVB = 32;            // value columns per scan workgroup
+
+struct GdnArgs {
+  int n_tokens, hk, hv, n_chunks;
+  float scale;
+  const __bf16 *q, *k, *v;           // [N][hk][128], [N][hk][128], [N][hv][128]
+  const float *g, *beta;             // [N][hv]
+  const int32_t *chunk_tok0, *chunk_len, *chunk_src, *chunk_dst;
+  __bf16* o;                         // [N][hv][128]
+  // per (chunk, value head) operands
+  __bf16* wn;                        // [64][128]  -W
+  __bf16* ut;                        // [128][64]  U transposed
+  __bf16* qg;                        // [64][128]  scale * Q * exp(gamma)
+  __bf16* kdt;                       // [128][64]  (K * exp(gamma_last - gamma)) transposed
+  __bf16* p;                         // [64][64]   scale * tril((Q K^T) * exp(gamma_i - gamma_j))
+  float* glast;                      // exp(gamma_last)
+  float* slots;                      // [n_slots][hv][128][128] saved node-end states
+};
+
+__device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)chunk * a.hv + h; }
+
+__global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
+  __shared__ __attribute__((aligned(16))) __bf16 ksm[GC][GROW];
+  __shared__ __attribute__((aligned(16))) __bf16 qsm[GC][GROW];
+  __shared__ __attribute__((aligned(16))) float am[GC][GC];
+  __shared__ float gam[GC], bet[GC];
+
+  const int chunk = blockIdx.x, h = blockIdx.y;
+  const int hkv = h / (a.hv / a.hk);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tok0 = a.chunk_tok0[chunk], len = a.chunk_len[chunk];
+  const size_t op = op_index(a, chunk, h);
+
+  if (tid < GC) {
+    const bool in = tid < len;
+    gam[tid] = in ? a.g[(size_t)(tok0 + tid) * a.hv + h] : 0.f;
+    bet[tid] = in ? a.beta[(size_t)(tok0 + tid) * a.hv + h] : 0.f;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float run = 0.f;
+    for (int i = 0; i < GC; i++) { run += gam[i]; gam[i] = run; }
+    a.glast[op] = __expf(run);
+  }
+  __syncthreads();
+  const float g_last = gam[GC - 1];
+
+  // K and Q rows into LDS (zero rows past the chunk's length); Qg written on the way
+  for (int piece = tid; piece < GC * (GD / 8); piece += G_THREADS) {
+    const int i = piece >> 4, c8 = (piece & 15) * 8;
+    bf16x8 kv, qv;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { kv[e] = (__bf16)0.f; qv[e] = (__bf16)0.f; }
+    if (i < len) {
+      kv = *(const bf16x8*)(a.k + ((size_t)(tok0 + i) * a.hk + hkv) * GD + c8);
+      qv = *(const bf16x8*)(a.q + ((size_t)(tok0 + i) * a.hk + hkv) * GD + c8);
+    }
+    *(bf16x8*)&ksm[i][c8] = kv;
+    *(bf16x8*)&qsm[i][c8] = qv;
+    *(bf16x8*)(a.qg + op * (GC * GD) + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
+  }
+  __syncthreads();
+
+  // K K^T and Q K^T, one 32x32 tile per wave; the tile above the diagonal is not needed
+  {
+    const int ib = w >> 1, jb = w & 1;
+    const int c = lane & 31, hf = lane >> 5;
+    if (jb <= ib) {
+      f32x16 kk = zero16(), qk = zero16();
+#pragma unroll
+      for (int ks = 0; ks < GD / 16; ks++) {
+        const bf16x8 kj = *(const bf16x8*)&ksm[jb * 32 + c][ks * 16 + hf * 8];
+        const bf16x8 ki = *(const bf16x8*)&ksm[ib * 32 + c][ks * 16 + hf * 8];
+        const bf16x8 qi = *(const bf16x8*)&qsm[ib * 32 + c][ks * 16 + hf * 8];
+        kk = mfma32(ki, kj, kk);
+        qk = mfma32(qi, kj, qk);
+      }
+      const int j = jb * 32 + c;
+      __bf16* pout = a.p + op * (GC * GC);
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+        const float dec = j <= i ? __expf(gam[i] - gam[j]) : 0.f;
+        am[i][j] = j < i ? bet[i] * kk[r] * dec : 0.f;
+        pout[i * GC + j] = (__bf16)(a.scale * qk[r] * dec);
+      }
+    } else {
+      const int j = jb * 32 + c;
+      __bf16* pout = a.p + op * (GC * GC);
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+        am[i][j] = 0.f;
+        pout[i * GC + j] = (__bf16)0.f;
+      }
+    }
+  }
+
+  // (K * exp(gamma_last - gamma)) transposed: one 16-byte piece = 8 consecutive tokens of one dim
+  for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
+    const int d = piece >> 3, i0 = (piece & 7) * 8;
+    float f[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
+    *(bf16x8*)(a.kdt + op * (GD * GC) + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+  }
+  __syncthreads();
+
+  // forward substitution, one lane per column of [beta V | beta exp(gamma) K]:
+  //   x_i = rhs_i - sum_{j<i} A_ij x_j
+  {
+    const int c = tid;                  // 0..127: value column, 128..255: key column
+    float x[GC];
+#pragma unroll
+    for (int i = 0; i < GC; i++) {
+      float rhs = 0.f;
+      if (i < len) {
+        if (c < GD) rhs = bet[i] * (float)a.v[((size_t)(tok0 + i) * a.hv + h) * GD + c];
+        else        rhs = bet[i] * __expf(gam[i]) * (float)ksm[i][c - GD];
+#pragma unroll
+        for (int j4 = 0; j4 < (i + 3) / 4; j4++) {
+          const float4 av = *(const float4*)&am[i][j4 * 4];      // entries at j >= i are zero
+          const float ae[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+          for (int e = 0; e < 4; e++)
+            if (j4 * 4 + e < i) rhs -= ae[e] * x[j4 * 4 + e];
+        }
+      }
+      x[i] = rhs;
+    }
+    if (c < GD) {
+      __bf16* dst = a.ut + op * (GD * GC) + c * GC;
+#pragma unroll
+      for (int i0 = 0; i0 < GC; i0 += 8)
+        *(bf16x8*)(dst + i0) = cvt8(x[i0], x[i0 + 1], x[i0 + 2], x[i0 + 3], x[i0 + 4], x[i0 + 5], x[i0 + 6], x[i0 + 7]);
+    } else {
+      __bf16* dst = a.wn + op * (GC * GD) + (c - GD);
+#pragma unroll
+      for (int i = 0; i < GC; i++) dst[i * GD] = (__bf16)(-x[i]);
+    }
+  }
+}
+
+// 8 k-values in the order in which an accumulator's registers enumerate rows: elements e = 0..3 are
+// columns base + 4 hf .. +3, e = 4..7 columns base + 8 + 4 hf .. +3 of a row-major matrix row.
+__device__ __forceinline__ bf16x8 load_perm_k(const __bf16* row, int base, int hf) {
+  const bf16x4 lo = *(const bf16x4*)(row + base + 4 * hf);
+  const bf16x4 hi = *(const bf16x4*)(row + base + 8 + 4 * hf);
+  return cat4(lo, hi);
+}
+
+__global__ __launch_bounds__(G_THREADS) void gdn_scan_kernel(GdnArgs a) {
+  __shared__ __attribute__((aligned(16))) __bf16 st[G_DVB][GROW];      // S0 transposed: [value col][key dim]
+
+  const int dvb = blockIdx.x, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane & 31, hf = lane >> 5;
+  f32x16 s = zero16();                  // S[32 w + rows(r)][dvb*32 + c]
+
+  for (int chunk = 0; chunk < a.n_chunks; chunk++) {
+    const int tok0 = a.chunk_tok0[chunk], len = a.chunk_len[chunk];
+    const int src = a.chunk_src[chunk], dst = a.chunk_dst[chunk];
+    const size_t op = op_index(a, chunk, h);
+    if (src == -1) {
+      s = zero16();
+    } else if (src >= 0) {
+      const float* sp = a.slots + ((size_t)src * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+      for (int r = 0; r < 16; r++) s[r] = sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
+    }
+    // S0 -> bf16, transposed into LDS
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++)
+      *(bf16x4*)&st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
+    __syncthreads();
+
+    bf16x8 sfrag[GD / 16];              // B operand: column c of S0, k = key dims
+#pragma unroll
+    for (int ks = 0; ks < GD / 16; ks++) sfrag[ks] = *(const bf16x8*)&st[c][ks * 16 + hf * 8];
+
+    // Vn = U - W S0 (every wave computes all 64 rows: it needs them all as the k dimension below)
+    const __bf16* wn = a.wn + op * (GC * GD);
+    const __bf16* ut = a.ut + op * (GD * GC) + (size_t)(dvb * G_DVB + c) * GC;
+    bf16x8 vfrag[2][2];                 // Vn as B operand, k = tokens, accumulator row order
+#pragma unroll
+    for (int rb = 0; rb < 2; rb++) {
+      f32x16 acc;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++) {
+        const bf16x4 u4 = *(const bf16x4*)(ut + rb * 32 + r4 * 8 + hf * 4);
+#pragma unroll
+        for (int e = 0; e < 4; e++) acc[4 * r4 + e] = (float)u4[e];
+      }
+#pragma unroll
+      for (int ks = 0; ks < GD / 16; ks++)
+        acc = mfma32(*(const bf16x8*)(wn + (rb * 32 + c) * GD + ks * 16 + hf * 8), sfrag[ks], acc);
+#pragma unroll
+      for (int t = 0; t < 2; t++)
+        vfrag[rb][t] = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
+                            acc[8 * t + 6], acc[8 * t + 7]);
+    }
+
+    // O rows 32 w .. 32 w + 31 (waves 0 and 1)
+    if (w < 2) {
+      f32x16 oacc = zero16();
+      const __bf16* qg = a.qg + op * (GC * GD) + (size_t)(w * 32 + c) * GD;
+#pragma unroll
+      for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(*(const bf16x8*)(qg + ks * 16 + hf * 8), sfrag[ks], oacc);
+      const __bf16* pr = a.p + op * (GC * GC) + (size_t)(w * 32 + c) * GC;
+#pragma unroll
+      for (int jb = 0; jb < 2; jb++) {
+        if (jb > w) continue;           // P is lower triangular
+#pragma unroll
+        for (int t = 0; t < 2; t++) oacc = mfma32(load_perm_k(pr, jb * 32 + t * 16, hf), vfrag[jb][t], oacc);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = w * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+        if (i < len) a.o[((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + c] = (__bf16)oacc[r];
+      }
+    }
+
+    // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state
+    {
+      const float gl = a.glast[op];
+#pragma unroll
+      for (int r = 0; r < 16; r++) s[r] *= gl;
+      const __bf16* kd = a.kdt + op * (GD * GC) + (size_t)(32 * w + c) * GC;
+#pragma unroll
+      for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) s = mfma32(load_perm_k(kd, jb * 32 + t * 16, hf), vfrag[jb][t], s);
+    }
+    if (dst >= 0) {
+      float* sp = a.slots + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
+    }
+    __syncthreads();                    // every wave is done with st before the next chunk rewrites it
+  }
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+}  // namespace
+
+size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
+  const size_t per = (size_t)n_chunks * hv;
+  return align256(per * GC * GD * 2) * 4 + align256(per * GC * GC * 2) + align256(per * 4) +
+         align256((size_t)n_slots * hv * GD * GD * 4) + 256;
+}
+
+hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
+                   const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
+                   const int32_t* chunk_dst, int n_slots, void* o, void* workspace, hipStream_t st) {
+  if (n_chunks == 0) return hipSuccess;
+  GdnArgs a{};
+  a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
+  a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v; a.g = g; a.beta = beta;
+  a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len; a.chunk_src = chunk_src; a.chunk_dst = chunk_dst;
+  a.o = (__bf16*)o;
+  const size_t per = (size_t)n_chunks * hv;
+  char* p = (char*)workspace;
+  a.wn = (__bf16*)p;  p += align256(per * GC * GD * 2);
+  a.ut = (__bf16*)p;  p += align256(per * GC * GD * 2);
+  a.qg = (__bf16*)p;  p += align256(per * GC * GD * 2);
+  a.kdt = (__bf16*)p; p += align256(per * GC * GD * 2);
+  a.p = (__bf16*)p;   p += align256(per * GC * GC * 2);
+  a.glast = (float*)p; p += align256(per * 4);
+  a.slots = (float*)p;
+  {
+    KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
+    gdn_prepare_kernel<<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
+  }
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  {
+    KernelTimer t(TT_KERNEL_GDN_SCAN, st);
+    gdn_scan_kernel<<<dim3(GD / G_DVB, hv), G_THREADS, 0, st>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace tt

@@ -76,4 +76,10 @@ hipError_t conv_bwd(int64_t n_tokens, int channels, int kernel_size, bool bf16, 
                     void* dx, int64_t dx_stride_bytes, float* dweight, float* dbias, void* workspace, hipStream_t st);
 size_t conv_bwd_workspace(int64_t n_tokens, int channels, int kernel_size, bool bf16);
 
+// gated delta rule with tree state routing, forward (tt_gdn.hip); dk = dv = 128, bf16
+hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
+                   const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
+                   const int32_t* chunk_dst, int n_slots, void* o, void* workspace, hipStream_t st);
+size_t gdn_workspace(int n_chunks, int n_slots, int hv);
+
 }  // namespace tt

@@ -295,3 +295,76 @@ extern "C" tt_status tt_tree_conv_plan(int64_t n_tokens, const int32_t* tok_pred
   fix_off[nf] = (int32_t)s_of.size();
   return TT_OK;
 }
+
+namespace {
+
+struct GdnPlan {
+  std::vector<int32_t> tok0, len, src, dst;
+  int32_t n_slots = 0;
+};
+
+// Chunk program of the gated-delta-rule scan: nodes in DFS order, TT_GDN_CHUNK tokens per chunk.
+tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, GdnPlan& pl) {
+  Forest f;
+  if (tt_status s = build_forest(n_nodes, parent, seg_len, 0, f)) return s;
+  // nearest token-bearing ancestor (input numbering), -1 if none
+  std::vector<int32_t> eff(n_nodes, -1), branches(n_nodes, 0), slot(n_nodes, -1), last_chunk(n_nodes, -1);
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk], p = parent[i];
+    eff[i] = p < 0 ? -1 : (seg_len[p] > 0 ? p : eff[p]);
+    if (seg_len[i] > 0 && eff[i] >= 0) branches[eff[i]]++;
+  }
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    if (branches[i] >= 2) slot[i] = pl.n_slots++;     // a single continuation stays on chip
+  }
+  int64_t tok = 0;
+  for (int32_t rk = 0; rk < n_nodes; rk++) {
+    const int32_t i = f.order[rk];
+    for (int32_t off = 0; off < seg_len[i]; off += TT_GDN_CHUNK) {
+      const int32_t n = seg_len[i] - off < TT_GDN_CHUNK ? seg_len[i] - off : TT_GDN_CHUNK;
+      int32_t src = -2;
+      if (off == 0) {
+        const int32_t e = eff[i];
+        if (e < 0) src = -1;
+        else if (last_chunk[e] == (int32_t)pl.tok0.size() - 1) src = -2;      // directly after its parent's last chunk
+        else src = slot[e];
+      }
+      pl.tok0.push_back((int32_t)(tok + off));
+      pl.len.push_back(n);
+      pl.src.push_back(src);
+      pl.dst.push_back(-1);
+    }
+    if (seg_len[i] > 0) {
+      last_chunk[i] = (int32_t)pl.tok0.size() - 1;
+      pl.dst.back() = slot[i];
+    }
+    tok += seg_len[i];
+  }
+  return TT_OK;
+}
+
+}  // namespace
+
+extern "C" tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t* n_chunks,
+                                            int32_t* n_slots) {
+  tt::clear_error();
+  if (!n_chunks || !n_slots) return tt::fail(TT_ERR_NULL, "n_chunks / n_slots is NULL");
+  GdnPlan pl;
+  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, pl)) return s;
+  *n_chunks = (int32_t)pl.tok0.size();
+  *n_slots = pl.n_slots;
+  return TT_OK;
+}
+
+extern "C" tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t* chunk_tok0,
+                                      int32_t* chunk_len, int32_t* chunk_src, int32_t* chunk_dst) {
+  tt::clear_error();
+  GdnPlan pl;
+  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, pl)) return s;
+  if (!pl.tok0.empty() && (!chunk_tok0 || !chunk_len || !chunk_src || !chunk_dst)) return tt::fail(TT_ERR_NULL, "an output array is NULL");
+  for (size_t c = 0; c < pl.tok0.size(); c++) {
+    chunk_tok0[c] = pl.tok0[c]; chunk_len[c] = pl.len[c]; chunk_src[c] = pl.src[c]; chunk_dst[c] = pl.dst[c];
+  }
+  return TT_OK;
+}

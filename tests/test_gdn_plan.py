@@ -1,0 +1,56 @@
+"""tt_tree_gdn_plan (host C++): run the chunk program on symbolic states (the state after token t is
+called t) and check that every chunk enters with the state of its first token's predecessor."""
+import numpy as np
+import pytest
+
+import paper_2511_00413_amd as T
+import workloads as W
+from oracle import meta as M
+
+
+def _simulate(parent, seg):
+    m = M.dfs_meta(parent, seg)
+    plan = T.tree_gdn_plan(parent, seg)
+    assert plan.n_chunks == sum(-(-int(s) // T.GDN_CHUNK) for s in seg)
+    state = -1                       # symbolic: index of the token whose state is held on chip; -1 = zero
+    slots = {}
+    covered = []
+    for c in range(plan.n_chunks):
+        t0, n, src, dst = (int(x[c]) for x in (plan.chunk_tok0, plan.chunk_len, plan.chunk_src, plan.chunk_dst))
+        assert 1 <= n <= T.GDN_CHUNK
+        if src == -1:
+            state = -1
+        elif src >= 0:
+            assert src in slots, "a slot is read before it was written"
+            state = slots[src]
+        assert state == m["tok_pred"][t0], f"chunk {c} enters with the wrong state"
+        toks = list(range(t0, t0 + n))
+        assert len(set(m["tok_node"][toks])) == 1, "a chunk crosses a node boundary"
+        for t in toks[1:]:
+            assert m["tok_pred"][t] == t - 1
+        covered += toks
+        state = toks[-1]
+        if dst >= 0:
+            assert 0 <= dst < plan.n_slots
+            slots[dst] = state
+    assert covered == list(range(m["n_tokens"]))
+    return plan
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_random_trees(seed):
+    t = W.random_tree(860 + seed, n_nodes=2 + 3 * seed, lo=1, hi=200, n_roots=1 + seed % 3, p_zero=0.2)
+    _simulate(list(t.parent), list(t.seg_len))
+
+
+def test_shapes():
+    plan = _simulate([-1, 0, 1], [64, 65, 1])                 # a chain: nothing is saved, everything continues
+    assert plan.n_slots == 0 and plan.chunk_src.tolist() == [-1, -2, -2, -2] and plan.chunk_len.tolist() == [64, 64, 1, 1]
+    plan = _simulate([-1, 0, 0, 0], [10, 5, 0, 7])           # two token-bearing children + an empty one
+    assert plan.n_slots == 1 and plan.chunk_src.tolist() == [-1, -2, 0] and plan.chunk_dst.tolist() == [0, -1, -1]
+    plan = _simulate([-1, 0, 1, 1], [10, 0, 3, 4])           # children hang below a zero-length node
+    assert plan.chunk_src.tolist() == [-1, -2, 0]
+    for cfg in (2, 3, 4):
+        t = W.tree_config(cfg)
+        _simulate(list(t.parent), list(t.seg_len))
+    assert T.tree_gdn_plan([], []).n_chunks == 0
