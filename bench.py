@@ -45,6 +45,7 @@ def parse_args():
     ap.add_argument("--no-rope", action="store_true")
     ap.add_argument("--no-partitioned", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
+    ap.add_argument("--no-gdn", action="store_true")
     ap.add_argument("--conv-channels", type=int, default=8192,
                     help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
     ap.add_argument("--partition-gather-all", action="store_true",
@@ -358,6 +359,42 @@ def main():
                 "bwd_frac_of_hbm_peak": round(b_bytes / (b_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}
         del xc, dyc, yc
 
+    # ---------------- gated delta rule with tree state routing on the same tree (SSM-layer adaptation) ----------------
+    gdn = None
+    if not args.no_gdn and n_prefix == 0 and dims.dtype == "bf16":
+        ghk, ghv = 16, 32                                   # key / value heads of the GDN layer, 128 x 128 states
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg * 1000 + 11)
+        gq = torch.randn((N, ghk, 128), generator=gen, device=dev, dtype=torch.float32)
+        gk = torch.randn((N, ghk, 128), generator=gen, device=dev, dtype=torch.float32)
+        gq = (gq / gq.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+        gk = (gk / gk.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+        gv = torch.randn((N, ghv, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        gg = -(torch.rand((N, ghv), generator=gen, device=dev) * 0.2 + 0.005)
+        gb = torch.rand((N, ghv), generator=gen, device=dev) * 0.8 + 0.1
+        gplan = T.tree_gdn_plan(tree.parent, tree.seg_len).to_device(dev)
+        go = torch.empty_like(gv)
+        gws = torch.empty(T.binding._lib().tt_tree_gdn_workspace(gplan.n_chunks, gplan.n_slots, ghv), dtype=torch.uint8, device=dev)
+        n_it = max(3, min(args.steps, 10))
+        for it in range(2 + n_it):
+            if it == 2:
+                torch.cuda.synchronize()
+                T.kernel_timing_enable(True)
+            T.tree_gdn_fwd(gq, gk, gv, gg, gb, gplan, out=go, workspace=gws)
+        gt = T.kernel_timing_read()
+        T.kernel_timing_enable(False)
+        p_ms, s_ms = gt["gdn_prepare"][0] / n_it, gt["gdn_scan"][0] / n_it
+        # MFMA flop actually needed per 64-token chunk and head: K K^T, Q K^T (lower halves count in full here),
+        # W S0, Q S0, P Vn, K^T Vn
+        chunk_flop = 2.0 * (2 * 64 * 64 * 128 + 2 * 64 * 128 * 128 + 64 * 64 * 128 + 128 * 64 * 128)
+        gdn = {"hk": ghk, "hv": ghv, "dk": 128, "dv": 128, "n_chunks": gplan.n_chunks, "saved_states": gplan.n_slots,
+               "ms_prepare": round(p_ms, 4), "ms_scan": round(s_ms, 4), "ms_fwd": round(p_ms + s_ms, 4),
+               "tokens_per_s": round(N / ((p_ms + s_ms) * 1e-3), 1),
+               "chunk_tflops": round(chunk_flop * gplan.n_chunks * ghv / ((p_ms + s_ms) * 1e-3) / 1e12, 2),
+               "us_per_chunk_step": round(s_ms * 1e3 / max(gplan.n_chunks, 1), 3),
+               "workspace_mb": round(gws.numel() / 1e6, 1)}
+        del gq, gk, gv, go, gws
+
     # ---------------- CPU oracle on a bounded sample (context only) ----------------
     cpu = None
     if not args.no_cpu_baseline and n_prefix == 0:
@@ -409,6 +446,7 @@ def main():
         "linearized": lin,
         "partitioned": part,
         "tree_conv": conv,
+        "tree_gdn": gdn,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

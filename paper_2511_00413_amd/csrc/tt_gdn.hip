@@ -182,94 +182,181 @@ __device__ __forceinline__ bf16x8 load_perm_k(const __bf16* row, int base, int h
   return cat4(lo, hi);
 }
 
-__global__ __launch_bounds__(G_THREADS) void gdn_scan_kernel(GdnArgs a) {
-  __shared__ __attribute__((aligned(16))) __bf16 st[G_DVB][GROW];      // S0 transposed: [value col][key dim]
+// LDS image of one chunk's operands (rows padded by 8 elements against bank conflicts)
+constexpr int GROW64 = GC + 8;
+struct ScanSmem {
+  __bf16 wn[GC][GROW];          // -W
+  __bf16 qg[GC][GROW];          // scale Q exp(gamma)
+  __bf16 kd[GD][GROW64];        // (K decayed)^T
+  __bf16 ut[G_DVB][GROW64];     // U^T, this workgroup's value columns
+  __bf16 p[GC][GROW64];         // scale tril(Q K^T decay)
+  __bf16 st[G_DVB][GROW];       // S0^T
+  __bf16 ot[2][32][G_DVB + 8];  // output tiles of waves 0 and 1 on their way to 16-byte stores
+};
+constexpr int SCAN_PIECES = (GC * GD * 3 + G_DVB * GC + GC * GC) / 8 / G_THREADS;   // 16-byte pieces per lane: 15
+static_assert(SCAN_PIECES * G_THREADS * 8 == GC * GD * 3 + G_DVB * GC + GC * GC, "operands must split evenly over the lanes");
 
-  const int dvb = blockIdx.x, h = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+typedef unsigned u32x4n __attribute__((ext_vector_type(4)));      // native vector type (stays in registers)
+
+// One chunk's operands as 16-byte pieces, 15 per lane, every wave-level load contiguous in memory.
+struct ChunkRegs {
+  u32x4n v[SCAN_PIECES];
+  int tok0, len, src, dst;
+  float glast;
+};
+
+// piece index -> (global address, LDS address); pieces 0..1023 Wn, ..2047 Qg, ..3071 KdT, ..3327 UT block, ..3839 P
+__device__ __forceinline__ const u32x4n* piece_src(const GdnArgs& a, size_t op, int dvb, int piece) {
+  if (piece < 1024) return (const u32x4n*)(a.wn + op * (GC * GD)) + piece;
+  if (piece < 2048) return (const u32x4n*)(a.qg + op * (GC * GD)) + (piece - 1024);
+  if (piece < 3072) return (const u32x4n*)(a.kdt + op * (GD * GC)) + (piece - 2048);
+  if (piece < 3328) return (const u32x4n*)(a.ut + op * (GD * GC) + (size_t)dvb * G_DVB * GC) + (piece - 3072);
+  return (const u32x4n*)(a.p + op * (GC * GC)) + (piece - 3328);
+}
+__device__ __forceinline__ u32x4n* piece_dst(ScanSmem& sm, int piece) {
+  if (piece < 1024) return (u32x4n*)&sm.wn[piece >> 4][(piece & 15) * 8];
+  if (piece < 2048) return (u32x4n*)&sm.qg[(piece - 1024) >> 4][(piece & 15) * 8];
+  if (piece < 3072) return (u32x4n*)&sm.kd[(piece - 2048) >> 3][(piece & 7) * 8];
+  if (piece < 3328) return (u32x4n*)&sm.ut[(piece - 3072) >> 3][(piece & 7) * 8];
+  return (u32x4n*)&sm.p[(piece - 3328) >> 3][(piece & 7) * 8];
+}
+
+// `z` is a per-lane zero the compiler cannot see through: the chunk's scalars are loaded per lane and
+// stay in vector registers, so the wait for them sits at their first use two chunks later (a value
+// proven uniform is moved to a scalar register right behind its load, which would stall every chunk
+// for a full memory latency).
+__device__ __forceinline__ void load_chunk(const GdnArgs& a, int chunk, int h, int dvb, int tid, int z, ChunkRegs& r) {
+  r.tok0 = a.chunk_tok0[chunk + z]; r.len = a.chunk_len[chunk + z]; r.src = a.chunk_src[chunk + z]; r.dst = a.chunk_dst[chunk + z];
+  const size_t op = op_index(a, chunk, h);
+  r.glast = a.glast[op + z];
+#pragma unroll
+  for (int i = 0; i < SCAN_PIECES; i++) r.v[i] = *piece_src(a, op, dvb, i * G_THREADS + tid);
+}
+
+__device__ __forceinline__ bf16x8 lds_perm_k(const __bf16* row, int base, int hf) {
+  const bf16x4 lo = *(const bf16x4*)(row + base + 4 * hf);
+  const bf16x4 hi = *(const bf16x4*)(row + base + 8 + 4 * hf);
+  return cat4(lo, hi);
+}
+
+// One chunk of the scan.  `regs` holds the chunk's operands on entry; they are moved to LDS and the
+// register set is refilled with the operands of the chunk two steps ahead (two sets alternate, so
+// every load has two chunk times to arrive).
+__device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkRegs& regs, int chunk, int h, int dvb, int tid, int z,
+                                          int w, int c, int hf, f32x16& s) {
+  const int lane = tid & 63;
+  const int tok0 = regs.tok0, len = regs.len, src = regs.src, dst = regs.dst;
+  const float glast = regs.glast;
+#pragma unroll
+  for (int i = 0; i < SCAN_PIECES; i++) *piece_dst(sm, i * G_THREADS + tid) = regs.v[i];
+  load_chunk(a, min(chunk + 2, a.n_chunks - 1), h, dvb, tid, z, regs);
+
+  if (src == -1) {
+    s = zero16();
+  } else if (src >= 0) {
+    const float* sp = a.slots + ((size_t)src * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[r] = sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
+    pin(s);       // the wait for these loads belongs inside this (rare) branch, not at the merge point
+  }
+  // S0 -> bf16, transposed into LDS
+#pragma unroll
+  for (int r4 = 0; r4 < 4; r4++)
+    *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
+  __syncthreads();
+
+  bf16x8 sfrag[GD / 16];              // B operand: column c of S0, k = key dims
+#pragma unroll
+  for (int ks = 0; ks < GD / 16; ks++) sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+
+  // Vn = U - W S0 (every wave computes all 64 rows: it needs them all as the k dimension below);
+  // the two row blocks are independent accumulation chains
+  f32x16 acc[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++) {
+      const bf16x4 u4 = *(const bf16x4*)&sm.ut[c][rb * 32 + r4 * 8 + hf * 4];
+#pragma unroll
+      for (int e = 0; e < 4; e++) acc[rb][4 * r4 + e] = (float)u4[e];
+    }
+#pragma unroll
+  for (int ks = 0; ks < GD / 16; ks++) {
+    acc[0] = mfma32(*(const bf16x8*)&sm.wn[c][ks * 16 + hf * 8], sfrag[ks], acc[0]);
+    acc[1] = mfma32(*(const bf16x8*)&sm.wn[32 + c][ks * 16 + hf * 8], sfrag[ks], acc[1]);
+  }
+  bf16x8 vfrag[2][2];                 // Vn as B operand, k = tokens, accumulator row order
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+      vfrag[rb][t] = cvt8(acc[rb][8 * t], acc[rb][8 * t + 1], acc[rb][8 * t + 2], acc[rb][8 * t + 3], acc[rb][8 * t + 4],
+                          acc[rb][8 * t + 5], acc[rb][8 * t + 6], acc[rb][8 * t + 7]);
+
+  // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state (the serial chain:
+  // done before the output, which nothing waits for)
+#pragma unroll
+  for (int r = 0; r < 16; r++) s[r] *= glast;
+#pragma unroll
+  for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) s = mfma32(lds_perm_k(&sm.kd[32 * w + c][0], jb * 32 + t * 16, hf), vfrag[jb][t], s);
+  if (dst >= 0) {
+    float* sp = a.slots + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
+  }
+
+  // O rows 32 w .. 32 w + 31 (waves 0 and 1)
+  if (w < 2) {
+    f32x16 oacc = zero16();
+#pragma unroll
+    for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(*(const bf16x8*)&sm.qg[w * 32 + c][ks * 16 + hf * 8], sfrag[ks], oacc);
+#pragma unroll
+    for (int jb = 0; jb < 2; jb++) {
+      if (jb > w) continue;           // P is lower triangular
+#pragma unroll
+      for (int t = 0; t < 2; t++) oacc = mfma32(lds_perm_k(&sm.p[w * 32 + c][0], jb * 32 + t * 16, hf), vfrag[jb][t], oacc);
+    }
+    // through LDS so that the tile leaves as two 16-byte stores per lane (a row of the tile is 64
+    // contiguous bytes of o); only this wave touches its tile, LDS operations of a wave are ordered
+#pragma unroll
+    for (int r = 0; r < 16; r++) sm.ot[w][(r >> 2) * 8 + hf * 4 + (r & 3)][c] = (__bf16)oacc[r];
+#pragma unroll
+    for (int half = 0; half < 2; half++) {
+      const int row = half * 16 + (lane >> 2), q8 = (lane & 3) * 8;
+      const u32x4n val = *(const u32x4n*)&sm.ot[w][row][q8];
+      const int i = w * 32 + row;
+      if (i < len) *(u32x4n*)(a.o + ((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + q8) = val;
+    }
+  }
+  __syncthreads();                    // every wave is done with this chunk's LDS image before it is overwritten
+}
+
+__global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
+  __shared__ __attribute__((aligned(16))) ScanSmem sm;
+
+  // (head, column block) from the workgroup id.  Consecutive ids go round-robin over the 8 XCDs;
+  // the four column blocks of a head read the same operands, so they are given ids 8 apart and
+  // share one XCD's L2.
+  const int id = blockIdx.x;
+  int h, dvb;
+  if (a.hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
+  else               { h = id >> 2; dvb = id & 3; }
+  const int tid = threadIdx.x & (G_THREADS - 1);      // the mask tells the compiler the range, so that
+  const int lane = tid & 63;                          // every piece's array is known at compile time
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 31, hf = lane >> 5;
   f32x16 s = zero16();                  // S[32 w + rows(r)][dvb*32 + c]
 
-  for (int chunk = 0; chunk < a.n_chunks; chunk++) {
-    const int tok0 = a.chunk_tok0[chunk], len = a.chunk_len[chunk];
-    const int src = a.chunk_src[chunk], dst = a.chunk_dst[chunk];
-    const size_t op = op_index(a, chunk, h);
-    if (src == -1) {
-      s = zero16();
-    } else if (src >= 0) {
-      const float* sp = a.slots + ((size_t)src * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
-#pragma unroll
-      for (int r = 0; r < 16; r++) s[r] = sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
-    }
-    // S0 -> bf16, transposed into LDS
-#pragma unroll
-    for (int r4 = 0; r4 < 4; r4++)
-      *(bf16x4*)&st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
-    __syncthreads();
-
-    bf16x8 sfrag[GD / 16];              // B operand: column c of S0, k = key dims
-#pragma unroll
-    for (int ks = 0; ks < GD / 16; ks++) sfrag[ks] = *(const bf16x8*)&st[c][ks * 16 + hf * 8];
-
-    // Vn = U - W S0 (every wave computes all 64 rows: it needs them all as the k dimension below)
-    const __bf16* wn = a.wn + op * (GC * GD);
-    const __bf16* ut = a.ut + op * (GD * GC) + (size_t)(dvb * G_DVB + c) * GC;
-    bf16x8 vfrag[2][2];                 // Vn as B operand, k = tokens, accumulator row order
-#pragma unroll
-    for (int rb = 0; rb < 2; rb++) {
-      f32x16 acc;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; r4++) {
-        const bf16x4 u4 = *(const bf16x4*)(ut + rb * 32 + r4 * 8 + hf * 4);
-#pragma unroll
-        for (int e = 0; e < 4; e++) acc[4 * r4 + e] = (float)u4[e];
-      }
-#pragma unroll
-      for (int ks = 0; ks < GD / 16; ks++)
-        acc = mfma32(*(const bf16x8*)(wn + (rb * 32 + c) * GD + ks * 16 + hf * 8), sfrag[ks], acc);
-#pragma unroll
-      for (int t = 0; t < 2; t++)
-        vfrag[rb][t] = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
-                            acc[8 * t + 6], acc[8 * t + 7]);
-    }
-
-    // O rows 32 w .. 32 w + 31 (waves 0 and 1)
-    if (w < 2) {
-      f32x16 oacc = zero16();
-      const __bf16* qg = a.qg + op * (GC * GD) + (size_t)(w * 32 + c) * GD;
-#pragma unroll
-      for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(*(const bf16x8*)(qg + ks * 16 + hf * 8), sfrag[ks], oacc);
-      const __bf16* pr = a.p + op * (GC * GC) + (size_t)(w * 32 + c) * GC;
-#pragma unroll
-      for (int jb = 0; jb < 2; jb++) {
-        if (jb > w) continue;           // P is lower triangular
-#pragma unroll
-        for (int t = 0; t < 2; t++) oacc = mfma32(load_perm_k(pr, jb * 32 + t * 16, hf), vfrag[jb][t], oacc);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int i = w * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-        if (i < len) a.o[((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + c] = (__bf16)oacc[r];
-      }
-    }
-
-    // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state
-    {
-      const float gl = a.glast[op];
-#pragma unroll
-      for (int r = 0; r < 16; r++) s[r] *= gl;
-      const __bf16* kd = a.kdt + op * (GD * GC) + (size_t)(32 * w + c) * GC;
-#pragma unroll
-      for (int jb = 0; jb < 2; jb++)
-#pragma unroll
-        for (int t = 0; t < 2; t++) s = mfma32(load_perm_k(kd, jb * 32 + t * 16, hf), vfrag[jb][t], s);
-    }
-    if (dst >= 0) {
-      float* sp = a.slots + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
-#pragma unroll
-      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
-    }
-    __syncthreads();                    // every wave is done with st before the next chunk rewrites it
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  ChunkRegs ra, rb;
+  load_chunk(a, 0, h, dvb, tid, z, ra);
+  load_chunk(a, min(1, a.n_chunks - 1), h, dvb, tid, z, rb);
+  for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
+    scan_step(a, sm, ra, chunk, h, dvb, tid, z, w, c, hf, s);
+    if (chunk + 1 < a.n_chunks) scan_step(a, sm, rb, chunk + 1, h, dvb, tid, z, w, c, hf, s);
   }
 }
 
@@ -308,7 +395,7 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {
     KernelTimer t(TT_KERNEL_GDN_SCAN, st);
-    gdn_scan_kernel<<<dim3(GD / G_DVB, hv), G_THREADS, 0, st>>>(a);
+    gdn_scan_kernel<<<dim3((GD / G_DVB) * hv), G_THREADS, 0, st>>>(a);
   }
   return hipGetLastError();
 }
