@@ -46,6 +46,7 @@ def parse_args():
     ap.add_argument("--no-partitioned", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-gdn", action="store_true")
+    ap.add_argument("--gdn-heads", type=int, default=32, help="value heads of the gated-delta-rule leg (key heads = half)")
     ap.add_argument("--conv-channels", type=int, default=8192,
                     help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
     ap.add_argument("--partition-gather-all", action="store_true",
@@ -362,7 +363,7 @@ def main():
     # ---------------- gated delta rule with tree state routing on the same tree (SSM-layer adaptation) ----------------
     gdn = None
     if not args.no_gdn and n_prefix == 0 and dims.dtype == "bf16":
-        ghk, ghv = 16, 32                                   # key / value heads of the GDN layer, 128 x 128 states
+        ghk, ghv = max(args.gdn_heads // 2, 1), args.gdn_heads   # key / value heads of the GDN layer, 128 x 128 states
         gen = torch.Generator(device=dev)
         gen.manual_seed(cfg * 1000 + 11)
         gq = torch.randn((N, ghk, 128), generator=gen, device=dev, dtype=torch.float32)

@@ -18,7 +18,7 @@ SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_timing.hip", "tt_att
 # arithmetic consumes them directly); the dK/dV kernel needs the accumulation VGPRs for its 128
 # accumulator registers per lane and is compiled with the default register form.
 VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]
-PER_FILE_FLAGS = {"tt_attn_fwd.hip": VGPR_FORM, "tt_attn_bwd.hip": VGPR_FORM}
+PER_FILE_FLAGS = {"tt_attn_fwd.hip": VGPR_FORM, "tt_attn_bwd.hip": VGPR_FORM, "tt_gdn.hip": VGPR_FORM}
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -354,7 +354,17 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
   ChunkRegs ra, rb;
   load_chunk(a, 0, h, dvb, tid, z, ra);
   load_chunk(a, min(1, a.n_chunks - 1), h, dvb, tid, z, rb);
-  for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
+  // Four steps per trip: the load queue is drained where the loop closes (the compiler cannot carry
+  // "which loads are still in flight" around the back edge), so the longer the straight-line stretch,
+  // the more of the time both register sets are in flight.
+  int chunk = 0;
+  for (; chunk + 4 <= a.n_chunks; chunk += 4) {
+    scan_step(a, sm, ra, chunk, h, dvb, tid, z, w, c, hf, s);
+    scan_step(a, sm, rb, chunk + 1, h, dvb, tid, z, w, c, hf, s);
+    scan_step(a, sm, ra, chunk + 2, h, dvb, tid, z, w, c, hf, s);
+    scan_step(a, sm, rb, chunk + 3, h, dvb, tid, z, w, c, hf, s);
+  }
+  for (; chunk < a.n_chunks; chunk += 2) {
     scan_step(a, sm, ra, chunk, h, dvb, tid, z, w, c, hf, s);
     if (chunk + 1 < a.n_chunks) scan_step(a, sm, rb, chunk + 1, h, dvb, tid, z, w, c, hf, s);
   }
