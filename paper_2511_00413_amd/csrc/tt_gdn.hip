@@ -265,9 +265,36 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
     *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
   __syncthreads();
 
+  // Every LDS read of the step is issued here, back to back, before the first MFMA: with one wave per
+  // SIMD nothing else hides an LDS round trip, and read-wait-multiply in turn costs one per product.
   bf16x8 sfrag[GD / 16];              // B operand: column c of S0, k = key dims
+  bf16x8 wfrag[2][GD / 16];           // A operands of W S0
+  bf16x4 ufrag[2][4];                 // U, the initial value of the Vn accumulators
+  bf16x8 kfrag[2][2];                 // A operands of the state update
+  bf16x8 qfrag[GD / 16];              // waves 0, 1: A operands of Q S0
+  bf16x8 pfrag[2][2];                 // waves 0, 1: A operands of P Vn
 #pragma unroll
-  for (int ks = 0; ks < GD / 16; ks++) sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+  for (int ks = 0; ks < GD / 16; ks++) {
+    sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+    wfrag[0][ks] = *(const bf16x8*)&sm.wn[c][ks * 16 + hf * 8];
+    wfrag[1][ks] = *(const bf16x8*)&sm.wn[32 + c][ks * 16 + hf * 8];
+  }
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++) {
+#pragma unroll
+    for (int r4 = 0; r4 < 4; r4++) ufrag[rb][r4] = *(const bf16x4*)&sm.ut[c][rb * 32 + r4 * 8 + hf * 4];
+#pragma unroll
+    for (int t = 0; t < 2; t++) kfrag[rb][t] = lds_perm_k(&sm.kd[32 * w + c][0], rb * 32 + t * 16, hf);
+  }
+  if (w < 2) {
+#pragma unroll
+    for (int ks = 0; ks < GD / 16; ks++) qfrag[ks] = *(const bf16x8*)&sm.qg[w * 32 + c][ks * 16 + hf * 8];
+#pragma unroll
+    for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+      for (int t = 0; t < 2; t++) pfrag[jb][t] = lds_perm_k(&sm.p[w * 32 + c][0], jb * 32 + t * 16, hf);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 
   // Vn = U - W S0 (every wave computes all 64 rows: it needs them all as the k dimension below);
   // the two row blocks are independent accumulation chains
@@ -275,15 +302,13 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
 #pragma unroll
   for (int rb = 0; rb < 2; rb++)
 #pragma unroll
-    for (int r4 = 0; r4 < 4; r4++) {
-      const bf16x4 u4 = *(const bf16x4*)&sm.ut[c][rb * 32 + r4 * 8 + hf * 4];
+    for (int r4 = 0; r4 < 4; r4++)
 #pragma unroll
-      for (int e = 0; e < 4; e++) acc[rb][4 * r4 + e] = (float)u4[e];
-    }
+      for (int e = 0; e < 4; e++) acc[rb][4 * r4 + e] = (float)ufrag[rb][r4][e];
 #pragma unroll
   for (int ks = 0; ks < GD / 16; ks++) {
-    acc[0] = mfma32(*(const bf16x8*)&sm.wn[c][ks * 16 + hf * 8], sfrag[ks], acc[0]);
-    acc[1] = mfma32(*(const bf16x8*)&sm.wn[32 + c][ks * 16 + hf * 8], sfrag[ks], acc[1]);
+    acc[0] = mfma32(wfrag[0][ks], sfrag[ks], acc[0]);
+    acc[1] = mfma32(wfrag[1][ks], sfrag[ks], acc[1]);
   }
   bf16x8 vfrag[2][2];                 // Vn as B operand, k = tokens, accumulator row order
 #pragma unroll
@@ -300,7 +325,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
 #pragma unroll
   for (int jb = 0; jb < 2; jb++)
 #pragma unroll
-    for (int t = 0; t < 2; t++) s = mfma32(lds_perm_k(&sm.kd[32 * w + c][0], jb * 32 + t * 16, hf), vfrag[jb][t], s);
+    for (int t = 0; t < 2; t++) s = mfma32(kfrag[jb][t], vfrag[jb][t], s);
   if (dst >= 0) {
     float* sp = a.slots + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
 #pragma unroll
@@ -311,12 +336,12 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
   if (w < 2) {
     f32x16 oacc = zero16();
 #pragma unroll
-    for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(*(const bf16x8*)&sm.qg[w * 32 + c][ks * 16 + hf * 8], sfrag[ks], oacc);
+    for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(qfrag[ks], sfrag[ks], oacc);
 #pragma unroll
     for (int jb = 0; jb < 2; jb++) {
       if (jb > w) continue;           // P is lower triangular
 #pragma unroll
-      for (int t = 0; t < 2; t++) oacc = mfma32(lds_perm_k(&sm.p[w * 32 + c][0], jb * 32 + t * 16, hf), vfrag[jb][t], oacc);
+      for (int t = 0; t < 2; t++) oacc = mfma32(pfrag[jb][t], vfrag[jb][t], oacc);
     }
     // through LDS so that the tile leaves as two 16-byte stores per lane (a row of the tile is 64
     // contiguous bytes of o); only this wave touches its tile, LDS operations of a wave are ordered
