@@ -144,12 +144,17 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   {
     const int c = tid;                  // 0..127: value column, 128..255: key column
     float x[GC];
+    // right-hand sides first: 64 independent loads per lane, all in flight together
 #pragma unroll
     for (int i = 0; i < GC; i++) {
-      float rhs = 0.f;
+      const int ic = min(i, len - 1);
+      const float raw = c < GD ? (float)a.v[((size_t)(tok0 + ic) * a.hv + h) * GD + c] : __expf(gam[i]) * (float)ksm[i][c - GD];
+      x[i] = i < len ? bet[i] * raw : 0.f;
+    }
+#pragma unroll
+    for (int i = 1; i < GC; i++) {
       if (i < len) {
-        if (c < GD) rhs = bet[i] * (float)a.v[((size_t)(tok0 + i) * a.hv + h) * GD + c];
-        else        rhs = bet[i] * __expf(gam[i]) * (float)ksm[i][c - GD];
+        float rhs = x[i];
 #pragma unroll
         for (int j4 = 0; j4 < (i + 3) / 4; j4++) {
           const float4 av = *(const float4*)&am[i][j4 * 4];      // entries at j >= i are zero
@@ -158,8 +163,8 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
           for (int e = 0; e < 4; e++)
             if (j4 * 4 + e < i) rhs -= ae[e] * x[j4 * 4 + e];
         }
+        x[i] = rhs;
       }
-      x[i] = rhs;
     }
     if (c < GD) {
       __bf16* dst = a.ut + op * (GD * GC) + c * GC;
