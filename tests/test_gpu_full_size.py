@@ -162,3 +162,89 @@ def test_more_than_4096_key_tiles():
     dv_sum = got["dv"].float().sum(dim=0).cpu().numpy()
     do_sum = do.float().view(n, 1, 2, dims.d).sum(dim=(0, 2)).numpy()
     assert rel_l2(dv_sum, do_sum) <= 2e-2
+
+
+# ---- the later entry points at config 2's full size, in the launch configurations bench.py times ----
+
+def test_cfg2_partitioned_quarter_capacity():
+    """bench.py's partitioned leg: config 2 cut at 5120 tokens; against the whole-tree call on the same
+    tensors and against the oracle on sampled rows / keys."""
+    t = W.tree_config(2)
+    d = W.DIMS[2]
+    meta = T.tree_build_meta(t.parent, t.seg_len, t.trained)
+    om = M.dfs_meta(t.parent, t.seg_len, t.trained)
+    n = meta.n_tokens
+    q, k, v, do = W.attn_inputs(n, n, d, 2)
+    plan = T.tree_partition_plan(t.parent, t.seg_len, 5120).to_device()
+    print(f"[case] cfg2 partitioned, capacity 5120: {plan.n_parts} partitions", flush=True)
+    qd, kd, vd, dod = (x.cuda() for x in (q, k, v, do))
+    o, lse = T.tree_attn_partitioned_fwd(qd, kd, vd, plan)
+    dq, dk, dv = T.tree_attn_partitioned_bwd(qd, kd, vd, plan, o, dod, lse)
+    torch.cuda.synchronize()
+    got = dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+    whole = _run_gpu(meta, q, k, v, do)
+    for key in TOL:
+        e = rel_l2(got[key].float().cpu().numpy(), whole[key].float().cpu().numpy())
+        assert e <= TOL[key], (key, e)
+    rng = np.random.default_rng(12)
+    rows = sorted(rng.choice(n, 24, replace=False).tolist())
+    keys = sorted(rng.choice(n, 6, replace=False).tolist())
+    _sample_check(om, got, q.float(), k.float(), v.float(), do.float(), 3, rows, keys, d.hq // d.hkv)
+
+
+def test_cfg2_tree_conv_sampled_channels():
+    """bench.py's tree_conv leg: N = 16406, C = 8192, K = 4, bf16.  The convolution is depthwise, so the
+    oracle is run on 48 sampled channels (all tokens); dweight / dbias of those channels as well."""
+    from oracle import ssm as S
+    t = W.tree_config(2)
+    meta = T.tree_build_meta(t.parent, t.seg_len, t.trained)
+    n, C, K = meta.n_tokens, 8192, 4
+    g = torch.Generator().manual_seed(21)
+    x = torch.randn((n, C), generator=g).to(torch.bfloat16)
+    dy = torch.randn((n, C), generator=g).to(torch.bfloat16)
+    w = torch.randn((C, K), generator=g) * 0.5
+    b = torch.randn(C, generator=g) * 0.1
+    pred = torch.from_numpy(meta.tok_pred).cuda()
+    plan = T.tree_conv_plan(meta.tok_pred, K)
+    print(f"[case] cfg2 tree conv full size: {len(plan.fix_tok)} fix-up tokens", flush=True)
+    y = T.tree_conv_fwd(x.cuda(), w.cuda(), b.cuda(), pred)
+    dx, dw, db = T.tree_conv_bwd(x.cuda(), w.cuda(), b.cuda(), pred, dy.cuda(), plan)
+    torch.cuda.synchronize()
+    ch = np.sort(np.random.default_rng(4).choice(C, 48, replace=False))
+    cht = torch.from_numpy(ch)
+    want_y, _ = S.tree_conv(x[:, cht], w[cht], b[cht], meta.tok_pred)
+    want_dx, want_dw, want_db = S.tree_conv_bwd(x[:, cht], w[cht], b[cht], meta.tok_pred, dy[:, cht])
+    assert rel_l2(y[:, cht.cuda()].float().cpu().numpy(), want_y) <= 4e-3
+    assert rel_l2(dx[:, cht.cuda()].float().cpu().numpy(), want_dx) <= 4e-3
+    assert rel_l2(dw[cht.cuda()].cpu().numpy(), want_dw) <= 1e-4          # fp32 sums over 16 406 tokens
+    assert rel_l2(db[cht.cuda()].cpu().numpy(), want_db) <= 1e-4
+    rows = np.unique(np.concatenate([plan.fix_tok, plan.fix_t]))
+    a, bq = dx[:, cht.cuda()].float().cpu().numpy()[rows], want_dx[rows]
+    assert np.abs(a - bq).max() <= 3e-2 * max(1.0, np.abs(bq).max())
+
+
+def test_cfg2_gdn_sampled_heads():
+    """bench.py's tree_gdn leg: N = 16406, 16 key / 32 value heads; the token recurrence is run for two
+    sampled value heads."""
+    from oracle import ssm as S
+    t = W.tree_config(2)
+    meta = T.tree_build_meta(t.parent, t.seg_len, t.trained)
+    n, hk, hv = meta.n_tokens, 16, 32
+    g_ = torch.Generator().manual_seed(22)
+    q = torch.randn((n, hk, 128), generator=g_); k = torch.randn((n, hk, 128), generator=g_)
+    q = (q / q.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    k = (k / k.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    v = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16)
+    gl = -(torch.rand((n, hv), generator=g_) * 0.2 + 0.005)
+    beta = torch.rand((n, hv), generator=g_) * 0.8 + 0.1
+    plan = T.tree_gdn_plan(t.parent, t.seg_len)
+    print(f"[case] cfg2 gdn full size: {plan.n_chunks} chunks, {plan.n_slots} saved states", flush=True)
+    o = T.tree_gdn_fwd(q.cuda(), k.cuda(), v.cuda(), gl.cuda(), beta.cuda(), plan)
+    torch.cuda.synchronize()
+    o = o.float().cpu().numpy()
+    for h in (7, 30):
+        want = S.gdn_tree(q[:, h // 2:h // 2 + 1], k[:, h // 2:h // 2 + 1], v[:, h:h + 1], gl[:, h:h + 1], beta[:, h:h + 1],
+                          meta.tok_pred)
+        e = rel_l2(o[:, h], want[:, 0])
+        print(f"   head {h}: rel-L2 {e:.2e}", flush=True)
+        assert e <= 2e-2, (h, e)
