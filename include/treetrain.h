@@ -449,11 +449,19 @@ tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_si
  *                            -1 = zero state, >= 0 = saved state slot
  *     chunk_dst [n_chunks]   -1, or the slot the chunk's leaving state is saved to (nodes that
  *                            have two or more token-bearing child branches)
+ *     chunk_cap [n_chunks]   -1, or i when the chunk's leaving state is the end state of
+ *                            capture_node[i]: the state a child partition starts from (Appendix
+ *                            "SSM State Gateway": state extraction / injection).  A zero-length
+ *                            capture node stands for its nearest token-bearing ancestor; two
+ *                            capture nodes may not share a chunk.
  *   Zero-length nodes have no chunk; their children continue from the nearest token-bearing
  *   ancestor.
  * tt_tree_gdn_fwd (device): q, k [n_tokens][hk][128], v, o [n_tokens][hv][128] bf16 contiguous;
- *   g, beta [n_tokens][hv] fp32 (g <= 0: log of the decay); the four chunk arrays are device
- *   copies of the plan.  dk = dv = 128, hv a multiple of hk.  q and k are used as given
+ *   g, beta [n_tokens][hv] fp32 (g <= 0: log of the decay); the chunk arrays are device
+ *   copies of the plan (chunk_cap may be NULL = nothing captured).  initial_state [hv][128][128]
+ *   fp32 or NULL (= 0): the state every root starts from (a partition's gateway state);
+ *   state_out [n_capture][hv][128][128] fp32: end states of the capture nodes (NULL iff
+ *   chunk_cap is NULL).  dk = dv = 128, hv a multiple of hk.  q and k are used as given
  *   (normalise them beforehand if the layer does).
  * Errors: TT_ERR_NULL, TT_ERR_SHAPE, TT_ERR_TREE, TT_ERR_ALIGN, TT_ERR_UNSUPPORTED (dims other
  *   than 128), TT_ERR_WORKSPACE.
@@ -462,12 +470,15 @@ tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_si
 tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
                                  int32_t* n_chunks, int32_t* n_slots);
 tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
-                           int32_t* chunk_tok0, int32_t* chunk_len, int32_t* chunk_src, int32_t* chunk_dst);
+                           int32_t n_capture, const int32_t* capture_node,
+                           int32_t* chunk_tok0, int32_t* chunk_len, int32_t* chunk_src, int32_t* chunk_dst,
+                           int32_t* chunk_cap);
 size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32_t hv);
 tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
                           const void* q, const void* k, const void* v, const float* g, const float* beta,
                           int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
                           const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                          const int32_t* chunk_cap, const float* initial_state, float* state_out,
                           void* o, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------

@@ -104,13 +104,13 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_gdn_plan_sizes.restype = ctypes.c_int32
         lib.tt_tree_gdn_plan_sizes.argtypes = [ctypes.c_int32, _vp, _vp, _c_i32p, _c_i32p]
         lib.tt_tree_gdn_plan.restype = ctypes.c_int32
-        lib.tt_tree_gdn_plan.argtypes = [ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _vp]
+        lib.tt_tree_gdn_plan.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp, _vp]
         lib.tt_tree_gdn_workspace.restype = ctypes.c_size_t
         lib.tt_tree_gdn_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.tt_tree_gdn_fwd.restype = ctypes.c_int32
         lib.tt_tree_gdn_fwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
-                                        _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp,
-                                        ctypes.c_size_t, _vp]
+                                        _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp,
+                                        _vp, _vp, ctypes.c_size_t, _vp]
         lib.tt_tree_path_weights.restype = ctypes.c_int32
         lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
@@ -263,23 +263,27 @@ class GdnPlan:
     chunk_len: np.ndarray
     chunk_src: np.ndarray
     chunk_dst: np.ndarray
+    chunk_cap: np.ndarray
+    n_capture: int = 0
     device: Optional[dict] = None
 
     def to_device(self, device="cuda"):
         torch = _torch()
-        self.device = {n: torch.from_numpy(getattr(self, n)).to(device) for n in ("chunk_tok0", "chunk_len", "chunk_src", "chunk_dst")}
+        self.device = {n: torch.from_numpy(getattr(self, n)).to(device)
+                       for n in ("chunk_tok0", "chunk_len", "chunk_src", "chunk_dst", "chunk_cap")}
         return self
 
 
-def tree_gdn_plan(parent, seg_len) -> GdnPlan:
+def tree_gdn_plan(parent, seg_len, capture_nodes=()) -> GdnPlan:
     parent, seg_len = _np(parent, np.int32), _np(seg_len, np.int32)
     if len(parent) != len(seg_len):
         raise ValueError("parent and seg_len differ in length")
     nc, ns = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(_lib().tt_tree_gdn_plan_sizes(len(parent), _hp(parent), _hp(seg_len), ctypes.byref(nc), ctypes.byref(ns)))
-    arrs = [np.zeros(nc.value, np.int32) for _ in range(4)]
-    _check(_lib().tt_tree_gdn_plan(len(parent), _hp(parent), _hp(seg_len), *(_hp(a) for a in arrs)))
-    return GdnPlan(nc.value, ns.value, *arrs)
+    arrs = [np.zeros(nc.value, np.int32) for _ in range(5)]
+    cap = _np(list(capture_nodes), np.int32)
+    _check(_lib().tt_tree_gdn_plan(len(parent), _hp(parent), _hp(seg_len), len(cap), _hp(cap), *(_hp(a) for a in arrs)))
+    return GdnPlan(nc.value, ns.value, *arrs, n_capture=len(cap))
 
 
 def tree_conv_plan(tok_pred, kernel_size: int) -> ConvPlan:
@@ -651,9 +655,12 @@ def tree_conv_bwd(x, weight, bias, tok_pred, dy, plan: ConvPlan, *, silu: bool =
     return dx, dw, db
 
 
-def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, workspace=None, stream=None):
+def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, workspace=None, stream=None,
+                 initial_state=None, return_states: bool = False):
     """Gated delta rule with tree state routing: q, k [n, hk, 128], v [n, hv, 128] bf16 contiguous; g, beta
-    [n, hv] fp32 (g = log decay <= 0).  Returns o [n, hv, 128] bf16."""
+    [n, hv] fp32 (g = log decay <= 0).  Returns o [n, hv, 128] bf16; with return_states also the end states
+    [n_capture, hv, 128, 128] fp32 of the plan's capture nodes.  initial_state [hv, 128, 128] fp32: the state
+    every root starts from."""
     torch = _torch()
     for t in (q, k, v):
         if t.dim() != 3 or t.dtype != torch.bfloat16 or not t.is_contiguous():
@@ -673,7 +680,15 @@ def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, works
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     d = plan.device
+    states = None
+    if return_states:
+        states = torch.empty((plan.n_capture, hv, dk, dv), dtype=torch.float32, device=q.device)
+    if initial_state is not None and (initial_state.shape != (hv, dk, dv) or initial_state.dtype != torch.float32
+                                      or not initial_state.is_contiguous()):
+        raise ValueError("initial_state must be a contiguous fp32 [hv, dk, dv] tensor")
     _check(_lib().tt_tree_gdn_fwd(n, hk, hv, dk, dv, float(dk) ** -0.5 if scale is None else float(scale), _dp(q), _dp(k), _dp(v),
                                   _dp(g), _dp(beta), plan.n_chunks, _dp(d["chunk_tok0"]), _dp(d["chunk_len"]), _dp(d["chunk_src"]),
-                                  _dp(d["chunk_dst"]), plan.n_slots, _dp(out), _dp(workspace), workspace.numel(), _stream_ptr(stream)))
-    return out
+                                  _dp(d["chunk_dst"]), plan.n_slots, _dp(d["chunk_cap"]) if return_states and plan.n_capture else None,
+                                  _dp(initial_state), _dp(states) if plan.n_capture else None, _dp(out), _dp(workspace), workspace.numel(),
+                                  _stream_ptr(stream)))
+    return (out, states) if return_states else out

@@ -289,7 +289,8 @@ extern "C" size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32
 extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
                                      const void* q, const void* k, const void* v, const float* g, const float* beta,
                                      int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
-                                     const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots, void* o,
+                                     const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                                     const int32_t* chunk_cap, const float* initial_state, float* state_out, void* o,
                                      void* workspace, size_t workspace_bytes, void* stream) {
   tt::clear_error();
   if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
@@ -300,13 +301,14 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
   if ((n_tokens > 0) != (n_chunks > 0)) return fail(TT_ERR_SHAPE, "n_tokens=%lld with %d chunks", (long long)n_tokens, n_chunks);
   if (n_chunks > 0 && (!q || !k || !v || !g || !beta || !o || !chunk_tok0 || !chunk_len || !chunk_src || !chunk_dst))
     return fail(TT_ERR_NULL, "a tensor or plan pointer is NULL");
-  const void* ptrs[] = {q, k, v, o};
+  if ((chunk_cap != nullptr) != (state_out != nullptr)) return fail(TT_ERR_NULL, "chunk_cap and state_out must be given together");
+  const void* ptrs[] = {q, k, v, o, initial_state, state_out};
   for (const void* p : ptrs)
     if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
   const size_t need = tt::gdn_workspace(n_chunks, n_slots, hv);
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
     return fail(TT_ERR_WORKSPACE, "gdn forward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
   return hip_result(tt::gdn_fwd(n_tokens, hk, hv, scale, q, k, v, g, beta, n_chunks, chunk_tok0, chunk_len, chunk_src, chunk_dst,
-                                n_slots, o, workspace, (hipStream_t)stream),
+                                n_slots, chunk_cap, initial_state, state_out, o, workspace, (hipStream_t)stream),
                     "tree_gdn_fwd");
 }

@@ -39,6 +39,9 @@ struct GdnArgs {
   const __bf16 *q, *k, *v;           // [N][hk][128], [N][hk][128], [N][hv][128]
   const float *g, *beta;             // [N][hv]
   const int32_t *chunk_tok0, *chunk_len, *chunk_src, *chunk_dst;
+  const int32_t* chunk_cap;          // nullptr, or per chunk: -1 / index into state_out
+  const float* initial_state;        // nullptr (zero) or [hv][128][128]: the state roots start from
+  float* state_out;                  // [n_capture][hv][128][128]
   __bf16* o;                         // [N][hv][128]
   // per (chunk, value head) operands
   __bf16* wn;                        // [64][128]  -W
@@ -206,7 +209,7 @@ typedef unsigned u32x4n __attribute__((ext_vector_type(4)));      // native vect
 // One chunk's operands as 16-byte pieces, 15 per lane, every wave-level load contiguous in memory.
 struct ChunkRegs {
   u32x4n v[SCAN_PIECES];
-  int tok0, len, src, dst;
+  int tok0, len, src, dst, cap;
   float glast;
 };
 
@@ -232,6 +235,7 @@ __device__ __forceinline__ u32x4n* piece_dst(ScanSmem& sm, int piece) {
 // for a full memory latency).
 __device__ __forceinline__ void load_chunk(const GdnArgs& a, int chunk, int h, int dvb, int tid, int z, ChunkRegs& r) {
   r.tok0 = a.chunk_tok0[chunk + z]; r.len = a.chunk_len[chunk + z]; r.src = a.chunk_src[chunk + z]; r.dst = a.chunk_dst[chunk + z];
+  r.cap = a.chunk_cap ? a.chunk_cap[chunk + z] : -1;
   const size_t op = op_index(a, chunk, h);
   r.glast = a.glast[op + z];
 #pragma unroll
@@ -250,16 +254,18 @@ __device__ __forceinline__ bf16x8 lds_perm_k(const __bf16* row, int base, int hf
 __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkRegs& regs, int chunk, int h, int dvb, int tid, int z,
                                           int w, int c, int hf, f32x16& s) {
   const int lane = tid & 63;
-  const int tok0 = regs.tok0, len = regs.len, src = regs.src, dst = regs.dst;
+  const int tok0 = regs.tok0, len = regs.len, src = regs.src, dst = regs.dst, cap = regs.cap;
   const float glast = regs.glast;
 #pragma unroll
   for (int i = 0; i < SCAN_PIECES; i++) *piece_dst(sm, i * G_THREADS + tid) = regs.v[i];
   load_chunk(a, min(chunk + 2, a.n_chunks - 1), h, dvb, tid, z, regs);
 
-  if (src == -1) {
+  if (src == -1 && !a.initial_state) {
     s = zero16();
-  } else if (src >= 0) {
-    const float* sp = a.slots + ((size_t)src * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+  } else if (src != -2) {
+    // a saved node-end state, or the state handed in for the roots
+    const float* sp = (src >= 0 ? a.slots + ((size_t)src * a.hv + h) * (GD * GD) : a.initial_state + (size_t)h * (GD * GD)) +
+                      dvb * G_DVB + c;
 #pragma unroll
     for (int r = 0; r < 16; r++) s[r] = sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
     pin(s);       // the wait for these loads belongs inside this (rare) branch, not at the merge point
@@ -333,6 +339,11 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
     for (int t = 0; t < 2; t++) s = mfma32(kfrag[jb][t], vfrag[jb][t], s);
   if (dst >= 0) {
     float* sp = a.slots + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
+  }
+  if (cap >= 0) {
+    float* sp = a.state_out + ((size_t)cap * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
 #pragma unroll
     for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
   }
@@ -412,12 +423,14 @@ size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
 
 hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
                    const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
-                   const int32_t* chunk_dst, int n_slots, void* o, void* workspace, hipStream_t st) {
+                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const float* initial_state, float* state_out,
+                   void* o, void* workspace, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   GdnArgs a{};
   a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v; a.g = g; a.beta = beta;
   a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len; a.chunk_src = chunk_src; a.chunk_dst = chunk_dst;
+  a.chunk_cap = chunk_cap; a.initial_state = initial_state; a.state_out = state_out;
   a.o = (__bf16*)o;
   const size_t per = (size_t)n_chunks * hv;
   char* p = (char*)workspace;

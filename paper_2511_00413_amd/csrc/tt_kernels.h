@@ -79,7 +79,8 @@ size_t conv_bwd_workspace(int64_t n_tokens, int channels, int kernel_size, bool 
 // gated delta rule with tree state routing, forward (tt_gdn.hip); dk = dv = 128, bf16
 hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
                    const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
-                   const int32_t* chunk_dst, int n_slots, void* o, void* workspace, hipStream_t st);
+                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const float* initial_state, float* state_out,
+                   void* o, void* workspace, hipStream_t st);
 size_t gdn_workspace(int n_chunks, int n_slots, int hv);
 
 }  // namespace tt

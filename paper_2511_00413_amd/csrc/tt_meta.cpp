@@ -299,12 +299,14 @@ extern "C" tt_status tt_tree_conv_plan(int64_t n_tokens, const int32_t* tok_pred
 namespace {
 
 struct GdnPlan {
-  std::vector<int32_t> tok0, len, src, dst;
+  std::vector<int32_t> tok0, len, src, dst, cap;
   int32_t n_slots = 0;
 };
 
 // Chunk program of the gated-delta-rule scan: nodes in DFS order, TT_GDN_CHUNK tokens per chunk.
-tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, GdnPlan& pl) {
+tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t n_capture,
+                   const int32_t* capture_node, GdnPlan& pl) {
+  if (n_capture < 0 || (n_capture > 0 && !capture_node)) return tt::fail(TT_ERR_NULL, "n_capture=%d with capture_node NULL", n_capture);
   Forest f;
   if (tt_status s = build_forest(n_nodes, parent, seg_len, 0, f)) return s;
   // nearest token-bearing ancestor (input numbering), -1 if none
@@ -341,6 +343,16 @@ tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_le
     }
     tok += seg_len[i];
   }
+  pl.cap.assign(pl.tok0.size(), -1);
+  for (int32_t k = 0; k < n_capture; k++) {
+    int32_t node = capture_node[k];
+    if (node < 0 || node >= n_nodes) return tt::fail(TT_ERR_SHAPE, "capture_node[%d]=%d is not a node", k, node);
+    if (seg_len[node] == 0) node = eff[node];
+    if (node < 0) return tt::fail(TT_ERR_SHAPE, "capture_node[%d] has no token on or above it: its state is the initial state", k);
+    int32_t& slot_of_chunk = pl.cap[last_chunk[node]];
+    if (slot_of_chunk >= 0) return tt::fail(TT_ERR_SHAPE, "capture nodes %d and %d end in the same chunk", slot_of_chunk, k);
+    slot_of_chunk = k;
+  }
   return TT_OK;
 }
 
@@ -351,20 +363,23 @@ extern "C" tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* pare
   tt::clear_error();
   if (!n_chunks || !n_slots) return tt::fail(TT_ERR_NULL, "n_chunks / n_slots is NULL");
   GdnPlan pl;
-  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, pl)) return s;
+  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, 0, nullptr, pl)) return s;
   *n_chunks = (int32_t)pl.tok0.size();
   *n_slots = pl.n_slots;
   return TT_OK;
 }
 
-extern "C" tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t* chunk_tok0,
-                                      int32_t* chunk_len, int32_t* chunk_src, int32_t* chunk_dst) {
+extern "C" tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t n_capture,
+                                      const int32_t* capture_node, int32_t* chunk_tok0, int32_t* chunk_len, int32_t* chunk_src,
+                                      int32_t* chunk_dst, int32_t* chunk_cap) {
   tt::clear_error();
   GdnPlan pl;
-  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, pl)) return s;
+  if (tt_status s = gdn_plan(n_nodes, parent, seg_len, n_capture, capture_node, pl)) return s;
+  if (n_capture > 0 && !chunk_cap) return tt::fail(TT_ERR_NULL, "chunk_cap is NULL");
   if (!pl.tok0.empty() && (!chunk_tok0 || !chunk_len || !chunk_src || !chunk_dst)) return tt::fail(TT_ERR_NULL, "an output array is NULL");
   for (size_t c = 0; c < pl.tok0.size(); c++) {
     chunk_tok0[c] = pl.tok0[c]; chunk_len[c] = pl.len[c]; chunk_src[c] = pl.src[c]; chunk_dst[c] = pl.dst[c];
+    if (chunk_cap) chunk_cap[c] = pl.cap[c];
   }
   return TT_OK;
 }

@@ -54,3 +54,23 @@ def test_shapes():
         t = W.tree_config(cfg)
         _simulate(list(t.parent), list(t.seg_len))
     assert T.tree_gdn_plan([], []).n_chunks == 0
+
+
+def test_capture_nodes():
+    """chunk_cap marks the chunk that ends with a capture node's last token (a zero-length node stands for its
+    nearest token-bearing ancestor)."""
+    parent, seg = [-1, 0, 0, 1, 1, 4], [70, 30, 40, 0, 64, 5]
+    m = M.dfs_meta(parent, seg)
+    rank = {int(i): rk for rk, i in enumerate(m["dfs_order"])}
+    plan = T.tree_gdn_plan(parent, seg, capture_nodes=[4, 0, 3])        # node 3 is empty -> its parent, node 1
+    assert plan.n_capture == 3
+    ends = {k: int(plan.chunk_tok0[c] + plan.chunk_len[c] - 1) for c, k in enumerate(plan.chunk_cap) if k >= 0}
+    assert ends == {0: m["node_end"][rank[4]] - 1, 1: m["node_end"][rank[0]] - 1, 2: m["node_end"][rank[1]] - 1}
+    assert (plan.chunk_cap >= 0).sum() == 3
+    with pytest.raises(T.TreeTrainError) as e:
+        T.tree_gdn_plan(parent, seg, capture_nodes=[1, 3])                # both end in node 1's last chunk
+    assert e.value.status == -2
+    with pytest.raises(T.TreeTrainError) as e:
+        T.tree_gdn_plan([-1, 0], [0, 5], capture_nodes=[0])               # nothing on or above it
+    assert e.value.status == -2
+    assert np.all(T.tree_gdn_plan(parent, seg).chunk_cap == -1)
