@@ -147,13 +147,19 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   {
     const int c = tid;                  // 0..127: value column, 128..255: key column
     float x[GC];
-    // right-hand sides first: 64 independent loads per lane, all in flight together
+    // right-hand sides first.  The value columns come from memory: 64 independent loads per lane in one
+    // straight-line block, so that they are all in flight together (inside a per-row branch each one
+    // was waited for in turn).
+    if (c < GD) {
+      const __bf16* vcol = a.v + ((size_t)tok0 * a.hv + h) * GD + c;
 #pragma unroll
-    for (int i = 0; i < GC; i++) {
-      const int ic = min(i, len - 1);
-      const float raw = c < GD ? (float)a.v[((size_t)(tok0 + ic) * a.hv + h) * GD + c] : __expf(gam[i]) * (float)ksm[i][c - GD];
-      x[i] = i < len ? bet[i] * raw : 0.f;
+      for (int i = 0; i < GC; i++) x[i] = (float)vcol[(size_t)min(i, len - 1) * a.hv * GD];
+    } else {
+#pragma unroll
+      for (int i = 0; i < GC; i++) x[i] = __expf(gam[i]) * (float)ksm[i][c - GD];
     }
+#pragma unroll
+    for (int i = 0; i < GC; i++) x[i] = i < len ? bet[i] * x[i] : 0.f;
 #pragma unroll
     for (int i = 1; i < GC; i++) {
       if (i < len) {
