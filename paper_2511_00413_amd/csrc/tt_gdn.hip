@@ -205,7 +205,8 @@ struct ScanSmem {
   __bf16 ut[G_DVB][GROW64];     // U^T, this workgroup's value columns
   __bf16 p[GC][GROW64];         // scale tril(Q K^T decay)
   __bf16 st[G_DVB][GROW];       // S0^T
-  __bf16 ot[2][32][G_DVB + 8];  // output tiles of waves 0 and 1 on their way to 16-byte stores
+  __bf16 ot[2][32][G_DVB + 8];  // output tiles of waves 2 and 3 on their way to 16-byte stores
+  bf16x8 vx[2][2][64];          // Vn as per-lane B-operand fragments, written by waves 0 and 1, read by all
 };
 constexpr int SCAN_PIECES = (GC * GD * 3 + G_DVB * GC + GC * GC) / 8 / G_THREADS;   // 16-byte pieces per lane: 15
 static_assert(SCAN_PIECES * G_THREADS * 8 == GC * GD * 3 + G_DVB * GC + GC * GC, "operands must split evenly over the lanes");
@@ -282,61 +283,59 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
     *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
   __syncthreads();
 
-  // Every LDS read of the step is issued here, back to back, before the first MFMA: with one wave per
-  // SIMD nothing else hides an LDS round trip, and read-wait-multiply in turn costs one per product.
+  // Waves 0 and 1 compute one 32-row block of Vn = U - W S0 each; waves 2 and 3 meanwhile compute their
+  // 32 rows of Q S0, the part of the output that does not need Vn.  Vn then goes through LDS as per-lane
+  // B-operand fragments (k = tokens, in the order the accumulator registers enumerate rows), and every
+  // wave updates its 32 rows of the state.  All LDS reads of a phase are issued before its first MFMA:
+  // with one wave per SIMD nothing else hides an LDS round trip.
   bf16x8 sfrag[GD / 16];              // B operand: column c of S0, k = key dims
-  bf16x8 wfrag[2][GD / 16];           // A operands of W S0
-  bf16x4 ufrag[2][4];                 // U, the initial value of the Vn accumulators
+  bf16x8 afrag[GD / 16];              // A operands: rows of -W (waves 0, 1) or of Q exp(gamma) (waves 2, 3)
   bf16x8 kfrag[2][2];                 // A operands of the state update
-  bf16x8 qfrag[GD / 16];              // waves 0, 1: A operands of Q S0
-  bf16x8 pfrag[2][2];                 // waves 0, 1: A operands of P Vn
+  bf16x8 pfrag[2][2];                 // waves 2, 3: A operands of P Vn
+  const int half = w & 1;             // which 32-row block this wave works on
+  {
+    const __bf16* arow = w < 2 ? &sm.wn[half * 32 + c][0] : &sm.qg[half * 32 + c][0];
 #pragma unroll
-  for (int ks = 0; ks < GD / 16; ks++) {
-    sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
-    wfrag[0][ks] = *(const bf16x8*)&sm.wn[c][ks * 16 + hf * 8];
-    wfrag[1][ks] = *(const bf16x8*)&sm.wn[32 + c][ks * 16 + hf * 8];
+    for (int ks = 0; ks < GD / 16; ks++) {
+      sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+      afrag[ks] = *(const bf16x8*)(arow + ks * 16 + hf * 8);
+    }
   }
-#pragma unroll
-  for (int rb = 0; rb < 2; rb++) {
-#pragma unroll
-    for (int r4 = 0; r4 < 4; r4++) ufrag[rb][r4] = *(const bf16x4*)&sm.ut[c][rb * 32 + r4 * 8 + hf * 4];
-#pragma unroll
-    for (int t = 0; t < 2; t++) kfrag[rb][t] = lds_perm_k(&sm.kd[32 * w + c][0], rb * 32 + t * 16, hf);
-  }
+  f32x16 acc;
   if (w < 2) {
 #pragma unroll
-    for (int ks = 0; ks < GD / 16; ks++) qfrag[ks] = *(const bf16x8*)&sm.qg[w * 32 + c][ks * 16 + hf * 8];
+    for (int r4 = 0; r4 < 4; r4++) {
+      const bf16x4 u4 = *(const bf16x4*)&sm.ut[c][half * 32 + r4 * 8 + hf * 4];
 #pragma unroll
-    for (int jb = 0; jb < 2; jb++)
-#pragma unroll
-      for (int t = 0; t < 2; t++) pfrag[jb][t] = lds_perm_k(&sm.p[w * 32 + c][0], jb * 32 + t * 16, hf);
+      for (int e = 0; e < 4; e++) acc[4 * r4 + e] = (float)u4[e];
+    }
+  } else {
+    acc = zero16();
   }
+#pragma unroll
+  for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      kfrag[jb][t] = lds_perm_k(&sm.kd[32 * w + c][0], jb * 32 + t * 16, hf);
+      pfrag[jb][t] = lds_perm_k(&sm.p[half * 32 + c][0], jb * 32 + t * 16, hf);     // used by waves 2, 3 only
+    }
   __builtin_amdgcn_sched_barrier(0);
-
-  // Vn = U - W S0 (every wave computes all 64 rows: it needs them all as the k dimension below);
-  // the two row blocks are independent accumulation chains
-  f32x16 acc[2];
 #pragma unroll
-  for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-    for (int r4 = 0; r4 < 4; r4++)
-#pragma unroll
-      for (int e = 0; e < 4; e++) acc[rb][4 * r4 + e] = (float)ufrag[rb][r4][e];
-#pragma unroll
-  for (int ks = 0; ks < GD / 16; ks++) {
-    acc[0] = mfma32(wfrag[0][ks], sfrag[ks], acc[0]);
-    acc[1] = mfma32(wfrag[1][ks], sfrag[ks], acc[1]);
-  }
-  bf16x8 vfrag[2][2];                 // Vn as B operand, k = tokens, accumulator row order
-#pragma unroll
-  for (int rb = 0; rb < 2; rb++)
+  for (int ks = 0; ks < GD / 16; ks++) acc = mfma32(afrag[ks], sfrag[ks], acc);
+  if (w < 2) {
 #pragma unroll
     for (int t = 0; t < 2; t++)
-      vfrag[rb][t] = cvt8(acc[rb][8 * t], acc[rb][8 * t + 1], acc[rb][8 * t + 2], acc[rb][8 * t + 3], acc[rb][8 * t + 4],
-                          acc[rb][8 * t + 5], acc[rb][8 * t + 6], acc[rb][8 * t + 7]);
+      sm.vx[half][t][lane] = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
+                                  acc[8 * t + 6], acc[8 * t + 7]);
+  }
+  __syncthreads();
+  bf16x8 vfrag[2][2];
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[rb][t][lane];
 
-  // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state (the serial chain:
-  // done before the output, which nothing waits for)
+  // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state
 #pragma unroll
   for (int r = 0; r < 16; r++) s[r] *= glast;
 #pragma unroll
@@ -354,26 +353,23 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
     for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
   }
 
-  // O rows 32 w .. 32 w + 31 (waves 0 and 1)
-  if (w < 2) {
-    f32x16 oacc = zero16();
-#pragma unroll
-    for (int ks = 0; ks < GD / 16; ks++) oacc = mfma32(qfrag[ks], sfrag[ks], oacc);
+  // O rows 32 half .. 32 half + 31 (waves 2 and 3): add P Vn to the Q S0 they already hold
+  if (w >= 2) {
 #pragma unroll
     for (int jb = 0; jb < 2; jb++) {
-      if (jb > w) continue;           // P is lower triangular
+      if (jb > half) continue;          // P is lower triangular
 #pragma unroll
-      for (int t = 0; t < 2; t++) oacc = mfma32(pfrag[jb][t], vfrag[jb][t], oacc);
+      for (int t = 0; t < 2; t++) acc = mfma32(pfrag[jb][t], vfrag[jb][t], acc);
     }
     // through LDS so that the tile leaves as two 16-byte stores per lane (a row of the tile is 64
     // contiguous bytes of o); only this wave touches its tile, LDS operations of a wave are ordered
 #pragma unroll
-    for (int r = 0; r < 16; r++) sm.ot[w][(r >> 2) * 8 + hf * 4 + (r & 3)][c] = (__bf16)oacc[r];
+    for (int r = 0; r < 16; r++) sm.ot[half][(r >> 2) * 8 + hf * 4 + (r & 3)][c] = (__bf16)acc[r];
 #pragma unroll
-    for (int half = 0; half < 2; half++) {
-      const int row = half * 16 + (lane >> 2), q8 = (lane & 3) * 8;
-      const u32x4n val = *(const u32x4n*)&sm.ot[w][row][q8];
-      const int i = w * 32 + row;
+    for (int part = 0; part < 2; part++) {
+      const int row = part * 16 + (lane >> 2), q8 = (lane & 3) * 8;
+      const u32x4n val = *(const u32x4n*)&sm.ot[half][row][q8];
+      const int i = half * 32 + row;
       if (i < len) *(u32x4n*)(a.o + ((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + q8) = val;
     }
   }
