@@ -44,16 +44,18 @@ struct GdnArgs {
   float* state_out;                  // [n_capture][hv][128][128]
   __bf16* o;                         // [N][hv][128]
   // per (chunk, value head) operands
-  __bf16* wn;                        // [64][128]  -W
-  __bf16* ut;                        // [128][64]  U transposed
-  __bf16* qg;                        // [64][128]  scale * Q * exp(gamma)
-  __bf16* kdt;                       // [128][64]  (K * exp(gamma_last - gamma)) transposed
-  __bf16* p;                         // [64][64]   scale * tril((Q K^T) * exp(gamma_i - gamma_j))
+  __bf16* rec;                       // records of REC_ELEMS: -W [64][128], U^T [128][64], scale Q exp(gamma) [64][128],
+                                     // (K exp(gamma_last - gamma))^T [128][64], scale tril((Q K^T) exp(gamma_i - gamma_j)) [64][64]
   float* glast;                      // exp(gamma_last)
   float* slots;                      // [n_slots][hv][128][128] saved node-end states
 };
 
-__device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)chunk * a.hv + h; }
+// The operands of one (head, chunk) form one contiguous record, records ordered head-major: a scan
+// workgroup (one head) then streams through memory front to back -- consecutive chunks are
+// adjacent, so address translation and DRAM pages are reused instead of missed on every step.
+constexpr size_t REC_WN = 0, REC_UT = GC * GD, REC_QG = 2 * GC * GD, REC_KDT = 3 * GC * GD, REC_P = 4 * GC * GD;
+constexpr size_t REC_ELEMS = 4 * GC * GD + GC * GC;      // bf16 elements per record (72 KB)
+__device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)h * a.n_chunks + chunk; }
 
 __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(16))) __bf16 ksm[GC][GROW];
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     }
     *(bf16x8*)&ksm[i][c8] = kv;
     *(bf16x8*)&qsm[i][c8] = qv;
-    *(bf16x8*)(a.qg + op * (GC * GD) + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
+    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
   }
   __syncthreads();
 
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         qk = mfma32(qi, kj, qk);
       }
       const int j = jb * 32 + c;
-      __bf16* pout = a.p + op * (GC * GC);
+      __bf16* pout = a.rec + op * REC_ELEMS + REC_P;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       }
     } else {
       const int j = jb * 32 + c;
-      __bf16* pout = a.p + op * (GC * GC);
+      __bf16* pout = a.rec + op * REC_ELEMS + REC_P;
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     float f[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
-    *(bf16x8*)(a.kdt + op * (GD * GC) + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
   }
   __syncthreads();
 
@@ -176,12 +178,12 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       }
     }
     if (c < GD) {
-      __bf16* dst = a.ut + op * (GD * GC) + c * GC;
+      __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + c * GC;
 #pragma unroll
       for (int i0 = 0; i0 < GC; i0 += 8)
         *(bf16x8*)(dst + i0) = cvt8(x[i0], x[i0 + 1], x[i0 + 2], x[i0 + 3], x[i0 + 4], x[i0 + 5], x[i0 + 6], x[i0 + 7]);
     } else {
-      __bf16* dst = a.wn + op * (GC * GD) + (c - GD);
+      __bf16* dst = a.rec + op * REC_ELEMS + REC_WN + (c - GD);
 #pragma unroll
       for (int i = 0; i < GC; i++) dst[i * GD] = (__bf16)(-x[i]);
     }
@@ -222,11 +224,12 @@ struct ChunkRegs {
 
 // piece index -> (global address, LDS address); pieces 0..1023 Wn, ..2047 Qg, ..3071 KdT, ..3327 UT block, ..3839 P
 __device__ __forceinline__ const u32x4n* piece_src(const GdnArgs& a, size_t op, int dvb, int piece) {
-  if (piece < 1024) return (const u32x4n*)(a.wn + op * (GC * GD)) + piece;
-  if (piece < 2048) return (const u32x4n*)(a.qg + op * (GC * GD)) + (piece - 1024);
-  if (piece < 3072) return (const u32x4n*)(a.kdt + op * (GD * GC)) + (piece - 2048);
-  if (piece < 3328) return (const u32x4n*)(a.ut + op * (GD * GC) + (size_t)dvb * G_DVB * GC) + (piece - 3072);
-  return (const u32x4n*)(a.p + op * (GC * GC)) + (piece - 3328);
+  const __bf16* rec = a.rec + op * REC_ELEMS;
+  if (piece < 1024) return (const u32x4n*)(rec + REC_WN) + piece;
+  if (piece < 2048) return (const u32x4n*)(rec + REC_QG) + (piece - 1024);
+  if (piece < 3072) return (const u32x4n*)(rec + REC_KDT) + (piece - 2048);
+  if (piece < 3328) return (const u32x4n*)(rec + REC_UT + (size_t)dvb * G_DVB * GC) + (piece - 3072);
+  return (const u32x4n*)(rec + REC_P) + (piece - 3328);
 }
 __device__ __forceinline__ u32x4n* piece_dst(ScanSmem& sm, int piece) {
   if (piece < 1024) return (u32x4n*)&sm.wn[piece >> 4][(piece & 15) * 8];
@@ -419,8 +422,7 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
   const size_t per = (size_t)n_chunks * hv;
-  return align256(per * GC * GD * 2) * 4 + align256(per * GC * GC * 2) + align256(per * 4) +
-         align256((size_t)n_slots * hv * GD * GD * 4) + 256;
+  return align256(per * REC_ELEMS * 2) + align256(per * 4) + align256((size_t)n_slots * hv * GD * GD * 4) + 256;
 }
 
 hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
@@ -436,11 +438,7 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
   a.o = (__bf16*)o;
   const size_t per = (size_t)n_chunks * hv;
   char* p = (char*)workspace;
-  a.wn = (__bf16*)p;  p += align256(per * GC * GD * 2);
-  a.ut = (__bf16*)p;  p += align256(per * GC * GD * 2);
-  a.qg = (__bf16*)p;  p += align256(per * GC * GD * 2);
-  a.kdt = (__bf16*)p; p += align256(per * GC * GD * 2);
-  a.p = (__bf16*)p;   p += align256(per * GC * GC * 2);
+  a.rec = (__bf16*)p; p += align256(per * REC_ELEMS * 2);
   a.glast = (float*)p; p += align256(per * 4);
   a.slots = (float*)p;
   {
