@@ -190,85 +190,77 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   }
 }
 
-// 8 k-values in the order in which an accumulator's registers enumerate rows: elements e = 0..3 are
-// columns base + 4 hf .. +3, e = 4..7 columns base + 8 + 4 hf .. +3 of a row-major matrix row.
-__device__ __forceinline__ bf16x8 load_perm_k(const __bf16* row, int base, int hf) {
-  const bf16x4 lo = *(const bf16x4*)(row + base + 4 * hf);
-  const bf16x4 hi = *(const bf16x4*)(row + base + 8 + 4 * hf);
-  return cat4(lo, hi);
-}
+typedef unsigned u32x4n __attribute__((ext_vector_type(4)));      // native vector type (stays in registers)
 
-// LDS image of one chunk's operands (rows padded by 8 elements against bank conflicts)
-constexpr int GROW64 = GC + 8;
+// ---- scan kernel ------------------------------------------------------------------------------------
+// LDS image of one chunk's operands, filled by direct global->LDS copies (no registers, no store
+// instructions; the copy engine's time overlaps the MFMA phases of the previous chunk).  A copy
+// instruction writes 1 KB contiguous, so rows cannot be padded; 16-byte pieces are permuted instead:
+// the [64][128] tiles use the attention kernels' swizzle (dma_tile64 / lds_row_frag), the arrays with
+// 64-element rows store piece q of row r at position q ^ (r & 7).
+struct ScanImage {
+  __bf16 wn[GC * GD];           // -W, swizzled tile
+  __bf16 qg[GC * GD];           // scale Q exp(gamma), swizzled tile
+  __bf16 kd[GD * GC];           // (K decayed)^T, rows of 64
+  __bf16 ut[G_DVB * GC];        // U^T, this workgroup's value columns, rows of 64
+  __bf16 p[GC * GC];            // scale tril(Q K^T decay), rows of 64
+};
 struct ScanSmem {
-  __bf16 wn[GC][GROW];          // -W
-  __bf16 qg[GC][GROW];          // scale Q exp(gamma)
-  __bf16 kd[GD][GROW64];        // (K decayed)^T
-  __bf16 ut[G_DVB][GROW64];     // U^T, this workgroup's value columns
-  __bf16 p[GC][GROW64];         // scale tril(Q K^T decay)
+  ScanImage img[2];
   __bf16 st[G_DVB][GROW];       // S0^T
   __bf16 ot[2][32][G_DVB + 8];  // output tiles of waves 2 and 3 on their way to 16-byte stores
   bf16x8 vx[2][2][64];          // Vn as per-lane B-operand fragments, written by waves 0 and 1, read by all
 };
-constexpr int SCAN_PIECES = (GC * GD * 3 + G_DVB * GC + GC * GC) / 8 / G_THREADS;   // 16-byte pieces per lane: 15
-static_assert(SCAN_PIECES * G_THREADS * 8 == GC * GD * 3 + G_DVB * GC + GC * GC, "operands must split evenly over the lanes");
 
-typedef unsigned u32x4n __attribute__((ext_vector_type(4)));      // native vector type (stays in registers)
+// 4 consecutive elements e0 .. e0+3 (e0 a multiple of 4) of row r of a rows-of-64 array
+__device__ __forceinline__ bf16x4 row64_read4(const __bf16* arr, int r, int e0) {
+  return *(const bf16x4*)(arr + r * GC + ((((e0 >> 3) ^ (r & 7)) << 3) | (e0 & 7)));
+}
+// 8 k-values in the order in which an accumulator's registers enumerate rows: elements e = 0..3 are
+// columns base + 4 hf .. +3, e = 4..7 columns base + 8 + 4 hf .. +3 of row r.
+__device__ __forceinline__ bf16x8 row64_perm_k(const __bf16* arr, int r, int base, int hf) {
+  return cat4(row64_read4(arr, r, base + 4 * hf), row64_read4(arr, r, base + 8 + 4 * hf));
+}
 
-// One chunk's operands as 16-byte pieces, 15 per lane, every wave-level load contiguous in memory.
-struct ChunkRegs {
-  u32x4n v[SCAN_PIECES];
+// Copies `rows` rows of 64 elements (contiguous in memory) into a rows-of-64 array; 8 rows per
+// instruction, instructions dealt round-robin to the 4 waves.
+__device__ __forceinline__ void dma_rows64(const __bf16* src, int rows, __bf16* dst, int w, int lane) {
+  const void* gb = uniform_ptr(src);
+  const int rr = lane >> 3, pos = lane & 7;
+  for (int g = w; g < rows / 8; g += 4)
+    dma16(gb, (uint32_t)((8 * g + rr) * 128 + ((pos ^ rr) << 4)), lds_addr_uniform(dst + g * 8 * GC));
+}
+
+// Starts the copy of one chunk's operands into `im` (15 instructions per wave).
+__device__ __forceinline__ void issue_chunk(const GdnArgs& a, int chunk, int h, int dvb, ScanImage& im, int w, int lane) {
+  const __bf16* rec = a.rec + op_index(a, chunk, h) * REC_ELEMS;
+  dma_tile64<4>(rec + REC_WN, GD * 2, GC, im.wn, w, lane);
+  dma_tile64<4>(rec + REC_QG, GD * 2, GC, im.qg, w, lane);
+  dma_rows64(rec + REC_KDT, GD, im.kd, w, lane);
+  dma_rows64(rec + REC_UT + (size_t)dvb * G_DVB * GC, G_DVB, im.ut, w, lane);
+  dma_rows64(rec + REC_P, GC, im.p, w, lane);
+}
+
+// The scalars of a chunk.  `z` is a per-lane zero the compiler cannot see through: they are loaded per
+// lane and stay in vector registers (a value proven uniform is moved to a scalar register right behind
+// its load, which would stall for a full memory latency).
+struct ChunkMeta {
   int tok0, len, src, dst, cap;
   float glast;
 };
-
-// piece index -> (global address, LDS address); pieces 0..1023 Wn, ..2047 Qg, ..3071 KdT, ..3327 UT block, ..3839 P
-__device__ __forceinline__ const u32x4n* piece_src(const GdnArgs& a, size_t op, int dvb, int piece) {
-  const __bf16* rec = a.rec + op * REC_ELEMS;
-  if (piece < 1024) return (const u32x4n*)(rec + REC_WN) + piece;
-  if (piece < 2048) return (const u32x4n*)(rec + REC_QG) + (piece - 1024);
-  if (piece < 3072) return (const u32x4n*)(rec + REC_KDT) + (piece - 2048);
-  if (piece < 3328) return (const u32x4n*)(rec + REC_UT + (size_t)dvb * G_DVB * GC) + (piece - 3072);
-  return (const u32x4n*)(rec + REC_P) + (piece - 3328);
-}
-__device__ __forceinline__ u32x4n* piece_dst(ScanSmem& sm, int piece) {
-  if (piece < 1024) return (u32x4n*)&sm.wn[piece >> 4][(piece & 15) * 8];
-  if (piece < 2048) return (u32x4n*)&sm.qg[(piece - 1024) >> 4][(piece & 15) * 8];
-  if (piece < 3072) return (u32x4n*)&sm.kd[(piece - 2048) >> 3][(piece & 7) * 8];
-  if (piece < 3328) return (u32x4n*)&sm.ut[(piece - 3072) >> 3][(piece & 7) * 8];
-  return (u32x4n*)&sm.p[(piece - 3328) >> 3][(piece & 7) * 8];
-}
-
-// `z` is a per-lane zero the compiler cannot see through: the chunk's scalars are loaded per lane and
-// stay in vector registers, so the wait for them sits at their first use two chunks later (a value
-// proven uniform is moved to a scalar register right behind its load, which would stall every chunk
-// for a full memory latency).
-__device__ __forceinline__ void load_chunk(const GdnArgs& a, int chunk, int h, int dvb, int tid, int z, ChunkRegs& r) {
+__device__ __forceinline__ void load_meta(const GdnArgs& a, int chunk, int h, int z, ChunkMeta& r) {
   r.tok0 = a.chunk_tok0[chunk + z]; r.len = a.chunk_len[chunk + z]; r.src = a.chunk_src[chunk + z]; r.dst = a.chunk_dst[chunk + z];
   r.cap = a.chunk_cap ? a.chunk_cap[chunk + z] : -1;
-  const size_t op = op_index(a, chunk, h);
-  r.glast = a.glast[op + z];
-#pragma unroll
-  for (int i = 0; i < SCAN_PIECES; i++) r.v[i] = *piece_src(a, op, dvb, i * G_THREADS + tid);
+  r.glast = a.glast[op_index(a, chunk, h) + z];
 }
 
-__device__ __forceinline__ bf16x8 lds_perm_k(const __bf16* row, int base, int hf) {
-  const bf16x4 lo = *(const bf16x4*)(row + base + 4 * hf);
-  const bf16x4 hi = *(const bf16x4*)(row + base + 8 + 4 * hf);
-  return cat4(lo, hi);
-}
-
-// One chunk of the scan.  `regs` holds the chunk's operands on entry; they are moved to LDS and the
-// register set is refilled with the operands of the chunk two steps ahead (two sets alternate, so
-// every load has two chunk times to arrive).
-__device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkRegs& regs, int chunk, int h, int dvb, int tid, int z,
-                                          int w, int c, int hf, f32x16& s) {
-  const int lane = tid & 63;
-  const int tok0 = regs.tok0, len = regs.len, src = regs.src, dst = regs.dst, cap = regs.cap;
-  const float glast = regs.glast;
-#pragma unroll
-  for (int i = 0; i < SCAN_PIECES; i++) *piece_dst(sm, i * G_THREADS + tid) = regs.v[i];
-  load_chunk(a, min(chunk + 2, a.n_chunks - 1), h, dvb, tid, z, regs);
+// One chunk of the scan.  On entry the copy of this chunk's operands into `im` is in flight (issued one
+// step earlier) and `meta` holds its scalars; the step waits for them, starts the next chunk's copy
+// into `im_next` and reloads `meta` for the next step.  Two barriers per step.
+__device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
+                                          int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s) {
+  const int tok0 = meta.tok0, len = meta.len, src = meta.src, dst = meta.dst, cap = meta.cap;
+  const float glast = meta.glast;
 
   if (src == -1 && !a.initial_state) {
     s = zero16();
@@ -284,7 +276,11 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
 #pragma unroll
   for (int r4 = 0; r4 < 4; r4++)
     *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
-  __syncthreads();
+  dma_wait_all();                     // this wave's share of the chunk's operands has landed ...
+  __syncthreads();                    // ... and so has everybody else's; every wave has also left the previous step,
+                                      // so the other image, st and vx may be overwritten
+  if (chunk + 1 < a.n_chunks) issue_chunk(a, chunk + 1, h, dvb, im_next, w, lane);
+  load_meta(a, min(chunk + 1, a.n_chunks - 1), h, z, meta);
 
   // Waves 0 and 1 compute one 32-row block of Vn = U - W S0 each; waves 2 and 3 meanwhile compute their
   // 32 rows of Q S0, the part of the output that does not need Vn.  Vn then goes through LDS as per-lane
@@ -297,18 +293,19 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
   bf16x8 pfrag[2][2];                 // waves 2, 3: A operands of P Vn
   const int half = w & 1;             // which 32-row block this wave works on
   {
-    const __bf16* arow = w < 2 ? &sm.wn[half * 32 + c][0] : &sm.qg[half * 32 + c][0];
+    const __bf16* atile = w < 2 ? im.wn : im.qg;
+    const int abase = row_frag_base(lane);
 #pragma unroll
     for (int ks = 0; ks < GD / 16; ks++) {
       sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
-      afrag[ks] = *(const bf16x8*)(arow + ks * 16 + hf * 8);
+      afrag[ks] = lds_row_frag(atile, abase, half, ks);
     }
   }
   f32x16 acc;
   if (w < 2) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
-      const bf16x4 u4 = *(const bf16x4*)&sm.ut[c][half * 32 + r4 * 8 + hf * 4];
+      const bf16x4 u4 = row64_read4(im.ut, c, half * 32 + r4 * 8 + hf * 4);
 #pragma unroll
       for (int e = 0; e < 4; e++) acc[4 * r4 + e] = (float)u4[e];
     }
@@ -319,8 +316,8 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
   for (int jb = 0; jb < 2; jb++)
 #pragma unroll
     for (int t = 0; t < 2; t++) {
-      kfrag[jb][t] = lds_perm_k(&sm.kd[32 * w + c][0], jb * 32 + t * 16, hf);
-      pfrag[jb][t] = lds_perm_k(&sm.p[half * 32 + c][0], jb * 32 + t * 16, hf);     // used by waves 2, 3 only
+      kfrag[jb][t] = row64_perm_k(im.kd, 32 * w + c, jb * 32 + t * 16, hf);
+      pfrag[jb][t] = row64_perm_k(im.p, half * 32 + c, jb * 32 + t * 16, hf);     // used by waves 2, 3 only
     }
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -376,11 +373,10 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ChunkR
       if (i < len) *(u32x4n*)(a.o + ((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + q8) = val;
     }
   }
-  __syncthreads();                    // every wave is done with this chunk's LDS image before it is overwritten
 }
 
 __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
-  __shared__ __attribute__((aligned(16))) ScanSmem sm;
+  __shared__ __attribute__((aligned(1024))) ScanSmem sm;
 
   // (head, column block) from the workgroup id.  Consecutive ids go round-robin over the 8 XCDs;
   // the four column blocks of a head read the same operands, so they are given ids 8 apart and
@@ -389,30 +385,20 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
   int h, dvb;
   if (a.hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
   else               { h = id >> 2; dvb = id & 3; }
-  const int tid = threadIdx.x & (G_THREADS - 1);      // the mask tells the compiler the range, so that
-  const int lane = tid & 63;                          // every piece's array is known at compile time
+  const int tid = threadIdx.x & (G_THREADS - 1);
+  const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 31, hf = lane >> 5;
   f32x16 s = zero16();                  // S[32 w + rows(r)][dvb*32 + c]
 
   int z = 0;
   asm volatile("" : "+v"(z));
-  ChunkRegs ra, rb;
-  load_chunk(a, 0, h, dvb, tid, z, ra);
-  load_chunk(a, min(1, a.n_chunks - 1), h, dvb, tid, z, rb);
-  // Four steps per trip: the load queue is drained where the loop closes (the compiler cannot carry
-  // "which loads are still in flight" around the back edge), so the longer the straight-line stretch,
-  // the more of the time both register sets are in flight.
-  int chunk = 0;
-  for (; chunk + 4 <= a.n_chunks; chunk += 4) {
-    scan_step(a, sm, ra, chunk, h, dvb, tid, z, w, c, hf, s);
-    scan_step(a, sm, rb, chunk + 1, h, dvb, tid, z, w, c, hf, s);
-    scan_step(a, sm, ra, chunk + 2, h, dvb, tid, z, w, c, hf, s);
-    scan_step(a, sm, rb, chunk + 3, h, dvb, tid, z, w, c, hf, s);
-  }
-  for (; chunk < a.n_chunks; chunk += 2) {
-    scan_step(a, sm, ra, chunk, h, dvb, tid, z, w, c, hf, s);
-    if (chunk + 1 < a.n_chunks) scan_step(a, sm, rb, chunk + 1, h, dvb, tid, z, w, c, hf, s);
+  ChunkMeta meta;
+  issue_chunk(a, 0, h, dvb, sm.img[0], w, lane);
+  load_meta(a, 0, h, z, meta);
+  for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
+    scan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s);
+    if (chunk + 1 < a.n_chunks) scan_step(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, h, dvb, lane, z, w, c, hf, s);
   }
 }
 
