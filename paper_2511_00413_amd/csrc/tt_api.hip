@@ -243,7 +243,7 @@ extern "C" tt_status tt_tree_conv_fwd(int64_t n_tokens, int32_t channels, int32_
   ConvChecked c;
   if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, tok_pred, y, y_stride_tok, c))
     return s;
-  if (x == y) return fail(TT_ERR_SHAPE, "y may not alias x (later tokens read earlier rows of x)");
+  if (n_tokens > 0 && x == y) return fail(TT_ERR_SHAPE, "y may not alias x (later tokens read earlier rows of x)");
   return hip_result(tt::conv_fwd(n_tokens, channels, kernel_size, c.bf16, activation == 1, x, c.xs, weight, bias, tok_pred, y, c.ys,
                                  (hipStream_t)stream),
                     "tree_conv_fwd");
@@ -271,7 +271,7 @@ extern "C" tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_
     return s;
   if (!dweight) return fail(TT_ERR_NULL, "dweight is NULL");
   if (n_fix < 0 || (n_fix > 0 && (!fix_tok || !fix_off || !fix_t || !fix_r))) return fail(TT_ERR_NULL, "n_fix=%d with a NULL list", n_fix);
-  if (dx == x || dx == dy) return fail(TT_ERR_SHAPE, "dx may not alias x or dy");
+  if (n_tokens > 0 && (dx == x || dx == dy)) return fail(TT_ERR_SHAPE, "dx may not alias x or dy");
   const size_t need = tt::conv_bwd_workspace(n_tokens, channels, kernel_size, c.bf16);
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
     return fail(TT_ERR_WORKSPACE, "conv backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
