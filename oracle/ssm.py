@@ -113,3 +113,44 @@ def gdn_tree(q, k, v, g, beta, tok_pred, scale: Optional[float] = None, return_s
             states[t, h] = s
             o[t, h] = scale * (s.T @ qt)
     return (o, states) if return_states else o
+
+
+def gdn_tree_bwd(q, k, v, g, beta, tok_pred, d_o, scale: Optional[float] = None):
+    """Vector-Jacobian product of gdn_tree for upstream d_o [N, Hv, Dv]: (dq, dk [N, Hk, Dk], dv [N, Hv, Dv],
+    dg, dbeta [N, Hv]).  The recurrence run backwards: dL/dS_t collects scale * q_t d_o_t^T and what every
+    successor of t on any branch sends back (several successors at a branch point: their contributions
+    add, which is the gradient accumulation at the shared parent state of the paper's "SSM Layers"
+    paragraph).  Per token, with S~ = e^g S_p, r = v - S~^T k, d = beta r, S_t = S~ + k d^T, R = dL/dS_t:
+        dq = scale S_t d_o;   dd = R^T k;   dv = beta dd;   dbeta = dd . r
+        dS~ = R - beta k dd^T;   dk = R d - beta S~ dd;   dg = <dS~, S~>;   dL/dS_p += e^g dS~
+    Small inputs only (keeps every state)."""
+    q, k, v, g, beta, d_o = _f64(q), _f64(k), _f64(v), _f64(g), _f64(beta), _f64(d_o)
+    n, hk, dk = q.shape
+    hv, dv = v.shape[1], v.shape[2]
+    rep = hv // hk
+    scale = float(dk) ** -0.5 if scale is None else float(scale)
+    tok_pred = np.asarray(tok_pred, dtype=np.int64)
+    _, states = gdn_tree(q, k, v, g, beta, tok_pred, scale, return_states=True)
+    dS = np.zeros_like(states)
+    dq, dkk, dvv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    dg, dbeta = np.zeros_like(g), np.zeros_like(beta)
+    for t in range(n - 1, -1, -1):               # successors always come later in DFS order
+        p = tok_pred[t]
+        for h in range(hv):
+            kh = h // rep
+            kt, qt = k[t, kh], q[t, kh]
+            s_t = states[t, h]
+            s_dec = np.exp(g[t, h]) * (states[p, h] if p >= 0 else np.zeros((dk, dv)))
+            r = v[t, h] - s_dec.T @ kt
+            d = beta[t, h] * r
+            R = dS[t, h] + scale * np.outer(qt, d_o[t, h])
+            dq[t, kh] += scale * (s_t @ d_o[t, h])
+            dd = R.T @ kt
+            dvv[t, h] = beta[t, h] * dd
+            dbeta[t, h] = dd @ r
+            ds_dec = R - beta[t, h] * np.outer(kt, dd)
+            dkk[t, kh] += R @ d - beta[t, h] * (s_dec @ dd)
+            dg[t, h] = float(np.sum(ds_dec * s_dec))
+            if p >= 0:
+                dS[p, h] += np.exp(g[t, h]) * ds_dec
+    return dq, dkk, dvv, dg, dbeta

@@ -205,3 +205,79 @@ def test_gdn_closed_forms():
     for t_ in range(n):
         want = sum(np.exp(gg[j + 1:t_ + 1, 0].sum()) * (qq[t_, 0] @ ko[j, 0]) * vv[j, 0] for j in range(t_ + 1))
         assert np.allclose(o[t_, 0], want)
+
+
+# ---- backward of the gated delta rule with tree state routing ----
+
+def _torch_branch_gdn(q, k, v, g, beta, scale):
+    """One standalone sequence with library tensors (autograd does the differentiation): q, k [L, Dk], v [L, Dv]."""
+    S_ = torch.zeros((q.shape[1], v.shape[1]), dtype=torch.float64)
+    outs = []
+    for t in range(q.shape[0]):
+        S_ = torch.exp(g[t]) * S_
+        d = beta[t] * (v[t] - S_.T @ k[t])
+        S_ = S_ + torch.outer(k[t], d)
+        outs.append(scale * (S_.T @ q[t]))
+    return torch.stack(outs)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_gdn_bwd_equals_autograd_over_branches(seed):
+    """Every branch run alone through autograd; a token shared by n branches gets 1/n of its upstream gradient
+    in each, so the summed branch gradients are the tree's."""
+    t = W.random_tree(75 + seed, n_nodes=4 + 2 * seed, lo=1, hi=5, n_roots=1 + seed % 2, p_zero=0.15)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n, hk, hv, dk, dv = m["n_tokens"], 1, 2, 5, 4
+    q, k, v, g, beta = _gdn_inputs(n, hk, hv, dk, dv, seed)
+    d_o = np.random.default_rng(seed + 50).normal(size=(n, hv, dv))
+    dq, dkk, dvv, dg, dbeta = S.gdn_tree_bwd(q, k, v, g, beta, m["tok_pred"], d_o, scale=0.6)
+    share = np.zeros(n)
+    paths = [p for p in M.paths(m) if len(p)]
+    for p in paths:
+        share[p] += 1
+    tq, tk, tv, tg, tb = (torch.tensor(x, requires_grad=True) for x in (q, k, v, g, beta))
+    total = 0.0
+    for p in paths:
+        idx = torch.tensor(p, dtype=torch.long)
+        for h in range(hv):
+            ob = _torch_branch_gdn(tq[idx, 0], tk[idx, 0], tv[idx, h], tg[idx, h], tb[idx, h], 0.6)
+            total = total + (ob * torch.tensor(d_o[p, h] / share[p][:, None])).sum()
+    total.backward()
+    for name, a, b in (("dq", dq, tq.grad), ("dk", dkk, tk.grad), ("dv", dvv, tv.grad), ("dg", dg, tg.grad), ("dbeta", dbeta, tb.grad)):
+        assert np.allclose(a, b.numpy(), rtol=1e-9, atol=1e-11), name
+
+
+def test_gdn_bwd_finite_differences():
+    m = M.dfs_meta([-1, 0, 0], [2, 2, 1])
+    n, hk, hv, dk, dv = m["n_tokens"], 1, 1, 3, 2
+    q, k, v, g, beta = _gdn_inputs(n, hk, hv, dk, dv, 9)
+    d_o = np.random.default_rng(1).normal(size=(n, hv, dv))
+    grads = S.gdn_tree_bwd(q, k, v, g, beta, m["tok_pred"], d_o)
+    args = [q, k, v, g, beta]
+    f = lambda a: float((S.gdn_tree(*a, m["tok_pred"]) * d_o).sum())
+    eps = 1e-6
+    for which, grad in enumerate(grads):
+        for idx in np.ndindex(args[which].shape):
+            hi = [x.copy() for x in args]; lo = [x.copy() for x in args]
+            hi[which][idx] += eps; lo[which][idx] -= eps
+            assert abs((f(hi) - f(lo)) / (2 * eps) - grad[idx]) < 1e-6, (which, idx)
+
+
+def test_gdn_bwd_gradients_add_at_a_branch_point():
+    """Two children of one parent: the parent's gradients are the sum of what each child alone would send
+    back plus the parent's own (linearity in d_o)."""
+    m = M.dfs_meta([-1, 0, 0], [3, 2, 2])
+    n = m["n_tokens"]
+    q, k, v, g, beta = _gdn_inputs(n, 1, 1, 4, 3, 4)
+    d_o = np.random.default_rng(2).normal(size=(n, 1, 3))
+    full = S.gdn_tree_bwd(q, k, v, g, beta, m["tok_pred"], d_o)
+    parts = []
+    for sel in (slice(0, 3), slice(3, 5), slice(5, 7)):
+        masked = np.zeros_like(d_o)
+        masked[sel] = d_o[sel]
+        parts.append(S.gdn_tree_bwd(q, k, v, g, beta, m["tok_pred"], masked))
+    for i in range(5):
+        assert np.allclose(full[i], parts[0][i] + parts[1][i] + parts[2][i], rtol=1e-12, atol=1e-14)
+    # a child's upstream gradient never reaches its sibling
+    only_c1 = parts[1]
+    assert np.all(only_c1[2][5:7] == 0) and np.all(only_c1[0][5:7] == 0) and np.any(only_c1[2][0:3] != 0)
