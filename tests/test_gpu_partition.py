@@ -2,7 +2,9 @@
 subtrees at node boundaries; every partition attends to the cached K/V of its ancestors' partition
 (with the non-ancestor part of the cached slice masked), gradients for the cached keys come back
 through the fp32 accumulators, and the stitched result must equal the oracle run on the whole tree
-(which knows nothing about partitions).  The greedy packer below is test harness only."""
+(which knows nothing about partitions).  The first group of tests stitches the partitions by hand on the
+host (its own small packer and gateway bookkeeping); the second group runs the library's planner and
+its one-call driver."""
 import numpy as np
 import pytest
 import torch
