@@ -482,6 +482,38 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
                           void* o, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Gated delta rule with tree state routing, backward (device)
+ *
+ * Vector-Jacobian product of tt_tree_gdn_fwd (same section and appendix): the recurrence run
+ * backwards over the tree.  The gradient of a state that several child branches start from is
+ * the sum of what they send back -- the gradient accumulation at the shared parent state of the
+ * paper's "SSM Layers" paragraph -- which the chunk program provides: a chunk that started from a
+ * saved-state slot adds the gradient of its entering state to that slot's gradient, and the
+ * chunk that saved the slot picks the sum up (reverse DFS order sees every reader first).
+ * Inputs as for the forward, plus d_o [n_tokens][hv][128] bf16.  The call recomputes the
+ * per-chunk states itself (it does not need a preceding forward call or its workspace).
+ * Outputs: dq, dk [n_tokens][hk][128] bf16 (summed over the hv / hk value heads of a key head in
+ * fp32, then rounded once), dv [n_tokens][hv][128] bf16, dg, dbeta [n_tokens][hv] fp32.
+ * Gateway (Appendix "SSM State Gateway"), all optional (NULL): initial_state as in the forward;
+ * d_state_out [n_capture][hv][128][128] fp32, the upstream gradient of the captured end states
+ * (what the child partitions' d_initial_state returned; needs chunk_cap);
+ * d_initial_state [hv][128][128] fp32, overwritten with the gradient of the state the roots
+ * start from.  Arithmetic: fp32 throughout (inputs are read as bf16).
+ * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 420 KB per chunk and value
+ * head, plus two fp32 [n_tokens][hv][128] arrays and 2 x n_slots saved states per head).
+ * Errors: as tt_tree_gdn_fwd.
+ * ------------------------------------------------------------------------------------------ */
+size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t hk, int32_t hv);
+tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
+                          const void* q, const void* k, const void* v, const float* g, const float* beta,
+                          const void* d_o,
+                          int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                          const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                          const int32_t* chunk_cap, const float* initial_state, const float* d_state_out,
+                          void* dq, void* dk_out, void* dv_out, float* dg, float* dbeta, float* d_initial_state,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (measurement aid; off by default).  When enabled, every kernel the library
  * launches is bracketed by HIP events on the launch stream.  tt_kernel_timing_read blocks until
  * the recorded events have completed and returns the totals since the last enable.
@@ -505,7 +537,10 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
 #define TT_KERNEL_CONV_FIX     16  /* its branch-point fix-up and weight-gradient reduce */
 #define TT_KERNEL_GDN_PREPARE  17  /* gated delta rule: per-chunk operands (parallel)     */
 #define TT_KERNEL_GDN_SCAN     18  /* gated delta rule: state scan over the tree          */
-#define TT_N_KERNELS          19
+#define TT_KERNEL_GDN_BWD_FSCAN  19  /* gated delta rule backward: forward walk that saves the states */
+#define TT_KERNEL_GDN_BWD_RSCAN  20  /* reverse walk (state gradients)                              */
+#define TT_KERNEL_GDN_BWD_FINISH 21  /* per-chunk gradients                                         */
+#define TT_N_KERNELS          22
 typedef struct {
   double  ms[TT_N_KERNELS];        /* summed kernel time in milliseconds */
   int64_t launches[TT_N_KERNELS];

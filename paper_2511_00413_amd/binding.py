@@ -111,6 +111,12 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_gdn_fwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                         _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp,
                                         _vp, _vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_gdn_bwd_workspace.restype = ctypes.c_size_t
+        lib.tt_tree_gdn_bwd_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.tt_tree_gdn_bwd.restype = ctypes.c_int32
+        lib.tt_tree_gdn_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         lib.tt_tree_path_weights.restype = ctypes.c_int32
         lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
         lib.tt_tree_partition_sizes.restype = ctypes.c_int32
@@ -132,7 +138,8 @@ def _lib() -> ctypes.CDLL:
 
 
 KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
-                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix", "gdn_prepare", "gdn_scan")
+                "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix", "gdn_prepare", "gdn_scan",
+                "gdn_bwd_fscan", "gdn_bwd_rscan", "gdn_bwd_finish")
 
 
 class _KernelTimes(ctypes.Structure):
@@ -692,3 +699,43 @@ def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, works
                                   _dp(initial_state), _dp(states) if plan.n_capture else None, _dp(out), _dp(workspace), workspace.numel(),
                                   _stream_ptr(stream)))
     return (out, states) if return_states else out
+
+
+def tree_gdn_bwd(q, k, v, g, beta, d_o, plan: GdnPlan, *, scale=None, initial_state=None, d_state_out=None,
+                 want_d_initial_state: bool = False, workspace=None, stream=None):
+    """Backward of tree_gdn_fwd for upstream d_o [n, hv, 128] bf16.  Returns (dq, dk [n, hk, 128] bf16, dv [n, hv, 128]
+    bf16, dg, dbeta [n, hv] fp32), plus d_initial_state [hv, 128, 128] fp32 when asked.  d_state_out
+    [n_capture, hv, 128, 128] fp32: upstream gradient of the plan's captured end states."""
+    torch = _torch()
+    for t in (q, k, v, d_o):
+        if t.dim() != 3 or t.dtype != torch.bfloat16 or not t.is_contiguous():
+            raise ValueError("q, k, v, d_o must be contiguous bf16 [tokens, heads, dim]")
+    n, hk, dk = q.shape
+    hv, dv = v.shape[1], v.shape[2]
+    if k.shape != q.shape or v.shape[0] != n or d_o.shape != v.shape:
+        raise ValueError("k must match q, v must have the same token count, d_o must match v")
+    for t in (g, beta):
+        if t.shape != (n, hv) or t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("g, beta must be contiguous fp32 [tokens, hv]")
+    for t, shape, name in ((initial_state, (hv, dk, dv), "initial_state"), (d_state_out, (plan.n_capture, hv, dk, dv), "d_state_out")):
+        if t is not None and (tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_contiguous()):
+            raise ValueError(f"{name} must be a contiguous fp32 tensor of shape {shape}")
+    if plan.device is None:
+        plan.to_device(q.device)
+    dev = q.device
+    dq, dk_ = torch.empty_like(q), torch.empty_like(k)
+    dv_ = torch.empty_like(v)
+    dg, dbeta = torch.empty_like(g), torch.empty_like(beta)
+    d_init = torch.empty((hv, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None
+    need = int(_lib().tt_tree_gdn_bwd_workspace(n, plan.n_chunks, plan.n_slots, hk, hv))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    d = plan.device
+    use_cap = d_state_out is not None and plan.n_capture > 0
+    _check(_lib().tt_tree_gdn_bwd(n, hk, hv, dk, dv, float(dk) ** -0.5 if scale is None else float(scale), _dp(q), _dp(k), _dp(v),
+                                  _dp(g), _dp(beta), _dp(d_o), plan.n_chunks, _dp(d["chunk_tok0"]), _dp(d["chunk_len"]),
+                                  _dp(d["chunk_src"]), _dp(d["chunk_dst"]), plan.n_slots, _dp(d["chunk_cap"]) if use_cap else None,
+                                  _dp(initial_state), _dp(d_state_out) if use_cap else None, _dp(dq), _dp(dk_), _dp(dv_), _dp(dg),
+                                  _dp(dbeta), _dp(d_init), _dp(workspace), workspace.numel(), _stream_ptr(stream)))
+    out = (dq, dk_, dv_, dg, dbeta)
+    return out + (d_init,) if want_d_initial_state else out

@@ -12,7 +12,7 @@ LIB = os.path.join(HERE, "libtreetrain.so")
 
 SOURCES = ["tt_error.cpp", "tt_meta.cpp", "tt_api.hip", "tt_timing.hip", "tt_attn_ref.hip", "tt_loss.hip",
            "tt_attn_fwd.hip", "tt_attn_bwd.hip", "tt_attn_dkdv.hip", "tt_rope.hip", "tt_partition.cpp",
-           "tt_partition_run.hip", "tt_conv.hip", "tt_gdn.hip"]
+           "tt_partition_run.hip", "tt_conv.hip", "tt_gdn.hip", "tt_gdn_bwd.hip"]
 
 # Kernels that run two waves per SIMD keep MFMA results in architectural VGPRs (the softmax / dS
 # arithmetic consumes them directly); the dK/dV kernel needs the accumulation VGPRs for its 128

@@ -312,3 +312,50 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
                                 n_slots, chunk_cap, initial_state, state_out, o, workspace, (hipStream_t)stream),
                     "tree_gdn_fwd");
 }
+
+extern "C" size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t hk, int32_t hv) {
+  tt::clear_error();
+  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || hk <= 0 || hv <= 0) return 0;
+  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, hk, hv);
+}
+
+extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
+                                     const void* q, const void* k, const void* v, const float* g, const float* beta,
+                                     const void* d_o, int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                                     const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                                     const int32_t* chunk_cap, const float* initial_state, const float* d_state_out,
+                                     void* dq, void* dk_out, void* dv_out, float* dg, float* dbeta, float* d_initial_state,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  tt::clear_error();
+  if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
+  if (dk != 128 || dv != 128) return fail(TT_ERR_UNSUPPORTED, "dk=%d, dv=%d: only 128 x 128 states are built", dk, dv);
+  if (hk <= 0 || hv <= 0 || hv % hk != 0 || hv > 65535) return fail(TT_ERR_SHAPE, "hv=%d must be a positive multiple of hk=%d", hv, hk);
+  if (!(scale > 0.f) || !std::isfinite(scale)) return fail(TT_ERR_SHAPE, "scale must be positive and finite");
+  if (n_chunks < 0 || n_slots < 0 || n_chunks > 65535 * 16) return fail(TT_ERR_SHAPE, "n_chunks=%d, n_slots=%d out of range", n_chunks, n_slots);
+  if ((n_tokens > 0) != (n_chunks > 0)) return fail(TT_ERR_SHAPE, "n_tokens=%lld with %d chunks", (long long)n_tokens, n_chunks);
+  if (n_chunks > 0 && (!q || !k || !v || !g || !beta || !d_o || !dq || !dk_out || !dv_out || !dg || !dbeta || !chunk_tok0 || !chunk_len ||
+                       !chunk_src || !chunk_dst))
+    return fail(TT_ERR_NULL, "a tensor or plan pointer is NULL");
+  if (d_state_out && !chunk_cap) return fail(TT_ERR_NULL, "d_state_out needs chunk_cap");
+  const void* ptrs[] = {q, k, v, d_o, dq, dk_out, dv_out, initial_state, d_state_out, d_initial_state};
+  for (const void* p : ptrs)
+    if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
+  if (n_tokens > 0) {
+    const void* outs[] = {dq, dk_out, dv_out, dg, dbeta, d_initial_state};
+    const void* ins[] = {q, k, v, g, beta, d_o, initial_state, d_state_out};
+    for (const void* o : outs)
+      for (const void* i : ins)
+        if (o && o == i) return fail(TT_ERR_SHAPE, "an output aliases an input");
+  }
+  const size_t need = tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, hk, hv);
+  if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
+    return fail(TT_ERR_WORKSPACE, "gdn backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+  tt::GdnBwdArgs a{};
+  a.n_tokens = n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.n_slots = n_slots; a.scale = scale;
+  a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.g = g; a.beta = beta;
+  a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len; a.chunk_src = chunk_src; a.chunk_dst = chunk_dst; a.chunk_cap = chunk_cap;
+  a.initial_state = initial_state; a.d_state_out = d_state_out;
+  a.dq = dq; a.dk = dk_out; a.dv = dv_out; a.dg = dg; a.dbeta = dbeta; a.d_initial_state = d_initial_state;
+  a.workspace = workspace;
+  return hip_result(tt::gdn_bwd(a, (hipStream_t)stream), "tree_gdn_bwd");
+}

@@ -48,6 +48,7 @@ struct GdnArgs {
                                      // (K exp(gamma_last - gamma))^T [128][64], scale tril((Q K^T) exp(gamma_i - gamma_j)) [64][64]
   float* glast;                      // exp(gamma_last)
   float* slots;                      // [n_slots][hv][128][128] saved node-end states
+  GdnChunkOps f32;                   // prepare kernel in its fp32-output form (backward pass) only
 };
 
 // The operands of one (head, chunk) form one contiguous record, records ordered head-major: a scan
@@ -57,6 +58,9 @@ constexpr size_t REC_WN = 0, REC_UT = GC * GD, REC_QG = 2 * GC * GD, REC_KDT = 3
 constexpr size_t REC_ELEMS = 4 * GC * GD + GC * GC;      // bf16 elements per record (72 KB)
 __device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)h * a.n_chunks + chunk; }
 
+// F32OUT: the same quantities unrounded, in the layouts the backward kernels read (GdnChunkOps), instead of
+// the forward scan's bf16 records.
+template <bool F32OUT>
 __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(16))) __bf16 ksm[GC][GROW];
   __shared__ __attribute__((aligned(16))) __bf16 qsm[GC][GROW];
@@ -78,10 +82,13 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   if (tid == 0) {
     float run = 0.f;
     for (int i = 0; i < GC; i++) { run += gam[i]; gam[i] = run; }
-    a.glast[op] = __expf(run);
+    if constexpr (!F32OUT) a.glast[op] = __expf(run);
   }
   __syncthreads();
   const float g_last = gam[GC - 1];
+  if constexpr (F32OUT) {
+    if (tid < GC) a.f32.gam[op * GC + tid] = gam[tid];
+  }
 
   // K and Q rows into LDS (zero rows past the chunk's length); Qg written on the way
   for (int piece = tid; piece < GC * (GD / 8); piece += G_THREADS) {
@@ -95,7 +102,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     }
     *(bf16x8*)&ksm[i][c8] = kv;
     *(bf16x8*)&qsm[i][c8] = qv;
-    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
+    if constexpr (!F32OUT) *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
   }
   __syncthreads();
 
@@ -119,8 +126,14 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       for (int r = 0; r < 16; r++) {
         const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
         const float dec = j <= i ? __expf(gam[i] - gam[j]) : 0.f;
-        am[i][j] = j < i ? bet[i] * kk[r] * dec : 0.f;
-        pout[i * GC + j] = (__bf16)(a.scale * qk[r] * dec);
+        const float a0 = j < i ? kk[r] * dec : 0.f;
+        am[i][j] = bet[i] * a0;
+        if constexpr (F32OUT) {
+          a.f32.a0[op * (GC * GC) + i * GC + j] = a0;
+          a.f32.p[op * (GC * GC) + i * GC + j] = a.scale * qk[r] * dec;
+        } else {
+          pout[i * GC + j] = (__bf16)(a.scale * qk[r] * dec);
+        }
       }
     } else {
       const int j = jb * 32 + c;
@@ -129,7 +142,12 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       for (int r = 0; r < 16; r++) {
         const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
         am[i][j] = 0.f;
-        pout[i * GC + j] = (__bf16)0.f;
+        if constexpr (F32OUT) {
+          a.f32.a0[op * (GC * GC) + i * GC + j] = 0.f;
+          a.f32.p[op * (GC * GC) + i * GC + j] = 0.f;
+        } else {
+          pout[i * GC + j] = (__bf16)0.f;
+        }
       }
     }
   }
@@ -140,7 +158,13 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     float f[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
-    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    if constexpr (F32OUT) {
+      float* dst = a.f32.kdt + op * (GD * GC) + d * GC + i0;
+      *(float4*)dst = make_float4(f[0], f[1], f[2], f[3]);
+      *(float4*)(dst + 4) = make_float4(f[4], f[5], f[6], f[7]);
+    } else {
+      *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    }
   }
   __syncthreads();
 
@@ -177,7 +201,17 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         x[i] = rhs;
       }
     }
-    if (c < GD) {
+    if constexpr (F32OUT) {
+      // U and W row-major (lanes = consecutive columns), W also transposed
+      float* rowmajor = (c < GD ? a.f32.u : a.f32.w) + op * (GC * GD) + (c & (GD - 1));
+#pragma unroll
+      for (int i = 0; i < GC; i++) rowmajor[i * GD] = x[i];
+      if (c >= GD) {
+        float* dst = a.f32.wt + op * (GD * GC) + (c - GD) * GC;
+#pragma unroll
+        for (int i0 = 0; i0 < GC; i0 += 4) *(float4*)(dst + i0) = make_float4(x[i0], x[i0 + 1], x[i0 + 2], x[i0 + 3]);
+      }
+    } else if (c < GD) {
       __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + c * GC;
 #pragma unroll
       for (int i0 = 0; i0 < GC; i0 += 8)
@@ -429,13 +463,27 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
   a.slots = (float*)p;
   {
     KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
-    gdn_prepare_kernel<<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
+    gdn_prepare_kernel<false><<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {
     KernelTimer t(TT_KERNEL_GDN_SCAN, st);
     gdn_scan_kernel<<<dim3((GD / G_DVB) * hv), G_THREADS, 0, st>>>(a);
   }
+  return hipGetLastError();
+}
+
+hipError_t gdn_prepare_f32(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
+                           const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                           const GdnChunkOps& out, hipStream_t st) {
+  if (n_chunks == 0) return hipSuccess;
+  GdnArgs a{};
+  a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
+  a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v; a.g = g; a.beta = beta;
+  a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len;
+  a.f32 = out;
+  KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
+  gdn_prepare_kernel<true><<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
   return hipGetLastError();
 }
 

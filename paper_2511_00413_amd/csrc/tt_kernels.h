@@ -83,4 +83,37 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
                    void* o, void* workspace, hipStream_t st);
 size_t gdn_workspace(int n_chunks, int n_slots, int hv);
 
+// The per-chunk quantities of the gated delta rule that do not depend on the state, in fp32, for the
+// backward pass; every array is indexed by (head * n_chunks + chunk).
+struct GdnChunkOps {
+  float* gam;      // [64]       running sum of the log-decays inside the chunk
+  float* a0;       // [64][64]   strictly-lower (k_i . k_j) exp(gamma_i - gamma_j)   (A without beta_i)
+  float* p;        // [64][64]   scale tril((q_i . k_j) exp(gamma_i - gamma_j))
+  float* u;        // [64][128]  (I + A)^-1 (beta V)
+  float* w;        // [64][128]  (I + A)^-1 (beta exp(gamma) K)
+  float* wt;       // [128][64]  W transposed
+  float* kdt;      // [128][64]  (K exp(gamma_last - gamma)) transposed
+};
+hipError_t gdn_prepare_f32(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
+                           const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
+                           const GdnChunkOps& out, hipStream_t st);
+
+// backward of the gated delta rule (tt_gdn_bwd.hip)
+struct GdnBwdArgs {
+  int64_t n_tokens;
+  int hk, hv, n_chunks, n_slots;
+  float scale;
+  const void *q, *k, *v, *d_o;       // bf16
+  const float *g, *beta;
+  const int32_t *chunk_tok0, *chunk_len, *chunk_src, *chunk_dst, *chunk_cap;
+  const float* initial_state;        // nullptr or [hv][128][128]
+  const float* d_state_out;          // nullptr or [n_capture][hv][128][128]: upstream gradient of the captured states
+  void *dq, *dk, *dv;                // bf16
+  float *dg, *dbeta;                 // [N][hv]
+  float* d_initial_state;            // nullptr or [hv][128][128], overwritten
+  void* workspace;
+};
+hipError_t gdn_bwd(const GdnBwdArgs& a, hipStream_t st);
+size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int hk, int hv);
+
 }  // namespace tt

@@ -24,6 +24,7 @@ def test_exports_every_declared_symbol():
     assert {"tt_tree_build_meta", "tt_tree_attn_fwd", "tt_tree_attn_bwd", "tt_tree_weighted_logprob",
             "tt_tree_weighted_logprob_bwd", "tt_tree_rope", "tt_tree_partition_sizes", "tt_tree_partition_plan", "tt_tree_path_weights", "tt_tree_conv_fwd", "tt_tree_conv_bwd", "tt_tree_conv_plan", "tt_tree_conv_plan_sizes",
             "tt_tree_conv_bwd_workspace", "tt_tree_gdn_plan_sizes", "tt_tree_gdn_plan", "tt_tree_gdn_workspace", "tt_tree_gdn_fwd",
+            "tt_tree_gdn_bwd_workspace", "tt_tree_gdn_bwd",
             "tt_tree_attn_partitioned_workspace", "tt_tree_attn_partitioned_fwd", "tt_tree_attn_partitioned_bwd",
             "tt_tree_attn_workspace", "tt_tree_meta_sizes", "tt_last_error", "tt_version"} <= set(names)
     for n in names:
