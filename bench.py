@@ -46,6 +46,7 @@ def parse_args():
     ap.add_argument("--no-partitioned", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-gdn", action="store_true")
+    ap.add_argument("--no-gdn-bwd", action="store_true")
     ap.add_argument("--gdn-heads", type=int, default=32, help="value heads of the gated-delta-rule leg (key heads = half)")
     ap.add_argument("--conv-channels", type=int, default=8192,
                     help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
@@ -394,7 +395,36 @@ def main():
                "chunk_tflops": round(chunk_flop * gplan.n_chunks * ghv / ((p_ms + s_ms) * 1e-3) / 1e12, 2),
                "us_per_chunk_step": round(s_ms * 1e3 / max(gplan.n_chunks, 1), 3),
                "workspace_mb": round(gws.numel() / 1e6, 1)}
-        del gq, gk, gv, go, gws
+        del gws
+        if not args.no_gdn_bwd:
+            gdo = torch.randn((N, ghv, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+            bws = torch.empty(T.binding._lib().tt_tree_gdn_bwd_workspace(N, gplan.n_chunks, gplan.n_slots, ghk, ghv), dtype=torch.uint8,
+                              device=dev)
+            n_it = 3
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            for it in range(1 + n_it):
+                if it == 1:
+                    torch.cuda.synchronize()
+                    T.kernel_timing_enable(True)
+                    ev[0].record()
+                T.tree_gdn_bwd(gq, gk, gv, gg, gb, gdo, gplan, workspace=bws)
+            ev[1].record()
+            ev[1].synchronize()
+            bt = T.kernel_timing_read()
+            T.kernel_timing_enable(False)
+            # fp32 multiply-adds per chunk and head of the backward as written (recomputed forward walk included)
+            bwd_flop = 2.0 * (64 * 128 * 128 * 2            # forward walk: W S0, Kd^T Vn
+                              + 64 * 64 * 128 + 64 * 128 * 128 * 3   # reverse walk: P^T dO, Kd dS1, Qg^T dO, W^T dVn
+                              + 64 * 128 * 128 * 3 + 64 * 64 * 256 + 64 * 64 * 128   # finish: dW, dQg, dKd, dA, dP
+                              + 64 * 64 * 128 * 3 + 64 * 64 * 128)   # products with dP and dA, the two triangular solves
+            b_ms = ev[0].elapsed_time(ev[1]) / n_it
+            gdn.update({"ms_bwd": round(b_ms, 4),
+                        "ms_bwd_kernels": {"prepare_f32": round(bt["gdn_prepare"][0] / n_it, 4), "forward_walk": round(bt["gdn_bwd_fscan"][0] / n_it, 4),
+                                           "reverse_walk": round(bt["gdn_bwd_rscan"][0] / n_it, 4), "finish": round(bt["gdn_bwd_finish"][0] / n_it, 4)},
+                        "bwd_fp32_tflops": round(bwd_flop * gplan.n_chunks * ghv / (b_ms * 1e-3) / 1e12, 2),
+                        "bwd_workspace_mb": round(bws.numel() / 1e6, 1)})
+            del gdo, bws
+        del gq, gk, gv, go
 
     # ---------------- CPU oracle on a bounded sample (context only) ----------------
     cpu = None

@@ -25,6 +25,8 @@ def test_empty_tree_everywhere():
     gb = torch.zeros((0, 1), dtype=torch.float32, device="cuda")
     o = T.tree_gdn_fwd(q, q, q, gb, gb, T.tree_gdn_plan([], []))
     assert o.shape == (0, 1, 128)
+    grads = T.tree_gdn_bwd(q, q, q, gb, gb, q, T.tree_gdn_plan([], []))
+    assert grads[0].shape == (0, 1, 128) and grads[3].shape == (0, 1)
     # partition driver: no tokens
     plan = T.tree_partition_plan([], [], 8).to_device()
     qa = torch.zeros((0, 2, 128), dtype=torch.bfloat16, device="cuda")
@@ -54,6 +56,12 @@ def test_zero_length_nodes_only_and_single_token():
     o = T.tree_gdn_fwd(k, k, v, 0 * one, one, T.tree_gdn_plan(parent, seg), scale=1.0)
     torch.cuda.synchronize()
     assert torch.allclose(o.float(), v.float(), rtol=1e-2, atol=1e-3)      # S = k v^T, o = (q.k) v
+    d_o = torch.randn((1, 1, 128), device="cuda").bfloat16()
+    dq, dk, dv, dg, dbeta = T.tree_gdn_bwd(k, k, v, 0 * one, one, d_o, T.tree_gdn_plan(parent, seg), scale=1.0)
+    torch.cuda.synchronize()
+    assert torch.allclose(dv.float(), d_o.float(), rtol=1e-2, atol=1e-3)   # o = beta (q.k) v  ->  dv = d_o
+    assert torch.allclose(dbeta, (d_o.float() * v.float()).sum().reshape(1, 1), rtol=1e-3, atol=1e-3)
+    assert torch.all(dg == 0)                                              # no earlier state to decay
     plan = T.tree_partition_plan(parent, seg, 1).to_device()
     qa = torch.randn((1, 2, 128), device="cuda").bfloat16()
     ka = torch.randn((1, 1, 128), device="cuda").bfloat16()

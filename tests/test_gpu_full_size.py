@@ -248,3 +248,33 @@ def test_cfg2_gdn_sampled_heads():
         e = rel_l2(o[:, h], want[:, 0])
         print(f"   head {h}: rel-L2 {e:.2e}", flush=True)
         assert e <= 2e-2, (h, e)
+
+
+def test_cfg2_gdn_backward_one_key_head():
+    """bench.py's tree_gdn leg, backward: N = 16406, 16 key / 32 value heads; the reverse recurrence is run for
+    the two value heads of one key head (dq and dk are sums over them)."""
+    from oracle import ssm as S
+    t = W.tree_config(2)
+    meta = T.tree_build_meta(t.parent, t.seg_len, t.trained)
+    n, hk, hv = meta.n_tokens, 16, 32
+    g_ = torch.Generator().manual_seed(23)
+    q = torch.randn((n, hk, 128), generator=g_); k = torch.randn((n, hk, 128), generator=g_)
+    q = (q / q.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    k = (k / k.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    v = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16)
+    gl = -(torch.rand((n, hv), generator=g_) * 0.2 + 0.005)
+    beta = torch.rand((n, hv), generator=g_) * 0.8 + 0.1
+    d_o = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16)
+    plan = T.tree_gdn_plan(t.parent, t.seg_len)
+    print(f"[case] cfg2 gdn backward full size: {plan.n_chunks} chunks, {plan.n_slots} saved states", flush=True)
+    got = T.tree_gdn_bwd(q.cuda(), k.cuda(), v.cuda(), gl.cuda(), beta.cuda(), d_o.cuda(), plan)
+    torch.cuda.synchronize()
+    kh = 5
+    hs = slice(2 * kh, 2 * kh + 2)
+    want = S.gdn_tree_bwd(q[:, kh:kh + 1].float().numpy(), k[:, kh:kh + 1].float().numpy(), v[:, hs].float().numpy(),
+                          gl[:, hs].numpy(), beta[:, hs].numpy(), meta.tok_pred, d_o[:, hs].float().numpy())
+    sel = (got[0][:, kh:kh + 1], got[1][:, kh:kh + 1], got[2][:, hs], got[3][:, hs], got[4][:, hs])
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), sel, want, (2e-2, 2e-2, 2e-2, 1e-3, 1e-3)):
+        e = rel_l2(a.float().cpu().numpy(), b)
+        print(f"   {name}: rel-L2 {e:.2e}", flush=True)
+        assert e <= tol, (name, e)

@@ -62,6 +62,59 @@ def test_gdn_state_gateway(seed, cap):
     assert e <= 2e-2, e
 
 
+@pytest.mark.parametrize("seed,cap", [(0, 400), (1, 250)])
+def test_gdn_state_gateway_backward(seed, cap):
+    """Backward through the gateway: partitions run in reverse, a child partition returns the gradient of the
+    state it started from, and the parent partition takes the sum over the children at each cut node as the
+    upstream gradient of that captured state.  Stitched gradients must equal the whole-tree oracle."""
+    tree = W.random_tree(990 + seed, n_nodes=14, lo=10, hi=180)
+    whole = M.dfs_meta(tree.parent, tree.seg_len)
+    n, hk, hv = whole["n_tokens"], 1, 2
+    g_ = torch.Generator().manual_seed(seed)
+    q = torch.randn((n, hk, 128), generator=g_); k = torch.randn((n, hk, 128), generator=g_)
+    q = (q / q.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    k = (k / k.norm(dim=-1, keepdim=True)).to(torch.bfloat16)
+    v = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16)
+    g = -(torch.rand((n, hv), generator=g_) * 0.2 + 0.005)
+    beta = torch.rand((n, hv), generator=g_) * 0.8 + 0.1
+    d_o = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16)
+    want = S.gdn_tree_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.numpy(), beta.numpy(), whole["tok_pred"],
+                          d_o.float().numpy())
+    plan, parts = _partitions(tree, cap)
+    assert plan.n_parts >= 3
+    print(f"[case] gdn state gateway backward seed={seed} cap={cap}: {plan.n_parts} partitions, N={n}", flush=True)
+    cut_state, runs = {}, []
+    for p, part in enumerate(parts):                 # forward: capture the cut nodes' end states
+        local = {nid: i for i, nid in enumerate(part)}
+        lparent = [-1 if nid == part[0] else local[int(tree.parent[nid])] for nid in part]
+        lseg = [int(tree.seg_len[nid]) for nid in part]
+        own = torch.from_numpy(plan.own_tok[plan.part_tok_off[p]:plan.part_tok_off[p + 1]].astype(np.int64))
+        cuts = sorted({int(tree.parent[c]) for c in range(len(tree.parent))
+                       if int(tree.parent[c]) in local and plan.part_of_node[c] != p})
+        cn = int(plan.part_cut_node[p])
+        gplan = T.tree_gdn_plan(lparent, lseg, capture_nodes=[local[c] for c in cuts])
+        dev = [t[own].cuda() for t in (q, k, v, g, beta)]
+        _, states = T.tree_gdn_fwd(*dev, gplan, initial_state=cut_state[cn] if cn >= 0 else None, return_states=True)
+        for i, c in enumerate(cuts):
+            cut_state[c] = states[i].contiguous()
+        runs.append((own, cuts, cn, gplan, dev))
+    got = [np.zeros((n, hk, 128)), np.zeros((n, hk, 128)), np.zeros((n, hv, 128)), np.zeros((n, hv)), np.zeros((n, hv))]
+    d_cut = {}                                       # cut node -> summed gradient of its end state
+    for own, cuts, cn, gplan, dev in reversed(runs):  # children before parents
+        up = torch.stack([d_cut[c] for c in cuts]) if cuts else None
+        out = T.tree_gdn_bwd(*dev, d_o[own].cuda(), gplan, initial_state=cut_state[cn] if cn >= 0 else None, d_state_out=up,
+                             want_d_initial_state=cn >= 0)
+        torch.cuda.synchronize()
+        for dstt, t in zip(got, out[:5]):
+            dstt[own.numpy()] = t.float().cpu().numpy()
+        if cn >= 0:
+            d_cut[cn] = d_cut[cn] + out[5] if cn in d_cut else out[5]
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (2e-2, 2e-2, 2e-2, 1e-2, 1e-2)):
+        e = rel_l2(a, b)
+        print(f"   {name}: rel-L2 {e:.2e}", flush=True)
+        assert e <= tol, (name, e)
+
+
 @pytest.mark.parametrize("seed,cap,K", [(0, 120, 4), (1, 60, 3)])
 def test_conv_context_gateway(seed, cap, K):
     """The convolution needs no extra entry point: the parent's last K-1 effective tokens become a context
