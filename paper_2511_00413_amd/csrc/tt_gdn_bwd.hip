@@ -62,122 +62,223 @@ __device__ __forceinline__ void scan_ids(int id, int hv, int& h, int& dvb) {
 __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
 __device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
 
+// fp32 matrix instruction: D (32 x 32) += A (32 x 2) B (2 x 32).  Lane l = 32 hf + c supplies A[row c][k = hf] and
+// B[k = hf][column c] and holds D[(r / 4) * 8 + 4 hf + r % 4][c] in register r.
+__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 acc) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
+__device__ __forceinline__ int tile_row(int r, int hf) { return (r >> 2) * 8 + 4 * hf + (r & 3); }
+
+// acc += sign A B over LK consecutive k (LK even).  `at` points at element (k = 0, this lane's row) of A stored
+// [k][row] with pitch pa, `bm` at element (k = 0, this lane's column) of B stored [k][column] with pitch pb.  The
+// instruction's two k-slots take k = s and k = LK / 2 + s.
+template <int LK, bool NEG = false>
+__device__ __forceinline__ void mfma_range(const float* at, int pa, const float* bm, int pb, int hf, f32x16& acc) {
+#pragma unroll 8
+  for (int s = 0; s < LK / 2; s++) {
+    const int k = hf * (LK / 2) + s;
+    const float av = at[k * pa];
+    acc = mfma_f32(NEG ? -av : av, bm[k * pb], acc);
+  }
+}
+
+// Barrier that waits for this wave's LDS traffic only: global stores (nobody in the workgroup reads them back)
+// and the prefetch loads of the next chunk stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// The walks are software-pipelined: the operands of chunk i + 1 are fetched into registers while chunk i is
+// computed and go to LDS at the top of the next step; the chunk's scalars are fetched per lane one step ahead as
+// well (`z` is a per-lane zero the compiler cannot see through, which keeps them in vector registers until they
+// are needed instead of waiting for them right behind the load).
+struct WalkMeta {
+  int tok0, len, src, dst, cap;
+};
+__device__ __forceinline__ WalkMeta load_walk_meta(const GdnBwdArgs& b, int chunk, int z, bool want_cap) {
+  WalkMeta m;
+  m.tok0 = b.chunk_tok0[chunk + z]; m.len = b.chunk_len[chunk + z]; m.src = b.chunk_src[chunk + z]; m.dst = b.chunk_dst[chunk + z];
+  m.cap = want_cap ? b.chunk_cap[chunk + z] : -1;
+  return m;
+}
+__device__ __forceinline__ WalkMeta uniform(const WalkMeta& m) {
+  WalkMeta u;
+  u.tok0 = __builtin_amdgcn_readfirstlane(m.tok0); u.len = __builtin_amdgcn_readfirstlane(m.len);
+  u.src = __builtin_amdgcn_readfirstlane(m.src); u.dst = __builtin_amdgcn_readfirstlane(m.dst);
+  u.cap = __builtin_amdgcn_readfirstlane(m.cap);
+  return u;
+}
+
 // ---- forward walk ------------------------------------------------------------------------------------
-// Thread (ty = tid / 8, tx = tid % 8) owns rows 4 ty .. +3, columns 4 tx .. +3 of the 128 x 32 state slice
-// and rows 2 ty .. +1, columns 4 tx .. +3 of the 64 x 32 slice of Vn.
+// Wave w owns rows 32 w .. 32 w + 31 of the 128 x 32 state slice (accumulator layout).  The two 32 x 32 blocks of
+// Vn are each computed by two waves, one per half of the contraction over the key dimension.
+struct FwdStage {                 // one chunk's operands on their way to LDS
+  f32x4 wt[(GD * GC / 4) / BT];      // native vector types: they stay in registers
+  bf16x8 k[(GC * GD / 8) / BT];
+  float gam[(GC * GD / 8) / BT];
+  f32x4 u[(GC * DVB / 4) / BT];
+  float glast;
+};
+__device__ __forceinline__ void fwd_fetch(const KArgs& a, int chunk, int h, int dvb, const __bf16* kb, size_t krow, int tid, int z,
+                                          FwdStage& st) {
+  const size_t op = (size_t)h * a.b.n_chunks + chunk;
+  const int tok0 = a.b.chunk_tok0[chunk + z], len = a.b.chunk_len[chunk + z];
+  const float* gam = a.w.ops.gam + op * GC;
+  const f32x4* wsrc = (const f32x4*)(a.w.ops.wt + op * (GD * GC));
+#pragma unroll
+  for (int p = 0; p < (GD * GC / 4) / BT; p++) st.wt[p] = wsrc[tid + p * BT];
+#pragma unroll
+  for (int p = 0; p < (GC * GD / 8) / BT; p++) {
+    const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
+    st.k[p] = *(const bf16x8*)(kb + (size_t)(tok0 + min(i, len - 1)) * krow + c8);
+    st.gam[p] = i < len ? gam[i] : 1e30f;                  // exp(glast - 1e30) = 0: rows past the chunk's length
+  }
+  const float* u = a.w.ops.u + op * (GC * GD) + dvb * DVB;
+#pragma unroll
+  for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
+    const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
+    st.u[p] = *(const f32x4*)(u + (size_t)i * GD + c4);
+  }
+  st.glast = gam[GC - 1 + z];
+}
+
 __global__ __launch_bounds__(BT, 1) void gdn_bwd_fscan_kernel(KArgs a) {
   __shared__ __attribute__((aligned(16))) float wt[GD * GC];      // W^T [d][i]
   __shared__ __attribute__((aligned(16))) float kd[GC * GD];      // Kd  [i][d]
   __shared__ __attribute__((aligned(16))) float us[GC * DVB];     // U   [i][c]
   __shared__ __attribute__((aligned(16))) float ss[GD * DVB];     // S0  [d][c]
   __shared__ __attribute__((aligned(16))) float vs[GC * DVB];     // Vn  [i][c]
+  __shared__ float half2nd[2][32 * DVB];                          // W S0 over the second half of the key dims
   int h, dvb;
   scan_ids(blockIdx.x, a.b.hv, h, dvb);
-  const int tid = threadIdx.x & (BT - 1), tx = tid & 7, ty = tid >> 3;
+  const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), ib = w & 1, kq = w >> 1;
   const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
   const __bf16* kb = (const __bf16*)a.b.k + (size_t)kh * GD;
   const size_t krow = (size_t)a.b.hk * GD;
-  float s[4][4];
-#pragma unroll
-  for (int r = 0; r < 4; r++)
-#pragma unroll
-    for (int c = 0; c < 4; c++) s[r][c] = 0.f;
+  const size_t col = (size_t)dvb * DVB + c;                   // this lane's column inside a [128][128] state
+  f32x16 s = zero16();
+  int z = 0;
+  asm volatile("" : "+v"(z));
 
+  FwdStage st;
+  fwd_fetch(a, 0, h, dvb, kb, krow, tid, z, st);
+  WalkMeta next = load_walk_meta(a.b, 0, z, false);
   for (int chunk = 0; chunk < nc; chunk++) {
-    const int tok0 = a.b.chunk_tok0[chunk], len = a.b.chunk_len[chunk], src = a.b.chunk_src[chunk], dst = a.b.chunk_dst[chunk];
+    const WalkMeta m = uniform(next);
     const size_t op = (size_t)h * nc + chunk;
-    const size_t tile = (size_t)(4 * ty) * GD + dvb * DVB + 4 * tx;      // this thread's tile inside a [128][128] state
-    if (src != -2) {
-      const float* sp = src >= 0 ? a.w.slots + ((size_t)src * hv + h) * (GD * GD) : a.b.initial_state ? a.b.initial_state + (size_t)h * (GD * GD) : nullptr;
+    if (m.src != -2) {
+      const float* sp = m.src >= 0 ? a.w.slots + ((size_t)m.src * hv + h) * (GD * GD) : a.b.initial_state ? a.b.initial_state + (size_t)h * (GD * GD) : nullptr;
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const float4 v = sp ? ld4(sp + tile + (size_t)r * GD) : make_float4(0.f, 0.f, 0.f, 0.f);
-        s[r][0] = v.x; s[r][1] = v.y; s[r][2] = v.z; s[r][3] = v.w;
+      for (int r = 0; r < 16; r++) s[r] = sp ? sp[(size_t)(32 * w + tile_row(r, hf)) * GD + col] : 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; r++) ss[(32 * w + tile_row(r, hf)) * DVB + c] = s[r];
+    const float glast = st.glast;
+#pragma unroll
+    for (int p = 0; p < (GD * GC / 4) / BT; p++) ((f32x4*)wt)[tid + p * BT] = st.wt[p];
+#pragma unroll
+    for (int p = 0; p < (GC * GD / 8) / BT; p++) {
+      const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
+      const float f = __expf(glast - st.gam[p]);
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (float)st.k[p][e] * f;
+      *(float4*)&kd[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
+      *(float4*)&kd[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
+    }
+#pragma unroll
+    for (int p = 0; p < (GC * DVB / 4) / BT; p++) ((f32x4*)us)[tid + p * BT] = st.u[p];
+    lds_barrier();
+
+    // next chunk's operands and scalars on their way (the last step re-fetches its own: no branch around loads)
+    const int nxt = min(chunk + 1, nc - 1);
+    fwd_fetch(a, nxt, h, dvb, kb, krow, tid, z, st);
+    next = load_walk_meta(a.b, nxt, z, false);
+    {   // the entering state, for the finish kernel: 16-byte stores from the LDS copy
+      float* s0 = a.w.s0 + op * (GD * GD) + dvb * DVB;
+#pragma unroll
+      for (int p = 0; p < (GD * DVB / 4) / BT; p++) {
+        const int piece = tid + p * BT, d = piece >> 3, c4 = (piece & 7) * 4;
+        *(float4*)(s0 + (size_t)d * GD + c4) = *(const float4*)&ss[d * DVB + c4];
       }
     }
-    float* s0 = a.w.s0 + op * (GD * GD);
+
+    // Vn = U - W S0: rows 32 ib .., key dims 64 kq .. 64 kq + 63
+    f32x16 part = zero16();
+    mfma_range<64>(wt + (64 * kq) * GC + 32 * ib + c, GC, ss + (64 * kq) * DVB + c, DVB, hf, part);
+    if (kq == 1) {
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      st4(&ss[(4 * ty + r) * DVB + 4 * tx], s[r]);
-      st4(s0 + tile + (size_t)r * GD, s[r]);
+      for (int r = 0; r < 16; r++) half2nd[ib][tile_row(r, hf) * DVB + c] = part[r];
     }
-    const float* gam = a.w.ops.gam + op * GC;
-    const float glast = gam[GC - 1];
+    lds_barrier();
+    if (kq == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * ib + tile_row(r, hf);
+        vs[i * DVB + c] = us[i * DVB + c] - (part[r] + half2nd[ib][tile_row(r, hf) * DVB + c]);
+      }
+    }
+    lds_barrier();
     {
-      const float4* wsrc = (const float4*)(a.w.ops.wt + op * (GD * GC));
-#pragma unroll
-      for (int p = 0; p < (GD * GC / 4) / BT; p++) ((float4*)wt)[tid + p * BT] = wsrc[tid + p * BT];
-#pragma unroll
-      for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-        const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-        const bf16x8 kv = *(const bf16x8*)(kb + (size_t)(tok0 + min(i, len - 1)) * krow + c8);
-        const float f = i < len ? __expf(glast - gam[i]) : 0.f;
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = (float)kv[e] * f;
-        *(float4*)&kd[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
-        *(float4*)&kd[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-      }
-      const float* u = a.w.ops.u + op * (GC * GD) + dvb * DVB;
+      float* vout = a.w.vn + op * (GC * GD) + dvb * DVB;
 #pragma unroll
       for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
         const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
-        *(float4*)&us[i * DVB + c4] = ld4(u + (size_t)i * GD + c4);
+        *(float4*)(vout + (size_t)i * GD + c4) = *(const float4*)&vs[i * DVB + c4];
       }
     }
-    __syncthreads();
-
-    // Vn = U - W S0
-    float vn[2][4];
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-      const float4 v = *(const float4*)&us[(2 * ty + r) * DVB + 4 * tx];
-      vn[r][0] = v.x; vn[r][1] = v.y; vn[r][2] = v.z; vn[r][3] = v.w;
-    }
-#pragma unroll 8
-    for (int k = 0; k < GD; k++) {
-      const float2 av = *(const float2*)&wt[k * GC + 2 * ty];
-      const float4 bv = *(const float4*)&ss[k * DVB + 4 * tx];
-      const float ar[2] = {av.x, av.y}, bc[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-      for (int r = 0; r < 2; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) vn[r][c] = fmaf(-ar[r], bc[c], vn[r][c]);
-    }
-    float* vout = a.w.vn + op * (GC * GD) + dvb * DVB + 4 * tx;
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-      st4(&vs[(2 * ty + r) * DVB + 4 * tx], vn[r]);
-      st4(vout + (size_t)(2 * ty + r) * GD, vn[r]);
-    }
-    __syncthreads();
 
     // S1 = EL S0 + Kd^T Vn
     const float el_last = __expf(glast);
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int r = 0; r < 16; r++) s[r] *= el_last;
+    mfma_range<GC>(kd + 32 * w + c, GD, vs + c, DVB, hf, s);
+    if (m.dst >= 0) {
+      float* sp = a.w.slots + ((size_t)m.dst * hv + h) * (GD * GD) + col;
 #pragma unroll
-      for (int c = 0; c < 4; c++) s[r][c] *= el_last;
-#pragma unroll 8
-    for (int i = 0; i < GC; i++) {
-      const float4 av = *(const float4*)&kd[i * GD + 4 * ty];
-      const float4 bv = *(const float4*)&vs[i * DVB + 4 * tx];
-      const float ar[4] = {av.x, av.y, av.z, av.w}, bc[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-      for (int r = 0; r < 4; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) s[r][c] = fmaf(ar[r], bc[c], s[r][c]);
+      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + tile_row(r, hf)) * GD] = s[r];
     }
-    if (dst >= 0) {
-      float* sp = a.w.slots + ((size_t)dst * hv + h) * (GD * GD) + tile;
-#pragma unroll
-      for (int r = 0; r < 4; r++) st4(sp + (size_t)r * GD, s[r]);
-    }
-    __syncthreads();       // the LDS arrays are rewritten by the next chunk
+    lds_barrier();         // the LDS arrays are rewritten by the next chunk
   }
 }
 
 // ---- reverse walk ------------------------------------------------------------------------------------
+struct RevStage {
+  f32x4 kdt[(GD * GC / 4) / BT], w[(GC * GD / 4) / BT], p[(GC * GC / 4) / BT];
+  bf16x8 q[(GC * GD / 8) / BT];
+  float gam[(GC * GD / 8) / BT];
+  bf16x8 d_o;
+  float glast;
+};
+__device__ __forceinline__ void rev_fetch(const KArgs& a, int chunk, int h, const __bf16* qb, size_t qrow, const __bf16* dob, size_t vrow,
+                                          int tid, int z, RevStage& st) {
+  const size_t op = (size_t)h * a.b.n_chunks + chunk;
+  const int tok0 = a.b.chunk_tok0[chunk + z], len = a.b.chunk_len[chunk + z];
+  const float* gam = a.w.ops.gam + op * GC;
+  const f32x4* ksrc = (const f32x4*)(a.w.ops.kdt + op * (GD * GC));
+  const f32x4* wsrc = (const f32x4*)(a.w.ops.w + op * (GC * GD));
+  const f32x4* psrc = (const f32x4*)(a.w.ops.p + op * (GC * GC));
+#pragma unroll
+  for (int p = 0; p < (GD * GC / 4) / BT; p++) {
+    st.kdt[p] = ksrc[tid + p * BT];
+    st.w[p] = wsrc[tid + p * BT];
+  }
+#pragma unroll
+  for (int p = 0; p < (GC * GC / 4) / BT; p++) st.p[p] = psrc[tid + p * BT];
+#pragma unroll
+  for (int p = 0; p < (GC * GD / 8) / BT; p++) {
+    const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
+    st.q[p] = *(const bf16x8*)(qb + (size_t)(tok0 + min(i, len - 1)) * qrow + c8);
+    st.gam[p] = i < len ? gam[i] : -1e30f;                 // exp(-1e30) = 0: rows past the chunk's length
+  }
+  {
+    const int i = tid >> 2, c8 = (tid & 3) * 8;            // 64 rows x 4 pieces of 8 columns
+    const bf16x8 dv = *(const bf16x8*)(dob + (size_t)(tok0 + min(i, len - 1)) * vrow + c8);
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; e++) zero[e] = (__bf16)0.f;
+    st.d_o = i < len ? dv : zero;
+  }
+  st.glast = gam[GC - 1 + z];
+}
+
 __global__ __launch_bounds__(BT, 1) void gdn_bwd_rscan_kernel(KArgs a) {
   __shared__ __attribute__((aligned(16))) float kdt[GD * GC];     // Kd^T [d][i]
   __shared__ __attribute__((aligned(16))) float qg[GC * GD];      // Qg   [i][d]
@@ -186,155 +287,129 @@ __global__ __launch_bounds__(BT, 1) void gdn_bwd_rscan_kernel(KArgs a) {
   __shared__ __attribute__((aligned(16))) float dos[GC * DVB];    // dO   [i][c]
   __shared__ __attribute__((aligned(16))) float dvs[GC * DVB];    // dVn  [i][c]
   __shared__ __attribute__((aligned(16))) float dss[GD * DVB];    // dS1  [d][c]
+  __shared__ float half2nd[2][32 * DVB];
   int h, dvb;
   scan_ids(blockIdx.x, a.b.hv, h, dvb);
-  const int tid = threadIdx.x & (BT - 1), tx = tid & 7, ty = tid >> 3;
+  const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), ib = w & 1, kq = w >> 1;
   const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
   const __bf16* qb = (const __bf16*)a.b.q + (size_t)kh * GD;
   const size_t qrow = (size_t)a.b.hk * GD;
   const __bf16* dob = (const __bf16*)a.b.d_o + (size_t)h * GD + dvb * DVB;
   const size_t vrow = (size_t)hv * GD;
-  float ds[4][4];
-#pragma unroll
-  for (int r = 0; r < 4; r++)
-#pragma unroll
-    for (int c = 0; c < 4; c++) ds[r][c] = 0.f;
+  const size_t col = (size_t)dvb * DVB + c;
+  const bool want_cap = a.b.chunk_cap && a.b.d_state_out;
+  f32x16 ds = zero16();
+  int z = 0;
+  asm volatile("" : "+v"(z));
 
+  RevStage st;
+  rev_fetch(a, nc - 1, h, qb, qrow, dob, vrow, tid, z, st);
+  WalkMeta next = load_walk_meta(a.b, nc - 1, z, want_cap);
+  int later_src = -1;                       // source of the chunk after this one in DFS order (handled one step earlier)
   for (int chunk = nc - 1; chunk >= 0; chunk--) {
-    const int tok0 = a.b.chunk_tok0[chunk], len = a.b.chunk_len[chunk], src = a.b.chunk_src[chunk], dst = a.b.chunk_dst[chunk];
-    const int cap = a.b.chunk_cap && a.b.d_state_out ? a.b.chunk_cap[chunk] : -1;
-    const bool continued = chunk + 1 < nc && a.b.chunk_src[chunk + 1] == -2;   // the next chunk took this one's end state on chip
+    const WalkMeta m = uniform(next);
     const size_t op = (size_t)h * nc + chunk;
-    const size_t tile = (size_t)(4 * ty) * GD + dvb * DVB + 4 * tx;
 
     // gradient of the state leaving this chunk
-    if (!continued) {
+    if (later_src != -2) ds = zero16();     // nobody took this chunk's end state on chip
+    later_src = m.src;
+    if (m.dst >= 0) {
+      float* sg = a.w.slot_grad + ((size_t)m.dst * hv + h) * (GD * GD) + col;
 #pragma unroll
-      for (int r = 0; r < 4; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) ds[r][c] = 0.f;
-    }
-    if (dst >= 0) {
-      float* sg = a.w.slot_grad + ((size_t)dst * hv + h) * (GD * GD) + tile;
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const float4 v = ld4(sg + (size_t)r * GD);
-        ds[r][0] += v.x; ds[r][1] += v.y; ds[r][2] += v.z; ds[r][3] += v.w;
-        *(float4*)(sg + (size_t)r * GD) = make_float4(0.f, 0.f, 0.f, 0.f);     // the slot is reused by an earlier node
+      for (int r = 0; r < 16; r++) {
+        float* e = sg + (size_t)(32 * w + tile_row(r, hf)) * GD;
+        ds[r] += *e;
+        *e = 0.f;                                   // the slot is reused by an earlier node
       }
     }
-    if (cap >= 0) {
-      const float* up = a.b.d_state_out + ((size_t)cap * hv + h) * (GD * GD) + tile;
+    if (m.cap >= 0) {
+      const float* up = a.b.d_state_out + ((size_t)m.cap * hv + h) * (GD * GD) + col;
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const float4 v = ld4(up + (size_t)r * GD);
-        ds[r][0] += v.x; ds[r][1] += v.y; ds[r][2] += v.z; ds[r][3] += v.w;
-      }
+      for (int r = 0; r < 16; r++) ds[r] += up[(size_t)(32 * w + tile_row(r, hf)) * GD];
     }
-    float* ds1 = a.w.ds1 + op * (GD * GD);
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      st4(&dss[(4 * ty + r) * DVB + 4 * tx], ds[r]);
-      st4(ds1 + tile + (size_t)r * GD, ds[r]);
+    for (int r = 0; r < 16; r++) dss[(32 * w + tile_row(r, hf)) * DVB + c] = ds[r];
+    const float glast = st.glast;
+#pragma unroll
+    for (int p = 0; p < (GD * GC / 4) / BT; p++) {
+      ((f32x4*)kdt)[tid + p * BT] = st.kdt[p];
+      ((f32x4*)wr)[tid + p * BT] = st.w[p];
     }
-    const float* gam = a.w.ops.gam + op * GC;
-    const float glast = gam[GC - 1];
+#pragma unroll
+    for (int p = 0; p < (GC * GC / 4) / BT; p++) ((f32x4*)pm)[tid + p * BT] = st.p[p];
+#pragma unroll
+    for (int p = 0; p < (GC * GD / 8) / BT; p++) {
+      const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
+      const float f = a.b.scale * __expf(st.gam[p]);
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (float)st.q[p][e] * f;
+      *(float4*)&qg[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
+      *(float4*)&qg[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
+    }
     {
-      const float4* ksrc = (const float4*)(a.w.ops.kdt + op * (GD * GC));
-      const float4* wsrc = (const float4*)(a.w.ops.w + op * (GC * GD));
+      const int i = tid >> 2, c8 = (tid & 3) * 8;
+      float o[8];
 #pragma unroll
-      for (int p = 0; p < (GD * GC / 4) / BT; p++) {
-        ((float4*)kdt)[tid + p * BT] = ksrc[tid + p * BT];
-        ((float4*)wr)[tid + p * BT] = wsrc[tid + p * BT];
-      }
-      const float4* psrc = (const float4*)(a.w.ops.p + op * (GC * GC));
-#pragma unroll
-      for (int p = 0; p < (GC * GC / 4) / BT; p++) ((float4*)pm)[tid + p * BT] = psrc[tid + p * BT];
-#pragma unroll
-      for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-        const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-        const bf16x8 qv = *(const bf16x8*)(qb + (size_t)(tok0 + min(i, len - 1)) * qrow + c8);
-        const float f = i < len ? a.b.scale * __expf(gam[i]) : 0.f;
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = (float)qv[e] * f;
-        *(float4*)&qg[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
-        *(float4*)&qg[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-      }
-      {
-        const int i = tid >> 2, c8 = (tid & 3) * 8;      // 64 rows x 4 pieces of 8 columns
-        const bf16x8 dv = *(const bf16x8*)(dob + (size_t)(tok0 + min(i, len - 1)) * vrow + c8);
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; e++) o[e] = i < len ? (float)dv[e] : 0.f;
-        *(float4*)&dos[i * DVB + c8] = make_float4(o[0], o[1], o[2], o[3]);
-        *(float4*)&dos[i * DVB + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-      }
+      for (int e = 0; e < 8; e++) o[e] = (float)st.d_o[e];
+      *(float4*)&dos[i * DVB + c8] = make_float4(o[0], o[1], o[2], o[3]);
+      *(float4*)&dos[i * DVB + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
     }
-    __syncthreads();
+    lds_barrier();
 
-    // dVn = P^T dO + Kd dS1
-    float dvn[2][4];
+    const int nxt = max(chunk - 1, 0);
+    rev_fetch(a, nxt, h, qb, qrow, dob, vrow, tid, z, st);
+    next = load_walk_meta(a.b, nxt, z, want_cap);
+    {
+      float* ds1 = a.w.ds1 + op * (GD * GD) + dvb * DVB;
 #pragma unroll
-    for (int r = 0; r < 2; r++)
-#pragma unroll
-      for (int c = 0; c < 4; c++) dvn[r][c] = 0.f;
-#pragma unroll 8
-    for (int j = 0; j < GC; j++) {
-      const float2 av = *(const float2*)&pm[j * GC + 2 * ty];
-      const float4 bv = *(const float4*)&dos[j * DVB + 4 * tx];
-      const float ar[2] = {av.x, av.y}, bc[4] = {bv.x, bv.y, bv.z, bv.w};
-#pragma unroll
-      for (int r = 0; r < 2; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) dvn[r][c] = fmaf(ar[r], bc[c], dvn[r][c]);
+      for (int p = 0; p < (GD * DVB / 4) / BT; p++) {
+        const int piece = tid + p * BT, d = piece >> 3, c4 = (piece & 7) * 4;
+        *(float4*)(ds1 + (size_t)d * GD + c4) = *(const float4*)&dss[d * DVB + c4];
+      }
     }
-#pragma unroll 8
-    for (int d = 0; d < GD; d++) {
-      const float2 av = *(const float2*)&kdt[d * GC + 2 * ty];
-      const float4 bv = *(const float4*)&dss[d * DVB + 4 * tx];
-      const float ar[2] = {av.x, av.y}, bc[4] = {bv.x, bv.y, bv.z, bv.w};
+
+    // dVn = P^T dO + Kd dS1, rows 32 ib ..; the contraction (64 tokens + 128 key dims) is split in two halves of 96
+    f32x16 part = zero16();
+    if (kq == 0) {
+      mfma_range<GC>(pm + 32 * ib + c, GC, dos + c, DVB, hf, part);
+      mfma_range<32>(kdt + 32 * ib + c, GC, dss + c, DVB, hf, part);
+    } else {
+      mfma_range<96>(kdt + 32 * GC + 32 * ib + c, GC, dss + 32 * DVB + c, DVB, hf, part);
 #pragma unroll
-      for (int r = 0; r < 2; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) dvn[r][c] = fmaf(ar[r], bc[c], dvn[r][c]);
+      for (int r = 0; r < 16; r++) half2nd[ib][tile_row(r, hf) * DVB + c] = part[r];
     }
-    float* dvout = a.w.dvn + op * (GC * GD) + dvb * DVB + 4 * tx;
+    lds_barrier();
+    if (kq == 0) {
 #pragma unroll
-    for (int r = 0; r < 2; r++) {
-      st4(&dvs[(2 * ty + r) * DVB + 4 * tx], dvn[r]);
-      st4(dvout + (size_t)(2 * ty + r) * GD, dvn[r]);
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * ib + tile_row(r, hf);
+        dvs[i * DVB + c] = part[r] + half2nd[ib][tile_row(r, hf) * DVB + c];
+      }
     }
-    __syncthreads();
+    lds_barrier();
+    {
+      float* dvout = a.w.dvn + op * (GC * GD) + dvb * DVB;
+#pragma unroll
+      for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
+        const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
+        *(float4*)(dvout + (size_t)i * GD + c4) = *(const float4*)&dvs[i * DVB + c4];
+      }
+    }
 
     // dS0 = EL dS1 + Qg^T dO - W^T dVn
     const float el_last = __expf(glast);
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int r = 0; r < 16; r++) ds[r] *= el_last;
+    mfma_range<GC>(qg + 32 * w + c, GD, dos + c, DVB, hf, ds);
+    mfma_range<GC, true>(wr + 32 * w + c, GD, dvs + c, DVB, hf, ds);
+    if (m.src >= 0 || (m.src == -1 && a.b.d_initial_state)) {
+      float* sg = (m.src >= 0 ? a.w.slot_grad + ((size_t)m.src * hv + h) * (GD * GD) : a.b.d_initial_state + (size_t)h * (GD * GD)) + col;
 #pragma unroll
-      for (int c = 0; c < 4; c++) ds[r][c] *= el_last;
-#pragma unroll 4
-    for (int i = 0; i < GC; i++) {
-      const float4 qv = *(const float4*)&qg[i * GD + 4 * ty];
-      const float4 ov = *(const float4*)&dos[i * DVB + 4 * tx];
-      const float4 wv = *(const float4*)&wr[i * GD + 4 * ty];
-      const float4 nv = *(const float4*)&dvs[i * DVB + 4 * tx];
-      const float qa[4] = {qv.x, qv.y, qv.z, qv.w}, oc[4] = {ov.x, ov.y, ov.z, ov.w};
-      const float wa[4] = {wv.x, wv.y, wv.z, wv.w}, ncol[4] = {nv.x, nv.y, nv.z, nv.w};
-#pragma unroll
-      for (int r = 0; r < 4; r++)
-#pragma unroll
-        for (int c = 0; c < 4; c++) ds[r][c] = fmaf(qa[r], oc[c], fmaf(-wa[r], ncol[c], ds[r][c]));
+      for (int r = 0; r < 16; r++) sg[(size_t)(32 * w + tile_row(r, hf)) * GD] += ds[r];
     }
-    if (src >= 0 || (src == -1 && a.b.d_initial_state)) {
-      float* sg = (src >= 0 ? a.w.slot_grad + ((size_t)src * hv + h) * (GD * GD) : a.b.d_initial_state + (size_t)h * (GD * GD)) + tile;
-#pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const float4 v = ld4(sg + (size_t)r * GD);
-        *(float4*)(sg + (size_t)r * GD) = make_float4(v.x + ds[r][0], v.y + ds[r][1], v.z + ds[r][2], v.w + ds[r][3]);
-      }
-    }
-    __syncthreads();
+    lds_barrier();
   }
 }
 
