@@ -48,7 +48,17 @@ struct GdnArgs {
                                      // (K exp(gamma_last - gamma))^T [128][64], scale tril((Q K^T) exp(gamma_i - gamma_j)) [64][64]
   float* glast;                      // exp(gamma_last)
   float* slots;                      // [n_slots][hv][128][128] saved node-end states
-  GdnChunkOps f32;                   // prepare kernel in its fp32-output form (backward pass) only
+  // backward pass only
+  GdnChunkOps f32;                   // unrounded per-chunk quantities for the finish kernel
+  const __bf16* d_o;                 // [N][hv][128]
+  __bf16* rev;                       // records of REV_ELEMS for the reverse walk (see REV_*)
+  __bf16* s0t;                       // per (head, chunk): entering state transposed [128 value cols][128 key dims]
+  __bf16* vns;                       // per (head, chunk): Vn as B-operand fragments [4 col blocks][2 row blocks][2][64 lanes][8]
+  __bf16* ds1t;                      // gradient of the leaving state, transposed like s0t
+  __bf16* dvns;                      // dVn, fragments like vns
+  float* slot_grad;                  // [n_slots][hv][128][128] gradients of the saved states
+  const float* d_state_out;          // nullptr or [n_capture][hv][128][128]
+  float* d_initial_state;            // nullptr or [hv][128][128] (zeroed by the caller)
 };
 
 // The operands of one (head, chunk) form one contiguous record, records ordered head-major: a scan
@@ -56,11 +66,15 @@ struct GdnArgs {
 // adjacent, so address translation and DRAM pages are reused instead of missed on every step.
 constexpr size_t REC_WN = 0, REC_UT = GC * GD, REC_QG = 2 * GC * GD, REC_KDT = 3 * GC * GD, REC_P = 4 * GC * GD;
 constexpr size_t REC_ELEMS = 4 * GC * GD + GC * GC;      // bf16 elements per record (72 KB)
+// Record of the reverse walk: Kd = K exp(gamma_last - gamma) [64][128], -W^T [128][64], (scale Q exp(gamma))^T
+// [128][64], P^T [64][64], dO^T [128 value cols][64]
+constexpr size_t REV_KD = 0, REV_WTN = GC * GD, REV_QGT = 2 * GC * GD, REV_PT = 3 * GC * GD, REV_DOT = 3 * GC * GD + GC * GC;
+constexpr size_t REV_ELEMS = 4 * GC * GD + GC * GC;
 __device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)h * a.n_chunks + chunk; }
 
-// F32OUT: the same quantities unrounded, in the layouts the backward kernels read (GdnChunkOps), instead of
-// the forward scan's bf16 records.
-template <bool F32OUT>
+// BWD: additionally the unrounded quantities the backward's finish kernel reads (GdnChunkOps) and the reverse
+// walk's record.
+template <bool BWD>
 __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(16))) __bf16 ksm[GC][GROW];
   __shared__ __attribute__((aligned(16))) __bf16 qsm[GC][GROW];
@@ -82,11 +96,11 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   if (tid == 0) {
     float run = 0.f;
     for (int i = 0; i < GC; i++) { run += gam[i]; gam[i] = run; }
-    if constexpr (!F32OUT) a.glast[op] = __expf(run);
+    a.glast[op] = __expf(run);
   }
   __syncthreads();
   const float g_last = gam[GC - 1];
-  if constexpr (F32OUT) {
+  if constexpr (BWD) {
     if (tid < GC) a.f32.gam[op * GC + tid] = gam[tid];
   }
 
@@ -102,7 +116,8 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     }
     *(bf16x8*)&ksm[i][c8] = kv;
     *(bf16x8*)&qsm[i][c8] = qv;
-    if constexpr (!F32OUT) *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
+    if constexpr (!BWD) *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
+    if constexpr (BWD) *(bf16x8*)(a.rev + op * REV_ELEMS + REV_KD + i * GD + c8) = scale_frag(kv, __expf(g_last - gam[i]));
   }
   __syncthreads();
 
@@ -128,9 +143,10 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         const float dec = j <= i ? __expf(gam[i] - gam[j]) : 0.f;
         const float a0 = j < i ? kk[r] * dec : 0.f;
         am[i][j] = bet[i] * a0;
-        if constexpr (F32OUT) {
+        if constexpr (BWD) {
           a.f32.a0[op * (GC * GC) + i * GC + j] = a0;
           a.f32.p[op * (GC * GC) + i * GC + j] = a.scale * qk[r] * dec;
+          a.rev[op * REV_ELEMS + REV_PT + j * GC + i] = (__bf16)(a.scale * qk[r] * dec);
         } else {
           pout[i * GC + j] = (__bf16)(a.scale * qk[r] * dec);
         }
@@ -142,9 +158,10 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       for (int r = 0; r < 16; r++) {
         const int i = ib * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
         am[i][j] = 0.f;
-        if constexpr (F32OUT) {
+        if constexpr (BWD) {
           a.f32.a0[op * (GC * GC) + i * GC + j] = 0.f;
           a.f32.p[op * (GC * GC) + i * GC + j] = 0.f;
+          a.rev[op * REV_ELEMS + REV_PT + j * GC + i] = (__bf16)0.f;
         } else {
           pout[i * GC + j] = (__bf16)0.f;
         }
@@ -158,15 +175,33 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     float f[8];
 #pragma unroll
     for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
-    if constexpr (F32OUT) {
-      float* dst = a.f32.kdt + op * (GD * GC) + d * GC + i0;
-      *(float4*)dst = make_float4(f[0], f[1], f[2], f[3]);
-      *(float4*)(dst + 4) = make_float4(f[4], f[5], f[6], f[7]);
-    } else {
-      *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    if constexpr (BWD) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) f[e] = (float)qsm[i0 + e][d] * a.scale * __expf(gam[i0 + e]);
+      *(bf16x8*)(a.rev + op * REV_ELEMS + REV_QGT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
     }
   }
   __syncthreads();
+  if constexpr (BWD) {
+    // dO^T: the rows of dO go through the Q tile's LDS (free now) and leave transposed
+    for (int piece = tid; piece < GC * (GD / 8); piece += G_THREADS) {
+      const int i = piece >> 4, c8 = (piece & 15) * 8;
+      bf16x8 dv;
+#pragma unroll
+      for (int e = 0; e < 8; e++) dv[e] = (__bf16)0.f;
+      if (i < len) dv = *(const bf16x8*)(a.d_o + ((size_t)(tok0 + i) * a.hv + h) * GD + c8);
+      *(bf16x8*)&qsm[i][c8] = dv;
+    }
+    __syncthreads();
+    for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
+      const int d = piece >> 3, i0 = (piece & 7) * 8;
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = qsm[i0 + e][d];
+      *(bf16x8*)(a.rev + op * REV_ELEMS + REV_DOT + d * GC + i0) = o;
+    }
+  }
 
   // forward substitution, one lane per column of [beta V | beta exp(gamma) K]:
   //   x_i = rhs_i - sum_{j<i} A_ij x_j
@@ -201,17 +236,19 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         x[i] = rhs;
       }
     }
-    if constexpr (F32OUT) {
-      // U and W row-major (lanes = consecutive columns), W also transposed
+    if constexpr (BWD) {
+      // U and W unrounded, row-major (lanes = consecutive columns); -W^T for the reverse walk
       float* rowmajor = (c < GD ? a.f32.u : a.f32.w) + op * (GC * GD) + (c & (GD - 1));
 #pragma unroll
       for (int i = 0; i < GC; i++) rowmajor[i * GD] = x[i];
       if (c >= GD) {
-        float* dst = a.f32.wt + op * (GD * GC) + (c - GD) * GC;
+        __bf16* dst = a.rev + op * REV_ELEMS + REV_WTN + (c - GD) * GC;
 #pragma unroll
-        for (int i0 = 0; i0 < GC; i0 += 4) *(float4*)(dst + i0) = make_float4(x[i0], x[i0 + 1], x[i0 + 2], x[i0 + 3]);
+        for (int i0 = 0; i0 < GC; i0 += 8)
+          *(bf16x8*)(dst + i0) = cvt8(-x[i0], -x[i0 + 1], -x[i0 + 2], -x[i0 + 3], -x[i0 + 4], -x[i0 + 5], -x[i0 + 6], -x[i0 + 7]);
       }
-    } else if (c < GD) {
+    }
+    if (c < GD) {
       __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + c * GC;
 #pragma unroll
       for (int i0 = 0; i0 < GC; i0 += 8)
@@ -265,14 +302,16 @@ __device__ __forceinline__ void dma_rows64(const __bf16* src, int rows, __bf16* 
     dma16(gb, (uint32_t)((8 * g + rr) * 128 + ((pos ^ rr) << 4)), lds_addr_uniform(dst + g * 8 * GC));
 }
 
-// Starts the copy of one chunk's operands into `im` (15 instructions per wave).
+// Starts the copy of one chunk's operands into `im` (15 instructions per wave; TRAIN: without the output's
+// operands, 9).
+template <bool TRAIN>
 __device__ __forceinline__ void issue_chunk(const GdnArgs& a, int chunk, int h, int dvb, ScanImage& im, int w, int lane) {
   const __bf16* rec = a.rec + op_index(a, chunk, h) * REC_ELEMS;
   dma_tile64<4>(rec + REC_WN, GD * 2, GC, im.wn, w, lane);
-  dma_tile64<4>(rec + REC_QG, GD * 2, GC, im.qg, w, lane);
+  if constexpr (!TRAIN) dma_tile64<4>(rec + REC_QG, GD * 2, GC, im.qg, w, lane);
   dma_rows64(rec + REC_KDT, GD, im.kd, w, lane);
   dma_rows64(rec + REC_UT + (size_t)dvb * G_DVB * GC, G_DVB, im.ut, w, lane);
-  dma_rows64(rec + REC_P, GC, im.p, w, lane);
+  if constexpr (!TRAIN) dma_rows64(rec + REC_P, GC, im.p, w, lane);
 }
 
 // The scalars of a chunk.  `z` is a per-lane zero the compiler cannot see through: they are loaded per
@@ -291,6 +330,9 @@ __device__ __forceinline__ void load_meta(const GdnArgs& a, int chunk, int h, in
 // One chunk of the scan.  On entry the copy of this chunk's operands into `im` is in flight (issued one
 // step earlier) and `meta` holds its scalars; the step waits for them, starts the next chunk's copy
 // into `im_next` and reloads `meta` for the next step.  Two barriers per step.
+// TRAIN (first pass of the backward): no output; the entering state (bf16, transposed, as it stands in LDS) and
+// Vn (as the B-operand fragments) of every chunk are saved instead.
+template <bool TRAIN>
 __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
                                           int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s) {
   const int tok0 = meta.tok0, len = meta.len, src = meta.src, dst = meta.dst, cap = meta.cap;
@@ -313,8 +355,9 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   dma_wait_all();                     // this wave's share of the chunk's operands has landed ...
   __syncthreads();                    // ... and so has everybody else's; every wave has also left the previous step,
                                       // so the other image, st and vx may be overwritten
-  if (chunk + 1 < a.n_chunks) issue_chunk(a, chunk + 1, h, dvb, im_next, w, lane);
+  if (chunk + 1 < a.n_chunks) issue_chunk<TRAIN>(a, chunk + 1, h, dvb, im_next, w, lane);
   load_meta(a, min(chunk + 1, a.n_chunks - 1), h, z, meta);
+  [[maybe_unused]] const size_t op = op_index(a, chunk, h);
 
   // Waves 0 and 1 compute one 32-row block of Vn = U - W S0 each; waves 2 and 3 meanwhile compute their
   // 32 rows of Q S0, the part of the output that does not need Vn.  Vn then goes through LDS as per-lane
@@ -326,13 +369,25 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   bf16x8 kfrag[2][2];                 // A operands of the state update
   bf16x8 pfrag[2][2];                 // waves 2, 3: A operands of P Vn
   const int half = w & 1;             // which 32-row block this wave works on
-  {
+  if (!TRAIN || w < 2) {
     const __bf16* atile = w < 2 ? im.wn : im.qg;
     const int abase = row_frag_base(lane);
 #pragma unroll
     for (int ks = 0; ks < GD / 16; ks++) {
       sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
       afrag[ks] = lds_row_frag(atile, abase, half, ks);
+    }
+  }
+  if constexpr (TRAIN) {
+    if (w >= 2) {
+      // 32 rows of 256 bytes: 512 pieces of 16 bytes over the 128 lanes of waves 2 and 3
+      const int t128 = half * 64 + lane;
+      u32x4n* sdst = (u32x4n*)(a.s0t + op * (GD * GD) + (size_t)dvb * G_DVB * GD);
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int piece = i * 128 + t128, row = piece >> 4, c8 = (piece & 15) * 8;
+        sdst[piece] = *(const u32x4n*)&sm.st[row][c8];
+      }
     }
   }
   f32x16 acc;
@@ -351,16 +406,21 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
 #pragma unroll
     for (int t = 0; t < 2; t++) {
       kfrag[jb][t] = row64_perm_k(im.kd, 32 * w + c, jb * 32 + t * 16, hf);
-      pfrag[jb][t] = row64_perm_k(im.p, half * 32 + c, jb * 32 + t * 16, hf);     // used by waves 2, 3 only
+      if constexpr (!TRAIN) pfrag[jb][t] = row64_perm_k(im.p, half * 32 + c, jb * 32 + t * 16, hf);     // used by waves 2, 3 only
     }
   __builtin_amdgcn_sched_barrier(0);
+  if (!TRAIN || w < 2) {
 #pragma unroll
-  for (int ks = 0; ks < GD / 16; ks++) acc = mfma32(afrag[ks], sfrag[ks], acc);
+    for (int ks = 0; ks < GD / 16; ks++) acc = mfma32(afrag[ks], sfrag[ks], acc);
+  }
   if (w < 2) {
 #pragma unroll
-    for (int t = 0; t < 2; t++)
-      sm.vx[half][t][lane] = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
-                                  acc[8 * t + 6], acc[8 * t + 7]);
+    for (int t = 0; t < 2; t++) {
+      const bf16x8 f = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
+                            acc[8 * t + 6], acc[8 * t + 7]);
+      sm.vx[half][t][lane] = f;
+      if constexpr (TRAIN) ((bf16x8*)a.vns)[(((op * 4 + dvb) * 2 + half) * 2 + t) * 64 + lane] = f;
+    }
   }
   __syncthreads();
   bf16x8 vfrag[2][2];
@@ -388,7 +448,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   }
 
   // O rows 32 half .. 32 half + 31 (waves 2 and 3): add P Vn to the Q S0 they already hold
-  if (w >= 2) {
+  if (!TRAIN && w >= 2) {
 #pragma unroll
     for (int jb = 0; jb < 2; jb++) {
       if (jb > half) continue;          // P is lower triangular
@@ -409,6 +469,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   }
 }
 
+template <bool TRAIN>
 __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(1024))) ScanSmem sm;
 
@@ -428,11 +489,158 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
   int z = 0;
   asm volatile("" : "+v"(z));
   ChunkMeta meta;
-  issue_chunk(a, 0, h, dvb, sm.img[0], w, lane);
+  issue_chunk<TRAIN>(a, 0, h, dvb, sm.img[0], w, lane);
   load_meta(a, 0, h, z, meta);
   for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
-    scan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s);
-    if (chunk + 1 < a.n_chunks) scan_step(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, h, dvb, lane, z, w, c, hf, s);
+    scan_step<TRAIN>(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s);
+    if (chunk + 1 < a.n_chunks) scan_step<TRAIN>(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, h, dvb, lane, z, w, c, hf, s);
+  }
+}
+
+// ---- reverse walk of the backward ---------------------------------------------------------------------
+// Per chunk, last to first:  dVn = P^T dO + Kd dS1,  dS0 = EL dS1 + Qg^T dO - W^T dVn  -- the forward step's
+// structure with (-W, S0, U) <-> (Kd, dS1, P^T dO) and (Kd^T, Vn) <-> (-W^T, dVn), plus the Qg^T dO term.  The
+// LDS image is reused with other contents: wn <- Kd (swizzled tile), kd <- -W^T, qg <- Qg^T (rows of 64),
+// p <- P^T, ut <- this workgroup's 32 rows of dO^T.  Saved for the finish kernel: dS1 (bf16, transposed) and dVn
+// (fragments), like the forward walk's S0 and Vn.
+// 8 consecutive elements e0 .. e0+7 (e0 a multiple of 8) of row r of a rows-of-64 array
+__device__ __forceinline__ bf16x8 row64_read8(const __bf16* arr, int r, int e0) {
+  return *(const bf16x8*)(arr + r * GC + (((e0 >> 3) ^ (r & 7)) << 3));
+}
+__device__ __forceinline__ void issue_rev_chunk(const GdnArgs& a, int chunk, int h, int dvb, ScanImage& im, int w, int lane) {
+  const __bf16* rec = a.rev + op_index(a, chunk, h) * REV_ELEMS;
+  dma_tile64<4>(rec + REV_KD, GD * 2, GC, im.wn, w, lane);
+  dma_rows64(rec + REV_WTN, GD, im.kd, w, lane);
+  dma_rows64(rec + REV_QGT, GD, im.qg, w, lane);
+  dma_rows64(rec + REV_PT, GC, im.p, w, lane);
+  dma_rows64(rec + REV_DOT + (size_t)dvb * G_DVB * GC, G_DVB, im.ut, w, lane);
+}
+
+// `later_src`: the source of the chunk that follows in DFS order (handled one step earlier); -2 means that chunk
+// continued from this one on chip, so `s` holds the gradient of this chunk's leaving state.
+__device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
+                                           int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s, int& later_src) {
+  const int src = meta.src, dst = meta.dst, cap = meta.cap;
+  const float glast = meta.glast;
+  const size_t op = op_index(a, chunk, h);
+
+  if (later_src != -2) s = zero16();
+  later_src = src;
+  if (dst >= 0) {
+    float* sp = a.slot_grad + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      float* e = sp + (size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD;
+      s[r] += *e;
+      *e = 0.f;                        // the slot is reused by an earlier node
+    }
+    pin(s);
+  }
+  if (cap >= 0) {
+    const float* sp = a.d_state_out + ((size_t)cap * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[r] += sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
+    pin(s);
+  }
+  // dS1 -> bf16, transposed into LDS
+#pragma unroll
+  for (int r4 = 0; r4 < 4; r4++)
+    *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
+  dma_wait_all();
+  __syncthreads();
+  if (chunk > 0) issue_rev_chunk(a, chunk - 1, h, dvb, im_next, w, lane);
+  load_meta(a, max(chunk - 1, 0), h, z, meta);
+
+  const int half = w & 1;
+  bf16x8 ofrag[GC / 16];              // B operand: column c of dO, k = tokens in plain order
+#pragma unroll
+  for (int js = 0; js < GC / 16; js++) ofrag[js] = row64_read8(im.ut, c, js * 16 + hf * 8);
+  bf16x8 wfrag[2][2], qfrag[GC / 16];
+#pragma unroll
+  for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) wfrag[jb][t] = row64_perm_k(im.kd, 32 * w + c, jb * 32 + t * 16, hf);
+#pragma unroll
+  for (int js = 0; js < GC / 16; js++) qfrag[js] = row64_read8(im.qg, 32 * w + c, js * 16 + hf * 8);
+  if (w < 2) {
+    // rows 32 half .. of dVn
+    bf16x8 sfrag[GD / 16], afrag[GD / 16], pfrag[GC / 16];
+    const int abase = row_frag_base(lane);
+#pragma unroll
+    for (int ks = 0; ks < GD / 16; ks++) {
+      sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+      afrag[ks] = lds_row_frag(im.wn, abase, half, ks);
+    }
+#pragma unroll
+    for (int js = 0; js < GC / 16; js++) pfrag[js] = row64_read8(im.p, half * 32 + c, js * 16 + hf * 8);
+    f32x16 acc = zero16();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < GD / 16; ks++) acc = mfma32(afrag[ks], sfrag[ks], acc);
+#pragma unroll
+    for (int js = 0; js < GC / 16; js++) acc = mfma32(pfrag[js], ofrag[js], acc);
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+      const bf16x8 f = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
+                            acc[8 * t + 6], acc[8 * t + 7]);
+      sm.vx[half][t][lane] = f;
+      ((bf16x8*)a.dvns)[(((op * 4 + dvb) * 2 + half) * 2 + t) * 64 + lane] = f;
+    }
+  } else {
+    // the gradient of the leaving state, for the finish kernel: 32 rows of 256 bytes over waves 2 and 3
+    const int t128 = half * 64 + lane;
+    u32x4n* sdst = (u32x4n*)(a.ds1t + op * (GD * GD) + (size_t)dvb * G_DVB * GD);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int piece = i * 128 + t128, row = piece >> 4, c8 = (piece & 15) * 8;
+      sdst[piece] = *(const u32x4n*)&sm.st[row][c8];
+    }
+  }
+  __syncthreads();
+  bf16x8 vfrag[2][2];
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[rb][t][lane];
+
+  // dS0 = exp(gamma_last) dS1 - W^T dVn + Qg^T dO, rows 32 w .. 32 w + 31
+#pragma unroll
+  for (int r = 0; r < 16; r++) s[r] *= glast;
+#pragma unroll
+  for (int jb = 0; jb < 2; jb++)
+#pragma unroll
+    for (int t = 0; t < 2; t++) s = mfma32(wfrag[jb][t], vfrag[jb][t], s);
+#pragma unroll
+  for (int js = 0; js < GC / 16; js++) s = mfma32(qfrag[js], ofrag[js], s);
+  if (src >= 0 || (src == -1 && a.d_initial_state)) {
+    float* sp = (src >= 0 ? a.slot_grad + ((size_t)src * a.hv + h) * (GD * GD) : a.d_initial_state + (size_t)h * (GD * GD)) +
+                dvb * G_DVB + c;
+#pragma unroll
+    for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] += s[r];
+  }
+}
+
+__global__ __launch_bounds__(G_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
+  __shared__ __attribute__((aligned(1024))) ScanSmem sm;
+  const int id = blockIdx.x;
+  int h, dvb;
+  if (a.hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
+  else               { h = id >> 2; dvb = id & 3; }
+  const int tid = threadIdx.x & (G_THREADS - 1);
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 31, hf = lane >> 5;
+  f32x16 s = zero16();                  // gradient of S[32 w + rows(r)][dvb*32 + c]
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  ChunkMeta meta;
+  int later_src = -1;
+  const int last = a.n_chunks - 1;
+  issue_rev_chunk(a, last, h, dvb, sm.img[0], w, lane);
+  load_meta(a, last, h, z, meta);
+  for (int chunk = last; chunk >= 0; chunk -= 2) {
+    rscan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s, later_src);
+    if (chunk > 0) rscan_step(a, sm, sm.img[1], sm.img[0], meta, chunk - 1, h, dvb, lane, z, w, c, hf, s, later_src);
   }
 }
 
@@ -468,22 +676,37 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {
     KernelTimer t(TT_KERNEL_GDN_SCAN, st);
-    gdn_scan_kernel<<<dim3((GD / G_DVB) * hv), G_THREADS, 0, st>>>(a);
+    gdn_scan_kernel<false><<<dim3((GD / G_DVB) * hv), G_THREADS, 0, st>>>(a);
   }
   return hipGetLastError();
 }
 
-hipError_t gdn_prepare_f32(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
-                           const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
-                           const GdnChunkOps& out, hipStream_t st) {
-  if (n_chunks == 0) return hipSuccess;
+hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st) {
+  if (b.n_chunks == 0) return hipSuccess;
   GdnArgs a{};
-  a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
-  a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v; a.g = g; a.beta = beta;
-  a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len;
-  a.f32 = out;
-  KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
-  gdn_prepare_kernel<true><<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
+  a.n_tokens = (int)b.n_tokens; a.hk = b.hk; a.hv = b.hv; a.n_chunks = b.n_chunks; a.scale = b.scale;
+  a.q = (const __bf16*)b.q; a.k = (const __bf16*)b.k; a.v = (const __bf16*)b.v; a.g = b.g; a.beta = b.beta;
+  a.chunk_tok0 = b.chunk_tok0; a.chunk_len = b.chunk_len; a.chunk_src = b.chunk_src; a.chunk_dst = b.chunk_dst;
+  a.initial_state = b.initial_state;
+  a.rec = (__bf16*)sv.fwd_rec; a.glast = sv.glast; a.slots = sv.slots;
+  a.f32 = ops; a.d_o = (const __bf16*)b.d_o; a.rev = (__bf16*)sv.rev_rec;
+  a.s0t = (__bf16*)sv.s0t; a.vns = (__bf16*)sv.vns; a.ds1t = (__bf16*)sv.ds1t; a.dvns = (__bf16*)sv.dvns;
+  a.slot_grad = sv.slot_grad; a.d_state_out = b.d_state_out; a.d_initial_state = b.d_initial_state;
+  {
+    KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
+    gdn_prepare_kernel<true><<<dim3(b.n_chunks, b.hv), G_THREADS, 0, st>>>(a);
+  }
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  {
+    KernelTimer t(TT_KERNEL_GDN_BWD_FSCAN, st);         // chunk_cap stays null: nothing is captured here
+    gdn_scan_kernel<true><<<dim3((GD / G_DVB) * b.hv), G_THREADS, 0, st>>>(a);
+  }
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  a.chunk_cap = b.d_state_out ? b.chunk_cap : nullptr;
+  {
+    KernelTimer t(TT_KERNEL_GDN_BWD_RSCAN, st);
+    gdn_rscan_kernel<<<dim3((GD / G_DVB) * b.hv), G_THREADS, 0, st>>>(a);
+  }
   return hipGetLastError();
 }
 

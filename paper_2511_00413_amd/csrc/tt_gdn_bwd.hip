@@ -14,11 +14,15 @@
 // started from the slot added its dS0 there; they all come later in DFS order, so a reverse walk over
 // the chunks has seen them), plus the upstream gradient of a captured state.
 //
-// All arithmetic here is plain fp32 (vector ALU, LDS-tiled products): a first, correct form of this pass.
-//   gdn_prepare_kernel<true>   (tt_gdn.hip)  per (chunk, head): gamma, A0, P, U, W in fp32
-//   gdn_bwd_fscan_kernel       (32 value columns, head): forward walk, saves S0 and Vn of every chunk
-//   gdn_bwd_rscan_kernel       (32 value columns, head): reverse walk, saves dS1 and dVn of every chunk
-//   gdn_bwd_finish_kernel      per (chunk, head): everything else; dq / dk per value head in fp32
+// Kernels (the first three live in tt_gdn.hip with the forward's):
+//   gdn_prepare_kernel<true>   per (chunk, head): the forward walk's bf16 record, the reverse walk's bf16 record
+//                              (Kd, -W^T, Qg^T, P^T, dO^T) and gamma, A0, P, U, W unrounded
+//   gdn_scan_kernel<true>      (32 value columns, head): the forward scan without its output; saves S0 and Vn
+//                              of every chunk (bf16)
+//   gdn_rscan_kernel           (32 value columns, head): reverse walk in the forward scan's form (bf16 matrix
+//                              instruction, fp32 state gradient in accumulators); saves dS1 and dVn (bf16)
+//   gdn_bwd_finish_kernel      per (chunk, head): everything else, fp32 vector arithmetic with LDS-tiled
+//                              products; dq / dk per value head in fp32
 //   gdn_bwd_group_sum_kernel   sums dq / dk over the value heads that share a key head, rounds to bf16
 #include <hip/hip_runtime.h>
 #include <algorithm>
@@ -37,14 +41,8 @@ constexpr int KS = 32;               // k-slab of the LDS-tiled products of the 
 
 struct BwdWs {
   GdnChunkOps ops;
-  // per (head, chunk)
-  float* s0;         // [128][128] state entering the chunk
-  float* vn;         // [64][128]
-  float* dvn;        // [64][128]
-  float* ds1;        // [128][128] gradient of the state leaving the chunk
-  float* x;          // [64][256]  [dW] on the way in, [dVb | dKb] after the transposed solve
-  float* slots;      // [n_slots][hv][128][128] saved node-end states
-  float* slot_grad;  // [n_slots][hv][128][128]
+  GdnBwdSaved sv;
+  float* x;          // per (head, chunk) [64][256]: [dW] on the way in, [dVb | dKb] after the transposed solve
   float* dqh;        // [N][hv][128] per-value-head dq, dk
   float* dkh;
 };
@@ -53,365 +51,8 @@ struct KArgs {
   BwdWs w;
 };
 
-__device__ __forceinline__ void scan_ids(int id, int hv, int& h, int& dvb) {
-  // consecutive ids go round-robin over the 8 XCDs; the four column blocks of a head share one
-  if (hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
-  else             { h = id >> 2; dvb = id & 3; }
-}
-
 __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
 __device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
-
-// fp32 matrix instruction: D (32 x 32) += A (32 x 2) B (2 x 32).  Lane l = 32 hf + c supplies A[row c][k = hf] and
-// B[k = hf][column c] and holds D[(r / 4) * 8 + 4 hf + r % 4][c] in register r.
-__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 acc) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
-__device__ __forceinline__ int tile_row(int r, int hf) { return (r >> 2) * 8 + 4 * hf + (r & 3); }
-
-// acc += sign A B over LK consecutive k (LK even).  `at` points at element (k = 0, this lane's row) of A stored
-// [k][row] with pitch pa, `bm` at element (k = 0, this lane's column) of B stored [k][column] with pitch pb.  The
-// instruction's two k-slots take k = s and k = LK / 2 + s.
-template <int LK, bool NEG = false>
-__device__ __forceinline__ void mfma_range(const float* at, int pa, const float* bm, int pb, int hf, f32x16& acc) {
-#pragma unroll 8
-  for (int s = 0; s < LK / 2; s++) {
-    const int k = hf * (LK / 2) + s;
-    const float av = at[k * pa];
-    acc = mfma_f32(NEG ? -av : av, bm[k * pb], acc);
-  }
-}
-
-// Barrier that waits for this wave's LDS traffic only: global stores (nobody in the workgroup reads them back)
-// and the prefetch loads of the next chunk stay in flight across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// The walks are software-pipelined: the operands of chunk i + 1 are fetched into registers while chunk i is
-// computed and go to LDS at the top of the next step; the chunk's scalars are fetched per lane one step ahead as
-// well (`z` is a per-lane zero the compiler cannot see through, which keeps them in vector registers until they
-// are needed instead of waiting for them right behind the load).
-struct WalkMeta {
-  int tok0, len, src, dst, cap;
-};
-__device__ __forceinline__ WalkMeta load_walk_meta(const GdnBwdArgs& b, int chunk, int z, bool want_cap) {
-  WalkMeta m;
-  m.tok0 = b.chunk_tok0[chunk + z]; m.len = b.chunk_len[chunk + z]; m.src = b.chunk_src[chunk + z]; m.dst = b.chunk_dst[chunk + z];
-  m.cap = want_cap ? b.chunk_cap[chunk + z] : -1;
-  return m;
-}
-__device__ __forceinline__ WalkMeta uniform(const WalkMeta& m) {
-  WalkMeta u;
-  u.tok0 = __builtin_amdgcn_readfirstlane(m.tok0); u.len = __builtin_amdgcn_readfirstlane(m.len);
-  u.src = __builtin_amdgcn_readfirstlane(m.src); u.dst = __builtin_amdgcn_readfirstlane(m.dst);
-  u.cap = __builtin_amdgcn_readfirstlane(m.cap);
-  return u;
-}
-
-// ---- forward walk ------------------------------------------------------------------------------------
-// Wave w owns rows 32 w .. 32 w + 31 of the 128 x 32 state slice (accumulator layout).  The two 32 x 32 blocks of
-// Vn are each computed by two waves, one per half of the contraction over the key dimension.
-struct FwdStage {                 // one chunk's operands on their way to LDS
-  f32x4 wt[(GD * GC / 4) / BT];      // native vector types: they stay in registers
-  bf16x8 k[(GC * GD / 8) / BT];
-  float gam[(GC * GD / 8) / BT];
-  f32x4 u[(GC * DVB / 4) / BT];
-  float glast;
-};
-__device__ __forceinline__ void fwd_fetch(const KArgs& a, int chunk, int h, int dvb, const __bf16* kb, size_t krow, int tid, int z,
-                                          FwdStage& st) {
-  const size_t op = (size_t)h * a.b.n_chunks + chunk;
-  const int tok0 = a.b.chunk_tok0[chunk + z], len = a.b.chunk_len[chunk + z];
-  const float* gam = a.w.ops.gam + op * GC;
-  const f32x4* wsrc = (const f32x4*)(a.w.ops.wt + op * (GD * GC));
-#pragma unroll
-  for (int p = 0; p < (GD * GC / 4) / BT; p++) st.wt[p] = wsrc[tid + p * BT];
-#pragma unroll
-  for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-    const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-    st.k[p] = *(const bf16x8*)(kb + (size_t)(tok0 + min(i, len - 1)) * krow + c8);
-    st.gam[p] = i < len ? gam[i] : 1e30f;                  // exp(glast - 1e30) = 0: rows past the chunk's length
-  }
-  const float* u = a.w.ops.u + op * (GC * GD) + dvb * DVB;
-#pragma unroll
-  for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
-    const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
-    st.u[p] = *(const f32x4*)(u + (size_t)i * GD + c4);
-  }
-  st.glast = gam[GC - 1 + z];
-}
-
-__global__ __launch_bounds__(BT, 1) void gdn_bwd_fscan_kernel(KArgs a) {
-  __shared__ __attribute__((aligned(16))) float wt[GD * GC];      // W^T [d][i]
-  __shared__ __attribute__((aligned(16))) float kd[GC * GD];      // Kd  [i][d]
-  __shared__ __attribute__((aligned(16))) float us[GC * DVB];     // U   [i][c]
-  __shared__ __attribute__((aligned(16))) float ss[GD * DVB];     // S0  [d][c]
-  __shared__ __attribute__((aligned(16))) float vs[GC * DVB];     // Vn  [i][c]
-  __shared__ float half2nd[2][32 * DVB];                          // W S0 over the second half of the key dims
-  int h, dvb;
-  scan_ids(blockIdx.x, a.b.hv, h, dvb);
-  const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), ib = w & 1, kq = w >> 1;
-  const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
-  const __bf16* kb = (const __bf16*)a.b.k + (size_t)kh * GD;
-  const size_t krow = (size_t)a.b.hk * GD;
-  const size_t col = (size_t)dvb * DVB + c;                   // this lane's column inside a [128][128] state
-  f32x16 s = zero16();
-  int z = 0;
-  asm volatile("" : "+v"(z));
-
-  FwdStage st;
-  fwd_fetch(a, 0, h, dvb, kb, krow, tid, z, st);
-  WalkMeta next = load_walk_meta(a.b, 0, z, false);
-  for (int chunk = 0; chunk < nc; chunk++) {
-    const WalkMeta m = uniform(next);
-    const size_t op = (size_t)h * nc + chunk;
-    if (m.src != -2) {
-      const float* sp = m.src >= 0 ? a.w.slots + ((size_t)m.src * hv + h) * (GD * GD) : a.b.initial_state ? a.b.initial_state + (size_t)h * (GD * GD) : nullptr;
-#pragma unroll
-      for (int r = 0; r < 16; r++) s[r] = sp ? sp[(size_t)(32 * w + tile_row(r, hf)) * GD + col] : 0.f;
-    }
-#pragma unroll
-    for (int r = 0; r < 16; r++) ss[(32 * w + tile_row(r, hf)) * DVB + c] = s[r];
-    const float glast = st.glast;
-#pragma unroll
-    for (int p = 0; p < (GD * GC / 4) / BT; p++) ((f32x4*)wt)[tid + p * BT] = st.wt[p];
-#pragma unroll
-    for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-      const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-      const float f = __expf(glast - st.gam[p]);
-      float o[8];
-#pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = (float)st.k[p][e] * f;
-      *(float4*)&kd[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
-      *(float4*)&kd[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-    }
-#pragma unroll
-    for (int p = 0; p < (GC * DVB / 4) / BT; p++) ((f32x4*)us)[tid + p * BT] = st.u[p];
-    lds_barrier();
-
-    // next chunk's operands and scalars on their way (the last step re-fetches its own: no branch around loads)
-    const int nxt = min(chunk + 1, nc - 1);
-    fwd_fetch(a, nxt, h, dvb, kb, krow, tid, z, st);
-    next = load_walk_meta(a.b, nxt, z, false);
-    {   // the entering state, for the finish kernel: 16-byte stores from the LDS copy
-      float* s0 = a.w.s0 + op * (GD * GD) + dvb * DVB;
-#pragma unroll
-      for (int p = 0; p < (GD * DVB / 4) / BT; p++) {
-        const int piece = tid + p * BT, d = piece >> 3, c4 = (piece & 7) * 4;
-        *(float4*)(s0 + (size_t)d * GD + c4) = *(const float4*)&ss[d * DVB + c4];
-      }
-    }
-
-    // Vn = U - W S0: rows 32 ib .., key dims 64 kq .. 64 kq + 63
-    f32x16 part = zero16();
-    mfma_range<64>(wt + (64 * kq) * GC + 32 * ib + c, GC, ss + (64 * kq) * DVB + c, DVB, hf, part);
-    if (kq == 1) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) half2nd[ib][tile_row(r, hf) * DVB + c] = part[r];
-    }
-    lds_barrier();
-    if (kq == 0) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int i = 32 * ib + tile_row(r, hf);
-        vs[i * DVB + c] = us[i * DVB + c] - (part[r] + half2nd[ib][tile_row(r, hf) * DVB + c]);
-      }
-    }
-    lds_barrier();
-    {
-      float* vout = a.w.vn + op * (GC * GD) + dvb * DVB;
-#pragma unroll
-      for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
-        const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
-        *(float4*)(vout + (size_t)i * GD + c4) = *(const float4*)&vs[i * DVB + c4];
-      }
-    }
-
-    // S1 = EL S0 + Kd^T Vn
-    const float el_last = __expf(glast);
-#pragma unroll
-    for (int r = 0; r < 16; r++) s[r] *= el_last;
-    mfma_range<GC>(kd + 32 * w + c, GD, vs + c, DVB, hf, s);
-    if (m.dst >= 0) {
-      float* sp = a.w.slots + ((size_t)m.dst * hv + h) * (GD * GD) + col;
-#pragma unroll
-      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + tile_row(r, hf)) * GD] = s[r];
-    }
-    lds_barrier();         // the LDS arrays are rewritten by the next chunk
-  }
-}
-
-// ---- reverse walk ------------------------------------------------------------------------------------
-struct RevStage {
-  f32x4 kdt[(GD * GC / 4) / BT], w[(GC * GD / 4) / BT], p[(GC * GC / 4) / BT];
-  bf16x8 q[(GC * GD / 8) / BT];
-  float gam[(GC * GD / 8) / BT];
-  bf16x8 d_o;
-  float glast;
-};
-__device__ __forceinline__ void rev_fetch(const KArgs& a, int chunk, int h, const __bf16* qb, size_t qrow, const __bf16* dob, size_t vrow,
-                                          int tid, int z, RevStage& st) {
-  const size_t op = (size_t)h * a.b.n_chunks + chunk;
-  const int tok0 = a.b.chunk_tok0[chunk + z], len = a.b.chunk_len[chunk + z];
-  const float* gam = a.w.ops.gam + op * GC;
-  const f32x4* ksrc = (const f32x4*)(a.w.ops.kdt + op * (GD * GC));
-  const f32x4* wsrc = (const f32x4*)(a.w.ops.w + op * (GC * GD));
-  const f32x4* psrc = (const f32x4*)(a.w.ops.p + op * (GC * GC));
-#pragma unroll
-  for (int p = 0; p < (GD * GC / 4) / BT; p++) {
-    st.kdt[p] = ksrc[tid + p * BT];
-    st.w[p] = wsrc[tid + p * BT];
-  }
-#pragma unroll
-  for (int p = 0; p < (GC * GC / 4) / BT; p++) st.p[p] = psrc[tid + p * BT];
-#pragma unroll
-  for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-    const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-    st.q[p] = *(const bf16x8*)(qb + (size_t)(tok0 + min(i, len - 1)) * qrow + c8);
-    st.gam[p] = i < len ? gam[i] : -1e30f;                 // exp(-1e30) = 0: rows past the chunk's length
-  }
-  {
-    const int i = tid >> 2, c8 = (tid & 3) * 8;            // 64 rows x 4 pieces of 8 columns
-    const bf16x8 dv = *(const bf16x8*)(dob + (size_t)(tok0 + min(i, len - 1)) * vrow + c8);
-    bf16x8 zero;
-#pragma unroll
-    for (int e = 0; e < 8; e++) zero[e] = (__bf16)0.f;
-    st.d_o = i < len ? dv : zero;
-  }
-  st.glast = gam[GC - 1 + z];
-}
-
-__global__ __launch_bounds__(BT, 1) void gdn_bwd_rscan_kernel(KArgs a) {
-  __shared__ __attribute__((aligned(16))) float kdt[GD * GC];     // Kd^T [d][i]
-  __shared__ __attribute__((aligned(16))) float qg[GC * GD];      // Qg   [i][d]
-  __shared__ __attribute__((aligned(16))) float wr[GC * GD];      // W    [i][d]
-  __shared__ __attribute__((aligned(16))) float pm[GC * GC];      // P    [j][i]
-  __shared__ __attribute__((aligned(16))) float dos[GC * DVB];    // dO   [i][c]
-  __shared__ __attribute__((aligned(16))) float dvs[GC * DVB];    // dVn  [i][c]
-  __shared__ __attribute__((aligned(16))) float dss[GD * DVB];    // dS1  [d][c]
-  __shared__ float half2nd[2][32 * DVB];
-  int h, dvb;
-  scan_ids(blockIdx.x, a.b.hv, h, dvb);
-  const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6), ib = w & 1, kq = w >> 1;
-  const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
-  const __bf16* qb = (const __bf16*)a.b.q + (size_t)kh * GD;
-  const size_t qrow = (size_t)a.b.hk * GD;
-  const __bf16* dob = (const __bf16*)a.b.d_o + (size_t)h * GD + dvb * DVB;
-  const size_t vrow = (size_t)hv * GD;
-  const size_t col = (size_t)dvb * DVB + c;
-  const bool want_cap = a.b.chunk_cap && a.b.d_state_out;
-  f32x16 ds = zero16();
-  int z = 0;
-  asm volatile("" : "+v"(z));
-
-  RevStage st;
-  rev_fetch(a, nc - 1, h, qb, qrow, dob, vrow, tid, z, st);
-  WalkMeta next = load_walk_meta(a.b, nc - 1, z, want_cap);
-  int later_src = -1;                       // source of the chunk after this one in DFS order (handled one step earlier)
-  for (int chunk = nc - 1; chunk >= 0; chunk--) {
-    const WalkMeta m = uniform(next);
-    const size_t op = (size_t)h * nc + chunk;
-
-    // gradient of the state leaving this chunk
-    if (later_src != -2) ds = zero16();     // nobody took this chunk's end state on chip
-    later_src = m.src;
-    if (m.dst >= 0) {
-      float* sg = a.w.slot_grad + ((size_t)m.dst * hv + h) * (GD * GD) + col;
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        float* e = sg + (size_t)(32 * w + tile_row(r, hf)) * GD;
-        ds[r] += *e;
-        *e = 0.f;                                   // the slot is reused by an earlier node
-      }
-    }
-    if (m.cap >= 0) {
-      const float* up = a.b.d_state_out + ((size_t)m.cap * hv + h) * (GD * GD) + col;
-#pragma unroll
-      for (int r = 0; r < 16; r++) ds[r] += up[(size_t)(32 * w + tile_row(r, hf)) * GD];
-    }
-#pragma unroll
-    for (int r = 0; r < 16; r++) dss[(32 * w + tile_row(r, hf)) * DVB + c] = ds[r];
-    const float glast = st.glast;
-#pragma unroll
-    for (int p = 0; p < (GD * GC / 4) / BT; p++) {
-      ((f32x4*)kdt)[tid + p * BT] = st.kdt[p];
-      ((f32x4*)wr)[tid + p * BT] = st.w[p];
-    }
-#pragma unroll
-    for (int p = 0; p < (GC * GC / 4) / BT; p++) ((f32x4*)pm)[tid + p * BT] = st.p[p];
-#pragma unroll
-    for (int p = 0; p < (GC * GD / 8) / BT; p++) {
-      const int piece = tid + p * BT, i = piece >> 4, c8 = (piece & 15) * 8;
-      const float f = a.b.scale * __expf(st.gam[p]);
-      float o[8];
-#pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = (float)st.q[p][e] * f;
-      *(float4*)&qg[i * GD + c8] = make_float4(o[0], o[1], o[2], o[3]);
-      *(float4*)&qg[i * GD + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-    }
-    {
-      const int i = tid >> 2, c8 = (tid & 3) * 8;
-      float o[8];
-#pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = (float)st.d_o[e];
-      *(float4*)&dos[i * DVB + c8] = make_float4(o[0], o[1], o[2], o[3]);
-      *(float4*)&dos[i * DVB + c8 + 4] = make_float4(o[4], o[5], o[6], o[7]);
-    }
-    lds_barrier();
-
-    const int nxt = max(chunk - 1, 0);
-    rev_fetch(a, nxt, h, qb, qrow, dob, vrow, tid, z, st);
-    next = load_walk_meta(a.b, nxt, z, want_cap);
-    {
-      float* ds1 = a.w.ds1 + op * (GD * GD) + dvb * DVB;
-#pragma unroll
-      for (int p = 0; p < (GD * DVB / 4) / BT; p++) {
-        const int piece = tid + p * BT, d = piece >> 3, c4 = (piece & 7) * 4;
-        *(float4*)(ds1 + (size_t)d * GD + c4) = *(const float4*)&dss[d * DVB + c4];
-      }
-    }
-
-    // dVn = P^T dO + Kd dS1, rows 32 ib ..; the contraction (64 tokens + 128 key dims) is split in two halves of 96
-    f32x16 part = zero16();
-    if (kq == 0) {
-      mfma_range<GC>(pm + 32 * ib + c, GC, dos + c, DVB, hf, part);
-      mfma_range<32>(kdt + 32 * ib + c, GC, dss + c, DVB, hf, part);
-    } else {
-      mfma_range<96>(kdt + 32 * GC + 32 * ib + c, GC, dss + 32 * DVB + c, DVB, hf, part);
-#pragma unroll
-      for (int r = 0; r < 16; r++) half2nd[ib][tile_row(r, hf) * DVB + c] = part[r];
-    }
-    lds_barrier();
-    if (kq == 0) {
-#pragma unroll
-      for (int r = 0; r < 16; r++) {
-        const int i = 32 * ib + tile_row(r, hf);
-        dvs[i * DVB + c] = part[r] + half2nd[ib][tile_row(r, hf) * DVB + c];
-      }
-    }
-    lds_barrier();
-    {
-      float* dvout = a.w.dvn + op * (GC * GD) + dvb * DVB;
-#pragma unroll
-      for (int p = 0; p < (GC * DVB / 4) / BT; p++) {
-        const int piece = tid + p * BT, i = piece >> 3, c4 = (piece & 7) * 4;
-        *(float4*)(dvout + (size_t)i * GD + c4) = *(const float4*)&dvs[i * DVB + c4];
-      }
-    }
-
-    // dS0 = EL dS1 + Qg^T dO - W^T dVn
-    const float el_last = __expf(glast);
-#pragma unroll
-    for (int r = 0; r < 16; r++) ds[r] *= el_last;
-    mfma_range<GC>(qg + 32 * w + c, GD, dos + c, DVB, hf, ds);
-    mfma_range<GC, true>(wr + 32 * w + c, GD, dvs + c, DVB, hf, ds);
-    if (m.src >= 0 || (m.src == -1 && a.b.d_initial_state)) {
-      float* sg = (m.src >= 0 ? a.w.slot_grad + ((size_t)m.src * hv + h) * (GD * GD) : a.b.d_initial_state + (size_t)h * (GD * GD)) + col;
-#pragma unroll
-      for (int r = 0; r < 16; r++) sg[(size_t)(32 * w + tile_row(r, hf)) * GD] += ds[r];
-    }
-    lds_barrier();
-  }
-}
 
 // ---- per-chunk finish ----------------------------------------------------------------------------------
 // acc[r][c] += sum_k fa(i, k) fb(k, j) for i = ty TM + r, j = tx + c (N / TN), over K (a multiple of KS), through
@@ -494,10 +135,15 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
   const float* Wm = a.w.ops.w + op * (GC * GD);
   const float* A0 = a.w.ops.a0 + op * (GC * GC);
   const float* Pm = a.w.ops.p + op * (GC * GC);
-  const float* S0 = a.w.s0 + op * (GD * GD);
-  const float* Vn = a.w.vn + op * (GC * GD);
-  const float* dVn = a.w.dvn + op * (GC * GD);
-  const float* dS1 = a.w.ds1 + op * (GD * GD);
+  // saved by the walks (bf16): S0 and dS1 transposed [value col][key dim], Vn and dVn in fragment order
+  const __bf16* s0t = (const __bf16*)a.w.sv.s0t + op * (GD * GD);
+  const __bf16* ds1t = (const __bf16*)a.w.sv.ds1t + op * (GD * GD);
+  const __bf16* vns = (const __bf16*)a.w.sv.vns + op * (GC * GD);
+  const __bf16* dvns = (const __bf16*)a.w.sv.dvns + op * (GC * GD);
+  auto s0_at = [&](int d, int cc) { return (float)s0t[cc * GD + d]; };
+  auto ds1_at = [&](int d, int cc) { return (float)ds1t[cc * GD + d]; };
+  auto vn_at = [&](int i, int cc) { return (float)vns[gdn_frag_index(i, cc)]; };
+  auto dvn_at = [&](int i, int cc) { return (float)dvns[gdn_frag_index(i, cc)]; };
   float* X = a.w.x + op * (GC * 2 * GD);
   const size_t qrow = (size_t)a.b.hk * GD, vrow = (size_t)hv * GD;
   const __bf16* qb = (const __bf16*)a.b.q + (size_t)tok0 * qrow + (size_t)kh * GD;
@@ -526,8 +172,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, true>(GD, [&](int i, int k) { return dVn[i * GD + k]; },
-                                           [&](int k, int j) { return S0[j * GD + k]; }, acc, as, bs, tid);
+    slab_product<GC, GD, 4, 8, true, false>(GD, dvn_at, [&](int k, int j) { return s0_at(j, k); }, acc, as, bs, tid);
     const int tx = tid & 15, ty = tid >> 4;
 #pragma unroll
     for (int r = 0; r < 4; r++)
@@ -546,10 +191,14 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
   {
     const int c = tid;
     float x[GC];
-    const float* rhs = c < GD ? dVn + c : X + c;
-    const int pitch = c < GD ? GD : 2 * GD;
+    // right-hand sides: 64 independent loads per lane in one straight-line block
+    if (c < GD) {
 #pragma unroll
-    for (int i = 0; i < GC; i++) x[i] = rhs[(size_t)i * pitch];
+      for (int i = 0; i < GC; i++) x[i] = dvn_at(i, c);
+    } else {
+#pragma unroll
+      for (int i = 0; i < GC; i++) x[i] = X[i * (2 * GD) + c];
+    }
 #pragma unroll
     for (int i = GC - 2; i >= 0; i--) {
       float v = x[i];
@@ -590,7 +239,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 4; c++) acc[r][c] = 0.f;
-    slab_product<GC, GC, 4, 4, true, true>(GD, do_at, [&](int k, int j) { return Vn[j * GD + k]; }, acc, as, bs, tid);
+    slab_product<GC, GC, 4, 4, true, true>(GD, do_at, [&](int k, int j) { return vn_at(j, k); }, acc, as, bs, tid);
 #pragma unroll
     for (int r = 0; r < 4; r++)
 #pragma unroll
@@ -644,7 +293,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, true>(GD, do_at, [&](int k, int j) { return S0[j * GD + k]; }, acc, as, bs, tid);
+    slab_product<GC, GD, 4, 8, true, false>(GD, do_at, [&](int k, int j) { return s0_at(j, k); }, acc, as, bs, tid);
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       const int i = ty * 4 + r;
@@ -676,8 +325,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, true>(GD, [&](int i, int k) { return Vn[i * GD + k]; },
-                                           [&](int k, int j) { return dS1[j * GD + k]; }, acc, as, bs, tid);
+    slab_product<GC, GD, 4, 8, true, false>(GD, vn_at, [&](int k, int j) { return ds1_at(j, k); }, acc, as, bs, tid);
 #pragma unroll
     for (int r = 0; r < 4; r++) {
       const int i = ty * 4 + r;
@@ -735,9 +383,10 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
   {
     float s = 0.f;
 #pragma unroll
-    for (int p = 0; p < (GD * GD / 4) / BT; p++) {
-      const float4 x = ld4(dS1 + 4 * (tid + p * BT)), y = ld4(S0 + 4 * (tid + p * BT));
-      s += x.x * y.x + x.y * y.y + x.z * y.z + x.w * y.w;
+    for (int p = 0; p < (GD * GD / 8) / BT; p++) {
+      const bf16x8 x = *(const bf16x8*)(ds1t + 8 * (tid + p * BT)), y = *(const bf16x8*)(s0t + 8 * (tid + p * BT));
+#pragma unroll
+      for (int e = 0; e < 8; e++) s += (float)x[e] * (float)y[e];
     }
     red[tid] = s;
   }
@@ -794,28 +443,29 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs* w) {
   const size_t per = (size_t)n_chunks * hv;
   size_t off = 0;
-  auto take = [&](size_t floats) {
-    float* r = p ? (float*)(p + off) : nullptr;
-    off += align256(floats * 4);
+  auto take = [&](size_t bytes) {
+    char* r = p ? p + off : nullptr;
+    off += align256(bytes);
     return r;
   };
   BwdWs t{};
-  t.ops.gam = take(per * GC);
-  t.ops.a0 = take(per * GC * GC);
-  t.ops.p = take(per * GC * GC);
-  t.ops.u = take(per * GC * GD);
-  t.ops.w = take(per * GC * GD);
-  t.ops.wt = take(per * GC * GD);
-  t.ops.kdt = take(per * GC * GD);
-  t.s0 = take(per * GD * GD);
-  t.vn = take(per * GC * GD);
-  t.dvn = take(per * GC * GD);
-  t.ds1 = take(per * GD * GD);
-  t.x = take(per * GC * 2 * GD);
-  t.slots = take((size_t)n_slots * hv * GD * GD);
-  t.slot_grad = take((size_t)n_slots * hv * GD * GD);
-  t.dqh = take((size_t)n_tokens * hv * GD);
-  t.dkh = take((size_t)n_tokens * hv * GD);
+  t.ops.gam = (float*)take(per * GC * 4);
+  t.ops.a0 = (float*)take(per * GC * GC * 4);
+  t.ops.p = (float*)take(per * GC * GC * 4);
+  t.ops.u = (float*)take(per * GC * GD * 4);
+  t.ops.w = (float*)take(per * GC * GD * 4);
+  t.sv.fwd_rec = take(per * GDN_REC_ELEMS * 2);
+  t.sv.rev_rec = take(per * GDN_REC_ELEMS * 2);
+  t.sv.glast = (float*)take(per * 4);
+  t.sv.s0t = take(per * GD * GD * 2);
+  t.sv.ds1t = take(per * GD * GD * 2);
+  t.sv.vns = take(per * GC * GD * 2);
+  t.sv.dvns = take(per * GC * GD * 2);
+  t.sv.slots = (float*)take((size_t)n_slots * hv * GD * GD * 4);
+  t.sv.slot_grad = (float*)take((size_t)n_slots * hv * GD * GD * 4);
+  t.x = (float*)take(per * GC * 2 * GD * 4);
+  t.dqh = (float*)take((size_t)n_tokens * hv * GD * 4);
+  t.dkh = (float*)take((size_t)n_tokens * hv * GD * 4);
   if (w) *w = t;
   return off + 256;
 }
@@ -837,23 +487,10 @@ hipError_t gdn_bwd(const GdnBwdArgs& b, hipStream_t st) {
     const size_t n4 = floats / 4;
     gdn_bwd_fill_zero_kernel<<<dim3((unsigned)std::min<size_t>((n4 + BT - 1) / BT, 4096)), BT, 0, st>>>((float4*)p, n4);
   };
-  zero(a.w.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
+  zero(a.w.sv.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
   if (b.d_initial_state) zero(b.d_initial_state, (size_t)b.hv * GD * GD);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  if (hipError_t e = gdn_prepare_f32(b.n_tokens, b.hk, b.hv, b.scale, b.q, b.k, b.v, b.g, b.beta, b.n_chunks, b.chunk_tok0, b.chunk_len,
-                                     a.w.ops, st);
-      e != hipSuccess)
-    return e;
-  {
-    KernelTimer t(TT_KERNEL_GDN_BWD_FSCAN, st);
-    gdn_bwd_fscan_kernel<<<dim3((GD / DVB) * b.hv), BT, 0, st>>>(a);
-  }
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  {
-    KernelTimer t(TT_KERNEL_GDN_BWD_RSCAN, st);
-    gdn_bwd_rscan_kernel<<<dim3((GD / DVB) * b.hv), BT, 0, st>>>(a);
-  }
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  if (hipError_t e = gdn_bwd_prepare_and_walks(b, a.w.ops, a.w.sv, st); e != hipSuccess) return e;
   {
     KernelTimer t(TT_KERNEL_GDN_BWD_FINISH, st);
     gdn_bwd_finish_kernel<<<dim3(b.n_chunks, b.hv), BT, 0, st>>>(a);

@@ -83,20 +83,35 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
                    void* o, void* workspace, hipStream_t st);
 size_t gdn_workspace(int n_chunks, int n_slots, int hv);
 
-// The per-chunk quantities of the gated delta rule that do not depend on the state, in fp32, for the
-// backward pass; every array is indexed by (head * n_chunks + chunk).
+// Backward of the gated delta rule.  Every per-chunk array is indexed by (head * n_chunks + chunk).
+// Unrounded per-chunk quantities that do not depend on the state (written by the prepare kernel, read by the
+// finish kernel):
 struct GdnChunkOps {
   float* gam;      // [64]       running sum of the log-decays inside the chunk
   float* a0;       // [64][64]   strictly-lower (k_i . k_j) exp(gamma_i - gamma_j)   (A without beta_i)
   float* p;        // [64][64]   scale tril((q_i . k_j) exp(gamma_i - gamma_j))
   float* u;        // [64][128]  (I + A)^-1 (beta V)
   float* w;        // [64][128]  (I + A)^-1 (beta exp(gamma) K)
-  float* wt;       // [128][64]  W transposed
-  float* kdt;      // [128][64]  (K exp(gamma_last - gamma)) transposed
 };
-hipError_t gdn_prepare_f32(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
-                           const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
-                           const GdnChunkOps& out, hipStream_t st);
+// bf16 operands of the two walks and what they save for the finish kernel:
+constexpr size_t GDN_REC_ELEMS = 4 * 64 * 128 + 64 * 64;     // elements of one walk record (forward and reverse alike)
+struct GdnBwdSaved {
+  void* fwd_rec;     // forward walk records
+  void* rev_rec;     // reverse walk records
+  float* glast;      // exp(gamma_last)
+  void* s0t;         // [128 value cols][128 key dims] bf16: state entering the chunk, transposed
+  void* ds1t;        // same layout: gradient of the state leaving the chunk
+  void* vns;         // Vn  [64][128] bf16 in matrix-instruction fragment order (gdn_frag_index)
+  void* dvns;        // dVn, same order
+  float* slots;      // [n_slots][hv][128][128] saved node-end states
+  float* slot_grad;  // their gradients (zeroed by the caller)
+};
+// position of element (token i, value column col) inside a chunk's fragment-ordered [64][128] array
+__host__ __device__ inline int gdn_frag_index(int i, int col) {
+  const int dvb = col >> 5, c = col & 31, half = i >> 5, t = (i >> 4) & 1, i16 = i & 15;
+  const int hf = (i16 >> 2) & 1, e = ((i16 >> 3) << 2) | (i16 & 3);
+  return ((((dvb * 2 + half) * 2 + t) * 64 + hf * 32 + c) << 3) | e;
+}
 
 // backward of the gated delta rule (tt_gdn_bwd.hip)
 struct GdnBwdArgs {
@@ -113,6 +128,8 @@ struct GdnBwdArgs {
   float* d_initial_state;            // nullptr or [hv][128][128], overwritten
   void* workspace;
 };
+// prepare kernel (backward form) + forward walk + reverse walk (tt_gdn.hip)
+hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st);
 hipError_t gdn_bwd(const GdnBwdArgs& a, hipStream_t st);
 size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int hk, int hv);
 

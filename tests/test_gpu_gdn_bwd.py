@@ -1,7 +1,9 @@
 """GPU parity: backward of the gated delta rule with tree state routing against the fp64 reverse recurrence.
-The kernels compute in fp32 from the bf16 inputs; dq, dk, dv are rounded to bf16 once at the end (dq, dk after
-the fp32 sum over the value heads of a key head).  Tolerance: rel-L2 <= 2e-2 as for the attention gradients;
-measured: a few 1e-3 on the bf16 outputs (their rounding), below 1e-4 on the fp32 outputs dg, dbeta."""
+The two walks over the chunks round their per-chunk operands and what they save for the per-chunk kernel
+(entering state, Vn, gradient of the leaving state, dVn) to bf16 once each and accumulate in fp32, like the
+forward; the per-chunk kernel computes in fp32; dq, dk, dv are rounded to bf16 at the end (dq, dk after the
+fp32 sum over the value heads of a key head).  Tolerance: rel-L2 <= 2e-2 on every output, as for the attention
+gradients; measured 2.5e-3 .. 3e-3."""
 import numpy as np
 import pytest
 import torch
@@ -39,7 +41,7 @@ def _check(tree, hk, hv, seed):
     got = [t.float().cpu().numpy() for t in got]
     want = S.gdn_tree_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.numpy(), beta.numpy(), m["tok_pred"],
                           d_o.float().numpy())
-    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (2e-2, 2e-2, 2e-2, 1e-3, 1e-3)):
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (2e-2, 2e-2, 2e-2, 2e-2, 2e-2)):
         e = rel_l2(a, b)
         print(f"   {name}: rel-L2 {e:.2e}", flush=True)
         assert np.isfinite(a).all(), name
