@@ -55,13 +55,19 @@ __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p
 __device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
 
 // ---- per-chunk finish ----------------------------------------------------------------------------------
-// acc[r][c] += sum_k fa(i, k) fb(k, j) for i = ty TM + r, j = tx + c (N / TN), over K (a multiple of KS), through
+// acc[r][c] += sum_k fa(i, k) fb(k, j) for i = 4 ty + r, j = tile_col(tx, c), over K (a multiple of KS), through
 // LDS slabs of KS k-values.  AKF / BKF: consecutive threads fetch consecutive k (operand stored with k
 // contiguous) rather than consecutive i / j.  Every thread of the workgroup must call it.
+// Output tile of thread (ty, tx): rows 4 ty .. 4 ty + 3; columns tile_col<N, TN>(tx, c), c = 0 .. TN - 1: groups of four
+// consecutive columns, the groups N / (TN / 4) apart -- every LDS read of the inner loop is one 16-byte read and
+// neighbouring threads read neighbouring 16-byte pieces.
+template <int N, int TN>
+__device__ __forceinline__ int tile_col(int tx, int c) { return (c >> 2) * (N / (TN / 4)) + tx * 4 + (c & 3); }
+
 template <int M, int N, int TM, int TN, bool AKF, bool BKF, class FA, class FB>
 __device__ __forceinline__ void slab_product(int K, FA fa, FB fb, float (&acc)[TM][TN], float* as, float* bs, int tid) {
-  constexpr int NT = N / TN;
-  static_assert((M / TM) * NT == BT, "one output tile per thread");
+  constexpr int NT = N / TN, PA = M + 4, PB = N + 4;      // row pitches: 16-byte aligned rows
+  static_assert((M / TM) * NT == BT && TM == 4 && TN % 4 == 0, "one 4 x TN output tile per thread");
   const int tx = tid % NT, ty = tid / NT;
   for (int k0 = 0; k0 < K; k0 += KS) {
     __syncthreads();
@@ -82,22 +88,25 @@ __device__ __forceinline__ void slab_product(int K, FA fa, FB fb, float (&acc)[T
     for (int p = 0; p < M * KS / BT; p++) {
       const int e = tid + p * BT;
       const int kk = AKF ? e % KS : e / M, i = AKF ? e / KS : e % M;
-      as[kk * (M + 1) + i] = av[p];
+      as[kk * PA + i] = av[p];
     }
 #pragma unroll
     for (int p = 0; p < N * KS / BT; p++) {
       const int e = tid + p * BT;
       const int kk = BKF ? e % KS : e / N, j = BKF ? e / KS : e % N;
-      bs[kk * (N + 1) + j] = bv[p];
+      bs[kk * PB + j] = bv[p];
     }
     __syncthreads();
 #pragma unroll 8
     for (int kk = 0; kk < KS; kk++) {
-      float ar[TM], bc[TN];
+      const float4 a4 = *(const float4*)&as[kk * PA + ty * 4];
+      const float ar[4] = {a4.x, a4.y, a4.z, a4.w};
+      float bc[TN];
 #pragma unroll
-      for (int r = 0; r < TM; r++) ar[r] = as[kk * (M + 1) + ty * TM + r];
-#pragma unroll
-      for (int c = 0; c < TN; c++) bc[c] = bs[kk * (N + 1) + tx + c * NT];
+      for (int c4 = 0; c4 < TN / 4; c4++) {
+        const float4 b4 = *(const float4*)&bs[kk * PB + tile_col<N, TN>(tx, 4 * c4)];
+        bc[4 * c4] = b4.x; bc[4 * c4 + 1] = b4.y; bc[4 * c4 + 2] = b4.z; bc[4 * c4 + 3] = b4.w;
+      }
 #pragma unroll
       for (int r = 0; r < TM; r++)
 #pragma unroll
@@ -116,8 +125,8 @@ constexpr int AP = GC + 1;     // row pitch of the 64 x 64 LDS matrices that are
 constexpr int TP = GC + 4;     // pitch of the transposed A during the solve (rows read as float4)
 
 __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
-  __shared__ float as[KS * (GC + 1)];
-  __shared__ float bs[GC * AP > KS * (GD + 1) ? GC * AP : KS * (GD + 1)];   // between products also: dA o A0
+  __shared__ __attribute__((aligned(16))) float as[KS * (GC + 4)];
+  __shared__ __attribute__((aligned(16))) float bs[GC * AP > KS * (GD + 4) ? GC * AP : KS * (GD + 4)];   // between products also: dA o A0
   __shared__ __attribute__((aligned(16))) float dam[GC * TP];     // A^T during the solve, then dA, then dA beta D
   __shared__ float dpm[GC * AP];                                  // dP, then dP scale D
   __shared__ float gm[GC * AP];                                   // dP o P + dA o A
@@ -177,7 +186,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
     for (int r = 0; r < 4; r++)
 #pragma unroll
-      for (int c = 0; c < 8; c++) X[(ty * 4 + r) * (2 * GD) + GD + tx + c * 16] = -acc[r][c];
+      for (int c = 0; c < 8; c++) X[(ty * 4 + r) * (2 * GD) + GD + tile_col<GD, 8>(tx, c)] = -acc[r][c];
   }
   // A^T into LDS: dam[i][j] = A_ji = beta_j A0_ji  (zero for j <= i)
 #pragma unroll
@@ -232,7 +241,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 4; c++) {
-        const int i = ty * 4 + r, j = tx + c * 16;
+        const int i = ty * 4 + r, j = tile_col<GC, 4>(tx, c);
         dam[i * AP + j] = i > j ? -acc[r][c] : 0.f;
       }
 #pragma unroll
@@ -244,7 +253,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++)
 #pragma unroll
       for (int c = 0; c < 4; c++) {
-        const int i = ty * 4 + r, j = tx + c * 16;
+        const int i = ty * 4 + r, j = tile_col<GC, 4>(tx, c);
         dpm[i * AP + j] = i >= j ? acc[r][c] : 0.f;
       }
   }
@@ -302,7 +311,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
       for (int c = 0; c < 8; c++) {
         acc[r][c] *= f;                               // dQg_i scaled = its contribution to dq_i
-        dot += acc[r][c] * q_at(i, tx + c * 16);      // dQg_i . Qg_i = (scale eg dQg_i) . q_i
+        dot += acc[r][c] * q_at(i, tile_col<GD, 8>(tx, c));      // dQg_i . Qg_i = (scale eg dQg_i) . q_i
       }
       dot = row16_sum(dot);
       if (tx == 0) dg_q[i] = dot;
@@ -312,9 +321,10 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++) {
       const int i = ty * 4 + r;
       if (i < len) {
-        float* dst = a.w.dqh + ((size_t)(tok0 + i) * hv + h) * GD + tx;
+        float* dst = a.w.dqh + ((size_t)(tok0 + i) * hv + h) * GD;
 #pragma unroll
-        for (int c = 0; c < 8; c++) dst[c * 16] = acc[r][c];
+        for (int c4 = 0; c4 < 2; c4++)
+          *(float4*)(dst + tile_col<GD, 8>(tx, 4 * c4)) = make_float4(acc[r][4 * c4], acc[r][4 * c4 + 1], acc[r][4 * c4 + 2], acc[r][4 * c4 + 3]);
       }
     }
   }
@@ -333,7 +343,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
       float dot_kd = 0.f, dot_kb = 0.f;
 #pragma unroll
       for (int c = 0; c < 8; c++) {
-        const int d = tx + c * 16;
+        const int d = tile_col<GD, 8>(tx, c);
         const float kv = k_at(i, d), dkb = X[i * (2 * GD) + GD + d];
         dot_kd += acc[r][c] * kv;
         dot_kb += dkb * kv;
@@ -353,9 +363,10 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     for (int r = 0; r < 4; r++) {
       const int i = ty * 4 + r;
       if (i < len) {
-        float* dst = a.w.dkh + ((size_t)(tok0 + i) * hv + h) * GD + tx;
+        float* dst = a.w.dkh + ((size_t)(tok0 + i) * hv + h) * GD;
 #pragma unroll
-        for (int c = 0; c < 8; c++) dst[c * 16] = acc[r][c];
+        for (int c4 = 0; c4 < 2; c4++)
+          *(float4*)(dst + tile_col<GD, 8>(tx, 4 * c4)) = make_float4(acc[r][4 * c4], acc[r][4 * c4 + 1], acc[r][4 * c4 + 2], acc[r][4 * c4 + 3]);
       }
     }
   }
