@@ -21,8 +21,9 @@
 //                              of every chunk (bf16)
 //   gdn_rscan_kernel           (32 value columns, head): reverse walk in the forward scan's form (bf16 matrix
 //                              instruction, fp32 state gradient in accumulators); saves dS1 and dVn (bf16)
-//   gdn_bwd_finish_kernel      per (chunk, head): everything else, fp32 vector arithmetic with LDS-tiled
-//                              products; dq / dk per value head in fp32
+//   gdn_bwd_finish_kernel      per (chunk, head): everything else in fp32: products on the fp32 matrix
+//                              instruction through LDS slabs, the transposed solve with one lane per column;
+//                              dq / dk per value head in fp32
 //   gdn_bwd_group_sum_kernel   sums dq / dk over the value heads that share a key head, rounds to bf16
 #include <hip/hip_runtime.h>
 #include <algorithm>
@@ -54,88 +55,226 @@ struct KArgs {
 __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
 __device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
 
-// ---- per-chunk finish ----------------------------------------------------------------------------------
-// acc[r][c] += sum_k fa(i, k) fb(k, j) for i = 4 ty + r, j = tile_col(tx, c), over K (a multiple of KS), through
-// LDS slabs of KS k-values.  AKF / BKF: consecutive threads fetch consecutive k (operand stored with k
-// contiguous) rather than consecutive i / j.  Every thread of the workgroup must call it.
-// Output tile of thread (ty, tx): rows 4 ty .. 4 ty + 3; columns tile_col<N, TN>(tx, c), c = 0 .. TN - 1: groups of four
-// consecutive columns, the groups N / (TN / 4) apart -- every LDS read of the inner loop is one 16-byte read and
-// neighbouring threads read neighbouring 16-byte pieces.
-template <int N, int TN>
-__device__ __forceinline__ int tile_col(int tx, int c) { return (c >> 2) * (N / (TN / 4)) + tx * 4 + (c & 3); }
+// fp32 matrix instruction: D (32 x 32) += A (32 x 2) B (2 x 32).  Lane l = 32 hf + c supplies A[row c][k = hf] and
+// B[k = hf][column c] and holds D[(r / 4) * 8 + 4 hf + r % 4][c] in register r.
+__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 acc) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
+__device__ __forceinline__ int tile_row(int r, int hf) { return (r >> 2) * 8 + 4 * hf + (r & 3); }
 
-template <int M, int N, int TM, int TN, bool AKF, bool BKF, class FA, class FB>
-__device__ __forceinline__ void slab_product(int K, FA fa, FB fb, float (&acc)[TM][TN], float* as, float* bs, int tid) {
-  constexpr int NT = N / TN, PA = M + 4, PB = N + 4;      // row pitches: 16-byte aligned rows
-  static_assert((M / TM) * NT == BT && TM == 4 && TN % 4 == 0, "one 4 x TN output tile per thread");
-  const int tx = tid % NT, ty = tid / NT;
+// ---- per-chunk finish ----------------------------------------------------------------------------------
+// Products C (64 x N) += A (64 x K) B (K x N) of a workgroup on the fp32 matrix instruction, operands through LDS
+// slabs of KS k-values fetched element by element through fa(i, k), fb(k, j) (global memory or LDS); the next
+// slab is fetched into registers while the current one is multiplied.  AKF / BKF: consecutive threads fetch
+// consecutive k (operand stored with k contiguous) rather than consecutive i / j.  Wave w holds, in accumulator
+// layout, N = 128: tiles (row block t, column block w), t = 0, 1;  N = 64: the tile (row block w & 1, column block
+// w >> 1).  Every thread of the workgroup must call it.
+template <int N>
+struct TileMap {
+  static constexpr int TPW = N / 64;                     // tiles per wave
+  __device__ static int ib(int w, int t) { return N == 128 ? t : (w & 1); }
+  __device__ static int jb(int w) { return N == 128 ? w : (w >> 1); }
+};
+
+// Slab pitches (floats): rows start 16-byte aligned, and 68 / 132 = 4 (mod 32) spreads 16-byte writes over the banks
+constexpr int PA = GC + 4;
+template <int N> constexpr int pitch_b() { return N + 4; }
+
+// ---- operand loaders ---------------------------------------------------------------------------------------
+// A loader brings one KS-wide slab of an operand from memory into registers (load) and from there into the LDS
+// slab (store): as[kk * PA + i] = A(i, k0 + kk), bs[kk * PB + j] = B(k0 + kk, j).  Memory is read in 16-byte pieces.
+
+// Vn / dVn in fragment order, element (token, value column).  As A: (i, k = column).  As B: (k = column, j = token).
+// One piece = 8 tokens of one column: tokens base .. base + 3 and base + 8 .. base + 11.
+template <int PITCH>
+struct FragLoader {
+  const __bf16* p;
+  typedef bf16x8 Regs;
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+    const int cl = tid & 31, g = tid >> 5;                                   // column inside the slab; (half, t, hf)
+    r = *(const bf16x8*)(p + ((((size_t)(k0 >> 5) * 4 + (g >> 1)) * 64 + (g & 1) * 32 + cl) << 3));
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
+    const int cl = tid & 31, g = tid >> 5;
+    const int base = 32 * (g >> 2) + 16 * ((g >> 1) & 1) + 4 * (g & 1);
+    float* d = lds + cl * PITCH + base;
+    *(float4*)d = make_float4((float)r[0], (float)r[1], (float)r[2], (float)r[3]);
+    *(float4*)(d + 8) = make_float4((float)r[4], (float)r[5], (float)r[6], (float)r[7]);
+  }
+};
+// bf16 rows with the contraction index contiguous, as A: (i, k) = p[i * pitch + k]; rows >= len are zero
+struct RowsKLoaderA {
+  const __bf16* p;
+  int pitch, len;
+  typedef bf16x8 Regs;
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+    const int i = tid >> 2, k8 = (tid & 3) * 8;
+    r = *(const bf16x8*)(p + (size_t)min(i, len - 1) * pitch + k0 + k8);
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
+    const int i = tid >> 2, k8 = (tid & 3) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; e++) lds[(k8 + e) * PA + i] = i < len ? (float)r[e] : 0.f;
+  }
+};
+// fp32 rows with the contraction index contiguous, as A: (i, k) = p[i * pitch + k]
+struct RowsKLoaderA32 {
+  const float* p;
+  int pitch;
+  struct Regs { f32x4 v[2]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, i = piece >> 3, k4 = (piece & 7) * 4;
+      r.v[q] = *(const f32x4*)(p + (size_t)i * pitch + k0 + k4);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, i = piece >> 3, k4 = (piece & 7) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; e++) lds[(k4 + e) * PA + i] = r.v[q][e];
+    }
+  }
+};
+// any A given element by element (LDS-resident matrices): consecutive threads take consecutive i
+template <class F>
+struct FnLoaderA {
+  F f;
+  struct Regs { float v[GC * KS / BT]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < GC * KS / BT; q++) {
+      const int e = tid + q * BT;
+      r.v[q] = f(e % GC, k0 + e / GC);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < GC * KS / BT; q++) {
+      const int e = tid + q * BT;
+      lds[(e / GC) * PA + e % GC] = r.v[q];
+    }
+  }
+};
+template <class F> __device__ __forceinline__ FnLoaderA<F> fn_loader_a(F f) { return FnLoaderA<F>{f}; }
+// bf16 rows of 128 with the output index contiguous, as B (N = 128): (k, j) = p[k * pitch + j]; rows >= len are zero
+struct RowsJLoaderB {
+  const __bf16* p;
+  int pitch, len;
+  struct Regs { bf16x8 v[2]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, kk = piece >> 4, j8 = (piece & 15) * 8;
+      r.v[q] = *(const bf16x8*)(p + (size_t)min(k0 + kk, len - 1) * pitch + j8);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int k0) const {
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, kk = piece >> 4, j8 = (piece & 15) * 8;
+      const bool in = k0 + kk < len;
+      float* d = lds + kk * pitch_b<GD>() + j8;
+      *(float4*)d = in ? make_float4((float)r.v[q][0], (float)r.v[q][1], (float)r.v[q][2], (float)r.v[q][3]) : make_float4(0.f, 0.f, 0.f, 0.f);
+      *(float4*)(d + 4) = in ? make_float4((float)r.v[q][4], (float)r.v[q][5], (float)r.v[q][6], (float)r.v[q][7]) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+};
+// [U | W] rows, fp32, as B (N = 64): (k, j) = k < 128 ? u[j * 128 + k] : w[j * 128 + k - 128]
+struct UwLoaderB {
+  const float *u, *w;
+  struct Regs { f32x4 v[2]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+    const float* src = k0 < GD ? u + k0 : w + (k0 - GD);
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, j = piece >> 3, k4 = (piece & 7) * 4;
+      r.v[q] = *(const f32x4*)(src + (size_t)j * GD + k4);
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int) const {
+#pragma unroll
+    for (int q = 0; q < 2; q++) {
+      const int piece = tid + q * BT, j = piece >> 3, k4 = (piece & 7) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; e++) lds[(k4 + e) * pitch_b<GC>() + j] = r.v[q][e];
+    }
+  }
+};
+// Vn as B (N = 64)
+struct FragLoaderB : FragLoader<pitch_b<GC>()> {
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int) const { FragLoader<pitch_b<GC>()>::store(lds, tid, r); }
+};
+
+template <int N, int K, class LA, class LB>
+__device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 (&acc)[N / 64], float* as, float* bs, int tid_in) {
+  constexpr int PB = pitch_b<N>();
+  // The fetch offsets are functions of the thread id alone.  Hidden behind an opaque copy they are computed at each
+  // call; otherwise the compiler computes those of all calls at the top of the kernel and keeps them in registers
+  // throughout (measured: 174 spilled registers at two waves per SIMD).
+  int tid = tid_in;
+  asm volatile("" : "+v"(tid));
+  typedef TileMap<N> TM;
+  const int lane = tid & 63, c = lane & 31, hf = lane >> 5, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  typename LA::Regs ra;
+  typename LB::Regs rb;
+  la.load(0, tid, ra);
+  lb.load(0, tid, rb);
+#pragma unroll 1
   for (int k0 = 0; k0 < K; k0 += KS) {
+    __syncthreads();                   // the previous slab (or whatever used the slab arrays before) has been read
+    la.store(as, tid, ra);
+    lb.store(bs, tid, rb, k0);
     __syncthreads();
-    float av[M * KS / BT], bv[N * KS / BT];
-#pragma unroll
-    for (int p = 0; p < M * KS / BT; p++) {
-      const int e = tid + p * BT;
-      const int kk = AKF ? e % KS : e / M, i = AKF ? e / KS : e % M;
-      av[p] = fa(i, k0 + kk);
-    }
-#pragma unroll
-    for (int p = 0; p < N * KS / BT; p++) {
-      const int e = tid + p * BT;
-      const int kk = BKF ? e % KS : e / N, j = BKF ? e / KS : e % N;
-      bv[p] = fb(k0 + kk, j);
-    }
-#pragma unroll
-    for (int p = 0; p < M * KS / BT; p++) {
-      const int e = tid + p * BT;
-      const int kk = AKF ? e % KS : e / M, i = AKF ? e / KS : e % M;
-      as[kk * PA + i] = av[p];
-    }
-#pragma unroll
-    for (int p = 0; p < N * KS / BT; p++) {
-      const int e = tid + p * BT;
-      const int kk = BKF ? e % KS : e / N, j = BKF ? e / KS : e % N;
-      bs[kk * PB + j] = bv[p];
-    }
-    __syncthreads();
+    // the next slab is on its way while this one is multiplied (the last step fetches its own slab again: a
+    // branch around the loads would put their wait at its end, in front of the multiplication)
+    const int kn = k0 + KS < K ? k0 + KS : K - KS;
+    la.load(kn, tid, ra);
+    lb.load(kn, tid, rb);
 #pragma unroll 8
-    for (int kk = 0; kk < KS; kk++) {
-      const float4 a4 = *(const float4*)&as[kk * PA + ty * 4];
-      const float ar[4] = {a4.x, a4.y, a4.z, a4.w};
-      float bc[TN];
+    for (int s = 0; s < KS / 2; s++) {
+      const int k = hf * (KS / 2) + s;
+      const float b = bs[k * PB + 32 * TM::jb(w) + c];
 #pragma unroll
-      for (int c4 = 0; c4 < TN / 4; c4++) {
-        const float4 b4 = *(const float4*)&bs[kk * PB + tile_col<N, TN>(tx, 4 * c4)];
-        bc[4 * c4] = b4.x; bc[4 * c4 + 1] = b4.y; bc[4 * c4 + 2] = b4.z; bc[4 * c4 + 3] = b4.w;
-      }
-#pragma unroll
-      for (int r = 0; r < TM; r++)
-#pragma unroll
-        for (int c = 0; c < TN; c++) acc[r][c] = fmaf(ar[r], bc[c], acc[r][c]);
+      for (int t = 0; t < TM::TPW; t++) acc[t] = mfma_f32(as[k * PA + 32 * TM::ib(w, t) + c], b, acc[t]);
     }
   }
 }
 
-// sum over the 16 consecutive lanes that share a row of a [64][128] tile
-__device__ __forceinline__ float row16_sum(float x) {
-  x += __shfl_xor(x, 1); x += __shfl_xor(x, 2); x += __shfl_xor(x, 4); x += __shfl_xor(x, 8);
+// Sum over the 32 lanes of a half wave (the lanes that hold one row of an accumulator tile), with data-parallel
+// lane moves instead of LDS-routed shuffles (the kernel forms 96 such sums per lane).  The total arrives in the
+// upper 16 lanes of the half (lanes 16 .. 31 and 48 .. 63).
+template <int CTRL, int ROW_MASK = 0xf>
+__device__ __forceinline__ float dpp_move(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float half_wave_sum(float x) {
+  x += dpp_move<0xb1>(x);          // quad_perm [1,0,3,2]: lane ^ 1
+  x += dpp_move<0x4e>(x);          // quad_perm [2,3,0,1]: lane ^ 2
+  x += dpp_move<0x141>(x);         // row_half_mirror: the other quad of each group of 8
+  x += dpp_move<0x140>(x);         // row_mirror: the other group of 8 of each row of 16
+  x += dpp_move<0x142, 0xa>(x);    // row_bcast15 into rows 1 and 3: adds the total of the row below
   return x;
 }
+constexpr int HALF_SUM_LANE = 16;  // a lane position (inside its half wave) that holds half_wave_sum's result
 
 constexpr int AP = GC + 1;     // row pitch of the 64 x 64 LDS matrices that are read along rows and columns
 constexpr int TP = GC + 4;     // pitch of the transposed A during the solve (rows read as float4)
 
-__global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
-  __shared__ __attribute__((aligned(16))) float as[KS * (GC + 4)];
-  __shared__ __attribute__((aligned(16))) float bs[GC * AP > KS * (GD + 4) ? GC * AP : KS * (GD + 4)];   // between products also: dA o A0
+__global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
+  __shared__ __attribute__((aligned(16))) float as[KS * PA];
+  __shared__ __attribute__((aligned(16))) float bs[GC * AP > KS * pitch_b<GD>() ? GC * AP : KS * pitch_b<GD>()];   // between products also: dA o A0
   __shared__ __attribute__((aligned(16))) float dam[GC * TP];     // A^T during the solve, then dA, then dA beta D
   __shared__ float dpm[GC * AP];                                  // dP, then dP scale D
   __shared__ float gm[GC * AP];                                   // dP o P + dA o A
   __shared__ float gam[GC], bet[GC], eg[GC], el[GC];
-  __shared__ float dg_row[GC], dg_col[GC], dg_q[GC], dg_kd[GC], dg_kb[GC], db_a[GC], db_kb[GC], db_v[GC], dgam[GC];
-  __shared__ float red[BT];
+  __shared__ float dg_row[GC], dg_col[GC], db_a[GC], db_v[GC], dgam[GC];
+  __shared__ float dot_q[4][GC], dot_kd[4][GC], dot_kb[4][GC];    // per-wave parts of row dot products
+  float* red = as;                                                // [BT], after the last product
 
   const int chunk = blockIdx.x, h = blockIdx.y;
-  const int tid = threadIdx.x & (BT - 1);
+  const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
   const size_t op = (size_t)h * nc + chunk;
   const int tok0 = a.b.chunk_tok0[chunk], len = a.b.chunk_len[chunk];
@@ -160,9 +299,11 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
   const __bf16* vb = (const __bf16*)a.b.v + (size_t)tok0 * vrow + (size_t)h * GD;
   const __bf16* dob = (const __bf16*)a.b.d_o + (size_t)tok0 * vrow + (size_t)h * GD;
   // rows past the chunk's length read a valid row and are then zeroed (no load sits inside a branch)
-  auto q_at = [&](int i, int d) { const float x = (float)qb[(size_t)min(i, len - 1) * qrow + d]; return i < len ? x : 0.f; };
-  auto k_at = [&](int i, int d) { const float x = (float)kb[(size_t)min(i, len - 1) * qrow + d]; return i < len ? x : 0.f; };
-  auto do_at = [&](int i, int c) { const float x = (float)dob[(size_t)min(i, len - 1) * vrow + c]; return i < len ? x : 0.f; };
+  // (32-bit offsets: a chunk spans at most 64 rows of at most 65535 * 128 elements)
+  const int qrow32 = (int)qrow, vrow32 = (int)vrow;
+  auto q_at = [&](int i, int d) { const float x = (float)qb[min(i, len - 1) * qrow32 + d]; return i < len ? x : 0.f; };
+  auto k_at = [&](int i, int d) { const float x = (float)kb[min(i, len - 1) * qrow32 + d]; return i < len ? x : 0.f; };
+  auto do_at = [&](int i, int cc) { const float x = (float)dob[min(i, len - 1) * vrow32 + cc]; return i < len ? x : 0.f; };
 
   const float glast = a.w.ops.gam[op * GC + GC - 1];
   const float el_last = __expf(glast);
@@ -173,20 +314,17 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     eg[tid] = __expf(gv);
     el[tid] = __expf(glast - gv);
   }
+  typedef TileMap<GD> T128;
+  typedef TileMap<GC> T64;
 
   // dW = -dVn S0^T  -> right half of X
   {
-    float acc[4][8];
+    f32x16 acc[2] = {zero16(), zero16()};
+    slab_product<GD, GD>(FragLoader<PA>{dvns}, RowsJLoaderB{s0t, GD, GD}, acc, as, bs, tid);
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int t = 0; t < 2; t++)
 #pragma unroll
-      for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, false>(GD, dvn_at, [&](int k, int j) { return s0_at(j, k); }, acc, as, bs, tid);
-    const int tx = tid & 15, ty = tid >> 4;
-#pragma unroll
-    for (int r = 0; r < 4; r++)
-#pragma unroll
-      for (int c = 0; c < 8; c++) X[(ty * 4 + r) * (2 * GD) + GD + tile_col<GD, 8>(tx, c)] = -acc[r][c];
+      for (int r = 0; r < 16; r++) X[(32 * T128::ib(w, t) + tile_row(r, hf)) * (2 * GD) + GD + 32 * T128::jb(w) + c] = -acc[t][r];
   }
   // A^T into LDS: dam[i][j] = A_ji = beta_j A0_ji  (zero for j <= i)
 #pragma unroll
@@ -198,15 +336,15 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
 
   // (I + A)^T x = rhs by back substitution, one lane per column of [dVn | dW]:  x_i = rhs_i - sum_{j>i} A_ji x_j
   {
-    const int c = tid;
+    const int cx = tid;
     float x[GC];
     // right-hand sides: 64 independent loads per lane in one straight-line block
-    if (c < GD) {
+    if (cx < GD) {
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = dvn_at(i, c);
+      for (int i = 0; i < GC; i++) x[i] = dvn_at(i, cx);
     } else {
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = X[i * (2 * GD) + c];
+      for (int i = 0; i < GC; i++) x[i] = X[i * (2 * GD) + cx];
     }
 #pragma unroll
     for (int i = GC - 2; i >= 0; i--) {
@@ -222,40 +360,26 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
       x[i] = v;
     }
 #pragma unroll
-    for (int i = 0; i < GC; i++) X[i * (2 * GD) + c] = x[i];
+    for (int i = 0; i < GC; i++) X[i * (2 * GD) + cx] = x[i];
   }
   __syncthreads();
 
   // dA = strictly-lower( -[dVb | dKb] [U | W]^T ),  dP = tril( dO Vn^T )
   {
-    float acc[4][4];
+    f32x16 acc[1] = {zero16()};
+    slab_product<GC, 2 * GD>(RowsKLoaderA32{X, 2 * GD}, UwLoaderB{U, Wm}, acc, as, bs, tid);
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int r = 0; r < 16; r++) {
+      const int i = 32 * T64::ib(w, 0) + tile_row(r, hf), j = 32 * T64::jb(w) + c;
+      dam[i * AP + j] = i > j ? -acc[0][r] : 0.f;
+    }
+    acc[0] = zero16();
+    slab_product<GC, GD>(RowsKLoaderA{dob, vrow32, len}, FragLoaderB{{vns}}, acc, as, bs, tid);
 #pragma unroll
-      for (int c = 0; c < 4; c++) acc[r][c] = 0.f;
-    slab_product<GC, GC, 4, 4, true, true>(2 * GD, [&](int i, int k) { return X[i * (2 * GD) + k]; },
-                                           [&](int k, int j) { return *(k < GD ? U + j * GD + k : Wm + j * GD + (k - GD)); }, acc, as, bs,
-                                           tid);
-    const int tx = tid & 15, ty = tid >> 4;
-#pragma unroll
-    for (int r = 0; r < 4; r++)
-#pragma unroll
-      for (int c = 0; c < 4; c++) {
-        const int i = ty * 4 + r, j = tile_col<GC, 4>(tx, c);
-        dam[i * AP + j] = i > j ? -acc[r][c] : 0.f;
-      }
-#pragma unroll
-    for (int r = 0; r < 4; r++)
-#pragma unroll
-      for (int c = 0; c < 4; c++) acc[r][c] = 0.f;
-    slab_product<GC, GC, 4, 4, true, true>(GD, do_at, [&](int k, int j) { return vn_at(j, k); }, acc, as, bs, tid);
-#pragma unroll
-    for (int r = 0; r < 4; r++)
-#pragma unroll
-      for (int c = 0; c < 4; c++) {
-        const int i = ty * 4 + r, j = tile_col<GC, 4>(tx, c);
-        dpm[i * AP + j] = i >= j ? acc[r][c] : 0.f;
-      }
+    for (int r = 0; r < 16; r++) {
+      const int i = 32 * T64::ib(w, 0) + tile_row(r, hf), j = 32 * T64::jb(w) + c;
+      dpm[i * AP + j] = i >= j ? acc[0][r] : 0.f;
+    }
   }
   __syncthreads();
 
@@ -294,81 +418,65 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
   }
   // (the first slab_product below starts with a barrier)
 
-  const int tx = tid & 15, ty = tid >> 4;
   // dq_i = scale exp(gamma_i) (dO S0^T)_i + sum_j (dP scale D)_ij k_j
   {
-    float acc[4][8];
+    f32x16 acc[2] = {zero16(), zero16()};
+    slab_product<GD, GD>(RowsKLoaderA{dob, vrow32, len}, RowsJLoaderB{s0t, GD, GD}, acc, as, bs, tid);
+    const int j = 32 * T128::jb(w) + c;
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int t = 0; t < 2; t++) {
+      __builtin_amdgcn_sched_barrier(0);          // one tile's loads at a time (register pressure)
 #pragma unroll
-      for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, false>(GD, do_at, [&](int k, int j) { return s0_at(j, k); }, acc, as, bs, tid);
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int i = ty * 4 + r;
-      const float f = scale * eg[i];
-      float dot = 0.f;
-#pragma unroll
-      for (int c = 0; c < 8; c++) {
-        acc[r][c] *= f;                               // dQg_i scaled = its contribution to dq_i
-        dot += acc[r][c] * q_at(i, tile_col<GD, 8>(tx, c));      // dQg_i . Qg_i = (scale eg dQg_i) . q_i
-      }
-      dot = row16_sum(dot);
-      if (tx == 0) dg_q[i] = dot;
-    }
-    slab_product<GC, GD, 4, 8, true, false>(GC, [&](int i, int k) { return dpm[i * AP + k]; }, k_at, acc, as, bs, tid);
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int i = ty * 4 + r;
-      if (i < len) {
-        float* dst = a.w.dqh + ((size_t)(tok0 + i) * hv + h) * GD;
-#pragma unroll
-        for (int c4 = 0; c4 < 2; c4++)
-          *(float4*)(dst + tile_col<GD, 8>(tx, 4 * c4)) = make_float4(acc[r][4 * c4], acc[r][4 * c4 + 1], acc[r][4 * c4 + 2], acc[r][4 * c4 + 3]);
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
+        acc[t][r] *= scale * eg[i];                                 // scale eg dQg_i: its contribution to dq_i
+        const float dot = half_wave_sum(acc[t][r] * q_at(i, j));    // dQg_i . Qg_i = (scale eg dQg_i) . q_i
+        if (c == HALF_SUM_LANE) dot_q[w][i] = dot;
       }
     }
+    slab_product<GD, GC>(fn_loader_a([&](int i, int k) { return dpm[i * AP + k]; }), RowsJLoaderB{kb, qrow32, len}, acc, as, bs, tid);
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
+        if (i < len) a.w.dqh[((size_t)(tok0 + i) * hv + h) * GD + j] = acc[t][r];
+      }
   }
+  __builtin_amdgcn_sched_barrier(0);
   // dk_j = el_j (Vn dS1^T)_j + beta_j eg_j dKb_j + sum_i (dP scale D)_ij q_i + sum_i (MA_ij + MA_ji) k_i
   {
-    float acc[4][8];
+    f32x16 acc[2] = {zero16(), zero16()};
+    slab_product<GD, GD>(FragLoader<PA>{vns}, RowsJLoaderB{ds1t, GD, GD}, acc, as, bs, tid);
+    int zz = 0;
+    asm volatile("" : "+v"(zz));          // row offsets are recomputed here, not kept in registers since the dq block
+    const int d = 32 * T128::jb(w) + c + zz;
 #pragma unroll
-    for (int r = 0; r < 4; r++)
+    for (int t = 0; t < 2; t++) {
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int c = 0; c < 8; c++) acc[r][c] = 0.f;
-    slab_product<GC, GD, 4, 8, true, false>(GD, vn_at, [&](int k, int j) { return ds1_at(j, k); }, acc, as, bs, tid);
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int i = ty * 4 + r;
-      const float fe = el[i], fb_ = bet[i] * eg[i];
-      float dot_kd = 0.f, dot_kb = 0.f;
-#pragma unroll
-      for (int c = 0; c < 8; c++) {
-        const int d = tile_col<GD, 8>(tx, c);
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
+        const float fe = el[i], fkb = bet[i] * eg[i];
         const float kv = k_at(i, d), dkb = X[i * (2 * GD) + GD + d];
-        dot_kd += acc[r][c] * kv;
-        dot_kb += dkb * kv;
-        acc[r][c] = fe * acc[r][c] + fb_ * dkb;
-      }
-      dot_kd = row16_sum(dot_kd);
-      dot_kb = row16_sum(dot_kb);
-      if (tx == 0) {
-        dg_kd[i] = fe * dot_kd;                 // dKd_i . Kd_i
-        db_kb[i] = eg[i] * dot_kb;
-        dg_kb[i] = fb_ * dot_kb;                // dKb_i . (beta eg K)_i
+        const float s_kd = half_wave_sum(acc[t][r] * kv), s_kb = half_wave_sum(dkb * kv);
+        if (c == HALF_SUM_LANE) {
+          dot_kd[w][i] = s_kd;
+          dot_kb[w][i] = s_kb;
+        }
+        acc[t][r] = fe * acc[t][r] + fkb * dkb;
       }
     }
-    slab_product<GC, GD, 4, 8, false, false>(GC, [&](int i, int k) { return dpm[k * AP + i]; }, q_at, acc, as, bs, tid);
-    slab_product<GC, GD, 4, 8, false, false>(GC, [&](int i, int k) { return dam[i * AP + k] + dam[k * AP + i]; }, k_at, acc, as, bs, tid);
+    slab_product<GD, GC>(fn_loader_a([&](int i, int k) { return dpm[k * AP + i]; }), RowsJLoaderB{qb, qrow32, len}, acc, as, bs, tid);
+    slab_product<GD, GC>(fn_loader_a([&](int i, int k) { return dam[i * AP + k] + dam[k * AP + i]; }), RowsJLoaderB{kb, qrow32, len}, acc, as, bs,
+                         tid);
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
-      const int i = ty * 4 + r;
-      if (i < len) {
-        float* dst = a.w.dkh + ((size_t)(tok0 + i) * hv + h) * GD;
+    for (int t = 0; t < 2; t++)
 #pragma unroll
-        for (int c4 = 0; c4 < 2; c4++)
-          *(float4*)(dst + tile_col<GD, 8>(tx, 4 * c4)) = make_float4(acc[r][4 * c4], acc[r][4 * c4 + 1], acc[r][4 * c4 + 2], acc[r][4 * c4 + 3]);
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
+        if (i < len) a.w.dkh[((size_t)(tok0 + i) * hv + h) * GD + d] = acc[t][r];
       }
-    }
   }
   // dv_i = beta_i dVb_i,  dbeta_i += dVb_i . v_i
   {
@@ -391,6 +499,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     if ((tid & 3) == 0) db_v[i] = i < len ? dot : 0.f;
   }
   // <dS1, S0>: gamma_last also scales the state that is carried over
+  __syncthreads();                     // every wave is done with the slab arrays (red lives there)
   {
     float s = 0.f;
 #pragma unroll
@@ -407,20 +516,22 @@ __global__ __launch_bounds__(BT) void gdn_bwd_finish_kernel(KArgs a) {
     __syncthreads();
   }
   if (tid < GC) {
-    float v = dg_row[tid] - dg_col[tid] + dg_q[tid] - dg_kd[tid] + dg_kb[tid];
-    if (tid == GC - 1) {
-      float s = el_last * red[0];
-      for (int i = 0; i < GC; i++) s += dg_kd[i];
-      v += s;
-    }
-    dgam[tid] = v;
+    // row dot products: the four waves hold a quarter of the columns each
+    const float dq_ = dot_q[0][tid] + dot_q[1][tid] + dot_q[2][tid] + dot_q[3][tid];
+    const float dkd = el[tid] * (dot_kd[0][tid] + dot_kd[1][tid] + dot_kd[2][tid] + dot_kd[3][tid]);      // dKd_i . Kd_i
+    const float dkb = dot_kb[0][tid] + dot_kb[1][tid] + dot_kb[2][tid] + dot_kb[3][tid];                  // dKb_i . k_i
+    dgam[tid] = dg_row[tid] - dg_col[tid] + dq_ - dkd + bet[tid] * eg[tid] * dkb;
+    red[64 + tid] = dkd;                                  // red[0] is the state inner product; 64.. are free now
+    red[128 + tid] = db_a[tid] + eg[tid] * dkb + db_v[tid];
   }
   __syncthreads();
   if (tid < len) {
     float s = 0.f;
-    for (int i = tid; i < GC; i++) s += dgam[i];        // gamma_i = sum of g_j over j <= i
-    a.b.dg[(size_t)(tok0 + tid) * hv + h] = s;
-    a.b.dbeta[(size_t)(tok0 + tid) * hv + h] = db_a[tid] + db_kb[tid] + db_v[tid];
+    for (int i = tid; i < GC; i++) s += dgam[i];          // gamma_i = sum of g_j over j <= i
+    float last = el_last * red[0];                        // what reaches every g through gamma_last
+    for (int i = 0; i < GC; i++) last += red[64 + i];
+    a.b.dg[(size_t)(tok0 + tid) * hv + h] = s + last;
+    a.b.dbeta[(size_t)(tok0 + tid) * hv + h] = red[128 + tid];
   }
 }
 
