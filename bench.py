@@ -412,16 +412,17 @@ def main():
             ev[1].synchronize()
             bt = T.kernel_timing_read()
             T.kernel_timing_enable(False)
-            # fp32 multiply-adds per chunk and head of the backward as written (recomputed forward walk included)
-            bwd_flop = 2.0 * (64 * 128 * 128 * 2            # forward walk: W S0, Kd^T Vn
-                              + 64 * 64 * 128 + 64 * 128 * 128 * 3   # reverse walk: P^T dO, Kd dS1, Qg^T dO, W^T dVn
+            # multiply-adds per chunk and head of the backward as written (the forward walk it recomputes included)
+            bwd_flop = 2.0 * (2 * 64 * 64 * 128                       # prepare: K K^T, Q K^T
+                              + 64 * 128 * 128 * 2                    # forward walk: W S0, Kd^T Vn
+                              + 64 * 64 * 128 + 64 * 128 * 128 * 3    # reverse walk: P^T dO, Kd dS1, Qg^T dO, W^T dVn
                               + 64 * 128 * 128 * 3 + 64 * 64 * 256 + 64 * 64 * 128   # finish: dW, dQg, dKd, dA, dP
-                              + 64 * 64 * 128 * 3 + 64 * 64 * 128)   # products with dP and dA, the two triangular solves
+                              + 64 * 64 * 128 * 3 + 64 * 64 * 128)    # products with dP and dA, the two triangular solves
             b_ms = ev[0].elapsed_time(ev[1]) / n_it
             gdn.update({"ms_bwd": round(b_ms, 4),
-                        "ms_bwd_kernels": {"prepare_f32": round(bt["gdn_prepare"][0] / n_it, 4), "forward_walk": round(bt["gdn_bwd_fscan"][0] / n_it, 4),
+                        "ms_bwd_kernels": {"prepare": round(bt["gdn_prepare"][0] / n_it, 4), "forward_walk": round(bt["gdn_bwd_fscan"][0] / n_it, 4),
                                            "reverse_walk": round(bt["gdn_bwd_rscan"][0] / n_it, 4), "finish": round(bt["gdn_bwd_finish"][0] / n_it, 4)},
-                        "bwd_fp32_tflops": round(bwd_flop * gplan.n_chunks * ghv / (b_ms * 1e-3) / 1e12, 2),
+                        "bwd_tflops": round(bwd_flop * gplan.n_chunks * ghv / (b_ms * 1e-3) / 1e12, 2),
                         "bwd_workspace_mb": round(bws.numel() / 1e6, 1)})
             del gdo, bws
         del gq, gk, gv, go
