@@ -65,6 +65,13 @@ def _lib() -> ctypes.CDLL:
             raise ImportError(
                 f"{path} is missing: build it with `python -m paper_2511_00413_amd.build` "
                 "(there is no fallback implementation)")
+        # The library and PyTorch must share one HIP runtime.  PyTorch ships its own copy under the same soname, so
+        # whichever is loaded first serves both; with the system's copy loaded first, device calls made after
+        # `import torch` have failed with "no ROCm-capable device".  Load PyTorch's first when it is there.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = ctypes.CDLL(path)
         lib.tt_last_error.restype = ctypes.c_char_p
         lib.tt_version.restype = ctypes.c_int32
