@@ -64,3 +64,11 @@ def test_branch_point_inside_deep_tree():
     """Several children per node and zero-length nodes: slots are reused, gradients meet at branch points."""
     t = W.random_tree(991, n_nodes=24, lo=0, hi=90, n_roots=2, p_zero=0.2)
     _check(t, 1, 2, 7)
+
+
+@pytest.mark.parametrize("hk,hv", [(3, 3), (2, 8), (8, 8)])
+def test_head_layouts(hk, hv):
+    """One value head per key head (no group sum), four per key head, and a head count that is a multiple of
+    eight (the workgroup-to-head mapping differs there)."""
+    t = W.random_tree(870 + hv, n_nodes=7, lo=1, hi=100, p_zero=0.1)
+    _check(t, hk, hv, 40 + hk)
