@@ -70,6 +70,8 @@ constexpr size_t REC_ELEMS = 4 * GC * GD + GC * GC;      // bf16 elements per re
 // [128][64], P^T [64][64], dO^T [128 value cols][64]
 constexpr size_t REV_KD = 0, REV_WTN = GC * GD, REV_QGT = 2 * GC * GD, REV_PT = 3 * GC * GD, REV_DOT = 3 * GC * GD + GC * GC;
 constexpr size_t REV_ELEMS = 4 * GC * GD + GC * GC;
+static_assert(REC_ELEMS == GDN_REC_ELEMS && REV_ELEMS == GDN_REC_ELEMS && REC_UT == GDN_REC_UT && REV_WTN == GDN_REV_WTN,
+              "record layout shared with the finish kernel");
 __device__ __forceinline__ size_t op_index(const GdnArgs& a, int chunk, int h) { return (size_t)h * a.n_chunks + chunk; }
 
 // BWD: additionally the unrounded quantities the backward's finish kernel reads (GdnChunkOps) and the reverse
@@ -237,10 +239,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       }
     }
     if constexpr (BWD) {
-      // U and W unrounded, row-major (lanes = consecutive columns); -W^T for the reverse walk
-      float* rowmajor = (c < GD ? a.f32.u : a.f32.w) + op * (GC * GD) + (c & (GD - 1));
-#pragma unroll
-      for (int i = 0; i < GC; i++) rowmajor[i * GD] = x[i];
+      // -W^T for the reverse walk (and, like U^T below, for the finish kernel)
       if (c >= GD) {
         __bf16* dst = a.rev + op * REV_ELEMS + REV_WTN + (c - GD) * GC;
 #pragma unroll

@@ -16,7 +16,7 @@
 //
 // Kernels (the first three live in tt_gdn.hip with the forward's):
 //   gdn_prepare_kernel<true>   per (chunk, head): the forward walk's bf16 record, the reverse walk's bf16 record
-//                              (Kd, -W^T, Qg^T, P^T, dO^T) and gamma, A0, P, U, W unrounded
+//                              (Kd, -W^T, Qg^T, P^T, dO^T) and gamma, A0, P unrounded
 //   gdn_scan_kernel<true>      (32 value columns, head): the forward scan without its output; saves S0 and Vn
 //                              of every chunk (bf16)
 //   gdn_rscan_kernel           (32 value columns, head): reverse walk in the forward scan's form (bf16 matrix
@@ -43,7 +43,7 @@ constexpr int KS = 32;               // k-slab of the LDS-tiled products of the 
 struct BwdWs {
   GdnChunkOps ops;
   GdnBwdSaved sv;
-  float* x;          // per (head, chunk) [64][256]: [dW] on the way in, [dVb | dKb] after the transposed solve
+  __bf16* x;         // per (head, chunk) [64][256]: [dW] on the way in, [dVb | dKb] after the transposed solve
   float* dqh;        // [N][hv][128] per-value-head dq, dk
   float* dkh;
 };
@@ -115,27 +115,6 @@ struct RowsKLoaderA {
     for (int e = 0; e < 8; e++) lds[(k8 + e) * PA + i] = i < len ? (float)r[e] : 0.f;
   }
 };
-// fp32 rows with the contraction index contiguous, as A: (i, k) = p[i * pitch + k]
-struct RowsKLoaderA32 {
-  const float* p;
-  int pitch;
-  struct Regs { f32x4 v[2]; };
-  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      const int piece = tid + q * BT, i = piece >> 3, k4 = (piece & 7) * 4;
-      r.v[q] = *(const f32x4*)(p + (size_t)i * pitch + k0 + k4);
-    }
-  }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      const int piece = tid + q * BT, i = piece >> 3, k4 = (piece & 7) * 4;
-#pragma unroll
-      for (int e = 0; e < 4; e++) lds[(k4 + e) * PA + i] = r.v[q][e];
-    }
-  }
-};
 // any A given element by element (LDS-resident matrices): consecutive threads take consecutive i
 template <class F>
 struct FnLoaderA {
@@ -180,25 +159,20 @@ struct RowsJLoaderB {
     }
   }
 };
-// [U | W] rows, fp32, as B (N = 64): (k, j) = k < 128 ? u[j * 128 + k] : w[j * 128 + k - 128]
+// [U | W]^T from the walks' bf16 records, as B (N = 64): (k, j) = k < 128 ? U^T[k][j] : -(-W^T)[k - 128][j]
 struct UwLoaderB {
-  const float *u, *w;
-  struct Regs { f32x4 v[2]; };
+  const __bf16 *ut, *wtn;
+  typedef bf16x8 Regs;
   __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
-    const float* src = k0 < GD ? u + k0 : w + (k0 - GD);
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      const int piece = tid + q * BT, j = piece >> 3, k4 = (piece & 7) * 4;
-      r.v[q] = *(const f32x4*)(src + (size_t)j * GD + k4);
-    }
+    const int kk = tid >> 3, j8 = (tid & 7) * 8;
+    r = *(const bf16x8*)((k0 < GD ? ut + (size_t)(k0 + kk) * GC : wtn + (size_t)(k0 - GD + kk) * GC) + j8);
   }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int) const {
-#pragma unroll
-    for (int q = 0; q < 2; q++) {
-      const int piece = tid + q * BT, j = piece >> 3, k4 = (piece & 7) * 4;
-#pragma unroll
-      for (int e = 0; e < 4; e++) lds[(k4 + e) * pitch_b<GC>() + j] = r.v[q][e];
-    }
+  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int k0) const {
+    const int kk = tid >> 3, j8 = (tid & 7) * 8;
+    const float sg = k0 < GD ? 1.f : -1.f;
+    float* d = lds + kk * pitch_b<GC>() + j8;
+    *(float4*)d = make_float4(sg * (float)r[0], sg * (float)r[1], sg * (float)r[2], sg * (float)r[3]);
+    *(float4*)(d + 4) = make_float4(sg * (float)r[4], sg * (float)r[5], sg * (float)r[6], sg * (float)r[7]);
   }
 };
 // Vn as B (N = 64)
@@ -279,8 +253,8 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   const size_t op = (size_t)h * nc + chunk;
   const int tok0 = a.b.chunk_tok0[chunk], len = a.b.chunk_len[chunk];
   const float scale = a.b.scale;
-  const float* U = a.w.ops.u + op * (GC * GD);
-  const float* Wm = a.w.ops.w + op * (GC * GD);
+  const __bf16* ut = (const __bf16*)a.w.sv.fwd_rec + op * GDN_REC_ELEMS + GDN_REC_UT;
+  const __bf16* wtn = (const __bf16*)a.w.sv.rev_rec + op * GDN_REC_ELEMS + GDN_REV_WTN;
   const float* A0 = a.w.ops.a0 + op * (GC * GC);
   const float* Pm = a.w.ops.p + op * (GC * GC);
   // saved by the walks (bf16): S0 and dS1 transposed [value col][key dim], Vn and dVn in fragment order
@@ -292,7 +266,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   auto ds1_at = [&](int d, int cc) { return (float)ds1t[cc * GD + d]; };
   auto vn_at = [&](int i, int cc) { return (float)vns[gdn_frag_index(i, cc)]; };
   auto dvn_at = [&](int i, int cc) { return (float)dvns[gdn_frag_index(i, cc)]; };
-  float* X = a.w.x + op * (GC * 2 * GD);
+  __bf16* X = a.w.x + op * (GC * 2 * GD);
   const size_t qrow = (size_t)a.b.hk * GD, vrow = (size_t)hv * GD;
   const __bf16* qb = (const __bf16*)a.b.q + (size_t)tok0 * qrow + (size_t)kh * GD;
   const __bf16* kb = (const __bf16*)a.b.k + (size_t)tok0 * qrow + (size_t)kh * GD;
@@ -324,7 +298,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
     for (int t = 0; t < 2; t++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) X[(32 * T128::ib(w, t) + tile_row(r, hf)) * (2 * GD) + GD + 32 * T128::jb(w) + c] = -acc[t][r];
+      for (int r = 0; r < 16; r++) X[(32 * T128::ib(w, t) + tile_row(r, hf)) * (2 * GD) + GD + 32 * T128::jb(w) + c] = (__bf16)(-acc[t][r]);
   }
   // A^T into LDS: dam[i][j] = A_ji = beta_j A0_ji  (zero for j <= i)
 #pragma unroll
@@ -344,7 +318,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
       for (int i = 0; i < GC; i++) x[i] = dvn_at(i, cx);
     } else {
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = X[i * (2 * GD) + cx];
+      for (int i = 0; i < GC; i++) x[i] = (float)X[i * (2 * GD) + cx];
     }
 #pragma unroll
     for (int i = GC - 2; i >= 0; i--) {
@@ -360,14 +334,14 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
       x[i] = v;
     }
 #pragma unroll
-    for (int i = 0; i < GC; i++) X[i * (2 * GD) + cx] = x[i];
+    for (int i = 0; i < GC; i++) X[i * (2 * GD) + cx] = (__bf16)x[i];
   }
   __syncthreads();
 
   // dA = strictly-lower( -[dVb | dKb] [U | W]^T ),  dP = tril( dO Vn^T )
   {
     f32x16 acc[1] = {zero16()};
-    slab_product<GC, 2 * GD>(RowsKLoaderA32{X, 2 * GD}, UwLoaderB{U, Wm}, acc, as, bs, tid);
+    slab_product<GC, 2 * GD>(RowsKLoaderA{X, 2 * GD, GC}, UwLoaderB{ut, wtn}, acc, as, bs, tid);
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int i = 32 * T64::ib(w, 0) + tile_row(r, hf), j = 32 * T64::jb(w) + c;
@@ -458,7 +432,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
       for (int r = 0; r < 16; r++) {
         const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
         const float fe = el[i], fkb = bet[i] * eg[i];
-        const float kv = k_at(i, d), dkb = X[i * (2 * GD) + GD + d];
+        const float kv = k_at(i, d), dkb = (float)X[i * (2 * GD) + GD + d];
         const float s_kd = half_wave_sum(acc[t][r] * kv), s_kb = half_wave_sum(dkb * kv);
         if (c == HALF_SUM_LANE) {
           dot_kd[w][i] = s_kd;
@@ -484,9 +458,11 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
     float dot = 0.f;
 #pragma unroll
     for (int c8 = 0; c8 < 32; c8 += 8) {
-      const float4 x0 = ld4(X + i * (2 * GD) + c0 + c8), x1 = ld4(X + i * (2 * GD) + c0 + c8 + 4);
+      const bf16x8 xb = *(const bf16x8*)(X + i * (2 * GD) + c0 + c8);
       const bf16x8 vv = *(const bf16x8*)(vb + (size_t)min(i, len - 1) * vrow + c0 + c8);
-      const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      float xv[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) xv[e] = (float)xb[e];
 #pragma unroll
       for (int e = 0; e < 8; e++) dot += xv[e] * (float)vv[e];
       const float b = bet[i];
@@ -574,8 +550,6 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs
   t.ops.gam = (float*)take(per * GC * 4);
   t.ops.a0 = (float*)take(per * GC * GC * 4);
   t.ops.p = (float*)take(per * GC * GC * 4);
-  t.ops.u = (float*)take(per * GC * GD * 4);
-  t.ops.w = (float*)take(per * GC * GD * 4);
   t.sv.fwd_rec = take(per * GDN_REC_ELEMS * 2);
   t.sv.rev_rec = take(per * GDN_REC_ELEMS * 2);
   t.sv.glast = (float*)take(per * 4);
@@ -585,7 +559,7 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs
   t.sv.dvns = take(per * GC * GD * 2);
   t.sv.slots = (float*)take((size_t)n_slots * hv * GD * GD * 4);
   t.sv.slot_grad = (float*)take((size_t)n_slots * hv * GD * GD * 4);
-  t.x = (float*)take(per * GC * 2 * GD * 4);
+  t.x = (__bf16*)take(per * GC * 2 * GD * 2);
   t.dqh = (float*)take((size_t)n_tokens * hv * GD * 4);
   t.dkh = (float*)take((size_t)n_tokens * hv * GD * 4);
   if (w) *w = t;

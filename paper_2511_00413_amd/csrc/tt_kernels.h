@@ -90,11 +90,11 @@ struct GdnChunkOps {
   float* gam;      // [64]       running sum of the log-decays inside the chunk
   float* a0;       // [64][64]   strictly-lower (k_i . k_j) exp(gamma_i - gamma_j)   (A without beta_i)
   float* p;        // [64][64]   scale tril((q_i . k_j) exp(gamma_i - gamma_j))
-  float* u;        // [64][128]  (I + A)^-1 (beta V)
-  float* w;        // [64][128]  (I + A)^-1 (beta exp(gamma) K)
 };
 // bf16 operands of the two walks and what they save for the finish kernel:
 constexpr size_t GDN_REC_ELEMS = 4 * 64 * 128 + 64 * 64;     // elements of one walk record (forward and reverse alike)
+constexpr size_t GDN_REC_UT = 64 * 128;      // forward record: U^T [128 value cols][64 tokens], U = (I + A)^-1 (beta V)
+constexpr size_t GDN_REV_WTN = 64 * 128;     // reverse record: -W^T [128 key dims][64 tokens], W = (I + A)^-1 (beta exp(gamma) K)
 struct GdnBwdSaved {
   void* fwd_rec;     // forward walk records
   void* rev_rec;     // reverse walk records
