@@ -500,7 +500,7 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * d_initial_state [hv][128][128] fp32, overwritten with the gradient of the state the roots
  * start from.  Arithmetic: the two walks over the chunks use bf16 operands with fp32 accumulation
  * (state and state gradient stay fp32), like the forward; everything else is fp32.
- * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 400 KB per chunk and value
+ * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 300 KB per chunk and value
  * head, plus two fp32 [n_tokens][hv][128] arrays and 2 x n_slots saved states per head).
  * Errors: as tt_tree_gdn_fwd.
  * ------------------------------------------------------------------------------------------ */

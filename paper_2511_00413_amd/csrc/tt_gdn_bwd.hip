@@ -180,6 +180,10 @@ struct FragLoaderB : FragLoader<pitch_b<GC>()> {
   __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int) const { FragLoader<pitch_b<GC>()>::store(lds, tid, r); }
 };
 
+// Barrier that waits for this wave's LDS traffic only (a __syncthreads also waits for every global load in flight,
+// i.e. for the slabs that were requested ahead).  Not for global data written by other threads of the workgroup.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int N, int K, class LA, class LB>
 __device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 (&acc)[N / 64], float* as, float* bs, int tid_in) {
   constexpr int PB = pitch_b<N>();
@@ -190,21 +194,17 @@ __device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 
   asm volatile("" : "+v"(tid));
   typedef TileMap<N> TM;
   const int lane = tid & 63, c = lane & 31, hf = lane >> 5, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  typename LA::Regs ra;
-  typename LB::Regs rb;
-  la.load(0, tid, ra);
-  lb.load(0, tid, rb);
-#pragma unroll 1
-  for (int k0 = 0; k0 < K; k0 += KS) {
-    __syncthreads();                   // the previous slab (or whatever used the slab arrays before) has been read
-    la.store(as, tid, ra);
-    lb.store(bs, tid, rb, k0);
-    __syncthreads();
-    // the next slab is on its way while this one is multiplied (the last step fetches its own slab again: a
-    // branch around the loads would put their wait at its end, in front of the multiplication)
-    const int kn = k0 + KS < K ? k0 + KS : K - KS;
-    la.load(kn, tid, ra);
-    lb.load(kn, tid, rb);
+  // Two slabs are in flight: while slab s is multiplied, s + 1 is on its way and s + 2 has just been requested
+  // (one slab's multiplication is shorter than a trip to memory).  Two register sets take turns; the last two
+  // steps request nothing (a branch around loads would put their wait at its end, so the steps are peeled).
+  typename LA::Regs ra[2];
+  typename LB::Regs rb[2];
+  static_assert(K % (2 * KS) == 0, "an even number of slabs");
+  la.load(0, tid, ra[0]);
+  lb.load(0, tid, rb[0]);
+  la.load(KS, tid, ra[1]);
+  lb.load(KS, tid, rb[1]);
+  auto multiply = [&]() {
 #pragma unroll 8
     for (int s = 0; s < KS / 2; s++) {
       const int k = hf * (KS / 2) + s;
@@ -212,6 +212,27 @@ __device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 
 #pragma unroll
       for (int t = 0; t < TM::TPW; t++) acc[t] = mfma_f32(as[k * PA + 32 * TM::ib(w, t) + c], b, acc[t]);
     }
+  };
+#pragma unroll 1
+  for (int k0 = 0; k0 < K - 2 * KS; k0 += 2 * KS) {
+#pragma unroll
+    for (int set = 0; set < 2; set++) {
+      lds_barrier();                   // the previous slab (or whatever used the slab arrays before) has been read
+      la.store(as, tid, ra[set]);
+      lb.store(bs, tid, rb[set], k0 + set * KS);
+      lds_barrier();
+      la.load(k0 + (2 + set) * KS, tid, ra[set]);
+      lb.load(k0 + (2 + set) * KS, tid, rb[set]);
+      multiply();
+    }
+  }
+#pragma unroll
+  for (int set = 0; set < 2; set++) {
+    lds_barrier();
+    la.store(as, tid, ra[set]);
+    lb.store(bs, tid, rb[set], K - (2 - set) * KS);
+    lds_barrier();
+    multiply();
   }
 }
 
@@ -399,12 +420,18 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
     const int j = 32 * T128::jb(w) + c;
 #pragma unroll
     for (int t = 0; t < 2; t++) {
-      __builtin_amdgcn_sched_barrier(0);          // one tile's loads at a time (register pressure)
+      // One tile at a time (register pressure); its 16 loads in one straight-line block in front of the sums: the
+      // conditional LDS write below ends a basic block per row, and a load left inside would be waited for there,
+      // one memory latency per row (measured: a quarter of the kernel's time).
+      __builtin_amdgcn_sched_barrier(0);
+      float qv[16];
+#pragma unroll
+      for (int r = 0; r < 16; r++) qv[r] = q_at(32 * T128::ib(w, t) + tile_row(r, hf), j);
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
         acc[t][r] *= scale * eg[i];                                 // scale eg dQg_i: its contribution to dq_i
-        const float dot = half_wave_sum(acc[t][r] * q_at(i, j));    // dQg_i . Qg_i = (scale eg dQg_i) . q_i
+        const float dot = half_wave_sum(acc[t][r] * qv[r]);         // dQg_i . Qg_i = (scale eg dQg_i) . q_i
         if (c == HALF_SUM_LANE) dot_q[w][i] = dot;
       }
     }
@@ -428,11 +455,18 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
     for (int t = 0; t < 2; t++) {
       __builtin_amdgcn_sched_barrier(0);
+      float kvs[16], dkbs[16];              // loads first, as above
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
+        kvs[r] = k_at(i, d);
+        dkbs[r] = (float)X[i * (2 * GD) + GD + d];
+      }
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
         const float fe = el[i], fkb = bet[i] * eg[i];
-        const float kv = k_at(i, d), dkb = (float)X[i * (2 * GD) + GD + d];
+        const float kv = kvs[r], dkb = dkbs[r];
         const float s_kd = half_wave_sum(acc[t][r] * kv), s_kb = half_wave_sum(dkb * kv);
         if (c == HALF_SUM_LANE) {
           dot_kd[w][i] = s_kd;
@@ -456,18 +490,23 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   {
     const int i = tid >> 2, c0 = (tid & 3) * 32;
     float dot = 0.f;
+    bf16x8 xb[4], vv[4];
 #pragma unroll
-    for (int c8 = 0; c8 < 32; c8 += 8) {
-      const bf16x8 xb = *(const bf16x8*)(X + i * (2 * GD) + c0 + c8);
-      const bf16x8 vv = *(const bf16x8*)(vb + (size_t)min(i, len - 1) * vrow + c0 + c8);
+    for (int q = 0; q < 4; q++) {
+      xb[q] = *(const bf16x8*)(X + i * (2 * GD) + c0 + 8 * q);
+      vv[q] = *(const bf16x8*)(vb + (size_t)min(i, len - 1) * vrow + c0 + 8 * q);
+    }
+    const float b = bet[i];
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
       float xv[8];
 #pragma unroll
-      for (int e = 0; e < 8; e++) xv[e] = (float)xb[e];
-#pragma unroll
-      for (int e = 0; e < 8; e++) dot += xv[e] * (float)vv[e];
-      const float b = bet[i];
+      for (int e = 0; e < 8; e++) {
+        xv[e] = (float)xb[q][e];
+        dot += xv[e] * (float)vv[q][e];
+      }
       if (i < len)
-        *(bf16x8*)((__bf16*)a.b.dv + ((size_t)(tok0 + i) * hv + h) * GD + c0 + c8) =
+        *(bf16x8*)((__bf16*)a.b.dv + ((size_t)(tok0 + i) * hv + h) * GD + c0 + 8 * q) =
             cvt8(b * xv[0], b * xv[1], b * xv[2], b * xv[3], b * xv[4], b * xv[5], b * xv[6], b * xv[7]);
     }
     dot += __shfl_xor(dot, 1);
