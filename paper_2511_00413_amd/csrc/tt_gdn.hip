@@ -19,6 +19,9 @@
 //       in MFMA accumulators (the columns of S evolve independently, so a head is cut into four
 //       independent workgroups); state routing = where a chunk takes S0 from (registers when it
 //       continues the previous chunk's sequence, a saved node-end state, or zero).
+// The backward pass (tt_gdn_bwd.hip) reuses both: the prepare kernel in a form that also writes the reverse walk's
+// operands, the scan in a form that saves every chunk's entering state and Vn instead of writing the output, and
+// gdn_rscan_kernel, the reverse walk, built like the scan.
 #include <hip/hip_runtime.h>
 #include "tt_internal.h"
 #include "tt_kernels.h"

@@ -37,7 +37,6 @@ namespace {
 constexpr int GC = TT_GDN_CHUNK;     // 64
 constexpr int GD = 128;
 constexpr int BT = 256;
-constexpr int DVB = 32;              // value columns per scan workgroup
 constexpr int KS = 32;               // k-slab of the LDS-tiled products of the finish kernel
 
 struct BwdWs {
@@ -53,7 +52,6 @@ struct KArgs {
 };
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
-__device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
 
 // fp32 matrix instruction: D (32 x 32) += A (32 x 2) B (2 x 32).  Lane l = 32 hf + c supplies A[row c][k = hf] and
 // B[k = hf][column c] and holds D[(r / 4) * 8 + 4 hf + r % 4][c] in register r.
@@ -61,12 +59,10 @@ __device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 acc) { retur
 __device__ __forceinline__ int tile_row(int r, int hf) { return (r >> 2) * 8 + 4 * hf + (r & 3); }
 
 // ---- per-chunk finish ----------------------------------------------------------------------------------
-// Products C (64 x N) += A (64 x K) B (K x N) of a workgroup on the fp32 matrix instruction, operands through LDS
-// slabs of KS k-values fetched element by element through fa(i, k), fb(k, j) (global memory or LDS); the next
-// slab is fetched into registers while the current one is multiplied.  AKF / BKF: consecutive threads fetch
-// consecutive k (operand stored with k contiguous) rather than consecutive i / j.  Wave w holds, in accumulator
-// layout, N = 128: tiles (row block t, column block w), t = 0, 1;  N = 64: the tile (row block w & 1, column block
-// w >> 1).  Every thread of the workgroup must call it.
+// Products C (64 x N) += A (64 x K) B (K x N) of a workgroup on the fp32 matrix instruction (slab_product below):
+// the operands go through LDS slabs of KS k-values, brought in by the loaders that follow.  Wave w holds, in
+// accumulator layout, N = 128: tiles (row block t, column block w), t = 0, 1;  N = 64: the tile (row block w & 1,
+// column block w >> 1).
 template <int N>
 struct TileMap {
   static constexpr int TPW = N / 64;                     // tiles per wave
@@ -283,9 +279,6 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   const __bf16* ds1t = (const __bf16*)a.w.sv.ds1t + op * (GD * GD);
   const __bf16* vns = (const __bf16*)a.w.sv.vns + op * (GC * GD);
   const __bf16* dvns = (const __bf16*)a.w.sv.dvns + op * (GC * GD);
-  auto s0_at = [&](int d, int cc) { return (float)s0t[cc * GD + d]; };
-  auto ds1_at = [&](int d, int cc) { return (float)ds1t[cc * GD + d]; };
-  auto vn_at = [&](int i, int cc) { return (float)vns[gdn_frag_index(i, cc)]; };
   auto dvn_at = [&](int i, int cc) { return (float)dvns[gdn_frag_index(i, cc)]; };
   __bf16* X = a.w.x + op * (GC * 2 * GD);
   const size_t qrow = (size_t)a.b.hk * GD, vrow = (size_t)hv * GD;
@@ -298,7 +291,6 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   const int qrow32 = (int)qrow, vrow32 = (int)vrow;
   auto q_at = [&](int i, int d) { const float x = (float)qb[min(i, len - 1) * qrow32 + d]; return i < len ? x : 0.f; };
   auto k_at = [&](int i, int d) { const float x = (float)kb[min(i, len - 1) * qrow32 + d]; return i < len ? x : 0.f; };
-  auto do_at = [&](int i, int cc) { const float x = (float)dob[min(i, len - 1) * vrow32 + cc]; return i < len ? x : 0.f; };
 
   const float glast = a.w.ops.gam[op * GC + GC - 1];
   const float el_last = __expf(glast);
