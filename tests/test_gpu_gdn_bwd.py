@@ -72,3 +72,11 @@ def test_head_layouts(hk, hv):
     eight (the workgroup-to-head mapping differs there)."""
     t = W.random_tree(870 + hv, n_nodes=7, lo=1, hi=100, p_zero=0.1)
     _check(t, hk, hv, 40 + hk)
+
+
+def test_chunk_boundary_lengths():
+    """Node lengths at and around the chunk size (63, 64, 65, 128, 129), a zero-length node between two others,
+    two roots: chunks of full and of one-token length, branch points at chunk ends."""
+    parent = [-1, 0, 0, 1, 1, 2, -1, 6, 7]
+    seg = [64, 63, 65, 128, 1, 0, 129, 0, 2]
+    _check(W._mk(parent, seg, [1] * len(seg), "boundaries"), 1, 2, 77)
