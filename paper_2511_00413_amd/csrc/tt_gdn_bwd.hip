@@ -37,7 +37,7 @@ namespace {
 constexpr int GC = TT_GDN_CHUNK;     // 64
 constexpr int GD = 128;
 constexpr int BT = 256;
-constexpr int KS = 32;               // k-slab of the LDS-tiled products of the finish kernel
+constexpr int KS = 64;               // k-values per LDS slab of the finish kernel's products
 
 struct BwdWs {
   GdnChunkOps ops;
@@ -53,16 +53,15 @@ struct KArgs {
 
 __device__ __forceinline__ float4 ld4(const float* p) { return *(const float4*)p; }
 
-// fp32 matrix instruction: D (32 x 32) += A (32 x 2) B (2 x 32).  Lane l = 32 hf + c supplies A[row c][k = hf] and
-// B[k = hf][column c] and holds D[(r / 4) * 8 + 4 hf + r % 4][c] in register r.
-__device__ __forceinline__ f32x16 mfma_f32(float a, float b, f32x16 acc) { return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0); }
+// Register r of a 32 x 32 accumulator tile holds row (r / 4) * 8 + 4 hf + r % 4 of column lane % 32.
 __device__ __forceinline__ int tile_row(int r, int hf) { return (r >> 2) * 8 + 4 * hf + (r & 3); }
 
 // ---- per-chunk finish ----------------------------------------------------------------------------------
-// Products C (64 x N) += A (64 x K) B (K x N) of a workgroup on the fp32 matrix instruction (slab_product below):
-// the operands go through LDS slabs of KS k-values, brought in by the loaders that follow.  Wave w holds, in
-// accumulator layout, N = 128: tiles (row block t, column block w), t = 0, 1;  N = 64: the tile (row block w & 1,
-// column block w >> 1).
+// Products C (64 x N) += A (64 x K) B (K x N) of a workgroup on the bf16 matrix instruction, fp32 accumulation
+// (slab_product below).  Nearly every operand is bf16 in memory already; only the two 64 x 64 matrices that the
+// kernel forms itself (dP scale D and dA beta D) are rounded here.  The operands go through LDS slabs of KS
+// k-values, brought in by the loaders that follow.  Wave w holds, in accumulator layout, N = 128: tiles (row
+// block t, column block w), t = 0, 1;  N = 64: the tile (row block w & 1, column block w >> 1).
 template <int N>
 struct TileMap {
   static constexpr int TPW = N / 64;                     // tiles per wave
@@ -70,64 +69,98 @@ struct TileMap {
   __device__ static int jb(int w) { return N == 128 ? w : (w >> 1); }
 };
 
-// Slab pitches (floats): rows start 16-byte aligned, and 68 / 132 = 4 (mod 32) spreads 16-byte writes over the banks
-constexpr int PA = GC + 4;
-template <int N> constexpr int pitch_b() { return N + 4; }
+// LDS slab layouts (bf16).  "k-major": [k][row or column], the orientation in which most operands arrive (a
+// 16-byte piece of memory holds 8 rows / columns of one k); fragments come out of it through the transposing LDS
+// read.  "row-major": [row][k] for A operands whose memory has k contiguous; fragments are plain 16-byte reads.
+// Pitches (elements): rows 16-byte aligned, 8 elements of padding against bank conflicts.
+constexpr int PK_A = GC + 8;                              // k-major A slab: KS rows of 64 (+8)
+constexpr int PR_A = KS + 8;                              // row-major A slab: 64 rows of KS (+8)
+template <int N> constexpr int pitch_b() { return N + 8; } // k-major B slab: KS rows of N (+8)
+constexpr int AS_ELEMS = KS * PK_A > GC * PR_A ? KS * PK_A : GC * PR_A;
+
+// 8 consecutive k (k0 .. k0 + 7) of row / column n0 + (lane % 16) from a k-major slab: two transposing reads of a
+// 4 (k) x 16 (n) block each; inside a group of 16 lanes, lane i supplies the address of 4 consecutive elements of
+// block row i / 4 and receives block column i.
+__device__ __forceinline__ bf16x8 kmajor_frag(const __bf16* slab, int pitch, int k0, int n0, int lane) {
+  const int i = lane & 15;
+  const __bf16* p = slab + (k0 + (i >> 2)) * pitch + n0 + 4 * (i & 3);
+  return cat4(lds_read_tr(p), lds_read_tr(p + 4 * pitch));
+}
 
 // ---- operand loaders ---------------------------------------------------------------------------------------
 // A loader brings one KS-wide slab of an operand from memory into registers (load) and from there into the LDS
-// slab (store): as[kk * PA + i] = A(i, k0 + kk), bs[kk * PB + j] = B(k0 + kk, j).  Memory is read in 16-byte pieces.
+// slab (store).  Memory is read in 16-byte pieces.  KMAJOR tells the layout of an A loader's slab.
 
-// Vn / dVn in fragment order, element (token, value column).  As A: (i, k = column).  As B: (k = column, j = token).
-// One piece = 8 tokens of one column: tokens base .. base + 3 and base + 8 .. base + 11.
+// Vn / dVn in fragment order, element (token, value column).  As A (k-major): (i = token, k = column).  As B:
+// (k = column, j = token).  One piece = 8 tokens of one column: tokens base .. base + 3 and base + 8 .. base + 11.
 template <int PITCH>
 struct FragLoader {
+  static constexpr bool KMAJOR = true;
   const __bf16* p;
-  typedef bf16x8 Regs;
-  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
-    const int cl = tid & 31, g = tid >> 5;                                   // column inside the slab; (half, t, hf)
-    r = *(const bf16x8*)(p + ((((size_t)(k0 >> 5) * 4 + (g >> 1)) * 64 + (g & 1) * 32 + cl) << 3));
-  }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
-    const int cl = tid & 31, g = tid >> 5;
-    const int base = 32 * (g >> 2) + 16 * ((g >> 1) & 1) + 4 * (g & 1);
-    float* d = lds + cl * PITCH + base;
-    *(float4*)d = make_float4((float)r[0], (float)r[1], (float)r[2], (float)r[3]);
-    *(float4*)(d + 8) = make_float4((float)r[4], (float)r[5], (float)r[6], (float)r[7]);
-  }
-};
-// bf16 rows with the contraction index contiguous, as A: (i, k) = p[i * pitch + k]; rows >= len are zero
-struct RowsKLoaderA {
-  const __bf16* p;
-  int pitch, len;
-  typedef bf16x8 Regs;
-  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
-    const int i = tid >> 2, k8 = (tid & 3) * 8;
-    r = *(const bf16x8*)(p + (size_t)min(i, len - 1) * pitch + k0 + k8);
-  }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
-    const int i = tid >> 2, k8 = (tid & 3) * 8;
-#pragma unroll
-    for (int e = 0; e < 8; e++) lds[(k8 + e) * PA + i] = i < len ? (float)r[e] : 0.f;
-  }
-};
-// any A given element by element (LDS-resident matrices): consecutive threads take consecutive i
-template <class F>
-struct FnLoaderA {
-  F f;
-  struct Regs { float v[GC * KS / BT]; };
+  struct Regs { bf16x8 v[KS * GC / 8 / BT]; };
   __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
 #pragma unroll
-    for (int q = 0; q < GC * KS / BT; q++) {
-      const int e = tid + q * BT;
-      r.v[q] = f(e % GC, k0 + e / GC);
+    for (int q = 0; q < KS * GC / 8 / BT; q++) {
+      const int piece = tid + q * BT, cl = piece % KS, g = piece / KS;     // column inside the slab; (half, t, hf)
+      const int col = k0 + cl;
+      r.v[q] = *(const bf16x8*)(p + ((((size_t)(col >> 5) * 4 + (g >> 1)) * 64 + (g & 1) * 32 + (col & 31)) << 3));
     }
   }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r) const {
+  __device__ __forceinline__ void store(__bf16* lds, int tid, const Regs& r, int = 0) const {
 #pragma unroll
-    for (int q = 0; q < GC * KS / BT; q++) {
-      const int e = tid + q * BT;
-      lds[(e / GC) * PA + e % GC] = r.v[q];
+    for (int q = 0; q < KS * GC / 8 / BT; q++) {
+      const int piece = tid + q * BT, cl = piece % KS, g = piece / KS;
+      const int base = 32 * (g >> 2) + 16 * ((g >> 1) & 1) + 4 * (g & 1);
+      __bf16* d = lds + cl * PITCH + base;
+      *(bf16x4*)d = __builtin_shufflevector(r.v[q], r.v[q], 0, 1, 2, 3);
+      *(bf16x4*)(d + 8) = __builtin_shufflevector(r.v[q], r.v[q], 4, 5, 6, 7);
+    }
+  }
+};
+// bf16 rows with the contraction index contiguous, as A (row-major): (i, k) = p[i * pitch + k]; rows >= len are zero
+struct RowsKLoaderA {
+  static constexpr bool KMAJOR = false;
+  const __bf16* p;
+  int pitch, len;
+  struct Regs { bf16x8 v[GC * KS / 8 / BT]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < GC * KS / 8 / BT; q++) {
+      const int piece = tid + q * BT, i = piece / (KS / 8), k8 = (piece % (KS / 8)) * 8;
+      r.v[q] = *(const bf16x8*)(p + (size_t)min(i, len - 1) * pitch + k0 + k8);
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* lds, int tid, const Regs& r) const {
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; e++) zero[e] = (__bf16)0.f;
+#pragma unroll
+    for (int q = 0; q < GC * KS / 8 / BT; q++) {
+      const int piece = tid + q * BT, i = piece / (KS / 8), k8 = (piece % (KS / 8)) * 8;
+      *(bf16x8*)(lds + i * PR_A + k8) = i < len ? r.v[q] : zero;
+    }
+  }
+};
+// any A given element by element as fp32 (the LDS-resident 64 x 64 matrices), row-major slab; a thread takes 8
+// consecutive k of one row
+template <class F>
+struct FnLoaderA {
+  static constexpr bool KMAJOR = false;
+  F f;
+  struct Regs { bf16x8 v[GC * KS / 8 / BT]; };
+  __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < GC * KS / 8 / BT; q++) {
+      const int piece = tid + q * BT, i = piece % GC, k8 = (piece / GC) * 8;
+      r.v[q] = cvt8(f(i, k0 + k8), f(i, k0 + k8 + 1), f(i, k0 + k8 + 2), f(i, k0 + k8 + 3), f(i, k0 + k8 + 4), f(i, k0 + k8 + 5),
+                    f(i, k0 + k8 + 6), f(i, k0 + k8 + 7));
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* lds, int tid, const Regs& r) const {
+#pragma unroll
+    for (int q = 0; q < GC * KS / 8 / BT; q++) {
+      const int piece = tid + q * BT, i = piece % GC, k8 = (piece / GC) * 8;
+      *(bf16x8*)(lds + i * PR_A + k8) = r.v[q];
     }
   }
 };
@@ -136,53 +169,56 @@ template <class F> __device__ __forceinline__ FnLoaderA<F> fn_loader_a(F f) { re
 struct RowsJLoaderB {
   const __bf16* p;
   int pitch, len;
-  struct Regs { bf16x8 v[2]; };
+  struct Regs { bf16x8 v[KS * GD / 8 / BT]; };
   __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
 #pragma unroll
-    for (int q = 0; q < 2; q++) {
+    for (int q = 0; q < KS * GD / 8 / BT; q++) {
       const int piece = tid + q * BT, kk = piece >> 4, j8 = (piece & 15) * 8;
       r.v[q] = *(const bf16x8*)(p + (size_t)min(k0 + kk, len - 1) * pitch + j8);
     }
   }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int k0) const {
+  __device__ __forceinline__ void store(__bf16* lds, int tid, const Regs& r, int k0) const {
+    bf16x8 zero;
 #pragma unroll
-    for (int q = 0; q < 2; q++) {
+    for (int e = 0; e < 8; e++) zero[e] = (__bf16)0.f;
+#pragma unroll
+    for (int q = 0; q < KS * GD / 8 / BT; q++) {
       const int piece = tid + q * BT, kk = piece >> 4, j8 = (piece & 15) * 8;
-      const bool in = k0 + kk < len;
-      float* d = lds + kk * pitch_b<GD>() + j8;
-      *(float4*)d = in ? make_float4((float)r.v[q][0], (float)r.v[q][1], (float)r.v[q][2], (float)r.v[q][3]) : make_float4(0.f, 0.f, 0.f, 0.f);
-      *(float4*)(d + 4) = in ? make_float4((float)r.v[q][4], (float)r.v[q][5], (float)r.v[q][6], (float)r.v[q][7]) : make_float4(0.f, 0.f, 0.f, 0.f);
+      *(bf16x8*)(lds + kk * pitch_b<GD>() + j8) = k0 + kk < len ? r.v[q] : zero;
     }
   }
 };
 // [U | W]^T from the walks' bf16 records, as B (N = 64): (k, j) = k < 128 ? U^T[k][j] : -(-W^T)[k - 128][j]
 struct UwLoaderB {
   const __bf16 *ut, *wtn;
-  typedef bf16x8 Regs;
+  struct Regs { bf16x8 v[KS * GC / 8 / BT]; };
   __device__ __forceinline__ void load(int k0, int tid, Regs& r) const {
-    const int kk = tid >> 3, j8 = (tid & 7) * 8;
-    r = *(const bf16x8*)((k0 < GD ? ut + (size_t)(k0 + kk) * GC : wtn + (size_t)(k0 - GD + kk) * GC) + j8);
+    const __bf16* src = k0 < GD ? ut + (size_t)k0 * GC : wtn + (size_t)(k0 - GD) * GC;     // a slab lies in one half
+#pragma unroll
+    for (int q = 0; q < KS * GC / 8 / BT; q++) {
+      const int piece = tid + q * BT, kk = piece >> 3, j8 = (piece & 7) * 8;
+      r.v[q] = *(const bf16x8*)(src + (size_t)kk * GC + j8);
+    }
   }
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int k0) const {
-    const int kk = tid >> 3, j8 = (tid & 7) * 8;
-    const float sg = k0 < GD ? 1.f : -1.f;
-    float* d = lds + kk * pitch_b<GC>() + j8;
-    *(float4*)d = make_float4(sg * (float)r[0], sg * (float)r[1], sg * (float)r[2], sg * (float)r[3]);
-    *(float4*)(d + 4) = make_float4(sg * (float)r[4], sg * (float)r[5], sg * (float)r[6], sg * (float)r[7]);
+  __device__ __forceinline__ void store(__bf16* lds, int tid, const Regs& r, int k0) const {
+#pragma unroll
+    for (int q = 0; q < KS * GC / 8 / BT; q++) {
+      const int piece = tid + q * BT, kk = piece >> 3, j8 = (piece & 7) * 8;
+      typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+      const u16x8 flipped = __builtin_bit_cast(u16x8, r.v[q]) ^ (unsigned short)0x8000;      // -x: the sign bit
+      *(bf16x8*)(lds + kk * pitch_b<GC>() + j8) = k0 < GD ? r.v[q] : __builtin_bit_cast(bf16x8, flipped);
+    }
   }
 };
-// Vn as B (N = 64)
-struct FragLoaderB : FragLoader<pitch_b<GC>()> {
-  __device__ __forceinline__ void store(float* lds, int tid, const Regs& r, int) const { FragLoader<pitch_b<GC>()>::store(lds, tid, r); }
-};
+typedef FragLoader<pitch_b<GC>()> FragLoaderB;             // Vn as B (N = 64)
 
 // Barrier that waits for this wave's LDS traffic only (a __syncthreads also waits for every global load in flight,
 // i.e. for the slabs that were requested ahead).  Not for global data written by other threads of the workgroup.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int N, int K, class LA, class LB>
-__device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 (&acc)[N / 64], float* as, float* bs, int tid_in) {
-  constexpr int PB = pitch_b<N>();
+__device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 (&acc)[N / 64], __bf16* as, __bf16* bs, int tid_in) {
+  constexpr int PB = pitch_b<N>(), NS = K / KS;
   // The fetch offsets are functions of the thread id alone.  Hidden behind an opaque copy they are computed at each
   // call; otherwise the compiler computes those of all calls at the top of the kernel and keeps them in registers
   // throughout (measured: 174 spilled registers at two waves per SIMD).
@@ -190,43 +226,49 @@ __device__ __forceinline__ void slab_product(const LA& la, const LB& lb, f32x16 
   asm volatile("" : "+v"(tid));
   typedef TileMap<N> TM;
   const int lane = tid & 63, c = lane & 31, hf = lane >> 5, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // Two slabs are in flight: while slab s is multiplied, s + 1 is on its way and s + 2 has just been requested
-  // (one slab's multiplication is shorter than a trip to memory).  Two register sets take turns; the last two
-  // steps request nothing (a branch around loads would put their wait at its end, so the steps are peeled).
-  typename LA::Regs ra[2];
-  typename LB::Regs rb[2];
-  static_assert(K % (2 * KS) == 0, "an even number of slabs");
-  la.load(0, tid, ra[0]);
-  lb.load(0, tid, rb[0]);
-  la.load(KS, tid, ra[1]);
-  lb.load(KS, tid, rb[1]);
   auto multiply = [&]() {
-#pragma unroll 8
-    for (int s = 0; s < KS / 2; s++) {
-      const int k = hf * (KS / 2) + s;
-      const float b = bs[k * PB + 32 * TM::jb(w) + c];
 #pragma unroll
-      for (int t = 0; t < TM::TPW; t++) acc[t] = mfma_f32(as[k * PA + 32 * TM::ib(w, t) + c], b, acc[t]);
+    for (int s = 0; s < KS / 16; s++) {
+      const bf16x8 b = kmajor_frag(bs, PB, 16 * s + 8 * hf, 32 * TM::jb(w) + 16 * (c >> 4), lane);
+#pragma unroll
+      for (int t = 0; t < TM::TPW; t++) {
+        const int ib = TM::ib(w, t);
+        const bf16x8 a = LA::KMAJOR ? kmajor_frag(as, PK_A, 16 * s + 8 * hf, 32 * ib + 16 * (c >> 4), lane)
+                                    : *(const bf16x8*)(as + (32 * ib + c) * PR_A + 16 * s + 8 * hf);
+        acc[t] = mfma32(a, b, acc[t]);
+      }
     }
   };
+  // Up to two slabs are in flight: while slab s is multiplied, s + 1 is on its way and s + 2 has just been
+  // requested.  Two register sets take turns; the last steps request nothing (a branch around loads would put
+  // their wait at its end, so the steps are peeled).
+  typename LA::Regs ra[2];
+  typename LB::Regs rb[2];
+  static_assert(NS == 1 || NS % 2 == 0, "one slab or an even number of slabs");
+  la.load(0, tid, ra[0]);
+  lb.load(0, tid, rb[0]);
+  if constexpr (NS > 1) {
+    la.load(KS, tid, ra[1]);
+    lb.load(KS, tid, rb[1]);
 #pragma unroll 1
-  for (int k0 = 0; k0 < K - 2 * KS; k0 += 2 * KS) {
+    for (int k0 = 0; k0 < K - 2 * KS; k0 += 2 * KS) {
 #pragma unroll
-    for (int set = 0; set < 2; set++) {
-      lds_barrier();                   // the previous slab (or whatever used the slab arrays before) has been read
-      la.store(as, tid, ra[set]);
-      lb.store(bs, tid, rb[set], k0 + set * KS);
-      lds_barrier();
-      la.load(k0 + (2 + set) * KS, tid, ra[set]);
-      lb.load(k0 + (2 + set) * KS, tid, rb[set]);
-      multiply();
+      for (int set = 0; set < 2; set++) {
+        lds_barrier();                 // the previous slab (or whatever used the slab arrays before) has been read
+        la.store(as, tid, ra[set]);
+        lb.store(bs, tid, rb[set], k0 + set * KS);
+        lds_barrier();
+        la.load(k0 + (2 + set) * KS, tid, ra[set]);
+        lb.load(k0 + (2 + set) * KS, tid, rb[set]);
+        multiply();
+      }
     }
   }
 #pragma unroll
-  for (int set = 0; set < 2; set++) {
+  for (int set = 0; set < (NS > 1 ? 2 : 1); set++) {
     lds_barrier();
     la.store(as, tid, ra[set]);
-    lb.store(bs, tid, rb[set], K - (2 - set) * KS);
+    lb.store(bs, tid, rb[set], K - ((NS > 1 ? 2 : 1) - set) * KS);
     lds_barrier();
     multiply();
   }
@@ -253,15 +295,20 @@ constexpr int AP = GC + 1;     // row pitch of the 64 x 64 LDS matrices that are
 constexpr int TP = GC + 4;     // pitch of the transposed A during the solve (rows read as float4)
 
 __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
-  __shared__ __attribute__((aligned(16))) float as[KS * PA];
-  __shared__ __attribute__((aligned(16))) float bs[GC * AP > KS * pitch_b<GD>() ? GC * AP : KS * pitch_b<GD>()];   // between products also: dA o A0
+  __shared__ __attribute__((aligned(16))) __bf16 as[AS_ELEMS];
+  constexpr int BS_FLOATS = GC * AP > KS * pitch_b<GD>() / 2 ? GC * AP : KS * pitch_b<GD>() / 2;
+  __shared__ __attribute__((aligned(16))) float bs_f[BS_FLOATS];  // B slabs (bf16); between products also dA o A0 (fp32)
+  __bf16* bs = (__bf16*)bs_f;
   __shared__ __attribute__((aligned(16))) float dam[GC * TP];     // A^T during the solve, then dA, then dA beta D
   __shared__ float dpm[GC * AP];                                  // dP, then dP scale D
   __shared__ float gm[GC * AP];                                   // dP o P + dA o A
   __shared__ float gam[GC], bet[GC], eg[GC], el[GC];
   __shared__ float dg_row[GC], dg_col[GC], db_a[GC], db_v[GC], dgam[GC];
-  __shared__ float dot_q[4][GC], dot_kd[4][GC], dot_kb[4][GC];    // per-wave parts of row dot products
-  float* red = as;                                                // [BT], after the last product
+  // per-wave parts of row dot products: they live in gm, which is dead by the time they are formed
+  float(*dot_q)[GC] = (float(*)[GC])gm;
+  float(*dot_kd)[GC] = (float(*)[GC])(gm + 4 * GC);
+  float(*dot_kb)[GC] = (float(*)[GC])(gm + 8 * GC);
+  float* red = (float*)as;                                        // [BT], after the last product
 
   const int chunk = blockIdx.x, h = blockIdx.y;
   const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
@@ -307,7 +354,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   // dW = -dVn S0^T  -> right half of X
   {
     f32x16 acc[2] = {zero16(), zero16()};
-    slab_product<GD, GD>(FragLoader<PA>{dvns}, RowsJLoaderB{s0t, GD, GD}, acc, as, bs, tid);
+    slab_product<GD, GD>(FragLoader<PK_A>{dvns}, RowsJLoaderB{s0t, GD, GD}, acc, as, bs, tid);
 #pragma unroll
     for (int t = 0; t < 2; t++)
 #pragma unroll
@@ -361,7 +408,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
       dam[i * AP + j] = i > j ? -acc[0][r] : 0.f;
     }
     acc[0] = zero16();
-    slab_product<GC, GD>(RowsKLoaderA{dob, vrow32, len}, FragLoaderB{{vns}}, acc, as, bs, tid);
+    slab_product<GC, GD>(RowsKLoaderA{dob, vrow32, len}, FragLoaderB{vns}, acc, as, bs, tid);
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       const int i = 32 * T64::ib(w, 0) + tile_row(r, hf), j = 32 * T64::jb(w) + c;
@@ -375,7 +422,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   for (int p = 0; p < GC * GC / BT; p++) {
     const int e = tid + p * BT, i = e / GC, j = e % GC;
     const float ga = dam[i * AP + j] * A0[e];
-    bs[i * AP + j] = ga;                     // its row sums are the part of dbeta that comes through A
+    bs_f[i * AP + j] = ga;                   // its row sums are the part of dbeta that comes through A
     gm[i * AP + j] = dpm[i * AP + j] * Pm[e] + bet[i] * ga;
   }
   __syncthreads();
@@ -391,7 +438,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   } else if (tid < 3 * GC) {
     const int i = tid - 2 * GC;
     float s = 0.f;
-    for (int j = 0; j < GC; j++) s += bs[i * AP + j];
+    for (int j = 0; j < GC; j++) s += bs_f[i * AP + j];
     db_a[i] = s;
   }
   __syncthreads();
@@ -440,7 +487,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   // dk_j = el_j (Vn dS1^T)_j + beta_j eg_j dKb_j + sum_i (dP scale D)_ij q_i + sum_i (MA_ij + MA_ji) k_i
   {
     f32x16 acc[2] = {zero16(), zero16()};
-    slab_product<GD, GD>(FragLoader<PA>{vns}, RowsJLoaderB{ds1t, GD, GD}, acc, as, bs, tid);
+    slab_product<GD, GD>(FragLoader<PK_A>{vns}, RowsJLoaderB{ds1t, GD, GD}, acc, as, bs, tid);
     int zz = 0;
     asm volatile("" : "+v"(zz));          // row offsets are recomputed here, not kept in registers since the dq block
     const int d = 32 * T128::jb(w) + c + zz;
