@@ -426,20 +426,25 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
     gm[i * AP + j] = dpm[i * AP + j] * Pm[e] + bet[i] * ga;
   }
   __syncthreads();
-  if (tid < GC) {
-    float s = 0.f;
-    for (int i = 0; i < GC; i++) s += gm[i * AP + tid];
-    dg_col[tid] = s;
-  } else if (tid < 2 * GC) {
-    const int i = tid - GC;
-    float s = 0.f;
-    for (int j = 0; j < GC; j++) s += gm[i * AP + j];
-    dg_row[i] = s;
-  } else if (tid < 3 * GC) {
-    const int i = tid - 2 * GC;
-    float s = 0.f;
-    for (int j = 0; j < GC; j++) s += bs_f[i * AP + j];
-    db_a[i] = s;
+  {
+    // row sums and column sums of G, row sums of dA o A0: four threads per row / column, 16 independent LDS reads
+    // each (a single thread walking all 64 waits for every read in turn), then two lane exchanges
+    const int n = tid >> 2, part = (tid & 3) * 16;
+    float s_row = 0.f, s_col = 0.f, s_a = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; e++) {
+      s_row += gm[n * AP + part + e];
+      s_col += gm[(part + e) * AP + n];
+      s_a += bs_f[n * AP + part + e];
+    }
+    s_row += __shfl_xor(s_row, 1); s_row += __shfl_xor(s_row, 2);
+    s_col += __shfl_xor(s_col, 1); s_col += __shfl_xor(s_col, 2);
+    s_a += __shfl_xor(s_a, 1); s_a += __shfl_xor(s_a, 2);
+    if ((tid & 3) == 0) {
+      dg_row[n] = s_row;
+      dg_col[n] = s_col;
+      db_a[n] = s_a;
+    }
   }
   __syncthreads();
   // dP -> dP scale D,  dA -> dA beta_i D   (the factors that multiply k_j, q_i, k_i in the products below)
@@ -565,25 +570,28 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
     red[tid] = s;
   }
   __syncthreads();
-  for (int stride = BT / 2; stride > 0; stride >>= 1) {
-    if (tid < stride) red[tid] += red[tid + stride];
-    __syncthreads();
+  if (tid < GC) {
+    // state inner product: 256 partial sums -> 64 (fixed order), the rest below
+    red[tid] = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
   }
+  __syncthreads();
   if (tid < GC) {
     // row dot products: the four waves hold a quarter of the columns each
     const float dq_ = dot_q[0][tid] + dot_q[1][tid] + dot_q[2][tid] + dot_q[3][tid];
     const float dkd = el[tid] * (dot_kd[0][tid] + dot_kd[1][tid] + dot_kd[2][tid] + dot_kd[3][tid]);      // dKd_i . Kd_i
     const float dkb = dot_kb[0][tid] + dot_kb[1][tid] + dot_kb[2][tid] + dot_kb[3][tid];                  // dKb_i . k_i
     dgam[tid] = dg_row[tid] - dg_col[tid] + dq_ - dkd + bet[tid] * eg[tid] * dkb;
-    red[64 + tid] = dkd;                                  // red[0] is the state inner product; 64.. are free now
+    red[64 + tid] = dkd + el_last * red[tid];             // what reaches every g through gamma_last, 64 parts
     red[128 + tid] = db_a[tid] + eg[tid] * dkb + db_v[tid];
   }
   __syncthreads();
   if (tid < len) {
-    float s = 0.f;
-    for (int i = tid; i < GC; i++) s += dgam[i];          // gamma_i = sum of g_j over j <= i
-    float last = el_last * red[0];                        // what reaches every g through gamma_last
-    for (int i = 0; i < GC; i++) last += red[64 + i];
+    float s = 0.f, last = 0.f;
+#pragma unroll
+    for (int i = 0; i < GC; i++) {                        // independent reads, fixed order
+      s += i >= tid ? dgam[i] : 0.f;                      // gamma_i = sum of g_j over j <= i
+      last += red[64 + i];
+    }
     a.b.dg[(size_t)(tok0 + tid) * hv + h] = s + last;
     a.b.dbeta[(size_t)(tok0 + tid) * hv + h] = red[128 + tid];
   }
