@@ -498,8 +498,9 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * d_state_out [n_capture][hv][128][128] fp32, the upstream gradient of the captured end states
  * (what the child partitions' d_initial_state returned; needs chunk_cap);
  * d_initial_state [hv][128][128] fp32, overwritten with the gradient of the state the roots
- * start from.  Arithmetic: the two walks over the chunks use bf16 operands with fp32 accumulation
- * (state and state gradient stay fp32), like the forward; everything else is fp32.
+ * start from.  Arithmetic: matrix products use bf16 operands with fp32 accumulation, like the
+ * forward (state and state gradient stay fp32); the triangular solves and all element-wise work
+ * are fp32.
  * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 300 KB per chunk and value
  * head, plus two fp32 [n_tokens][hv][128] arrays and 2 x n_slots saved states per head).
  * Errors: as tt_tree_gdn_fwd.

@@ -21,9 +21,9 @@
 //                              of every chunk (bf16)
 //   gdn_rscan_kernel           (32 value columns, head): reverse walk in the forward scan's form (bf16 matrix
 //                              instruction, fp32 state gradient in accumulators); saves dS1 and dVn (bf16)
-//   gdn_bwd_finish_kernel      per (chunk, head): everything else in fp32: products on the fp32 matrix
-//                              instruction through LDS slabs, the transposed solve with one lane per column;
-//                              dq / dk per value head in fp32
+//   gdn_bwd_finish_kernel      per (chunk, head): everything else: products on the bf16 matrix instruction (fp32
+//                              accumulation) through LDS slabs, the transposed solve with one lane per column
+//                              and all element-wise work in fp32; dq / dk per value head in fp32
 //   gdn_bwd_group_sum_kernel   sums dq / dk over the value heads that share a key head, rounds to bf16
 #include <hip/hip_runtime.h>
 #include <algorithm>

@@ -1,9 +1,9 @@
 """GPU parity: backward of the gated delta rule with tree state routing against the fp64 reverse recurrence.
-The two walks over the chunks round their per-chunk operands and what they save for the per-chunk kernel
-(entering state, Vn, gradient of the leaving state, dVn) to bf16 once each and accumulate in fp32, like the
-forward; the per-chunk kernel computes in fp32; dq, dk, dv are rounded to bf16 at the end (dq, dk after the
-fp32 sum over the value heads of a key head).  Tolerance: rel-L2 <= 2e-2 on every output, as for the attention
-gradients; measured 2.5e-3 .. 3e-3."""
+Like the forward, the kernels round the operands of their matrix products to bf16 once each (per-chunk
+operands, entering state, Vn, gradient of the leaving state, dVn, the solved right-hand sides) and accumulate in
+fp32; solves and element-wise work are fp32; dq, dk, dv are rounded to bf16 at the end (dq, dk after the fp32 sum
+over the value heads of a key head).  Tolerance: rel-L2 <= 2e-2 on every output, as for the attention
+gradients; measured 2.3e-3 .. 3.4e-3."""
 import numpy as np
 import pytest
 import torch
