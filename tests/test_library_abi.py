@@ -92,3 +92,34 @@ def test_device_calls_validate_before_launch():
     assert rc == -2                      # row stride smaller than vocab
     rc = lib.tt_tree_weighted_logprob(4, 128, 0, null, 0, fake, null, fake, null, null, null)
     assert rc == -1
+
+
+def test_gdn_calls_validate_before_launch():
+    """Shape, pointer, alignment and workspace errors of the gated-delta-rule entry points are reported before
+    anything is launched (the pointers below are never dereferenced)."""
+    lib = B._lib()
+    null, fake = ctypes.c_void_p(0), ctypes.c_void_p(4096)
+    n, hk, hv, nc, ns = 128, 2, 4, 2, 1
+    plan = [fake] * 4                                        # chunk_tok0, chunk_len, chunk_src, chunk_dst
+
+    def fwd(*, dk=128, dv=128, hv_=hv, scale=0.1, q=fake, o=fake, cap=null, state_out=null, ws=fake, ws_bytes=1 << 40):
+        return lib.tt_tree_gdn_fwd(n, hk, hv_, dk, dv, scale, q, fake, fake, fake, fake, nc, *plan, ns, cap, null, state_out, o, ws,
+                                   ws_bytes, null)
+
+    def bwd(*, dk=128, hv_=hv, scale=0.1, q=fake, d_o=fake, dq=ctypes.c_void_p(24576), cap=null, d_state_out=null, ws=fake, ws_bytes=1 << 40):
+        return lib.tt_tree_gdn_bwd(n, hk, hv_, dk, 128, scale, q, fake, fake, fake, fake, d_o, nc, *plan, ns, cap, null, d_state_out,
+                                   dq, ctypes.c_void_p(8192), ctypes.c_void_p(12288), ctypes.c_void_p(16384),
+                                   ctypes.c_void_p(20480), null, ws, ws_bytes, null)
+
+    assert lib.tt_tree_gdn_workspace(nc, ns, hv) > 0
+    assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, hk, hv) > lib.tt_tree_gdn_workspace(nc, ns, hv)
+    assert fwd(dk=64) == -8 and bwd(dk=64) == -8             # only 128 x 128 states (TT_ERR_UNSUPPORTED)
+    assert fwd(hv_=3) == -2 and bwd(hv_=3) == -2             # hv not a multiple of hk
+    assert fwd(scale=0.0) == -2 and bwd(scale=float("nan")) == -2
+    assert fwd(q=null) == -1 and bwd(d_o=null) == -1 and bwd(dq=null) == -1
+    assert fwd(cap=fake) == -1                               # chunk_cap without state_out
+    assert bwd(d_state_out=fake) == -1                       # d_state_out without chunk_cap
+    assert fwd(q=ctypes.c_void_p(4100)) == -5 and bwd(q=ctypes.c_void_p(4100)) == -5
+    assert fwd(ws=null) == -6 and fwd(ws_bytes=16) == -6 and bwd(ws=null) == -6 and bwd(ws_bytes=16) == -6
+    assert bwd(dq=fake, q=fake) == -2                        # an output aliases an input
+    assert T.last_error()
