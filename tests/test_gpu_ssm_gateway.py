@@ -162,3 +162,28 @@ def test_conv_context_gateway(seed, cap, K):
         e = rel_l2(a, bq)
         print(f"   {name}: rel-L2 {e:.2e}", flush=True)
         assert e <= tol, (name, e)
+
+
+def test_gdn_initial_state_zero_equals_none():
+    """No initial state and an explicit all-zero initial state are the same computation: every output of the
+    backward, the gradient of the initial state included, must agree bit for bit."""
+    tree = W.random_tree(1234, n_nodes=9, lo=5, hi=120, n_roots=2)
+    whole = M.dfs_meta(tree.parent, tree.seg_len)
+    n, hk, hv = whole["n_tokens"], 1, 2
+    g_ = torch.Generator().manual_seed(5)
+    q = torch.randn((n, hk, 128), generator=g_); k = torch.randn((n, hk, 128), generator=g_)
+    q = (q / q.norm(dim=-1, keepdim=True)).to(torch.bfloat16).cuda()
+    k = (k / k.norm(dim=-1, keepdim=True)).to(torch.bfloat16).cuda()
+    v = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16).cuda()
+    g = (-(torch.rand((n, hv), generator=g_) * 0.2 + 0.005)).cuda()
+    beta = (torch.rand((n, hv), generator=g_) * 0.8 + 0.1).cuda()
+    d_o = torch.randn((n, hv, 128), generator=g_).to(torch.bfloat16).cuda()
+    plan = T.tree_gdn_plan(tree.parent, tree.seg_len)
+    print(f"[case] gdn zero initial state: N={n}, {plan.n_chunks} chunks", flush=True)
+    a = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, want_d_initial_state=True)
+    zero = torch.zeros((hv, 128, 128), dtype=torch.float32, device="cuda")
+    b = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, initial_state=zero, want_d_initial_state=True)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    assert torch.isfinite(a[5]).all() and float(a[5].abs().max()) > 0      # two roots send gradient into it
