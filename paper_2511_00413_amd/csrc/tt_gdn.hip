@@ -93,15 +93,17 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   const size_t op = op_index(a, chunk, h);
 
   if (tid < GC) {
+    // running sum of the log-decays over the chunk: a parallel scan inside the first wave
     const bool in = tid < len;
-    gam[tid] = in ? a.g[(size_t)(tok0 + tid) * a.hv + h] : 0.f;
+    float run = in ? a.g[(size_t)(tok0 + tid) * a.hv + h] : 0.f;
     bet[tid] = in ? a.beta[(size_t)(tok0 + tid) * a.hv + h] : 0.f;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    float run = 0.f;
-    for (int i = 0; i < GC; i++) { run += gam[i]; gam[i] = run; }
-    a.glast[op] = __expf(run);
+#pragma unroll
+    for (int d = 1; d < GC; d <<= 1) {
+      const float up = __shfl_up(run, d);
+      if (tid >= d) run += up;
+    }
+    gam[tid] = run;
+    if (tid == GC - 1) a.glast[op] = __expf(run);
   }
   __syncthreads();
   const float g_last = gam[GC - 1];
