@@ -92,6 +92,26 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   const int tok0 = a.chunk_tok0[chunk], len = a.chunk_len[chunk];
   const size_t op = op_index(a, chunk, h);
 
+  // Every row load of the chunk is issued here, in one straight-line block (K, Q, V -- and dO in the backward
+  // form -- as four 16-byte pieces per thread each), so that the trips to memory overlap each other and the scan
+  // below.  Rows past the chunk's length read the last valid row and are zeroed on their way into LDS.  (Loaded
+  // piece by piece inside the staging loops, behind a row-in-range branch, every piece is waited for in turn.)
+  constexpr int NPIECE = GC * (GD / 8) / G_THREADS;
+  bf16x8 kreg[NPIECE], qreg[NPIECE], vreg[NPIECE];
+  [[maybe_unused]] bf16x8 doreg[NPIECE];
+#pragma unroll
+  for (int p = 0; p < NPIECE; p++) {
+    const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
+    const size_t row = (size_t)(tok0 + min(i, len - 1));
+    kreg[p] = *(const bf16x8*)(a.k + (row * a.hk + hkv) * GD + c8);
+    qreg[p] = *(const bf16x8*)(a.q + (row * a.hk + hkv) * GD + c8);
+    vreg[p] = *(const bf16x8*)(a.v + (row * a.hv + h) * GD + c8);
+    if constexpr (BWD) doreg[p] = *(const bf16x8*)(a.d_o + (row * a.hv + h) * GD + c8);
+  }
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; e++) zero8[e] = (__bf16)0.f;
+
   if (tid < GC) {
     // running sum of the log-decays over the chunk: a parallel scan inside the first wave
     const bool in = tid < len;
@@ -112,15 +132,10 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   }
 
   // K and Q rows into LDS (zero rows past the chunk's length); Qg written on the way
-  for (int piece = tid; piece < GC * (GD / 8); piece += G_THREADS) {
-    const int i = piece >> 4, c8 = (piece & 15) * 8;
-    bf16x8 kv, qv;
 #pragma unroll
-    for (int e = 0; e < 8; e++) { kv[e] = (__bf16)0.f; qv[e] = (__bf16)0.f; }
-    if (i < len) {
-      kv = *(const bf16x8*)(a.k + ((size_t)(tok0 + i) * a.hk + hkv) * GD + c8);
-      qv = *(const bf16x8*)(a.q + ((size_t)(tok0 + i) * a.hk + hkv) * GD + c8);
-    }
+  for (int p = 0; p < NPIECE; p++) {
+    const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
+    const bf16x8 kv = i < len ? kreg[p] : zero8, qv = i < len ? qreg[p] : zero8;
     *(bf16x8*)&ksm[i][c8] = kv;
     *(bf16x8*)&qsm[i][c8] = qv;
     if constexpr (!BWD) *(bf16x8*)(a.rec + op * REC_ELEMS + REC_QG + i * GD + c8) = scale_frag(qv, a.scale * __expf(gam[i]));
@@ -192,13 +207,10 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __syncthreads();
   if constexpr (BWD) {
     // dO^T: the rows of dO go through the Q tile's LDS (free now) and leave transposed
-    for (int piece = tid; piece < GC * (GD / 8); piece += G_THREADS) {
-      const int i = piece >> 4, c8 = (piece & 15) * 8;
-      bf16x8 dv;
 #pragma unroll
-      for (int e = 0; e < 8; e++) dv[e] = (__bf16)0.f;
-      if (i < len) dv = *(const bf16x8*)(a.d_o + ((size_t)(tok0 + i) * a.hv + h) * GD + c8);
-      *(bf16x8*)&qsm[i][c8] = dv;
+    for (int p = 0; p < NPIECE; p++) {
+      const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
+      *(bf16x8*)&qsm[i][c8] = i < len ? doreg[p] : zero8;
     }
     __syncthreads();
     for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
@@ -208,20 +220,25 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       for (int e = 0; e < 8; e++) o[e] = qsm[i0 + e][d];
       *(bf16x8*)(a.rev + op * REV_ELEMS + REV_DOT + d * GC + i0) = o;
     }
+    __syncthreads();
   }
+  // V rows into the Q tile's LDS (free now): the solve below reads its value columns from there
+#pragma unroll
+  for (int p = 0; p < NPIECE; p++) {
+    const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
+    *(bf16x8*)&qsm[i][c8] = i < len ? vreg[p] : zero8;
+  }
+  __syncthreads();
 
   // forward substitution, one lane per column of [beta V | beta exp(gamma) K]:
   //   x_i = rhs_i - sum_{j<i} A_ij x_j
   {
     const int c = tid;                  // 0..127: value column, 128..255: key column
     float x[GC];
-    // right-hand sides first.  The value columns come from memory: 64 independent loads per lane in one
-    // straight-line block, so that they are all in flight together (inside a per-row branch each one
-    // was waited for in turn).
+    // right-hand sides first
     if (c < GD) {
-      const __bf16* vcol = a.v + ((size_t)tok0 * a.hv + h) * GD + c;
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = (float)vcol[(size_t)min(i, len - 1) * a.hv * GD];
+      for (int i = 0; i < GC; i++) x[i] = (float)qsm[i][c];
     } else {
 #pragma unroll
       for (int i = 0; i < GC; i++) x[i] = __expf(gam[i]) * (float)ksm[i][c - GD];
