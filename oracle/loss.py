@@ -15,15 +15,23 @@ def _f64(x) -> np.ndarray:
     return np.asarray(x, dtype=np.float64)
 
 
+def _used(target, vocab):
+    """Rows that enter the loss: the target names a vocabulary entry.  A negative target is the usual
+    "ignore" marker; a target >= vocab names no class either and is read the same way (the paper's
+    objective, "Derivation" section, is only defined for y_t in the vocabulary)."""
+    return (target >= 0) & (target < vocab)
+
+
 def log_softmax_gather(logits, target):
-    """Per row: lse = log sum_v exp(z_v); logp = z[target] - lse (0 where target < 0)."""
+    """Per row: lse = log sum_v exp(z_v); logp = z[target] - lse (0 on ignored rows, see _used)."""
     z = _f64(logits)
     target = np.asarray(target).astype(np.int64)
+    used = _used(target, z.shape[1])
     m = z.max(axis=1)
     lse = m + np.log(np.exp(z - m[:, None]).sum(axis=1))
-    safe = np.where(target >= 0, target, 0)
+    safe = np.where(used, target, 0)
     logp = z[np.arange(z.shape[0]), safe] - lse
-    logp = np.where(target >= 0, logp, 0.0)
+    logp = np.where(used, logp, 0.0)
     return logp, lse
 
 
@@ -49,8 +57,8 @@ def loss_sep_avg(paths, logp, trained_tok, adv=None) -> float:
 
 def dlogits(logits, target, weight, lse=None, grad_scale: float = 1.0) -> np.ndarray:
     """Gradient of grad_scale * sum_r weight_r * (-logp_r) with respect to the logits:
-    d/dz_rv = grad_scale * weight_r * (softmax(z_r)_v - [v == target_r]); rows with a negative
-    target contribute nothing to the loss and get a zero gradient.  (Derivative of Eq. 4 through
+    d/dz_rv = grad_scale * weight_r * (softmax(z_r)_v - [v == target_r]); ignored rows (_used)
+    contribute nothing to the loss and get a zero gradient.  (Derivative of Eq. 4 through
     l_t = -log softmax; `lse` may be passed in, it is what the forward pass saved.)"""
     z = _f64(logits)
     target = np.asarray(target).astype(np.int64)
@@ -59,8 +67,9 @@ def dlogits(logits, target, weight, lse=None, grad_scale: float = 1.0) -> np.nda
         _, lse = log_softmax_gather(z, target)
     p = np.exp(z - _f64(lse)[:, None])
     g = p.copy()
-    rows = np.nonzero(target >= 0)[0]
+    used = _used(target, z.shape[1])
+    rows = np.nonzero(used)[0]
     g[rows, target[rows]] -= 1.0
     g *= (grad_scale * w)[:, None]
-    g[target < 0] = 0.0
+    g[~used] = 0.0
     return g

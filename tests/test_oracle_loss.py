@@ -106,3 +106,27 @@ def test_dlogits_against_library_autograd():
     loss = (torch.tensor(w * (y >= 0)) * nll).sum()
     loss.backward()
     assert np.allclose(zt.grad.numpy(), L.dlogits(z, y, w), rtol=1e-12, atol=1e-14)
+
+
+def test_ignored_rows_against_library_ignore_index():
+    """A negative target and a target >= vocab are both ignored rows: zero loss term, zero gradient.
+    Pinned to the library's cross entropy with ignore_index (sum reduction) and its autograd."""
+    V = 50
+    logits, target = W.loss_inputs(12, V, 5, std=2.0)
+    target = target.clone().long()
+    target[3] = -1
+    target[7] = V            # first value outside the vocabulary
+    target[9] = V + 1000
+    w = np.linspace(0.5, 1.5, 12)
+    logp, _ = L.log_softmax_gather(logits, target.numpy())
+    assert logp[3] == 0.0 and logp[7] == 0.0 and logp[9] == 0.0
+    z = logits.double().clone().requires_grad_(True)
+    lib_t = target.clone()
+    lib_t[(lib_t < 0) | (lib_t >= V)] = -100
+    per_row = torch.nn.functional.cross_entropy(z, lib_t, ignore_index=-100, reduction="none")
+    loss = (torch.from_numpy(w) * per_row).sum()
+    loss.backward()
+    assert abs(L.loss_tree(logp, w) - float(loss.detach())) < 1e-12
+    g = L.dlogits(logits, target.numpy(), w)
+    assert np.allclose(g, z.grad.numpy(), atol=1e-13)
+    assert np.all(g[[3, 7, 9]] == 0.0)
