@@ -233,23 +233,22 @@ def mask_common_path(meta) -> np.ndarray:
 
 
 def mask_chunks(meta) -> np.ndarray:
-    """Appendix "Tree Attention Mask via FlashMask": full access to every ancestor chunk, causal
-    inside the own chunk."""
-    n = meta["n_tokens"]
-    par = meta["node_parent"]
-    m = np.zeros((n, n), dtype=bool)
-    for c in range(meta["n_nodes"]):
-        cs, ce = int(meta["node_start"][c]), int(meta["node_end"][c])
-        a = c
-        while a >= 0:
-            as_, ae = int(meta["node_start"][a]), int(meta["node_end"][a])
-            for i in range(cs, ce):
-                if a == c:
-                    m[i, cs:i + 1] = True
-                else:
-                    m[i, as_:ae] = True
-            a = int(par[a])
-    return m
+    """Appendix "Tree Attention Mask via FlashMask": a token has full access to the chunk of every
+    strict ancestor of its node and causal access inside its own chunk.  Stated at node level first
+    (which chunks a chunk may look at), then expanded to tokens."""
+    nn, n = meta["n_nodes"], meta["n_tokens"]
+    par = np.asarray(meta["node_parent"])
+    tn = np.asarray(meta["tok_node"])
+    # strict_anc[c, a]: a is a strict ancestor of c (nodes are in pre-order, so parents come first)
+    strict_anc = np.zeros((nn, nn), dtype=bool)
+    for c in range(nn):
+        if par[c] >= 0:
+            strict_anc[c] = strict_anc[par[c]]
+            strict_anc[c, par[c]] = True
+    tok = np.arange(n)
+    ancestor_chunk = strict_anc[tn[:, None], tn[None, :]]                       # all of an ancestor's tokens
+    own_chunk_causal = (tn[:, None] == tn[None, :]) & (tok[None, :] <= tok[:, None])
+    return ancestor_chunk | own_chunk_causal
 
 
 def por(n_tree: int, n_base: int) -> float:
