@@ -89,12 +89,18 @@ def branches(meta, q, k, v, d_o=None, scale: Optional[float] = None, kv_heads: O
 
 
 def rows(meta, q, k, v, d_o, kvh: int, row_tokens: Sequence[int], key_tokens: Sequence[int] = (),
-         scale: Optional[float] = None, real: str = "f64"):
+         scale: Optional[float] = None, real: str = "f64", complete_keys: bool = True):
     """Sampled outputs for key/value head `kvh` and its query heads.
 
     o/lse/dq are returned for `row_tokens`; dk/dv for `key_tokens`.  For dk/dv to be complete, every
     token that can see a wanted key is evaluated as well (all tokens from the key to the end of its
     node's subtree) -- they are appended to the evaluated rows automatically.
+
+    complete_keys=False evaluates `row_tokens` only: dk/dv then hold the contributions of those query
+    rows alone.  By Eq. 5 every term of dK_j / dV_j carries a factor dO_i (dV_j = sum_i P_ij dO_i,
+    dS_ij = P_ij (dO_i . V_j - dO_i . O_i)), so this is the complete gradient whenever d_o is zero on
+    every token outside `row_tokens` -- which makes a key near the root, seen by tens of thousands of
+    queries, checkable at full size.
     """
     q, k, v = _f32(q), _f32(k), _f32(v)
     n, hq, d = q.shape
@@ -106,7 +112,7 @@ def rows(meta, q, k, v, d_o, kvh: int, row_tokens: Sequence[int], key_tokens: Se
     row_tokens = [int(t) for t in row_tokens]
     need = list(row_tokens)
     have = set(need)
-    for j in key_tokens:
+    for j in (key_tokens if complete_keys else ()):
         end = int(meta["subtree_end"][meta["tok_node"][int(j)]])
         for t in range(int(j), end):
             if t not in have:

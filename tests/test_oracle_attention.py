@@ -145,6 +145,31 @@ def test_rows_matches_branches():
         assert rel_l2(s["dv"], full["dv"][keys][:, kvh]) < 1e-12
 
 
+def test_rows_restricted_to_a_query_subset():
+    """complete_keys=False: with d_o zero outside the subset, the subset's contributions are the whole
+    dK / dV (every term of Eq. 5's sum carries a factor dO_i); pinned against branches() on the masked d_o,
+    and against the unrestricted rows() call on the same masked d_o."""
+    t = W.random_tree(6, n_nodes=8, lo=2, hi=9)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n = m["n_tokens"]
+    q, k, v, do = _inputs(n, 4, 2, 8, 12)
+    subset = sorted({1, n // 4, n // 2, n - 2, n - 1})
+    do_masked = torch.zeros_like(do)
+    do_masked[subset] = do[subset]
+    full = A.branches(m, q, k, v, do_masked)
+    keys = [0, 1, n // 4, n - 1]
+    for kvh in (0, 1):
+        s = A.rows(m, q, k, v, do_masked, kvh, subset, keys, complete_keys=False)
+        assert s["n_rows_evaluated"] == len(subset)
+        assert rel_l2(s["dk"], full["dk"][keys][:, kvh]) < 1e-12
+        assert rel_l2(s["dv"], full["dv"][keys][:, kvh]) < 1e-12
+        c = A.rows(m, q, k, v, do_masked, kvh, subset, keys)
+        assert rel_l2(s["dk"], c["dk"]) < 1e-12 and rel_l2(s["dv"], c["dv"]) < 1e-12
+    # and it is NOT the whole gradient when d_o is not masked (the option really drops rows)
+    s = A.rows(m, q, k, v, do, 0, subset, [0], complete_keys=False)
+    assert rel_l2(s["dv"], A.branches(m, q, k, v, do)["dv"][[0]][:, 0]) > 1e-2
+
+
 def test_fp32_variant_close_to_fp64():
     t = W.tree_cfg1()
     m = M.dfs_meta(t.parent, t.seg_len)
