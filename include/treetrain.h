@@ -331,7 +331,9 @@ tt_status tt_tree_attn_partitioned_bwd(const tt_attn_desc* desc, const tt_partit
  * token (times an advantage for policy-gradient objectives, "Derivation" section).  The logits
  * are read from memory once.
  *   logits [n_rows][vocab], row stride `row_stride` elements (0 = vocab), dtype bf16 or fp32.
- *   target [n_rows] int32; a negative target gives logp = 0 and adds nothing.
+ *   target [n_rows] int32; a row whose target is negative or >= vocab is ignored: logp = 0, nothing
+ *     is added to the loss (lse is still written).  The targets live in device memory, so they are
+ *     not validated on the host; this rule is what the kernels do with an out-of-range value.
  *   weight [n_rows] fp32 or NULL (= 1).
  *   logp   [n_rows] fp32, required (also the staging for the deterministic reduction).
  *   lse    [n_rows] fp32 or NULL.
@@ -352,7 +354,8 @@ tt_status tt_tree_weighted_logprob(int64_t n_rows, int32_t vocab, int32_t dtype,
  * Gradient of grad_scale * sum_r weight_r * (-logp_r) (Eq. 4 through l_t = -log softmax) with
  * respect to the logits:
  *   dlogits[r][v] = grad_scale * weight_r * (exp(z_rv - lse_r) - [v == target_r]),
- * zero for rows with a negative target.  One read of the logits, one write of the gradient.
+ * exactly zero for ignored rows (target negative or >= vocab, the same rule as the forward;
+ * lse[r] of such a row is not read).  One read of the logits, one write of the gradient.
  *   logits, target, weight as for tt_tree_weighted_logprob; lse [n_rows] fp32 from that call
  *   (required).  dlogits [n_rows][vocab], row stride `dlogits_row_stride` elements (0 = vocab),
  *   same dtype as the logits (bf16: round to nearest even); it may alias logits when the two

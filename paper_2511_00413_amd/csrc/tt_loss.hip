@@ -202,8 +202,12 @@ row_dlogits_kernel(int vocab, const T* logits, int64_t row_stride, const int32_t
   T* out = dlogits + r * out_stride;
   const int t = threadIdx.x;
   const int y = target[r];
-  const float w = y >= 0 ? grad_scale * (weight ? weight[r] : 1.f) : 0.f;     // ignored row: zeros
-  const float lse = y >= 0 ? lse_in[r] : 0.f;
+  // A row whose target is negative or not below the vocabulary size is ignored, as in the forward (logp = 0,
+  // nothing added to the loss): its gradient is exactly zero -- weight 0 and lse = +inf, so that every
+  // exponential is 0 whatever the logits and whatever the caller left in lse[r].
+  const bool used = y >= 0 && y < vocab;
+  const float w = used ? grad_scale * (weight ? weight[r] : 1.f) : 0.f;
+  const float lse = used ? lse_in[r] : INFINITY;
   const bool vec_ok = ((reinterpret_cast<uintptr_t>(row) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
   const int nvec = vec_ok ? vocab / EPV : 0;
   const u32x4* vp = reinterpret_cast<const u32x4*>(row);

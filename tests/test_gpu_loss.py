@@ -111,8 +111,8 @@ def _check_bwd(logits, target, weight, grad_scale=1.0, inplace=False):
         assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-7 * np.abs(want).max())
     else:
         assert num / den <= 1e-5, num / den
-    # ignored rows are exactly zero
-    ign = target.numpy() < 0
+    # ignored rows (target negative or not below the vocabulary size) are exactly zero
+    ign = (target.numpy() < 0) | (target.numpy() >= logits.shape[1])
     assert np.all(got[ign] == 0.0)
     return got
 
@@ -127,6 +127,35 @@ def test_bwd_shapes_and_misaligned_rows(rows, vocab, dtype):
         target[1] = -1
     w = (np.random.default_rng(rows).random(rows) + 0.25).astype(np.float32)
     _check_bwd(logits, target, w, grad_scale=0.5)
+
+
+def test_out_of_range_target_is_an_ignored_row():
+    """target >= vocab: forward gives logp = 0 and adds nothing, backward gives an exactly zero row -- also
+    when the logits are large and the lse entry of that row holds garbage."""
+    V = 1000
+    logits, target = W.loss_inputs(8, V, 31, 2.0, "bf16")
+    logits = logits.clone()
+    logits[2] = 300.0                      # exp(300) overflows fp32: must not turn 0 * inf into NaN
+    target = target.clone()
+    target[2] = V
+    target[5] = V + 12345
+    target[6] = -7
+    w = np.linspace(0.5, 2.0, 8).astype(np.float32)
+    logp, lse, loss = _run(logits, target, w)
+    wl, _ = L.log_softmax_gather(logits, target.numpy())
+    assert logp[2] == 0.0 and logp[5] == 0.0 and logp[6] == 0.0
+    assert np.allclose(logp, wl, rtol=1e-6, atol=4e-5)
+    assert abs(loss - L.loss_tree(wl, w)) <= 1e-5 * abs(L.loss_tree(wl, w))
+    got = _check_bwd(logits, target, w, grad_scale=2.0)
+    assert np.all(got[[2, 5, 6]] == 0.0) and np.isfinite(got).all()
+    # garbage in the saved lse of the ignored rows changes nothing
+    lg, tg, wt = logits.cuda(), target.cuda(), torch.from_numpy(w).cuda()
+    _, lse_d, _ = T.tree_weighted_logprob(lg, tg, wt)
+    lse_d = lse_d.clone()
+    lse_d[[2, 5, 6]] = float("nan")
+    again = T.tree_weighted_logprob_bwd(lg, tg, wt, lse_d, grad_scale=2.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(again.float().cpu().numpy(), got.astype(np.float32))
 
 
 def test_bwd_in_place_and_no_weight():
