@@ -8,10 +8,10 @@
 //
 // Kernels, no atomics (results are bit-reproducible); the dK/dV pass lives in tt_attn_dkdv.hip:
 //   delta     D_i                                                      (memory bound)
-//   dkdv      column-parallel: one workgroup = 128 keys x one kv head, 4 wavefronts x 32 keys;
-//             loops over the query heads of the group and over the query tiles that can see the
-//             keys -- a contiguous range [first key, max kend) because in DFS order a subtree is
-//             contiguous.  S[q,key] = Q K^T and dP[q,key] = dO V^T come out with one key per lane,
+//   dkdv      column-parallel: one work item = a key tile of up to 256 keys x one kv head, 8 wavefronts
+//             x 32 keys; loops over the query heads of the group and over the 64-query steps that can
+//             see the keys -- a contiguous range [first key, max kend) because in DFS order a subtree
+//             is contiguous.  S[q,key] = Q K^T and dP[q,key] = dO V^T come out with one key per lane,
 //             already in B-operand layout for dV^T[d,key] += dO^T[d,q] P[q,key] and
 //             dK^T[d,key] += Q^T[d,q] dS[q,key]; Q^T / dO^T come from transposed LDS reads.
 //   dq        row-parallel, same structure as the forward: S^T = K Q^T, dP^T = V dO^T with one
@@ -271,7 +271,7 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
     u_cur = u_next;                                                                                     \
     cls_cur = cls_next;                                                                                 \
   }
-  // candidate tiles are classified in chunks of 64 *   // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
+  // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
   // longer than 262144 keys)
   KTileIter it;
   it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);

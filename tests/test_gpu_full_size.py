@@ -3,7 +3,11 @@ times.  The per-branch oracle is too slow to run in full there, so it is evaluat
 complete key/value head group on config 2 and (b) for sampled outputs elsewhere: O / LSE / dQ rows of
 sampled query tokens and dK / dV of sampled key tokens (the oracle then evaluates every query that
 can see the key).  For the cached-prefix step of config 5 the prefix gradients are additionally
-checked through the column-sum identity sum_j dV_j = sum_i dO_i (softmax rows sum to one)."""
+checked through the column-sum identity sum_j dV_j = sum_i dO_i (softmax rows sum to one).
+Keys near the root, which tens of thousands of queries see and whose gradients go through the cut
+tiles' partial sums, are checked with an upstream gradient that is zero outside a sample of query
+rows (test_large_configs_trunk_keys).  Every comparison asserts the whole-sample relative L2 and the
+largest per-row error (tt_testutil.ATTN_TOL)."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +16,7 @@ import paper_2511_00413_amd as T
 import workloads as W
 from oracle import attention as A
 from oracle import meta as M
-from tt_testutil import rel_l2
+from tt_testutil import assert_attention_close, dq_allowance, rel_l2
 
 pytestmark = pytest.mark.gpu
 TOL = dict(o=1e-2, lse=1e-2, dq=2e-2, dk=2e-2, dv=2e-2)
@@ -39,18 +43,18 @@ def _sample_check(om, got, q, k, v, do, kvh, rows, keys, G, offset=0):
     s = A.rows(om, q, k, v, do, kvh, rows, keys)
     hs = slice(kvh * G, kvh * G + G)
     ridx = torch.tensor([r - offset for r in rows], device="cuda")
-    errs = dict(
-        o=rel_l2(got["o"][ridx][:, hs].float().cpu().numpy(), s["o"]),
-        lse=rel_l2(got["lse"][hs][:, ridx].T.cpu().numpy(), s["lse"]),
-        dq=rel_l2(got["dq"][ridx][:, hs].float().cpu().numpy(), s["dq"]))
+    mine = dict(o=got["o"][ridx][:, hs].float().cpu().numpy(), lse=got["lse"][hs][:, ridx].T.cpu().numpy(),
+                dq=got["dq"][ridx][:, hs].float().cpu().numpy())
+    want = dict(o=s["o"], lse=s["lse"], dq=s["dq"])
     if len(keys):
         kidx = torch.tensor([j - offset for j in keys], device="cuda")
-        errs["dk"] = rel_l2(got["dk"][kidx][:, kvh].float().cpu().numpy(), s["dk"])
-        errs["dv"] = rel_l2(got["dv"][kidx][:, kvh].float().cpu().numpy(), s["dv"])
-    print(f"   kvh {kvh}: rows {len(rows)} keys {len(keys)} (oracle evaluated {s['n_rows_evaluated']} rows) rel-L2:",
-          {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
-    for key, e in errs.items():
-        assert e <= TOL[key], (key, e)
+        mine["dk"], mine["dv"] = got["dk"][kidx][:, kvh].float().cpu().numpy(), got["dv"][kidx][:, kvh].float().cpu().numpy()
+        want["dk"], want["dv"] = s["dk"], s["dv"]
+    kmax = float(np.linalg.norm(k[:, kvh].numpy(), axis=-1).max())
+    allow = dq_allowance(do[rows][:, hs].numpy(), s["o"], kmax, k.shape[-1] ** -0.5, "bf16")
+    assert_attention_close(mine, want, "bf16",
+                           f"kvh {kvh}: rows {len(rows)} keys {len(keys)} (oracle evaluated {s['n_rows_evaluated']} rows)",
+                           dq_allow=allow)
 
 
 def test_cfg2_full_group_and_samples():
@@ -64,14 +68,13 @@ def test_cfg2_full_group_and_samples():
     qf, kf, vf, dof = q.float(), k.float(), v.float(), do.float()
     G = dims.hq // dims.hkv
     want = A.branches(om, qf, kf, vf, dof, kv_heads=[0])
-    errs = dict(o=rel_l2(got["o"][:, :G].float().cpu().numpy(), want["o"][:, :G]),
-                lse=rel_l2(got["lse"][:G].cpu().numpy(), want["lse"][:G]),
-                dq=rel_l2(got["dq"][:, :G].float().cpu().numpy(), want["dq"][:, :G]),
-                dk=rel_l2(got["dk"][:, 0].float().cpu().numpy(), want["dk"][:, 0]),
-                dv=rel_l2(got["dv"][:, 0].float().cpu().numpy(), want["dv"][:, 0]))
-    print("   complete kv group 0 rel-L2:", {k_: f"{e:.2e}" for k_, e in errs.items()}, flush=True)
-    for key, e in errs.items():
-        assert e <= TOL[key], (key, e)
+    mine = dict(o=got["o"][:, :G].float().cpu().numpy(), lse=got["lse"][:G].cpu().numpy(),
+                dq=got["dq"][:, :G].float().cpu().numpy(), dk=got["dk"][:, 0].float().cpu().numpy(),
+                dv=got["dv"][:, 0].float().cpu().numpy())
+    ref = dict(o=want["o"][:, :G], lse=want["lse"][:G], dq=want["dq"][:, :G], dk=want["dk"][:, 0], dv=want["dv"][:, 0])
+    kmax = float(np.linalg.norm(kf[:, 0].numpy(), axis=-1).max())
+    assert_attention_close(mine, ref, "bf16", "complete kv group 0",
+                           dq_allow=dq_allowance(dof[:, :G].numpy(), ref["o"], kmax, dims.d ** -0.5, "bf16"))
     # other groups: sampled rows at tile edges and node boundaries, keys in leaves
     ns, ne = om["node_start"], om["node_end"]
     rows = sorted({0, 63, 64, 127, 128, int(ns[1]), int(ne[1]) - 1, int(ns[-1]), n - 1, n // 2})
@@ -104,6 +107,41 @@ def test_large_configs_sampled(cfg):
     dv_sum = got["dv"].float().sum(dim=0).cpu().numpy()                       # [hkv, d]
     do_sum = do.float().view(n, dims.hkv, G, dims.d).sum(dim=(0, 2)).numpy()
     assert rel_l2(dv_sum, do_sum) <= 2e-2
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_large_configs_trunk_keys(cfg):
+    """dK / dV of keys near the root at full size.  Such a key is seen by every query of its subtree, too
+    many for the oracle; but every term of its gradient carries a factor dO_i (Eq. 5), so with an
+    upstream gradient that is zero outside a sample of query rows the sample's contributions are the
+    whole gradient.  The GPU call is the ordinary full-size backward (all tiles, all chunks of the cut
+    tiles, the ordered reduce); only d_o differs.  The sampled rows are spread over the whole subtree so
+    that every chunk of the trunk's tiles contributes."""
+    tree, dims = W.tree_config(cfg), W.DIMS[cfg]
+    meta = T.tree_build_meta(tree.parent, tree.seg_len, tree.trained)
+    om = M.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    n = meta.n_tokens
+    q, k, v, do = W.attn_inputs(n, n, dims, cfg)
+    rng = np.random.default_rng(100 + cfg)
+    ns, ne = om["node_start"], om["node_end"]
+    n_rows = 96 if cfg == 2 else 48
+    rows = np.unique(np.concatenate([rng.choice(n, n_rows, replace=False), [0, int(ne[0]) - 1, int(ns[1]), n - 1]]))
+    do_masked = torch.zeros_like(do)
+    do_masked[torch.from_numpy(rows)] = do[torch.from_numpy(rows)]
+    print(f"[case] cfg{cfg} trunk keys, N={n}, d_o non-zero on {len(rows)} rows", flush=True)
+    got = _run_gpu(meta, q, k, v, do_masked)
+    G = dims.hq // dims.hkv
+    # keys of the root node (first, a tile edge, last) and of the first child (seen by its subtree only)
+    keys = sorted({0, 63, 64, int(ne[0]) // 2, int(ne[0]) - 1, int(ns[1]), int(ne[1]) - 1})
+    for kvh in (0, dims.hkv - 1):
+        s = A.rows(om, q.float(), k.float(), v.float(), do_masked.float(), kvh, [int(r) for r in rows], keys,
+                   complete_keys=False)
+        kidx = torch.tensor(keys, device="cuda")
+        mine = dict(dk=got["dk"][kidx][:, kvh].float().cpu().numpy(), dv=got["dv"][kidx][:, kvh].float().cpu().numpy())
+        assert_attention_close(mine, dict(dk=s["dk"], dv=s["dv"]), "bf16", f"kvh {kvh}: {len(keys)} trunk keys")
+    # rows outside the sample have zero upstream gradient: their dQ is exactly zero
+    outside = np.setdiff1d(np.arange(n), rows)[:: max(1, n // 512)]
+    assert float(got["dq"][torch.from_numpy(outside).cuda()].float().abs().max()) == 0.0
 
 
 def test_cfg5_partition_step_sampled():
@@ -183,6 +221,8 @@ def test_cfg2_partitioned_quarter_capacity():
     torch.cuda.synchronize()
     got = dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
     whole = _run_gpu(meta, q, k, v, do)
+    # the partitioned run against the whole-tree call of the same library: both carry bf16 rounding, so
+    # the whole-tensor bound applies (the per-row comparison is against the oracle, below)
     for key in TOL:
         e = rel_l2(got[key].float().cpu().numpy(), whole[key].float().cpu().numpy())
         assert e <= TOL[key], (key, e)
@@ -274,7 +314,7 @@ def test_cfg2_gdn_backward_one_key_head():
     want = S.gdn_tree_bwd(q[:, kh:kh + 1].float().numpy(), k[:, kh:kh + 1].float().numpy(), v[:, hs].float().numpy(),
                           gl[:, hs].numpy(), beta[:, hs].numpy(), meta.tok_pred, d_o[:, hs].float().numpy())
     sel = (got[0][:, kh:kh + 1], got[1][:, kh:kh + 1], got[2][:, hs], got[3][:, hs], got[4][:, hs])
-    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), sel, want, (2e-2, 2e-2, 2e-2, 2e-2, 2e-2)):
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), sel, want, (8e-3, 8e-3, 8e-3, 8e-3, 8e-3)):
         e = rel_l2(a.float().cpu().numpy(), b)
         print(f"   {name}: rel-L2 {e:.2e}", flush=True)
         assert e <= tol, (name, e)

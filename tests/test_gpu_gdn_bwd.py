@@ -41,7 +41,7 @@ def _check(tree, hk, hv, seed):
     got = [t.float().cpu().numpy() for t in got]
     want = S.gdn_tree_bwd(q.float().numpy(), k.float().numpy(), v.float().numpy(), g.numpy(), beta.numpy(), m["tok_pred"],
                           d_o.float().numpy())
-    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (2e-2, 2e-2, 2e-2, 2e-2, 2e-2)):
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (8e-3, 8e-3, 8e-3, 8e-3, 8e-3)):
         e = rel_l2(a, b)
         print(f"   {name}: rel-L2 {e:.2e}", flush=True)
         assert np.isfinite(a).all(), name

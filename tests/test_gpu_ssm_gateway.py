@@ -109,7 +109,7 @@ def test_gdn_state_gateway_backward(seed, cap):
             dstt[own.numpy()] = t.float().cpu().numpy()
         if cn >= 0:
             d_cut[cn] = d_cut[cn] + out[5] if cn in d_cut else out[5]
-    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (2e-2, 2e-2, 2e-2, 2e-2, 2e-2)):
+    for name, a, b, tol in zip(("dq", "dk", "dv", "dg", "dbeta"), got, want, (8e-3, 8e-3, 8e-3, 8e-3, 8e-3)):
         e = rel_l2(a, b)
         print(f"   {name}: rel-L2 {e:.2e}", flush=True)
         assert e <= tol, (name, e)
