@@ -69,7 +69,7 @@ def main():
 
     import torch
     import paper_2511_00413_amd as T
-    from paper_2511_00413_amd import linearize
+    import linearize
     import workloads as W
 
     if not torch.cuda.is_available():

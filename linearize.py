@@ -2,13 +2,13 @@
 "Derivation", X_base / Eq. 7: every root-to-leaf path written out in full, shared prefixes
 repeated; Section "Evaluation Setups": linearised branches + sequence packing).
 
-Used by the benchmark to run the *same* library on the K-chain forest, so that the only
+Benchmark helper (not part of the library): bench.py uses it to run the *same* library on the K-chain forest, so that the only
 difference from the tree run is the redundancy."""
 from __future__ import annotations
 
 import numpy as np
 
-from .binding import TreeMeta
+from paper_2511_00413_amd import TreeMeta
 
 
 def branch_token_lists(meta: TreeMeta):
