@@ -435,6 +435,34 @@ tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_si
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * tt_tree_conv_bwd_static (device) -- tt_tree_conv_bwd for callers that cannot allocate
+ *
+ * For code that runs where device memory may not be allocated and no workspace can be brought in:
+ * under HIP graph capture, in tight serving / training loops, in harnesses that forbid allocation.
+ * Same arguments, same kernels and bit-identical results as tt_tree_conv_bwd, minus the workspace:
+ * the per-tile partial sums of dweight / dbias go to an array of
+ * TT_CONV_BWD_STATIC_SCRATCH_BYTES bytes that is part of the library's device code (every GPU the
+ * library runs on holds one copy from the first use of the library on it until the process ends).
+ * The call allocates and frees nothing.
+ *   Limit: tt_tree_conv_bwd_workspace(n_tokens, channels, kernel_size, dtype) must not exceed
+ *   TT_CONV_BWD_STATIC_SCRATCH_BYTES (e.g. 16 406 tokens x 8192 channels, K = 4, bf16 needs 42 MB);
+ *   a larger shape is refused with TT_ERR_WORKSPACE before anything is launched.
+ *   The scratch needs no clearing: every call overwrites the part it reads (one row per token tile).
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different
+ *   streams, or threads) race on it and must be ordered by the caller; calls on one stream are safe.
+ * Errors: as tt_tree_conv_bwd; TT_ERR_HIP if the array's device address cannot be obtained.
+ * ------------------------------------------------------------------------------------------ */
+#define TT_CONV_BWD_STATIC_SCRATCH_BYTES (64u << 20)
+tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype,
+                                  int32_t activation, const void* x, int64_t x_stride_tok,
+                                  const float* weight, const float* bias, const int32_t* tok_pred,
+                                  const void* dy, int64_t dy_stride_tok,
+                                  int32_t n_fix, const int32_t* fix_tok, const int32_t* fix_off,
+                                  const int32_t* fix_t, const int32_t* fix_r,
+                                  void* dx, int64_t dx_stride_tok, float* dweight, float* dbias,
+                                  void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Gated delta rule with tree state routing, forward (device; host plan)
  *
  * The recurrent core of a GDN layer, Section "Implementation", paragraph "SSM Layers (GDN)" (i)

@@ -108,6 +108,10 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_conv_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp,
                                          ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_int32, _vp, _vp, _vp, _vp,
                                          _vp, ctypes.c_int64, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_conv_bwd_static.restype = ctypes.c_int32
+        lib.tt_tree_conv_bwd_static.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp,
+                                                ctypes.c_int64, _vp, _vp, _vp, _vp, ctypes.c_int64, ctypes.c_int32, _vp, _vp, _vp,
+                                                _vp, _vp, ctypes.c_int64, _vp, _vp, _vp]
         lib.tt_tree_gdn_plan_sizes.restype = ctypes.c_int32
         lib.tt_tree_gdn_plan_sizes.argtypes = [ctypes.c_int32, _vp, _vp, _c_i32p, _c_i32p]
         lib.tt_tree_gdn_plan.restype = ctypes.c_int32
@@ -667,6 +671,29 @@ def tree_conv_bwd(x, weight, bias, tok_pred, dy, plan: ConvPlan, *, silu: bool =
                                    _dp(d["fix_t"]), _dp(d["fix_r"]), _dp(dx), _row_stride(dx), _dp(dw), _dp(db),
                                    _dp(workspace), workspace.numel(), _stream_ptr(stream)))
     return dx, dw, db
+
+
+CONV_BWD_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def tree_conv_bwd_static(x, weight, bias, tok_pred, dy, plan: ConvPlan, dx, dweight, dbias=None, *, silu: bool = True,
+                         stream=None) -> None:
+    """tree_conv_bwd for callers that may not allocate: every output is passed in (dx [n, C] in x's dtype,
+    dweight [C, K] fp32, dbias [C] fp32 or None), the plan must already be on the device, and the scratch is the
+    library's static array (shapes whose scratch exceeds CONV_BWD_STATIC_SCRATCH_BYTES are refused)."""
+    n, c, k, dt = _conv_check(x, weight)
+    _conv_check(dy, weight, "dy")
+    if plan.kernel_size != k:
+        raise ValueError(f"the plan was made for kernel size {plan.kernel_size}, weight has {k}")
+    if plan.device is None:
+        raise ValueError("move the plan to the device first (plan.to_device): this call does not allocate")
+    if dx.shape != x.shape or dx.dtype != x.dtype or dweight.shape != weight.shape:
+        raise ValueError("dx must match x, dweight must match weight")
+    d = plan.device
+    _check(_lib().tt_tree_conv_bwd_static(n, c, k, dt, 1 if silu else 0, _dp(x), _row_stride(x), _dp(weight), _dp(bias),
+                                          _dp(tok_pred), _dp(dy), _row_stride(dy), len(plan.fix_tok), _dp(d["fix_tok"]),
+                                          _dp(d["fix_off"]), _dp(d["fix_t"]), _dp(d["fix_r"]), _dp(dx), _row_stride(dx),
+                                          _dp(dweight), _dp(dbias), _stream_ptr(stream)))
 
 
 def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, workspace=None, stream=None,

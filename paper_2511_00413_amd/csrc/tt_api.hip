@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <climits>
 #include <cmath>
+#include <mutex>
 #include "tt_internal.h"
 #include "tt_kernels.h"
 
@@ -257,6 +258,68 @@ extern "C" size_t tt_tree_conv_bwd_workspace(int64_t n_tokens, int32_t channels,
   return tt::conv_bwd_workspace(n_tokens, channels, kernel_size, dtype == TT_DTYPE_BF16);
 }
 
+namespace {
+
+// Arguments of a convolution backward call (tt_tree_conv_bwd and tt_tree_conv_bwd_static share validation and launch).
+struct ConvBwdCall {
+  int64_t n_tokens; int32_t channels, kernel_size, dtype, activation;
+  const void* x; int64_t x_stride_tok; const float *weight, *bias; const int32_t* tok_pred;
+  const void* dy; int64_t dy_stride_tok;
+  int32_t n_fix; const int32_t *fix_tok, *fix_off, *fix_t, *fix_r;
+  void* dx; int64_t dx_stride_tok; float *dweight, *dbias;
+};
+
+// Host-side checks; on success `need` is the scratch the kernels use for this shape.
+tt_status conv_bwd_validate(const ConvBwdCall& k, ConvChecked& c, ConvChecked& cd, size_t& need) {
+  if (tt_status s = check_conv(k.n_tokens, k.channels, k.kernel_size, k.dtype, k.activation, k.x, k.x_stride_tok, k.weight,
+                               k.tok_pred, k.dx, k.dx_stride_tok, c))
+    return s;
+  if (tt_status s = check_conv(k.n_tokens, k.channels, k.kernel_size, k.dtype, k.activation, k.dy, k.dy_stride_tok, k.weight,
+                               k.tok_pred, k.dx, k.dx_stride_tok, cd))
+    return s;
+  if (!k.dweight) return fail(TT_ERR_NULL, "dweight is NULL");
+  if (k.n_fix < 0 || (k.n_fix > 0 && (!k.fix_tok || !k.fix_off || !k.fix_t || !k.fix_r)))
+    return fail(TT_ERR_NULL, "n_fix=%d with a NULL list", k.n_fix);
+  if (k.n_tokens > 0 && (k.dx == k.x || k.dx == k.dy)) return fail(TT_ERR_SHAPE, "dx may not alias x or dy");
+  need = tt::conv_bwd_workspace(k.n_tokens, k.channels, k.kernel_size, c.bf16);
+  return TT_OK;
+}
+
+tt_status conv_bwd_launch(const ConvBwdCall& k, const ConvChecked& c, const ConvChecked& cd, void* workspace, void* stream,
+                          const char* what) {
+  return hip_result(tt::conv_bwd(k.n_tokens, k.channels, k.kernel_size, c.bf16, k.activation == 1, k.x, c.xs, k.weight, k.bias,
+                                 k.tok_pred, k.dy, cd.xs, k.n_fix, k.fix_tok, k.fix_off, k.fix_t, k.fix_r, k.dx, c.ys, k.dweight,
+                                 k.dbias, workspace, (hipStream_t)stream),
+                    what);
+}
+
+// ---- static scratch of the allocation-free variant ---------------------------------------------------------
+// One array per GPU, part of the code object: the loader places it when the library is loaded on a device and
+// it lives until the process ends.  In host code the array's name is only a handle; its device address is
+// looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[TT_CONV_BWD_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES];
+
+// Device address of the scratch array on the current device, looked up on the first call per device.
+tt_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess || dev < 0 || dev >= MAX_DEVICES)
+    return fail(TT_ERR_HIP, "tree_conv_bwd_static: no usable current device (%s)", hipGetErrorString(e));
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)); e != hipSuccess || !p)
+      return fail(TT_ERR_HIP, "tree_conv_bwd_static: address of the scratch array on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TT_OK;
+}
+
+}  // namespace
+
 extern "C" tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype, int32_t activation,
                                       const void* x, int64_t x_stride_tok, const float* weight, const float* bias,
                                       const int32_t* tok_pred, const void* dy, int64_t dy_stride_tok, int32_t n_fix,
@@ -264,20 +327,36 @@ extern "C" tt_status tt_tree_conv_bwd(int64_t n_tokens, int32_t channels, int32_
                                       void* dx, int64_t dx_stride_tok, float* dweight, float* dbias, void* workspace,
                                       size_t workspace_bytes, void* stream) {
   tt::clear_error();
+  const ConvBwdCall k{n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, bias, tok_pred, dy, dy_stride_tok,
+                      n_fix, fix_tok, fix_off, fix_t, fix_r, dx, dx_stride_tok, dweight, dbias};
   ConvChecked c, cd;
-  if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, tok_pred, dx, dx_stride_tok, c))
-    return s;
-  if (tt_status s = check_conv(n_tokens, channels, kernel_size, dtype, activation, dy, dy_stride_tok, weight, tok_pred, dx, dx_stride_tok, cd))
-    return s;
-  if (!dweight) return fail(TT_ERR_NULL, "dweight is NULL");
-  if (n_fix < 0 || (n_fix > 0 && (!fix_tok || !fix_off || !fix_t || !fix_r))) return fail(TT_ERR_NULL, "n_fix=%d with a NULL list", n_fix);
-  if (n_tokens > 0 && (dx == x || dx == dy)) return fail(TT_ERR_SHAPE, "dx may not alias x or dy");
-  const size_t need = tt::conv_bwd_workspace(n_tokens, channels, kernel_size, c.bf16);
+  size_t need = 0;
+  if (tt_status s = conv_bwd_validate(k, c, cd, need)) return s;
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
     return fail(TT_ERR_WORKSPACE, "conv backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
-  return hip_result(tt::conv_bwd(n_tokens, channels, kernel_size, c.bf16, activation == 1, x, c.xs, weight, bias, tok_pred, dy, cd.xs,
-                                 n_fix, fix_tok, fix_off, fix_t, fix_r, dx, c.ys, dweight, dbias, workspace, (hipStream_t)stream),
-                    "tree_conv_bwd");
+  return conv_bwd_launch(k, c, cd, workspace, stream, "tree_conv_bwd");
+}
+
+extern "C" tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels, int32_t kernel_size, int32_t dtype,
+                                             int32_t activation, const void* x, int64_t x_stride_tok, const float* weight,
+                                             const float* bias, const int32_t* tok_pred, const void* dy, int64_t dy_stride_tok,
+                                             int32_t n_fix, const int32_t* fix_tok, const int32_t* fix_off, const int32_t* fix_t,
+                                             const int32_t* fix_r, void* dx, int64_t dx_stride_tok, float* dweight, float* dbias,
+                                             void* stream) {
+  tt::clear_error();
+  const ConvBwdCall k{n_tokens, channels, kernel_size, dtype, activation, x, x_stride_tok, weight, bias, tok_pred, dy, dy_stride_tok,
+                      n_fix, fix_tok, fix_off, fix_t, fix_r, dx, dx_stride_tok, dweight, dbias};
+  ConvChecked c, cd;
+  size_t need = 0;
+  if (tt_status s = conv_bwd_validate(k, c, cd, need)) return s;
+  if (need > (size_t)TT_CONV_BWD_STATIC_SCRATCH_BYTES)
+    return fail(TT_ERR_WORKSPACE,
+                "conv backward of this shape needs %zu bytes of scratch, the static array of tt_tree_conv_bwd_static holds %zu; "
+                "use tt_tree_conv_bwd with a caller workspace",
+                need, (size_t)TT_CONV_BWD_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if (tt_status s = static_scratch(&ws)) return s;
+  return conv_bwd_launch(k, c, cd, ws, stream, "tree_conv_bwd_static");
 }
 
 extern "C" size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32_t hv) {
