@@ -2,11 +2,13 @@
 """Benchmark of the tree-attention hot path on one MI355X.
 
 One "step" = one pass of the whole path over one synthetic tree: host metadata build
-(tree_build_meta) + upload of the mask bounds, tree attention forward, backward, and the weighted
-log-prob loss.  The headline value is the attention forward+backward rate in *useful* TFLOP/s:
-14 * Hq * D * visible_pairs flops (4 D per pair forward, 10 D backward) divided by the forward +
-backward time measured with events on the launch stream.  Inputs are resident in HBM before the
-timed region starts.
+(tree_build_meta) + upload of the mask bounds and position ids, rotary embedding of Q and K with the tree
+position ids, tree attention forward, backward, inverse rotation of dQ and dK, and the weighted log-prob
+loss forward and backward.  The headline value is the attention forward+backward rate in *useful* TFLOP/s:
+14 * Hq * D * visible_pairs flops (4 D per pair forward, 10 D backward) divided by the forward + backward
+time measured with events on the launch stream, with no other instrumentation switched on.  Inputs are
+resident in HBM before the timed region starts.  Per-kernel durations (kernel_avg_ms, roofline) come from
+a second pass over the same steps with the library's per-kernel event bracketing on.
 
 Prints one JSON line (see README for the fields).
 """
@@ -23,12 +25,22 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0
 
 # HBM bytes per launch (read + write) of the attention kernels, from the rocprofv3 FETCH_SIZE /
-# WRITE_SIZE runs summarised under profiles/ (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the plain
-# 1 GiB copy of the same run).  Offline measurements: reported only for the workload they cover.
+# WRITE_SIZE runs summarised in the named profile (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the plain
+# 1 GiB copy of the same run).  Offline measurements: reported only for the workload they cover, and
+# refreshed whenever an attention kernel changes.
+TRAFFIC_SOURCE = "profiles/attention_and_loss_kernels_cfg2.md"
 MEASURED_TRAFFIC_BYTES = {
     (2, "attn_fwd"): 230.3e6 + 149.2e6,
     (2, "attn_dkdv"): 2394.4e6 + 271.8e6,
     (2, "attn_dq"): 372.4e6 + 142.8e6,
+}
+
+WORKLOADS = {
+    1: "cfg1: worked 3-leaf tree, N=240, MHA 4x64, fp32",
+    2: "cfg2: random depth-4 tree seed 117, N=16406, GQA 32/8, d=128, bf16, vocab 32768",
+    3: "cfg3: agentic fan-out 8K->16x(2K->2x1K), N=73728, GQA 64/8, d=128, bf16, vocab 151936 in 4K-row chunks",
+    4: "cfg4: deep chain seed 195, N=131091, GQA 32/8, d=128, bf16",
+    5: "cfg5-step: 32768-token chunk (8 nodes) x 65536 cached prefix keys (variant b), GQA 64/8, d=128, bf16",
 }
 
 
@@ -47,6 +59,10 @@ def parse_args():
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-gdn", action="store_true")
     ap.add_argument("--no-gdn-bwd", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the short runs of the other full-size configurations (3, 4 and the config-5 step)")
+    ap.add_argument("--other-configs-budget-s", type=float, default=150.0,
+                    help="wall-clock budget for the other configurations; one that would start after it is skipped")
     ap.add_argument("--gdn-heads", type=int, default=32, help="value heads of the gated-delta-rule leg (key heads = half)")
     ap.add_argument("--conv-channels", type=int, default=8192,
                     help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
@@ -60,217 +76,228 @@ def parse_args():
     return ap.parse_args()
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
-              f"--gpus {args.gpus} is not supported", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import paper_2511_00413_amd as T
-    import linearize
+def make_workload(cfg):
+    """(tree, n_prefix, prefix_visible, root_pos_offset) of a benchmark configuration."""
     import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    cfg = args.config
-    dims = W.DIMS[cfg]
-    tdt = torch.bfloat16 if dims.dtype == "bf16" else torch.float32
-
-    # ---------------- workload ----------------
     if cfg == 5:
-        step_w = W.step_cfg5()
-        tree, n_prefix, prefix_visible = step_w.chunk, step_w.n_prefix, step_w.prefix_visible
-        root_off = [int(prefix_visible.sum())]
-        workload = "cfg5-step: 32768-token chunk (8 nodes) x 65536 cached prefix keys (variant b), GQA 64/8, d=128, bf16"
-    else:
-        tree, n_prefix, prefix_visible, root_off = W.tree_config(cfg), 0, None, None
-        workload = {
-            1: "cfg1: worked 3-leaf tree, N=240, MHA 4x64, fp32",
-            2: "cfg2: random depth-4 tree seed 117, N=16406, GQA 32/8, d=128, bf16, vocab 32768",
-            3: "cfg3: agentic fan-out 8K->16x(2K->2x1K), N=73728, GQA 64/8, d=128, bf16, vocab 151936 in 4K-row chunks",
-            4: "cfg4: deep chain seed 195, N=131091, GQA 32/8, d=128, bf16",
-        }[cfg]
+        s = W.step_cfg5()
+        return s.chunk, s.n_prefix, s.prefix_visible, [int(s.prefix_visible.sum())]
+    return W.tree_config(cfg), 0, None, None
 
-    def build_meta():
-        return T.tree_build_meta(tree.parent, tree.seg_len, tree.trained, root_pos_offset=root_off,
-                                 n_prefix=n_prefix, prefix_visible=prefix_visible)
 
-    meta = build_meta()
-    N = meta.n_tokens
-    pairs = linearize.visible_pairs(meta)
-    q, k, v, do = (x.to(dev) for x in W.attn_inputs(N, N, dims, cfg))
-    kp = vp = dkp = dvp = None
-    if n_prefix:
-        _, kp, vp, _ = (x.to(dev) for x in W.attn_inputs(1, n_prefix, dims, cfg + 100))
-        dkp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
-        dvp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
-    kend_d = torch.empty(n_prefix + N, dtype=torch.int32, device=dev)
-    kmin_d = torch.empty(meta.n_ktiles, dtype=torch.int32, device=dev)
-    kmax_d = torch.empty(meta.n_ktiles, dtype=torch.int32, device=dev)
-    kend_h = torch.empty(n_prefix + N, dtype=torch.int32).pin_memory()
-    kmin_h = torch.empty(meta.n_ktiles, dtype=torch.int32).pin_memory()
-    kmax_h = torch.empty(meta.n_ktiles, dtype=torch.int32).pin_memory()
-    w_h = torch.empty(N, dtype=torch.float32).pin_memory()
-    w_d = torch.empty(N, dtype=torch.float32, device=dev)
+def device_randn(torch, shape, std, dtype, seed, dev):
+    """std * N(0,1) drawn on the device (timing-only inputs: same distribution as workloads.randn, drawn
+    where they are used because the large configurations would spend minutes in the host generator)."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * std).to(dtype)
 
-    # loss inputs (value distribution of the config; drawn on the device to keep start-up short)
-    do_loss = dims.vocab > 0 and not args.no_loss
-    loss_rows = 0
-    if do_loss:
-        gen = torch.Generator(device=dev)
-        gen.manual_seed(cfg * 1000 + 5)
-        chunk_rows = N if cfg != 3 else 4096
-        logits = (torch.randn((chunk_rows, dims.vocab), generator=gen, device=dev, dtype=torch.float32)
-                  * dims.logit_std).to(torch.bfloat16 if dims.logit_dtype == "bf16" else torch.float32)
-        target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
-        logp = torch.empty(N, dtype=torch.float32, device=dev)
-        lse_l = torch.empty(N, dtype=torch.float32, device=dev)
-        loss_acc = torch.zeros(1, dtype=torch.float32, device=dev)
-        dlogits = torch.empty_like(logits)          # gradient of the loss w.r.t. the logits (same chunking)
-        loss_rows = N
 
-    ws_f = torch.empty(T.tree_attn_workspace(q, k, v, n_prefix, False), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(T.tree_attn_workspace(q, k, v, n_prefix, True), dtype=torch.uint8, device=dev)
-    o = torch.empty_like(q)
-    lse = torch.empty((dims.hq, N), dtype=torch.float32, device=dev)
-    dq = torch.empty_like(q)
-    dk = torch.empty_like(k)
-    dv = torch.empty_like(v)
+class PathRun:
+    """Device buffers and the step of one pass of the hot path over one tree or forest.
 
-    # rotary embedding with the tree position ids: q_raw / k_raw -> q / k before the attention, and the
-    # inverse rotation of dq / dk after it (the steps either side of the attention path)
-    q_raw, k_raw = q.clone(), k.clone()
-    pos_h = torch.empty(N, dtype=torch.int32).pin_memory()
-    pos_d = torch.empty(N, dtype=torch.int32, device=dev)
-    do_rope = dims.dtype == "bf16" and not args.no_rope
+    step(events): host metadata + uploads, RoPE(Q, K), attention forward, backward, inverse RoPE(dQ, dK),
+    loss forward + backward; events (6 of them) are recorded before the rotary embedding, before and after
+    the forward, after the backward, after the inverse rotation and after the loss."""
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    host_ms = []
+    def __init__(self, T, torch, dev, dims, tree, n_prefix, prefix_visible, root_off, q_raw, k_raw, v, do, kp=None, vp=None,
+                 logits=None, target=None, weight=None, do_rope=True):
+        self.T, self.torch, self.dims, self.tree = T, torch, dims, tree
+        self.n_prefix, self.prefix_visible, self.root_off = n_prefix, prefix_visible, root_off
+        self.meta = self.build_meta()
+        N = self.N = self.meta.n_tokens
+        self.q_raw, self.k_raw, self.v, self.do, self.kp, self.vp = q_raw, k_raw, v, do, kp, vp
+        self.do_rope = do_rope and dims.dtype == "bf16"
+        self.q = torch.empty_like(q_raw) if self.do_rope else q_raw
+        self.k = torch.empty_like(k_raw) if self.do_rope else k_raw
+        self.dkp = self.dvp = None
+        if n_prefix:
+            self.dkp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
+            self.dvp = torch.zeros(kp.shape, dtype=torch.float32, device=dev)
+        nk = self.meta.n_ktiles
+        self.kend_d = torch.empty(n_prefix + N, dtype=torch.int32, device=dev)
+        self.kmin_d = torch.empty(nk, dtype=torch.int32, device=dev)
+        self.kmax_d = torch.empty(nk, dtype=torch.int32, device=dev)
+        self.pos_d = torch.empty(N, dtype=torch.int32, device=dev)
+        self.w_d = torch.empty(N, dtype=torch.float32, device=dev)
+        self.kend_h = torch.empty(n_prefix + N, dtype=torch.int32).pin_memory()
+        self.kmin_h = torch.empty(nk, dtype=torch.int32).pin_memory()
+        self.kmax_h = torch.empty(nk, dtype=torch.int32).pin_memory()
+        self.pos_h = torch.empty(N, dtype=torch.int32).pin_memory()
+        self.w_h = torch.empty(N, dtype=torch.float32).pin_memory()
+        self.weight_override = weight
+        self.ws_f = torch.empty(T.tree_attn_workspace(self.q, self.k, v, n_prefix, False), dtype=torch.uint8, device=dev)
+        self.ws_b = torch.empty(T.tree_attn_workspace(self.q, self.k, v, n_prefix, True), dtype=torch.uint8, device=dev)
+        self.o = torch.empty_like(q_raw)
+        self.lse = torch.empty((dims.hq, N), dtype=torch.float32, device=dev)
+        self.dq, self.dk, self.dv = torch.empty_like(q_raw), torch.empty_like(k_raw), torch.empty_like(v)
+        self.logits, self.target = logits, target
+        self.do_loss = logits is not None
+        if self.do_loss:
+            self.logp = torch.empty(N, dtype=torch.float32, device=dev)
+            self.lse_l = torch.empty(N, dtype=torch.float32, device=dev)
+            self.loss_acc = torch.zeros(1, dtype=torch.float32, device=dev)
+            self.dlogits = torch.empty_like(logits)        # gradient w.r.t. the logits (same row chunking)
+        self.host_ms = []
 
-    def step(events=None):
+    def build_meta(self):
+        t = self.tree
+        return self.T.tree_build_meta(t.parent, t.seg_len, t.trained, root_pos_offset=self.root_off, n_prefix=self.n_prefix,
+                                      prefix_visible=self.prefix_visible)
+
+    def step(self, events=None):
+        T, N = self.T, self.N
         t0 = time.perf_counter()
-        m = build_meta()                                   # a1-a4 on the host
-        kend_h.numpy()[:] = m.kend
-        kmin_h.numpy()[:] = m.ktile_kend_min
-        kmax_h.numpy()[:] = m.ktile_kend_max
-        w_h.numpy()[:] = m.tok_weight
-        kend_d.copy_(kend_h, non_blocking=True)
-        kmin_d.copy_(kmin_h, non_blocking=True)
-        kmax_d.copy_(kmax_h, non_blocking=True)
-        w_d.copy_(w_h, non_blocking=True)
-        if do_rope:
-            pos_h.numpy()[:] = m.tok_pos
-            pos_d.copy_(pos_h, non_blocking=True)
-        host_ms.append((time.perf_counter() - t0) * 1e3)
-        if do_rope:
-            T.tree_rope(q_raw, pos_d, out=q)
-            T.tree_rope(k_raw, pos_d, out=k)
+        m = self.build_meta()                                   # a1-a4 on the host
+        self.kend_h.numpy()[:] = m.kend
+        self.kmin_h.numpy()[:] = m.ktile_kend_min
+        self.kmax_h.numpy()[:] = m.ktile_kend_max
+        self.kend_d.copy_(self.kend_h, non_blocking=True)
+        self.kmin_d.copy_(self.kmin_h, non_blocking=True)
+        self.kmax_d.copy_(self.kmax_h, non_blocking=True)
+        if self.weight_override is None:
+            self.w_h.numpy()[:] = m.tok_weight
+            self.w_d.copy_(self.w_h, non_blocking=True)
+        if self.do_rope:
+            self.pos_h.numpy()[:] = m.tok_pos
+            self.pos_d.copy_(self.pos_h, non_blocking=True)
+        self.host_ms.append((time.perf_counter() - t0) * 1e3)
+        w_d = self.w_d if self.weight_override is None else self.weight_override
+        kb = (self.kend_d, self.kmin_d, self.kmax_d)
         if events:
             events[0].record()
-        T.tree_attn_fwd(q, k, v, kend_d, kmin_d, kmax_d, k_prefix=kp, v_prefix=vp, o=o, lse=lse, workspace=ws_f)
+        if self.do_rope:
+            T.tree_rope(self.q_raw, self.pos_d, out=self.q)
+            T.tree_rope(self.k_raw, self.pos_d, out=self.k)
         if events:
             events[1].record()
-        T.tree_attn_bwd(q, k, v, kend_d, kmin_d, kmax_d, o, do, lse, k_prefix=kp, v_prefix=vp,
-                        dk_prefix_acc=dkp, dv_prefix_acc=dvp, dq=dq, dk=dk, dv=dv, workspace=ws_b)
+        T.tree_attn_fwd(self.q, self.k, self.v, *kb, k_prefix=self.kp, v_prefix=self.vp, o=self.o, lse=self.lse, workspace=self.ws_f)
         if events:
             events[2].record()
-        if do_rope:
-            T.tree_rope(dq, pos_d, inverse=True, out=dq)
-            T.tree_rope(dk, pos_d, inverse=True, out=dk)
-        if do_loss:
-            loss_acc.zero_()
-            rows = logits.shape[0]
-            for lo in range(0, N, rows):
-                n = min(rows, N - lo)
-                T.tree_weighted_logprob(logits[:n], target[lo:lo + n], w_d[lo:lo + n], loss_acc=loss_acc,
-                                        logp=logp[lo:lo + n], lse=lse_l[lo:lo + n])
-                T.tree_weighted_logprob_bwd(logits[:n], target[lo:lo + n], w_d[lo:lo + n], lse_l[lo:lo + n],
-                                            out=dlogits[:n])
+        T.tree_attn_bwd(self.q, self.k, self.v, *kb, self.o, self.do, self.lse, k_prefix=self.kp, v_prefix=self.vp,
+                        dk_prefix_acc=self.dkp, dv_prefix_acc=self.dvp, dq=self.dq, dk=self.dk, dv=self.dv, workspace=self.ws_b)
         if events:
             events[3].record()
+        if self.do_rope:
+            T.tree_rope(self.dq, self.pos_d, inverse=True, out=self.dq)
+            T.tree_rope(self.dk, self.pos_d, inverse=True, out=self.dk)
+        if events:
+            events[4].record()
+        if self.do_loss:
+            self.loss_acc.zero_()
+            rows = self.logits.shape[0]
+            for lo in range(0, N, rows):
+                n = min(rows, N - lo)
+                T.tree_weighted_logprob(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], loss_acc=self.loss_acc,
+                                        logp=self.logp[lo:lo + n], lse=self.lse_l[lo:lo + n])
+                T.tree_weighted_logprob_bwd(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], self.lse_l[lo:lo + n],
+                                            out=self.dlogits[:n])
+        if events:
+            events[5].record()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    host_ms.clear()
-    T.kernel_timing_enable(True)
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(ev[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ktimes = T.kernel_timing_read()
-    T.kernel_timing_enable(False)
-
-    ms_fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    ms_bwd = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-    ms_loss = sum(e[2].elapsed_time(e[3]) for e in ev) / args.steps
-    useful_flop = 14.0 * dims.hq * dims.d * pairs
-    value = useful_flop / ((ms_fwd + ms_bwd) * 1e-3) / 1e12
-
-    # ---------------- roofline of the dominant kernel ----------------
-    alg_flop = {"attn_fwd": 4.0, "attn_dkdv": 8.0, "attn_dq": 2.0, "ref_fwd": 4.0, "ref_bwd": 10.0}
-    attn_k = {n: t for n, t in ktimes.items() if n in alg_flop and t[1] > 0}
-    roofline = None
-    kernel_ms = {n: (t[0] / t[1]) for n, t in ktimes.items() if t[1] > 0}
-    if attn_k:
-        dom = max(attn_k, key=lambda n: attn_k[n][0])
-        avg_ms = attn_k[dom][0] / attn_k[dom][1]
-        achieved = alg_flop[dom] * dims.hq * dims.d * pairs / (avg_ms * 1e-3) / 1e12
-        peak = PEAK_BF16_TFLOPS if dims.dtype == "bf16" else 157.3
-        roofline = {"kernel": dom, "bound": "mfma" if dims.dtype == "bf16" else "alu", "achieved": round(achieved, 2),
-                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, dom)),
-                    "avg_ms": round(avg_ms, 4),
-                    "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
-    loss_gbps = loss_bwd_gbps = None
-    if do_loss and "loss_rows" in kernel_ms:
-        esz = 2 if dims.logit_dtype == "bf16" else 4
-        bytes_total = loss_rows * (dims.vocab * esz + 12)
-        loss_ms_total = ktimes["loss_rows"][0] / args.steps
-        loss_gbps = bytes_total / (loss_ms_total * 1e-3) / 1e9
-        # backward: one read of the logits + one write of the gradient + target, weight, lse per row
-        loss_bwd_gbps = loss_rows * (2 * dims.vocab * esz + 12) / (ktimes["loss_bwd"][0] / args.steps * 1e-3) / 1e9
-
-    rope_gbps = None
-    if do_rope and "rope" in kernel_ms:
-        esz_a = 2
-        rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * esz_a * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
-        rope_gbps = rope_bytes / (ktimes["rope"][0] / args.steps * 1e-3) / 1e9
-
-    # ---------------- linearised per-branch baseline on the same GPU ----------------
-    lin = None
-    if not args.no_linearized and n_prefix == 0:
-        idx, lparent, lseg = linearize.linearized_forest(meta)
-        lmeta = T.tree_build_meta(lparent, lseg)
-        idx_d = torch.from_numpy(idx).to(dev)
-        ql, kl, vl, dol = (x.index_select(0, idx_d) for x in (q, k, v, do))
-        lk = [torch.from_numpy(x).to(dev) for x in (lmeta.kend, lmeta.ktile_kend_min, lmeta.ktile_kend_max)]
-        ol = torch.empty_like(ql); lsel = torch.empty((dims.hq, len(idx)), dtype=torch.float32, device=dev)
-        dql = torch.empty_like(ql); dkl = torch.empty_like(kl); dvl = torch.empty_like(vl)
-        wsl = torch.empty(T.tree_attn_workspace(ql, kl, vl, 0, True), dtype=torch.uint8, device=dev)
-        n_it = max(3, min(args.steps, 10))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for it in range(2 + n_it):
-            if it == 2:
-                e0.record()
-            T.tree_attn_fwd(ql, kl, vl, *lk, o=ol, lse=lsel, workspace=wsl)
-            T.tree_attn_bwd(ql, kl, vl, *lk, ol, dol, lsel, dq=dql, dk=dkl, dv=dvl, workspace=wsl)
-        e1.record()
+    def timed(self, warmup, steps):
+        """Runs warmup + steps; returns (wall seconds of the timed steps, per-phase mean ms)."""
+        torch = self.torch
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)]
+        for _ in range(warmup):
+            self.step()
         torch.cuda.synchronize()
-        ms_lin = e0.elapsed_time(e1) / n_it
-        pairs_lin = linearize.visible_pairs(lmeta)
-        lin = {"ms_fwd_bwd": round(ms_lin, 4), "n_lin": int(len(idx)), "pairs_lin": pairs_lin,
-               "speedup": round(ms_lin / (ms_fwd + ms_bwd), 3),
-               "r_tok": round(len(idx) / N, 3), "r_pair": round(pairs_lin / pairs, 3)}
-        lin["speedup_over_r_tok"] = round(lin["speedup"] / lin["r_tok"], 3)
-        lin["speedup_over_r_pair"] = round(lin["speedup"] / lin["r_pair"], 3)
-        del ql, kl, vl, dol, ol, dql, dkl, dvl
+        self.host_ms.clear()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            self.step(ev[s])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        names = ("rope", "attn_fwd", "attn_bwd", "rope_inverse", "loss")
+        ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in ev) / steps for i, n in enumerate(names)}
+        ms["path"] = sum(e[0].elapsed_time(e[5]) for e in ev) / steps
+        return wall, ms
 
+
+def linearized_run(T, torch, dev, dims, run: PathRun, linearize):
+    """The same path on the K-chain forest (every root-to-leaf branch written out in full, packed): the
+    paper's baseline layout, run through the same library so that only the redundancy differs."""
+    import workloads as W
+    idx, lparent, lseg = linearize.linearized_forest(run.meta)
+    idx_d = torch.from_numpy(idx).to(dev)
+    forest = W.Tree(parent=lparent, seg_len=lseg, trained=np.ones(len(lparent), dtype=np.uint8), name="linearized")
+    ql, kl, vl, dol = (x.index_select(0, idx_d) for x in (run.q_raw, run.k_raw, run.v, run.do))
+    tl = wl = None
+    if run.do_loss:
+        tl = run.target.index_select(0, idx_d)
+        # per-branch weights (1/K on trained tokens): the tree weight g/K split over the g branches of a token
+        g_tok = torch.from_numpy(run.meta.node_g[run.meta.tok_node].astype(np.float32)).to(dev)
+        wl = (run.w_d / g_tok).index_select(0, idx_d)
+    lin = PathRun(T, torch, dev, dims, forest, 0, None, None, ql, kl, vl, dol, logits=run.logits, target=tl, weight=wl,
+                  do_rope=run.do_rope)
+    return lin, idx
+
+
+def speedup_record(ms_tree, ms_lin, run: PathRun, lin: PathRun, pairs, pairs_lin):
+    attn_t, attn_l = ms_tree["attn_fwd"] + ms_tree["attn_bwd"], ms_lin["attn_fwd"] + ms_lin["attn_bwd"]
+    r_tok, r_pair = lin.N / run.N, pairs_lin / pairs
+    rec = {"ms_fwd_bwd": round(attn_l, 4), "n_lin": lin.N, "pairs_lin": pairs_lin, "speedup": round(attn_l / attn_t, 3),
+           "r_tok": round(r_tok, 3), "r_pair": round(r_pair, 3),
+           "speedup_over_r_tok": round(attn_l / attn_t / r_tok, 3), "speedup_over_r_pair": round(attn_l / attn_t / r_pair, 3),
+           # the whole device path (rotary embedding, attention, inverse rotation, loss forward + backward): the
+           # token-linear steps speed up by r_tok, the attention by at most r_pair
+           "path": {"steps": "rope + attn fwd + attn bwd + inverse rope" + (" + loss fwd + loss bwd" if run.do_loss else ""),
+                    "ms_tree": round(ms_tree["path"], 4), "ms_linearized": round(ms_lin["path"], 4),
+                    "speedup": round(ms_lin["path"] / ms_tree["path"], 3),
+                    "speedup_over_r_tok": round(ms_lin["path"] / ms_tree["path"] / r_tok, 3),
+                    "ms_tree_by_step": {k_: round(v_, 4) for k_, v_ in ms_tree.items() if k_ != "path"},
+                    "ms_linearized_by_step": {k_: round(v_, 4) for k_, v_ in ms_lin.items() if k_ != "path"}}}
+    return rec
+
+
+def other_config(T, torch, dev, linearize, cfg, with_linearized):
+    """Short run (2 warm-up + 3 timed steps) of another full-size configuration: attention rates, the
+    linearized forest beside it, and the path-level times; inputs drawn on the device."""
+    import workloads as W
+    dims = W.DIMS[cfg]
+    tree, n_prefix, vis, root_off = make_workload(cfg)
+    N = int(tree.seg_len.sum())
+    tdt = torch.bfloat16
+    q = device_randn(torch, (N, dims.hq, dims.d), dims.std, tdt, cfg * 1000 + 1, dev)
+    k = device_randn(torch, (N, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 2, dev)
+    v = device_randn(torch, (N, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 3, dev)
+    do = device_randn(torch, (N, dims.hq, dims.d), dims.std, tdt, cfg * 1000 + 4, dev)
+    kp = vp = None
+    if n_prefix:
+        kp = device_randn(torch, (n_prefix, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 102, dev)
+        vp = device_randn(torch, (n_prefix, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 103, dev)
+    logits = target = None
+    if dims.vocab > 0:
+        rows = min(N, 4096)
+        logits = device_randn(torch, (rows, dims.vocab), dims.logit_std, torch.bfloat16, cfg * 1000 + 5, dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg * 1000 + 6)
+        target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
+    run = PathRun(T, torch, dev, dims, tree, n_prefix, vis, root_off, q, k, v, do, kp, vp, logits, target)
+    pairs = linearize.visible_pairs(run.meta)
+    _, ms = run.timed(2, 3)
+    attn = ms["attn_fwd"] + ms["attn_bwd"]
+    useful = 14.0 * dims.hq * dims.d * pairs
+    rec = {"workload": WORKLOADS[cfg], "n_tokens": N, "n_prefix": n_prefix, "visible_pairs": pairs,
+           "useful_tflops": round(useful / (attn * 1e-3) / 1e12, 2),
+           "pct_of_bf16_mfma_peak": round(100.0 * useful / (attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+           "ms_attn_fwd": round(ms["attn_fwd"], 4), "ms_attn_bwd": round(ms["attn_bwd"], 4), "ms_path": round(ms["path"], 4),
+           "ms_host_meta": round(float(np.mean(run.host_ms)), 4), "steps": 3, "warmup": 2}
+    if n_prefix:
+        rec["prefix_grad_accumulate_bytes"] = 2 * n_prefix * dims.hkv * dims.d * 4
+    if with_linearized and n_prefix == 0:
+        lin, _ = linearized_run(T, torch, dev, dims, run, linearize)
+        _, ms_l = lin.timed(1, 3)
+        rec["linearized"] = speedup_record(ms, ms_l, run, lin, pairs, linearize.visible_pairs(lin.meta))
+        del lin
+    del run, q, k, v, do, kp, vp, logits, target
+    torch.cuda.empty_cache()
+    return rec
+
+
+def leg_partitioned(c):
+    args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix = c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix
+    q, k, v, do, lse, ms_fwd, ms_bwd, pairs = c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs
     # ---------------- the same tree cut into partitions (boundary overhead) ----------------
     part = None
     if not args.no_partitioned and n_prefix == 0 and dims.dtype == "bf16":
@@ -329,6 +356,12 @@ def main():
                 "ms_host_plan": round(plan_ms, 3)}
         del op, lsep, dqp, dkp_, dvp_, wsp
 
+    return part
+
+
+def leg_conv(c):
+    args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix = c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix
+    q, k, v, do, lse, ms_fwd, ms_bwd, pairs = c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs
     # ---------------- tree-correct causal convolution on the same tree (SSM-layer adaptation) ----------------
     conv = None
     if not args.no_conv and n_prefix == 0 and dims.dtype == "bf16":
@@ -361,6 +394,12 @@ def main():
                 "bwd_frac_of_hbm_peak": round(b_bytes / (b_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)}
         del xc, dyc, yc
 
+    return conv
+
+
+def leg_gdn(c):
+    args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix = c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix
+    q, k, v, do, lse, ms_fwd, ms_bwd, pairs = c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs
     # ---------------- gated delta rule with tree state routing on the same tree (SSM-layer adaptation) ----------------
     gdn = None
     if not args.no_gdn and n_prefix == 0 and dims.dtype == "bf16":
@@ -427,6 +466,12 @@ def main():
             del gdo, bws
         del gq, gk, gv, go
 
+    return gdn
+
+
+def leg_cpu(c):
+    args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix = c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix
+    q, k, v, do, lse, ms_fwd, ms_bwd, pairs = c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs
     # ---------------- CPU oracle on a bounded sample (context only) ----------------
     cpu = None
     if not args.no_cpu_baseline and n_prefix == 0:
@@ -452,6 +497,116 @@ def main():
         cpu = {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(),
                "kind": "oracle", "sample": sample, "seconds": round(dtc, 2)}
 
+    return cpu
+
+
+class Ctx:
+    pass
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2511_00413_amd as T
+    import linearize
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = args.config
+    dims = W.DIMS[cfg]
+
+    # ---------------- workload (headline configuration: inputs from the seeded host generator) ----------------
+    tree, n_prefix, prefix_visible, root_off = make_workload(cfg)
+    N = int(tree.seg_len.sum())
+    q, k, v, do = (x.to(dev) for x in W.attn_inputs(N, N, dims, cfg))
+    kp = vp = None
+    if n_prefix:
+        _, kp, vp, _ = (x.to(dev) for x in W.attn_inputs(1, n_prefix, dims, cfg + 100))
+    do_loss = dims.vocab > 0 and not args.no_loss
+    logits = target = None
+    if do_loss:
+        # value distribution of the config; drawn on the device to keep start-up short
+        chunk_rows = N if cfg != 3 else 4096
+        logits = device_randn(torch, (chunk_rows, dims.vocab), dims.logit_std,
+                              torch.bfloat16 if dims.logit_dtype == "bf16" else torch.float32, cfg * 1000 + 5, dev)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg * 1000 + 6)
+        target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
+    run = PathRun(T, torch, dev, dims, tree, n_prefix, prefix_visible, root_off, q, k, v, do, kp, vp, logits, target,
+                  do_rope=not args.no_rope)
+    meta = run.meta
+    pairs = linearize.visible_pairs(meta)
+
+    # ---------------- the timed region: W warm-up steps, K timed steps, nothing else switched on ----------------
+    wall, ms = run.timed(args.warmup, args.steps)
+    ms_fwd, ms_bwd, ms_loss = ms["attn_fwd"], ms["attn_bwd"], ms["loss"]
+    host_ms = float(np.mean(run.host_ms))
+    useful_flop = 14.0 * dims.hq * dims.d * pairs
+    value = useful_flop / ((ms_fwd + ms_bwd) * 1e-3) / 1e12
+
+    # ---------------- second pass over the same steps with per-kernel event bracketing ----------------
+    k_steps = args.steps
+    T.kernel_timing_enable(True)
+    for _ in range(k_steps):
+        run.step()
+    torch.cuda.synchronize()
+    ktimes = T.kernel_timing_read()
+    T.kernel_timing_enable(False)
+
+    # ---------------- roofline of the dominant kernel ----------------
+    alg_flop = {"attn_fwd": 4.0, "attn_dkdv": 8.0, "attn_dq": 2.0, "ref_fwd": 4.0, "ref_bwd": 10.0}
+    attn_k = {n: t for n, t in ktimes.items() if n in alg_flop and t[1] > 0}
+    roofline = None
+    kernel_ms = {n: (t[0] / t[1]) for n, t in ktimes.items() if t[1] > 0}
+    if attn_k:
+        dom = max(attn_k, key=lambda n: attn_k[n][0])
+        avg_ms = attn_k[dom][0] / attn_k[dom][1]
+        achieved = alg_flop[dom] * dims.hq * dims.d * pairs / (avg_ms * 1e-3) / 1e12
+        peak = PEAK_BF16_TFLOPS if dims.dtype == "bf16" else 157.3
+        traffic = MEASURED_TRAFFIC_BYTES.get((cfg, dom))
+        roofline = {"kernel": dom, "bound": "mfma" if dims.dtype == "bf16" else "alu", "achieved": round(achieved, 2),
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": traffic,
+                    "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
+                    "avg_ms": round(avg_ms, 4), "launches_timed": attn_k[dom][1],
+                    "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
+    loss_gbps = loss_bwd_gbps = None
+    if do_loss and "loss_rows" in kernel_ms:
+        esz = 2 if dims.logit_dtype == "bf16" else 4
+        bytes_total = N * (dims.vocab * esz + 12)
+        loss_gbps = bytes_total / (ktimes["loss_rows"][0] / k_steps * 1e-3) / 1e9
+        # backward: one read of the logits + one write of the gradient + target, weight, lse per row
+        loss_bwd_gbps = N * (2 * dims.vocab * esz + 12) / (ktimes["loss_bwd"][0] / k_steps * 1e-3) / 1e9
+    rope_gbps = None
+    if run.do_rope and "rope" in kernel_ms:
+        rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * 2 * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
+        rope_gbps = rope_bytes / (ktimes["rope"][0] / k_steps * 1e-3) / 1e9
+
+    # ---------------- linearised per-branch baseline on the same GPU ----------------
+    lin = None
+    if not args.no_linearized and n_prefix == 0:
+        lrun, _ = linearized_run(T, torch, dev, dims, run, linearize)
+        _, ms_l = lrun.timed(2, max(3, min(args.steps, 10)))
+        lin = speedup_record(ms, ms_l, run, lrun, pairs, linearize.visible_pairs(lrun.meta))
+        del lrun
+        torch.cuda.empty_cache()
+
+    c = Ctx()
+    c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix = args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix
+    c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs = run.q, run.k, run.v, run.do, run.lse, ms_fwd, ms_bwd, pairs
+    part = leg_partitioned(c)
+    conv = leg_conv(c)
+    gdn = leg_gdn(c)
+    cpu = leg_cpu(c)
+
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
@@ -459,26 +614,43 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---------------- the other full-size configurations, briefly ----------------
+    others = None
+    if not args.no_other_configs and cfg == 2:
+        del run, q, k, v, do, logits, c
+        torch.cuda.empty_cache()
+        others = {}
+        t_start = time.perf_counter()
+        for oc in (3, 4, 5):
+            if time.perf_counter() - t_start > args.other_configs_budget_s:
+                others[f"cfg{oc}"] = {"skipped": "time budget"}
+                continue
+            others[f"cfg{oc}" if oc != 5 else "cfg5_step"] = other_config(T, torch, dev, linearize, oc, not args.no_linearized)
+
     out = {
         "metric": "tree-attn fwd+bwd useful TFLOP/s",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dims.dtype, "data": "synthetic",
-        "config": {"workload": workload, "n_tokens": N, "n_prefix": n_prefix, "hq": dims.hq, "hkv": dims.hkv,
+        "config": {"workload": WORKLOADS[cfg], "n_tokens": N, "n_prefix": n_prefix, "hq": dims.hq, "hkv": dims.hkv,
                    "d": dims.d, "visible_pairs": pairs, "useful_tflop_per_step": round(useful_flop / 1e12, 4)},
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "ms_attn_fwd": round(ms_fwd, 4), "ms_attn_bwd": round(ms_bwd, 4), "ms_loss": round(ms_loss, 4),
-        "ms_host_meta": round(float(np.mean(host_ms)), 4),
+        "ms_rope": round(ms["rope"] + ms["rope_inverse"], 4), "ms_device_path": round(ms["path"], 4),
+        "ms_host_meta": round(host_ms, 4),
         "kernel_avg_ms": {n: round(t, 4) for n, t in kernel_ms.items()},
+        "kernel_avg_ms_source": "second pass over the same steps with per-kernel event bracketing (the headline is timed without it)",
         "loss_hbm_gbps": None if loss_gbps is None else round(loss_gbps, 1),
         "loss_frac_of_hbm_peak": None if loss_gbps is None else round(loss_gbps / PEAK_HBM_GBPS, 4),
         "rope_hbm_gbps": None if rope_gbps is None else round(rope_gbps, 1),
+        "rope_frac_of_hbm_peak": None if rope_gbps is None else round(rope_gbps / PEAK_HBM_GBPS, 4),
         "loss_bwd_hbm_gbps": None if loss_bwd_gbps is None else round(loss_bwd_gbps, 1),
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,
         "partitioned": part,
         "tree_conv": conv,
         "tree_gdn": gdn,
+        "other_configs": others,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
