@@ -552,7 +552,7 @@ tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * the recorded events have completed and returns the totals since the last enable.
  * ------------------------------------------------------------------------------------------ */
 #define TT_KERNEL_ATTN_FWD    0   /* bf16 MFMA forward                                   */
-#define TT_KERNEL_ATTN_DELTA  1   /* rowsum(dO o O)                                      */
+#define TT_KERNEL_ATTN_DELTA  1   /* (unused: the dQ kernel forms rowsum(dO o O) itself)  */
 #define TT_KERNEL_ATTN_DKDV   2   /* bf16 MFMA dK/dV                                     */
 #define TT_KERNEL_ATTN_DQ     3   /* bf16 MFMA dQ                                        */
 #define TT_KERNEL_LOSS_ROWS   4   /* log-softmax + gather, one pass over the logits      */

@@ -6,8 +6,8 @@
 // Eq. 5), and over the query heads of the kv group.  Gradients of cached prefix keys are added
 // in fp32 to caller-owned accumulators (Appendix "Float32 Gradient Accumulation").
 //
-// Kernels, no atomics (results are bit-reproducible); the dK/dV pass lives in tt_attn_dkdv.hip:
-//   delta     D_i                                                      (memory bound)
+// Kernels, no atomics (results are bit-reproducible); the dK/dV pass lives in tt_attn_dkdv.hip and runs
+// after the dQ pass, whose prologue also produces the per-row terms D_i and LSE_i log2 e:
 //   dkdv      column-parallel: one work item = a key tile of up to 256 keys x one kv head, 8 wavefronts
 //             x 32 keys; loops over the query heads of the group and over the 64-query steps that can
 //             see the keys -- a contiguous range [first key, max kend) because in DFS order a subtree
@@ -26,32 +26,6 @@ namespace {
 
 constexpr int D = 128;
 constexpr int NTHREADS = 256;
-
-// ------------------------------------------------------------------------------------------------
-// Per-row terms of the backward pass, stored negated so that the MFMA accumulators can start from them:
-//   neg_delta[h][i] = -sum_d dO[i][h][d] * O[i][h][d]      neg_lse2[h][i] = -lse[h][i] * log2(e)
-// 16 lanes per (token, head) row of 128.
-// ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(NTHREADS)
-delta_kernel(const __bf16* __restrict__ o, const __bf16* __restrict__ d_o, const float* __restrict__ lse,
-             float* __restrict__ neg_delta, float* __restrict__ neg_lse2, int n_q, int hq) {
-  const int64_t row = (int64_t)blockIdx.x * (NTHREADS / 16) + (threadIdx.x >> 4);   // 16 lanes per row
-  const int sub = threadIdx.x & 15;
-  float acc = 0.f;
-  if (row < (int64_t)n_q * hq) {
-    const bf16x8 a = *(const bf16x8*)(o + row * D + sub * 8);
-    const bf16x8 b = *(const bf16x8*)(d_o + row * D + sub * 8);
-#pragma unroll
-    for (int e = 0; e < 8; e++) acc = fmaf((float)a[e], (float)b[e], acc);
-  }
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-  if (sub == 0 && row < (int64_t)n_q * hq) {
-    const int i = (int)(row / hq), h = (int)(row % hq);
-    neg_delta[(int64_t)h * n_q + i] = -acc;
-    neg_lse2[(int64_t)h * n_q + i] = -lse[(int64_t)h * n_q + i] * LOG2E_F;
-  }
-}
 
 // ------------------------------------------------------------------------------------------------
 // dQ
@@ -234,8 +208,29 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
 #pragma unroll
     for (int s = 0; s < 8; s++) { qf[s] = *(const bf16x8*)(qp + 16 * s); gf[s] = *(const bf16x8*)(gp + 16 * s); }
   }
-  const float nlse2 = a.neg_lse2[(int64_t)h * N + my_q];
-  const float ndelta = a.delta[(int64_t)h * N + my_q];
+  // Per-row terms, stored negated so that the MFMA accumulators can start from them:
+  //   -D_i = -sum_d dO[i][h][d] O[i][h][d]   and   -LSE_i log2 e.
+  // This lane holds half of its query's dO row (the d values of its operand fragments), so D_i is the sum of
+  // the two half-lanes' dot products with the matching half of O.  The terms are also written out for the
+  // dK/dV pass, which runs after this kernel.
+  float ndelta, nlse2;
+  {
+    const __bf16* op = (const __bf16*)a.o + ((int64_t)my_q * a.hq + h) * D + 8 * hf;
+    bf16x8 of[8];
+#pragma unroll
+    for (int s = 0; s < 8; s++) of[s] = *(const bf16x8*)(op + 16 * s);
+    nlse2 = -a.lse[(int64_t)h * N + my_q] * LOG2E_F;
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; s++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) acc = fmaf((float)gf[s][e], (float)of[s][e], acc);
+    ndelta = -half_swap_sum(acc);
+    if (q < N && hf == 0) {
+      a.delta[(int64_t)h * N + q] = ndelta;
+      a.neg_lse2[(int64_t)h * N + q] = nlse2;
+    }
+  }
 
   f32x16 dq_acc[4];
 #pragma unroll
@@ -331,22 +326,14 @@ size_t mfma_attn_workspace(int n_q, int n_prefix, int hq, int hkv, int d, bool b
 
 hipError_t mfma_attn_bwd(const AttnArgs& args, hipStream_t st) {
   if (args.n_q == 0) return hipSuccess;
-  // the front of the workspace holds -lse * log2(e); the rest goes to the dK/dV pass
+  // the front of the workspace holds -lse * log2(e) (a.delta, before it, holds -D); the rest goes to the dK/dV pass
   AttnArgs a = args;
   const size_t stat = row_stat_bytes(a.n_q, a.hq);
   if (a.workspace_bytes < stat) return hipErrorInvalidValue;
   a.neg_lse2 = (float*)a.workspace;
   a.workspace = (char*)a.workspace + stat;
   a.workspace_bytes -= stat;
-  {
-    const int64_t rows = (int64_t)a.n_q * a.hq;
-    const int rows_per_block = NTHREADS / 16;
-    KernelTimer timer(TT_KERNEL_ATTN_DELTA, st);
-    delta_kernel<<<(unsigned)((rows + rows_per_block - 1) / rows_per_block), NTHREADS, 0, st>>>(
-        (const __bf16*)a.o, (const __bf16*)a.d_o, a.lse, a.delta, a.neg_lse2, a.n_q, a.hq);
-    if (hipError_t e = hipGetLastError()) return e;
-  }
-  if (hipError_t e = mfma_attn_dkdv(a, st)) return e;
+  // dQ first: its prologue writes the per-row terms the dK/dV pass streams
   {
     const int n_qtiles = (a.n_q + Q_BM - 1) / Q_BM;
     if (hipError_t e = hipFuncSetAttribute((const void*)tree_attn_dq_kernel,
@@ -356,7 +343,7 @@ hipError_t mfma_attn_bwd(const AttnArgs& args, hipStream_t st) {
     tree_attn_dq_kernel<<<(unsigned)((int64_t)n_qtiles * a.hq), NTHREADS, sizeof(QSmem), st>>>(a, n_qtiles);
     if (hipError_t e = hipGetLastError()) return e;
   }
-  return hipSuccess;
+  return mfma_attn_dkdv(a, st);
 }
 
 }  // namespace tt
