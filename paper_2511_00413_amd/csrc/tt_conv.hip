@@ -16,11 +16,21 @@ constexpr int CONV_THREADS = 256;
 
 template <bool BF16> struct Chan { static constexpr int NV = BF16 ? 8 : 4; };
 
-template <bool BF16>
-__device__ __forceinline__ void load_row(const void* base, int64_t row, int64_t stride_bytes, int cv, float (&v)[Chan<BF16>::NV]) {
+// one 16-byte channel vector of a row, as loaded (8 bf16 or 4 fp32); STREAM: a non-temporal access, for rows
+// that this kernel touches once
+typedef unsigned int u32x4c __attribute__((ext_vector_type(4)));
+template <bool STREAM = false>
+__device__ __forceinline__ uint4 load_raw(const void* base, int64_t row, int64_t stride_bytes, int cv) {
   const char* p = (const char*)base + row * stride_bytes + (int64_t)cv * 16;
+  if (STREAM) {
+    const u32x4c v = __builtin_nontemporal_load(reinterpret_cast<const u32x4c*>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+  }
+  return *reinterpret_cast<const uint4*>(p);
+}
+template <bool BF16>
+__device__ __forceinline__ void unpack_raw(const uint4& u, float (&v)[Chan<BF16>::NV]) {
   if (BF16) {
-    const uint4 u = *reinterpret_cast<const uint4*>(p);
     const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
     for (int i = 0; i < 4; i++) {
@@ -28,26 +38,31 @@ __device__ __forceinline__ void load_row(const void* base, int64_t row, int64_t 
       v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
     }
   } else {
-    const float4 f = *reinterpret_cast<const float4*>(p);
-    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+    v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
   }
+}
+template <bool BF16>
+__device__ __forceinline__ void load_row(const void* base, int64_t row, int64_t stride_bytes, int cv, float (&v)[Chan<BF16>::NV]) {
+  unpack_raw<BF16>(load_raw(base, row, stride_bytes, cv), v);
 }
 
 typedef float f32x8v __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
 
-template <bool BF16>
+template <bool BF16, bool STREAM = false>
 __device__ __forceinline__ void store_row(void* base, int64_t row, int64_t stride_bytes, int cv, const float (&v)[Chan<BF16>::NV]) {
   char* p = (char*)base + row * stride_bytes + (int64_t)cv * 16;
+  u32x4c out;
   if (BF16) {
     f32x8v f;
 #pragma unroll
     for (int i = 0; i < 8; i++) f[i] = v[i];
-    const bf16x8v b = __builtin_convertvector(f, bf16x8v);       // round to nearest even
-    *reinterpret_cast<uint4*>(p) = __builtin_bit_cast(uint4, b);
+    out = __builtin_bit_cast(u32x4c, __builtin_convertvector(f, bf16x8v));       // round to nearest even
   } else {
-    *reinterpret_cast<float4*>(p) = float4{v[0], v[1], v[2], v[3]};
+    out = u32x4c{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
   }
+  if (STREAM) __builtin_nontemporal_store(out, reinterpret_cast<u32x4c*>(p));
+  else *reinterpret_cast<u32x4c*>(p) = out;
 }
 
 struct ConvArgs {
@@ -119,57 +134,84 @@ __device__ __forceinline__ void pre_activation(const Weights<BF16, K>& wt, const
   }
 }
 
-template <bool BF16, int K>
-__device__ __forceinline__ void shift_window(float (&win)[K > 1 ? K - 1 : 1][Chan<BF16>::NV], const float (&xt)[Chan<BF16>::NV]) {
-  constexpr int NV = Chan<BF16>::NV;
-#pragma unroll
-  for (int m = K - 2; m >= 1; m--)
-#pragma unroll
-    for (int i = 0; i < NV; i++) win[m][i] = win[m - 1][i];
-  if (K > 1)
-#pragma unroll
-    for (int i = 0; i < NV; i++) win[0][i] = xt[i];
-}
+// Tokens whose loads are issued together.  A multiple of K: the kernels keep the last K inputs (and, backward,
+// the last K gradients) in rings of K register slots, token t0 + i in slot i % K, and with batches that are
+// multiples of K every slot index is a compile-time constant after unrolling -- the rings never move.
+template <int K> struct ConvBatch { static constexpr int U = K == 3 ? 3 : 4; };
 
-constexpr int CONV_U = 4;      // tokens whose loads are issued together
+// ring slot m places before slot `slot`
+template <int K> __device__ __forceinline__ constexpr int ring_back(int slot, int m) { return (slot - m + 2 * K) % K; }
+
+// xr[ring_back(slot, m)] = x[pred^m(t)] for m = 1..K-1, zero past the start of the branch
+template <bool BF16, int K>
+__device__ __forceinline__ void rebuild_ring(const ConvArgs& a, int pred, int cv, int slot, float (&xr)[K][Chan<BF16>::NV]) {
+  constexpr int NV = Chan<BF16>::NV;
+  int q = pred;
+#pragma unroll
+  for (int m = 1; m < K; m++) {
+    if (q >= 0) {
+      load_row<BF16>(a.x, q, a.x_stride, cv, xr[ring_back<K>(slot, m)]);
+      q = a.tok_pred[q];
+    } else {
+#pragma unroll
+      for (int i = 0; i < NV; i++) xr[ring_back<K>(slot, m)][i] = 0.f;
+    }
+  }
+}
 
 template <bool BF16, int K>
 __global__ __launch_bounds__(CONV_THREADS) void tree_conv_fwd_kernel(ConvArgs a) {
   constexpr int NV = Chan<BF16>::NV;
+  constexpr int U = ConvBatch<K>::U;
+  // consecutive workgroups cover one token tile's channel vectors (a row is read in full by neighbours)
   const int64_t gid = (int64_t)blockIdx.x * CONV_THREADS + threadIdx.x;
   const int vpr = a.channels / NV;
-  const int64_t tile = gid / vpr;
-  const int cv = (int)(gid - tile * vpr);
+  const int tile = (int)(gid / vpr);
+  const int cv = (int)(gid - (int64_t)tile * vpr);
   if (tile >= a.n_tiles) return;
   Weights<BF16, K> wt;
   wt.load(a, cv * NV);
-  float win[K > 1 ? K - 1 : 1][NV];
+  float xr[K][NV];                                  // ring of the last K inputs
   const int t0 = (int)tile * a.tok_tile;
   const int t1 = min(t0 + a.tok_tile, a.n_tokens);
-  for (int tb = t0; tb < t1; tb += CONV_U) {
-    int p[CONV_U];
-    float xt[CONV_U][NV];
+  // Two batches of U tokens are in flight: the loads of the next batch are issued before the current one is
+  // worked on, so the memory round trip of a batch runs under the arithmetic of the one before.
+  struct Batch { int p[U]; uint4 x[U]; };
+  auto load_batch = [&](int tb, Batch& b) {
 #pragma unroll
-    for (int u = 0; u < CONV_U; u++) {
+    for (int u = 0; u < U; u++) {
       const int t = min(tb + u, t1 - 1);
-      p[u] = a.tok_pred[t];
-      load_row<BF16>(a.x, t, a.x_stride, cv, xt[u]);
+      b.p[u] = a.tok_pred[t];
+      b.x[u] = load_raw<true>(a.x, t, a.x_stride, cv);
     }
+  };
+  auto work_batch = [&](int tb, const Batch& b) {       // (tb - t0) is a multiple of U, hence of K
 #pragma unroll
-    for (int u = 0; u < CONV_U; u++) {
+    for (int u = 0; u < U; u++) {
       const int t = tb + u;
+      const int slot = u % K;
       if (t < t1) {
+        unpack_raw<BF16>(b.x[u], xr[slot]);
+        if (t == t0 || b.p[u] != t - 1) rebuild_ring<BF16, K>(a, b.p[u], cv, slot, xr);
         float pre[NV];
-        if (t == t0 || p[u] != t - 1) rebuild_window<BF16, K>(a, p[u], cv, win);
-        pre_activation<BF16, K>(wt, xt[u], win, pre);
-        if (a.silu) {
 #pragma unroll
-          for (int i = 0; i < NV; i++) pre[i] = silu_f(pre[i]);
+        for (int i = 0; i < NV; i++) {
+          float acc = wt.b[i] + wt.w[K - 1][i] * xr[slot][i];
+#pragma unroll
+          for (int m = 1; m < K; m++) acc += wt.w[K - 1 - m][i] * xr[ring_back<K>(slot, m)][i];
+          pre[i] = a.silu ? silu_f(acc) : acc;
         }
         store_row<BF16>(a.y, t, a.y_stride, cv, pre);
-        shift_window<BF16, K>(win, xt[u]);
       }
     }
+  };
+  Batch ba, bb;
+  load_batch(t0, ba);
+  for (int tb = t0; tb < t1; tb += 2 * U) {
+    load_batch(tb + U, bb);
+    work_batch(tb, ba);
+    load_batch(tb + 2 * U, ba);
+    work_batch(tb + U, bb);
   }
 }
 
@@ -196,88 +238,99 @@ __device__ __forceinline__ void grad_pre_at(const ConvArgs& a, const Weights<BF1
 template <bool BF16, int K>
 __global__ __launch_bounds__(CONV_THREADS) void tree_conv_bwd_kernel(ConvArgs a) {
   constexpr int NV = Chan<BF16>::NV;
+  constexpr int U = ConvBatch<K>::U;
   const int64_t gid = (int64_t)blockIdx.x * CONV_THREADS + threadIdx.x;
   const int vpr = a.channels / NV;
-  const int64_t tile = gid / vpr;
-  const int cv = (int)(gid - tile * vpr);
+  const int tile = (int)(gid / vpr);
+  const int cv = (int)(gid - (int64_t)tile * vpr);
   if (tile >= a.n_tiles) return;
   Weights<BF16, K> wt;
   wt.load(a, cv * NV);
-  float win[K > 1 ? K - 1 : 1][NV];
-  float gq[K][NV];          // gq[j] = g[t - j]
-  bool lk[K];               // lk[j] = token t-j directly follows token t-j-1 on its sequence
+  // rings of K slots, token t0 + i in slot i % K: inputs, g = dy * act'(pre), and the "directly follows its
+  // predecessor" flags
+  float xr[K][NV], gq[K][NV];
+  bool lk[K];
   float dw[K][NV], db[NV];
 #pragma unroll
   for (int i = 0; i < NV; i++) {
     db[i] = 0.f;
 #pragma unroll
-    for (int j = 0; j < K; j++) { dw[j][i] = 0.f; gq[j][i] = 0.f; }
+    for (int j = 0; j < K; j++) { dw[j][i] = 0.f; gq[j][i] = 0.f; xr[j][i] = 0.f; }
   }
 #pragma unroll
   for (int j = 0; j < K; j++) lk[j] = false;
   const int t0 = (int)tile * a.tok_tile;
   const int t1 = min(t0 + a.tok_tile, a.n_tokens);
   const int t_end = t1 + K - 1;                     // look-ahead: g of the K-1 tokens after the tile
-  for (int tb = t0; tb < t_end; tb += CONV_U) {
-    int p[CONV_U];
-    float xt[CONV_U][NV], dyt[CONV_U][NV];
+  // two batches of U tokens in flight, as in the forward
+  struct Batch { int p[U]; uint4 x[U], dy[U]; };
+  auto load_batch = [&](int tb, Batch& b) {
 #pragma unroll
-    for (int u = 0; u < CONV_U; u++) {
+    for (int u = 0; u < U; u++) {
       const int t = min(tb + u, a.n_tokens - 1);
-      p[u] = a.tok_pred[t];
-      load_row<BF16>(a.x, t, a.x_stride, cv, xt[u]);
-      load_row<BF16>(a.dy, t, a.dy_stride, cv, dyt[u]);
+      b.p[u] = a.tok_pred[t];
+      b.x[u] = load_raw<true>(a.x, t, a.x_stride, cv);
+      b.dy[u] = load_raw<true>(a.dy, t, a.dy_stride, cv);
     }
+  };
+  auto work_batch = [&](int tb, const Batch& b) {       // (tb - t0) is a multiple of U, hence of K
 #pragma unroll
-    for (int u = 0; u < CONV_U; u++) {
+    for (int u = 0; u < U; u++) {
       const int t = tb + u;
-      if (t >= t_end) break;
-      // shift the ring
-#pragma unroll
-      for (int j = K - 1; j >= 1; j--) {
-        lk[j] = lk[j - 1];
-#pragma unroll
-        for (int i = 0; i < NV; i++) gq[j][i] = gq[j - 1][i];
-      }
-      if (t < a.n_tokens) {
-        float pre[NV];
-        if (t == t0 || p[u] != t - 1) rebuild_window<BF16, K>(a, p[u], cv, win);
-        pre_activation<BF16, K>(wt, xt[u], win, pre);
-#pragma unroll
-        for (int i = 0; i < NV; i++) gq[0][i] = a.silu ? dyt[u][i] * dsilu_f(pre[i]) : dyt[u][i];
-        lk[0] = p[u] == t - 1;
-        if (t < t1) {
+      const int slot = u % K;
+      if (t < t_end) {
+        if (t < a.n_tokens) {
+          float dyt[NV];
+          unpack_raw<BF16>(b.x[u], xr[slot]);
+          unpack_raw<BF16>(b.dy[u], dyt);
+          if (t == t0 || b.p[u] != t - 1) rebuild_ring<BF16, K>(a, b.p[u], cv, slot, xr);
 #pragma unroll
           for (int i = 0; i < NV; i++) {
-            db[i] += gq[0][i];
-            dw[K - 1][i] += gq[0][i] * xt[u][i];
+            float pre = wt.b[i] + wt.w[K - 1][i] * xr[slot][i];
 #pragma unroll
-            for (int m = 1; m < K; m++) dw[K - 1 - m][i] += gq[0][i] * win[m - 1][i];
+            for (int m = 1; m < K; m++) pre += wt.w[K - 1 - m][i] * xr[ring_back<K>(slot, m)][i];
+            gq[slot][i] = a.silu ? dyt[i] * dsilu_f(pre) : dyt[i];
           }
-        }
-        shift_window<BF16, K>(win, xt[u]);
-      } else {
-        lk[0] = false;
+          lk[slot] = b.p[u] == t - 1;
+          if (t < t1) {
 #pragma unroll
-        for (int i = 0; i < NV; i++) gq[0][i] = 0.f;
-      }
-      const int s = t - (K - 1);
-      if (s >= t0) {          // s < t1 by the loop bound
-        float dx[NV];
+            for (int i = 0; i < NV; i++) {
+              db[i] += gq[slot][i];
 #pragma unroll
-        for (int i = 0; i < NV; i++) dx[i] = wt.w[K - 1][i] * gq[K - 1][i];
-        bool valid = true;
-#pragma unroll
-        for (int m = 1; m < K; m++) {
-          valid = valid && lk[K - 1 - m];
-          if (valid) {
-#pragma unroll
-            for (int i = 0; i < NV; i++) dx[i] += wt.w[K - 1 - m][i] * gq[K - 1 - m][i];
+              for (int m = 0; m < K; m++) dw[K - 1 - m][i] += gq[slot][i] * xr[ring_back<K>(slot, m)][i];
+            }
           }
+        } else {
+          lk[slot] = false;
+#pragma unroll
+          for (int i = 0; i < NV; i++) gq[slot][i] = 0.f;
         }
-        store_row<BF16>(a.y, s, a.y_stride, cv, dx);
+        const int s = t - (K - 1);                // its g sits K-1 slots back; successor m one slot further on each
+        if (s >= t0) {                            // s < t1 by the loop bound
+          float dx[NV];
+#pragma unroll
+          for (int i = 0; i < NV; i++) dx[i] = wt.w[K - 1][i] * gq[ring_back<K>(slot, K - 1)][i];
+          bool valid = true;
+#pragma unroll
+          for (int m = 1; m < K; m++) {
+            valid = valid && lk[ring_back<K>(slot, K - 1 - m)];
+            if (valid) {
+#pragma unroll
+              for (int i = 0; i < NV; i++) dx[i] += wt.w[K - 1 - m][i] * gq[ring_back<K>(slot, K - 1 - m)][i];
+            }
+          }
+          store_row<BF16, true>(a.y, s, a.y_stride, cv, dx);
+        }
       }
     }
+  };
+  Batch ba, bb;
+  load_batch(t0, ba);
+  for (int tb = t0; tb < t_end; tb += 2 * U) {
+    load_batch(tb + U, bb);
+    work_batch(tb, ba);
+    load_batch(tb + 2 * U, ba);
+    work_batch(tb + U, bb);
   }
   float* part = a.partial + (int64_t)tile * (K + 1) * a.channels + cv * NV;
 #pragma unroll
@@ -292,9 +345,9 @@ __global__ __launch_bounds__(CONV_THREADS) void tree_conv_bwd_kernel(ConvArgs a)
 // Each listed token is recomputed completely (chain part + listed extra successors) and overwrites
 // what the fast path stored, so every dx row has one writer last and one rounding.
 template <bool BF16, int K>
-__global__ __launch_bounds__(CONV_THREADS) void tree_conv_fix_kernel(ConvArgs a) {
+__device__ __forceinline__ void conv_fix_block(const ConvArgs& a, int64_t block) {
   constexpr int NV = Chan<BF16>::NV;
-  const int64_t gid = (int64_t)blockIdx.x * CONV_THREADS + threadIdx.x;
+  const int64_t gid = block * CONV_THREADS + threadIdx.x;
   const int vpr = a.channels / NV;
   const int64_t f = gid / vpr;
   const int cv = (int)(gid - f * vpr);
@@ -327,27 +380,51 @@ __global__ __launch_bounds__(CONV_THREADS) void tree_conv_fix_kernel(ConvArgs a)
   store_row<BF16>(a.y, s, a.y_stride, cv, dx);
 }
 
-// dweight[c][j] = sum over tiles of partial[tile][j][c]; dbias[c] = same for j = K.  Fixed order.
-__global__ __launch_bounds__(CONV_THREADS) void tree_conv_reduce_kernel(const float* __restrict__ partial, int n_tiles, int K,
-                                                                        int channels, float* __restrict__ dweight,
-                                                                        float* __restrict__ dbias) {
-  const int64_t gid = (int64_t)blockIdx.x * CONV_THREADS + threadIdx.x;
-  if (gid >= (int64_t)(K + 1) * channels) return;
-  const int j = (int)(gid / channels), c = (int)(gid - (int64_t)j * channels);
-  const float* src = partial + (int64_t)j * channels + c;
-  const int64_t step = (int64_t)(K + 1) * channels;
+// dweight[c][j] = sum over tiles of partial[tile][j][c]; dbias[c] = same for j = K.  Fixed order: the tiles are
+// cut into RED_SEG consecutive segments, one thread sums one segment of one output in tile order (16 loads in
+// flight), and the segment sums are added in segment order -- the same association on every run.  A workgroup
+// covers RED_OUT consecutive outputs x RED_SEG segments, so a wavefront reads 256 contiguous bytes per tile.
+constexpr int RED_SEG = 4, RED_OUT = CONV_THREADS / RED_SEG;
+__device__ __forceinline__ void conv_reduce_block(const float* __restrict__ partial, int n_tiles, int K, int channels,
+                                                  float* __restrict__ dweight, float* __restrict__ dbias, int64_t block) {
+  __shared__ float seg_sum[RED_SEG][RED_OUT];
+  const int o = threadIdx.x % RED_OUT, sg = threadIdx.x / RED_OUT;
+  const int64_t n_out = (int64_t)(K + 1) * channels;
+  const int64_t gid = block * RED_OUT + o;
+  const int per = (n_tiles + RED_SEG - 1) / RED_SEG;
+  const int t_lo = min(sg * per, n_tiles), t_hi = min(t_lo + per, n_tiles);
   float acc = 0.f;
-  int t = 0;
-  for (; t + 8 <= n_tiles; t += 8) {               // eight loads in flight, added in tile order
-    float v[8];
+  if (gid < n_out) {
+    const float* src = partial + gid;
+    int t = t_lo;
+    for (; t + 16 <= t_hi; t += 16) {
+      float v[16];
 #pragma unroll
-    for (int u = 0; u < 8; u++) v[u] = src[(t + u) * step];
+      for (int u = 0; u < 16; u++) v[u] = src[(int64_t)(t + u) * n_out];
 #pragma unroll
-    for (int u = 0; u < 8; u++) acc += v[u];
+      for (int u = 0; u < 16; u++) acc += v[u];
+    }
+    for (; t < t_hi; t++) acc += src[(int64_t)t * n_out];
   }
-  for (; t < n_tiles; t++) acc += src[t * step];
-  if (j < K) dweight[(int64_t)c * K + j] = acc;
-  else if (dbias) dbias[c] = acc;
+  seg_sum[sg][o] = acc;
+  __syncthreads();
+  if (sg == 0 && gid < n_out) {
+    float tot = seg_sum[0][o];
+#pragma unroll
+    for (int q = 1; q < RED_SEG; q++) tot += seg_sum[q][o];
+    const int j = (int)(gid / channels), c = (int)(gid - (int64_t)j * channels);
+    if (j < K) dweight[(int64_t)c * K + j] = tot;
+    else if (dbias) dbias[c] = tot;
+  }
+}
+
+// What follows the fast path of the backward, in one launch: the first n_reduce_blocks workgroups sum the
+// weight-gradient partials, the others recompute the dx rows of the listed branch-point tokens (the two jobs touch
+// different outputs and both only need the fast path to have finished).
+template <bool BF16, int K>
+__global__ __launch_bounds__(CONV_THREADS) void tree_conv_finish_kernel(ConvArgs a, float* dweight, float* dbias, int n_reduce_blocks) {
+  if ((int)blockIdx.x < n_reduce_blocks) conv_reduce_block(a.partial, a.n_tiles, K, a.channels, dweight, dbias, blockIdx.x);
+  else conv_fix_block<BF16, K>(a, (int64_t)blockIdx.x - n_reduce_blocks);
 }
 
 int pick_tile(int64_t n_tokens, int vpr, int lo, int hi) {
@@ -361,8 +438,7 @@ inline unsigned blocks_for(int64_t n) { return (unsigned)((n + CONV_THREADS - 1)
 
 template <bool BF16, int K>
 hipError_t launch_fwd(const ConvArgs& a, hipStream_t st) {
-  const int64_t lanes = (int64_t)a.n_tiles * (a.channels / Chan<BF16>::NV);
-  tree_conv_fwd_kernel<BF16, K><<<blocks_for(lanes), CONV_THREADS, 0, st>>>(a);
+  tree_conv_fwd_kernel<BF16, K><<<blocks_for((int64_t)a.n_tiles * (a.channels / Chan<BF16>::NV)), CONV_THREADS, 0, st>>>(a);
   return hipGetLastError();
 }
 
@@ -374,15 +450,12 @@ hipError_t launch_bwd(const ConvArgs& a, float* dweight, float* dbias, hipStream
     tree_conv_bwd_kernel<BF16, K><<<blocks_for((int64_t)a.n_tiles * vpr), CONV_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  if (a.n_fix > 0) {
-    KernelTimer t(TT_KERNEL_CONV_FIX, st);
-    tree_conv_fix_kernel<BF16, K><<<blocks_for((int64_t)a.n_fix * vpr), CONV_THREADS, 0, st>>>(a);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  }
   {
     KernelTimer t(TT_KERNEL_CONV_FIX, st);
-    tree_conv_reduce_kernel<<<blocks_for((int64_t)(K + 1) * a.channels), CONV_THREADS, 0, st>>>(a.partial, a.n_tiles, K, a.channels,
-                                                                                                 dweight, dbias);
+    const int64_t n_out = (int64_t)(K + 1) * a.channels;
+    const int n_reduce_blocks = (int)((n_out + RED_OUT - 1) / RED_OUT);
+    const unsigned n_fix_blocks = a.n_fix > 0 ? blocks_for((int64_t)a.n_fix * vpr) : 0;
+    tree_conv_finish_kernel<BF16, K><<<(unsigned)n_reduce_blocks + n_fix_blocks, CONV_THREADS, 0, st>>>(a, dweight, dbias, n_reduce_blocks);
   }
   return hipGetLastError();
 }

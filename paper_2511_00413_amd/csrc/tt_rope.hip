@@ -57,6 +57,27 @@ rope_kernel(int64_t n_tokens, int n_heads, int d, const char* x, int64_t x_strid
   const int half = d / 2;
   const int64_t tok0 = (int64_t)blockIdx.x * tpb;
   const int ntok = (int)min((int64_t)tpb, n_tokens - tok0);
+  const int vph = half / EPV;                       // vectors per half head
+  const int per_tok = n_heads * vph;
+  const int n_work = ntok * per_tok;
+  // element offset of work item wk (one vector pair) inside x / y, and where its (cos, sin) pairs start
+  auto locate = [&](int wk, int64_t& x_off, int64_t& y_off, int& cs_off) {
+    const int tk = wk / per_tok, rem = wk % per_tok;
+    const int h = rem / vph, vi = rem % vph;
+    const int64_t off = (int64_t)h * d + (int64_t)vi * EPV;
+    x_off = ((tok0 + tk) * x_stride + off) * ESZ;
+    y_off = ((tok0 + tk) * y_stride + off) * ESZ;
+    cs_off = tk * half + vi * EPV;
+  };
+  // the first vector pair of every thread is requested before the angles are worked out, so that the memory
+  // round trip runs under the fp64 arithmetic; streaming (non-temporal) accesses: nothing is read twice
+  u32x4 vlo = {0, 0, 0, 0}, vhi = {0, 0, 0, 0};
+  if ((int)threadIdx.x < n_work) {
+    int64_t xo, yo; int co;
+    locate(threadIdx.x, xo, yo, co);
+    vlo = __builtin_nontemporal_load((const u32x4*)(x + xo));
+    vhi = __builtin_nontemporal_load((const u32x4*)(x + xo + (int64_t)half * ESZ));
+  }
   for (int idx = threadIdx.x; idx < ntok * half; idx += ROPE_THREADS) {
     const int tk = idx / half, i = idx % half;
     const double inv_freq = exp2(-(2.0 * i / d) * log2_base);
@@ -68,28 +89,25 @@ rope_kernel(int64_t n_tokens, int n_heads, int d, const char* x, int64_t x_strid
     cs[idx] = make_float2(c, inverse ? -s : s);
   }
   __syncthreads();
-  const int vph = half / EPV;                       // vectors per half head
-  const int per_tok = n_heads * vph;
-  for (int wk = threadIdx.x; wk < ntok * per_tok; wk += ROPE_THREADS) {
-    const int tk = wk / per_tok, rem = wk % per_tok;
-    const int h = rem / vph, vi = rem % vph;
-    const int64_t off = (int64_t)h * d + (int64_t)vi * EPV;
-    const char* xp = x + ((tok0 + tk) * x_stride + off) * ESZ;
-    char* yp = y + ((tok0 + tk) * y_stride + off) * ESZ;
-    const u32x4 vlo = *(const u32x4*)xp;
-    const u32x4 vhi = *(const u32x4*)(xp + (int64_t)half * ESZ);
+  for (int wk = threadIdx.x; wk < n_work; wk += ROPE_THREADS) {
+    int64_t xo, yo; int co;
+    locate(wk, xo, yo, co);
+    if (wk != (int)threadIdx.x) {
+      vlo = __builtin_nontemporal_load((const u32x4*)(x + xo));
+      vhi = __builtin_nontemporal_load((const u32x4*)(x + xo + (int64_t)half * ESZ));
+    }
     float lo[EPV], hi[EPV], olo[EPV], ohi[EPV];
     Vec<EPV>::unpack(vlo, lo);
     Vec<EPV>::unpack(vhi, hi);
-    const float2* t = cs + tk * half + vi * EPV;
+    const float2* t = cs + co;
 #pragma unroll
     for (int e = 0; e < EPV; e++) {
       const float2 q = t[e];
       olo[e] = lo[e] * q.x - hi[e] * q.y;
       ohi[e] = hi[e] * q.x + lo[e] * q.y;
     }
-    *(u32x4*)yp = Vec<EPV>::pack(olo);
-    *(u32x4*)(yp + (int64_t)half * ESZ) = Vec<EPV>::pack(ohi);
+    __builtin_nontemporal_store(Vec<EPV>::pack(olo), (u32x4*)(y + yo));
+    __builtin_nontemporal_store(Vec<EPV>::pack(ohi), (u32x4*)(y + yo + (int64_t)half * ESZ));
   }
 }
 
