@@ -437,7 +437,7 @@ def leg_gdn(c):
         del gws
         if not args.no_gdn_bwd:
             gdo = torch.randn((N, ghv, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-            bws = torch.empty(T.binding._lib().tt_tree_gdn_bwd_workspace(N, gplan.n_chunks, gplan.n_slots, ghk, ghv), dtype=torch.uint8,
+            bws = torch.empty(T.binding._lib().tt_tree_gdn_bwd_workspace(N, gplan.n_chunks, gplan.n_slots, gplan.n_segments, ghk, ghv), dtype=torch.uint8,
                               device=dev)
             n_it = 3
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]

@@ -487,6 +487,20 @@ tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels, int32_t ke
  *                            capture nodes may not share a chunk.
  *   Zero-length nodes have no chunk; their children continue from the nearest token-bearing
  *   ancestor.
+ * tt_tree_gdn_schedule (host): which parts of the chunk program may run side by side.  A segment
+ *   is a maximal run of chunks whose state stays on chip (all but its first chunk have src = -2);
+ *   it depends only on the segment that saved the slot its first chunk loads.  Level 0 holds the
+ *   segments that start from the initial state, level l + 1 those whose slot a level-l segment
+ *   saves: sibling subtrees land in one level and are walked by different workgroups at the same
+ *   time, one launch per level.  Outputs, segments in level order (inside a level the longest
+ *   first, ties in chunk order):
+ *     seg_chunk0, seg_chunk1 [n_segments]  first chunk and one past the last chunk
+ *     level_off [n_levels + 1]             segments of level l: level_off[l] .. level_off[l+1]-1
+ *     slot_cons_off [n_slots + 1], slot_cons [n_consumers]   per slot, the segments that start
+ *                                          from it, in chunk order (the backward sums their
+ *                                          gradients in this order)
+ *   The device calls take the schedule as tt_gdn_schedule (level_off stays a host array, the
+ *   others are device copies); NULL = one set of workgroups walks all chunks in sequence order.
  * tt_tree_gdn_fwd (device): q, k [n_tokens][hk][128], v, o [n_tokens][hv][128] bf16 contiguous;
  *   g, beta [n_tokens][hv] fp32 (g <= 0: log of the decay); the chunk arrays are device
  *   copies of the plan (chunk_cap may be NULL = nothing captured).  initial_state [hv][128][128]
@@ -498,6 +512,20 @@ tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels, int32_t ke
  *   than 128), TT_ERR_WORKSPACE.
  * ------------------------------------------------------------------------------------------ */
 #define TT_GDN_CHUNK 64
+typedef struct {
+  int32_t n_segments, n_levels;
+  const int32_t* level_off;       /* HOST   [n_levels + 1]                    */
+  const int32_t* seg_chunk0;      /* device [n_segments]                      */
+  const int32_t* seg_chunk1;      /* device [n_segments]                      */
+  const int32_t* slot_cons_off;   /* device [n_slots + 1]   (backward only)   */
+  const int32_t* slot_cons;       /* device [n_consumers]   (backward only)   */
+} tt_gdn_schedule;
+tt_status tt_tree_gdn_schedule_sizes(int32_t n_chunks, const int32_t* chunk_src, const int32_t* chunk_dst,
+                                     int32_t n_slots, int32_t* n_segments, int32_t* n_levels,
+                                     int32_t* n_consumers);
+tt_status tt_tree_gdn_schedule(int32_t n_chunks, const int32_t* chunk_src, const int32_t* chunk_dst,
+                               int32_t n_slots, int32_t* seg_chunk0, int32_t* seg_chunk1,
+                               int32_t* level_off, int32_t* slot_cons_off, int32_t* slot_cons);
 tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
                                  int32_t* n_chunks, int32_t* n_slots);
 tt_status tt_tree_gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len,
@@ -509,7 +537,8 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
                           const void* q, const void* k, const void* v, const float* g, const float* beta,
                           int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
                           const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
-                          const int32_t* chunk_cap, const float* initial_state, float* state_out,
+                          const int32_t* chunk_cap, const tt_gdn_schedule* schedule,
+                          const float* initial_state, float* state_out,
                           void* o, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
@@ -533,16 +562,22 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * forward (state and state gradient stay fp32); the triangular solves and all element-wise work
  * are fp32.
  * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 300 KB per chunk and value
- * head, plus two fp32 [n_tokens][hv][128] arrays and 2 x n_slots saved states per head).
+ * head, plus two fp32 [n_tokens][hv][128] arrays, 2 x n_slots saved states per head and, with a
+ * schedule, one state gradient per segment and head; n_segments = 0 when the call gets no schedule).
+ * With a schedule the reverse walk also runs level by level (last level first): every segment
+ * stores the gradient of the state it started from, and the chunk that saved a slot adds the
+ * gradients of the slot's readers in the order of slot_cons -- a fixed order, no atomics.
  * Errors: as tt_tree_gdn_fwd.
  * ------------------------------------------------------------------------------------------ */
-size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t hk, int32_t hv);
+size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments,
+                                 int32_t hk, int32_t hv);
 tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
                           const void* q, const void* k, const void* v, const float* g, const float* beta,
                           const void* d_o,
                           int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
                           const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
-                          const int32_t* chunk_cap, const float* initial_state, const float* d_state_out,
+                          const int32_t* chunk_cap, const tt_gdn_schedule* schedule,
+                          const float* initial_state, const float* d_state_out,
                           void* dq, void* dk_out, void* dv_out, float* dg, float* dbeta, float* d_initial_state,
                           void* workspace, size_t workspace_bytes, void* stream);
 

@@ -120,13 +120,17 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_gdn_workspace.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.tt_tree_gdn_fwd.restype = ctypes.c_int32
         lib.tt_tree_gdn_fwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
-                                        _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp,
                                         _vp, _vp, ctypes.c_size_t, _vp]
+        lib.tt_tree_gdn_schedule_sizes.restype = ctypes.c_int32
+        lib.tt_tree_gdn_schedule_sizes.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, _c_i32p, _c_i32p, _c_i32p]
+        lib.tt_tree_gdn_schedule.restype = ctypes.c_int32
+        lib.tt_tree_gdn_schedule.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp]
         lib.tt_tree_gdn_bwd_workspace.restype = ctypes.c_size_t
-        lib.tt_tree_gdn_bwd_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.tt_tree_gdn_bwd_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
         lib.tt_tree_gdn_bwd.restype = ctypes.c_int32
         lib.tt_tree_gdn_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
-                                        _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp,
                                         _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         lib.tt_tree_path_weights.restype = ctypes.c_int32
         lib.tt_tree_path_weights.argtypes = [ctypes.c_int32, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp]
@@ -272,6 +276,17 @@ class ConvPlan:
 GDN_CHUNK = 64
 
 
+class _GdnSchedule(ctypes.Structure):
+    _fields_ = [("n_segments", ctypes.c_int32), ("n_levels", ctypes.c_int32), ("level_off", ctypes.c_void_p),
+                ("seg_chunk0", ctypes.c_void_p), ("seg_chunk1", ctypes.c_void_p), ("slot_cons_off", ctypes.c_void_p),
+                ("slot_cons", ctypes.c_void_p)]
+
+
+def _sched_ref(plan):
+    sc = plan._schedule()
+    return None if sc is None else ctypes.byref(sc)
+
+
 @dataclass
 class GdnPlan:
     """Host output of tt_tree_gdn_plan: the chunk program of the gated-delta-rule scan."""
@@ -284,12 +299,38 @@ class GdnPlan:
     chunk_cap: np.ndarray
     n_capture: int = 0
     device: Optional[dict] = None
+    # tt_tree_gdn_schedule: segments of the chunk program by dependency level (sibling subtrees side by side)
+    seg_chunk0: Optional[np.ndarray] = None
+    seg_chunk1: Optional[np.ndarray] = None
+    level_off: Optional[np.ndarray] = None
+    slot_cons_off: Optional[np.ndarray] = None
+    slot_cons: Optional[np.ndarray] = None
+    parallel: bool = True          # False: the device calls walk all chunks in sequence order (for cross-checks)
+
+    @property
+    def n_segments(self) -> int:
+        return 0 if self.seg_chunk0 is None else len(self.seg_chunk0)
+
+    @property
+    def n_levels(self) -> int:
+        return 0 if self.level_off is None else len(self.level_off) - 1
 
     def to_device(self, device="cuda"):
         torch = _torch()
-        self.device = {n: torch.from_numpy(getattr(self, n)).to(device)
-                       for n in ("chunk_tok0", "chunk_len", "chunk_src", "chunk_dst", "chunk_cap")}
+        names = ["chunk_tok0", "chunk_len", "chunk_src", "chunk_dst", "chunk_cap"]
+        if self.seg_chunk0 is not None:
+            names += ["seg_chunk0", "seg_chunk1", "slot_cons_off", "slot_cons"]
+        self.device = {n: torch.from_numpy(getattr(self, n)).to(device) for n in names}
         return self
+
+    def _schedule(self):
+        """ctypes tt_gdn_schedule for the device calls, or None (sequential walk)."""
+        if not self.parallel or self.seg_chunk0 is None or self.device is None or "seg_chunk0" not in self.device:
+            return None
+        d = self.device
+        return _GdnSchedule(self.n_segments, self.n_levels, _hp(self.level_off), ctypes.c_void_p(d["seg_chunk0"].data_ptr()),
+                            ctypes.c_void_p(d["seg_chunk1"].data_ptr()), ctypes.c_void_p(d["slot_cons_off"].data_ptr()),
+                            ctypes.c_void_p(d["slot_cons"].data_ptr()) if len(self.slot_cons) else None)
 
 
 def tree_gdn_plan(parent, seg_len, capture_nodes=()) -> GdnPlan:
@@ -301,7 +342,16 @@ def tree_gdn_plan(parent, seg_len, capture_nodes=()) -> GdnPlan:
     arrs = [np.zeros(nc.value, np.int32) for _ in range(5)]
     cap = _np(list(capture_nodes), np.int32)
     _check(_lib().tt_tree_gdn_plan(len(parent), _hp(parent), _hp(seg_len), len(cap), _hp(cap), *(_hp(a) for a in arrs)))
-    return GdnPlan(nc.value, ns.value, *arrs, n_capture=len(cap))
+    plan = GdnPlan(nc.value, ns.value, *arrs, n_capture=len(cap))
+    nseg, nlev, ncons = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(_lib().tt_tree_gdn_schedule_sizes(plan.n_chunks, _hp(plan.chunk_src), _hp(plan.chunk_dst), plan.n_slots,
+                                             ctypes.byref(nseg), ctypes.byref(nlev), ctypes.byref(ncons)))
+    plan.seg_chunk0, plan.seg_chunk1 = np.zeros(nseg.value, np.int32), np.zeros(nseg.value, np.int32)
+    plan.level_off = np.zeros(nlev.value + 1, np.int32)
+    plan.slot_cons_off, plan.slot_cons = np.zeros(plan.n_slots + 1, np.int32), np.zeros(ncons.value, np.int32)
+    _check(_lib().tt_tree_gdn_schedule(plan.n_chunks, _hp(plan.chunk_src), _hp(plan.chunk_dst), plan.n_slots, _hp(plan.seg_chunk0),
+                                       _hp(plan.seg_chunk1), _hp(plan.level_off), _hp(plan.slot_cons_off), _hp(plan.slot_cons)))
+    return plan
 
 
 def tree_conv_plan(tok_pred, kernel_size: int) -> ConvPlan:
@@ -730,7 +780,7 @@ def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, works
     _check(_lib().tt_tree_gdn_fwd(n, hk, hv, dk, dv, float(dk) ** -0.5 if scale is None else float(scale), _dp(q), _dp(k), _dp(v),
                                   _dp(g), _dp(beta), plan.n_chunks, _dp(d["chunk_tok0"]), _dp(d["chunk_len"]), _dp(d["chunk_src"]),
                                   _dp(d["chunk_dst"]), plan.n_slots, _dp(d["chunk_cap"]) if return_states and plan.n_capture else None,
-                                  _dp(initial_state), _dp(states) if plan.n_capture else None, _dp(out), _dp(workspace), workspace.numel(),
+                                  _sched_ref(plan), _dp(initial_state), _dp(states) if plan.n_capture else None, _dp(out), _dp(workspace), workspace.numel(),
                                   _stream_ptr(stream)))
     return (out, states) if return_states else out
 
@@ -761,7 +811,8 @@ def tree_gdn_bwd(q, k, v, g, beta, d_o, plan: GdnPlan, *, scale=None, initial_st
     dv_ = torch.empty_like(v)
     dg, dbeta = torch.empty_like(g), torch.empty_like(beta)
     d_init = torch.empty((hv, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None
-    need = int(_lib().tt_tree_gdn_bwd_workspace(n, plan.n_chunks, plan.n_slots, hk, hv))
+    need = int(_lib().tt_tree_gdn_bwd_workspace(n, plan.n_chunks, plan.n_slots, plan.n_segments if plan._schedule() is not None else 0,
+                                                 hk, hv))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     d = plan.device
@@ -769,7 +820,7 @@ def tree_gdn_bwd(q, k, v, g, beta, d_o, plan: GdnPlan, *, scale=None, initial_st
     _check(_lib().tt_tree_gdn_bwd(n, hk, hv, dk, dv, float(dk) ** -0.5 if scale is None else float(scale), _dp(q), _dp(k), _dp(v),
                                   _dp(g), _dp(beta), _dp(d_o), plan.n_chunks, _dp(d["chunk_tok0"]), _dp(d["chunk_len"]),
                                   _dp(d["chunk_src"]), _dp(d["chunk_dst"]), plan.n_slots, _dp(d["chunk_cap"]) if use_cap else None,
-                                  _dp(initial_state), _dp(d_state_out) if use_cap else None, _dp(dq), _dp(dk_), _dp(dv_), _dp(dg),
+                                  _sched_ref(plan), _dp(initial_state), _dp(d_state_out) if use_cap else None, _dp(dq), _dp(dk_), _dp(dv_), _dp(dg),
                                   _dp(dbeta), _dp(d_init), _dp(workspace), workspace.numel(), _stream_ptr(stream)))
     out = (dq, dk_, dv_, dg, dbeta)
     return out + (d_init,) if want_d_initial_state else out

@@ -359,6 +359,24 @@ extern "C" tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels,
   return conv_bwd_launch(k, c, cd, ws, stream, "tree_conv_bwd_static");
 }
 
+namespace {
+// Host-checkable part of a schedule: counts, the level table (a host array) and the presence of the device arrays.
+tt_status check_gdn_schedule(const tt_gdn_schedule* sc, int32_t n_chunks, bool backward) {
+  if (!sc) return TT_OK;
+  if (sc->n_segments < 0 || sc->n_levels < 0 || sc->n_segments > n_chunks || sc->n_levels > sc->n_segments)
+    return fail(TT_ERR_SHAPE, "schedule: %d segments in %d levels for %d chunks", sc->n_segments, sc->n_levels, n_chunks);
+  if ((n_chunks > 0) != (sc->n_segments > 0)) return fail(TT_ERR_SHAPE, "schedule: %d segments for %d chunks", sc->n_segments, n_chunks);
+  if (!sc->level_off || (sc->n_segments > 0 && (!sc->seg_chunk0 || !sc->seg_chunk1))) return fail(TT_ERR_NULL, "schedule: an array is NULL");
+  if (backward && !sc->slot_cons_off) return fail(TT_ERR_NULL, "schedule: the backward needs slot_cons_off / slot_cons");
+  if (sc->level_off[0] != 0 || sc->level_off[sc->n_levels] != sc->n_segments) return fail(TT_ERR_SHAPE, "schedule: level_off does not cover the segments");
+  for (int32_t l = 0; l < sc->n_levels; l++) {
+    const int32_t n = sc->level_off[l + 1] - sc->level_off[l];
+    if (n <= 0 || n > 65535) return fail(TT_ERR_SHAPE, "schedule: level %d has %d segments (1..65535)", l, n);
+  }
+  return TT_OK;
+}
+}  // namespace
+
 extern "C" size_t tt_tree_gdn_workspace(int32_t n_chunks, int32_t n_slots, int32_t hv) {
   tt::clear_error();
   if (n_chunks < 0 || n_slots < 0 || hv <= 0) return 0;
@@ -369,8 +387,8 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
                                      const void* q, const void* k, const void* v, const float* g, const float* beta,
                                      int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
                                      const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
-                                     const int32_t* chunk_cap, const float* initial_state, float* state_out, void* o,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+                                     const int32_t* chunk_cap, const tt_gdn_schedule* schedule, const float* initial_state,
+                                     float* state_out, void* o, void* workspace, size_t workspace_bytes, void* stream) {
   tt::clear_error();
   if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
   if (dk != 128 || dv != 128) return fail(TT_ERR_UNSUPPORTED, "dk=%d, dv=%d: only 128 x 128 states are built", dk, dv);
@@ -381,6 +399,7 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
   if (n_chunks > 0 && (!q || !k || !v || !g || !beta || !o || !chunk_tok0 || !chunk_len || !chunk_src || !chunk_dst))
     return fail(TT_ERR_NULL, "a tensor or plan pointer is NULL");
   if ((chunk_cap != nullptr) != (state_out != nullptr)) return fail(TT_ERR_NULL, "chunk_cap and state_out must be given together");
+  if (tt_status sst = check_gdn_schedule(schedule, n_chunks, false)) return sst;
   const void* ptrs[] = {q, k, v, o, initial_state, state_out};
   for (const void* p : ptrs)
     if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
@@ -388,23 +407,24 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
     return fail(TT_ERR_WORKSPACE, "gdn forward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
   return hip_result(tt::gdn_fwd(n_tokens, hk, hv, scale, q, k, v, g, beta, n_chunks, chunk_tok0, chunk_len, chunk_src, chunk_dst,
-                                n_slots, chunk_cap, initial_state, state_out, o, workspace, (hipStream_t)stream),
+                                n_slots, chunk_cap, schedule, initial_state, state_out, o, workspace, (hipStream_t)stream),
                     "tree_gdn_fwd");
 }
 
-extern "C" size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t hk, int32_t hv) {
+extern "C" size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments, int32_t hk,
+                                            int32_t hv) {
   tt::clear_error();
-  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || hk <= 0 || hv <= 0) return 0;
-  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, hk, hv);
+  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || n_segments < 0 || hk <= 0 || hv <= 0) return 0;
+  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, n_segments, hk, hv);
 }
 
 extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
                                      const void* q, const void* k, const void* v, const float* g, const float* beta,
                                      const void* d_o, int32_t n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len,
                                      const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
-                                     const int32_t* chunk_cap, const float* initial_state, const float* d_state_out,
-                                     void* dq, void* dk_out, void* dv_out, float* dg, float* dbeta, float* d_initial_state,
-                                     void* workspace, size_t workspace_bytes, void* stream) {
+                                     const int32_t* chunk_cap, const tt_gdn_schedule* schedule, const float* initial_state,
+                                     const float* d_state_out, void* dq, void* dk_out, void* dv_out, float* dg, float* dbeta,
+                                     float* d_initial_state, void* workspace, size_t workspace_bytes, void* stream) {
   tt::clear_error();
   if (n_tokens < 0 || n_tokens >= INT32_MAX) return fail(TT_ERR_SHAPE, "n_tokens=%lld out of range", (long long)n_tokens);
   if (dk != 128 || dv != 128) return fail(TT_ERR_UNSUPPORTED, "dk=%d, dv=%d: only 128 x 128 states are built", dk, dv);
@@ -416,6 +436,7 @@ extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, i
                        !chunk_src || !chunk_dst))
     return fail(TT_ERR_NULL, "a tensor or plan pointer is NULL");
   if (d_state_out && !chunk_cap) return fail(TT_ERR_NULL, "d_state_out needs chunk_cap");
+  if (tt_status sst = check_gdn_schedule(schedule, n_chunks, true)) return sst;
   const void* ptrs[] = {q, k, v, d_o, dq, dk_out, dv_out, initial_state, d_state_out, d_initial_state};
   for (const void* p : ptrs)
     if (!tt::aligned16(p)) return fail(TT_ERR_ALIGN, "device pointer %p is not 16-byte aligned", p);
@@ -426,13 +447,14 @@ extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, i
       for (const void* i : ins)
         if (o && o == i) return fail(TT_ERR_SHAPE, "an output aliases an input");
   }
-  const size_t need = tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, hk, hv);
+  const size_t need = tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, schedule ? schedule->n_segments : 0, hk, hv);
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
     return fail(TT_ERR_WORKSPACE, "gdn backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
   tt::GdnBwdArgs a{};
   a.n_tokens = n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.n_slots = n_slots; a.scale = scale;
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.g = g; a.beta = beta;
   a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len; a.chunk_src = chunk_src; a.chunk_dst = chunk_dst; a.chunk_cap = chunk_cap;
+  a.sched = schedule;
   a.initial_state = initial_state; a.d_state_out = d_state_out;
   a.dq = dq; a.dk = dk_out; a.dv = dv_out; a.dg = dg; a.dbeta = dbeta; a.d_initial_state = d_initial_state;
   a.workspace = workspace;

@@ -43,6 +43,8 @@ struct GdnArgs {
   const float *g, *beta;             // [N][hv]
   const int32_t *chunk_tok0, *chunk_len, *chunk_src, *chunk_dst;
   const int32_t* chunk_cap;          // nullptr, or per chunk: -1 / index into state_out
+  const int32_t *seg_chunk0, *seg_chunk1;   // nullptr (one segment: all chunks), or the chunk ranges of the segments
+  int seg_base;                      // first segment of the level this launch walks (blockIdx.y counts from it)
   const float* initial_state;        // nullptr (zero) or [hv][128][128]: the state roots start from
   float* state_out;                  // [n_capture][hv][128][128]
   __bf16* o;                         // [N][hv][128]
@@ -59,7 +61,9 @@ struct GdnArgs {
   __bf16* vns;                       // per (head, chunk): Vn as B-operand fragments [4 col blocks][2 row blocks][2][64 lanes][8]
   __bf16* ds1t;                      // gradient of the leaving state, transposed like s0t
   __bf16* dvns;                      // dVn, fragments like vns
-  float* slot_grad;                  // [n_slots][hv][128][128] gradients of the saved states
+  float* slot_grad;                  // [n_slots][hv][128][128] gradients of the saved states (walk in sequence order)
+  float* seg_grad;                   // [n_segments][hv][128][128] gradient of the state a segment started from (scheduled walk)
+  const int32_t *slot_cons_off, *slot_cons;   // scheduled walk: the segments that start from every slot
   const float* d_state_out;          // nullptr or [n_capture][hv][128][128]
   float* d_initial_state;            // nullptr or [hv][128][128] (zeroed by the caller)
 };
@@ -355,7 +359,7 @@ __device__ __forceinline__ void load_meta(const GdnArgs& a, int chunk, int h, in
 // Vn (as the B-operand fragments) of every chunk are saved instead.
 template <bool TRAIN>
 __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
-                                          int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s) {
+                                          int c_end, int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s) {
   const int tok0 = meta.tok0, len = meta.len, src = meta.src, dst = meta.dst, cap = meta.cap;
   const float glast = meta.glast;
 
@@ -376,8 +380,8 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   dma_wait_all();                     // this wave's share of the chunk's operands has landed ...
   __syncthreads();                    // ... and so has everybody else's; every wave has also left the previous step,
                                       // so the other image, st and vx may be overwritten
-  if (chunk + 1 < a.n_chunks) issue_chunk<TRAIN>(a, chunk + 1, h, dvb, im_next, w, lane);
-  load_meta(a, min(chunk + 1, a.n_chunks - 1), h, z, meta);
+  if (chunk + 1 < c_end) issue_chunk<TRAIN>(a, chunk + 1, h, dvb, im_next, w, lane);
+  load_meta(a, min(chunk + 1, c_end - 1), h, z, meta);
   [[maybe_unused]] const size_t op = op_index(a, chunk, h);
 
   // Waves 0 and 1 compute one 32-row block of Vn = U - W S0 each; waves 2 and 3 meanwhile compute their
@@ -509,12 +513,17 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
 
   int z = 0;
   asm volatile("" : "+v"(z));
+  // this workgroup's segment of the chunk program (blockIdx.y-th segment of the level being walked); the first
+  // chunk of a segment never continues a previous chunk, so the state starts from its own source
+  const int seg = a.seg_base + blockIdx.y;
+  const int c_begin = a.seg_chunk0 ? a.seg_chunk0[seg] : 0;
+  const int c_end = a.seg_chunk1 ? a.seg_chunk1[seg] : a.n_chunks;
   ChunkMeta meta;
-  issue_chunk<TRAIN>(a, 0, h, dvb, sm.img[0], w, lane);
-  load_meta(a, 0, h, z, meta);
-  for (int chunk = 0; chunk < a.n_chunks; chunk += 2) {
-    scan_step<TRAIN>(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s);
-    if (chunk + 1 < a.n_chunks) scan_step<TRAIN>(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, h, dvb, lane, z, w, c, hf, s);
+  issue_chunk<TRAIN>(a, c_begin, h, dvb, sm.img[0], w, lane);
+  load_meta(a, c_begin, h, z, meta);
+  for (int chunk = c_begin; chunk < c_end; chunk += 2) {
+    scan_step<TRAIN>(a, sm, sm.img[0], sm.img[1], meta, chunk, c_end, h, dvb, lane, z, w, c, hf, s);
+    if (chunk + 1 < c_end) scan_step<TRAIN>(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, c_end, h, dvb, lane, z, w, c, hf, s);
   }
 }
 
@@ -540,7 +549,8 @@ __device__ __forceinline__ void issue_rev_chunk(const GdnArgs& a, int chunk, int
 // `later_src`: the source of the chunk that follows in DFS order (handled one step earlier); -2 means that chunk
 // continued from this one on chip, so `s` holds the gradient of this chunk's leaving state.
 __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
-                                           int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s, int& later_src) {
+                                           int c_begin, int seg, int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s,
+                                           int& later_src) {
   const int src = meta.src, dst = meta.dst, cap = meta.cap;
   const float glast = meta.glast;
   const size_t op = op_index(a, chunk, h);
@@ -548,14 +558,26 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
   if (later_src != -2) s = zero16();
   later_src = src;
   if (dst >= 0) {
-    float* sp = a.slot_grad + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+    if (a.seg_chunk0) {
+      // scheduled walk: every segment that started from this slot (all of later levels, hence done) has stored
+      // the gradient of its entering state; they are added in the order of the slot's reader list
+      const int k0 = a.slot_cons_off[dst + z], k1 = a.slot_cons_off[dst + 1 + z];
+      for (int kk = k0; kk < k1; kk++) {
+        const float* sp = a.seg_grad + ((size_t)a.slot_cons[kk + z] * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      float* e = sp + (size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD;
-      s[r] += *e;
-      *e = 0.f;                        // the slot is reused by an earlier node
+        for (int r = 0; r < 16; r++) s[r] += sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD];
+        pin(s);
+      }
+    } else {
+      float* sp = a.slot_grad + ((size_t)dst * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        float* e = sp + (size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD;
+        s[r] += *e;
+        *e = 0.f;                        // the slot is reused by an earlier node
+      }
+      pin(s);
     }
-    pin(s);
   }
   if (cap >= 0) {
     const float* sp = a.d_state_out + ((size_t)cap * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
@@ -569,8 +591,8 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
     *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
   dma_wait_all();
   __syncthreads();
-  if (chunk > 0) issue_rev_chunk(a, chunk - 1, h, dvb, im_next, w, lane);
-  load_meta(a, max(chunk - 1, 0), h, z, meta);
+  if (chunk > c_begin) issue_rev_chunk(a, chunk - 1, h, dvb, im_next, w, lane);
+  load_meta(a, max(chunk - 1, c_begin), h, z, meta);
 
   const int half = w & 1;
   bf16x8 ofrag[GC / 16];              // B operand: column c of dO, k = tokens in plain order
@@ -634,10 +656,18 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
 #pragma unroll
   for (int js = 0; js < GC / 16; js++) s = mfma32(qfrag[js], ofrag[js], s);
   if (src >= 0 || (src == -1 && a.d_initial_state)) {
-    float* sp = (src >= 0 ? a.slot_grad + ((size_t)src * a.hv + h) * (GD * GD) : a.d_initial_state + (size_t)h * (GD * GD)) +
-                dvb * G_DVB + c;
+    if (a.seg_chunk0) {
+      // scheduled walk: this is the first chunk of segment `seg`; its entering-state gradient is stored (not
+      // added) in the segment's own array -- the slot's saver, or the sum over the roots, picks it up later
+      float* sp = a.seg_grad + ((size_t)seg * a.hv + h) * (GD * GD) + dvb * G_DVB + c;
 #pragma unroll
-    for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] += s[r];
+      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] = s[r];
+    } else {
+      float* sp = (src >= 0 ? a.slot_grad + ((size_t)src * a.hv + h) * (GD * GD) : a.d_initial_state + (size_t)h * (GD * GD)) +
+                  dvb * G_DVB + c;
+#pragma unroll
+      for (int r = 0; r < 16; r++) sp[(size_t)(32 * w + (r >> 2) * 8 + hf * 4 + (r & 3)) * GD] += s[r];
+    }
   }
 }
 
@@ -656,12 +686,27 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
   asm volatile("" : "+v"(z));
   ChunkMeta meta;
   int later_src = -1;
-  const int last = a.n_chunks - 1;
+  // this workgroup's segment, walked from its last chunk to its first (nothing continues from a segment's last
+  // chunk on chip, so the state gradient starts from zero)
+  const int seg = a.seg_base + blockIdx.y;
+  const int c_begin = a.seg_chunk0 ? a.seg_chunk0[seg] : 0;
+  const int last = (a.seg_chunk1 ? a.seg_chunk1[seg] : a.n_chunks) - 1;
   issue_rev_chunk(a, last, h, dvb, sm.img[0], w, lane);
   load_meta(a, last, h, z, meta);
-  for (int chunk = last; chunk >= 0; chunk -= 2) {
-    rscan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, h, dvb, lane, z, w, c, hf, s, later_src);
-    if (chunk > 0) rscan_step(a, sm, sm.img[1], sm.img[0], meta, chunk - 1, h, dvb, lane, z, w, c, hf, s, later_src);
+  for (int chunk = last; chunk >= c_begin; chunk -= 2) {
+    rscan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, c_begin, seg, h, dvb, lane, z, w, c, hf, s, later_src);
+    if (chunk > c_begin) rscan_step(a, sm, sm.img[1], sm.img[0], meta, chunk - 1, c_begin, seg, h, dvb, lane, z, w, c, hf, s, later_src);
+  }
+}
+
+// d_initial_state = sum over the root segments (level 0, in order) of the gradients they stored
+__global__ __launch_bounds__(G_THREADS) void gdn_root_grad_kernel(const float* __restrict__ seg_grad, int n_roots, int hv,
+                                                                  float* __restrict__ d_initial_state) {
+  const size_t n = (size_t)hv * GD * GD;
+  for (size_t e = (size_t)blockIdx.x * G_THREADS + threadIdx.x; e < n; e += (size_t)gridDim.x * G_THREADS) {
+    float acc = 0.f;
+    for (int r = 0; r < n_roots; r++) acc += seg_grad[(size_t)r * n + e];
+    d_initial_state[e] = acc;
   }
 }
 
@@ -674,10 +719,29 @@ size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
   return align256(per * REC_ELEMS * 2) + align256(per * 4) + align256((size_t)n_slots * hv * GD * GD * 4) + 256;
 }
 
+// Walks the chunk program forward: one launch for everything without a schedule, else one launch per dependency
+// level with the level's segments side by side (blockIdx.y).
+template <bool TRAIN>
+static hipError_t launch_scan(GdnArgs& a, const tt_gdn_schedule* sched, hipStream_t st) {
+  const unsigned gx = (unsigned)((GD / G_DVB) * a.hv);
+  if (!sched) {
+    a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
+    gdn_scan_kernel<TRAIN><<<dim3(gx, 1), G_THREADS, 0, st>>>(a);
+    return hipGetLastError();
+  }
+  a.seg_chunk0 = sched->seg_chunk0; a.seg_chunk1 = sched->seg_chunk1;
+  for (int l = 0; l < sched->n_levels; l++) {
+    a.seg_base = sched->level_off[l];
+    gdn_scan_kernel<TRAIN><<<dim3(gx, (unsigned)(sched->level_off[l + 1] - sched->level_off[l])), G_THREADS, 0, st>>>(a);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
                    const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
-                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const float* initial_state, float* state_out,
-                   void* o, void* workspace, hipStream_t st) {
+                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const tt_gdn_schedule* sched,
+                   const float* initial_state, float* state_out, void* o, void* workspace, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   GdnArgs a{};
   a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
@@ -695,11 +759,8 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
     gdn_prepare_kernel<false><<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  {
-    KernelTimer t(TT_KERNEL_GDN_SCAN, st);
-    gdn_scan_kernel<false><<<dim3((GD / G_DVB) * hv), G_THREADS, 0, st>>>(a);
-  }
-  return hipGetLastError();
+  KernelTimer t(TT_KERNEL_GDN_SCAN, st);
+  return launch_scan<false>(a, sched, st);
 }
 
 hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st) {
@@ -720,13 +781,26 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {
     KernelTimer t(TT_KERNEL_GDN_BWD_FSCAN, st);         // chunk_cap stays null: nothing is captured here
-    gdn_scan_kernel<true><<<dim3((GD / G_DVB) * b.hv), G_THREADS, 0, st>>>(a);
+    if (hipError_t e = launch_scan<true>(a, b.sched, st); e != hipSuccess) return e;
   }
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   a.chunk_cap = b.d_state_out ? b.chunk_cap : nullptr;
   {
     KernelTimer t(TT_KERNEL_GDN_BWD_RSCAN, st);
-    gdn_rscan_kernel<<<dim3((GD / G_DVB) * b.hv), G_THREADS, 0, st>>>(a);
+    const unsigned gx = (unsigned)((GD / G_DVB) * b.hv);
+    if (!b.sched) {
+      a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
+      gdn_rscan_kernel<<<dim3(gx, 1), G_THREADS, 0, st>>>(a);
+    } else {
+      // last level first: a level's segments only need the gradients stored by later levels
+      a.seg_grad = sv.seg_grad; a.slot_cons_off = b.sched->slot_cons_off; a.slot_cons = b.sched->slot_cons;
+      for (int l = b.sched->n_levels - 1; l >= 0; l--) {
+        a.seg_base = b.sched->level_off[l];
+        gdn_rscan_kernel<<<dim3(gx, (unsigned)(b.sched->level_off[l + 1] - b.sched->level_off[l])), G_THREADS, 0, st>>>(a);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+      }
+      if (b.d_initial_state && b.sched->n_levels > 0)
+        gdn_root_grad_kernel<<<256, G_THREADS, 0, st>>>(sv.seg_grad, b.sched->level_off[1], b.hv, b.d_initial_state);
+    }
   }
   return hipGetLastError();
 }

@@ -624,7 +624,7 @@ __global__ __launch_bounds__(BT) void gdn_bwd_fill_zero_kernel(float4* p, size_t
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 // carves the workspace; returns the total size (with p == nullptr: only the size)
-size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs* w) {
+size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hv, BwdWs* w) {
   const size_t per = (size_t)n_chunks * hv;
   size_t off = 0;
   auto take = [&](size_t bytes) {
@@ -645,6 +645,7 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs
   t.sv.dvns = take(per * GC * GD * 2);
   t.sv.slots = (float*)take((size_t)n_slots * hv * GD * GD * 4);
   t.sv.slot_grad = (float*)take((size_t)n_slots * hv * GD * GD * 4);
+  t.sv.seg_grad = (float*)take((size_t)n_segments * hv * GD * GD * 4);
   t.x = (__bf16*)take(per * GC * 2 * GD * 2);
   t.dqh = (float*)take((size_t)n_tokens * hv * GD * 4);
   t.dkh = (float*)take((size_t)n_tokens * hv * GD * 4);
@@ -654,23 +655,27 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int hv, BwdWs
 
 }  // namespace
 
-size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int hk, int hv) {
+size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv) {
   (void)hk;
-  return carve(nullptr, n_tokens, n_chunks, n_slots, hv, nullptr);
+  return carve(nullptr, n_tokens, n_chunks, n_slots, n_segments, hv, nullptr);
 }
 
 hipError_t gdn_bwd(const GdnBwdArgs& b, hipStream_t st) {
   if (b.n_chunks == 0 || b.n_tokens == 0) return hipSuccess;
   KArgs a{};
   a.b = b;
-  carve((char*)b.workspace, b.n_tokens, b.n_chunks, b.n_slots, b.hv, &a.w);
+  carve((char*)b.workspace, b.n_tokens, b.n_chunks, b.n_slots, b.sched ? b.sched->n_segments : 0, b.hv, &a.w);
   auto zero = [&](float* p, size_t floats) {
     if (floats == 0) return;
     const size_t n4 = floats / 4;
     gdn_bwd_fill_zero_kernel<<<dim3((unsigned)std::min<size_t>((n4 + BT - 1) / BT, 4096)), BT, 0, st>>>((float4*)p, n4);
   };
-  zero(a.w.sv.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
-  if (b.d_initial_state) zero(b.d_initial_state, (size_t)b.hv * GD * GD);
+  // walking all chunks in sequence order, readers add into the slot gradients and into d_initial_state; with a
+  // schedule every segment stores its own gradient and nothing has to start from zero
+  if (!b.sched) {
+    zero(a.w.sv.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
+    if (b.d_initial_state) zero(b.d_initial_state, (size_t)b.hv * GD * GD);
+  }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   if (hipError_t e = gdn_bwd_prepare_and_walks(b, a.w.ops, a.w.sv, st); e != hipSuccess) return e;
   {

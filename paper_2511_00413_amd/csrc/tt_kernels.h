@@ -77,10 +77,11 @@ hipError_t conv_bwd(int64_t n_tokens, int channels, int kernel_size, bool bf16, 
 size_t conv_bwd_workspace(int64_t n_tokens, int channels, int kernel_size, bool bf16);
 
 // gated delta rule with tree state routing, forward (tt_gdn.hip); dk = dv = 128, bf16
+// `sched` (nullable): the segments of the chunk program by dependency level; see tt_gdn_schedule
 hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q, const void* k, const void* v, const float* g,
                    const float* beta, int n_chunks, const int32_t* chunk_tok0, const int32_t* chunk_len, const int32_t* chunk_src,
-                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const float* initial_state, float* state_out,
-                   void* o, void* workspace, hipStream_t st);
+                   const int32_t* chunk_dst, int n_slots, const int32_t* chunk_cap, const tt_gdn_schedule* sched,
+                   const float* initial_state, float* state_out, void* o, void* workspace, hipStream_t st);
 size_t gdn_workspace(int n_chunks, int n_slots, int hv);
 
 // Backward of the gated delta rule.  Every per-chunk array is indexed by (head * n_chunks + chunk).
@@ -104,7 +105,8 @@ struct GdnBwdSaved {
   void* vns;         // Vn  [64][128] bf16 in matrix-instruction fragment order (gdn_frag_index)
   void* dvns;        // dVn, same order
   float* slots;      // [n_slots][hv][128][128] saved node-end states
-  float* slot_grad;  // their gradients (zeroed by the caller)
+  float* slot_grad;  // their gradients (zeroed by the caller); walk in sequence order only
+  float* seg_grad;   // [n_segments][hv][128][128] gradient of the state every segment starts from; scheduled walk only
 };
 // position of element (token i, value column col) inside a chunk's fragment-ordered [64][128] array
 __host__ __device__ inline int gdn_frag_index(int i, int col) {
@@ -121,6 +123,7 @@ struct GdnBwdArgs {
   const void *q, *k, *v, *d_o;       // bf16
   const float *g, *beta;
   const int32_t *chunk_tok0, *chunk_len, *chunk_src, *chunk_dst, *chunk_cap;
+  const tt_gdn_schedule* sched;      // nullptr: all chunks in one sequence
   const float* initial_state;        // nullptr or [hv][128][128]
   const float* d_state_out;          // nullptr or [n_capture][hv][128][128]: upstream gradient of the captured states
   void *dq, *dk, *dv;                // bf16
@@ -131,6 +134,6 @@ struct GdnBwdArgs {
 // prepare kernel (backward form) + forward walk + reverse walk (tt_gdn.hip)
 hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st);
 hipError_t gdn_bwd(const GdnBwdArgs& a, hipStream_t st);
-size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int hk, int hv);
+size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv);
 
 }  // namespace tt

@@ -3,6 +3,7 @@
 // per-key visibility bound with its tile summaries (Section "Attention Mask", Appendix
 // "Ancestor-Aware Attention Bias").  O(nodes + tokens), no recursion (trees can be deep chains).
 #include <climits>
+#include <algorithm>
 #include <vector>
 #include "tt_internal.h"
 
@@ -357,6 +358,99 @@ tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_le
 }
 
 }  // namespace
+
+namespace {
+
+// Segments of a chunk program: maximal runs of chunks whose state stays on chip (every chunk but the first has
+// src == -2).  A segment depends only on the segment that saved the slot its first chunk loads, so segments form a
+// forest; level 0 = segments that start from the initial state, level l + 1 = segments whose slot is saved by a
+// segment of level l.  Segments of one level are independent of each other.
+struct GdnSchedule {
+  std::vector<int32_t> c0, c1, level_off;        // segments in level order (stable: chunk order inside a level)
+  std::vector<int32_t> cons_off, cons;           // per slot: the segments (positions in c0 / c1) that start from it
+};
+
+tt_status gdn_schedule(int32_t n_chunks, const int32_t* src, const int32_t* dst, int32_t n_slots, GdnSchedule& sc) {
+  if (n_chunks < 0 || n_slots < 0) return tt::fail(TT_ERR_SHAPE, "n_chunks=%d, n_slots=%d", n_chunks, n_slots);
+  if (n_chunks > 0 && (!src || !dst)) return tt::fail(TT_ERR_NULL, "chunk_src / chunk_dst is NULL");
+  std::vector<int32_t> first, last, level, slot_seg(n_slots, -1), seg_slot;
+  for (int32_t c = 0; c < n_chunks; c++) {
+    if (src[c] < -2 || src[c] >= n_slots || dst[c] < -1 || dst[c] >= n_slots)
+      return tt::fail(TT_ERR_TREE, "chunk %d: src=%d / dst=%d out of range", c, src[c], dst[c]);
+    if (c == 0 && src[c] == -2) return tt::fail(TT_ERR_TREE, "the first chunk cannot continue a previous one");
+    if (src[c] != -2) {
+      int32_t lv = 0;
+      if (src[c] >= 0) {
+        if (slot_seg[src[c]] < 0) return tt::fail(TT_ERR_TREE, "chunk %d starts from slot %d before any chunk saved it", c, src[c]);
+        lv = level[slot_seg[src[c]]] + 1;
+      }
+      first.push_back(c); last.push_back(c + 1); level.push_back(lv); seg_slot.push_back(src[c]);
+    } else {
+      last.back() = c + 1;
+    }
+    if (dst[c] >= 0) {
+      if (slot_seg[dst[c]] >= 0) return tt::fail(TT_ERR_TREE, "slot %d is saved twice", dst[c]);
+      slot_seg[dst[c]] = (int32_t)first.size() - 1;
+    }
+  }
+  const int32_t n_seg = (int32_t)first.size();
+  int32_t n_levels = 0;
+  for (int32_t l : level) n_levels = l + 1 > n_levels ? l + 1 : n_levels;
+  sc.level_off.assign(n_levels + 1, 0);
+  for (int32_t l : level) sc.level_off[l + 1]++;
+  for (int32_t l = 0; l < n_levels; l++) sc.level_off[l + 1] += sc.level_off[l];
+  // position of every segment: by level, inside a level the longest first (a level's segments are dealt to the
+  // compute units in this order, so the long ones start first and the short ones fill in), ties in chunk order
+  std::vector<int32_t> by_pos(n_seg), pos(n_seg);
+  for (int32_t s = 0; s < n_seg; s++) by_pos[s] = s;
+  std::stable_sort(by_pos.begin(), by_pos.end(), [&](int32_t x, int32_t y) {
+    if (level[x] != level[y]) return level[x] < level[y];
+    return last[x] - first[x] > last[y] - first[y];
+  });
+  sc.c0.resize(n_seg); sc.c1.resize(n_seg);
+  for (int32_t i = 0; i < n_seg; i++) {
+    pos[by_pos[i]] = i;
+    sc.c0[i] = first[by_pos[i]]; sc.c1[i] = last[by_pos[i]];
+  }
+  sc.cons_off.assign(n_slots + 1, 0);
+  for (int32_t s = 0; s < n_seg; s++)
+    if (seg_slot[s] >= 0) sc.cons_off[seg_slot[s] + 1]++;
+  for (int32_t k = 0; k < n_slots; k++) sc.cons_off[k + 1] += sc.cons_off[k];
+  sc.cons.resize(sc.cons_off[n_slots]);
+  std::vector<int32_t> cc(sc.cons_off.begin(), sc.cons_off.end() - 1);
+  for (int32_t s = 0; s < n_seg; s++)
+    if (seg_slot[s] >= 0) sc.cons[cc[seg_slot[s]]++] = pos[s];
+  return TT_OK;
+}
+
+}  // namespace
+
+extern "C" tt_status tt_tree_gdn_schedule_sizes(int32_t n_chunks, const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                                                int32_t* n_segments, int32_t* n_levels, int32_t* n_consumers) {
+  tt::clear_error();
+  if (!n_segments || !n_levels || !n_consumers) return tt::fail(TT_ERR_NULL, "an output is NULL");
+  GdnSchedule sc;
+  if (tt_status s = gdn_schedule(n_chunks, chunk_src, chunk_dst, n_slots, sc)) return s;
+  *n_segments = (int32_t)sc.c0.size();
+  *n_levels = (int32_t)sc.level_off.size() - 1;
+  *n_consumers = (int32_t)sc.cons.size();
+  return TT_OK;
+}
+
+extern "C" tt_status tt_tree_gdn_schedule(int32_t n_chunks, const int32_t* chunk_src, const int32_t* chunk_dst, int32_t n_slots,
+                                          int32_t* seg_chunk0, int32_t* seg_chunk1, int32_t* level_off, int32_t* slot_cons_off,
+                                          int32_t* slot_cons) {
+  tt::clear_error();
+  GdnSchedule sc;
+  if (tt_status s = gdn_schedule(n_chunks, chunk_src, chunk_dst, n_slots, sc)) return s;
+  if (!level_off || !slot_cons_off || (!sc.c0.empty() && (!seg_chunk0 || !seg_chunk1)) || (!sc.cons.empty() && !slot_cons))
+    return tt::fail(TT_ERR_NULL, "an output array is NULL");
+  for (size_t i = 0; i < sc.c0.size(); i++) { seg_chunk0[i] = sc.c0[i]; seg_chunk1[i] = sc.c1[i]; }
+  for (size_t i = 0; i < sc.level_off.size(); i++) level_off[i] = sc.level_off[i];
+  for (size_t i = 0; i < sc.cons_off.size(); i++) slot_cons_off[i] = sc.cons_off[i];
+  for (size_t i = 0; i < sc.cons.size(); i++) slot_cons[i] = sc.cons[i];
+  return TT_OK;
+}
 
 extern "C" tt_status tt_tree_gdn_plan_sizes(int32_t n_nodes, const int32_t* parent, const int32_t* seg_len, int32_t* n_chunks,
                                             int32_t* n_slots) {

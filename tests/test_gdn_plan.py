@@ -34,7 +34,60 @@ def _simulate(parent, seg):
             assert 0 <= dst < plan.n_slots
             slots[dst] = state
     assert covered == list(range(m["n_tokens"]))
+    _check_schedule(plan, m)
     return plan
+
+
+def _check_schedule(plan, m):
+    """tt_tree_gdn_schedule: segments = maximal runs that stay on chip, grouped into dependency levels.  Structure
+    first, then the chunk program is run again level by level with the segments of a level taken in REVERSE order
+    (any order inside a level must do): every chunk must still enter with its first token's predecessor state."""
+    src, dst = plan.chunk_src, plan.chunk_dst
+    c0, c1, lo = plan.seg_chunk0, plan.seg_chunk1, plan.level_off
+    assert len(c0) == len(c1) == plan.n_segments and lo[0] == 0 and lo[-1] == plan.n_segments
+    assert sorted((int(a), int(b)) for a, b in zip(c0, c1)) == [
+        (a, b) for a, b in zip(sorted(int(x) for x in c0), sorted(int(x) for x in c1))]      # ranges pair up in order
+    covered = sorted(c for a, b in zip(c0, c1) for c in range(a, b))
+    assert covered == list(range(plan.n_chunks)), "segments must cover every chunk once"
+    for a, b in zip(c0, c1):
+        assert b > a and src[a] != -2 and all(src[c] == -2 for c in range(a + 1, b))
+    level_of_seg = np.zeros(plan.n_segments, dtype=int)
+    for l in range(plan.n_levels):
+        assert lo[l + 1] > lo[l]
+        level_of_seg[lo[l]:lo[l + 1]] = l
+        order = [(-(int(c1[s_]) - int(c0[s_])), int(c0[s_])) for s_ in range(lo[l], lo[l + 1])]
+        assert order == sorted(order), "inside a level: longest segment first, ties in chunk order"
+    seg_of_chunk = {c: s for s, (a, b) in enumerate(zip(c0, c1)) for c in range(a, b)}
+    saver = {int(dst[c]): c for c in range(plan.n_chunks) if dst[c] >= 0}
+    for s_, a in enumerate(c0):
+        if src[a] == -1:
+            assert level_of_seg[s_] == 0
+        else:
+            assert level_of_seg[s_] == level_of_seg[seg_of_chunk[saver[int(src[a])]]] + 1
+    # consumers of every slot, in chunk order
+    for k in range(plan.n_slots):
+        cons = list(plan.slot_cons[plan.slot_cons_off[k]:plan.slot_cons_off[k + 1]])
+        want = [s_ for s_, a in sorted(enumerate(c0), key=lambda x: x[1]) if src[a] == k]
+        assert cons == want, (k, cons, want)
+    assert plan.slot_cons_off[-1] == len(plan.slot_cons) == sum(1 for a in c0 if src[a] >= 0)
+    # level-by-level execution, reversed inside a level
+    slots = {}
+    for l in range(plan.n_levels):
+        written = {}
+        for s_ in reversed(range(lo[l], lo[l + 1])):
+            state = None
+            for c in range(c0[s_], c1[s_]):
+                t0, n = int(plan.chunk_tok0[c]), int(plan.chunk_len[c])
+                if src[c] == -1:
+                    state = -1
+                elif src[c] >= 0:
+                    assert int(src[c]) in slots, "a slot is read in the level that writes it, or earlier"
+                    state = slots[int(src[c])]
+                assert state == m["tok_pred"][t0]
+                state = t0 + n - 1
+                if dst[c] >= 0:
+                    written[int(dst[c])] = state
+        slots.update(written)              # visible to later levels only
 
 
 @pytest.mark.parametrize("seed", range(25))

@@ -72,6 +72,28 @@ def test_routing_figure_and_reproducible():
     assert np.array_equal(o1, o2)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_level_schedule_equals_sequence_order(seed):
+    """Sibling subtrees walked side by side (one launch per dependency level of the chunk program) give bit-identical
+    outputs and captured states to one walk over all chunks in sequence order: every chunk does the same arithmetic
+    on the same entering state, only when and where it runs differs."""
+    t = W.random_tree(930 + seed, n_nodes=10 + 8 * seed, lo=1, hi=160, n_roots=1 + seed % 2, p_zero=0.15)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n = m["n_tokens"]
+    q, k, v, g, beta = (x.cuda() for x in _inputs(n, 2, 4, 20 + seed))
+    cap = [i for i in range(len(t.parent)) if t.seg_len[i] > 0][:: max(1, len(t.parent) // 3)][:3]
+    plan = T.tree_gdn_plan(t.parent, t.seg_len, capture_nodes=cap)
+    print(f"[case] gdn schedule n={n}: {plan.n_chunks} chunks in {plan.n_segments} segments, {plan.n_levels} levels", flush=True)
+    init = torch.randn((4, 128, 128), generator=torch.Generator().manual_seed(seed)).cuda() * 0.1
+    plan.to_device()
+    plan.parallel = True
+    o_par, st_par = T.tree_gdn_fwd(q, k, v, g, beta, plan, initial_state=init, return_states=True)
+    plan.parallel = False
+    o_seq, st_seq = T.tree_gdn_fwd(q, k, v, g, beta, plan, initial_state=init, return_states=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o_par, o_seq) and torch.equal(st_par, st_seq)
+
+
 def test_larger_tree_sampled_heads():
     t = W.random_tree(895, n_nodes=24, lo=50, hi=400)
     _check(t, 4, 8, 11, heads_checked=[0, 5])

@@ -48,6 +48,34 @@ def _check(tree, hk, hv, seed):
         assert e <= tol, (name, e)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_level_schedule_against_sequence_order(seed):
+    """The backward with the level schedule (forward walk and reverse walk one launch per dependency level, sibling
+    subtrees side by side; state gradients of a slot's readers stored per segment and added in list order) against
+    the walk over all chunks in sequence order.  dv and the per-chunk work are identical; where several readers'
+    gradients meet, the two walks add them in a different association, so the comparison is to fp32 rounding of the
+    sums (1e-5 relative on fp32 outputs, equal up to one bf16 ulp on a few bf16 elements), not bit for bit.  Also
+    checks run-to-run reproducibility of the scheduled walk and the gradient of the initial state."""
+    t = W.random_tree(940 + seed, n_nodes=9 + 7 * seed, lo=1, hi=150, n_roots=1 + seed % 2, p_zero=0.15)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n = m["n_tokens"]
+    q, k, v, g, beta, d_o = (x.cuda() for x in _inputs(n, 2, 4, 30 + seed))
+    plan = T.tree_gdn_plan(t.parent, t.seg_len).to_device()
+    init = torch.randn((4, 128, 128), generator=torch.Generator().manual_seed(seed)).cuda() * 0.1
+    print(f"[case] gdn bwd schedule n={n}: {plan.n_chunks} chunks in {plan.n_segments} segments, {plan.n_levels} levels", flush=True)
+    plan.parallel = True
+    par = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, initial_state=init, want_d_initial_state=True)
+    par2 = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, initial_state=init, want_d_initial_state=True)
+    plan.parallel = False
+    seq = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, initial_state=init, want_d_initial_state=True)
+    torch.cuda.synchronize()
+    for name, a, b, c in zip(("dq", "dk", "dv", "dg", "dbeta", "d_initial_state"), par, par2, seq):
+        assert torch.equal(a, b), f"{name}: the scheduled walk is not reproducible"
+        e = rel_l2(a.float().cpu().numpy(), c.float().cpu().numpy())
+        print(f"   {name}: scheduled vs sequence order rel-L2 {e:.2e}", flush=True)
+        assert e <= (2e-3 if a.dtype == torch.bfloat16 else 1e-4), (name, e)
+
+
 def test_chain_partial_chunks():
     """One sequence of 150 tokens: chunks of 64, 64, 22; then a 1-token sequence."""
     _check(W._mk([-1], [150], [1], "chain"), 1, 2, 0)

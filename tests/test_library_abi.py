@@ -102,17 +102,19 @@ def test_gdn_calls_validate_before_launch():
     n, hk, hv, nc, ns = 128, 2, 4, 2, 1
     plan = [fake] * 4                                        # chunk_tok0, chunk_len, chunk_src, chunk_dst
 
-    def fwd(*, dk=128, dv=128, hv_=hv, scale=0.1, q=fake, o=fake, cap=null, state_out=null, ws=fake, ws_bytes=1 << 40):
-        return lib.tt_tree_gdn_fwd(n, hk, hv_, dk, dv, scale, q, fake, fake, fake, fake, nc, *plan, ns, cap, null, state_out, o, ws,
-                                   ws_bytes, null)
+    def fwd(*, dk=128, dv=128, hv_=hv, scale=0.1, q=fake, o=fake, cap=null, state_out=null, ws=fake, ws_bytes=1 << 40, sched=null):
+        return lib.tt_tree_gdn_fwd(n, hk, hv_, dk, dv, scale, q, fake, fake, fake, fake, nc, *plan, ns, cap, sched, null, state_out, o,
+                                   ws, ws_bytes, null)
 
-    def bwd(*, dk=128, hv_=hv, scale=0.1, q=fake, d_o=fake, dq=ctypes.c_void_p(24576), cap=null, d_state_out=null, ws=fake, ws_bytes=1 << 40):
-        return lib.tt_tree_gdn_bwd(n, hk, hv_, dk, 128, scale, q, fake, fake, fake, fake, d_o, nc, *plan, ns, cap, null, d_state_out,
-                                   dq, ctypes.c_void_p(8192), ctypes.c_void_p(12288), ctypes.c_void_p(16384),
+    def bwd(*, dk=128, hv_=hv, scale=0.1, q=fake, d_o=fake, dq=ctypes.c_void_p(24576), cap=null, d_state_out=null, ws=fake,
+            ws_bytes=1 << 40, sched=null):
+        return lib.tt_tree_gdn_bwd(n, hk, hv_, dk, 128, scale, q, fake, fake, fake, fake, d_o, nc, *plan, ns, cap, sched, null,
+                                   d_state_out, dq, ctypes.c_void_p(8192), ctypes.c_void_p(12288), ctypes.c_void_p(16384),
                                    ctypes.c_void_p(20480), null, ws, ws_bytes, null)
 
     assert lib.tt_tree_gdn_workspace(nc, ns, hv) > 0
-    assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, hk, hv) > lib.tt_tree_gdn_workspace(nc, ns, hv)
+    assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, hk, hv) > lib.tt_tree_gdn_workspace(nc, ns, hv)
+    assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 3, hk, hv) == lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, hk, hv) + 3 * hv * 128 * 128 * 4
     assert fwd(dk=64) == -8 and bwd(dk=64) == -8             # only 128 x 128 states (TT_ERR_UNSUPPORTED)
     assert fwd(hv_=3) == -2 and bwd(hv_=3) == -2             # hv not a multiple of hk
     assert fwd(scale=0.0) == -2 and bwd(scale=float("nan")) == -2
@@ -122,4 +124,10 @@ def test_gdn_calls_validate_before_launch():
     assert fwd(q=ctypes.c_void_p(4100)) == -5 and bwd(q=ctypes.c_void_p(4100)) == -5
     assert fwd(ws=null) == -6 and fwd(ws_bytes=16) == -6 and bwd(ws=null) == -6 and bwd(ws_bytes=16) == -6
     assert bwd(dq=fake, q=fake) == -2                        # an output aliases an input
+    # a schedule whose host-side level table does not cover its segments, or with a missing device array
+    lo = (ctypes.c_int32 * 2)(0, 1)
+    bad = B._GdnSchedule(2, 1, ctypes.cast(lo, ctypes.c_void_p), fake, fake, fake, fake)
+    assert fwd(sched=ctypes.byref(bad)) == -2 and bwd(sched=ctypes.byref(bad)) == -2
+    missing = B._GdnSchedule(1, 1, ctypes.cast(lo, ctypes.c_void_p), null, fake, fake, fake)
+    assert fwd(sched=ctypes.byref(missing)) == -1
     assert T.last_error()
