@@ -39,7 +39,7 @@ struct KvSmem {
   // (lane l of wave w keeps fragment f at [w][f][8 l]): the 8 k-steps of V (dP = dO V^T), then
   // k-steps KV_KREG .. 7 of K
   __bf16 frag[KV_NW][KV_NFRAG][64 * 8];
-  int work;
+  int work, queue, exhausted;
 };
 // byte offsets between the LDS arrays, used as immediate offsets of the LDS reads
 constexpr int KV_STAGE_B = KV_BM * TILE_ROW * 2;        // one staged tile
@@ -89,9 +89,18 @@ constexpr int KV_SORT_BELOW = 16;        // items per workgroup below which the 
 constexpr int PLAN_THREADS = 1024;
 constexpr int KV_EPT = KV_BN / 64;       // summary entries per key tile, at most
 
+constexpr int KV_MAX_QUEUES = 64;
 struct KvPlanHeader {
   int n_work;        // work items = n_items * hkv
-  int counter;       // next work item to hand out
+  // Work queues.  With hkv <= KV_MAX_QUEUES there is one queue per kv head (entry w of queue q = item
+  // item_order[w] for kv head q) and a workgroup starts on the queue of its XCD: the workgroups of one XCD then
+  // work on neighbouring key tiles of one kv head, which stream the same Q / dO tiles at about the same time, so
+  // the XCD's L2 serves part of those reads (at a 131 K-token tree: 348 GB fetched per launch with one shared
+  // queue, 229 GB with one per head, the pass 5 % faster).  A workgroup whose queue is empty moves on to the next
+  // one.  Used when every workgroup gets many items (the plain hand-out order); with few items per workgroup (the
+  // longest-first order) one shared queue balances better and is what the planner sets up.
+  int n_queues, per_queue;
+  int counter[KV_MAX_QUEUES];   // next entry of every queue
   int chunk;         // steps per chunk
   int n_split_items; // items [0, n_split_items) write partial slots (slot index = item index)
   int n_tiles;       // key tiles formed
@@ -250,7 +259,7 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   //      Results do not depend on the order: every item has its own output rows or partial slot.
   //      With many items per workgroup the end effect is small and the plain order (key tiles in sequence order)
   //      measured 1-2 % faster, so the sort is applied only below KV_SORT_BELOW items per workgroup. ----
-  constexpr int NCLS = 64, PLAN_WAVES = PLAN_THREADS / 64;
+  constexpr int NCLS = 64, PLAN_WAVES = PLAN_THREADS / 64;      // NCLS = wavefront size (see the placement loop)
   __shared__ int cls_base[NCLS];
   __shared__ int wave_cnt[PLAN_WAVES][NCLS];
   const int n_items = n_split + n_whole;
@@ -258,7 +267,9 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
     for (int i = t; i < n_items; i += PLAN_THREADS) pl.item_order[i] = i;
     if (t == 0) {
       pl.hdr->n_work = (n_split + n_whole) * hkv;
-      pl.hdr->counter = 0;
+      pl.hdr->n_queues = hkv <= KV_MAX_QUEUES ? hkv : 1;
+      pl.hdr->per_queue = hkv <= KV_MAX_QUEUES ? n_split + n_whole : (n_split + n_whole) * hkv;
+      for (int q = 0; q < KV_MAX_QUEUES; q++) pl.hdr->counter[q] = 0;
       pl.hdr->chunk = chunk;
       pl.hdr->n_split_items = n_split;
       pl.hdr->n_tiles = n_tiles;
@@ -275,29 +286,29 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   if (t < NCLS) cls_base[t] = 0;
   __syncthreads();                       // (also publishes the item tables written above)
   // class sizes -> first position of every class
-  for (int i0 = 0; i0 < n_items; i0 += PLAN_THREADS) {
-    const int i = i0 + t;
-    const int c = i < n_items ? item_class(i) : -1;
-    for (int k = 0; k < NCLS; k++) {
-      const uint64_t m = __ballot(c == k);
-      if (lane == 0 && m) atomicAdd(&cls_base[k], __popcll(m));        // integer counts: order-independent
-    }
-  }
+  for (int i = t; i < n_items; i += PLAN_THREADS) atomicAdd(&cls_base[item_class(i)], 1);      // integer counts: order-independent
   __syncthreads();
   if (t == 0) {
     int run = 0;
     for (int c = 0; c < NCLS; c++) { const int n = cls_base[c]; cls_base[c] = run; run += n; }
   }
   __syncthreads();
-  // placement, 1024 items at a time in item order
+  // placement, 1024 items at a time in item order.  Inside a wavefront the rank of an item among the items of
+  // its class comes from one ballot per class that actually occurs in the wavefront (a few: neighbouring
+  // items are chunks of the same tile).
   for (int i0 = 0; i0 < n_items; i0 += PLAN_THREADS) {
     const int i = i0 + t;
     const int c = i < n_items ? item_class(i) : -1;
+    wave_cnt[wv][lane] = 0;                            // NCLS == wavefront size: one class count per lane
     int rank_in_wave = 0;
-    for (int k = 0; k < NCLS; k++) {
-      const uint64_t m = __ballot(c == k);
-      if (c == k) rank_in_wave = __popcll(m & ((1ull << lane) - 1ull));
-      if (lane == 0) wave_cnt[wv][k] = __popcll(m);
+    uint64_t todo = __ballot(c >= 0);
+    while (todo) {
+      const int leader = __builtin_ctzll(todo);
+      const int lc = __builtin_amdgcn_readlane(c, leader);
+      const uint64_t m = __ballot(c == lc);
+      if (c == lc) rank_in_wave = __popcll(m & ((1ull << lane) - 1ull));
+      if (lane == 0) wave_cnt[wv][lc] = __popcll(m);
+      todo &= ~m;
     }
     __syncthreads();
     if (c >= 0) {
@@ -315,7 +326,9 @@ kv_plan_kernel(KvPlan pl, const int32_t* __restrict__ kt_max, int n_q, int n_pre
   }
   if (t == 0) {
     pl.hdr->n_work = (n_split + n_whole) * hkv;
-    pl.hdr->counter = 0;
+    pl.hdr->n_queues = 1;                      // few items per workgroup: one shared queue balances best (measured)
+    pl.hdr->per_queue = (n_split + n_whole) * hkv;
+    for (int q = 0; q < KV_MAX_QUEUES; q++) pl.hdr->counter[q] = 0;
     pl.hdr->chunk = chunk;
     pl.hdr->n_split_items = n_split;
     pl.hdr->n_tiles = n_tiles;
@@ -333,7 +346,6 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
   const int G = a.hq / a.hkv;
   const int P = a.n_prefix, N = a.n_q;
   const float c_scale = a.scale * LOG2E_F;     // folded into K: S comes out of the MFMAs as a base-2 exponent
-  const int n_work = pl.hdr->n_work;
   const int chunk = pl.hdr->chunk;
 
   // LDS byte addresses of this lane's operand fragments in stage `buf` of the Q tile.  The dO tile,
@@ -348,14 +360,33 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
   int buf = 0;                                  // stage of the next step; carried across work items
   int stage_step = KV_STAGE_B, scalar_step = KV_SCALAR_STAGE_B;   // signed distance to the other stage
 
+  const int n_queues = pl.hdr->n_queues, per_queue = pl.hdr->per_queue;
+  int queue, exhausted = 0;                  // current queue; queues this workgroup has found empty
+  {
+    unsigned xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+    queue = (int)(xcc & 0xf) % n_queues;
+  }
   for (;;) {
-    if (threadIdx.x == 0) sm.work = atomicAdd(&pl.hdr->counter, 1);
+    if (threadIdx.x == 0) {
+      // next entry of the current queue; an empty queue is left for good (the counters only grow), and once all
+      // queues have been found empty the workgroup is done -- every wave reaches that point
+      int wk = -1, q = queue, ex = exhausted;
+      while (ex < n_queues) {
+        const int t = atomicAdd(&pl.hdr->counter[q], 1);
+        if (t < per_queue) { wk = t; break; }
+        ex++;
+        q = q + 1 == n_queues ? 0 : q + 1;
+      }
+      sm.work = wk; sm.queue = q; sm.exhausted = ex;
+    }
     __syncthreads();
     const int work = sm.work;
-    __syncthreads();                         // everyone has read the slot before it is rewritten
-    if (work >= n_work) break;               // the counter only grows: every wave gets here
-    const int kvh = work % a.hkv;            // neighbouring items differ in kv head (XCD locality)
-    const int item = pl.item_order[work / a.hkv];
+    queue = sm.queue; exhausted = sm.exhausted;
+    __syncthreads();                         // everyone has read the slots before they are rewritten
+    if (work < 0) break;
+    const int kvh = n_queues == a.hkv ? queue : work % a.hkv;
+    const int item = pl.item_order[n_queues == a.hkv ? work : work / a.hkv];
     const int tile = pl.item_tile[item];
     const int nq = pl.tile_nq[tile], qt_lo = pl.tile_qtlo[tile];
     const int s_lo = pl.item_chunk[item] * chunk;
