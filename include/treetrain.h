@@ -479,7 +479,9 @@ tt_status tt_tree_conv_bwd_static(int64_t n_tokens, int32_t channels, int32_t ke
  *     chunk_src [n_chunks]   -2 = continues the previous chunk's sequence (state stays on chip),
  *                            -1 = zero state, >= 0 = saved state slot
  *     chunk_dst [n_chunks]   -1, or the slot the chunk's leaving state is saved to (nodes that
- *                            have two or more token-bearing child branches)
+ *                            have two or more token-bearing child branches; EVERY such branch
+ *                            starts from the slot, the one that follows directly included, so
+ *                            that the branches are independent of each other)
  *     chunk_cap [n_chunks]   -1, or i when the chunk's leaving state is the end state of
  *                            capture_node[i]: the state a child partition starts from (Appendix
  *                            "SSM State Gateway": state extraction / injection).  A zero-length

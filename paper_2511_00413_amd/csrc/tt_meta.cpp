@@ -330,8 +330,9 @@ tt_status gdn_plan(int32_t n_nodes, const int32_t* parent, const int32_t* seg_le
       if (off == 0) {
         const int32_t e = eff[i];
         if (e < 0) src = -1;
-        else if (last_chunk[e] == (int32_t)pl.tok0.size() - 1) src = -2;      // directly after its parent's last chunk
-        else src = slot[e];
+        else if (slot[e] < 0) src = -2;      // the only continuation: directly after its parent's last chunk
+        else src = slot[e];                  // every branch of a branch point starts from the saved state, the first one
+                                             // too: the branches are then independent of each other (tt_tree_gdn_schedule)
       }
       pl.tok0.push_back((int32_t)(tok + off));
       pl.len.push_back(n);

@@ -100,9 +100,12 @@ def test_shapes():
     plan = _simulate([-1, 0, 1], [64, 65, 1])                 # a chain: nothing is saved, everything continues
     assert plan.n_slots == 0 and plan.chunk_src.tolist() == [-1, -2, -2, -2] and plan.chunk_len.tolist() == [64, 64, 1, 1]
     plan = _simulate([-1, 0, 0, 0], [10, 5, 0, 7])           # two token-bearing children + an empty one
-    assert plan.n_slots == 1 and plan.chunk_src.tolist() == [-1, -2, 0] and plan.chunk_dst.tolist() == [0, -1, -1]
+    assert plan.n_slots == 1 and plan.chunk_src.tolist() == [-1, 0, 0] and plan.chunk_dst.tolist() == [0, -1, -1]
+    assert plan.n_segments == 3 and plan.level_off.tolist() == [0, 1, 3]     # both branches in one level
     plan = _simulate([-1, 0, 1, 1], [10, 0, 3, 4])           # children hang below a zero-length node
-    assert plan.chunk_src.tolist() == [-1, -2, 0]
+    assert plan.chunk_src.tolist() == [-1, 0, 0]
+    plan = _simulate([-1, 0, 0], [10, 5, 0])                 # one token-bearing child: it continues on chip
+    assert plan.n_slots == 0 and plan.chunk_src.tolist() == [-1, -2]
     for cfg in (2, 3, 4):
         t = W.tree_config(cfg)
         _simulate(list(t.parent), list(t.seg_len))
