@@ -314,17 +314,19 @@ def leg_partitioned(c):
         op = torch.empty_like(q); lsep = torch.empty_like(lse)
         dqp = torch.empty_like(q); dkp_ = torch.empty_like(k); dvp_ = torch.empty_like(v)
         n_it = max(3, min(args.steps, 10))
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_it + 1)]
         def part_step():
             T.tree_attn_partitioned_fwd(q, k, v, plan, o=op, lse=lsep, workspace=wsp)
             T.tree_attn_partitioned_bwd(q, k, v, plan, op, do, lsep, dq=dqp, dk=dkp_, dv=dvp_, workspace=wsp)
-        for it in range(2 + n_it):
-            if it == 2:
-                e0.record()
+        for it in range(2):
             part_step()
-        e1.record()
+        evs[0].record()
+        for it in range(n_it):
+            part_step()
+            evs[it + 1].record()
         torch.cuda.synchronize()
-        ms_part = e0.elapsed_time(e1) / n_it
+        per_step = [evs[i].elapsed_time(evs[i + 1]) for i in range(n_it)]
+        ms_part = evs[0].elapsed_time(evs[n_it]) / n_it
         T.kernel_timing_enable(True)               # a second pass for the per-kernel split
         for it in range(n_it):
             part_step()
@@ -347,6 +349,7 @@ def leg_partitioned(c):
         part = {"capacity": cap, "n_parts": plan.n_parts, "max_prefix": plan.max_prefix,
                 "in_place_own": int((plan.part_own_start >= 0).sum()), "in_place_prefix": int((plan.part_prefix_start >= 0).sum()),
                 "sum_prefix": int(plan.part_prefix_off[-1]), "ms_fwd_bwd": round(ms_part, 4),
+                "ms_fwd_bwd_per_step": [round(x, 3) for x in per_step],
                 "ms_whole_fwd_bwd": round(ms_fwd + ms_bwd, 4),
                 "ratio_to_whole": round(ms_part / (ms_fwd + ms_bwd), 3),
                 "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
