@@ -15,9 +15,10 @@
 //       Q K^T on MFMA, the unit-lower-triangular solve by forward substitution with one lane per
 //       column of [V | K] (no synchronisation inside the solve), operands written in the layouts
 //       the second kernel's MFMA fragments want;
-//   gdn_scan_kernel  (32 value columns, value head): walks the chunks in DFS order with the state
+//   gdn_scan_kernel  (64 value columns, value head): walks the chunks in DFS order with the state
 //       in MFMA accumulators (the columns of S evolve independently, so a head is cut into four
-//       independent workgroups); state routing = where a chunk takes S0 from (registers when it
+//       independent blocks of 32 columns, four wavefronts each; two blocks form a workgroup and share
+//       the LDS copy of the chunk's operands); state routing = where a chunk takes S0 from (registers when it
 //       continues the previous chunk's sequence, a saved node-end state, or zero).
 // The backward pass (tt_gdn_bwd.hip) reuses both: the prepare kernel in a form that also writes the reverse walk's
 // operands, the scan in a form that saves every chunk's entering state and Vn instead of writing the output, and
@@ -34,7 +35,10 @@ constexpr int GC = TT_GDN_CHUNK;     // tokens per chunk (64)
 constexpr int GD = 128;              // head dim of keys and values
 constexpr int GROW = GD + 8;         // padded LDS row (elements) for [*][128] bf16 tiles
 constexpr int G_THREADS = 256;
-constexpr int G_DVB = 32;            // value columns per scan workgroup
+constexpr int G_DVB = 32;            // value columns per column block of the scan (one 32 x 32 accumulator tile per wave)
+constexpr int SCAN_NB = 2;           // column blocks per scan workgroup: 4 wavefronts each, sharing the chunk's operands in LDS
+constexpr int SCAN_NW = 4 * SCAN_NB; // wavefronts per scan workgroup (two per SIMD)
+constexpr int SCAN_THREADS = 64 * SCAN_NW;
 
 struct GdnArgs {
   int n_tokens, hk, hv, n_chunks;
@@ -298,15 +302,20 @@ struct ScanImage {
   __bf16 wn[GC * GD];           // -W, swizzled tile
   __bf16 qg[GC * GD];           // scale Q exp(gamma), swizzled tile
   __bf16 kd[GD * GC];           // (K decayed)^T, rows of 64
-  __bf16 ut[G_DVB * GC];        // U^T, this workgroup's value columns, rows of 64
+  __bf16 ut[SCAN_NB * G_DVB * GC];   // U^T, this workgroup's value columns (block after block), rows of 64
   __bf16 p[GC * GC];            // scale tril(Q K^T decay), rows of 64
 };
+// Per column block: st, vx.  The output tiles of waves 2 and 3 of a block, on their way to 16-byte stores, reuse
+// the current image's qg tile (OT_ELEMS elements per wave): qg is only read before the step's second barrier, the
+// tiles are written after it, and the next copy into that image is issued behind the next step's first barrier.
 struct ScanSmem {
   ScanImage img[2];
-  __bf16 st[G_DVB][GROW];       // S0^T
-  __bf16 ot[2][32][G_DVB + 8];  // output tiles of waves 2 and 3 on their way to 16-byte stores
-  bf16x8 vx[2][2][64];          // Vn as per-lane B-operand fragments, written by waves 0 and 1, read by all
+  __bf16 st[SCAN_NB][G_DVB][GROW];   // S0^T
+  bf16x8 vx[SCAN_NB][2][2][64];      // Vn as per-lane B-operand fragments, written by waves 0 and 1, read by the block
 };
+constexpr int OT_ROW = G_DVB + 8, OT_ELEMS = 32 * OT_ROW;
+static_assert(2 * SCAN_NB * OT_ELEMS <= GC * GD, "output tiles fit into the qg tile");
+static_assert(sizeof(ScanSmem) <= 160 * 1024, "LDS of one compute unit");
 
 // 4 consecutive elements e0 .. e0+3 (e0 a multiple of 4) of row r of a rows-of-64 array
 __device__ __forceinline__ bf16x4 row64_read4(const __bf16* arr, int r, int e0) {
@@ -319,24 +328,24 @@ __device__ __forceinline__ bf16x8 row64_perm_k(const __bf16* arr, int r, int bas
 }
 
 // Copies `rows` rows of 64 elements (contiguous in memory) into a rows-of-64 array; 8 rows per
-// instruction, instructions dealt round-robin to the 4 waves.
-__device__ __forceinline__ void dma_rows64(const __bf16* src, int rows, __bf16* dst, int w, int lane) {
+// instruction, instructions dealt round-robin to the workgroup's waves (w8 = 0 .. SCAN_NW - 1).
+__device__ __forceinline__ void dma_rows64(const __bf16* src, int rows, __bf16* dst, int w8, int lane) {
   const void* gb = uniform_ptr(src);
   const int rr = lane >> 3, pos = lane & 7;
-  for (int g = w; g < rows / 8; g += 4)
+  for (int g = w8; g < rows / 8; g += SCAN_NW)
     dma16(gb, (uint32_t)((8 * g + rr) * 128 + ((pos ^ rr) << 4)), lds_addr_uniform(dst + g * 8 * GC));
 }
 
-// Starts the copy of one chunk's operands into `im` (15 instructions per wave; TRAIN: without the output's
-// operands, 9).
+// Starts the copy of one chunk's operands into `im` (8 instructions per wave; TRAIN: without the output's
+// operands, 5).  dvb0: the workgroup's first column block; the U^T rows of its blocks are adjacent in the record.
 template <bool TRAIN>
-__device__ __forceinline__ void issue_chunk(const GdnArgs& a, int chunk, int h, int dvb, ScanImage& im, int w, int lane) {
+__device__ __forceinline__ void issue_chunk(const GdnArgs& a, int chunk, int h, int dvb0, ScanImage& im, int w8, int lane) {
   const __bf16* rec = a.rec + op_index(a, chunk, h) * REC_ELEMS;
-  dma_tile64<4>(rec + REC_WN, GD * 2, GC, im.wn, w, lane);
-  if constexpr (!TRAIN) dma_tile64<4>(rec + REC_QG, GD * 2, GC, im.qg, w, lane);
-  dma_rows64(rec + REC_KDT, GD, im.kd, w, lane);
-  dma_rows64(rec + REC_UT + (size_t)dvb * G_DVB * GC, G_DVB, im.ut, w, lane);
-  if constexpr (!TRAIN) dma_rows64(rec + REC_P, GC, im.p, w, lane);
+  dma_tile64<SCAN_NW>(rec + REC_WN, GD * 2, GC, im.wn, w8, lane);
+  if constexpr (!TRAIN) dma_tile64<SCAN_NW>(rec + REC_QG, GD * 2, GC, im.qg, w8, lane);
+  dma_rows64(rec + REC_KDT, GD, im.kd, w8, lane);
+  dma_rows64(rec + REC_UT + (size_t)dvb0 * G_DVB * GC, SCAN_NB * G_DVB, im.ut, w8, lane);
+  if constexpr (!TRAIN) dma_rows64(rec + REC_P, GC, im.p, w8, lane);
 }
 
 // The scalars of a chunk.  `z` is a per-lane zero the compiler cannot see through: they are loaded per
@@ -359,7 +368,8 @@ __device__ __forceinline__ void load_meta(const GdnArgs& a, int chunk, int h, in
 // Vn (as the B-operand fragments) of every chunk are saved instead.
 template <bool TRAIN>
 __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
-                                          int c_end, int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s) {
+                                          int c_end, int h, int dvb0, int blk, int lane, int z, int w8, int w, int c, int hf, f32x16& s) {
+  const int dvb = dvb0 + blk;                     // this wave's column block; w = its wave index inside the block
   const int tok0 = meta.tok0, len = meta.len, src = meta.src, dst = meta.dst, cap = meta.cap;
   const float glast = meta.glast;
 
@@ -376,11 +386,11 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   // S0 -> bf16, transposed into LDS
 #pragma unroll
   for (int r4 = 0; r4 < 4; r4++)
-    *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
+    *(bf16x4*)&sm.st[blk][c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
   dma_wait_all();                     // this wave's share of the chunk's operands has landed ...
   __syncthreads();                    // ... and so has everybody else's; every wave has also left the previous step,
                                       // so the other image, st and vx may be overwritten
-  if (chunk + 1 < c_end) issue_chunk<TRAIN>(a, chunk + 1, h, dvb, im_next, w, lane);
+  if (chunk + 1 < c_end) issue_chunk<TRAIN>(a, chunk + 1, h, dvb0, im_next, w8, lane);
   load_meta(a, min(chunk + 1, c_end - 1), h, z, meta);
   [[maybe_unused]] const size_t op = op_index(a, chunk, h);
 
@@ -399,7 +409,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
     const int abase = row_frag_base(lane);
 #pragma unroll
     for (int ks = 0; ks < GD / 16; ks++) {
-      sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+      sfrag[ks] = *(const bf16x8*)&sm.st[blk][c][ks * 16 + hf * 8];
       afrag[ks] = lds_row_frag(atile, abase, half, ks);
     }
   }
@@ -411,7 +421,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int piece = i * 128 + t128, row = piece >> 4, c8 = (piece & 15) * 8;
-        sdst[piece] = *(const u32x4n*)&sm.st[row][c8];
+        sdst[piece] = *(const u32x4n*)&sm.st[blk][row][c8];
       }
     }
   }
@@ -419,7 +429,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
   if (w < 2) {
 #pragma unroll
     for (int r4 = 0; r4 < 4; r4++) {
-      const bf16x4 u4 = row64_read4(im.ut, c, half * 32 + r4 * 8 + hf * 4);
+      const bf16x4 u4 = row64_read4(im.ut + blk * (G_DVB * GC), c, half * 32 + r4 * 8 + hf * 4);
 #pragma unroll
       for (int e = 0; e < 4; e++) acc[4 * r4 + e] = (float)u4[e];
     }
@@ -443,7 +453,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
     for (int t = 0; t < 2; t++) {
       const bf16x8 f = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
                             acc[8 * t + 6], acc[8 * t + 7]);
-      sm.vx[half][t][lane] = f;
+      sm.vx[blk][half][t][lane] = f;
       if constexpr (TRAIN) ((bf16x8*)a.vns)[(((op * 4 + dvb) * 2 + half) * 2 + t) * 64 + lane] = f;
     }
   }
@@ -452,7 +462,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
 #pragma unroll
   for (int rb = 0; rb < 2; rb++)
 #pragma unroll
-    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[rb][t][lane];
+    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[blk][rb][t][lane];
 
   // S1 = exp(gamma_last) S0 + (K decayed)^T Vn, rows 32 w .. 32 w + 31 of the state
 #pragma unroll
@@ -482,32 +492,38 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
     }
     // through LDS so that the tile leaves as two 16-byte stores per lane (a row of the tile is 64
     // contiguous bytes of o); only this wave touches its tile, LDS operations of a wave are ordered
+    __bf16(*ot)[OT_ROW] = (__bf16(*)[OT_ROW])(im.qg + (blk * 2 + half) * OT_ELEMS);
 #pragma unroll
-    for (int r = 0; r < 16; r++) sm.ot[half][(r >> 2) * 8 + hf * 4 + (r & 3)][c] = (__bf16)acc[r];
+    for (int r = 0; r < 16; r++) ot[(r >> 2) * 8 + hf * 4 + (r & 3)][c] = (__bf16)acc[r];
 #pragma unroll
     for (int part = 0; part < 2; part++) {
       const int row = part * 16 + (lane >> 2), q8 = (lane & 3) * 8;
-      const u32x4n val = *(const u32x4n*)&sm.ot[half][row][q8];
+      const u32x4n val = *(const u32x4n*)&ot[row][q8];
       const int i = half * 32 + row;
       if (i < len) *(u32x4n*)(a.o + ((size_t)(tok0 + i) * a.hv + h) * GD + dvb * G_DVB + q8) = val;
     }
   }
 }
 
-template <bool TRAIN>
-__global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
-  __shared__ __attribute__((aligned(1024))) ScanSmem sm;
+// (head, first column block) of a scan workgroup from its id.  Consecutive ids go round-robin over the 8 XCDs;
+// the workgroups of a head read the same operands, so they are given ids 8 apart and share one XCD's L2.
+__device__ __forceinline__ void scan_workgroup(const GdnArgs& a, int id, int& h, int& dvb0) {
+  constexpr int PER_HEAD = GD / G_DVB / SCAN_NB;        // workgroups per head
+  int part;
+  if (a.hv % 8 == 0) { h = (id / (8 * PER_HEAD)) * 8 + (id & 7); part = (id >> 3) % PER_HEAD; }
+  else               { h = id / PER_HEAD; part = id % PER_HEAD; }
+  dvb0 = part * SCAN_NB;
+}
 
-  // (head, column block) from the workgroup id.  Consecutive ids go round-robin over the 8 XCDs;
-  // the four column blocks of a head read the same operands, so they are given ids 8 apart and
-  // share one XCD's L2.
-  const int id = blockIdx.x;
-  int h, dvb;
-  if (a.hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
-  else               { h = id >> 2; dvb = id & 3; }
-  const int tid = threadIdx.x & (G_THREADS - 1);
+template <bool TRAIN>
+__global__ __launch_bounds__(SCAN_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
+  __shared__ __attribute__((aligned(1024))) ScanSmem sm;
+  int h, dvb0;
+  scan_workgroup(a, blockIdx.x, h, dvb0);
+  const int tid = threadIdx.x & (SCAN_THREADS - 1);
   const int lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int blk = w8 >> 2, w = w8 & 3;
   const int c = lane & 31, hf = lane >> 5;
   f32x16 s = zero16();                  // S[32 w + rows(r)][dvb*32 + c]
 
@@ -519,11 +535,11 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
   const int c_begin = a.seg_chunk0 ? a.seg_chunk0[seg] : 0;
   const int c_end = a.seg_chunk1 ? a.seg_chunk1[seg] : a.n_chunks;
   ChunkMeta meta;
-  issue_chunk<TRAIN>(a, c_begin, h, dvb, sm.img[0], w, lane);
+  issue_chunk<TRAIN>(a, c_begin, h, dvb0, sm.img[0], w8, lane);
   load_meta(a, c_begin, h, z, meta);
   for (int chunk = c_begin; chunk < c_end; chunk += 2) {
-    scan_step<TRAIN>(a, sm, sm.img[0], sm.img[1], meta, chunk, c_end, h, dvb, lane, z, w, c, hf, s);
-    if (chunk + 1 < c_end) scan_step<TRAIN>(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, c_end, h, dvb, lane, z, w, c, hf, s);
+    scan_step<TRAIN>(a, sm, sm.img[0], sm.img[1], meta, chunk, c_end, h, dvb0, blk, lane, z, w8, w, c, hf, s);
+    if (chunk + 1 < c_end) scan_step<TRAIN>(a, sm, sm.img[1], sm.img[0], meta, chunk + 1, c_end, h, dvb0, blk, lane, z, w8, w, c, hf, s);
   }
 }
 
@@ -537,20 +553,21 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_scan_kernel(GdnArgs a) {
 __device__ __forceinline__ bf16x8 row64_read8(const __bf16* arr, int r, int e0) {
   return *(const bf16x8*)(arr + r * GC + (((e0 >> 3) ^ (r & 7)) << 3));
 }
-__device__ __forceinline__ void issue_rev_chunk(const GdnArgs& a, int chunk, int h, int dvb, ScanImage& im, int w, int lane) {
+__device__ __forceinline__ void issue_rev_chunk(const GdnArgs& a, int chunk, int h, int dvb0, ScanImage& im, int w8, int lane) {
   const __bf16* rec = a.rev + op_index(a, chunk, h) * REV_ELEMS;
-  dma_tile64<4>(rec + REV_KD, GD * 2, GC, im.wn, w, lane);
-  dma_rows64(rec + REV_WTN, GD, im.kd, w, lane);
-  dma_rows64(rec + REV_QGT, GD, im.qg, w, lane);
-  dma_rows64(rec + REV_PT, GC, im.p, w, lane);
-  dma_rows64(rec + REV_DOT + (size_t)dvb * G_DVB * GC, G_DVB, im.ut, w, lane);
+  dma_tile64<SCAN_NW>(rec + REV_KD, GD * 2, GC, im.wn, w8, lane);
+  dma_rows64(rec + REV_WTN, GD, im.kd, w8, lane);
+  dma_rows64(rec + REV_QGT, GD, im.qg, w8, lane);
+  dma_rows64(rec + REV_PT, GC, im.p, w8, lane);
+  dma_rows64(rec + REV_DOT + (size_t)dvb0 * G_DVB * GC, SCAN_NB * G_DVB, im.ut, w8, lane);
 }
 
 // `later_src`: the source of the chunk that follows in DFS order (handled one step earlier); -2 means that chunk
 // continued from this one on chip, so `s` holds the gradient of this chunk's leaving state.
 __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanImage& im, ScanImage& im_next, ChunkMeta& meta, int chunk,
-                                           int c_begin, int seg, int h, int dvb, int lane, int z, int w, int c, int hf, f32x16& s,
-                                           int& later_src) {
+                                           int c_begin, int seg, int h, int dvb0, int blk, int lane, int z, int w8, int w, int c, int hf,
+                                           f32x16& s, int& later_src) {
+  const int dvb = dvb0 + blk;
   const int src = meta.src, dst = meta.dst, cap = meta.cap;
   const float glast = meta.glast;
   const size_t op = op_index(a, chunk, h);
@@ -588,30 +605,28 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
   // dS1 -> bf16, transposed into LDS
 #pragma unroll
   for (int r4 = 0; r4 < 4; r4++)
-    *(bf16x4*)&sm.st[c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
+    *(bf16x4*)&sm.st[blk][c][32 * w + r4 * 8 + hf * 4] = cvt4(s[4 * r4], s[4 * r4 + 1], s[4 * r4 + 2], s[4 * r4 + 3]);
   dma_wait_all();
   __syncthreads();
-  if (chunk > c_begin) issue_rev_chunk(a, chunk - 1, h, dvb, im_next, w, lane);
+  if (chunk > c_begin) issue_rev_chunk(a, chunk - 1, h, dvb0, im_next, w8, lane);
   load_meta(a, max(chunk - 1, c_begin), h, z, meta);
 
   const int half = w & 1;
   bf16x8 ofrag[GC / 16];              // B operand: column c of dO, k = tokens in plain order
 #pragma unroll
-  for (int js = 0; js < GC / 16; js++) ofrag[js] = row64_read8(im.ut, c, js * 16 + hf * 8);
+  for (int js = 0; js < GC / 16; js++) ofrag[js] = row64_read8(im.ut + blk * (G_DVB * GC), c, js * 16 + hf * 8);
   bf16x8 wfrag[2][2], qfrag[GC / 16];
 #pragma unroll
   for (int jb = 0; jb < 2; jb++)
 #pragma unroll
     for (int t = 0; t < 2; t++) wfrag[jb][t] = row64_perm_k(im.kd, 32 * w + c, jb * 32 + t * 16, hf);
-#pragma unroll
-  for (int js = 0; js < GC / 16; js++) qfrag[js] = row64_read8(im.qg, 32 * w + c, js * 16 + hf * 8);
   if (w < 2) {
     // rows 32 half .. of dVn
     bf16x8 sfrag[GD / 16], afrag[GD / 16], pfrag[GC / 16];
     const int abase = row_frag_base(lane);
 #pragma unroll
     for (int ks = 0; ks < GD / 16; ks++) {
-      sfrag[ks] = *(const bf16x8*)&sm.st[c][ks * 16 + hf * 8];
+      sfrag[ks] = *(const bf16x8*)&sm.st[blk][c][ks * 16 + hf * 8];
       afrag[ks] = lds_row_frag(im.wn, abase, half, ks);
     }
 #pragma unroll
@@ -626,7 +641,7 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
     for (int t = 0; t < 2; t++) {
       const bf16x8 f = cvt8(acc[8 * t], acc[8 * t + 1], acc[8 * t + 2], acc[8 * t + 3], acc[8 * t + 4], acc[8 * t + 5],
                             acc[8 * t + 6], acc[8 * t + 7]);
-      sm.vx[half][t][lane] = f;
+      sm.vx[blk][half][t][lane] = f;
       ((bf16x8*)a.dvns)[(((op * 4 + dvb) * 2 + half) * 2 + t) * 64 + lane] = f;
     }
   } else {
@@ -636,7 +651,7 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       const int piece = i * 128 + t128, row = piece >> 4, c8 = (piece & 15) * 8;
-      sdst[piece] = *(const u32x4n*)&sm.st[row][c8];
+      sdst[piece] = *(const u32x4n*)&sm.st[blk][row][c8];
     }
   }
   __syncthreads();
@@ -644,7 +659,11 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
 #pragma unroll
   for (int rb = 0; rb < 2; rb++)
 #pragma unroll
-    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[rb][t][lane];
+    for (int t = 0; t < 2; t++) vfrag[rb][t] = sm.vx[blk][rb][t][lane];
+  // (Qg^T fragments only now: fetched with the others in front of the first product they would push the wave past
+  // its register budget at two waves per SIMD; the image is not overwritten before the next step's first barrier)
+#pragma unroll
+  for (int js = 0; js < GC / 16; js++) qfrag[js] = row64_read8(im.qg, 32 * w + c, js * 16 + hf * 8);
 
   // dS0 = exp(gamma_last) dS1 - W^T dVn + Qg^T dO, rows 32 w .. 32 w + 31
 #pragma unroll
@@ -671,15 +690,14 @@ __device__ __forceinline__ void rscan_step(const GdnArgs& a, ScanSmem& sm, ScanI
   }
 }
 
-__global__ __launch_bounds__(G_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
+__global__ __launch_bounds__(SCAN_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(1024))) ScanSmem sm;
-  const int id = blockIdx.x;
-  int h, dvb;
-  if (a.hv % 8 == 0) { h = (id >> 5) * 8 + (id & 7); dvb = (id >> 3) & 3; }
-  else               { h = id >> 2; dvb = id & 3; }
-  const int tid = threadIdx.x & (G_THREADS - 1);
+  int h, dvb0;
+  scan_workgroup(a, blockIdx.x, h, dvb0);
+  const int tid = threadIdx.x & (SCAN_THREADS - 1);
   const int lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int w8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int blk = w8 >> 2, w = w8 & 3;
   const int c = lane & 31, hf = lane >> 5;
   f32x16 s = zero16();                  // gradient of S[32 w + rows(r)][dvb*32 + c]
   int z = 0;
@@ -691,11 +709,12 @@ __global__ __launch_bounds__(G_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
   const int seg = a.seg_base + blockIdx.y;
   const int c_begin = a.seg_chunk0 ? a.seg_chunk0[seg] : 0;
   const int last = (a.seg_chunk1 ? a.seg_chunk1[seg] : a.n_chunks) - 1;
-  issue_rev_chunk(a, last, h, dvb, sm.img[0], w, lane);
+  issue_rev_chunk(a, last, h, dvb0, sm.img[0], w8, lane);
   load_meta(a, last, h, z, meta);
   for (int chunk = last; chunk >= c_begin; chunk -= 2) {
-    rscan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, c_begin, seg, h, dvb, lane, z, w, c, hf, s, later_src);
-    if (chunk > c_begin) rscan_step(a, sm, sm.img[1], sm.img[0], meta, chunk - 1, c_begin, seg, h, dvb, lane, z, w, c, hf, s, later_src);
+    rscan_step(a, sm, sm.img[0], sm.img[1], meta, chunk, c_begin, seg, h, dvb0, blk, lane, z, w8, w, c, hf, s, later_src);
+    if (chunk > c_begin)
+      rscan_step(a, sm, sm.img[1], sm.img[0], meta, chunk - 1, c_begin, seg, h, dvb0, blk, lane, z, w8, w, c, hf, s, later_src);
   }
 }
 
@@ -723,16 +742,16 @@ size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
 // level with the level's segments side by side (blockIdx.y).
 template <bool TRAIN>
 static hipError_t launch_scan(GdnArgs& a, const tt_gdn_schedule* sched, hipStream_t st) {
-  const unsigned gx = (unsigned)((GD / G_DVB) * a.hv);
+  const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * a.hv);
   if (!sched) {
     a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
-    gdn_scan_kernel<TRAIN><<<dim3(gx, 1), G_THREADS, 0, st>>>(a);
+    gdn_scan_kernel<TRAIN><<<dim3(gx, 1), SCAN_THREADS, 0, st>>>(a);
     return hipGetLastError();
   }
   a.seg_chunk0 = sched->seg_chunk0; a.seg_chunk1 = sched->seg_chunk1;
   for (int l = 0; l < sched->n_levels; l++) {
     a.seg_base = sched->level_off[l];
-    gdn_scan_kernel<TRAIN><<<dim3(gx, (unsigned)(sched->level_off[l + 1] - sched->level_off[l])), G_THREADS, 0, st>>>(a);
+    gdn_scan_kernel<TRAIN><<<dim3(gx, (unsigned)(sched->level_off[l + 1] - sched->level_off[l])), SCAN_THREADS, 0, st>>>(a);
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
   return hipSuccess;
@@ -786,16 +805,16 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
   a.chunk_cap = b.d_state_out ? b.chunk_cap : nullptr;
   {
     KernelTimer t(TT_KERNEL_GDN_BWD_RSCAN, st);
-    const unsigned gx = (unsigned)((GD / G_DVB) * b.hv);
+    const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * b.hv);
     if (!b.sched) {
       a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
-      gdn_rscan_kernel<<<dim3(gx, 1), G_THREADS, 0, st>>>(a);
+      gdn_rscan_kernel<<<dim3(gx, 1), SCAN_THREADS, 0, st>>>(a);
     } else {
       // last level first: a level's segments only need the gradients stored by later levels
       a.seg_grad = sv.seg_grad; a.slot_cons_off = b.sched->slot_cons_off; a.slot_cons = b.sched->slot_cons;
       for (int l = b.sched->n_levels - 1; l >= 0; l--) {
         a.seg_base = b.sched->level_off[l];
-        gdn_rscan_kernel<<<dim3(gx, (unsigned)(b.sched->level_off[l + 1] - b.sched->level_off[l])), G_THREADS, 0, st>>>(a);
+        gdn_rscan_kernel<<<dim3(gx, (unsigned)(b.sched->level_off[l + 1] - b.sched->level_off[l])), SCAN_THREADS, 0, st>>>(a);
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
       }
       if (b.d_initial_state && b.sched->n_levels > 0)
