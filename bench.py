@@ -440,8 +440,7 @@ def leg_gdn(c):
         del gws
         if not args.no_gdn_bwd:
             gdo = torch.randn((N, ghv, 128), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-            bws = torch.empty(T.binding._lib().tt_tree_gdn_bwd_workspace(N, gplan.n_chunks, gplan.n_slots, gplan.n_segments, ghk, ghv), dtype=torch.uint8,
-                              device=dev)
+            bws = torch.empty(T.tree_gdn_bwd_workspace(N, ghk, ghv, gplan), dtype=torch.uint8, device=dev)
             n_it = 3
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
             for it in range(1 + n_it):
@@ -466,6 +465,17 @@ def leg_gdn(c):
                                            "reverse_walk": round(bt["gdn_bwd_rscan"][0] / n_it, 4), "finish": round(bt["gdn_bwd_finish"][0] / n_it, 4)},
                         "bwd_tflops": round(bwd_flop * gplan.n_chunks * ghv / (b_ms * 1e-3) / 1e12, 2),
                         "bwd_workspace_mb": round(bws.numel() / 1e6, 1)})
+            # the same with the workspace capped at 1 GB: the call then takes the heads in passes of whole key-head groups
+            cap = 1_000_000_000
+            if T.tree_gdn_bwd_workspace(N, ghk, ghv, gplan, smallest=True) <= cap < bws.numel():
+                small = bws[:cap]
+                for it in range(1 + n_it):
+                    if it == 1:
+                        ev[0].record()
+                    T.tree_gdn_bwd(gq, gk, gv, gg, gb, gdo, gplan, workspace=small)
+                ev[1].record()
+                ev[1].synchronize()
+                gdn.update({"ms_bwd_capped_workspace": round(ev[0].elapsed_time(ev[1]) / n_it, 4), "capped_workspace_mb": cap / 1e6})
             del gdo, bws
         del gq, gk, gv, go
 

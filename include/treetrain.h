@@ -563,9 +563,13 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * start from.  Arithmetic: matrix products use bf16 operands with fp32 accumulation, like the
  * forward (state and state gradient stay fp32); the triangular solves and all element-wise work
  * are fp32.
- * Workspace: tt_tree_gdn_bwd_workspace bytes, 16-byte aligned (about 300 KB per chunk and value
- * head, plus two fp32 [n_tokens][hv][128] arrays, 2 x n_slots saved states per head and, with a
- * schedule, one state gradient per segment and head; n_segments = 0 when the call gets no schedule).
+ * Workspace, 16-byte aligned: tt_tree_gdn_bwd_workspace bytes let all heads run in one pass (about
+ * 300 KB per chunk and value head, plus two fp32 [n_tokens][hv][128] arrays, 2 x n_slots saved
+ * states per head and, with a schedule, one state gradient per segment and head; n_segments = 0
+ * when the call gets no schedule).  The heads are independent up to the sum over the value heads
+ * of a key head, so any size from tt_tree_gdn_bwd_workspace_min (one key head with its value heads
+ * per pass) upwards is accepted: the call then runs in passes of as many key heads as fit -- less
+ * memory for more launches and walks that fill less of the chip; results do not depend on it.
  * With a schedule the reverse walk also runs level by level (last level first): every segment
  * stores the gradient of the state it started from, and the chunk that saved a slot adds the
  * gradients of the slot's readers in the order of slot_cons -- a fixed order, no atomics.
@@ -573,6 +577,8 @@ tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * ------------------------------------------------------------------------------------------ */
 size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments,
                                  int32_t hk, int32_t hv);
+size_t tt_tree_gdn_bwd_workspace_min(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments,
+                                     int32_t hk, int32_t hv);
 tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
                           const void* q, const void* k, const void* v, const float* g, const float* beta,
                           const void* d_o,

@@ -128,6 +128,8 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_gdn_schedule.argtypes = [ctypes.c_int32, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, _vp]
         lib.tt_tree_gdn_bwd_workspace.restype = ctypes.c_size_t
         lib.tt_tree_gdn_bwd_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        lib.tt_tree_gdn_bwd_workspace_min.restype = ctypes.c_size_t
+        lib.tt_tree_gdn_bwd_workspace_min.argtypes = lib.tt_tree_gdn_bwd_workspace.argtypes
         lib.tt_tree_gdn_bwd.restype = ctypes.c_int32
         lib.tt_tree_gdn_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                         _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp, _vp,
@@ -785,11 +787,19 @@ def tree_gdn_fwd(q, k, v, g, beta, plan: GdnPlan, *, scale=None, out=None, works
     return (out, states) if return_states else out
 
 
+def tree_gdn_bwd_workspace(n_tokens: int, hk: int, hv: int, plan: GdnPlan, smallest: bool = False) -> int:
+    """Bytes of workspace with which tree_gdn_bwd takes all heads in one pass, or (smallest) the least it accepts:
+    one key head with its value heads per pass.  Anything in between is used for as many key heads per pass as fit."""
+    f = _lib().tt_tree_gdn_bwd_workspace_min if smallest else _lib().tt_tree_gdn_bwd_workspace
+    return int(f(n_tokens, plan.n_chunks, plan.n_slots, plan.n_segments if plan._schedule() is not None else 0, hk, hv))
+
+
 def tree_gdn_bwd(q, k, v, g, beta, d_o, plan: GdnPlan, *, scale=None, initial_state=None, d_state_out=None,
                  want_d_initial_state: bool = False, workspace=None, stream=None):
     """Backward of tree_gdn_fwd for upstream d_o [n, hv, 128] bf16.  Returns (dq, dk [n, hk, 128] bf16, dv [n, hv, 128]
     bf16, dg, dbeta [n, hv] fp32), plus d_initial_state [hv, 128, 128] fp32 when asked.  d_state_out
-    [n_capture, hv, 128, 128] fp32: upstream gradient of the plan's captured end states."""
+    [n_capture, hv, 128, 128] fp32: upstream gradient of the plan's captured end states.  workspace: a uint8 tensor of
+    tree_gdn_bwd_workspace(...) bytes (default: allocated here, full size) or of any size down to its `smallest`."""
     torch = _torch()
     for t in (q, k, v, d_o):
         if t.dim() != 3 or t.dtype != torch.bfloat16 or not t.is_contiguous():
@@ -811,8 +821,7 @@ def tree_gdn_bwd(q, k, v, g, beta, d_o, plan: GdnPlan, *, scale=None, initial_st
     dv_ = torch.empty_like(v)
     dg, dbeta = torch.empty_like(g), torch.empty_like(beta)
     d_init = torch.empty((hv, dk, dv), dtype=torch.float32, device=dev) if want_d_initial_state else None
-    need = int(_lib().tt_tree_gdn_bwd_workspace(n, plan.n_chunks, plan.n_slots, plan.n_segments if plan._schedule() is not None else 0,
-                                                 hk, hv))
+    need = tree_gdn_bwd_workspace(n, hk, hv, plan)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     d = plan.device

@@ -414,8 +414,15 @@ extern "C" tt_status tt_tree_gdn_fwd(int64_t n_tokens, int32_t hk, int32_t hv, i
 extern "C" size_t tt_tree_gdn_bwd_workspace(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments, int32_t hk,
                                             int32_t hv) {
   tt::clear_error();
-  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || n_segments < 0 || hk <= 0 || hv <= 0) return 0;
-  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, n_segments, hk, hv);
+  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || n_segments < 0 || hk <= 0 || hv <= 0 || hv % hk != 0) return 0;
+  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, n_segments, hk, hv, hk);
+}
+
+extern "C" size_t tt_tree_gdn_bwd_workspace_min(int64_t n_tokens, int32_t n_chunks, int32_t n_slots, int32_t n_segments, int32_t hk,
+                                                int32_t hv) {
+  tt::clear_error();
+  if (n_tokens < 0 || n_chunks < 0 || n_slots < 0 || n_segments < 0 || hk <= 0 || hv <= 0 || hv % hk != 0) return 0;
+  return tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, n_segments, hk, hv, 1);
 }
 
 extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, int32_t dv, float scale,
@@ -447,9 +454,9 @@ extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, i
       for (const void* i : ins)
         if (o && o == i) return fail(TT_ERR_SHAPE, "an output aliases an input");
   }
-  const size_t need = tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, schedule ? schedule->n_segments : 0, hk, hv);
+  const size_t need = tt::gdn_bwd_workspace(n_tokens, n_chunks, n_slots, schedule ? schedule->n_segments : 0, hk, hv, 1);
   if (!workspace || workspace_bytes < need || !tt::aligned16(workspace))
-    return fail(TT_ERR_WORKSPACE, "gdn backward needs %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
+    return fail(TT_ERR_WORKSPACE, "gdn backward needs at least %zu bytes of 16-byte aligned workspace, got %zu", need, workspace_bytes);
   tt::GdnBwdArgs a{};
   a.n_tokens = n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.n_slots = n_slots; a.scale = scale;
   a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.g = g; a.beta = beta;
@@ -457,6 +464,6 @@ extern "C" tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, i
   a.sched = schedule;
   a.initial_state = initial_state; a.d_state_out = d_state_out;
   a.dq = dq; a.dk = dk_out; a.dv = dv_out; a.dg = dg; a.dbeta = dbeta; a.d_initial_state = d_initial_state;
-  a.workspace = workspace;
+  a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   return hip_result(tt::gdn_bwd(a, (hipStream_t)stream), "tree_gdn_bwd");
 }

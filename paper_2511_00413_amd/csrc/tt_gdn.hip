@@ -41,7 +41,8 @@ constexpr int SCAN_NW = 4 * SCAN_NB; // wavefronts per scan workgroup (two per S
 constexpr int SCAN_THREADS = 64 * SCAN_NW;
 
 struct GdnArgs {
-  int n_tokens, hk, hv, n_chunks;
+  int n_tokens, hk, hv, n_chunks;    // hk, hv: heads of the tensors (their strides)
+  int hv_n;                          // value heads this launch works on (h = 0 .. hv_n - 1 relative to the pointers below)
   float scale;
   const __bf16 *q, *k, *v;           // [N][hk][128], [N][hk][128], [N][hv][128]
   const float *g, *beta;             // [N][hv]
@@ -510,7 +511,7 @@ __device__ __forceinline__ void scan_step(const GdnArgs& a, ScanSmem& sm, ScanIm
 __device__ __forceinline__ void scan_workgroup(const GdnArgs& a, int id, int& h, int& dvb0) {
   constexpr int PER_HEAD = GD / G_DVB / SCAN_NB;        // workgroups per head
   int part;
-  if (a.hv % 8 == 0) { h = (id / (8 * PER_HEAD)) * 8 + (id & 7); part = (id >> 3) % PER_HEAD; }
+  if (a.hv_n % 8 == 0) { h = (id / (8 * PER_HEAD)) * 8 + (id & 7); part = (id >> 3) % PER_HEAD; }
   else               { h = id / PER_HEAD; part = id % PER_HEAD; }
   dvb0 = part * SCAN_NB;
 }
@@ -719,12 +720,12 @@ __global__ __launch_bounds__(SCAN_THREADS, 1) void gdn_rscan_kernel(GdnArgs a) {
 }
 
 // d_initial_state = sum over the root segments (level 0, in order) of the gradients they stored
-__global__ __launch_bounds__(G_THREADS) void gdn_root_grad_kernel(const float* __restrict__ seg_grad, int n_roots, int hv,
+__global__ __launch_bounds__(G_THREADS) void gdn_root_grad_kernel(const float* __restrict__ seg_grad, int n_roots, int hv, int hv_n,
                                                                   float* __restrict__ d_initial_state) {
-  const size_t n = (size_t)hv * GD * GD;
+  const size_t n = (size_t)hv_n * GD * GD, seg_stride = (size_t)hv * GD * GD;
   for (size_t e = (size_t)blockIdx.x * G_THREADS + threadIdx.x; e < n; e += (size_t)gridDim.x * G_THREADS) {
     float acc = 0.f;
-    for (int r = 0; r < n_roots; r++) acc += seg_grad[(size_t)r * n + e];
+    for (int r = 0; r < n_roots; r++) acc += seg_grad[(size_t)r * seg_stride + e];
     d_initial_state[e] = acc;
   }
 }
@@ -742,7 +743,7 @@ size_t gdn_workspace(int n_chunks, int n_slots, int hv) {
 // level with the level's segments side by side (blockIdx.y).
 template <bool TRAIN>
 static hipError_t launch_scan(GdnArgs& a, const tt_gdn_schedule* sched, hipStream_t st) {
-  const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * a.hv);
+  const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * a.hv_n);
   if (!sched) {
     a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
     gdn_scan_kernel<TRAIN><<<dim3(gx, 1), SCAN_THREADS, 0, st>>>(a);
@@ -763,7 +764,7 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
                    const float* initial_state, float* state_out, void* o, void* workspace, hipStream_t st) {
   if (n_chunks == 0) return hipSuccess;
   GdnArgs a{};
-  a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.n_chunks = n_chunks; a.scale = scale;
+  a.n_tokens = (int)n_tokens; a.hk = hk; a.hv = hv; a.hv_n = hv; a.n_chunks = n_chunks; a.scale = scale;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v; a.g = g; a.beta = beta;
   a.chunk_tok0 = chunk_tok0; a.chunk_len = chunk_len; a.chunk_src = chunk_src; a.chunk_dst = chunk_dst;
   a.chunk_cap = chunk_cap; a.initial_state = initial_state; a.state_out = state_out;
@@ -785,7 +786,7 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
 hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st) {
   if (b.n_chunks == 0) return hipSuccess;
   GdnArgs a{};
-  a.n_tokens = (int)b.n_tokens; a.hk = b.hk; a.hv = b.hv; a.n_chunks = b.n_chunks; a.scale = b.scale;
+  a.n_tokens = (int)b.n_tokens; a.hk = b.hk; a.hv = b.hv; a.hv_n = b.hv_n; a.n_chunks = b.n_chunks; a.scale = b.scale;
   a.q = (const __bf16*)b.q; a.k = (const __bf16*)b.k; a.v = (const __bf16*)b.v; a.g = b.g; a.beta = b.beta;
   a.chunk_tok0 = b.chunk_tok0; a.chunk_len = b.chunk_len; a.chunk_src = b.chunk_src; a.chunk_dst = b.chunk_dst;
   a.initial_state = b.initial_state;
@@ -795,7 +796,7 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
   a.slot_grad = sv.slot_grad; a.d_state_out = b.d_state_out; a.d_initial_state = b.d_initial_state;
   {
     KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
-    gdn_prepare_kernel<true><<<dim3(b.n_chunks, b.hv), G_THREADS, 0, st>>>(a);
+    gdn_prepare_kernel<true><<<dim3(b.n_chunks, b.hv_n), G_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {
@@ -805,7 +806,7 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
   a.chunk_cap = b.d_state_out ? b.chunk_cap : nullptr;
   {
     KernelTimer t(TT_KERNEL_GDN_BWD_RSCAN, st);
-    const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * b.hv);
+    const unsigned gx = (unsigned)((GD / G_DVB / SCAN_NB) * b.hv_n);
     if (!b.sched) {
       a.seg_chunk0 = a.seg_chunk1 = nullptr; a.seg_base = 0;
       gdn_rscan_kernel<<<dim3(gx, 1), SCAN_THREADS, 0, st>>>(a);
@@ -818,7 +819,7 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
       }
       if (b.d_initial_state && b.sched->n_levels > 0)
-        gdn_root_grad_kernel<<<256, G_THREADS, 0, st>>>(sv.seg_grad, b.sched->level_off[1], b.hv, b.d_initial_state);
+        gdn_root_grad_kernel<<<256, G_THREADS, 0, st>>>(sv.seg_grad, b.sched->level_off[1], b.hv, b.hv_n, b.d_initial_state);
     }
   }
   return hipGetLastError();

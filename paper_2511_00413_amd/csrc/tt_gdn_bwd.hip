@@ -43,7 +43,7 @@ struct BwdWs {
   GdnChunkOps ops;
   GdnBwdSaved sv;
   __bf16* x;         // per (head, chunk) [64][256]: [dW] on the way in, [dVb | dKb] after the transposed solve
-  float* dqh;        // [N][hv][128] per-value-head dq, dk
+  float* dqh;        // [N][hv_n][128] per-value-head dq, dk (the heads of the pass)
   float* dkh;
 };
 struct KArgs {
@@ -485,7 +485,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
-        if (i < len) a.w.dqh[((size_t)(tok0 + i) * hv + h) * GD + j] = acc[t][r];
+        if (i < len) a.w.dqh[((size_t)(tok0 + i) * a.b.hv_n + h) * GD + j] = acc[t][r];
       }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -527,7 +527,7 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; r++) {
         const int i = 32 * T128::ib(w, t) + tile_row(r, hf);
-        if (i < len) a.w.dkh[((size_t)(tok0 + i) * hv + h) * GD + d] = acc[t][r];
+        if (i < len) a.w.dkh[((size_t)(tok0 + i) * a.b.hv_n + h) * GD + d] = acc[t][r];
       }
   }
   // dv_i = beta_i dVb_i,  dbeta_i += dVb_i . v_i
@@ -599,14 +599,14 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
 
 // dq, dk [N][hk][128] bf16 = sum over the value heads of a group of the per-head fp32 gradients
 __global__ __launch_bounds__(BT) void gdn_bwd_group_sum_kernel(KArgs a) {
-  const int rep = a.b.hv / a.b.hk;
-  const size_t n4 = (size_t)a.b.n_tokens * a.b.hk * (GD / 4);
+  const int rep = a.b.hv / a.b.hk, hk_n = a.b.hv_n / rep;          // key heads of this pass
+  const size_t n4 = (size_t)a.b.n_tokens * hk_n * (GD / 4);
   for (size_t e = (size_t)blockIdx.x * BT + threadIdx.x; e < n4; e += (size_t)gridDim.x * BT) {
-    const size_t t = e / ((size_t)a.b.hk * (GD / 4));
-    const int rem = (int)(e % ((size_t)a.b.hk * (GD / 4))), kh = rem / (GD / 4), d4 = (rem % (GD / 4)) * 4;
+    const size_t t = e / ((size_t)hk_n * (GD / 4));
+    const int rem = (int)(e % ((size_t)hk_n * (GD / 4))), kh = rem / (GD / 4), d4 = (rem % (GD / 4)) * 4;
     float4 sq = make_float4(0.f, 0.f, 0.f, 0.f), sk = sq;
     for (int r = 0; r < rep; r++) {
-      const size_t src = ((size_t)t * a.b.hv + kh * rep + r) * GD + d4;
+      const size_t src = ((size_t)t * a.b.hv_n + kh * rep + r) * GD + d4;
       const float4 x = ld4(a.w.dqh + src), y = ld4(a.w.dkh + src);
       sq.x += x.x; sq.y += x.y; sq.z += x.z; sq.w += x.w;
       sk.x += y.x; sk.y += y.y; sk.z += y.z; sk.w += y.w;
@@ -624,8 +624,9 @@ __global__ __launch_bounds__(BT) void gdn_bwd_fill_zero_kernel(float4* p, size_t
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 // carves the workspace; returns the total size (with p == nullptr: only the size)
-size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hv, BwdWs* w) {
-  const size_t per = (size_t)n_chunks * hv;
+// (hv_n: value heads of one pass; the saved states and their gradients keep the tensors' head stride hv)
+size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hv, int hv_n, BwdWs* w) {
+  const size_t per = (size_t)n_chunks * hv_n;
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* r = p ? p + off : nullptr;
@@ -647,47 +648,72 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int n_segment
   t.sv.slot_grad = (float*)take((size_t)n_slots * hv * GD * GD * 4);
   t.sv.seg_grad = (float*)take((size_t)n_segments * hv * GD * GD * 4);
   t.x = (__bf16*)take(per * GC * 2 * GD * 2);
-  t.dqh = (float*)take((size_t)n_tokens * hv * GD * 4);
-  t.dkh = (float*)take((size_t)n_tokens * hv * GD * 4);
+  t.dqh = (float*)take((size_t)n_tokens * hv_n * GD * 4);
+  t.dkh = (float*)take((size_t)n_tokens * hv_n * GD * 4);
   if (w) *w = t;
   return off + 256;
 }
 
 }  // namespace
 
-size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv) {
-  (void)hk;
-  return carve(nullptr, n_tokens, n_chunks, n_slots, n_segments, hv, nullptr);
+size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv, int key_heads_per_pass) {
+  return carve(nullptr, n_tokens, n_chunks, n_slots, n_segments, hv, key_heads_per_pass * (hv / hk), nullptr);
 }
 
-hipError_t gdn_bwd(const GdnBwdArgs& b, hipStream_t st) {
-  if (b.n_chunks == 0 || b.n_tokens == 0) return hipSuccess;
-  KArgs a{};
-  a.b = b;
-  carve((char*)b.workspace, b.n_tokens, b.n_chunks, b.n_slots, b.sched ? b.sched->n_segments : 0, b.hv, &a.w);
+// The value heads are independent of each other up to the final sum over the value heads of a key head, so the
+// pass can be cut into batches of whole key-head groups: as many per batch as the workspace holds.  A batch sees
+// the tensors through pointers moved to its first head (the head counts stay the strides).
+hipError_t gdn_bwd(const GdnBwdArgs& b0, hipStream_t st) {
+  if (b0.n_chunks == 0 || b0.n_tokens == 0) return hipSuccess;
+  const int rep = b0.hv / b0.hk, n_seg = b0.sched ? b0.sched->n_segments : 0;
+  int per_pass = b0.hk;
+  while (per_pass > 1 && gdn_bwd_workspace(b0.n_tokens, b0.n_chunks, b0.n_slots, n_seg, b0.hk, b0.hv, per_pass) > b0.workspace_bytes)
+    per_pass--;
+  if (gdn_bwd_workspace(b0.n_tokens, b0.n_chunks, b0.n_slots, n_seg, b0.hk, b0.hv, per_pass) > b0.workspace_bytes)
+    return hipErrorInvalidValue;
   auto zero = [&](float* p, size_t floats) {
     if (floats == 0) return;
     const size_t n4 = floats / 4;
     gdn_bwd_fill_zero_kernel<<<dim3((unsigned)std::min<size_t>((n4 + BT - 1) / BT, 4096)), BT, 0, st>>>((float4*)p, n4);
   };
-  // walking all chunks in sequence order, readers add into the slot gradients and into d_initial_state; with a
-  // schedule every segment stores its own gradient and nothing has to start from zero
-  if (!b.sched) {
-    zero(a.w.sv.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
-    if (b.d_initial_state) zero(b.d_initial_state, (size_t)b.hv * GD * GD);
+  for (int kh0 = 0; kh0 < b0.hk; kh0 += per_pass) {
+    const int hk_n = std::min(per_pass, b0.hk - kh0), h0 = kh0 * rep;
+    GdnBwdArgs b = b0;
+    b.hv_n = hk_n * rep;
+    const size_t ko = (size_t)kh0 * GD, vo = (size_t)h0 * GD, so = (size_t)h0 * GD * GD;
+    b.q = (const __bf16*)b0.q + ko; b.k = (const __bf16*)b0.k + ko; b.v = (const __bf16*)b0.v + vo; b.d_o = (const __bf16*)b0.d_o + vo;
+    b.g = b0.g + h0; b.beta = b0.beta + h0;
+    b.dq = (__bf16*)b0.dq + ko; b.dk = (__bf16*)b0.dk + ko; b.dv = (__bf16*)b0.dv + vo;
+    b.dg = b0.dg + h0; b.dbeta = b0.dbeta + h0;
+    if (b0.initial_state) b.initial_state = b0.initial_state + so;
+    if (b0.d_state_out) b.d_state_out = b0.d_state_out + so;
+    if (b0.d_initial_state) b.d_initial_state = b0.d_initial_state + so;
+    KArgs a{};
+    a.b = b;
+    carve((char*)b.workspace, b.n_tokens, b.n_chunks, b.n_slots, n_seg, b.hv, b.hv_n, &a.w);
+    // walking all chunks in sequence order, readers add into the slot gradients and into d_initial_state; with a
+    // schedule every segment stores its own gradient and nothing has to start from zero
+    if (!b.sched) {
+      zero(a.w.sv.slot_grad, (size_t)b.n_slots * b.hv * GD * GD);
+      if (b.d_initial_state) {
+        // the rows of this pass's heads (one contiguous piece: heads are the outer index)
+        zero(b.d_initial_state, (size_t)b.hv_n * GD * GD);
+      }
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    if (hipError_t e = gdn_bwd_prepare_and_walks(b, a.w.ops, a.w.sv, st); e != hipSuccess) return e;
+    {
+      KernelTimer t(TT_KERNEL_GDN_BWD_FINISH, st);
+      gdn_bwd_finish_kernel<<<dim3(b.n_chunks, b.hv_n), BT, 0, st>>>(a);
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    {
+      const size_t n4 = (size_t)b.n_tokens * hk_n * (GD / 4);
+      gdn_bwd_group_sum_kernel<<<dim3((unsigned)std::min<size_t>((n4 + BT - 1) / BT, 8192)), BT, 0, st>>>(a);
+    }
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   }
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  if (hipError_t e = gdn_bwd_prepare_and_walks(b, a.w.ops, a.w.sv, st); e != hipSuccess) return e;
-  {
-    KernelTimer t(TT_KERNEL_GDN_BWD_FINISH, st);
-    gdn_bwd_finish_kernel<<<dim3(b.n_chunks, b.hv), BT, 0, st>>>(a);
-  }
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  {
-    const size_t n4 = (size_t)b.n_tokens * b.hk * (GD / 4);
-    gdn_bwd_group_sum_kernel<<<dim3((unsigned)std::min<size_t>((n4 + BT - 1) / BT, 8192)), BT, 0, st>>>(a);
-  }
-  return hipGetLastError();
+  return hipSuccess;
 }
 
 }  // namespace tt

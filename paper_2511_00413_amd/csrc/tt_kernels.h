@@ -119,6 +119,8 @@ __host__ __device__ inline int gdn_frag_index(int i, int col) {
 struct GdnBwdArgs {
   int64_t n_tokens;
   int hk, hv, n_chunks, n_slots;
+  int hv_n;                          // value heads this pass works on (set by gdn_bwd: a batch of whole key-head groups;
+                                     // the tensor pointers are moved to the batch's first head, hk / hv stay the strides)
   float scale;
   const void *q, *k, *v, *d_o;       // bf16
   const float *g, *beta;
@@ -130,10 +132,12 @@ struct GdnBwdArgs {
   float *dg, *dbeta;                 // [N][hv]
   float* d_initial_state;            // nullptr or [hv][128][128], overwritten
   void* workspace;
+  size_t workspace_bytes;            // decides how many key-head groups one pass takes
 };
 // prepare kernel (backward form) + forward walk + reverse walk (tt_gdn.hip)
 hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops, const GdnBwdSaved& sv, hipStream_t st);
 hipError_t gdn_bwd(const GdnBwdArgs& a, hipStream_t st);
-size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv);
+// workspace for passes of key_heads_per_pass key heads (with their hv / hk value heads) at a time
+size_t gdn_bwd_workspace(int64_t n_tokens, int n_chunks, int n_slots, int n_segments, int hk, int hv, int key_heads_per_pass);
 
 }  // namespace tt

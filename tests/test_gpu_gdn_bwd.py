@@ -2,8 +2,8 @@
 Like the forward, the kernels round the operands of their matrix products to bf16 once each (per-chunk
 operands, entering state, Vn, gradient of the leaving state, dVn, the solved right-hand sides) and accumulate in
 fp32; solves and element-wise work are fp32; dq, dk, dv are rounded to bf16 at the end (dq, dk after the fp32 sum
-over the value heads of a key head).  Tolerance: rel-L2 <= 2e-2 on every output, as for the attention
-gradients; measured 2.3e-3 .. 3.4e-3."""
+over the value heads of a key head).  Tolerance: rel-L2 <= 8e-3 on every output (a product of two or three
+operands rounded to bf16, fp32 sums; measured 2.3e-3 .. 3.4e-3)."""
 import numpy as np
 import pytest
 import torch
@@ -74,6 +74,44 @@ def test_level_schedule_against_sequence_order(seed):
         e = rel_l2(a.float().cpu().numpy(), c.float().cpu().numpy())
         print(f"   {name}: scheduled vs sequence order rel-L2 {e:.2e}", flush=True)
         assert e <= (2e-3 if a.dtype == torch.bfloat16 else 1e-4), (name, e)
+
+
+@pytest.mark.parametrize("parallel", [True, False])
+def test_passes_of_key_head_groups(parallel):
+    """A workspace too small for all heads makes the call run in passes of whole key-head groups (here 3 key heads x 2
+    value heads: one, two or all three key heads per pass).  The heads are independent, so every output must be
+    bit-identical whatever the pass size -- with the state gateway in both directions, with and without the level
+    schedule; below the smallest size the call is refused."""
+    t = W.random_tree(977, n_nodes=12, lo=1, hi=140, n_roots=2, p_zero=0.1)
+    m = M.dfs_meta(t.parent, t.seg_len)
+    n, hk, hv = m["n_tokens"], 3, 6
+    q, k, v, g, beta, d_o = (x.cuda() for x in _inputs(n, hk, hv, 41))
+    cap = [i for i in range(len(t.seg_len)) if t.seg_len[i] > 0][:2]
+    plan = T.tree_gdn_plan(t.parent, t.seg_len, capture_nodes=cap).to_device()
+    plan.parallel = parallel
+    gen = torch.Generator().manual_seed(5)
+    init = (torch.randn((hv, 128, 128), generator=gen) * 0.1).cuda()
+    d_state = (torch.randn((plan.n_capture, hv, 128, 128), generator=gen) * 0.1).cuda()
+    full = T.tree_gdn_bwd_workspace(n, hk, hv, plan)
+    least = T.tree_gdn_bwd_workspace(n, hk, hv, plan, smallest=True)
+    assert least < full
+    print(f"[case] gdn bwd passes n={n} hk={hk} hv={hv} schedule={parallel}: workspace {least} .. {full} bytes", flush=True)
+
+    def run(nbytes):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        out = T.tree_gdn_bwd(q, k, v, g, beta, d_o, plan, initial_state=init, d_state_out=d_state, want_d_initial_state=True,
+                             workspace=ws)
+        torch.cuda.synchronize()
+        return out
+
+    ref = run(full)
+    for nbytes in (least, (least + full) // 2 + 4096, full - 16):
+        got = run(nbytes)
+        for name, a, b in zip(("dq", "dk", "dv", "dg", "dbeta", "d_initial_state"), got, ref):
+            assert torch.equal(a, b), (name, nbytes)
+    with pytest.raises(T.TreeTrainError) as e:
+        run(least - 256)
+    assert e.value.status == -6
 
 
 def test_chain_partial_chunks():

@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol():
     assert {"tt_tree_build_meta", "tt_tree_attn_fwd", "tt_tree_attn_bwd", "tt_tree_weighted_logprob",
             "tt_tree_weighted_logprob_bwd", "tt_tree_rope", "tt_tree_partition_sizes", "tt_tree_partition_plan", "tt_tree_path_weights", "tt_tree_conv_fwd", "tt_tree_conv_bwd", "tt_tree_conv_plan", "tt_tree_conv_plan_sizes",
             "tt_tree_conv_bwd_workspace", "tt_tree_gdn_plan_sizes", "tt_tree_gdn_plan", "tt_tree_gdn_workspace", "tt_tree_gdn_fwd",
-            "tt_tree_gdn_bwd_workspace", "tt_tree_gdn_bwd",
+            "tt_tree_gdn_bwd_workspace", "tt_tree_gdn_bwd_workspace_min", "tt_tree_gdn_bwd",
             "tt_tree_attn_partitioned_workspace", "tt_tree_attn_partitioned_fwd", "tt_tree_attn_partitioned_bwd",
             "tt_tree_attn_workspace", "tt_tree_meta_sizes", "tt_last_error", "tt_version"} <= set(names)
     for n in names:
@@ -115,6 +115,11 @@ def test_gdn_calls_validate_before_launch():
     assert lib.tt_tree_gdn_workspace(nc, ns, hv) > 0
     assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, hk, hv) > lib.tt_tree_gdn_workspace(nc, ns, hv)
     assert lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 3, hk, hv) == lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, hk, hv) + 3 * hv * 128 * 128 * 4
+    least = lib.tt_tree_gdn_bwd_workspace_min(n, nc, ns, 0, hk, hv)
+    assert 0 < least < lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, hk, hv)       # one of the two key heads per pass
+    assert lib.tt_tree_gdn_bwd_workspace_min(n, nc, ns, 0, 1, hv) == lib.tt_tree_gdn_bwd_workspace(n, nc, ns, 0, 1, hv)
+    assert lib.tt_tree_gdn_bwd_workspace_min(n, nc, ns, 0, 3, hv) == 0           # hv not a multiple of hk
+    assert bwd(ws_bytes=least - 256) == -6
     assert fwd(dk=64) == -8 and bwd(dk=64) == -8             # only 128 x 128 states (TT_ERR_UNSUPPORTED)
     assert fwd(hv_=3) == -2 and bwd(hv_=3) == -2             # hv not a multiple of hk
     assert fwd(scale=0.0) == -2 and bwd(scale=float("nan")) == -2
