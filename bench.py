@@ -64,6 +64,8 @@ def parse_args():
     ap.add_argument("--other-configs-budget-s", type=float, default=150.0,
                     help="wall-clock budget for the other configurations; one that would start after it is skipped")
     ap.add_argument("--gdn-heads", type=int, default=32, help="value heads of the gated-delta-rule leg (key heads = half)")
+    ap.add_argument("--gdn-capped-workspace-mb", type=int, default=1000,
+                    help="also time the gated-delta-rule backward with its workspace capped at this size (0: skip)")
     ap.add_argument("--conv-channels", type=int, default=8192,
                     help="channels of the tree-convolution leg (2*16*128 + 32*128 for a GDN layer with 16 key / 32 value heads)")
     ap.add_argument("--partition-gather-all", action="store_true",
@@ -466,8 +468,8 @@ def leg_gdn(c):
                         "bwd_tflops": round(bwd_flop * gplan.n_chunks * ghv / (b_ms * 1e-3) / 1e12, 2),
                         "bwd_workspace_mb": round(bws.numel() / 1e6, 1)})
             # the same with the workspace capped at 1 GB: the call then takes the heads in passes of whole key-head groups
-            cap = 1_000_000_000
-            if T.tree_gdn_bwd_workspace(N, ghk, ghv, gplan, smallest=True) <= cap < bws.numel():
+            cap = args.gdn_capped_workspace_mb * 1_000_000
+            if cap > 0 and T.tree_gdn_bwd_workspace(N, ghk, ghv, gplan, smallest=True) <= cap < bws.numel():
                 small = bws[:cap]
                 for it in range(1 + n_it):
                     if it == 1:
