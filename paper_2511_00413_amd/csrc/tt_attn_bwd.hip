@@ -269,12 +269,16 @@ tree_attn_dq_kernel(AttnArgs a, int n_qtiles) {
   // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
   // longer than 262144 keys)
   KTileIter it;
+  // as in the forward kernel: tile 0 is nearly always the first tile delivered, so its copy is started before
+  // the classification and runs beside it (a wrong guess costs one wasted tile copy)
+  q_issue_tile(ctx, sm, buf, 0, w, lane);
   it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
-  // the first tile's copy is started before anything waits for the per-query operands, so that the
-  // memory round trips of the prologue (Q / dO / row terms, tile summaries, first tile) overlap
   int cls_cur = KT_FULL;
   int u_cur = it.next(cls_cur);
-  if (u_cur >= 0) q_issue_tile(ctx, sm, buf, u_cur, w, lane);
+  if (u_cur > 0) {
+    dma_wait_all();
+    q_issue_tile(ctx, sm, buf, u_cur, w, lane);
+  }
   // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the MFMAs
   // as the base-2 exponent
   {

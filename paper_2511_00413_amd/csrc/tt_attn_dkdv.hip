@@ -393,6 +393,17 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
     const int s_hi = min(s_lo + chunk, nq * G);
     const bool partial = pl.tile_nchunks[tile] > 1;
 
+    // steps are head-major: step s = (head kvh*G + s / nq, query tile qt_lo + s % nq)
+    int head = kvh * G + s_lo / nq;
+    int qi = s_lo % nq;
+    // the first step's tiles are requested first, so that their round trip runs beside those of the visibility bounds and the K / V fragments
+    // (both stages are free: every wave has passed the barrier behind the previous item's last step)
+    {
+      int lane_o = lane;
+      asm volatile("" : "+v"(lane_o));
+      kv_issue(a, sm, buf, head, (qt_lo + qi) * KV_BM, w, lane_o);
+    }
+
     const int e0 = pl.tile_e0[tile];
     const int n_keys = pl.tile_ne[tile] * 64;        // keys of the tile (the last entry of a region may be ragged)
     const bool is_prefix = e0 < pl.np64;
@@ -440,21 +451,11 @@ tree_attn_dkdv_kernel(AttnArgs a, KvPlan pl) {
 #pragma unroll
     for (int db = 0; db < 4; db++) { dk_acc[db] = zero16(); dv_acc[db] = zero16(); }
 
-    // steps are head-major: step s = (head kvh*G + s / nq, query tile qt_lo + s % nq)
-    int head = kvh * G + s_lo / nq;
-    int qi = s_lo % nq;
-
     // every register loaded from global memory is consumed here, so that no wait for it (which would
     // also wait for the tile copies in flight) lands inside the step loop
 #pragma unroll
     for (int s = 0; s < KV_KREG; s++) pin(kf[s]);
     pin(q_lim);
-
-    {
-      int lane_o = lane;
-      asm volatile("" : "+v"(lane_o));
-      kv_issue(a, sm, buf, head, (qt_lo + qi) * KV_BM, w, lane_o);
-    }
     dma_wait_all();
     __syncthreads();
 

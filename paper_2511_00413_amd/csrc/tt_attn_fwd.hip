@@ -279,12 +279,18 @@ tree_attn_fwd_kernel(AttnArgs a, int n_qtiles) {
   // candidate tiles are classified in chunks of 64 * KT_MAX_WIN (one chunk unless the sequence is
   // longer than 262144 keys)
   KTileIter it;
+  // The copy of tile 0 is started before the tile summaries have even been requested: a root's first keys are
+  // visible to every later query, so tile 0 is nearly always the first tile delivered, and its round trip then runs
+  // beside the classification's instead of behind it (and beside the Q fragments').  A wrong guess (several roots,
+  // a prefix whose first tile is hidden) costs one wasted tile copy: the right tile is fetched over it.
+  issue_tile(ctx, sm, buf, 0, w, lane);
   it.fill(&sm.masks, a.kt_max, a.kt_min, 0, u_end, gi_first, gi_last, npt, P, N, w, NTHREADS / 64);
-  // the first tile's copy is started before anything waits for the Q fragments, so that the memory
-  // round trips of the prologue (Q, tile summaries, first tile) overlap
   int cls_cur = KT_FULL;
   int u_cur = it.next(cls_cur);
-  if (u_cur >= 0) issue_tile(ctx, sm, buf, u_cur, w, lane);
+  if (u_cur > 0) {
+    dma_wait_all();                        // this wave's rows of the guessed tile have landed; they are overwritten
+    issue_tile(ctx, sm, buf, u_cur, w, lane);
+  }
   {
     // Q is multiplied by scale * log2(e) once (rounded to bf16 again), so that S comes out of the
     // MFMAs as a base-2 exponent
