@@ -54,6 +54,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-linearized", action="store_true")
     ap.add_argument("--no-loss", action="store_true")
+    ap.add_argument("--loss-two-pass", action="store_true",
+                    help="loss forward and backward as two calls (two reads of the logits) instead of the one-pass call")
     ap.add_argument("--no-rope", action="store_true")
     ap.add_argument("--no-partitioned", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
@@ -103,7 +105,7 @@ class PathRun:
     the forward, after the backward, after the inverse rotation and after the loss."""
 
     def __init__(self, T, torch, dev, dims, tree, n_prefix, prefix_visible, root_off, q_raw, k_raw, v, do, kp=None, vp=None,
-                 logits=None, target=None, weight=None, do_rope=True):
+                 logits=None, target=None, weight=None, do_rope=True, loss_one_pass=True):
         self.T, self.torch, self.dims, self.tree = T, torch, dims, tree
         self.n_prefix, self.prefix_visible, self.root_off = n_prefix, prefix_visible, root_off
         self.meta = self.build_meta()
@@ -135,6 +137,7 @@ class PathRun:
         self.dq, self.dk, self.dv = torch.empty_like(q_raw), torch.empty_like(k_raw), torch.empty_like(v)
         self.logits, self.target = logits, target
         self.do_loss = logits is not None
+        self.loss_one_pass = loss_one_pass
         if self.do_loss:
             self.logp = torch.empty(N, dtype=torch.float32, device=dev)
             self.lse_l = torch.empty(N, dtype=torch.float32, device=dev)
@@ -190,10 +193,14 @@ class PathRun:
             rows = self.logits.shape[0]
             for lo in range(0, N, rows):
                 n = min(rows, N - lo)
-                T.tree_weighted_logprob(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], loss_acc=self.loss_acc,
-                                        logp=self.logp[lo:lo + n], lse=self.lse_l[lo:lo + n])
-                T.tree_weighted_logprob_bwd(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], self.lse_l[lo:lo + n],
-                                            out=self.dlogits[:n])
+                if self.loss_one_pass:
+                    T.tree_weighted_logprob_fwd_bwd(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], loss_acc=self.loss_acc,
+                                                    logp=self.logp[lo:lo + n], lse=self.lse_l[lo:lo + n], out=self.dlogits[:n])
+                else:
+                    T.tree_weighted_logprob(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], loss_acc=self.loss_acc,
+                                            logp=self.logp[lo:lo + n], lse=self.lse_l[lo:lo + n])
+                    T.tree_weighted_logprob_bwd(self.logits[:n], self.target[lo:lo + n], w_d[lo:lo + n], self.lse_l[lo:lo + n],
+                                                out=self.dlogits[:n])
         if events:
             events[5].record()
 
@@ -231,7 +238,7 @@ def linearized_run(T, torch, dev, dims, run: PathRun, linearize):
         g_tok = torch.from_numpy(run.meta.node_g[run.meta.tok_node].astype(np.float32)).to(dev)
         wl = (run.w_d / g_tok).index_select(0, idx_d)
     lin = PathRun(T, torch, dev, dims, forest, 0, None, None, ql, kl, vl, dol, logits=run.logits, target=tl, weight=wl,
-                  do_rope=run.do_rope)
+                  do_rope=run.do_rope, loss_one_pass=run.loss_one_pass)
     return lin, idx
 
 
@@ -243,7 +250,7 @@ def speedup_record(ms_tree, ms_lin, run: PathRun, lin: PathRun, pairs, pairs_lin
            "speedup_over_r_tok": round(attn_l / attn_t / r_tok, 3), "speedup_over_r_pair": round(attn_l / attn_t / r_pair, 3),
            # the whole device path (rotary embedding, attention, inverse rotation, loss forward + backward): the
            # token-linear steps speed up by r_tok, the attention by at most r_pair
-           "path": {"steps": "rope + attn fwd + attn bwd + inverse rope" + (" + loss fwd + loss bwd" if run.do_loss else ""),
+           "path": {"steps": "rope + attn fwd + attn bwd + inverse rope" + ((" + loss fwd and bwd in one pass" if run.loss_one_pass else " + loss fwd + loss bwd") if run.do_loss else ""),
                     "ms_tree": round(ms_tree["path"], 4), "ms_linearized": round(ms_lin["path"], 4),
                     "speedup": round(ms_lin["path"] / ms_tree["path"], 3),
                     "speedup_over_r_tok": round(ms_lin["path"] / ms_tree["path"] / r_tok, 3),
@@ -354,7 +361,7 @@ def leg_partitioned(c):
                 "ms_fwd_bwd_per_step": [round(x, 3) for x in per_step],
                 "ms_whole_fwd_bwd": round(ms_fwd + ms_bwd, 4),
                 "ratio_to_whole": round(ms_part / (ms_fwd + ms_bwd), 3),
-                "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
+                "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
                 "ms_gather": round(pt["part_gather"][0] / n_it, 4), "ms_scatter": round(pt["part_scatter"][0] / n_it, 4),
                 "movement_gb": round((gather_b + scatter_b) / 1e9, 4),
                 "movement_hbm_gbps": round((gather_b + scatter_b) / (move_ms * 1e-3) / 1e9, 1) if move_ms > 0 else None,
@@ -557,7 +564,7 @@ def main():
         gen.manual_seed(cfg * 1000 + 6)
         target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
     run = PathRun(T, torch, dev, dims, tree, n_prefix, prefix_visible, root_off, q, k, v, do, kp, vp, logits, target,
-                  do_rope=not args.no_rope)
+                  do_rope=not args.no_rope, loss_one_pass=not args.loss_two_pass)
     meta = run.meta
     pairs = linearize.visible_pairs(meta)
 
@@ -593,13 +600,31 @@ def main():
                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
                     "avg_ms": round(avg_ms, 4), "launches_timed": attn_k[dom][1],
                     "algorithmic_flop_per_launch": alg_flop[dom] * dims.hq * dims.d * pairs}
-    loss_gbps = loss_bwd_gbps = None
-    if do_loss and "loss_rows" in kernel_ms:
+    loss_gbps = loss_bwd_gbps = loss_fused_gbps = None
+    if do_loss:
         esz = 2 if dims.logit_dtype == "bf16" else 4
-        bytes_total = N * (dims.vocab * esz + 12)
-        loss_gbps = bytes_total / (ktimes["loss_rows"][0] / k_steps * 1e-3) / 1e9
+        if "loss_fused" in kernel_ms:
+            # one read of the logits + one write of the gradient + target, weight in, logp, lse out per row
+            loss_fused_gbps = N * (2 * dims.vocab * esz + 16) / (ktimes["loss_fused"][0] / k_steps * 1e-3) / 1e9
+            # the two separate kernels on the same rows, outside the step, for their own figures
+            T.kernel_timing_enable(True)
+            rows = run.logits.shape[0]
+            for _ in range(3):
+                for lo in range(0, N, rows):
+                    n = min(rows, N - lo)
+                    T.tree_weighted_logprob(run.logits[:n], run.target[lo:lo + n], run.w_d[lo:lo + n], loss_acc=run.loss_acc,
+                                            logp=run.logp[lo:lo + n], lse=run.lse_l[lo:lo + n])
+                    T.tree_weighted_logprob_bwd(run.logits[:n], run.target[lo:lo + n], run.w_d[lo:lo + n], run.lse_l[lo:lo + n],
+                                                out=run.dlogits[:n])
+            torch.cuda.synchronize()
+            lt = T.kernel_timing_read()
+            T.kernel_timing_enable(False)
+            t_rows, t_bwd = lt["loss_rows"][0] / 3, lt["loss_bwd"][0] / 3
+        else:
+            t_rows, t_bwd = ktimes["loss_rows"][0] / k_steps, ktimes["loss_bwd"][0] / k_steps
+        loss_gbps = N * (dims.vocab * esz + 12) / (t_rows * 1e-3) / 1e9
         # backward: one read of the logits + one write of the gradient + target, weight, lse per row
-        loss_bwd_gbps = N * (2 * dims.vocab * esz + 12) / (ktimes["loss_bwd"][0] / k_steps * 1e-3) / 1e9
+        loss_bwd_gbps = N * (2 * dims.vocab * esz + 12) / (t_bwd * 1e-3) / 1e9
     rope_gbps = None
     if run.do_rope and "rope" in kernel_ms:
         rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * 2 * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
@@ -661,6 +686,8 @@ def main():
         "rope_frac_of_hbm_peak": None if rope_gbps is None else round(rope_gbps / PEAK_HBM_GBPS, 4),
         "loss_bwd_hbm_gbps": None if loss_bwd_gbps is None else round(loss_bwd_gbps, 1),
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
+        "loss_one_pass_hbm_gbps": None if loss_fused_gbps is None else round(loss_fused_gbps, 1),
+        "loss_one_pass_frac_of_hbm_peak": None if loss_fused_gbps is None else round(loss_fused_gbps / PEAK_HBM_GBPS, 4),
         "linearized": lin,
         "partitioned": part,
         "tree_conv": conv,

@@ -370,6 +370,27 @@ tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab, int32_t dt
                                        void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * tt_tree_weighted_logprob_fwd_bwd (device)
+ *
+ * tt_tree_weighted_logprob and tt_tree_weighted_logprob_bwd in one pass, for the training step
+ * that wants the loss of Eq. 4 and its gradient together: the logits are read from memory once
+ * (a row stays on chip between the log-softmax statistics and the gradient; of a row longer than
+ * 64 KB the rest is read a second time right behind the first).  Same results as the two calls
+ * (the row sums are added in a different order: lse and logp agree to rounding).
+ *   Arguments as for the two calls; logp and lse [n_rows] fp32 are both required; loss_acc may be
+ *   NULL; grad_scale must be known beforehand (it usually is: 1, or 1 / accumulation steps).
+ *   dlogits may alias logits when the strides are equal.
+ * Alignment: when the logits' and the gradient's rows all start on 16-byte boundaries (aligned
+ *   bases, row strides a multiple of 16 bytes) the one-pass kernel runs; otherwise the call runs
+ *   the two passes one after the other.
+ * ------------------------------------------------------------------------------------------ */
+tt_status tt_tree_weighted_logprob_fwd_bwd(int64_t n_rows, int32_t vocab, int32_t dtype,
+                                           const void* logits, int64_t row_stride,
+                                           const int32_t* target, const float* weight, float grad_scale,
+                                           float* logp, float* lse, float* loss_acc,
+                                           void* dlogits, int64_t dlogits_row_stride, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * tt_tree_rope (device)
  *
  * Rotary position embedding of a [n_tokens][n_heads][d] tensor (Q or K) with the tree position ids
@@ -595,7 +616,7 @@ tt_status tt_tree_gdn_bwd(int64_t n_tokens, int32_t hk, int32_t hv, int32_t dk, 
  * the recorded events have completed and returns the totals since the last enable.
  * ------------------------------------------------------------------------------------------ */
 #define TT_KERNEL_ATTN_FWD    0   /* bf16 MFMA forward                                   */
-#define TT_KERNEL_ATTN_DELTA  1   /* (unused: the dQ kernel forms rowsum(dO o O) itself)  */
+#define TT_KERNEL_LOSS_FUSED  1   /* loss forward + gradient in one pass over the logits  */
 #define TT_KERNEL_ATTN_DKDV   2   /* bf16 MFMA dK/dV                                     */
 #define TT_KERNEL_ATTN_DQ     3   /* bf16 MFMA dQ                                        */
 #define TT_KERNEL_LOSS_ROWS   4   /* log-softmax + gather, one pass over the logits      */

@@ -92,6 +92,9 @@ def _lib() -> ctypes.CDLL:
         lib.tt_tree_weighted_logprob_bwd.restype = ctypes.c_int32
         lib.tt_tree_weighted_logprob_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                                      _vp, _vp, _vp, ctypes.c_float, _vp, ctypes.c_int64, _vp]
+        lib.tt_tree_weighted_logprob_fwd_bwd.restype = ctypes.c_int32
+        lib.tt_tree_weighted_logprob_fwd_bwd.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
+                                                         _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, ctypes.c_int64, _vp]
         lib.tt_tree_rope.restype = ctypes.c_int32
         lib.tt_tree_rope.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, ctypes.c_int64,
                                      _vp, ctypes.c_float, ctypes.c_int32, _vp, ctypes.c_int64, _vp]
@@ -154,7 +157,7 @@ def _lib() -> ctypes.CDLL:
     return _LIB
 
 
-KERNEL_NAMES = ("attn_fwd", "attn_delta", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
+KERNEL_NAMES = ("attn_fwd", "loss_fused", "attn_dkdv", "attn_dq", "loss_rows", "loss_sum", "ref_fwd", "ref_bwd",
                 "attn_plan", "attn_reduce", "loss_bwd", "rope", "part_gather", "part_scatter", "conv_fwd", "conv_bwd", "conv_fix", "gdn_prepare", "gdn_scan",
                 "gdn_bwd_fscan", "gdn_bwd_rscan", "gdn_bwd_finish")
 
@@ -617,6 +620,34 @@ def tree_weighted_logprob_bwd(logits, target, weight, lse, *, grad_scale: float 
         logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), _dp(lse), float(grad_scale), _dp(out),
         out.stride(0) if n > 1 else vocab, _stream_ptr(stream)))
     return out
+
+
+def tree_weighted_logprob_fwd_bwd(logits, target, weight=None, *, grad_scale: float = 1.0, loss_acc=None, logp=None,
+                                  lse=None, out=None, stream=None):
+    """tree_weighted_logprob and tree_weighted_logprob_bwd in one pass over the logits.  Returns (logp [n], lse [n],
+    loss_acc [1] (added to; zeroed if created here), dlogits like logits); `out` may be the logits tensor itself."""
+    torch = _torch()
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [rows, vocab] with contiguous vocab")
+    if logits.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("logits must be bf16 or fp32")
+    n, vocab = logits.shape
+    dev = logits.device
+    if logp is None:
+        logp = torch.empty(n, dtype=torch.float32, device=dev)
+    if lse is None:
+        lse = torch.empty(n, dtype=torch.float32, device=dev)
+    if loss_acc is None:
+        loss_acc = torch.zeros(1, dtype=torch.float32, device=dev)
+    if out is None:
+        out = torch.empty((n, vocab), dtype=logits.dtype, device=dev)
+    if out.shape != logits.shape or out.dtype != logits.dtype or out.stride(1) != 1:
+        raise ValueError("out must match logits in shape and dtype, with contiguous vocab")
+    _check(_lib().tt_tree_weighted_logprob_fwd_bwd(
+        n, vocab, DTYPE_BF16 if logits.dtype == torch.bfloat16 else DTYPE_FP32, _dp(logits),
+        logits.stride(0) if n > 1 else vocab, _dp(target), _dp(weight), float(grad_scale), _dp(logp), _dp(lse), _dp(loss_acc),
+        _dp(out), out.stride(0) if n > 1 else vocab, _stream_ptr(stream)))
+    return logp, lse, loss_acc, out
 
 
 def tree_attn_partitioned_workspace(q, k, v, plan: PartitionPlan, backward: bool = False, scale=None,

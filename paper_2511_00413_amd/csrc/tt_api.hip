@@ -183,6 +183,42 @@ extern "C" tt_status tt_tree_weighted_logprob_bwd(int64_t n_rows, int32_t vocab,
                     "tree_weighted_logprob_bwd");
 }
 
+extern "C" tt_status tt_tree_weighted_logprob_fwd_bwd(int64_t n_rows, int32_t vocab, int32_t dtype, const void* logits,
+                                                      int64_t row_stride, const int32_t* target, const float* weight,
+                                                      float grad_scale, float* logp, float* lse, float* loss_acc,
+                                                      void* dlogits, int64_t dlogits_row_stride, void* stream) {
+  tt::clear_error();
+  if (dtype != TT_DTYPE_BF16 && dtype != TT_DTYPE_FP32) return fail(TT_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (n_rows < 0 || n_rows > 0x7fffffffLL) return fail(TT_ERR_SHAPE, "n_rows=%lld out of range", (long long)n_rows);
+  if (vocab <= 0) return fail(TT_ERR_SHAPE, "vocab=%d must be positive", vocab);
+  if (row_stride == 0) row_stride = vocab;
+  if (dlogits_row_stride == 0) dlogits_row_stride = vocab;
+  if (row_stride < vocab || dlogits_row_stride < vocab)
+    return fail(TT_ERR_SHAPE, "row strides %lld / %lld are smaller than vocab=%d", (long long)row_stride,
+                (long long)dlogits_row_stride, vocab);
+  if (!std::isfinite(grad_scale)) return fail(TT_ERR_SHAPE, "grad_scale must be finite");
+  if (n_rows > 0 && (!logits || !target || !logp || !lse || !dlogits))
+    return fail(TT_ERR_NULL, "logits / target / logp / lse / dlogits is NULL");
+  if (dlogits == logits && dlogits_row_stride != row_stride)
+    return fail(TT_ERR_SHAPE, "dlogits may alias logits only with equal row strides");
+  const size_t es = dtype == TT_DTYPE_BF16 ? 2 : 4;
+  if (reinterpret_cast<uintptr_t>(logits) % es || reinterpret_cast<uintptr_t>(dlogits) % es)
+    return fail(TT_ERR_ALIGN, "logits / dlogits is not aligned to its element size");
+  const bool bf16 = dtype == TT_DTYPE_BF16;
+  hipStream_t st = (hipStream_t)stream;
+  if (tt::weighted_logprob_fused_ok(bf16, logits, row_stride, dlogits, dlogits_row_stride))
+    return hip_result(tt::weighted_logprob_fused(n_rows, vocab, bf16, logits, row_stride, target, weight, grad_scale, logp, lse,
+                                                 loss_acc, dlogits, dlogits_row_stride, st),
+                      "tree_weighted_logprob_fwd_bwd");
+  // rows off the 16-byte grid: the two passes one after the other
+  if (tt_status s = hip_result(tt::weighted_logprob(n_rows, vocab, bf16, logits, row_stride, target, weight, logp, lse, loss_acc, st),
+                               "tree_weighted_logprob_fwd_bwd (forward pass)"))
+    return s;
+  return hip_result(tt::weighted_logprob_bwd(n_rows, vocab, bf16, logits, row_stride, target, weight, lse, grad_scale, dlogits,
+                                             dlogits_row_stride, st),
+                    "tree_weighted_logprob_fwd_bwd (backward pass)");
+}
+
 extern "C" tt_status tt_tree_rope(int64_t n_tokens, int32_t n_heads, int32_t d, int32_t dtype, const void* x,
                                   int64_t x_stride_tok, const int32_t* tok_pos, float theta_base, int32_t inverse,
                                   void* y, int64_t y_stride_tok, void* stream) {

@@ -62,6 +62,13 @@ hipError_t weighted_logprob_bwd(int64_t n_rows, int vocab, bool bf16, const void
                                 const int32_t* target, const float* weight, const float* lse, float grad_scale,
                                 void* dlogits, int64_t out_stride, hipStream_t st);
 
+// both in one pass over the logits; weighted_logprob_fused_ok tells whether the pointers and strides allow it (rows of
+// the logits and of the gradient on 16-byte boundaries)
+bool weighted_logprob_fused_ok(bool bf16, const void* logits, int64_t row_stride, const void* dlogits, int64_t out_stride);
+hipError_t weighted_logprob_fused(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                                  const int32_t* target, const float* weight, float grad_scale, float* logp, float* lse,
+                                  float* loss_acc, void* dlogits, int64_t out_stride, hipStream_t st);
+
 // rotary position embedding (tt_rope.hip); strides in elements
 hipError_t rope(int64_t n_tokens, int n_heads, int d, bool bf16, const void* x, int64_t x_stride, const int32_t* pos,
                 float theta_base, bool inverse, void* y, int64_t y_stride, hipStream_t st);

@@ -244,7 +244,161 @@ row_dlogits_kernel(int vocab, const T* logits, int64_t row_stride, const int32_t
     }
 }
 
+// ---- forward and backward in one pass ----------------------------------------------------------------
+// When the gradient is wanted together with the loss (the usual training step), a row is read from memory
+// once: the workgroup streams it, keeps its first `lds_vecs` 16-byte vectors in LDS while it accumulates
+// (max, sum of exp), and then forms the gradient from that copy; what did not fit (a vocabulary beyond
+// FUSED_LDS_BYTES per row) is read a second time, right behind the first read, so that it mostly comes out of
+// the caches.  Both the row and the gradient row must start on a 16-byte boundary (the host checks that and
+// uses the two separate kernels otherwise).  Same arithmetic per element as the separate kernels.
+constexpr int FUSED_THREADS = 512;
+constexpr int FUSED_LDS_BYTES = 64 * 1024;             // two workgroups per compute unit
+
+template <typename T>
+__global__ void __launch_bounds__(FUSED_THREADS)
+row_logprob_dlogits_kernel(int vocab, const T* logits, int64_t row_stride, const int32_t* __restrict__ target,
+                           const float* __restrict__ weight, float grad_scale, float* __restrict__ logp,
+                           float* __restrict__ lse_out, T* dlogits, int64_t out_stride, int lds_vecs) {
+  constexpr int EPV = 16 / sizeof(T);
+  extern __shared__ u32x4 rowbuf[];
+  __shared__ MS part[FUSED_THREADS / 64];
+  __shared__ float row_stat[2];                        // max, ln(sum)
+  const int64_t r = blockIdx.x;
+  const T* row = logits + r * row_stride;
+  T* out = dlogits + r * out_stride;
+  const int t = threadIdx.x;
+  const int nvec = vocab / EPV;
+  const u32x4* vp = reinterpret_cast<const u32x4*>(row);
+  u32x4* op = reinterpret_cast<u32x4*>(out);
+  const int y = target[r];
+  const bool used = y >= 0 && y < vocab;
+  const float w = used ? grad_scale * (weight ? weight[r] : 1.f) : 0.f;
+
+  // ---- pass 1: statistics; the part of the row that is kept goes to LDS ----
+  MS st = {-INFINITY, 0.f};
+  auto push_vec = [&](const u32x4& v) {
+    if constexpr (sizeof(T) == 2) {
+      float z[8];
+      unpack8(v, z);
+      push8(st, z);
+    } else {
+      push1(st, __uint_as_float(v.x)); push1(st, __uint_as_float(v.y));
+      push1(st, __uint_as_float(v.z)); push1(st, __uint_as_float(v.w));
+    }
+  };
+  const int n_kept = min(nvec, lds_vecs);
+  {
+    int i = t;
+    for (; i + 3 * FUSED_THREADS < n_kept; i += 4 * FUSED_THREADS) {      // 4 loads in flight per thread
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      const u32x4 v1 = __builtin_nontemporal_load(vp + i + FUSED_THREADS);
+      const u32x4 v2 = __builtin_nontemporal_load(vp + i + 2 * FUSED_THREADS);
+      const u32x4 v3 = __builtin_nontemporal_load(vp + i + 3 * FUSED_THREADS);
+      rowbuf[i] = v0; rowbuf[i + FUSED_THREADS] = v1; rowbuf[i + 2 * FUSED_THREADS] = v2; rowbuf[i + 3 * FUSED_THREADS] = v3;
+      push_vec(v0); push_vec(v1); push_vec(v2); push_vec(v3);
+    }
+    for (; i < n_kept; i += FUSED_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      rowbuf[i] = v0;
+      push_vec(v0);
+    }
+  }
+  {
+    int i = n_kept + t;                                 // the rest: ordinary loads, they are wanted again soon
+    for (; i + 3 * FUSED_THREADS < nvec; i += 4 * FUSED_THREADS) {
+      const u32x4 v0 = vp[i], v1 = vp[i + FUSED_THREADS], v2 = vp[i + 2 * FUSED_THREADS], v3 = vp[i + 3 * FUSED_THREADS];
+      push_vec(v0); push_vec(v1); push_vec(v2); push_vec(v3);
+    }
+    for (; i < nvec; i += FUSED_THREADS) push_vec(vp[i]);
+  }
+  for (int e = nvec * EPV + t; e < vocab; e += FUSED_THREADS) push1(st, elem(row, e));
+  for (int o = 32; o > 0; o >>= 1) {
+    MS other = {__shfl_xor(st.m, o), __shfl_xor(st.s, o)};
+    st = merge(st, other);
+  }
+  if ((t & 63) == 0) part[t >> 6] = st;
+  __syncthreads();
+  if (t == 0) {
+    MS a = part[0];
+    for (int wv = 1; wv < FUSED_THREADS / 64; wv++) a = merge(a, part[wv]);
+    const float ln_s = LN2 * log2f(a.s);
+    row_stat[0] = a.m; row_stat[1] = ln_s;
+    logp[r] = used ? (elem(row, y) - a.m) - ln_s : 0.f;
+    if (lse_out) lse_out[r] = a.m + ln_s;
+  }
+  __syncthreads();                                      // also: every kept vector is in LDS
+  // an ignored row gets an exactly zero gradient whatever its logits are (weight 0, lse = +inf)
+  const float lse = used ? row_stat[0] + row_stat[1] : INFINITY;
+
+  // ---- pass 2: gradient ----
+  auto grad = [&](const u32x4& v, int i) {
+    if constexpr (sizeof(T) == 2) return grad_vec_bf16(v, lse, w, i * EPV, y);
+    else return grad_vec_f32(v, lse, w, i * EPV, y);
+  };
+  for (int i = t; i < n_kept; i += FUSED_THREADS) __builtin_nontemporal_store(grad(rowbuf[i], i), op + i);
+  {
+    int i = n_kept + t;
+    for (; i + 3 * FUSED_THREADS < nvec; i += 4 * FUSED_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      const u32x4 v1 = __builtin_nontemporal_load(vp + i + FUSED_THREADS);
+      const u32x4 v2 = __builtin_nontemporal_load(vp + i + 2 * FUSED_THREADS);
+      const u32x4 v3 = __builtin_nontemporal_load(vp + i + 3 * FUSED_THREADS);
+      __builtin_nontemporal_store(grad(v0, i), op + i);
+      __builtin_nontemporal_store(grad(v1, i + FUSED_THREADS), op + i + FUSED_THREADS);
+      __builtin_nontemporal_store(grad(v2, i + 2 * FUSED_THREADS), op + i + 2 * FUSED_THREADS);
+      __builtin_nontemporal_store(grad(v3, i + 3 * FUSED_THREADS), op + i + 3 * FUSED_THREADS);
+    }
+    for (; i < nvec; i += FUSED_THREADS) {
+      const u32x4 v0 = __builtin_nontemporal_load(vp + i);
+      __builtin_nontemporal_store(grad(v0, i), op + i);
+    }
+  }
+  for (int e = nvec * EPV + t; e < vocab; e += FUSED_THREADS) {
+    const float g = w * ex2((elem(row, e) - lse) * LOG2E) - (e == y ? w : 0.f);
+    store_elem(out, e, g);
+  }
+}
+
 }  // namespace
+
+bool weighted_logprob_fused_ok(bool bf16, const void* logits, int64_t row_stride, const void* dlogits, int64_t out_stride) {
+  const int esz = bf16 ? 2 : 4;
+  return ((reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(dlogits)) & 15) == 0 && (row_stride * esz) % 16 == 0 &&
+         (out_stride * esz) % 16 == 0;
+}
+
+hipError_t weighted_logprob_fused(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
+                                  const int32_t* target, const float* weight, float grad_scale, float* logp, float* lse,
+                                  float* loss_acc, void* dlogits, int64_t out_stride, hipStream_t st) {
+  if (n_rows == 0) return hipSuccess;
+  const int nvec = vocab / (bf16 ? 8 : 4);
+  const int lds_vecs = std::min(nvec, FUSED_LDS_BYTES / 16);
+  const size_t lds = (size_t)lds_vecs * 16;
+  {
+    KernelTimer timer(TT_KERNEL_LOSS_FUSED, st);
+    if (bf16) {
+      if (hipError_t e = hipFuncSetAttribute((const void*)row_logprob_dlogits_kernel<__hip_bfloat16>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, FUSED_LDS_BYTES))
+        return e;
+      row_logprob_dlogits_kernel<__hip_bfloat16><<<(unsigned)n_rows, FUSED_THREADS, lds, st>>>(
+          vocab, (const __hip_bfloat16*)logits, row_stride, target, weight, grad_scale, logp, lse, (__hip_bfloat16*)dlogits,
+          out_stride, lds_vecs);
+    } else {
+      if (hipError_t e = hipFuncSetAttribute((const void*)row_logprob_dlogits_kernel<float>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, FUSED_LDS_BYTES))
+        return e;
+      row_logprob_dlogits_kernel<float><<<(unsigned)n_rows, FUSED_THREADS, lds, st>>>(
+          vocab, (const float*)logits, row_stride, target, weight, grad_scale, logp, lse, (float*)dlogits, out_stride, lds_vecs);
+    }
+  }
+  if (hipError_t e = hipGetLastError()) return e;
+  if (loss_acc) {
+    KernelTimer timer(TT_KERNEL_LOSS_SUM, st);
+    weighted_sum_kernel<<<1, 1024, 0, st>>>(n_rows, logp, weight, target, loss_acc);
+    return hipGetLastError();
+  }
+  return hipSuccess;
+}
 
 hipError_t weighted_logprob(int64_t n_rows, int vocab, bool bf16, const void* logits, int64_t row_stride,
                             const int32_t* target, const float* weight, float* logp, float* lse,

@@ -207,3 +207,110 @@ def test_general_path_weights_against_branch_by_branch_loss(scheme):
     print(f"[case] loss with general path weights, scheme {scheme}, N={n}, K={K}", flush=True)
     _, _, loss = _run(logits, target, lam)
     assert abs(loss - want) <= 1e-3 * max(abs(want), 1e-6), (loss, want)
+
+
+# ---- forward and backward in one pass over the logits ---------------------------------------------
+# Same bounds as the two separate calls: the one-pass kernel does the same arithmetic per element and only
+# adds the row's partial sums in another order (512 instead of 256 threads), so lse / logp may differ from
+# the separate call's in the last bit.
+
+def _check_fused(logits, target, weight, grad_scale=1.0, inplace=False, stride_pad=0):
+    rows, vocab = logits.shape
+    print(f"[case] loss fwd+bwd rows={rows} vocab={vocab} {logits.dtype} inplace={inplace} pad={stride_pad}", flush=True)
+    if stride_pad:
+        buf = torch.zeros(rows, vocab + stride_pad, dtype=logits.dtype, device="cuda")
+        buf[:, :vocab] = logits.cuda()
+        lg = buf[:, :vocab]
+    else:
+        lg = logits.cuda()
+    tg = target.cuda()
+    wt = None if weight is None else torch.from_numpy(weight).cuda()
+    sep_logp, sep_lse, sep_loss = T.tree_weighted_logprob(lg, tg, wt)
+    sep_grad = T.tree_weighted_logprob_bwd(lg, tg, wt, sep_lse, grad_scale=grad_scale)
+    src = lg.clone() if inplace else lg
+    logp, lse, loss, got = T.tree_weighted_logprob_fwd_bwd(src, tg, wt, grad_scale=grad_scale, out=src if inplace else None)
+    torch.cuda.synchronize()
+    atol = (4e-6 if logits.dtype == torch.bfloat16 else 2e-6) * max(1.0, np.log(vocab))
+    wl, wlse = L.log_softmax_gather(logits, target.numpy())
+    assert np.abs(lse.cpu().numpy().astype(np.float64) - wlse).max() <= atol
+    assert np.abs(logp.cpu().numpy().astype(np.float64) - wl).max() <= atol
+    w = np.ones(rows) if weight is None else weight
+    want_loss = L.loss_tree(wl, w)
+    assert abs(float(loss.item()) - want_loss) <= 1e-3 * max(abs(want_loss), 1e-6)
+    g = got.float().cpu().numpy().astype(np.float64)
+    want = L.dlogits(logits, target.numpy(), weight, grad_scale=grad_scale)
+    num, den = np.sqrt(((g - want) ** 2).sum()), max(np.sqrt((want ** 2).sum()), 1e-30)
+    if logits.dtype == torch.bfloat16:
+        assert num / den <= 4e-3, num / den
+        assert np.all(np.abs(g - want) <= 2.0 ** -8 * np.abs(want) + 1e-7 * np.abs(want).max())
+    else:
+        assert num / den <= 1e-5, num / den
+    ign = (target.numpy() < 0) | (target.numpy() >= vocab)
+    assert np.all(g[ign] == 0.0) and np.all(logp.cpu().numpy()[ign] == 0.0)
+    # against the two separate calls: statistics to the last bits, gradient to one rounding of the output
+    assert torch.allclose(lse, sep_lse, rtol=0, atol=atol) and torch.allclose(logp, sep_logp, rtol=0, atol=atol)
+    assert abs(float(loss.item()) - float(sep_loss.item())) <= 1e-5 * max(abs(want_loss), 1e-6)
+    gs = sep_grad.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(g - gs) <= 2.0 ** -7 * np.abs(gs) + 1e-7 * np.abs(gs).max())
+
+
+@pytest.mark.parametrize("rows,vocab,dtype", [(37, 32768, "bf16"),      # a row fills the LDS copy exactly
+                                              (5, 151936, "bf16"),      # longer than the copy: the rest is read twice
+                                              (21, 40000, "bf16"), (64, 777, "bf16"), (300, 5000, "bf16"), (9, 1, "bf16"),
+                                              (33, 1001, "fp32"), (3, 8, "fp32"), (16, 4096, "fp32"), (6, 20000, "fp32")])
+def test_fwd_bwd_one_pass(rows, vocab, dtype):
+    logits, target = W.loss_inputs(rows, vocab, 5 * rows + vocab, 2.0, dtype)
+    target = target.clone()
+    if rows > 2:
+        target[1] = -1
+        target[2] = vocab            # out of range: ignored as well
+    w = (np.random.default_rng(rows).random(rows) + 0.25).astype(np.float32)
+    _check_fused(logits, target, w, grad_scale=0.5)
+
+
+def test_fwd_bwd_one_pass_in_place_and_strides():
+    logits, target = W.loss_inputs(40, 4096, 77, 2.0, "bf16")
+    w = (np.random.default_rng(3).random(40) + 0.25).astype(np.float32)
+    _check_fused(logits, target, w, inplace=True)
+    _check_fused(logits, target, None, stride_pad=24)        # rows stay on the 16-byte grid: one-pass kernel
+    _check_fused(logits, target, w, stride_pad=3)            # rows off the grid: the call runs the two passes
+    logits, target = W.loss_inputs(12, 1000, 78, 1.0, "fp32")
+    _check_fused(logits, target, w[:12], inplace=True, grad_scale=2.0)
+
+
+def test_fwd_bwd_one_pass_special_rows_and_chunks():
+    V = 4096
+    z = torch.zeros(6, V)
+    z[0, 5] = 80.0
+    z[1] = 0.25
+    z[2] = -1e4; z[2, 9] = -9990.0
+    z[3, :100] = float("-inf")
+    z[4] = 3e4
+    tgt = torch.tensor([5, 17, 9, 200, 0, -1], dtype=torch.int32)
+    logp, lse, loss, grad = T.tree_weighted_logprob_fwd_bwd(z.cuda(), tgt.cuda())
+    torch.cuda.synchronize()
+    wl, _ = L.log_softmax_gather(z, tgt.numpy())
+    assert np.allclose(logp.cpu().numpy(), wl, rtol=1e-6, atol=1e-5) and np.isfinite(grad.cpu().numpy()).all()
+    want = L.dlogits(z, tgt.numpy(), None)
+    # lse is an fp32 number of the logits' magnitude: its rounding (|lse| 2^-24) is a relative error of every
+    # exponential of the row, on top of the fp32 arithmetic
+    zn = z.numpy()
+    mag = np.where(np.isfinite(zn), np.abs(zn), 0.0).max(axis=1, keepdims=True)
+    gnp = grad.cpu().numpy().astype(np.float64)
+    onehot = np.zeros_like(want)
+    for r_, y_ in enumerate(tgt.numpy()):
+        if 0 <= y_ < V:
+            onehot[r_, y_] = 1.0
+    prob = want + onehot                       # the error is relative to the softmax value, not to softmax - 1
+    bad = np.argwhere(np.abs(gnp - want) > (1e-5 + 2.0 ** -23 * mag) * np.abs(prob) + 1e-7)
+    assert len(bad) == 0, [(int(r), int(c), gnp[r, c], want[r, c]) for r, c in bad[:5]]
+    # loss accumulated over row chunks; reproducible
+    logits, target = W.loss_inputs(48, 2048, 7, 2.0, "bf16")
+    ld, td = logits.cuda(), target.cuda()
+    whole = T.tree_weighted_logprob_fwd_bwd(ld, td)
+    acc = torch.zeros(1, dtype=torch.float32, device="cuda")
+    parts = [T.tree_weighted_logprob_fwd_bwd(ld[lo:lo + 16], td[lo:lo + 16], loss_acc=acc)[3] for lo in range(0, 48, 16)]
+    assert abs(acc.item() - whole[2].item()) <= 1e-5 * abs(whole[2].item())
+    assert torch.equal(torch.cat(parts), whole[3])
+    again = T.tree_weighted_logprob_fwd_bwd(ld, td)
+    assert all(torch.equal(a, b) for a, b in zip(whole, again))

@@ -22,7 +22,7 @@ def test_exports_every_declared_symbol():
     lib = ctypes.CDLL(T.lib_path())
     names = _declared_symbols()
     assert {"tt_tree_build_meta", "tt_tree_attn_fwd", "tt_tree_attn_bwd", "tt_tree_weighted_logprob",
-            "tt_tree_weighted_logprob_bwd", "tt_tree_rope", "tt_tree_partition_sizes", "tt_tree_partition_plan", "tt_tree_path_weights", "tt_tree_conv_fwd", "tt_tree_conv_bwd", "tt_tree_conv_plan", "tt_tree_conv_plan_sizes",
+            "tt_tree_weighted_logprob_bwd", "tt_tree_weighted_logprob_fwd_bwd", "tt_tree_rope", "tt_tree_partition_sizes", "tt_tree_partition_plan", "tt_tree_path_weights", "tt_tree_conv_fwd", "tt_tree_conv_bwd", "tt_tree_conv_plan", "tt_tree_conv_plan_sizes",
             "tt_tree_conv_bwd_workspace", "tt_tree_gdn_plan_sizes", "tt_tree_gdn_plan", "tt_tree_gdn_workspace", "tt_tree_gdn_fwd",
             "tt_tree_gdn_bwd_workspace", "tt_tree_gdn_bwd_workspace_min", "tt_tree_gdn_bwd",
             "tt_tree_attn_partitioned_workspace", "tt_tree_attn_partitioned_fwd", "tt_tree_attn_partitioned_bwd",
@@ -92,6 +92,13 @@ def test_device_calls_validate_before_launch():
     assert rc == -2                      # row stride smaller than vocab
     rc = lib.tt_tree_weighted_logprob(4, 128, 0, null, 0, fake, null, fake, null, null, null)
     assert rc == -1
+    fb = lib.tt_tree_weighted_logprob_fwd_bwd
+    assert fb(4, 128, 0, fake, 0, fake, null, 1.0, fake, null, null, fake, 0, null) == -1         # lse is required
+    assert fb(4, 128, 0, fake, 64, fake, null, 1.0, fake, fake, null, fake, 0, null) == -2        # stride < vocab
+    assert fb(4, 128, 0, fake, 0, fake, null, float("inf"), fake, fake, null, fake, 0, null) == -2
+    assert fb(4, 128, 0, fake, 256, fake, null, 1.0, fake, fake, null, fake, 128, null) == -2     # in place, unequal strides
+    assert fb(4, 128, 9, fake, 0, fake, null, 1.0, fake, fake, null, fake, 0, null) == -4
+    assert fb(0, 128, 0, null, 0, null, null, 1.0, null, null, null, null, 0, null) == 0          # nothing to do
 
 
 def test_gdn_calls_validate_before_launch():
