@@ -30,9 +30,9 @@ PEAK_HBM_GBPS = 8000.0
 # refreshed whenever an attention kernel changes.
 TRAFFIC_SOURCE = "profiles/attention_and_loss_kernels_cfg2.md"
 MEASURED_TRAFFIC_BYTES = {
-    (2, "attn_fwd"): 227.3e6 + 149.2e6,
-    (2, "attn_dkdv"): 2385.8e6 + 206.3e6,
-    (2, "attn_dq"): 514.8e6 + 151.4e6,
+    (2, "attn_fwd"): 226.6e6 + 149.2e6,
+    (2, "attn_dkdv"): 2377.8e6 + 206.3e6,
+    (2, "attn_dq"): 513.2e6 + 151.4e6,
 }
 
 WORKLOADS = {
