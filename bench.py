@@ -10,7 +10,9 @@ time measured with events on the launch stream, with no other instrumentation sw
 resident in HBM before the timed region starts.  Per-kernel durations (kernel_avg_ms, roofline) come from
 a second pass over the same steps with the library's per-kernel event bracketing on.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric / value / unit and the timing fields of the step, `roofline` (dominant kernel),
+`linearized` (the per-branch forest through the same library: attention-only and whole-path speedup),
+`other_configs` (configs 3, 4 and the config-5 step), `partitioned`, `tree_conv`, `tree_gdn`, `cpu_baseline`.
 """
 from __future__ import annotations
 
