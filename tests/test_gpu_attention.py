@@ -131,6 +131,18 @@ def test_partition_prefix(dtype, ref):
     _prefix_case(dtype, 12, 200, allv, W.chain_tree([150]), 2, 1, 128 if dtype == "bf16" else 64, ref)
 
 
+@pytest.mark.parametrize("ref", [True, False], ids=["reference-kernels", "mfma"])
+def test_first_tile_is_not_the_first_visible_one(ref):
+    """The forward and dQ kernels request key tile 0 before they know which tiles a query tile sees.  Cases in which
+    that guess is wrong: a prefix whose first 150 tokens are hidden (tile 0 and tile 1 invisible to everybody), and a
+    forest of four roots (the queries of the later roots do not see the first root's keys)."""
+    vis = np.ones(400, dtype=np.uint8)
+    vis[:150] = 0
+    _prefix_case("bf16", 21, 400, vis, W.random_tree(31, n_nodes=5, lo=20, hi=200), 4, 2, 128, ref)
+    t = W.random_tree(33, n_nodes=9, lo=50, hi=300, n_roots=4, shuffle=False)
+    _full_parity(t, W.AttnDims(4, 2, 128, "bf16", 0.5), 5, reference_kernels=ref, label="four-roots")
+
+
 def test_prefix_gradients_accumulate():
     from gpu_util import gpu_attention
     s = W.step_cfg5(seed=4, n_chunk=300, n_prefix=256, lo=50, hi=120, root_visible=100)
