@@ -12,7 +12,7 @@ a second pass over the same steps with the library's per-kernel event bracketing
 
 Prints one JSON line: metric / value / unit and the timing fields of the step, `roofline` (dominant kernel),
 `linearized` (the per-branch forest through the same library: attention-only and whole-path speedup),
-`other_configs` (configs 3, 4 and the config-5 step), `partitioned`, `tree_conv`, `tree_gdn`, `cpu_baseline`.
+`other_configs` (configs 1, 3, 4 and the config-5 step, each with its own linearized run and CPU sample), `partitioned`, `tree_conv`, `tree_gdn`, `cpu_baseline`.
 """
 from __future__ import annotations
 
@@ -261,14 +261,14 @@ def speedup_record(ms_tree, ms_lin, run: PathRun, lin: PathRun, pairs, pairs_lin
     return rec
 
 
-def other_config(T, torch, dev, linearize, cfg, with_linearized):
-    """Short run (2 warm-up + 3 timed steps) of another full-size configuration: attention rates, the
-    linearized forest beside it, and the path-level times; inputs drawn on the device."""
+def other_config(T, torch, dev, linearize, cfg, with_linearized, with_cpu):
+    """Short run (2 warm-up + 3 timed steps) of another configuration: attention rates, the linearized forest
+    beside it, the path-level times and a bounded sample of the CPU oracle; inputs drawn on the device."""
     import workloads as W
     dims = W.DIMS[cfg]
     tree, n_prefix, vis, root_off = make_workload(cfg)
     N = int(tree.seg_len.sum())
-    tdt = torch.bfloat16
+    tdt = torch.bfloat16 if dims.dtype == "bf16" else torch.float32
     q = device_randn(torch, (N, dims.hq, dims.d), dims.std, tdt, cfg * 1000 + 1, dev)
     k = device_randn(torch, (N, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 2, dev)
     v = device_randn(torch, (N, dims.hkv, dims.d), dims.std, tdt, cfg * 1000 + 3, dev)
@@ -280,7 +280,8 @@ def other_config(T, torch, dev, linearize, cfg, with_linearized):
     logits = target = None
     if dims.vocab > 0:
         rows = min(N, 4096)
-        logits = device_randn(torch, (rows, dims.vocab), dims.logit_std, torch.bfloat16, cfg * 1000 + 5, dev)
+        logits = device_randn(torch, (rows, dims.vocab), dims.logit_std,
+                              torch.bfloat16 if dims.logit_dtype == "bf16" else torch.float32, cfg * 1000 + 5, dev)
         gen = torch.Generator(device=dev)
         gen.manual_seed(cfg * 1000 + 6)
         target = torch.randint(0, dims.vocab, (N,), generator=gen, device=dev, dtype=torch.int32)
@@ -290,8 +291,9 @@ def other_config(T, torch, dev, linearize, cfg, with_linearized):
     attn = ms["attn_fwd"] + ms["attn_bwd"]
     useful = 14.0 * dims.hq * dims.d * pairs
     rec = {"workload": WORKLOADS[cfg], "n_tokens": N, "n_prefix": n_prefix, "visible_pairs": pairs,
-           "useful_tflops": round(useful / (attn * 1e-3) / 1e12, 2),
-           "pct_of_bf16_mfma_peak": round(100.0 * useful / (attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+           "dtype": dims.dtype, "useful_tflops": round(useful / (attn * 1e-3) / 1e12, 2 if dims.dtype == "bf16" else 4),
+           ("pct_of_bf16_mfma_peak" if dims.dtype == "bf16" else "pct_of_fp32_alu_peak"):
+               round(100.0 * useful / (attn * 1e-3) / 1e12 / (PEAK_BF16_TFLOPS if dims.dtype == "bf16" else 157.3), 2),
            "ms_attn_fwd": round(ms["attn_fwd"], 4), "ms_attn_bwd": round(ms["attn_bwd"], 4), "ms_path": round(ms["path"], 4),
            "ms_host_meta": round(float(np.mean(run.host_ms)), 4), "steps": 3, "warmup": 2}
     if n_prefix:
@@ -301,6 +303,8 @@ def other_config(T, torch, dev, linearize, cfg, with_linearized):
         _, ms_l = lin.timed(1, 3)
         rec["linearized"] = speedup_record(ms, ms_l, run, lin, pairs, linearize.visible_pairs(lin.meta))
         del lin
+    if with_cpu and n_prefix == 0:
+        rec["cpu_baseline"] = cpu_rows_sample(tree, dims, q, k, v, do, n_rows=512)
     del run, q, k, v, do, kp, vp, logits, target
     torch.cuda.empty_cache()
     return rec
@@ -509,19 +513,31 @@ def leg_cpu(c):
             dtc = time.perf_counter() - t0c
             cpu_flop = 14.0 * G * n_groups * dims.d * pairs
             sample = "per-branch oracle, fwd+bwd, all branches, kv head groups 0..%d of %d (%d query heads)" % (n_groups - 1, dims.hkv, G * n_groups)
+            cpu = {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(),
+                   "kind": "oracle", "sample": sample, "seconds": round(dtc, 2)}
         else:
-            # a slice of rows of the deepest leaf: same arithmetic, bounded time
-            rows = list(range(N - 96, N))
-            t0c = time.perf_counter()
-            OA.rows(om, q.float().cpu(), k.float().cpu(), v.float().cpu(), do.float().cpu(), 0, rows)
-            dtc = time.perf_counter() - t0c
-            depth = om["tok_pos"][rows].astype(np.int64) + 1
-            cpu_flop = 14.0 * G * dims.d * float(depth.sum())
-            sample = "per-row oracle, fwd+bwd, last 96 tokens, kv head group 0 (%d query heads)" % G
-        cpu = {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(),
-               "kind": "oracle", "sample": sample, "seconds": round(dtc, 2)}
-
+            cpu = cpu_rows_sample(tree, dims, q, k, v, do)
     return cpu
+
+
+def cpu_rows_sample(tree, dims, q, k, v, do, n_rows=96):
+    """The oracle on a slice of rows of the deepest leaf (the last tokens in DFS order), kv head group 0: the same
+    arithmetic as a full run, bounded time."""
+    from oracle import attention as OA, meta as OM
+    om = OM.dfs_meta(tree.parent, tree.seg_len, tree.trained)
+    N = om["n_tokens"]
+    G = dims.hq // dims.hkv
+    rows = list(range(max(0, N - n_rows), N))
+    # only kv head 0 and its query heads travel to the host
+    qc, kc, vc, dc = (x[:, :h].float().cpu() for x, h in ((q, G), (k, 1), (v, 1), (do, G)))
+    t0c = time.perf_counter()
+    OA.rows(om, qc, kc, vc, dc, 0, rows)
+    dtc = time.perf_counter() - t0c
+    depth = om["tok_pos"][rows].astype(np.int64) + 1
+    cpu_flop = 14.0 * G * dims.d * float(depth.sum())
+    return {"value": round(cpu_flop / dtc / 1e12, 6), "unit": "useful TFLOP/s", "cores": OA.n_threads(), "kind": "oracle",
+            "sample": "per-row oracle, fwd+bwd, last %d tokens, kv head group 0 (%d query heads)" % (len(rows), G),
+            "seconds": round(dtc, 2)}
 
 
 class Ctx:
@@ -663,11 +679,12 @@ def main():
         torch.cuda.empty_cache()
         others = {}
         t_start = time.perf_counter()
-        for oc in (3, 4, 5):
+        for oc in (1, 3, 4, 5):
             if time.perf_counter() - t_start > args.other_configs_budget_s:
                 others[f"cfg{oc}"] = {"skipped": "time budget"}
                 continue
-            others[f"cfg{oc}" if oc != 5 else "cfg5_step"] = other_config(T, torch, dev, linearize, oc, not args.no_linearized)
+            others[f"cfg{oc}" if oc != 5 else "cfg5_step"] = other_config(T, torch, dev, linearize, oc, not args.no_linearized,
+                                                                               not args.no_cpu_baseline)
 
     out = {
         "metric": "tree-attn fwd+bwd useful TFLOP/s",
