@@ -63,6 +63,7 @@ def parse_args():
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-gdn", action="store_true")
     ap.add_argument("--no-gdn-bwd", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step's device part")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="skip the short runs of the other full-size configurations (3, 4 and the config-5 step)")
     ap.add_argument("--other-configs-budget-s", type=float, default=150.0,
@@ -169,6 +170,11 @@ class PathRun:
             self.pos_h.numpy()[:] = m.tok_pos
             self.pos_d.copy_(self.pos_h, non_blocking=True)
         self.host_ms.append((time.perf_counter() - t0) * 1e3)
+        self.device_part(events)
+
+    def device_part(self, events=None):
+        """The library calls of one step (what a HIP graph of the step holds)."""
+        T, N = self.T, self.N
         w_d = self.w_d if self.weight_override is None else self.weight_override
         kb = (self.kend_d, self.kmin_d, self.kmax_d)
         if events:
@@ -648,6 +654,30 @@ def main():
         rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * 2 * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
         rope_gbps = rope_bytes / (ktimes["rope"][0] / k_steps * 1e-3) / 1e9
 
+    # ---------------- the device part of the step as one HIP graph (launch overhead taken out) ----------------
+    graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            run.device_part()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            run.device_part()
+        n_rep = max(3, min(args.steps, 10))
+        gev = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
+        g.replay()
+        gev[0].record()
+        for i in range(n_rep):
+            g.replay()
+            gev[i + 1].record()
+        torch.cuda.synchronize()
+        graph = {"ms_device_path_replayed": round(gev[0].elapsed_time(gev[n_rep]) / n_rep, 4),
+                 "ms_device_path_eager": round(ms["path"], 4), "replays": n_rep}
+        del g
+
     # ---------------- linearised per-branch baseline on the same GPU ----------------
     lin = None
     if not args.no_linearized and n_prefix == 0:
@@ -707,6 +737,7 @@ def main():
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "loss_one_pass_hbm_gbps": None if loss_fused_gbps is None else round(loss_fused_gbps, 1),
         "loss_one_pass_frac_of_hbm_peak": None if loss_fused_gbps is None else round(loss_fused_gbps / PEAK_HBM_GBPS, 4),
+        "hip_graph": graph,
         "linearized": lin,
         "partitioned": part,
         "tree_conv": conv,
