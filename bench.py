@@ -348,6 +348,26 @@ def leg_partitioned(c):
         torch.cuda.synchronize()
         per_step = [evs[i].elapsed_time(evs[i + 1]) for i in range(n_it)]
         ms_part = evs[0].elapsed_time(evs[n_it]) / n_it
+        ms_part_graph = None
+        if not args.no_graph:
+            # the same step replayed from a HIP graph: one launch per kernel of every partition is what a graph removes
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                part_step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                part_step()
+            g.replay()
+            evs[0].record()
+            for it in range(n_it):
+                g.replay()
+            evs[1].record()
+            torch.cuda.synchronize()
+            ms_part_graph = evs[0].elapsed_time(evs[1]) / n_it
+            del g
         T.kernel_timing_enable(True)               # a second pass for the per-kernel split
         for it in range(n_it):
             part_step()
@@ -371,6 +391,7 @@ def leg_partitioned(c):
                 "in_place_own": int((plan.part_own_start >= 0).sum()), "in_place_prefix": int((plan.part_prefix_start >= 0).sum()),
                 "sum_prefix": int(plan.part_prefix_off[-1]), "ms_fwd_bwd": round(ms_part, 4),
                 "ms_fwd_bwd_per_step": [round(x, 3) for x in per_step],
+                "ms_fwd_bwd_graph_replay": None if ms_part_graph is None else round(ms_part_graph, 4),
                 "ms_whole_fwd_bwd": round(ms_fwd + ms_bwd, 4),
                 "ratio_to_whole": round(ms_part / (ms_fwd + ms_bwd), 3),
                 "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
