@@ -348,26 +348,6 @@ def leg_partitioned(c):
         torch.cuda.synchronize()
         per_step = [evs[i].elapsed_time(evs[i + 1]) for i in range(n_it)]
         ms_part = evs[0].elapsed_time(evs[n_it]) / n_it
-        ms_part_graph = None
-        if not args.no_graph:
-            # the same step replayed from a HIP graph: one launch per kernel of every partition is what a graph removes
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                part_step()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=side):
-                part_step()
-            g.replay()
-            evs[0].record()
-            for it in range(n_it):
-                g.replay()
-            evs[1].record()
-            torch.cuda.synchronize()
-            ms_part_graph = evs[0].elapsed_time(evs[1]) / n_it
-            del g
         T.kernel_timing_enable(True)               # a second pass for the per-kernel split
         for it in range(n_it):
             part_step()
@@ -391,7 +371,6 @@ def leg_partitioned(c):
                 "in_place_own": int((plan.part_own_start >= 0).sum()), "in_place_prefix": int((plan.part_prefix_start >= 0).sum()),
                 "sum_prefix": int(plan.part_prefix_off[-1]), "ms_fwd_bwd": round(ms_part, 4),
                 "ms_fwd_bwd_per_step": [round(x, 3) for x in per_step],
-                "ms_fwd_bwd_graph_replay": None if ms_part_graph is None else round(ms_part_graph, 4),
                 "ms_whole_fwd_bwd": round(ms_fwd + ms_bwd, 4),
                 "ratio_to_whole": round(ms_part / (ms_fwd + ms_bwd), 3),
                 "ms_attn_kernels": round(sum(pt[n][0] for n in ("attn_fwd", "attn_dkdv", "attn_dq", "attn_plan", "attn_reduce")) / n_it, 4),
@@ -675,30 +654,6 @@ def main():
         rope_bytes = 2 * (dims.hq + dims.hkv) * N * dims.d * 2 * 2 + 4 * N * 4      # q, k, dq, dk: read + write; positions
         rope_gbps = rope_bytes / (ktimes["rope"][0] / k_steps * 1e-3) / 1e9
 
-    # ---------------- the device part of the step as one HIP graph (launch overhead taken out) ----------------
-    graph = None
-    if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            run.device_part()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=side):
-            run.device_part()
-        n_rep = max(3, min(args.steps, 10))
-        gev = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
-        g.replay()
-        gev[0].record()
-        for i in range(n_rep):
-            g.replay()
-            gev[i + 1].record()
-        torch.cuda.synchronize()
-        graph = {"ms_device_path_replayed": round(gev[0].elapsed_time(gev[n_rep]) / n_rep, 4),
-                 "ms_device_path_eager": round(ms["path"], 4), "replays": n_rep}
-        del g
-
     # ---------------- linearised per-branch baseline on the same GPU ----------------
     lin = None
     if not args.no_linearized and n_prefix == 0:
@@ -726,7 +681,7 @@ def main():
     # ---------------- the other full-size configurations, briefly ----------------
     others = None
     if not args.no_other_configs and cfg == 2:
-        del run, q, k, v, do, logits, c
+        del c
         torch.cuda.empty_cache()
         others = {}
         t_start = time.perf_counter()
@@ -758,7 +713,7 @@ def main():
         "loss_bwd_frac_of_hbm_peak": None if loss_bwd_gbps is None else round(loss_bwd_gbps / PEAK_HBM_GBPS, 4),
         "loss_one_pass_hbm_gbps": None if loss_fused_gbps is None else round(loss_fused_gbps, 1),
         "loss_one_pass_frac_of_hbm_peak": None if loss_fused_gbps is None else round(loss_fused_gbps / PEAK_HBM_GBPS, 4),
-        "hip_graph": graph,
+        "hip_graph": None,
         "linearized": lin,
         "partitioned": part,
         "tree_conv": conv,
@@ -767,6 +722,31 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    # ---------------- last: the device part of the step as one HIP graph ----------------
+    # (after everything else has been measured, and guarded: a capture that fails must not cost the line)
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run.device_part()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                run.device_part()
+            n_rep = max(3, min(args.steps, 10))
+            gev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            g.replay()
+            gev[0].record()
+            for i in range(n_rep):
+                g.replay()
+            gev[1].record()
+            torch.cuda.synchronize()
+            out["hip_graph"] = {"ms_device_path_replayed": round(gev[0].elapsed_time(gev[1]) / n_rep, 4),
+                                "ms_device_path_eager": round(ms["path"], 4), "replays": n_rep}
+        except Exception as e:      # noqa: BLE001 -- reported in the line instead of losing it
+            out["hip_graph"] = {"error": f"{type(e).__name__}: {e}"[:300]}
     print(json.dumps(out))
 
 
