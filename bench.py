@@ -550,6 +550,14 @@ class Ctx:
     pass
 
 
+def guarded(fn, *a):
+    """The side legs report a failure in their own field; the headline has been measured by then and must get out."""
+    try:
+        return fn(*a)
+    except Exception as e:      # noqa: BLE001
+        return {"error": f"{fn.__name__}: {type(e).__name__}: {e}"[:300]}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -666,10 +674,10 @@ def main():
     c = Ctx()
     c.args, c.T, c.torch, c.dev, c.cfg, c.dims, c.tree, c.meta, c.N, c.n_prefix = args, T, torch, dev, cfg, dims, tree, meta, N, n_prefix
     c.q, c.k, c.v, c.do, c.lse, c.ms_fwd, c.ms_bwd, c.pairs = run.q, run.k, run.v, run.do, run.lse, ms_fwd, ms_bwd, pairs
-    part = leg_partitioned(c)
-    conv = leg_conv(c)
-    gdn = leg_gdn(c)
-    cpu = leg_cpu(c)
+    part = guarded(leg_partitioned, c)
+    conv = guarded(leg_conv, c)
+    gdn = guarded(leg_gdn, c)
+    cpu = guarded(leg_cpu, c)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -689,8 +697,8 @@ def main():
             if time.perf_counter() - t_start > args.other_configs_budget_s:
                 others[f"cfg{oc}"] = {"skipped": "time budget"}
                 continue
-            others[f"cfg{oc}" if oc != 5 else "cfg5_step"] = other_config(T, torch, dev, linearize, oc, not args.no_linearized,
-                                                                               not args.no_cpu_baseline)
+            others[f"cfg{oc}" if oc != 5 else "cfg5_step"] = guarded(other_config, T, torch, dev, linearize, oc,
+                                                                         not args.no_linearized, not args.no_cpu_baseline)
 
     out = {
         "metric": "tree-attn fwd+bwd useful TFLOP/s",
