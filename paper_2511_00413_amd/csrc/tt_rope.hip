@@ -70,7 +70,8 @@ rope_kernel(int64_t n_tokens, int n_heads, int d, const char* x, int64_t x_strid
     cs_off = tk * half + vi * EPV;
   };
   // the first vector pair of every thread is requested before the angles are worked out, so that the memory
-  // round trip runs under the fp64 arithmetic; streaming (non-temporal) accesses: nothing is read twice
+  // round trip runs under the fp64 arithmetic; streaming (non-temporal) loads: nothing is read twice (the stores
+  // are ordinary ones: measured 2-3 % faster than non-temporal stores here, and the next kernel reads what they wrote)
   u32x4 vlo = {0, 0, 0, 0}, vhi = {0, 0, 0, 0};
   if ((int)threadIdx.x < n_work) {
     int64_t xo, yo; int co;
@@ -106,8 +107,8 @@ rope_kernel(int64_t n_tokens, int n_heads, int d, const char* x, int64_t x_strid
       olo[e] = lo[e] * q.x - hi[e] * q.y;
       ohi[e] = hi[e] * q.x + lo[e] * q.y;
     }
-    __builtin_nontemporal_store(Vec<EPV>::pack(olo), (u32x4*)(y + yo));
-    __builtin_nontemporal_store(Vec<EPV>::pack(ohi), (u32x4*)(y + yo + (int64_t)half * ESZ));
+    *(u32x4*)(y + yo) = Vec<EPV>::pack(olo);
+    *(u32x4*)(y + yo + (int64_t)half * ESZ) = Vec<EPV>::pack(ohi);
   }
 }
 
