@@ -35,6 +35,8 @@ constexpr int GC = TT_GDN_CHUNK;     // tokens per chunk (64)
 constexpr int GD = 128;              // head dim of keys and values
 constexpr int GROW = GD + 8;         // padded LDS row (elements) for [*][128] bf16 tiles
 constexpr int G_THREADS = 256;
+constexpr int T_PITCH = GC + 8;      // padded LDS row (elements) of the 64 x 64 bf16 halves of the triangular inverse
+static_assert(2 * GC * T_PITCH * 2 >= GC * GC * 4, "the inverse's halves take the place of A");
 constexpr int G_DVB = 32;            // value columns per column block of the scan (one 32 x 32 accumulator tile per wave)
 constexpr int SCAN_NB = 2;           // column blocks per scan workgroup: 4 wavefronts each, sharing the chunk's operands in LDS
 constexpr int SCAN_NW = 4 * SCAN_NB; // wavefronts per scan workgroup (two per SIMD)
@@ -92,7 +94,11 @@ template <bool BWD>
 __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(16))) __bf16 ksm[GC][GROW];
   __shared__ __attribute__((aligned(16))) __bf16 qsm[GC][GROW];
-  __shared__ __attribute__((aligned(16))) float am[GC][GC];
+  // A (fp32) until the triangular inverse has been formed from it, then the two bf16 halves of the scaled inverse
+  __shared__ __attribute__((aligned(16))) float am_raw[2 * GC * T_PITCH / 2];
+  float(*am)[GC] = (float(*)[GC])am_raw;
+  __bf16(*t_hi)[T_PITCH] = (__bf16(*)[T_PITCH])am_raw;
+  __bf16(*t_lo)[T_PITCH] = t_hi + GC;
   __shared__ float gam[GC], bet[GC];
 
   const int chunk = blockIdx.x, h = blockIdx.y;
@@ -239,54 +245,99 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   }
   __syncthreads();
 
-  // forward substitution, one lane per column of [beta V | beta exp(gamma) K]:
-  //   x_i = rhs_i - sum_{j<i} A_ij x_j
-  {
-    const int c = tid;                  // 0..127: value column, 128..255: key column
-    float x[GC];
-    // right-hand sides first
-    if (c < GD) {
+  // U = (I + A)^-1 (beta V),  W = (I + A)^-1 (beta exp(gamma) K) as products with the explicit inverse
+  // T = (I + A)^-1 (unit lower triangular, like I + A): the first wave forms T by forward substitution on the
+  // identity, one lane per column (a quarter of the multiply-adds that substitution on the 256 columns of
+  // [V | K] took, which kept all four waves busy for most of this kernel's time); the products
+  // (T diag(beta)) V and (T diag(beta exp(gamma))) K then run on the matrix cores.  V and K are bf16 as they stand;
+  // the scaled T is split into two bf16 halves (hi + lo, relative error 2^-17), so the products carry fp32-grade
+  // operands, and U, W are rounded to bf16 once, as before.
+  // (the wave that does it differs from workgroup to workgroup: the waves of a workgroup sit on different SIMDs, and
+  // with always the same one the inverses of the compute unit's resident workgroups would queue up on one SIMD)
+  const int tw = (int)((blockIdx.x + blockIdx.y) & 3);
+  float x[GC];                          // wave tw: column `lane` of T
+  if (w == tw) {
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = (float)qsm[i][c];
-    } else {
-#pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = __expf(gam[i]) * (float)ksm[i][c - GD];
-    }
-#pragma unroll
-    for (int i = 0; i < GC; i++) x[i] = i < len ? bet[i] * x[i] : 0.f;
+    for (int i = 0; i < GC; i++) x[i] = i == lane ? 1.f : 0.f;
 #pragma unroll
     for (int i = 1; i < GC; i++) {
-      if (i < len) {
-        float rhs = x[i];
+      // x_i = delta_ij - sum_{k<i} A_ik x_k, four partial sums (the chain of one sum would leave the wave waiting)
+      float s0 = x[i], s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
-        for (int j4 = 0; j4 < (i + 3) / 4; j4++) {
-          const float4 av = *(const float4*)&am[i][j4 * 4];      // entries at j >= i are zero
-          const float ae[4] = {av.x, av.y, av.z, av.w};
-#pragma unroll
-          for (int e = 0; e < 4; e++)
-            if (j4 * 4 + e < i) rhs -= ae[e] * x[j4 * 4 + e];
-        }
-        x[i] = rhs;
+      for (int j4 = 0; j4 < (i + 3) / 4; j4++) {
+        const float4 av = *(const float4*)&am[i][j4 * 4];      // entries at k >= i are zero; rows past the chunk too
+        s0 -= av.x * x[j4 * 4];
+        s1 -= av.y * x[j4 * 4 + 1];
+        s2 -= av.z * x[j4 * 4 + 2];
+        s3 -= av.w * x[j4 * 4 + 3];
       }
+      x[i] = (s0 + s1) + (s2 + s3);
     }
     if constexpr (BWD) {
-      // -W^T for the reverse walk (and, like U^T below, for the finish kernel)
-      if (c >= GD) {
-        __bf16* dst = a.rev + op * REV_ELEMS + REV_WTN + (c - GD) * GC;
+      // T itself, for the finish kernel's transposed solve (row i, column lane: 256 contiguous bytes per store)
 #pragma unroll
-        for (int i0 = 0; i0 < GC; i0 += 8)
-          *(bf16x8*)(dst + i0) = cvt8(-x[i0], -x[i0 + 1], -x[i0 + 2], -x[i0 + 3], -x[i0 + 4], -x[i0 + 5], -x[i0 + 6], -x[i0 + 7]);
+      for (int i = 0; i < GC; i++) a.f32.t[op * (GC * GC) + i * GC + lane] = x[i];
+    }
+  }
+  const int c = lane & 31, hf = lane >> 5;
+  // one product: C (64 x 128) = (hi + lo) (64 x 64) B (64 tokens x 128, row-major in LDS); wave w takes the column
+  // block w, both row blocks
+  auto product = [&](const __bf16 (*bsm)[GROW], f32x16 (&acc)[2]) {
+    acc[0] = zero16(); acc[1] = zero16();
+#pragma unroll
+    for (int ks = 0; ks < GC / 16; ks++) {
+      const bf16x8 b = kmajor_frag(&bsm[0][0], GROW, 16 * ks + 8 * hf, 32 * w + 16 * (c >> 4), lane);
+#pragma unroll
+      for (int t = 0; t < 2; t++) {
+        const bf16x8 ah = *(const bf16x8*)&t_hi[32 * t + c][16 * ks + 8 * hf];
+        const bf16x8 al = *(const bf16x8*)&t_lo[32 * t + c][16 * ks + 8 * hf];
+        acc[t] = mfma32(ah, b, acc[t]);
+        acc[t] = mfma32(al, b, acc[t]);
       }
     }
-    if (c < GD) {
-      __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + c * GC;
+  };
+  // the scaled inverse, column `lane` times f, as hi + lo
+  auto put_scaled = [&](float f) {
 #pragma unroll
-      for (int i0 = 0; i0 < GC; i0 += 8)
-        *(bf16x8*)(dst + i0) = cvt8(x[i0], x[i0 + 1], x[i0 + 2], x[i0 + 3], x[i0 + 4], x[i0 + 5], x[i0 + 6], x[i0 + 7]);
-    } else {
-      __bf16* dst = a.rec + op * REC_ELEMS + REC_WN + (c - GD);
+    for (int i = 0; i < GC; i++) {
+      const float v = x[i] * f;
+      const __bf16 h = (__bf16)v;
+      t_hi[i][lane] = h;
+      t_lo[i][lane] = (__bf16)(v - (float)h);
+    }
+  };
+  f32x16 acc[2];
+  if (w == tw) put_scaled(bet[lane]);    // (behind that wave's own reads of A: LDS operations of a wave are ordered)
+  __syncthreads();
+  product(qsm, acc);                    // U: rows = tokens, columns = value dims 32 w .. 32 w + 31
+  {
+    // U^T [value dim][token]: a lane holds 4 consecutive tokens of its column per register group
+    __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + (size_t)(32 * w + c) * GC;
 #pragma unroll
-      for (int i = 0; i < GC; i++) dst[i * GD] = (__bf16)(-x[i]);
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; r4++)
+        *(bf16x4*)(dst + 32 * t + r4 * 8 + 4 * hf) = cvt4(acc[t][4 * r4], acc[t][4 * r4 + 1], acc[t][4 * r4 + 2], acc[t][4 * r4 + 3]);
+  }
+  __syncthreads();                      // every wave has read the halves
+  if (w == tw) put_scaled(bet[lane] * __expf(gam[lane]));
+  __syncthreads();
+  product(ksm, acc);                    // W: columns = key dims
+  {
+    __bf16* dst = a.rec + op * REC_ELEMS + REC_WN + 32 * w + c;
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) dst[(size_t)(32 * t + (r >> 2) * 8 + 4 * hf + (r & 3)) * GD] = (__bf16)(-acc[t][r]);
+    if constexpr (BWD) {
+      // -W^T for the reverse walk (and, like U^T, for the finish kernel)
+      __bf16* dt = a.rev + op * REV_ELEMS + REV_WTN + (size_t)(32 * w + c) * GC;
+#pragma unroll
+      for (int t = 0; t < 2; t++)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++)
+          *(bf16x4*)(dt + 32 * t + r4 * 8 + 4 * hf) =
+              cvt4(-acc[t][4 * r4], -acc[t][4 * r4 + 1], -acc[t][4 * r4 + 2], -acc[t][4 * r4 + 3]);
     }
   }
 }

@@ -78,15 +78,6 @@ constexpr int PR_A = KS + 8;                              // row-major A slab: 6
 template <int N> constexpr int pitch_b() { return N + 8; } // k-major B slab: KS rows of N (+8)
 constexpr int AS_ELEMS = KS * PK_A > GC * PR_A ? KS * PK_A : GC * PR_A;
 
-// 8 consecutive k (k0 .. k0 + 7) of row / column n0 + (lane % 16) from a k-major slab: two transposing reads of a
-// 4 (k) x 16 (n) block each; inside a group of 16 lanes, lane i supplies the address of 4 consecutive elements of
-// block row i / 4 and receives block column i.
-__device__ __forceinline__ bf16x8 kmajor_frag(const __bf16* slab, int pitch, int k0, int n0, int lane) {
-  const int i = lane & 15;
-  const __bf16* p = slab + (k0 + (i >> 2)) * pitch + n0 + 4 * (i & 3);
-  return cat4(lds_read_tr(p), lds_read_tr(p + 4 * pitch));
-}
-
 // ---- operand loaders ---------------------------------------------------------------------------------------
 // A loader brings one KS-wide slab of an operand from memory into registers (load) and from there into the LDS
 // slab (store).  Memory is read in 16-byte pieces.  KMAJOR tells the layout of an A loader's slab.
@@ -326,7 +317,6 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   const __bf16* ds1t = (const __bf16*)a.w.sv.ds1t + op * (GD * GD);
   const __bf16* vns = (const __bf16*)a.w.sv.vns + op * (GC * GD);
   const __bf16* dvns = (const __bf16*)a.w.sv.dvns + op * (GC * GD);
-  auto dvn_at = [&](int i, int cc) { return (float)dvns[gdn_frag_index(i, cc)]; };
   __bf16* X = a.w.x + op * (GC * 2 * GD);
   const size_t qrow = (size_t)a.b.hk * GD, vrow = (size_t)hv * GD;
   const __bf16* qb = (const __bf16*)a.b.q + (size_t)tok0 * qrow + (size_t)kh * GD;
@@ -351,50 +341,69 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   typedef TileMap<GD> T128;
   typedef TileMap<GC> T64;
 
-  // dW = -dVn S0^T  -> right half of X
+  // dW = -dVn S0^T, kept in fragment order (the registers of an accumulator tile, eight at a time, are exactly the
+  // fragment of its column) in the first 16 KB of X: it is the second half of the right-hand side below
   {
     f32x16 acc[2] = {zero16(), zero16()};
     slab_product<GD, GD>(FragLoader<PK_A>{dvns}, RowsJLoaderB{s0t, GD, GD}, acc, as, bs, tid);
 #pragma unroll
-    for (int t = 0; t < 2; t++)
+    for (int t = 0; t < 2; t++)                        // tile (row block t, column block w)
 #pragma unroll
-      for (int r = 0; r < 16; r++) X[(32 * T128::ib(w, t) + tile_row(r, hf)) * (2 * GD) + GD + 32 * T128::jb(w) + c] = (__bf16)(-acc[t][r]);
+      for (int tt = 0; tt < 2; tt++)
+        ((bf16x8*)X)[(((w * 2 + T128::ib(w, t)) * 2 + tt) * 64 + lane)] =
+            cvt8(-acc[t][8 * tt], -acc[t][8 * tt + 1], -acc[t][8 * tt + 2], -acc[t][8 * tt + 3], -acc[t][8 * tt + 4],
+                 -acc[t][8 * tt + 5], -acc[t][8 * tt + 6], -acc[t][8 * tt + 7]);
   }
-  // A^T into LDS: dam[i][j] = A_ji = beta_j A0_ji  (zero for j <= i)
-#pragma unroll
-  for (int p = 0; p < GC * GC / BT; p++) {
-    const int e = tid + p * BT, j = e / GC, i = e % GC;
-    dam[i * TP + j] = bet[j] * A0[e];
-  }
-  __syncthreads();
-
-  // (I + A)^T x = rhs by back substitution, one lane per column of [dVn | dW]:  x_i = rhs_i - sum_{j>i} A_ji x_j
+  // (I + A)^T x = rhs for the 256 columns of [dVn | dW]: x = T^T rhs with T = (I + A)^-1 from the prepare kernel,
+  // computed transposed, X^T = rhs^T T, on the matrix cores.  rhs^T comes straight from the fragment-ordered
+  // arrays (a fragment is the A operand of its column block for one k-step, its 8 tokens in accumulator order);
+  // T is split into two bf16 halves (hi + lo) in LDS, k-major, read in the same token order.
   {
-    const int cx = tid;
-    float x[GC];
-    // right-hand sides: 64 independent loads per lane in one straight-line block
-    if (cx < GD) {
+    __bf16* th = as;                                   // [token][i], pitch PK_A
+    __bf16* tl = (__bf16*)dam;
+    const float* Tg = a.w.ops.t + op * (GC * GC);
+    lds_barrier();                                     // the last slab of the product above has been read
 #pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = dvn_at(i, cx);
-    } else {
-#pragma unroll
-      for (int i = 0; i < GC; i++) x[i] = (float)X[i * (2 * GD) + cx];
+    for (int p = 0; p < GC * GC / 4 / BT; p++) {
+      const int e4 = tid + p * BT, k = e4 >> 4, i4 = (e4 & 15) * 4;
+      const float4 v = ld4(Tg + e4 * 4);
+      const bf16x4 h4 = cvt4(v.x, v.y, v.z, v.w);
+      *(bf16x4*)(th + k * PK_A + i4) = h4;
+      *(bf16x4*)(tl + k * PK_A + i4) = cvt4(v.x - (float)h4[0], v.y - (float)h4[1], v.z - (float)h4[2], v.w - (float)h4[3]);
     }
+    // wave w: right-hand-side column blocks 2 w and 2 w + 1 (blocks 0 .. 3: dVn, 4 .. 7: dW)
+    bf16x8 af[2][GC / 16];
+    __syncthreads();                                   // T in LDS; the dW fragments written above are visible
 #pragma unroll
-    for (int i = GC - 2; i >= 0; i--) {
-      float v = x[i];
+    for (int rbi = 0; rbi < 2; rbi++) {
+      const int rb = 2 * w + rbi;
+      const bf16x8* src = rb < 4 ? (const bf16x8*)dvns + (size_t)rb * 4 * 64 : (const bf16x8*)X + (size_t)(rb - 4) * 4 * 64;
 #pragma unroll
-      for (int j4 = (i + 1) / 4; j4 < GC / 4; j4++) {
-        const float4 av = *(const float4*)&dam[i * TP + j4 * 4];
-        const float ae[4] = {av.x, av.y, av.z, av.w};
+      for (int s4 = 0; s4 < GC / 16; s4++) af[rbi][s4] = src[s4 * 64 + lane];      // (half, t) = (s4 / 2, s4 % 2)
+    }
+    f32x16 xa[2][2] = {{zero16(), zero16()}, {zero16(), zero16()}};
 #pragma unroll
-        for (int e = 0; e < 4; e++)
-          if (j4 * 4 + e > i) v -= ae[e] * x[j4 * 4 + e];
+    for (int s4 = 0; s4 < GC / 16; s4++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++) {
+        const bf16x8 bh = kmajor_frag_acc_order(th, PK_A, 16 * s4 + 4 * hf, 32 * cb + 16 * (c >> 4), lane);
+        const bf16x8 bl = kmajor_frag_acc_order(tl, PK_A, 16 * s4 + 4 * hf, 32 * cb + 16 * (c >> 4), lane);
+#pragma unroll
+        for (int rbi = 0; rbi < 2; rbi++) {
+          xa[rbi][cb] = mfma32(af[rbi][s4], bh, xa[rbi][cb]);
+          xa[rbi][cb] = mfma32(af[rbi][s4], bl, xa[rbi][cb]);
+        }
       }
-      x[i] = v;
-    }
+    __syncthreads();                                   // every wave holds its dW fragments: X may be overwritten
+    // X[i][column]: a lane holds row i = 32 cb + c and, per register group, 4 consecutive columns
 #pragma unroll
-    for (int i = 0; i < GC; i++) X[i * (2 * GD) + cx] = (__bf16)x[i];
+    for (int rbi = 0; rbi < 2; rbi++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; r4++)
+          *(bf16x4*)(X + (size_t)(32 * cb + c) * (2 * GD) + 32 * (2 * w + rbi) + r4 * 8 + 4 * hf) =
+              cvt4(xa[rbi][cb][4 * r4], xa[rbi][cb][4 * r4 + 1], xa[rbi][cb][4 * r4 + 2], xa[rbi][cb][4 * r4 + 3]);
   }
   __syncthreads();
 
@@ -637,6 +646,7 @@ size_t carve(char* p, int64_t n_tokens, int n_chunks, int n_slots, int n_segment
   t.ops.gam = (float*)take(per * GC * 4);
   t.ops.a0 = (float*)take(per * GC * GC * 4);
   t.ops.p = (float*)take(per * GC * GC * 4);
+  t.ops.t = (float*)take(per * GC * GC * 4);
   t.sv.fwd_rec = take(per * GDN_REC_ELEMS * 2);
   t.sv.rev_rec = take(per * GDN_REC_ELEMS * 2);
   t.sv.glast = (float*)take(per * 4);

@@ -98,6 +98,7 @@ struct GdnChunkOps {
   float* gam;      // [64]       running sum of the log-decays inside the chunk
   float* a0;       // [64][64]   strictly-lower (k_i . k_j) exp(gamma_i - gamma_j)   (A without beta_i)
   float* p;        // [64][64]   scale tril((q_i . k_j) exp(gamma_i - gamma_j))
+  float* t;        // [64][64]   (I + A)^-1, A = diag(beta) a0: the inverse both triangular solves are products with
 };
 // bf16 operands of the two walks and what they save for the finish kernel:
 constexpr size_t GDN_REC_ELEMS = 4 * 64 * 128 + 64 * 64;     // elements of one walk record (forward and reverse alike)

@@ -63,6 +63,23 @@ __device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
   return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// 8 consecutive k (k0 .. k0 + 7) of row / column n0 + (lane % 16) from a k-major LDS array ([k][n], `pitch`
+// elements per k): two transposing reads of a 4 (k) x 16 (n) block each; inside a group of 16 lanes, lane i supplies
+// the address of 4 consecutive elements of block row i / 4 and receives block column i.
+__device__ __forceinline__ bf16x8 kmajor_frag(const __bf16* slab, int pitch, int k0, int n0, int lane) {
+  const int i = lane & 15;
+  const __bf16* p = slab + (k0 + (i >> 2)) * pitch + n0 + 4 * (i & 3);
+  return cat4(lds_read_tr(p), lds_read_tr(p + 4 * pitch));
+}
+
+// The same for 8 k in the order in which an accumulator's registers enumerate rows: k0 .. k0 + 3 and k0 + 8 .. k0 + 11
+// (k0 = 16 s + 4 hf of k-step s) -- the B operand that matches an A operand taken straight from accumulator registers.
+__device__ __forceinline__ bf16x8 kmajor_frag_acc_order(const __bf16* slab, int pitch, int k0, int n0, int lane) {
+  const int i = lane & 15;
+  const __bf16* p = slab + (k0 + (i >> 2)) * pitch + n0 + 4 * (i & 3);
+  return cat4(lds_read_tr(p), lds_read_tr(p + 8 * pitch));
+}
+
 // max / sum of a value with the lane 32 positions away (the other half of the same column)
 __device__ __forceinline__ float half_swap_max(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
