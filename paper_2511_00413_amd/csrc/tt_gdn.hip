@@ -306,40 +306,55 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       t_lo[i][lane] = (__bf16)(v - (float)h);
     }
   };
-  f32x16 acc[2];
-  if (w == tw) put_scaled(bet[lane]);    // (behind that wave's own reads of A: LDS operations of a wave are ordered)
-  __syncthreads();
-  product(qsm, acc);                    // U: rows = tokens, columns = value dims 32 w .. 32 w + 31
-  {
-    // U^T [value dim][token]: a lane holds 4 consecutive tokens of its column per register group
-    __bf16* dst = a.rec + op * REC_ELEMS + REC_UT + (size_t)(32 * w + c) * GC;
+  // The results leave through LDS, so that memory sees whole 16-byte pieces from consecutive lanes (stored straight
+  // from the accumulators, U^T goes out as 8-byte pieces 128 bytes apart and W as 2-byte elements: most of this
+  // part's time).  The V tile's LDS holds U^T once the first product has read it, the K tile's LDS holds -W after the
+  // second.  [column][token] arrays: 8-byte piece p of column col sits at position p ^ 2 (col % 8) (keeps the two
+  // halves of a 16-byte piece together; without it the 32 columns of a wave would start in two banks).
+  __bf16* stage_v = &qsm[0][0];
+  __bf16* stage_k = &ksm[0][0];
+  auto stage_transposed = [&](__bf16* st, const f32x16 (&ac)[2], float sign) {     // [128 columns][64 tokens]
+    const int col = 32 * w + c, sw = (col & 7) << 1;
 #pragma unroll
     for (int t = 0; t < 2; t++)
 #pragma unroll
       for (int r4 = 0; r4 < 4; r4++)
-        *(bf16x4*)(dst + 32 * t + r4 * 8 + 4 * hf) = cvt4(acc[t][4 * r4], acc[t][4 * r4 + 1], acc[t][4 * r4 + 2], acc[t][4 * r4 + 3]);
-  }
-  __syncthreads();                      // every wave has read the halves
+        *(bf16x4*)(st + col * GC + (((8 * t + 2 * r4 + hf) ^ sw) << 2)) =
+            cvt4(sign * ac[t][4 * r4], sign * ac[t][4 * r4 + 1], sign * ac[t][4 * r4 + 2], sign * ac[t][4 * r4 + 3]);
+  };
+  auto copy_out_transposed = [&](const __bf16* st, __bf16* dst) {                  // dst [128][64], contiguous
+#pragma unroll
+    for (int p = 0; p < GD * GC / 8 / G_THREADS; p++) {
+      const int piece = tid + p * G_THREADS, col = piece >> 3, q = piece & 7;
+      *(bf16x8*)(dst + (size_t)piece * 8) = *(const bf16x8*)(st + col * GC + (((2 * q) ^ ((col & 7) << 1)) << 2));
+    }
+  };
+  f32x16 acc[2];
+  if (w == tw) put_scaled(bet[lane]);    // (behind that wave's own reads of A: LDS operations of a wave are ordered)
+  __syncthreads();
+  product(qsm, acc);                    // U: rows = tokens, columns = value dims 32 w .. 32 w + 31
+  __syncthreads();                      // every wave has read the halves and V
+  stage_transposed(stage_v, acc, 1.f);
   if (w == tw) put_scaled(bet[lane] * __expf(gam[lane]));
   __syncthreads();
+  copy_out_transposed(stage_v, a.rec + op * REC_ELEMS + REC_UT);
   product(ksm, acc);                    // W: columns = key dims
+  __syncthreads();                      // K has been read, U^T has left
   {
-    __bf16* dst = a.rec + op * REC_ELEMS + REC_WN + 32 * w + c;
+    // -W [token][key dim]: 2-byte elements, consecutive lanes = consecutive columns of a row
 #pragma unroll
     for (int t = 0; t < 2; t++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) dst[(size_t)(32 * t + (r >> 2) * 8 + 4 * hf + (r & 3)) * GD] = (__bf16)(-acc[t][r]);
-    if constexpr (BWD) {
-      // -W^T for the reverse walk (and, like U^T, for the finish kernel)
-      __bf16* dt = a.rev + op * REV_ELEMS + REV_WTN + (size_t)(32 * w + c) * GC;
-#pragma unroll
-      for (int t = 0; t < 2; t++)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; r4++)
-          *(bf16x4*)(dt + 32 * t + r4 * 8 + 4 * hf) =
-              cvt4(-acc[t][4 * r4], -acc[t][4 * r4 + 1], -acc[t][4 * r4 + 2], -acc[t][4 * r4 + 3]);
-    }
+      for (int r = 0; r < 16; r++) stage_k[(32 * t + (r >> 2) * 8 + 4 * hf + (r & 3)) * GD + 32 * w + c] = (__bf16)(-acc[t][r]);
+    if constexpr (BWD) stage_transposed(stage_v, acc, -1.f);      // -W^T for the reverse walk and the finish kernel
   }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < GC * GD / 8 / G_THREADS; p++) {
+    const int piece = tid + p * G_THREADS;
+    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_WN + (size_t)piece * 8) = *(const bf16x8*)(stage_k + piece * 8);
+  }
+  if constexpr (BWD) copy_out_transposed(stage_v, a.rev + op * REV_ELEMS + REV_WTN);
 }
 
 typedef unsigned u32x4n __attribute__((ext_vector_type(4)));      // native vector type (stays in registers)
