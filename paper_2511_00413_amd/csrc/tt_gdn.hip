@@ -12,9 +12,9 @@
 // which is the token recurrence  S <- e^g S + beta k (v - (e^g S)^T k)^T,  o = scale S^T q  written
 // per chunk.  Two kernels:
 //   gdn_prepare_kernel  (chunk, value head): everything that does not depend on S0 -- K K^T and
-//       Q K^T on MFMA, the unit-lower-triangular solve by forward substitution with one lane per
-//       column of [V | K] (no synchronisation inside the solve), operands written in the layouts
-//       the second kernel's MFMA fragments want;
+//       Q K^T on MFMA, the inverse T = (I + A)^-1 by forward substitution on the identity (one wave, one
+//       lane per column, no synchronisation inside), U and W as products with T on MFMA, operands
+//       written in the layouts the second kernel's MFMA fragments want;
 //   gdn_scan_kernel  (64 value columns, value head): walks the chunks in DFS order with the state
 //       in MFMA accumulators (the columns of S evolve independently, so a head is cut into four
 //       independent blocks of 32 columns, four wavefronts each; two blocks form a workgroup and share
@@ -164,6 +164,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     const int c = lane & 31, hf = lane >> 5;
     if (jb <= ib) {
       f32x16 kk = zero16(), qk = zero16();
+      [[maybe_unused]] f32x16 kq = zero16();      // BWD: (Q K^T)^T formed as K Q^T, so that P^T too is stored along its rows
 #pragma unroll
       for (int ks = 0; ks < GD / 16; ks++) {
         const bf16x8 kj = *(const bf16x8*)&ksm[jb * 32 + c][ks * 16 + hf * 8];
@@ -171,6 +172,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         const bf16x8 qi = *(const bf16x8*)&qsm[ib * 32 + c][ks * 16 + hf * 8];
         kk = mfma32(ki, kj, kk);
         qk = mfma32(qi, kj, qk);
+        if constexpr (BWD) kq = mfma32(kj, qi, kq);
       }
       const int j = jb * 32 + c;
       __bf16* pout = a.rec + op * REC_ELEMS + REC_P;
@@ -183,7 +185,9 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         if constexpr (BWD) {
           a.f32.a0[op * (GC * GC) + i * GC + j] = a0;
           a.f32.p[op * (GC * GC) + i * GC + j] = a.scale * qk[r] * dec;
-          a.rev[op * REV_ELEMS + REV_PT + j * GC + i] = (__bf16)(a.scale * qk[r] * dec);
+          // element (row jt, column it) of the transposed tile: key token jt, query token it
+          const int jt = jb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3), it = ib * 32 + c;
+          a.rev[op * REV_ELEMS + REV_PT + jt * GC + it] = (__bf16)(jt <= it ? a.scale * kq[r] * __expf(gam[it] - gam[jt]) : 0.f);
         } else {
           pout[i * GC + j] = (__bf16)(a.scale * qk[r] * dec);
         }
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
         if constexpr (BWD) {
           a.f32.a0[op * (GC * GC) + i * GC + j] = 0.f;
           a.f32.p[op * (GC * GC) + i * GC + j] = 0.f;
-          a.rev[op * REV_ELEMS + REV_PT + j * GC + i] = (__bf16)0.f;
+          a.rev[op * REV_ELEMS + REV_PT + (jb * 32 + (r >> 2) * 8 + hf * 4 + (r & 3)) * GC + ib * 32 + c] = (__bf16)0.f;
         } else {
           pout[i * GC + j] = (__bf16)0.f;
         }
