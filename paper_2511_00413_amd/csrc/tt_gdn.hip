@@ -210,14 +210,12 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     }
   }
 
-  // (K * exp(gamma_last - gamma)) transposed: one 16-byte piece = 8 consecutive tokens of one dim
-  for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
-    const int d = piece >> 3, i0 = (piece & 7) * 8;
-    float f[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
-    *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
-    if constexpr (BWD) {
+  // (scale Q exp(gamma)) transposed: one 16-byte piece = 8 consecutive tokens of one dim.  (The same of K exp(gamma_last
+  // - gamma) is written further down, by the waves that would otherwise wait for the triangular inverse.)
+  if constexpr (BWD) {
+    for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
+      const int d = piece >> 3, i0 = (piece & 7) * 8;
+      float f[8];
 #pragma unroll
       for (int e = 0; e < 8; e++) f[e] = (float)qsm[i0 + e][d] * a.scale * __expf(gam[i0 + e]);
       *(bf16x8*)(a.rev + op * REV_ELEMS + REV_QGT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
@@ -225,29 +223,24 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   }
   __syncthreads();
   if constexpr (BWD) {
-    // dO^T: the rows of dO go through the Q tile's LDS (free now) and leave transposed
+    // dO^T: the rows of dO go through the Q tile's LDS (free now) and leave transposed (further down, beside the
+    // triangular inverse)
 #pragma unroll
     for (int p = 0; p < NPIECE; p++) {
       const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
       *(bf16x8*)&qsm[i][c8] = i < len ? doreg[p] : zero8;
     }
     __syncthreads();
-    for (int piece = tid; piece < GD * (GC / 8); piece += G_THREADS) {
-      const int d = piece >> 3, i0 = (piece & 7) * 8;
-      bf16x8 o;
+  }
+  // V rows into the Q tile's LDS (once that is free), for the first product: every thread its own pieces, the wave that
+  // forms the inverse after it has done so (the barrier in front of the product covers both)
+  auto stage_v_rows = [&]() {
 #pragma unroll
-      for (int e = 0; e < 8; e++) o[e] = qsm[i0 + e][d];
-      *(bf16x8*)(a.rev + op * REV_ELEMS + REV_DOT + d * GC + i0) = o;
+    for (int p = 0; p < NPIECE; p++) {
+      const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
+      *(bf16x8*)&qsm[i][c8] = i < len ? vreg[p] : zero8;
     }
-    __syncthreads();
-  }
-  // V rows into the Q tile's LDS (free now): the solve below reads its value columns from there
-#pragma unroll
-  for (int p = 0; p < NPIECE; p++) {
-    const int piece = tid + p * G_THREADS, i = piece >> 4, c8 = (piece & 15) * 8;
-    *(bf16x8*)&qsm[i][c8] = i < len ? vreg[p] : zero8;
-  }
-  __syncthreads();
+  };
 
   // U = (I + A)^-1 (beta V),  W = (I + A)^-1 (beta exp(gamma) K) as products with the explicit inverse
   // T = (I + A)^-1 (unit lower triangular, like I + A): the first wave forms T by forward substitution on the
@@ -282,6 +275,33 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
 #pragma unroll
       for (int i = 0; i < GC; i++) a.f32.t[op * (GC * GC) + i * GC + lane] = x[i];
     }
+    if constexpr (!BWD) stage_v_rows();
+  } else {
+    // meanwhile the other three waves write (K exp(gamma_last - gamma)) transposed (K stays in LDS until the second
+    // product) and, in the backward form, dO^T: 8 consecutive tokens of one dim per piece
+    const int t3 = 64 * (w - (w > tw ? 1 : 0)) + lane;
+    if constexpr (BWD) {
+      for (int piece = t3; piece < GD * (GC / 8); piece += G_THREADS - 64) {
+        const int d = piece >> 3, i0 = (piece & 7) * 8;
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = qsm[i0 + e][d];
+        *(bf16x8*)(a.rev + op * REV_ELEMS + REV_DOT + d * GC + i0) = o;
+      }
+    } else {
+      stage_v_rows();
+    }
+    for (int piece = t3; piece < GD * (GC / 8); piece += G_THREADS - 64) {
+      const int d = piece >> 3, i0 = (piece & 7) * 8;
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) f[e] = (float)ksm[i0 + e][d] * __expf(g_last - gam[i0 + e]);
+      *(bf16x8*)(a.rec + op * REC_ELEMS + REC_KDT + d * GC + i0) = cvt8(f[0], f[1], f[2], f[3], f[4], f[5], f[6], f[7]);
+    }
+  }
+  if constexpr (BWD) {
+    __syncthreads();                    // dO has been read: V may take its place
+    stage_v_rows();
   }
   const int c = lane & 31, hf = lane >> 5;
   // one product: C (64 x 128) = (hi + lo) (64 x 64) B (64 tokens x 128, row-major in LDS); wave w takes the column
