@@ -36,7 +36,8 @@ constexpr int GD = 128;              // head dim of keys and values
 constexpr int GROW = GD + 8;         // padded LDS row (elements) for [*][128] bf16 tiles
 constexpr int G_THREADS = 256;
 constexpr int T_PITCH = GC + 8;      // padded LDS row (elements) of the 64 x 64 bf16 halves of the triangular inverse
-static_assert(2 * GC * T_PITCH * 2 >= GC * GC * 4, "the inverse's halves take the place of A");
+constexpr int AM_PITCH = GC + 4;     // LDS row (floats) of A: rows 16-byte aligned, a column of 32 rows spreads over 16 banks
+static_assert(2 * GC * T_PITCH * 2 >= GC * AM_PITCH * 4, "the inverse's halves take the place of A");
 constexpr int G_DVB = 32;            // value columns per column block of the scan (one 32 x 32 accumulator tile per wave)
 constexpr int SCAN_NB = 2;           // column blocks per scan workgroup: 4 wavefronts each, sharing the chunk's operands in LDS
 constexpr int SCAN_NW = 4 * SCAN_NB; // wavefronts per scan workgroup (two per SIMD)
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __shared__ __attribute__((aligned(16))) __bf16 qsm[GC][GROW];
   // A (fp32) until the triangular inverse has been formed from it, then the two bf16 halves of the scaled inverse
   __shared__ __attribute__((aligned(16))) float am_raw[2 * GC * T_PITCH / 2];
-  float(*am)[GC] = (float(*)[GC])am_raw;
+  float(*am)[AM_PITCH] = (float(*)[AM_PITCH])am_raw;
   __bf16(*t_hi)[T_PITCH] = (__bf16(*)[T_PITCH])am_raw;
   __bf16(*t_lo)[T_PITCH] = t_hi + GC;
   __shared__ float gam[GC], bet[GC];
@@ -243,26 +244,31 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   };
 
   // U = (I + A)^-1 (beta V),  W = (I + A)^-1 (beta exp(gamma) K) as products with the explicit inverse
-  // T = (I + A)^-1 (unit lower triangular, like I + A): the first wave forms T by forward substitution on the
-  // identity, one lane per column (a quarter of the multiply-adds that substitution on the 256 columns of
-  // [V | K] took, which kept all four waves busy for most of this kernel's time); the products
-  // (T diag(beta)) V and (T diag(beta exp(gamma))) K then run on the matrix cores.  V and K are bf16 as they stand;
-  // the scaled T is split into two bf16 halves (hi + lo, relative error 2^-17), so the products carry fp32-grade
-  // operands, and U, W are rounded to bf16 once, as before.
+  // T = (I + A)^-1 (unit lower triangular, like I + A), formed by one wave (a quarter of the multiply-adds that
+  // substitution on the 256 columns of [V | K] took, which kept all four waves busy for most of this kernel's time);
+  // the products (T diag(beta)) V and (T diag(beta exp(gamma))) K then run on the matrix cores.  V and K are bf16 as
+  // they stand; the scaled T is split into two bf16 halves (hi + lo, relative error 2^-17), so the products carry
+  // fp32-grade operands, and U, W are rounded to bf16 once, as before.
+  // The inverse by 32 x 32 blocks, T = [T11 0; T21 T22]: the diagonal blocks by forward substitution on the identity,
+  // one lane per column, both blocks at once in the two halves of the wave (31 steps instead of 63); then
+  // T21 = -T22 (A21 T11) as two products on the fp32 matrix instruction.
   // (the wave that does it differs from workgroup to workgroup: the waves of a workgroup sit on different SIMDs, and
   // with always the same one the inverses of the compute unit's resident workgroups would queue up on one SIMD)
   const int tw = (int)((blockIdx.x + blockIdx.y) & 3);
-  float x[GC];                          // wave tw: column `lane` of T
+  const int c = lane & 31, hf = lane >> 5;
+  float x[32];                          // wave tw: column c of T11 (lanes 0 .. 31) / of T22 (lanes 32 .. 63)
+  f32x16 t21;                           // wave tw: T21 as an accumulator tile (rows 32 + tile row, column c)
   if (w == tw) {
+    const float* ablk = &am[32 * hf][32 * hf];
 #pragma unroll
-    for (int i = 0; i < GC; i++) x[i] = i == lane ? 1.f : 0.f;
+    for (int i = 0; i < 32; i++) x[i] = i == c ? 1.f : 0.f;
 #pragma unroll
-    for (int i = 1; i < GC; i++) {
+    for (int i = 1; i < 32; i++) {
       // x_i = delta_ij - sum_{k<i} A_ik x_k, four partial sums (the chain of one sum would leave the wave waiting)
       float s0 = x[i], s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
       for (int j4 = 0; j4 < (i + 3) / 4; j4++) {
-        const float4 av = *(const float4*)&am[i][j4 * 4];      // entries at k >= i are zero; rows past the chunk too
+        const float4 av = *(const float4*)(ablk + i * AM_PITCH + j4 * 4);   // entries at k >= i are zero; rows past the chunk too
         s0 -= av.x * x[j4 * 4];
         s1 -= av.y * x[j4 * 4 + 1];
         s2 -= av.z * x[j4 * 4 + 2];
@@ -270,10 +276,38 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       }
       x[i] = (s0 + s1) + (s2 + s3);
     }
-    if constexpr (BWD) {
-      // T itself, for the finish kernel's transposed solve (row i, column lane: 256 contiguous bytes per store)
+    // Y = A21 T11: step s contracts k = 2 s (lower half of the wave) and 2 s + 1 (upper half); the upper half takes
+    // its T11 row from the lower half's registers
+    f32x16 y = zero16();
 #pragma unroll
-      for (int i = 0; i < GC; i++) a.f32.t[op * (GC * GC) + i * GC + lane] = x[i];
+    for (int s2 = 0; s2 < 16; s2++) {
+      const float from_lower = __shfl(x[2 * s2 + 1], c);
+      y = __builtin_amdgcn_mfma_f32_32x32x2f32(am[32 + c][2 * s2 + hf], hf ? from_lower : x[2 * s2], y, 0, 0, 0);
+    }
+    // T21 = -T22 Y: Y's registers are the B operand as they stand when step s contracts the rows that register s
+    // holds (8 (s / 4) + 4 hf + s % 4); T22 goes through LDS to become the A operand (row c, that k) -- into the upper
+    // right block of A, which nothing reads
+    if (hf) {
+#pragma unroll
+      for (int i = 0; i < 32; i++) am[i][32 + c] = x[i];
+    }
+    t21 = zero16();
+#pragma unroll
+    for (int s2 = 0; s2 < 16; s2++)
+      t21 = __builtin_amdgcn_mfma_f32_32x32x2f32(am[c][32 + 8 * (s2 >> 2) + 4 * hf + (s2 & 3)], y[s2], t21, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 16; r++) t21[r] = -t21[r];
+    if constexpr (BWD) {
+      // T itself, for the finish kernel's transposed solve: the diagonal blocks (row 32 hf + i, column lane), T21, and
+      // the zero block
+      float* tg = a.f32.t + op * (GC * GC);
+#pragma unroll
+      for (int i = 0; i < 32; i++) tg[(32 * hf + i) * GC + lane] = x[i];
+#pragma unroll
+      for (int r = 0; r < 16; r++) {
+        tg[(32 + (r >> 2) * 8 + 4 * hf + (r & 3)) * GC + c] = t21[r];
+        tg[(2 * r + hf) * GC + 32 + c] = 0.f;
+      }
     }
     if constexpr (!BWD) stage_v_rows();
   } else {
@@ -303,7 +337,6 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     __syncthreads();                    // dO has been read: V may take its place
     stage_v_rows();
   }
-  const int c = lane & 31, hf = lane >> 5;
   // one product: C (64 x 128) = (hi + lo) (64 x 64) B (64 tokens x 128, row-major in LDS); wave w takes the column
   // block w, both row blocks
   auto product = [&](const __bf16 (*bsm)[GROW], f32x16 (&acc)[2]) {
@@ -312,7 +345,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     for (int ks = 0; ks < GC / 16; ks++) {
       const bf16x8 b = kmajor_frag(&bsm[0][0], GROW, 16 * ks + 8 * hf, 32 * w + 16 * (c >> 4), lane);
 #pragma unroll
-      for (int t = 0; t < 2; t++) {
+      for (int t = ks < GC / 32 ? 0 : 1; t < 2; t++) {   // (rows 0 .. 31 of T are zero from column 32 on)
         const bf16x8 ah = *(const bf16x8*)&t_hi[32 * t + c][16 * ks + 8 * hf];
         const bf16x8 al = *(const bf16x8*)&t_lo[32 * t + c][16 * ks + 8 * hf];
         acc[t] = mfma32(ah, b, acc[t]);
@@ -320,15 +353,18 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
       }
     }
   };
-  // the scaled inverse, column `lane` times f, as hi + lo
-  auto put_scaled = [&](float f) {
-#pragma unroll
-    for (int i = 0; i < GC; i++) {
-      const float v = x[i] * f;
+  // the inverse with column j scaled by f(j), as hi + lo (its upper right block is zero and is neither written nor read)
+  auto put_scaled = [&](auto f) {
+    auto put = [&](int i, int j, float v) {
       const __bf16 h = (__bf16)v;
-      t_hi[i][lane] = h;
-      t_lo[i][lane] = (__bf16)(v - (float)h);
-    }
+      t_hi[i][j] = h;
+      t_lo[i][j] = (__bf16)(v - (float)h);
+    };
+    const float fd = f(lane), fo = f(c);
+#pragma unroll
+    for (int i = 0; i < 32; i++) put(32 * hf + i, lane, x[i] * fd);
+#pragma unroll
+    for (int r = 0; r < 16; r++) put(32 + (r >> 2) * 8 + 4 * hf + (r & 3), c, t21[r] * fo);
   };
   // The results leave through LDS, so that memory sees whole 16-byte pieces from consecutive lanes (stored straight
   // from the accumulators, U^T goes out as 8-byte pieces 128 bytes apart and W as 2-byte elements: most of this
@@ -354,12 +390,12 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
     }
   };
   f32x16 acc[2];
-  if (w == tw) put_scaled(bet[lane]);    // (behind that wave's own reads of A: LDS operations of a wave are ordered)
+  if (w == tw) put_scaled([&](int j) { return bet[j]; });    // (behind that wave's own reads of A: LDS operations of a wave are ordered)
   __syncthreads();
   product(qsm, acc);                    // U: rows = tokens, columns = value dims 32 w .. 32 w + 31
   __syncthreads();                      // every wave has read the halves and V
   stage_transposed(stage_v, acc, 1.f);
-  if (w == tw) put_scaled(bet[lane] * __expf(gam[lane]));
+  if (w == tw) put_scaled([&](int j) { return bet[j] * __expf(gam[j]); });
   __syncthreads();
   copy_out_transposed(stage_v, a.rec + op * REC_ELEMS + REC_UT);
   product(ksm, acc);                    // W: columns = key dims
