@@ -102,7 +102,8 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   __bf16(*t_lo)[T_PITCH] = t_hi + GC;
   __shared__ float gam[GC], bet[GC];
 
-  const int chunk = blockIdx.x, h = blockIdx.y;
+  int chunk, h;
+  if (!gdn_group_order(blockIdx.x, a.n_chunks, a.hv_n, a.hv / a.hk, chunk, h)) return;
   const int hkv = h / (a.hv / a.hk);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int tok0 = a.chunk_tok0[chunk], len = a.chunk_len[chunk];
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(G_THREADS) void gdn_prepare_kernel(GdnArgs a) {
   // T21 = -T22 (A21 T11) as two products on the fp32 matrix instruction.
   // (the wave that does it differs from workgroup to workgroup: the waves of a workgroup sit on different SIMDs, and
   // with always the same one the inverses of the compute unit's resident workgroups would queue up on one SIMD)
-  const int tw = (int)((blockIdx.x + blockIdx.y) & 3);
+  const int tw = (int)((blockIdx.x >> 3) & 3);
   const int c = lane & 31, hf = lane >> 5;
   float x[32];                          // wave tw: column c of T11 (lanes 0 .. 31) / of T22 (lanes 32 .. 63)
   f32x16 t21;                           // wave tw: T21 as an accumulator tile (rows 32 + tile row, column c)
@@ -902,7 +903,7 @@ hipError_t gdn_fwd(int64_t n_tokens, int hk, int hv, float scale, const void* q,
   a.slots = (float*)p;
   {
     KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
-    gdn_prepare_kernel<false><<<dim3(n_chunks, hv), G_THREADS, 0, st>>>(a);
+    gdn_prepare_kernel<false><<<gdn_group_order_grid(n_chunks, hv, hv / hk), G_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   KernelTimer t(TT_KERNEL_GDN_SCAN, st);
@@ -922,7 +923,7 @@ hipError_t gdn_bwd_prepare_and_walks(const GdnBwdArgs& b, const GdnChunkOps& ops
   a.slot_grad = sv.slot_grad; a.d_state_out = b.d_state_out; a.d_initial_state = b.d_initial_state;
   {
     KernelTimer t(TT_KERNEL_GDN_PREPARE, st);
-    gdn_prepare_kernel<true><<<dim3(b.n_chunks, b.hv_n), G_THREADS, 0, st>>>(a);
+    gdn_prepare_kernel<true><<<gdn_group_order_grid(b.n_chunks, b.hv_n, b.hv / b.hk), G_THREADS, 0, st>>>(a);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   {

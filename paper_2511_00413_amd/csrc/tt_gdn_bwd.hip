@@ -301,7 +301,8 @@ __global__ __launch_bounds__(BT, 2) void gdn_bwd_finish_kernel(KArgs a) {
   float(*dot_kb)[GC] = (float(*)[GC])(gm + 8 * GC);
   float* red = (float*)as;                                        // [BT], after the last product
 
-  const int chunk = blockIdx.x, h = blockIdx.y;
+  int chunk, h;
+  if (!gdn_group_order(blockIdx.x, a.b.n_chunks, a.b.hv_n, a.b.hv / a.b.hk, chunk, h)) return;
   const int tid = threadIdx.x & (BT - 1), lane = tid & 63, c = lane & 31, hf = lane >> 5;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nc = a.b.n_chunks, hv = a.b.hv, kh = h / (hv / a.b.hk);
@@ -714,7 +715,7 @@ hipError_t gdn_bwd(const GdnBwdArgs& b0, hipStream_t st) {
     if (hipError_t e = gdn_bwd_prepare_and_walks(b, a.w.ops, a.w.sv, st); e != hipSuccess) return e;
     {
       KernelTimer t(TT_KERNEL_GDN_BWD_FINISH, st);
-      gdn_bwd_finish_kernel<<<dim3(b.n_chunks, b.hv_n), BT, 0, st>>>(a);
+      gdn_bwd_finish_kernel<<<gdn_group_order_grid(b.n_chunks, b.hv_n, b.hv / b.hk), BT, 0, st>>>(a);
     }
     if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     {

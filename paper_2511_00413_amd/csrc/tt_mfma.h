@@ -278,4 +278,23 @@ struct KTileIter {
   }
 };
 
+// Workgroup order of the gated delta rule's per-(chunk, value head) kernels.  The value heads of one key head read the
+// same q and k rows; workgroups are dealt to the chip's 8 XCDs (each with its own L2) round-robin by their linear id,
+// so the `group` members of a (chunk, key head) pair get ids that differ by multiples of 8 and follow each other
+// directly on their XCD: they run at the same time behind the same L2.  The grid is padded to whole rounds of 8
+// pairs; a workgroup past the last pair gets `false` and returns.
+constexpr unsigned GDN_XCDS = 8;
+inline unsigned gdn_group_order_grid(int n_chunks, int hv_n, int group) {
+  const unsigned pairs = (unsigned)n_chunks * (unsigned)(hv_n / group);
+  return (pairs + GDN_XCDS - 1) / GDN_XCDS * GDN_XCDS * (unsigned)group;
+}
+__device__ __forceinline__ bool gdn_group_order(unsigned id, int n_chunks, int hv_n, int group, int& chunk, int& h) {
+  const unsigned xcd = id % GDN_XCDS, t = id / GDN_XCDS;
+  const unsigned member = t % (unsigned)group, pair = t / (unsigned)group * GDN_XCDS + xcd;
+  if (pair >= (unsigned)n_chunks * (unsigned)(hv_n / group)) return false;
+  chunk = (int)(pair % (unsigned)n_chunks);
+  h = (int)(pair / (unsigned)n_chunks) * group + (int)member;
+  return true;
+}
+
 }  // namespace tt
