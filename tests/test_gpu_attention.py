@@ -4,7 +4,8 @@ Two assertions per output (tt_testutil.ATTN_TOL): the relative L2 over the whole
 bf16 path 1e-2 for O and LSE, 2e-2 for dQ/dK/dV) and the largest per-row error -- per (query token, head)
 for O and dQ, per (key token, kv head) for dK and dV, largest absolute difference for LSE -- because the
 equivalence the method claims holds per token (Eq. 6) and the gradient sum per key (Eq. 5): one wrong row
-must fail.  The oracle consumes the same (bf16-rounded) inputs upcast to fp32."""
+must fail.  dQ and dK rows get an absolute budget for what the rounding of the saved O (an input of the backward
+call, in the I/O dtype) can contribute (tt_testutil.dq_allowance / dk_allowance).  The oracle consumes the same (bf16-rounded) inputs upcast to fp32."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +14,7 @@ import paper_2511_00413_amd as T
 import workloads as W
 from oracle import attention as A
 from oracle import meta as M
-from tt_testutil import assert_attention_close, dq_allowance
+from tt_testutil import assert_attention_close, dk_allowance, dq_allowance
 
 pytestmark = pytest.mark.gpu
 
@@ -28,8 +29,11 @@ def _full_parity(tree, dims, seed, scale=None, reference_kernels=False, label=""
     print(f"[case] {label} {tree.name} N={n} hq={dims.hq} hkv={dims.hkv} d={dims.d} {dims.dtype} ref={reference_kernels}", flush=True)
     got = gpu_attention(meta, q, k, v, do, scale=scale, reference_kernels=reference_kernels)
     want = A.branches(om, q.float(), k.float(), v.float(), do.float(), scale=scale)
+    sc = dims.d ** -0.5 if scale is None else scale
+    dk_allow = dk_allowance(q.float().numpy(), k.float().numpy(), want["lse"], M.mask_chunks(om), do.float().numpy(), want["o"],
+                            sc, dims.dtype) if 0 < n <= 8192 else None
     errs, _ = assert_attention_close(got, {key: want[key] for key in ("o", "lse", "dq", "dk", "dv")}, dims.dtype,
-                                     dq_allow=_dq_allow(do, want["o"], k, scale, dims))
+                                     dq_allow=_dq_allow(do, want["o"], k, scale, dims), dk_allow=dk_allow)
     return errs
 
 
@@ -61,6 +65,19 @@ def test_bf16_random_trees(seed, ref):
     t = W.random_tree(70 + seed, n_nodes=3 + 4 * seed, lo=1, hi=400, n_roots=1 + seed % 2, p_zero=0.1)
     hq, hkv = [(4, 1), (8, 2), (4, 4), (16, 2)][seed]
     _full_parity(t, W.AttnDims(hq, hkv, 128, "bf16", 0.5), seed, reference_kernels=ref, label="bf16-random")
+
+
+@pytest.mark.parametrize("ref", [True, False], ids=["reference-kernels", "mfma"])
+def test_bf16_rows_small_by_cancellation(ref):
+    """Trees in which most queries see one to three keys (nodes of 1 .. 3 tokens, several roots), and wider ones with
+    many heads: there dQ_i and the dK rows of the first keys of a root are small by cancellation, and what the
+    rounding of the saved O contributes dominates their error.  These shapes (found by a randomized sweep over 1600
+    trees) are the ones that need the per-row budgets of dQ and dK; both kernel sets show the same errors on them."""
+    for seed, nn, hi, roots, pz, hq, hkv, inseed, scale in [(1100096, 9, 3, 3, 0.0, 8, 8, 96, 0.11), (1100437, 24, 3, 3, 0.0, 8, 8, 437, None),
+                                                            (1100197, 12, 3, 2, 0.3, 2, 1, 197, None), (1102897, 18, 3, 3, 0.0, 2, 2, 897, None),
+                                                            (1102144, 19, 70, 3, 0.0, 8, 8, 144, None), (1100200, 19, 300, 3, 0.3, 32, 8, 200, None)]:
+        t = W.random_tree(seed, n_nodes=nn, lo=1, hi=hi, n_roots=roots, p_zero=pz)
+        _full_parity(t, W.AttnDims(hq, hkv, 128, "bf16", 0.5), inseed, scale=scale, reference_kernels=ref, label="cancellation")
 
 
 def test_bf16_chain_is_causal_attention():
@@ -117,7 +134,10 @@ def _prefix_case(dtype, seed, P, vis, chunk, hq, hkv, d, ref=False):
         # fp32 accumulators of the visible cached keys: same bounds (the products are bf16 all the same)
         ref["dk_prefix"], ref["dv_prefix"] = want["dk"][:nvis], want["dv"][:nvis]
         mine["dk_prefix"], mine["dv_prefix"] = got["dk_prefix"][sel.numpy()], got["dv_prefix"][sel.numpy()]
-    assert_attention_close(mine, ref, dtype, dq_allow=_dq_allow(do, ref["o"], kw, None, dims))
+    # budgets of the dK rows on the whole tree (the prefix's zero query rows have dO = 0 and add nothing)
+    dk_all = dk_allowance(qw.numpy(), kw.numpy(), want["lse"], M.mask_chunks(om), dow.numpy(), want["o"], d ** -0.5, dtype)
+    assert_attention_close(mine, ref, dtype, dq_allow=_dq_allow(do, ref["o"], kw, None, dims),
+                           dk_allow={"dk": dk_all[nvis:], "dk_prefix": dk_all[:nvis]} if nvis else dk_all)
     hidden = np.nonzero(vis == 0)[0]
     assert np.all(got["dk_prefix"][hidden] == 0) and np.all(got["dv_prefix"][hidden] == 0)
     return meta, (q, k, v, do, kp, vp), got
