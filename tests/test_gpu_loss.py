@@ -93,6 +93,22 @@ def test_special_rows():
 # bf16 output: one round-to-nearest-even of each element (relative 2^-9) on top of fp32 arithmetic ->
 # rel-L2 <= 4e-3 and every element within 2^-8 relative + a small absolute floor; fp32 output: 1e-5.
 
+def _grad_elem_bound(logits, weight, grad_scale, want):
+    """Element-wise bound of a bf16 gradient: one rounding of the output (2^-8 of the value), plus the fp32 evaluation
+    of the softmax value behind it -- exp(z - lse) carries a relative error of about 1e-5 + 2^-23 max|z| (lse is an
+    fp32 number of the logits' magnitude; its rounding is a relative error of every exponential of the row).  That
+    second term is relative to the softmax value p, not to p - 1: at the target of a confident row (p near 1, the
+    gradient w (p - 1) small by cancellation) it is what is left, and with a vocabulary of a handful of entries every
+    row of a test can be such a row."""
+    z = logits.float().numpy().astype(np.float64)
+    w = np.ones(z.shape[0]) if weight is None else np.asarray(weight, dtype=np.float64)
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    prob = e / e.sum(axis=1, keepdims=True)
+    mag = np.abs(z).max(axis=1, keepdims=True)
+    return 2.0 ** -8 * np.abs(want) + np.abs(grad_scale * w)[:, None] * prob * (1e-5 + 2.0 ** -23 * mag)
+
+
 def _check_bwd(logits, target, weight, grad_scale=1.0, inplace=False):
     print(f"[case] loss bwd rows={logits.shape[0]} vocab={logits.shape[1]} {logits.dtype} inplace={inplace}", flush=True)
     lg = logits.cuda()
@@ -108,7 +124,7 @@ def _check_bwd(logits, target, weight, grad_scale=1.0, inplace=False):
     den = max(np.sqrt((want ** 2).sum()), 1e-30)
     if logits.dtype == torch.bfloat16:
         assert num / den <= 4e-3, num / den
-        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-7 * np.abs(want).max())
+        assert np.all(np.abs(got - want) <= _grad_elem_bound(logits, weight, grad_scale, want))
     else:
         assert num / den <= 1e-5, num / den
     # ignored rows (target negative or not below the vocabulary size) are exactly zero
@@ -119,7 +135,7 @@ def _check_bwd(logits, target, weight, grad_scale=1.0, inplace=False):
 
 @pytest.mark.parametrize("rows,vocab,dtype", [(37, 32768, "bf16"), (5, 151936, "bf16"), (64, 777, "bf16"),
                                               (33, 1001, "fp32"), (3, 8, "fp32"), (9, 1, "bf16"), (300, 5000, "bf16"),
-                                              (16, 4096, "fp32")])
+                                              (16, 4096, "fp32"), (196, 8, "bf16"), (131, 7, "bf16")])
 def test_bwd_shapes_and_misaligned_rows(rows, vocab, dtype):
     logits, target = W.loss_inputs(rows, vocab, rows + 3 * vocab, 2.0, dtype)
     target = target.clone()
@@ -127,6 +143,17 @@ def test_bwd_shapes_and_misaligned_rows(rows, vocab, dtype):
         target[1] = -1
     w = (np.random.default_rng(rows).random(rows) + 0.25).astype(np.float32)
     _check_bwd(logits, target, w, grad_scale=0.5)
+
+
+@pytest.mark.parametrize("rows,vocab,seed", [(196, 8, 3100021), (131, 7, 3101361)])
+def test_confident_rows_of_a_small_vocabulary(rows, vocab, seed):
+    """Wide logits over a handful of entries: nearly every row puts p close to 1 on one entry, so the gradient at a
+    hit target, w (p - 1), is small by cancellation and no element of the test is large.  (Shapes from a randomized
+    sweep; they need the softmax-relative term of _grad_elem_bound.)"""
+    logits, target = W.loss_inputs(rows, vocab, seed % 100000, 6.0, "bf16")
+    w = (np.random.default_rng(rows).random(rows) + 0.25).astype(np.float32)
+    _check_bwd(logits, target, w, grad_scale=0.5)
+    _check_fused(logits, target, w, grad_scale=1.0 / 64, stride_pad=8)
 
 
 def test_out_of_range_target_is_an_ignored_row():
@@ -242,7 +269,7 @@ def _check_fused(logits, target, weight, grad_scale=1.0, inplace=False, stride_p
     num, den = np.sqrt(((g - want) ** 2).sum()), max(np.sqrt((want ** 2).sum()), 1e-30)
     if logits.dtype == torch.bfloat16:
         assert num / den <= 4e-3, num / den
-        assert np.all(np.abs(g - want) <= 2.0 ** -8 * np.abs(want) + 1e-7 * np.abs(want).max())
+        assert np.all(np.abs(g - want) <= _grad_elem_bound(logits, weight, grad_scale, want))
     else:
         assert num / den <= 1e-5, num / den
     ign = (target.numpy() < 0) | (target.numpy() >= vocab)
@@ -251,12 +278,14 @@ def _check_fused(logits, target, weight, grad_scale=1.0, inplace=False, stride_p
     assert torch.allclose(lse, sep_lse, rtol=0, atol=atol) and torch.allclose(logp, sep_logp, rtol=0, atol=atol)
     assert abs(float(loss.item()) - float(sep_loss.item())) <= 1e-5 * max(abs(want_loss), 1e-6)
     gs = sep_grad.float().cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(g - gs) <= 2.0 ** -7 * np.abs(gs) + 1e-7 * np.abs(gs).max())
+    assert np.all(np.abs(g - gs) <= (2 * _grad_elem_bound(logits, weight, grad_scale, want) if logits.dtype == torch.bfloat16
+                                     else 2.0 ** -7 * np.abs(gs) + 1e-7 * np.abs(gs).max()))
 
 
 @pytest.mark.parametrize("rows,vocab,dtype", [(37, 32768, "bf16"),      # a row fills the LDS copy exactly
                                               (5, 151936, "bf16"),      # longer than the copy: the rest is read twice
                                               (21, 40000, "bf16"), (64, 777, "bf16"), (300, 5000, "bf16"), (9, 1, "bf16"),
+                                              (103, 8, "bf16"), (132, 7, "bf16"),   # a handful of entries: confident rows
                                               (33, 1001, "fp32"), (3, 8, "fp32"), (16, 4096, "fp32"), (6, 20000, "fp32")])
 def test_fwd_bwd_one_pass(rows, vocab, dtype):
     logits, target = W.loss_inputs(rows, vocab, 5 * rows + vocab, 2.0, dtype)
